@@ -1,0 +1,151 @@
+"""Seeded synthetic workloads for the stacked-LSTM forward pass.
+
+This module only draws random numbers and shapes them; it contains none of the
+LSTM arithmetic.  Both the CPU oracle's tests and the GPU parity tests take their
+inputs from here so that the two sides see bit-identical host arrays.
+
+Shapes follow the models of the paper's experiments (Section 5): a 2-layer
+1500-wide language-model stack and a 5-layer bidirectional 800-wide speech stack,
+with weight sparsity in the range the paper reports after weight pruning.  Values
+are synthetic (uniform weights, Bernoulli masks, normal inputs).
+
+Gate-row order of every weight matrix is f, i, o, g (the order in which the paper
+stacks the four gates in its cell equations, Section 4): rows [0,H) forget,
+[H,2H) input, [2H,3H) output, [3H,4H) cell candidate.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+
+SEED_BASE = 190110997
+
+
+@dataclass(frozen=True)
+class Workload:
+    """Shape and value recipe of one synthetic LSTM workload."""
+    cid: int                 # config number, enters the seed
+    name: str
+    layers: int
+    bidirectional: bool
+    input_dim: int
+    hidden: int
+    T: int
+    B: int
+    dtype: str = "f32"       # "f32" | "bf16" (bf16 = operands rounded to bf16 on the host)
+    a: float = 0.1           # weights ~ U(-a, a)
+    keep: Optional[float] = None   # Bernoulli keep-probability of the masks; None = dense (no masks)
+    bias: str = "forget1"    # "forget1": 0 except forget gate 1.0 ; "uniform": U(-a, a)
+
+    @property
+    def ndir(self) -> int:
+        return 2 if self.bidirectional else 1
+
+    def layer_input_dim(self, l: int) -> int:
+        return self.input_dim if l == 0 else self.ndir * self.hidden
+
+
+def c1() -> Workload:
+    return Workload(1, "c1_small_dense", 1, False, 200, 200, 35, 1, "f32", 0.1, None, "forget1")
+
+
+def c2(B: int = 1) -> Workload:
+    return Workload(2, f"c2_lm_2x1500_b{B}", 2, False, 1500, 1500, 35, B, "f32", 0.04, 0.10, "uniform")
+
+
+def c3(H: int) -> Workload:
+    return Workload(3, f"c3_sweep_h{H}", 1, False, H, H, 35, 1, "f32", 0.1, None, "forget1")
+
+
+def c3_hidden_sizes() -> List[int]:
+    return list(range(64, 2048 + 1, 32))
+
+
+def c4() -> Workload:
+    return Workload(4, "c4_speech_5x800_bidir", 5, True, 640, 800, 300, 16, "f32", 0.035, 0.15, "uniform")
+
+
+def c5() -> Workload:
+    return Workload(5, "c5_throughput_2x1024_bf16", 2, False, 1024, 1024, 128, 256, "bf16", 0.03, None, "uniform")
+
+
+def shrink(w: Workload, **kw) -> Workload:
+    """Same recipe at other sizes (used by tests that need the oracle to finish quickly)."""
+    return replace(w, **kw)
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16 (ties to even); result stays stored as fp32."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    u = (u + 0x7FFF + lsb) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+@dataclass
+class Case:
+    """Host arrays of one seeded instance of a workload.
+
+    weights[(l, d)] = dict(Wx[4H,D_l] f32, Mx u8 or None, Wh[4H,H] f32, Mh u8 or None, b[4H] f32)
+    x[T,B,D0] f32 ; h0, c0 [L*ndir, B, H] f32 or None (= zeros)
+    """
+    w: Workload
+    seed: int
+    weights: Dict[Tuple[int, int], Dict[str, Optional[np.ndarray]]]
+    x: np.ndarray
+    h0: Optional[np.ndarray]
+    c0: Optional[np.ndarray]
+
+
+def make_case(w: Workload, k: int = 0, random_state: bool = False) -> Case:
+    """Draw instance `k` of workload `w`.
+
+    Draw order (fixed, so that a case is reproducible from (cid, k) alone):
+    for each layer, for each direction: Wx, mask_x, Wh, mask_h, b; then x; then,
+    if `random_state`, h0 and c0 ~ U(-0.5, 0.5).
+    """
+    seed = SEED_BASE + 1000 * w.cid + k
+    rng = np.random.Generator(np.random.PCG64(seed))
+    H = w.hidden
+    G = 4 * H
+    weights: Dict[Tuple[int, int], Dict[str, Optional[np.ndarray]]] = {}
+    for l in range(w.layers):
+        D = w.layer_input_dim(l)
+        for d in range(w.ndir):
+            Wx = rng.uniform(-w.a, w.a, (G, D)).astype(np.float32)
+            Mx = (rng.random((G, D)) < w.keep).astype(np.uint8) if w.keep is not None else None
+            Wh = rng.uniform(-w.a, w.a, (G, H)).astype(np.float32)
+            Mh = (rng.random((G, H)) < w.keep).astype(np.uint8) if w.keep is not None else None
+            if w.bias == "forget1":
+                b = np.zeros(G, dtype=np.float32)
+                b[0:H] = 1.0
+            elif w.bias == "uniform":
+                b = rng.uniform(-w.a, w.a, G).astype(np.float32)
+            else:
+                raise ValueError(w.bias)
+            if w.dtype == "bf16":
+                Wx = round_to_bf16(Wx)
+                Wh = round_to_bf16(Wh)
+            weights[(l, d)] = dict(Wx=Wx, Mx=Mx, Wh=Wh, Mh=Mh, b=b)
+    x = rng.standard_normal((w.T, w.B, w.input_dim)).astype(np.float32)
+    if w.dtype == "bf16":
+        x = round_to_bf16(x)
+    h0 = c0 = None
+    if random_state:
+        n = w.layers * w.ndir
+        h0 = rng.uniform(-0.5, 0.5, (n, w.B, H)).astype(np.float32)
+        c0 = rng.uniform(-0.5, 0.5, (n, w.B, H)).astype(np.float32)
+    return Case(w, seed, weights, x, h0, c0)
+
+
+def select_batch(case: Case, cols: List[int]) -> Case:
+    """The same case restricted to the given batch columns (sequences are independent)."""
+    cols = list(cols)
+    w = replace(case.w, B=len(cols))
+    x = np.ascontiguousarray(case.x[:, cols, :])
+    h0 = None if case.h0 is None else np.ascontiguousarray(case.h0[:, cols, :])
+    c0 = None if case.c0 is None else np.ascontiguousarray(case.c0[:, cols, :])
+    return Case(w, case.seed, case.weights, x, h0, c0)
