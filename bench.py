@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the stacked-LSTM forward pass on one MI355X.
+
+A "step" is one lstm_forward (input projection of every layer + the whole recurrence) over one seeded synthetic
+batch that is already resident in device memory.  Default workload: the 2-layer 1500-wide language-model-shaped
+stack with 90 % masked weights at batch 1, T = 35 (the configuration the latency metric is quoted on).
+
+Prints ONE JSON line.  `value` = microseconds per sequence (lower is better).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2_b1", choices=["c1", "c2_b1", "c2_b20", "c4", "c5"])
+    ap.add_argument("--format", default="auto", choices=["auto", "dense", "csr"])
+    ap.add_argument("--plan", default="auto", choices=["auto", "stepwise", "persistent"])
+    ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also run the hidden-size latency sweep (written to --out)")
+    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"))
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_1901_10997_amd import binding as B
+    from paper_1901_10997_amd import inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.load(build_if_missing=True)
+    dev = torch.device("cuda:0")
+    wl = {"c1": inputs.c1(), "c2_b1": inputs.c2(1), "c2_b20": inputs.c2(20), "c4": inputs.c4(), "c5": inputs.c5()}[args.workload]
+    case = inputs.make_case(wl, 0)
+    dtype = B.LSTM_BF16 if wl.dtype == "bf16" else B.LSTM_F32
+    fmt = {"auto": B.LSTM_FMT_AUTO, "dense": B.LSTM_FMT_DENSE_MASKED, "csr": B.LSTM_FMT_ROW_COMPRESSED}[args.format]
+    plan = {"auto": B.LSTM_PLAN_AUTO, "stepwise": B.LSTM_PLAN_STEPWISE, "persistent": B.LSTM_PLAN_PERSISTENT}[args.plan]
+    m = B.Lstm(wl.layers, wl.input_dim, wl.hidden, wl.bidirectional, dtype)
+    m.set_weights_from(case.weights, fmt)
+    B.lstm_set_plan(m.handle, plan, args.waves)
+    x = torch.from_numpy(case.x).to(dev)
+    if dtype == B.LSTM_BF16:
+        x = x.to(torch.bfloat16)
+    x = x.contiguous()
+    T, Bn, H = wl.T, wl.B, wl.hidden
+    n = wl.layers * wl.ndir
+    y = torch.empty((T, Bn, wl.ndir * H), dtype=torch.float32, device=dev)
+    hT = torch.empty((n, Bn, H), dtype=torch.float32, device=dev)
+    cT = torch.empty((n, Bn, H), dtype=torch.float32, device=dev)
+    ws_bytes = B.lstm_workspace_bytes(m.handle, T, Bn)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+
+    def step():
+        B.lstm_forward(m.handle, T, Bn, x.data_ptr(), None, None, y.data_ptr(), hT.data_ptr(), cT.data_ptr(),
+                       ws.data_ptr(), ws_bytes, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize(dev)
+    B.lstm_check(m.handle)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize(dev)
+    wall = time.perf_counter() - t0
+    B.lstm_check(m.handle)
+    ms_per_step = wall * 1e3 / args.steps
+    us_per_seq = ms_per_step * 1e3 / Bn
+    plan_desc = B.lstm_describe_plan(m.handle)
+
+    # per-kernel durations from events the library records on the same stream (separate pass: the event
+    # pairs perturb the stream, so they stay out of the latency figure above)
+    B.lstm_set_profiling(m.handle, True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize(dev)
+    prof = B.lstm_get_profile(m.handle)
+    B.lstm_set_profiling(m.handle, False)
+    rec_us = prof["rec_us"] / max(prof["rec_launches"], 1)      # average per recurrence launch (one layer-direction)
+    proj_us = prof["proj_us"] / max(prof["proj_launches"], 1)
+
+    # algorithmic bytes of one recurrence launch (one layer, one direction, all T steps)
+    persistent = "persist" in plan_desc
+    compressed = "rec=persist_b1-csr" in plan_desc or "rec=stepwise-csr" in plan_desc
+    wsize = 2 if dtype == B.LSTM_BF16 else 4
+    if compressed:
+        nnz_h = float(np.mean([int(case.weights[k]["Mh"].sum()) if case.weights[k]["Mh"] is not None else 4 * H * H
+                               for k in case.weights]))
+        w_bytes = nnz_h * (4 + 2) + (4 * H + 1) * 4
+    else:
+        w_bytes = 4.0 * H * H * wsize
+    io_bytes = T * Bn * (4 * H * 4 + H * 4)             # read P[t], write y[t]
+    alg_bytes = (w_bytes if persistent else w_bytes * T) + io_bytes
+    achieved = alg_bytes / (rec_us * 1e-6) / 1e9 if rec_us > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "recurrence (" + ("persistent, weights resident on chip" if persistent else "one launch per step") + ")",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": None, "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": rec_us,
+                "proj_avg_launch_us": proj_us}
+    if persistent and Bn == 1:
+        # latency criterion for the on-chip-resident plan: step time against the bare hidden-state exchange
+        try:
+            ex_us = B.lstm_bench_exchange(H, args.waves, 200, 5, stream)
+            roofline["step_us"] = rec_us / T
+            roofline["exchange_only_step_us"] = ex_us
+            roofline["step_over_exchange"] = (rec_us / T) / ex_us if ex_us > 0 else None
+        except B.LstmError as e:
+            roofline["exchange_only_step_us"] = None
+            roofline["exchange_error"] = str(e)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import lstm_oracle
+        cols = list(range(min(Bn, 2)))
+        sub = inputs.select_batch(case, cols)
+        Tc = T
+        if wl.cid == 4:
+            import dataclasses
+            Tc = 30
+            sub = dataclasses.replace(sub, x=sub.x[:Tc].copy())
+        t1 = time.perf_counter()
+        lstm_oracle.forward_case(sub)
+        cpu_s = time.perf_counter() - t1
+        cpu_us_per_seq = cpu_s * 1e6 / len(cols) * (T / Tc)
+        cpu = {"value": cpu_us_per_seq, "unit": "us/seq", "cores": lstm_oracle.max_threads(), "kind": "oracle",
+               "sample": f"{len(cols)} sequence(s) of the same workload, T={Tc} of {T}" + (" (scaled linearly in T)" if Tc != T else "")}
+
+    out = {
+        "metric": "lstm_fwd_latency_us_per_seq", "value": us_per_seq, "unit": "us/seq", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if dtype == B.LSTM_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.layers, "bidirectional": wl.bidirectional, "input_dim": wl.input_dim,
+                   "hidden": H, "T": T, "batch": Bn, "mask_keep": wl.keep, "format": args.format, "plan": plan_desc},
+        "timestep_batch_per_s": T * Bn / (ms_per_step * 1e-3),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    if args.sweep:
+        os.makedirs(args.out, exist_ok=True)
+        Hs = inputs.c3_hidden_sizes()
+        med, p10, p90, flags = B.lstm_latency_sweep(Hs, 35, 1, B.LSTM_F32, 1, 10, 100, stream)
+        f2, red2 = B.lstm_find_lhp(Hs, med, 0.02)
+        f0, red0 = B.lstm_find_lhp(Hs, med, 0.0)
+        with open(os.path.join(args.out, "latency_sweep.json"), "w") as fh:
+            json.dump({"H": Hs, "median_us": list(med), "p10_us": list(p10), "p90_us": list(p90),
+                       "is_lhp_eps0": [int(v) for v in f0], "is_lhp_eps2pct": [int(v) for v in f2],
+                       "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2}, fh)
+        out["sweep"] = {"points": len(Hs), "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2,
+                        "min_us": float(min(med)), "max_us": float(max(med))}
+    m.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

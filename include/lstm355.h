@@ -1,0 +1,180 @@
+/*
+ * liblstm355 -- stacked (optionally bidirectional) LSTM inference forward pass with
+ * sparsity masks, for one AMD MI355X (gfx950).  Plain C ABI: opaque handle, plain
+ * pointers and sizes.  Every pointer below is marked HOST or DEVICE.
+ *
+ * What is computed (paper: Yin et al., "Hardware-Guided Symbiotic Training for Compact,
+ * Accurate, yet Execution-Efficient LSTM", Section 4, cell equations, with zero hidden
+ * layers inside each gate, i.e. the conventional cell used as the paper's baseline in
+ * Section 5):
+ *
+ *     [f; i; o; g] = [sigmoid; sigmoid; sigmoid; tanh]( W . [x_t, h_{t-1}] + b )
+ *     c_t = f (x) c_{t-1} + i (x) g          h_t = o (x) tanh(c_t)
+ *
+ * W is passed as its two column blocks W_x (acts on x_t) and W_h (acts on h_{t-1}).
+ * Each weight matrix may carry a binary mask of the same shape (Section 4, "mask-based
+ * approach"; effective weight = W (x) Msk).  Layers are stacked (Section 5.1); with two
+ * directions (Section 5.2) the second one walks the sequence backwards and the two hidden
+ * sequences are concatenated on the feature axis, forward half first.
+ *
+ * Symbols: L layers, Dn in {1,2} directions, D_0 = input_dim, D_l = Dn*H for l > 0,
+ * H hidden width, T timesteps, B batch.
+ *
+ * All functions return LSTM_OK (0) or a negative LSTM_ERR_* code; none throws or aborts.
+ * lstm_last_error() returns a human-readable description of the most recent failure.
+ * A handle may be used from one host thread and one stream at a time.
+ */
+#ifndef LSTM355_H
+#define LSTM355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lstm355 lstm_t; /* opaque; owned by the library */
+
+/* arithmetic type of the matrix products */
+enum {
+    LSTM_F32 = 0, /* fp32 operands, fp32 accumulation */
+    LSTM_BF16 = 1 /* bf16 weights, inputs and recurrent operand h; fp32 accumulation, fp32 cell state, fp32 outputs */
+};
+
+enum {
+    LSTM_OK = 0,
+    LSTM_ERR_ARG = -1,    /* NULL where a pointer is required, non-positive size, bad enum, mask byte not in {0,1} */
+    LSTM_ERR_SHAPE = -2,  /* layer / direction index outside the model */
+    LSTM_ERR_STATE = -3,  /* forward before every (layer, direction) has weights */
+    LSTM_ERR_NOMEM = -4,  /* device allocation failed, or caller's workspace too small */
+    LSTM_ERR_LAUNCH = -5, /* a HIP call or kernel launch failed */
+    LSTM_ERR_TIMEOUT = -6 /* a bounded device-side wait expired (reported by the next synchronising call) */
+};
+
+/* storage format of one (layer, direction)'s matrices on the device */
+enum {
+    LSTM_FMT_AUTO = 0,          /* library chooses from the mask density */
+    LSTM_FMT_DENSE_MASKED = 1,  /* dense matrix with +0 stored where Msk = 0 */
+    LSTM_FMT_ROW_COMPRESSED = 2 /* per row: the kept positions only, ascending column order */
+};
+
+/* execution plan of the recurrence (debug / measurement override; AUTO is the product path) */
+enum {
+    LSTM_PLAN_AUTO = 0,
+    LSTM_PLAN_STEPWISE = 1,  /* one fused kernel launch per timestep */
+    LSTM_PLAN_PERSISTENT = 2 /* one launch per layer; the time loop runs on the device */
+};
+
+/*
+ * Create a model.  layers >= 1, input_dim >= 1, hidden_dim >= 1, bidirectional in {0,1},
+ * dtype LSTM_F32 or LSTM_BF16.  *out receives the handle.  Uses the current HIP device.
+ */
+int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, int dtype, lstm_t** out);
+
+/* Frees the handle and every device buffer it owns.  NULL is accepted. */
+int lstm_destroy(lstm_t* m);
+
+/* Text of the most recent error on this handle (or of the last failed lstm_create when m is NULL).
+ * The string is owned by the library and valid until the next call on the handle. */
+const char* lstm_last_error(const lstm_t* m);
+
+/*
+ * Set the weights of one (layer, direction).  All pointers HOST, row-major, fp32.
+ *   Wx[4H, D_l], Wh[4H, H], b[4H]; gate rows in the paper's order f, i, o, g:
+ *   rows [0,H) forget, [H,2H) input, [2H,3H) output, [3H,4H) cell candidate.
+ *   mask_x, mask_h: uint8 in {0,1} with the shape of Wx / Wh, or NULL for "keep everything".
+ * The mask is applied as a selection: where the mask byte is 0 the stored value is never read into
+ * the arithmetic, so NaN or Inf there is harmless.  The compressed form keeps exactly the positions
+ * with mask byte 1 (a kept zero value stays a stored entry), columns ascending within a row.
+ * With dtype LSTM_BF16 the matrices are rounded to bf16 (nearest, ties to even); b stays fp32.
+ * The library copies everything; the caller may free its arrays on return.  Synchronous.
+ */
+int lstm_set_weights(lstm_t* m, int layer, int direction,
+                     const float* Wx, const uint8_t* mask_x,
+                     const float* Wh, const uint8_t* mask_h,
+                     const float* b, int format);
+
+/* Bytes of DEVICE workspace lstm_forward needs for (T, B); 0 on bad arguments. */
+size_t lstm_workspace_bytes(const lstm_t* m, int T, int B);
+
+/*
+ * Forward pass of the whole stack.  All data pointers DEVICE, owned by the caller.
+ *   x   [T, B, D_0]     fp32 for LSTM_F32, bf16 (raw uint16 bit patterns) for LSTM_BF16
+ *   h0, c0 [L*Dn, B, H] fp32, index l*Dn + d; NULL = zeros
+ *   y   [T, B, Dn*H]    fp32, hidden sequence of the last layer; the backward direction's state is
+ *                       stored at the input position it was computed for
+ *   hT, cT [L*Dn, B, H] fp32, state after the last step each (layer, direction) processed
+ *                       (t = T-1 forward, t = 0 backward); NULL = not wanted
+ *   workspace           at least lstm_workspace_bytes(m, T, B) bytes, 256-byte aligned
+ *   stream              hipStream_t passed as void*; NULL = the default stream
+ * Asynchronous on `stream`: no host synchronisation and no allocation inside.  T = 0 or B = 0 is a
+ * no-op that returns LSTM_OK.  Two forwards on the same handle must not overlap in time.
+ */
+int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0,
+                 float* y, float* hT, float* cT, void* workspace, size_t workspace_bytes, void* stream);
+
+/* After the stream has been synchronised: LSTM_OK, or LSTM_ERR_TIMEOUT if a device-side bounded wait
+ * expired during an earlier forward on this handle (its outputs are then invalid).  Clears the flag. */
+int lstm_check(lstm_t* m);
+
+/* Override the recurrence plan (LSTM_PLAN_*) and, for measurement, the number of waves per workgroup of
+ * the persistent kernels (0 = library default). */
+int lstm_set_plan(lstm_t* m, int plan, int waves_per_group);
+
+/*
+ * Kernel timing for measurement.  With profiling enabled every forward brackets each of its kernels (or, for
+ * the stepwise plan, each run of per-step launches) with a pair of events on the caller's stream; this
+ * perturbs the stream slightly, so end-to-end latency is quoted with profiling off.
+ * lstm_get_profile synchronises on the recorded events and returns, accumulated since the last call:
+ * total microseconds and launch count of the input-projection kernels (proj) and of the recurrence kernels
+ * (rec).  All pointers HOST, each may be NULL.  Clears the accumulated records.
+ */
+int lstm_set_profiling(lstm_t* m, int enable);
+int lstm_get_profile(lstm_t* m, double* proj_us, int* proj_launches, double* rec_us, int* rec_launches);
+
+/* Writes a short description of the plan the last forward used ("l0:proj=...,rec=...;...") into buf. */
+int lstm_describe_plan(const lstm_t* m, char* buf, size_t buf_bytes);
+
+/*
+ * Read back the row-compressed structure of one matrix as the library stores it, translated to the
+ * ABI row order (row r = q*H + j).  which: 0 = W_x, 1 = W_h.  All pointers HOST.
+ * Call with row_ptr = col = val = NULL to obtain *nnz only.  row_ptr has 4H+1 entries.
+ * LSTM_ERR_STATE if that matrix is not held in compressed form.
+ */
+int lstm_get_compressed(const lstm_t* m, int layer, int direction, int which,
+                        int64_t* nnz, int64_t* row_ptr, int32_t* col, float* val);
+
+/*
+ * Latency profile over the gate dimension (paper Section 3: latency is globally increasing in the
+ * dimension but locally non-monotonic; Section 4: the flow profiles latency on the target hardware to
+ * pick hardware-favoured dimensions).  For each H in Hs: a 1-layer unidirectional model with
+ * input_dim = H, dense seeded weights ~ U(-0.1, 0.1), forget-gate bias 1, x ~ N(0,1); `warmup` untimed
+ * and `iters` timed forwards on `stream`, each bracketed by events.  Writes per point the median, 10th
+ * and 90th percentile latency in microseconds and is_lhp (see lstm_find_lhp, eps = 0).
+ * All pointers HOST.  Allocates and frees its own device buffers; synchronises the stream.
+ */
+int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t seed,
+                       int warmup, int iters, double* med_us, double* p10_us, double* p90_us,
+                       uint8_t* is_lhp, void* stream);
+
+/*
+ * Latency hysteresis points of a measured curve (paper Section 3).  A dimension is a latency
+ * hysteresis point iff it is faster, by the relative margin eps, than every larger dimension:
+ * lat[i] < (1 - eps) * lat[j] for all j with dims[j] > dims[i]; the largest dimension always is one.
+ * redundancy_pct = (1 - #LHP / n) * 100 (caption of the paper's model-level latency figure).
+ * All pointers HOST; dims need not be sorted.  No GPU needed.
+ */
+int lstm_find_lhp(const int* dims, const double* lat, int n, double eps, uint8_t* is_lhp, double* redundancy_pct);
+
+/* Measurement helpers (used by the benchmark to quote achievable peaks next to spec-sheet ones).
+ * copy: device-to-device copy kernel of `bytes` bytes, `iters` times, returns the average microseconds.
+ * barrier: `steps` rounds of the hidden-state exchange with no arithmetic, for `hidden` units and `groups`
+ * workgroups of `waves` waves; returns the average microseconds per round.  DEVICE pointers where named. */
+int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double* avg_us, void* stream);
+int lstm_bench_exchange(int hidden, int waves, int steps, int iters, double* avg_us_per_step, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSTM355_H */

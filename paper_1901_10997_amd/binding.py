@@ -1,0 +1,254 @@
+"""ctypes binding of liblstm355 (include/lstm355.h).  Argument marshalling only: every step of the
+forward pass runs in the library's HIP kernels.  There is no CPU fallback; if the shared library is
+missing, loading raises.
+
+Function names mirror the C ABI.  Device buffers are passed as integer addresses (e.g. the
+``data_ptr()`` of a torch tensor); host arrays are numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+LSTM_F32, LSTM_BF16 = 0, 1
+LSTM_OK = 0
+LSTM_ERR_ARG, LSTM_ERR_SHAPE, LSTM_ERR_STATE, LSTM_ERR_NOMEM, LSTM_ERR_LAUNCH, LSTM_ERR_TIMEOUT = -1, -2, -3, -4, -5, -6
+LSTM_FMT_AUTO, LSTM_FMT_DENSE_MASKED, LSTM_FMT_ROW_COMPRESSED = 0, 1, 2
+LSTM_PLAN_AUTO, LSTM_PLAN_STEPWISE, LSTM_PLAN_PERSISTENT = 0, 1, 2
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblstm355.so")
+
+# every symbol include/lstm355.h declares
+EXPORTS = [
+    "lstm_create", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_workspace_bytes",
+    "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
+    "lstm_latency_sweep", "lstm_find_lhp", "lstm_bench_copy", "lstm_bench_exchange",
+]
+
+_lib = None
+
+
+class LstmError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"liblstm355 error {code}: {msg}")
+        self.code = code
+
+
+def load(build_if_missing: bool = True):
+    """Load liblstm355.so; builds it with hipcc only when no built library is present."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(LIB_PATH)
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    vp, ci = c.c_void_p, c.c_int
+    lib.lstm_create.restype = ci
+    lib.lstm_create.argtypes = [ci, ci, ci, ci, ci, c.POINTER(vp)]
+    lib.lstm_destroy.restype = ci
+    lib.lstm_destroy.argtypes = [vp]
+    lib.lstm_last_error.restype = c.c_char_p
+    lib.lstm_last_error.argtypes = [vp]
+    lib.lstm_set_weights.restype = ci
+    lib.lstm_set_weights.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, ci]
+    lib.lstm_workspace_bytes.restype = c.c_size_t
+    lib.lstm_workspace_bytes.argtypes = [vp, ci, ci]
+    lib.lstm_forward.restype = ci
+    lib.lstm_forward.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, vp, vp, c.c_size_t, vp]
+    lib.lstm_check.restype = ci
+    lib.lstm_check.argtypes = [vp]
+    lib.lstm_set_plan.restype = ci
+    lib.lstm_set_plan.argtypes = [vp, ci, ci]
+    lib.lstm_set_profiling.restype = ci
+    lib.lstm_set_profiling.argtypes = [vp, ci]
+    lib.lstm_get_profile.restype = ci
+    lib.lstm_get_profile.argtypes = [vp, c.POINTER(c.c_double), c.POINTER(ci), c.POINTER(c.c_double), c.POINTER(ci)]
+    lib.lstm_describe_plan.restype = ci
+    lib.lstm_describe_plan.argtypes = [vp, c.c_char_p, c.c_size_t]
+    lib.lstm_get_compressed.restype = ci
+    lib.lstm_get_compressed.argtypes = [vp, ci, ci, ci, c.POINTER(c.c_int64), vp, vp, vp]
+    lib.lstm_latency_sweep.restype = ci
+    lib.lstm_latency_sweep.argtypes = [vp, ci, ci, ci, ci, c.c_uint64, ci, ci, vp, vp, vp, vp, vp]
+    lib.lstm_find_lhp.restype = ci
+    lib.lstm_find_lhp.argtypes = [vp, vp, ci, c.c_double, vp, c.POINTER(c.c_double)]
+    lib.lstm_bench_copy.restype = ci
+    lib.lstm_bench_copy.argtypes = [vp, vp, c.c_size_t, ci, c.POINTER(c.c_double), vp]
+    lib.lstm_bench_exchange.restype = ci
+    lib.lstm_bench_exchange.argtypes = [ci, ci, ci, ci, c.POINTER(c.c_double), vp]
+    _lib = lib
+    return lib
+
+
+def _err(handle) -> str:
+    s = load().lstm_last_error(handle)
+    return s.decode() if s else ""
+
+
+def _check(rc: int, handle=None):
+    if rc != LSTM_OK:
+        raise LstmError(rc, _err(handle))
+
+
+def _host(a, dtype) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data
+
+
+def lstm_create(layers: int, input_dim: int, hidden_dim: int, bidirectional: bool, dtype: int = LSTM_F32):
+    h = ctypes.c_void_p()
+    _check(load().lstm_create(layers, input_dim, hidden_dim, int(bool(bidirectional)), dtype, ctypes.byref(h)))
+    return h
+
+
+def lstm_destroy(handle) -> None:
+    _check(load().lstm_destroy(handle))
+
+
+def lstm_set_weights(handle, layer: int, direction: int, Wx, mask_x, Wh, mask_h, b, fmt: int = LSTM_FMT_AUTO) -> None:
+    Wx, Wh, b = _host(Wx, np.float32), _host(Wh, np.float32), _host(b, np.float32)
+    mx, mh = _host(mask_x, np.uint8), _host(mask_h, np.uint8)
+    if mx is not None and mx.shape != Wx.shape or mh is not None and mh.shape != Wh.shape:
+        raise ValueError("mask shape differs from its weight matrix")
+    _check(load().lstm_set_weights(handle, layer, direction, _p(Wx), _p(mx), _p(Wh), _p(mh), _p(b), fmt), handle)
+
+
+def lstm_workspace_bytes(handle, T: int, B: int) -> int:
+    return int(load().lstm_workspace_bytes(handle, T, B))
+
+
+def lstm_forward(handle, T: int, B: int, x_ptr: int, h0_ptr: Optional[int], c0_ptr: Optional[int], y_ptr: int,
+                 hT_ptr: Optional[int], cT_ptr: Optional[int], ws_ptr: int, ws_bytes: int, stream: Optional[int] = None):
+    _check(load().lstm_forward(handle, T, B, x_ptr, h0_ptr, c0_ptr, y_ptr, hT_ptr, cT_ptr, ws_ptr, ws_bytes, stream),
+           handle)
+
+
+def lstm_check(handle) -> None:
+    _check(load().lstm_check(handle), handle)
+
+
+def lstm_set_plan(handle, plan: int, waves_per_group: int = 0) -> None:
+    _check(load().lstm_set_plan(handle, plan, waves_per_group), handle)
+
+
+def lstm_set_profiling(handle, enable: bool) -> None:
+    _check(load().lstm_set_profiling(handle, int(bool(enable))), handle)
+
+
+def lstm_get_profile(handle):
+    """Returns dict(proj_us, proj_launches, rec_us, rec_launches) accumulated since the previous call."""
+    pu, ru = ctypes.c_double(), ctypes.c_double()
+    pn, rn = ctypes.c_int(), ctypes.c_int()
+    _check(load().lstm_get_profile(handle, ctypes.byref(pu), ctypes.byref(pn), ctypes.byref(ru), ctypes.byref(rn)), handle)
+    return dict(proj_us=pu.value, proj_launches=pn.value, rec_us=ru.value, rec_launches=rn.value)
+
+
+def lstm_describe_plan(handle) -> str:
+    buf = ctypes.create_string_buffer(2048)
+    _check(load().lstm_describe_plan(handle, buf, len(buf)), handle)
+    return buf.value.decode()
+
+
+def lstm_get_compressed(handle, layer: int, direction: int, which: int, rows: int):
+    lib = load()
+    nnz = ctypes.c_int64()
+    _check(lib.lstm_get_compressed(handle, layer, direction, which, ctypes.byref(nnz), None, None, None), handle)
+    row_ptr = np.zeros(rows + 1, np.int64)
+    col = np.zeros(max(nnz.value, 1), np.int32)
+    val = np.zeros(max(nnz.value, 1), np.float32)
+    _check(lib.lstm_get_compressed(handle, layer, direction, which, ctypes.byref(nnz), row_ptr.ctypes.data,
+                                   col.ctypes.data, val.ctypes.data), handle)
+    return row_ptr, col[:nnz.value], val[:nnz.value]
+
+
+def lstm_latency_sweep(Hs: Sequence[int], T: int, B: int, dtype: int = LSTM_F32, seed: int = 1, warmup: int = 10,
+                       iters: int = 100, stream: Optional[int] = None):
+    Hs = np.ascontiguousarray(Hs, dtype=np.int32)
+    n = len(Hs)
+    med, p10, p90 = np.zeros(n), np.zeros(n), np.zeros(n)
+    flags = np.zeros(n, np.uint8)
+    _check(load().lstm_latency_sweep(Hs.ctypes.data, n, T, B, dtype, seed, warmup, iters, med.ctypes.data,
+                                     p10.ctypes.data, p90.ctypes.data, flags.ctypes.data, stream))
+    return med, p10, p90, flags
+
+
+def lstm_find_lhp(dims: Sequence[int], lat: Sequence[float], eps: float = 0.0):
+    dims = np.ascontiguousarray(dims, dtype=np.int32)
+    lat = np.ascontiguousarray(lat, dtype=np.float64)
+    flags = np.zeros(len(dims), np.uint8)
+    red = ctypes.c_double()
+    _check(load().lstm_find_lhp(dims.ctypes.data, lat.ctypes.data, len(dims), eps, flags.ctypes.data, ctypes.byref(red)))
+    return flags, red.value
+
+
+def lstm_bench_copy(dst_ptr: int, src_ptr: int, nbytes: int, iters: int = 20, stream: Optional[int] = None) -> float:
+    us = ctypes.c_double()
+    _check(load().lstm_bench_copy(dst_ptr, src_ptr, nbytes, iters, ctypes.byref(us), stream))
+    return us.value
+
+
+def lstm_bench_exchange(hidden: int, waves: int = 0, steps: int = 200, iters: int = 5, stream: Optional[int] = None) -> float:
+    us = ctypes.c_double()
+    _check(load().lstm_bench_exchange(hidden, waves, steps, iters, ctypes.byref(us), stream))
+    return us.value
+
+
+# ------------------------------------------------------------------------------------------------------------
+# Convenience wrapper for tests and the benchmark: owns a handle plus torch device buffers.
+# ------------------------------------------------------------------------------------------------------------
+class Lstm:
+    def __init__(self, layers: int, input_dim: int, hidden: int, bidirectional: bool = False, dtype: int = LSTM_F32):
+        self.layers, self.input_dim, self.hidden = layers, input_dim, hidden
+        self.ndir = 2 if bidirectional else 1
+        self.dtype = dtype
+        self.handle = lstm_create(layers, input_dim, hidden, bidirectional, dtype)
+        self._ws = None
+
+    def close(self):
+        if self.handle is not None:
+            lstm_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_weights_from(self, weights, fmt: int = LSTM_FMT_AUTO):
+        for (l, d), p in weights.items():
+            lstm_set_weights(self.handle, l, d, p["Wx"], p.get("Mx"), p["Wh"], p.get("Mh"), p["b"], fmt)
+
+    def forward(self, x, h0=None, c0=None, want_state: bool = True, stream=None, check: bool = True):
+        """x: torch device tensor [T,B,D0] (float32, or bfloat16 for bf16 models).  Returns (y, hT, cT)."""
+        import torch
+        T, B, D0 = x.shape
+        assert D0 == self.input_dim and x.is_contiguous()
+        assert x.dtype == (torch.bfloat16 if self.dtype == LSTM_BF16 else torch.float32)
+        dev = x.device
+        n = self.layers * self.ndir
+        y = torch.empty((T, B, self.ndir * self.hidden), dtype=torch.float32, device=dev)
+        hT = torch.empty((n, B, self.hidden), dtype=torch.float32, device=dev) if want_state else None
+        cT = torch.empty((n, B, self.hidden), dtype=torch.float32, device=dev) if want_state else None
+        need = lstm_workspace_bytes(self.handle, T, B)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        if stream is None:
+            stream = torch.cuda.current_stream(dev).cuda_stream
+        lstm_forward(self.handle, T, B, x.data_ptr(),
+                     None if h0 is None else h0.data_ptr(), None if c0 is None else c0.data_ptr(),
+                     y.data_ptr(), None if hT is None else hT.data_ptr(), None if cT is None else cT.data_ptr(),
+                     self._ws.data_ptr(), self._ws.numel(), stream)
+        if check:
+            torch.cuda.synchronize(dev)
+            lstm_check(self.handle)
+        return y, hT, cT

@@ -1,0 +1,99 @@
+// Internal declarations shared by the host code and the kernel launchers of liblstm355.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+namespace l355 {
+
+// One weight matrix (W_x or W_h) of one (layer, direction), as held on the device.
+// Row order is "packed": packed row 4*j + q holds gate q (0=f,1=i,2=o,3=g) of hidden unit j, so the
+// four pre-activations a cell update needs are adjacent.
+struct PackedMat {
+    int rows = 0, cols = 0;
+    bool compressed = false;
+    void* dense = nullptr;       // [rows][cols], fp32 or bf16 bits; +0 where the mask is 0
+    int64_t nnz = 0;             // compressed: kept positions (== popcount of the mask)
+    int32_t* row_ptr = nullptr;  // device [rows+1]
+    uint16_t* col16 = nullptr;   // device [nnz]  (cols <= 65536)
+    float* val = nullptr;        // device [nnz], fp32 (bf16-representable values in bf16 models)
+    int max_row_nnz = 0;
+    // register-resident slices for the persistent batch-1 kernel: [rows][slots][64] entries
+    int slots = 0;               // ceil(max_row_nnz / 64)
+    float* ell_val = nullptr;    // device [rows*slots*64]
+    uint16_t* ell_col = nullptr; // device [rows*slots*64]
+    // host copy of the compressed structure in packed row order (for read-back)
+    std::vector<int64_t> h_row_ptr;
+    std::vector<int32_t> h_col;
+    std::vector<float> h_val;
+};
+
+struct LayerDir {
+    bool set = false;
+    PackedMat wx, wh;
+    float* bias = nullptr;  // device [4H], packed row order, fp32
+};
+
+// ---- kernel launchers (all asynchronous on `s`; return hipError_t of the launch) ----
+
+// P[m][n] = bias[n] + sum_k X[m][k] * W[n][k];  X fp32 or bf16 (x_bf16), W fp32 or bf16 (w_bf16).
+hipError_t launch_proj_dense(const void* X, bool x_bf16, int ldx, const void* W, bool w_bf16, const float* bias,
+                             float* P, int M, int N, int K, hipStream_t s);
+// XT[k][m] = (float) X[m][k]   (optionally rounding fp32 -> bf16 -> fp32 on the way)
+hipError_t launch_transpose_to_f32(const void* X, bool x_bf16, int ldx, float* XT, int M, int K, bool round_bf16,
+                                   hipStream_t s);
+// P[m][r] = bias[r] + sum_{i in row r} val[i] * XT[col[i]][m]
+hipError_t launch_proj_csr(const float* XT, const int32_t* row_ptr, const uint16_t* col, const float* val,
+                           const float* bias, float* P, int M, int rows, hipStream_t s);
+
+struct StepArgs {
+    const float* P;        // [T*B][4H] pre-activations from the input projection (bias included)
+    const float* h_prev;   // h_{t-1}: element (b,k) at h_prev[b*h_prev_ld + k]; nullptr = zeros
+    int h_prev_ld;
+    float* c;              // [B][H] cell state, updated in place
+    float* y_t;            // h_t goes to y_t[b*y_ld + j]
+    int y_ld;
+    float* hT;             // optional [B][H]: written when last != 0
+    float* cT;
+    int last;
+    int t;                 // time index into P
+    int B, H;
+    int round_h_bf16;      // bf16 models: the recurrent operand h is rounded to bf16 when read
+};
+hipError_t launch_step_dense(const StepArgs& a, const void* Wh, bool w_bf16, hipStream_t s);
+hipError_t launch_step_csr(const StepArgs& a, const int32_t* row_ptr, const uint16_t* col, const float* val,
+                           hipStream_t s);
+
+struct PersistB1Args {
+    const float* P;        // [T][4H]
+    const float* h0;       // [H] or nullptr
+    const float* c0;       // [H] or nullptr
+    float* y;              // h_t -> y[t*y_ld + j]
+    int y_ld;
+    float* hT;             // [H] or nullptr
+    float* cT;
+    int T, H;
+    int reverse;           // 1: walk t = T-1 .. 0
+    int round_h_bf16;
+    unsigned long long* xchg;  // [2][H] (value, tag) slots, library-owned
+    unsigned tag_base;         // tags tag_base+1 .. tag_base+T are used by this launch
+    int* timeout_flag;         // set to 1 if a bounded wait expired
+    unsigned spin_limit;
+};
+// Dense, weights resident in registers.  Wh: [4H][H] fp32 or bf16 in packed row order.
+hipError_t launch_persist_b1_dense(const PersistB1Args& a, const void* Wh, bool w_bf16, int waves_per_group,
+                                   hipStream_t s);
+// Row-compressed, (value, column) slices resident in registers.
+hipError_t launch_persist_b1_sparse(const PersistB1Args& a, const float* ell_val, const uint16_t* ell_col, int slots,
+                                    int waves_per_group, hipStream_t s);
+bool persist_b1_dense_supported(int H);
+bool persist_b1_sparse_supported(int H, int slots);
+
+hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
+hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t launch_exchange_only(unsigned long long* xchg, unsigned tag_base, int H, int waves, int steps,
+                                int* timeout_flag, unsigned spin_limit, hipStream_t s);
+
+}  // namespace l355

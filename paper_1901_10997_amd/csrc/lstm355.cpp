@@ -1,0 +1,736 @@
+// Host side of liblstm355: handle, weight packing, workspace carve-up, launch sequencing, latency sweep.
+// The C ABI is declared and documented in include/lstm355.h.
+#include "../../include/lstm355.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+using namespace l355;
+
+struct lstm355 {
+    int L = 0, D0 = 0, H = 0, Dn = 1, dtype = LSTM_F32;
+    int device = 0;
+    std::vector<LayerDir> ld;  // index l*Dn + d
+    mutable std::string err;
+    unsigned long long* xchg = nullptr;  // [Dn][2][H] tagged exchange slots of the persistent batch-1 kernels
+    unsigned tag_base = 0;               // tags <= tag_base have been used
+    int* timeout_flag = nullptr;         // device int
+    unsigned spin_limit = 1u << 22;
+    int plan = LSTM_PLAN_AUTO;
+    int waves_per_group = 0;
+    std::string last_plan;
+    bool profiling = false;
+    struct Span { hipEvent_t e0, e1; int kind; };
+    std::vector<Span> spans;             // recorded, not yet read
+    std::vector<hipEvent_t> event_pool;  // idle events
+    int in_dim(int l) const { return l == 0 ? D0 : Dn * H; }
+};
+
+static thread_local std::string g_create_error;
+
+static int fail(const lstm_t* m, int code, const std::string& msg)
+{
+    if (m) m->err = msg; else g_create_error = msg;
+    return code;
+}
+static int fail_hip(const lstm_t* m, hipError_t e, const char* what)
+{
+    return fail(m, e == hipErrorOutOfMemory ? LSTM_ERR_NOMEM : LSTM_ERR_LAUNCH,
+                std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(m, call)                                   \
+    do {                                                   \
+        hipError_t e__ = (call);                           \
+        if (e__ != hipSuccess) return fail_hip(m, e__, #call); \
+    } while (0)
+
+// RAII bracket: records an event pair around the launches issued during its lifetime (profiling only).
+struct ProfSpan {
+    lstm_t* m; hipStream_t s; int idx = -1;
+    ProfSpan(lstm_t* m_, hipStream_t s_, int kind) : m(m_), s(s_)
+    {
+        if (!m->profiling) return;
+        hipEvent_t ev[2];
+        for (auto& e : ev) {
+            if (!m->event_pool.empty()) { e = m->event_pool.back(); m->event_pool.pop_back(); }
+            else if (hipEventCreate(&e) != hipSuccess) return;
+        }
+        m->spans.push_back({ev[0], ev[1], kind});
+        idx = (int)m->spans.size() - 1;
+        (void)hipEventRecord(ev[0], s);
+    }
+    ~ProfSpan() { if (idx >= 0) (void)hipEventRecord(m->spans[idx].e1, s); }
+};
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+static uint16_t host_f32_to_bf16(float f)
+{
+    uint32_t u;
+    std::memcpy(&u, &f, 4);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) return (uint16_t)((u >> 16) | 0x0040u);  // NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+static float host_bf16_to_f32(uint16_t b)
+{
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+static void free_mat(PackedMat& p)
+{
+    if (p.dense) (void)hipFree(p.dense);
+    if (p.row_ptr) (void)hipFree(p.row_ptr);
+    if (p.col16) (void)hipFree(p.col16);
+    if (p.val) (void)hipFree(p.val);
+    if (p.ell_val) (void)hipFree(p.ell_val);
+    if (p.ell_col) (void)hipFree(p.ell_col);
+    p = PackedMat();
+}
+
+template <typename T>
+static hipError_t upload(T** dst, const std::vector<T>& src)
+{
+    *dst = nullptr;
+    const size_t bytes = std::max<size_t>(src.size(), 1) * sizeof(T);
+    hipError_t e = hipMalloc((void**)dst, bytes);
+    if (e != hipSuccess) return e;
+    if (!src.empty()) e = hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+    return e;
+}
+
+// Pack one matrix W[4H][cols] (ABI row order q*H + j) with its optional mask into device storage.
+static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t* mask, int H, int cols, bool compressed,
+                       bool bf16)
+{
+    free_mat(out);
+    const int rows = 4 * H;
+    out.rows = rows;
+    out.cols = cols;
+    out.compressed = compressed;
+    auto abi_row = [H](int rp) { return (rp & 3) * H + (rp >> 2); };
+    if (!compressed) {
+        const size_t n = (size_t)rows * cols;
+        if (bf16) {
+            std::vector<uint16_t> buf(n);
+            for (int rp = 0; rp < rows; ++rp) {
+                const size_t src = (size_t)abi_row(rp) * cols, dst = (size_t)rp * cols;
+                for (int k = 0; k < cols; ++k)
+                    buf[dst + k] = (mask == nullptr || mask[src + k]) ? host_f32_to_bf16(W[src + k]) : (uint16_t)0;
+            }
+            uint16_t* d = nullptr;
+            HIP_TRY(m, upload(&d, buf));
+            out.dense = d;
+        } else {
+            std::vector<float> buf(n);
+            for (int rp = 0; rp < rows; ++rp) {
+                const size_t src = (size_t)abi_row(rp) * cols, dst = (size_t)rp * cols;
+                for (int k = 0; k < cols; ++k) buf[dst + k] = (mask == nullptr || mask[src + k]) ? W[src + k] : 0.0f;
+            }
+            float* d = nullptr;
+            HIP_TRY(m, upload(&d, buf));
+            out.dense = d;
+        }
+        return LSTM_OK;
+    }
+    // row-compressed: structure = the mask (every position when there is no mask), columns ascending
+    out.h_row_ptr.assign(rows + 1, 0);
+    out.h_col.clear();
+    out.h_val.clear();
+    int max_nnz = 0;
+    for (int rp = 0; rp < rows; ++rp) {
+        const size_t src = (size_t)abi_row(rp) * cols;
+        int cnt = 0;
+        for (int k = 0; k < cols; ++k) {
+            if (mask == nullptr || mask[src + k]) {
+                float v = W[src + k];
+                if (bf16) v = host_bf16_to_f32(host_f32_to_bf16(v));
+                out.h_col.push_back(k);
+                out.h_val.push_back(v);
+                ++cnt;
+            }
+        }
+        out.h_row_ptr[rp + 1] = (int64_t)out.h_col.size();
+        max_nnz = std::max(max_nnz, cnt);
+    }
+    out.nnz = (int64_t)out.h_col.size();
+    out.max_row_nnz = max_nnz;
+    std::vector<int32_t> rp32(rows + 1);
+    for (int i = 0; i <= rows; ++i) rp32[i] = (int32_t)out.h_row_ptr[i];
+    std::vector<uint16_t> c16(out.h_col.size());
+    for (size_t i = 0; i < c16.size(); ++i) c16[i] = (uint16_t)out.h_col[i];
+    HIP_TRY(m, upload(&out.row_ptr, rp32));
+    HIP_TRY(m, upload(&out.col16, c16));
+    HIP_TRY(m, upload(&out.val, out.h_val));
+    // 64-lane slices for the register-resident batch-1 kernel: entry i of a row -> slot i/64, lane i%64
+    out.slots = std::max(1, (max_nnz + 63) / 64);
+    if (out.slots <= 8) {
+        std::vector<float> ev((size_t)rows * out.slots * 64, 0.0f);
+        std::vector<uint16_t> ec((size_t)rows * out.slots * 64, 0);
+        for (int rp = 0; rp < rows; ++rp) {
+            const int64_t beg = out.h_row_ptr[rp], end = out.h_row_ptr[rp + 1];
+            for (int64_t e = beg; e < end; ++e) {
+                const size_t idx = (size_t)rp * out.slots * 64 + (size_t)(e - beg);
+                ev[idx] = out.h_val[e];
+                ec[idx] = (uint16_t)out.h_col[e];
+            }
+        }
+        HIP_TRY(m, upload(&out.ell_val, ev));
+        HIP_TRY(m, upload(&out.ell_col, ec));
+    }
+    return LSTM_OK;
+}
+
+extern "C" {
+
+int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, int dtype, lstm_t** out)
+{
+    if (!out) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: out is NULL");
+    *out = nullptr;
+    if (layers < 1 || input_dim < 1 || hidden_dim < 1)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_create: layers, input_dim and hidden_dim must be >= 1");
+    if (bidirectional != 0 && bidirectional != 1)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_create: bidirectional must be 0 or 1");
+    if (dtype != LSTM_F32 && dtype != LSTM_BF16) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: unknown dtype");
+    if ((long long)hidden_dim * 4 > (1 << 28) || input_dim > (1 << 28))
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_create: dimension too large");
+    lstm_t* m = new (std::nothrow) lstm355();
+    if (!m) return fail(nullptr, LSTM_ERR_NOMEM, "lstm_create: host allocation failed");
+    m->L = layers;
+    m->D0 = input_dim;
+    m->H = hidden_dim;
+    m->Dn = bidirectional ? 2 : 1;
+    m->dtype = dtype;
+    m->ld.resize((size_t)m->L * m->Dn);
+    if (const char* sl = std::getenv("LSTM355_SPIN_LIMIT")) {
+        const long v = std::atol(sl);
+        if (v > 0) m->spin_limit = (unsigned)v;
+    }
+    hipError_t e = hipGetDevice(&m->device);
+    const size_t slots = (size_t)m->Dn * 2 * m->H;
+    if (e == hipSuccess) e = hipMalloc((void**)&m->xchg, slots * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMemset(m->xchg, 0, slots * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMalloc((void**)&m->timeout_flag, sizeof(int));
+    if (e == hipSuccess) e = hipMemset(m->timeout_flag, 0, sizeof(int));
+    if (e != hipSuccess) {
+        const int rc = fail_hip(nullptr, e, "lstm_create: device set-up");
+        lstm_destroy(m);
+        return rc;
+    }
+    *out = m;
+    return LSTM_OK;
+}
+
+int lstm_destroy(lstm_t* m)
+{
+    if (!m) return LSTM_OK;
+    for (auto& x : m->ld) {
+        free_mat(x.wx);
+        free_mat(x.wh);
+        if (x.bias) (void)hipFree(x.bias);
+    }
+    for (auto& sp : m->spans) { (void)hipEventDestroy(sp.e0); (void)hipEventDestroy(sp.e1); }
+    for (auto& e : m->event_pool) (void)hipEventDestroy(e);
+    if (m->xchg) (void)hipFree(m->xchg);
+    if (m->timeout_flag) (void)hipFree(m->timeout_flag);
+    delete m;
+    return LSTM_OK;
+}
+
+const char* lstm_last_error(const lstm_t* m) { return m ? m->err.c_str() : g_create_error.c_str(); }
+
+int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const uint8_t* mask_x, const float* Wh,
+                     const uint8_t* mask_h, const float* b, int format)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_set_weights: handle is NULL");
+    if (layer < 0 || layer >= m->L || direction < 0 || direction >= m->Dn)
+        return fail(m, LSTM_ERR_SHAPE, "lstm_set_weights: layer/direction outside the model");
+    if (!Wx || !Wh || !b) return fail(m, LSTM_ERR_ARG, "lstm_set_weights: Wx, Wh and b are required");
+    if (format != LSTM_FMT_AUTO && format != LSTM_FMT_DENSE_MASKED && format != LSTM_FMT_ROW_COMPRESSED)
+        return fail(m, LSTM_ERR_ARG, "lstm_set_weights: unknown format");
+    const int H = m->H, D = m->in_dim(layer), rows = 4 * H;
+    size_t kept = 0, total = (size_t)rows * D + (size_t)rows * H;
+    for (int which = 0; which < 2; ++which) {
+        const uint8_t* mk = which ? mask_h : mask_x;
+        const size_t n = (size_t)rows * (which ? H : D);
+        if (!mk) { kept += n; continue; }
+        for (size_t i = 0; i < n; ++i) {
+            if (mk[i] > 1) return fail(m, LSTM_ERR_ARG, "lstm_set_weights: mask bytes must be 0 or 1");
+            kept += mk[i];
+        }
+    }
+    bool compressed;
+    if (format == LSTM_FMT_AUTO)
+        compressed = (mask_x || mask_h) && (double)kept <= 0.25 * (double)total;
+    else
+        compressed = (format == LSTM_FMT_ROW_COMPRESSED);
+    if (compressed && (D > 65536 || H > 65536))
+        return fail(m, LSTM_ERR_ARG, "lstm_set_weights: row-compressed form needs dimensions <= 65536");
+    HIP_TRY(m, hipSetDevice(m->device));
+    LayerDir& x = m->ld[(size_t)layer * m->Dn + direction];
+    x.set = false;
+    const bool bf16 = (m->dtype == LSTM_BF16);
+    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16);
+    if (rc != LSTM_OK) return rc;
+    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16);
+    if (rc != LSTM_OK) return rc;
+    std::vector<float> bp(rows);
+    for (int rp = 0; rp < rows; ++rp) bp[rp] = b[(rp & 3) * H + (rp >> 2)];
+    if (x.bias) { (void)hipFree(x.bias); x.bias = nullptr; }
+    HIP_TRY(m, upload(&x.bias, bp));
+    x.set = true;
+    return LSTM_OK;
+}
+
+// ---- workspace carve-up --------------------------------------------------------------------------------
+struct Workspace {
+    size_t P_off[2], XT_off, Y_off[2], c_off[2], total;
+};
+static Workspace carve(const lstm_t* m, int T, int B)
+{
+    Workspace w{};
+    size_t off = 0;
+    const size_t M = (size_t)T * B, H = m->H;
+    for (int d = 0; d < 2; ++d) {
+        w.P_off[d] = off;
+        if (d < m->Dn) off += align256(M * 4 * H * sizeof(float));
+    }
+    size_t Dmax = (size_t)m->D0;
+    if (m->L > 1) Dmax = std::max(Dmax, (size_t)m->Dn * H);
+    w.XT_off = off;
+    off += align256(Dmax * M * sizeof(float));
+    for (int i = 0; i < 2; ++i) {
+        w.Y_off[i] = off;
+        if (m->L > 1) off += align256(M * m->Dn * H * sizeof(float));
+    }
+    for (int d = 0; d < 2; ++d) {
+        w.c_off[d] = off;
+        if (d < m->Dn) off += align256((size_t)B * H * sizeof(float));
+    }
+    w.total = off;
+    return w;
+}
+
+size_t lstm_workspace_bytes(const lstm_t* m, int T, int B)
+{
+    if (!m || T < 0 || B < 0) return 0;
+    if (T == 0 || B == 0) return 256;
+    return carve(m, T, B).total;
+}
+
+int lstm_set_plan(lstm_t* m, int plan, int waves_per_group)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_set_plan: handle is NULL");
+    if (plan != LSTM_PLAN_AUTO && plan != LSTM_PLAN_STEPWISE && plan != LSTM_PLAN_PERSISTENT)
+        return fail(m, LSTM_ERR_ARG, "lstm_set_plan: unknown plan");
+    if (waves_per_group < 0 || waves_per_group > 16)
+        return fail(m, LSTM_ERR_ARG, "lstm_set_plan: waves_per_group must be in [0,16]");
+    m->plan = plan;
+    m->waves_per_group = waves_per_group;
+    return LSTM_OK;
+}
+
+int lstm_set_profiling(lstm_t* m, int enable)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_set_profiling: handle is NULL");
+    m->profiling = enable != 0;
+    return LSTM_OK;
+}
+
+int lstm_get_profile(lstm_t* m, double* proj_us, int* proj_launches, double* rec_us, int* rec_launches)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_get_profile: handle is NULL");
+    double us[2] = {0.0, 0.0};
+    int cnt[2] = {0, 0};
+    int rc = LSTM_OK;
+    for (auto& sp : m->spans) {
+        float ms = 0.f;
+        hipError_t e = hipEventSynchronize(sp.e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, sp.e0, sp.e1);
+        if (e != hipSuccess) rc = fail_hip(m, e, "lstm_get_profile");
+        us[sp.kind] += (double)ms * 1000.0;
+        cnt[sp.kind] += 1;
+        m->event_pool.push_back(sp.e0);
+        m->event_pool.push_back(sp.e1);
+    }
+    m->spans.clear();
+    if (proj_us) *proj_us = us[0];
+    if (proj_launches) *proj_launches = cnt[0];
+    if (rec_us) *rec_us = us[1];
+    if (rec_launches) *rec_launches = cnt[1];
+    return rc;
+}
+
+int lstm_describe_plan(const lstm_t* m, char* buf, size_t buf_bytes)
+{
+    if (!m || !buf || buf_bytes == 0) return fail(m, LSTM_ERR_ARG, "lstm_describe_plan: bad arguments");
+    std::snprintf(buf, buf_bytes, "%s", m->last_plan.c_str());
+    return LSTM_OK;
+}
+
+int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0, float* y, float* hT,
+                 float* cT, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_forward: handle is NULL");
+    if (T < 0 || B < 0) return fail(m, LSTM_ERR_ARG, "lstm_forward: T and B must be >= 0");
+    for (const auto& x_ : m->ld)
+        if (!x_.set) return fail(m, LSTM_ERR_STATE, "lstm_forward: weights of some (layer, direction) not set");
+    if (T == 0 || B == 0) return LSTM_OK;
+    if (!x || !y) return fail(m, LSTM_ERR_ARG, "lstm_forward: x and y are required");
+    if (!workspace) return fail(m, LSTM_ERR_ARG, "lstm_forward: workspace is NULL");
+    if (((uintptr_t)workspace & 255) != 0) return fail(m, LSTM_ERR_ARG, "lstm_forward: workspace must be 256-byte aligned");
+    if ((long long)T * B > (1ll << 30)) return fail(m, LSTM_ERR_ARG, "lstm_forward: T*B too large");
+    const Workspace ws = carve(m, T, B);
+    if (workspace_bytes < ws.total) return fail(m, LSTM_ERR_NOMEM, "lstm_forward: workspace too small");
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)workspace;
+    const int H = m->H, Dn = m->Dn, L = m->L;
+    const int M = T * B;
+    const bool bf16 = (m->dtype == LSTM_BF16);
+    float* P[2] = {(float*)(base + ws.P_off[0]), (float*)(base + ws.P_off[1])};
+    float* XT = (float*)(base + ws.XT_off);
+    float* Ybuf[2] = {(float*)(base + ws.Y_off[0]), (float*)(base + ws.Y_off[1])};
+    float* cbuf[2] = {(float*)(base + ws.c_off[0]), (float*)(base + ws.c_off[1])};
+    m->last_plan.clear();
+
+    for (int l = 0; l < L; ++l) {
+        const int D = m->in_dim(l);
+        const void* X = (l == 0) ? x : (const void*)Ybuf[(l - 1) & 1];
+        const bool x_is_bf16 = (l == 0) && bf16;
+        float* Yout = (l == L - 1) ? y : Ybuf[l & 1];
+        const int y_ld = Dn * H;
+        // ---- input projection for every timestep, both directions
+        bool xt_ready = false;
+        for (int d = 0; d < Dn; ++d) {
+            const LayerDir& w = m->ld[(size_t)l * Dn + d];
+            ProfSpan span(m, s, 0);
+            if (w.wx.compressed) {
+                if (!xt_ready) {
+                    HIP_TRY(m, launch_transpose_to_f32(X, x_is_bf16, D, XT, M, D, bf16 && !x_is_bf16, s));
+                    xt_ready = true;
+                }
+                HIP_TRY(m, launch_proj_csr(XT, w.wx.row_ptr, w.wx.col16, w.wx.val, w.bias, P[d], M, 4 * H, s));
+            } else {
+                HIP_TRY(m, launch_proj_dense(X, x_is_bf16, D, w.wx.dense, bf16, w.bias, P[d], M, 4 * H, D, s));
+            }
+        }
+        // ---- recurrence
+        for (int d = 0; d < Dn; ++d) {
+            const LayerDir& w = m->ld[(size_t)l * Dn + d];
+            const size_t n = (size_t)l * Dn + d;
+            const float* h0n = h0 ? h0 + n * B * H : nullptr;
+            const float* c0n = c0 ? c0 + n * B * H : nullptr;
+            float* hTn = hT ? hT + n * B * H : nullptr;
+            float* cTn = cT ? cT + n * B * H : nullptr;
+            bool persistent = false;
+            if (B == 1 && m->plan != LSTM_PLAN_STEPWISE) {
+                persistent = w.wh.compressed ? (w.wh.ell_val && persist_b1_sparse_supported(H, w.wh.slots) && H <= 8192)
+                                             : persist_b1_dense_supported(H);
+            }
+            if (m->plan == LSTM_PLAN_PERSISTENT && !persistent)
+                return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
+            char tag[96];
+            std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=%s-%s;", l, d, w.wx.compressed ? "csr" : "dense",
+                          persistent ? "persist_b1" : "stepwise", w.wh.compressed ? "csr" : "dense");
+            m->last_plan += tag;
+            ProfSpan span(m, s, 1);
+            if (persistent) {
+                if (m->tag_base > 0xFFFFFFFFu - (unsigned)T - 2u) {
+                    // tag space exhausted: restart from a clean slate
+                    HIP_TRY(m, launch_fill_u64(m->xchg, (size_t)Dn * 2 * H, 0ull, s));
+                    m->tag_base = 0;
+                }
+                PersistB1Args a{};
+                a.P = P[d];
+                a.h0 = h0n;
+                a.c0 = c0n;
+                a.y = Yout + (size_t)d * H;
+                a.y_ld = y_ld;
+                a.hT = hTn;
+                a.cT = cTn;
+                a.T = T;
+                a.H = H;
+                a.reverse = d;
+                a.round_h_bf16 = bf16 ? 1 : 0;
+                a.xchg = m->xchg + (size_t)d * 2 * H;
+                a.tag_base = m->tag_base;
+                a.timeout_flag = m->timeout_flag;
+                a.spin_limit = m->spin_limit;
+                m->tag_base += (unsigned)T;
+                if (w.wh.compressed)
+                    HIP_TRY(m, launch_persist_b1_sparse(a, w.wh.ell_val, w.wh.ell_col, w.wh.slots, m->waves_per_group, s));
+                else
+                    HIP_TRY(m, launch_persist_b1_dense(a, w.wh.dense, bf16, m->waves_per_group, s));
+            } else {
+                const size_t state_bytes = (size_t)B * H * sizeof(float);
+                if (c0n)
+                    HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0n, state_bytes, hipMemcpyDeviceToDevice, s));
+                else
+                    HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
+                for (int step = 0; step < T; ++step) {
+                    const int t = d ? (T - 1 - step) : step;
+                    StepArgs a{};
+                    a.P = P[d];
+                    if (step == 0) {
+                        a.h_prev = h0n;
+                        a.h_prev_ld = H;
+                    } else {
+                        const int tp = d ? t + 1 : t - 1;
+                        a.h_prev = Yout + (size_t)tp * B * y_ld + (size_t)d * H;
+                        a.h_prev_ld = y_ld;
+                    }
+                    a.c = cbuf[d];
+                    a.y_t = Yout + (size_t)t * B * y_ld + (size_t)d * H;
+                    a.y_ld = y_ld;
+                    a.hT = hTn;
+                    a.cT = cTn;
+                    a.last = (step == T - 1);
+                    a.t = t;
+                    a.B = B;
+                    a.H = H;
+                    a.round_h_bf16 = bf16 ? 1 : 0;
+                    if (w.wh.compressed)
+                        HIP_TRY(m, launch_step_csr(a, w.wh.row_ptr, w.wh.col16, w.wh.val, s));
+                    else
+                        HIP_TRY(m, launch_step_dense(a, w.wh.dense, bf16, s));
+                }
+            }
+        }
+    }
+    return LSTM_OK;
+}
+
+int lstm_check(lstm_t* m)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_check: handle is NULL");
+    int flag = 0;
+    HIP_TRY(m, hipMemcpy(&flag, m->timeout_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (flag) {
+        HIP_TRY(m, hipMemset(m->timeout_flag, 0, sizeof(int)));
+        return fail(m, LSTM_ERR_TIMEOUT, "a bounded device-side wait expired; outputs of that forward are invalid");
+    }
+    return LSTM_OK;
+}
+
+int lstm_get_compressed(const lstm_t* m, int layer, int direction, int which, int64_t* nnz, int64_t* row_ptr,
+                        int32_t* col, float* val)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_get_compressed: handle is NULL");
+    if (layer < 0 || layer >= m->L || direction < 0 || direction >= m->Dn || (which != 0 && which != 1))
+        return fail(m, LSTM_ERR_SHAPE, "lstm_get_compressed: index outside the model");
+    const LayerDir& x = m->ld[(size_t)layer * m->Dn + direction];
+    const PackedMat& p = which ? x.wh : x.wx;
+    if (!x.set || !p.compressed) return fail(m, LSTM_ERR_STATE, "lstm_get_compressed: matrix not held in compressed form");
+    if (nnz) *nnz = p.nnz;
+    if (!row_ptr && !col && !val) return LSTM_OK;
+    if (!row_ptr || !col || !val) return fail(m, LSTM_ERR_ARG, "lstm_get_compressed: pass all of row_ptr, col, val or none");
+    // translate packed row order (4j+q) back to the ABI order (q*H + j)
+    const int H = m->H;
+    int64_t pos = 0;
+    for (int r = 0; r < 4 * H; ++r) {
+        const int rp = 4 * (r % H) + (r / H);
+        row_ptr[r] = pos;
+        for (int64_t e = p.h_row_ptr[rp]; e < p.h_row_ptr[rp + 1]; ++e, ++pos) {
+            col[pos] = p.h_col[e];
+            val[pos] = p.h_val[e];
+        }
+    }
+    row_ptr[4 * H] = pos;
+    return LSTM_OK;
+}
+
+int lstm_find_lhp(const int* dims, const double* lat, int n, double eps, uint8_t* is_lhp, double* redundancy_pct)
+{
+    if (n < 0 || (n > 0 && (!dims || !lat || !is_lhp)) || !(eps >= 0.0) || eps >= 1.0)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_find_lhp: bad arguments");
+    std::vector<int> order(n);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return dims[a] > dims[b]; });
+    // walk from the largest dimension down, carrying the best latency among strictly larger dimensions
+    double best_larger = INFINITY;
+    int count = 0;
+    size_t i = 0;
+    while (i < order.size()) {
+        size_t jn = i;
+        double group_best = INFINITY;
+        while (jn < order.size() && dims[order[jn]] == dims[order[i]]) {
+            const int idx = order[jn];
+            const bool lhp = std::isinf(best_larger) ? true : (lat[idx] < (1.0 - eps) * best_larger);
+            is_lhp[idx] = lhp ? 1 : 0;
+            count += lhp ? 1 : 0;
+            group_best = std::min(group_best, lat[idx]);
+            ++jn;
+        }
+        best_larger = std::min(best_larger, group_best);
+        i = jn;
+    }
+    if (redundancy_pct) *redundancy_pct = n ? (1.0 - (double)count / n) * 100.0 : 0.0;
+    return LSTM_OK;
+}
+
+// ---- latency sweep -----------------------------------------------------------------------------------------
+namespace {
+struct SplitMix {
+    uint64_t s;
+    uint64_t next() { uint64_t z = (s += 0x9E3779B97F4A7C15ull); z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+                      z = (z ^ (z >> 27)) * 0x94D049BB133111EBull; return z ^ (z >> 31); }
+    double uniform() { return (double)(next() >> 11) * (1.0 / 9007199254740992.0); }
+    double normal() { double u1 = uniform(), u2 = uniform(); if (u1 < 1e-300) u1 = 1e-300;
+                      return std::sqrt(-2.0 * std::log(u1)) * std::cos(6.283185307179586 * u2); }
+};
+double percentile(std::vector<double> v, double p)
+{
+    std::sort(v.begin(), v.end());
+    if (v.empty()) return 0.0;
+    const double pos = p * (v.size() - 1);
+    const size_t lo = (size_t)pos;
+    const size_t hi = std::min(lo + 1, v.size() - 1);
+    return v[lo] + (v[hi] - v[lo]) * (pos - lo);
+}
+}  // namespace
+
+int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t seed, int warmup, int iters,
+                       double* med_us, double* p10_us, double* p90_us, uint8_t* is_lhp, void* stream)
+{
+    if (nH < 0 || (nH > 0 && (!Hs || !med_us)) || T < 1 || B < 1 || warmup < 0 || iters < 1)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_latency_sweep: bad arguments");
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    HIP_TRY(nullptr, hipEventCreate(&e0));
+    HIP_TRY(nullptr, hipEventCreate(&e1));
+    int rc = LSTM_OK;
+    for (int idx = 0; idx < nH && rc == LSTM_OK; ++idx) {
+        const int H = Hs[idx];
+        lstm_t* m = nullptr;
+        rc = lstm_create(1, H, H, 0, dtype, &m);
+        if (rc != LSTM_OK) break;
+        SplitMix rng{seed + 0x1000ull * (uint64_t)idx};
+        std::vector<float> Wx((size_t)4 * H * H), Wh((size_t)4 * H * H), b((size_t)4 * H, 0.0f);
+        for (auto& v : Wx) v = (float)(0.2 * rng.uniform() - 0.1);
+        for (auto& v : Wh) v = (float)(0.2 * rng.uniform() - 0.1);
+        for (int j = 0; j < H; ++j) b[j] = 1.0f;
+        rc = lstm_set_weights(m, 0, 0, Wx.data(), nullptr, Wh.data(), nullptr, b.data(), LSTM_FMT_DENSE_MASKED);
+        void *dx = nullptr, *dy = nullptr, *dws = nullptr;
+        const size_t xelems = (size_t)T * B * H;
+        const size_t wsb = lstm_workspace_bytes(m, T, B);
+        hipError_t e = hipSuccess;
+        if (rc == LSTM_OK) {
+            std::vector<float> xf(xelems);
+            for (auto& v : xf) v = (float)rng.normal();
+            if (dtype == LSTM_BF16) {
+                std::vector<uint16_t> xb(xelems);
+                for (size_t i = 0; i < xelems; ++i) xb[i] = host_f32_to_bf16(xf[i]);
+                e = hipMalloc(&dx, xelems * 2);
+                if (e == hipSuccess) e = hipMemcpy(dx, xb.data(), xelems * 2, hipMemcpyHostToDevice);
+            } else {
+                e = hipMalloc(&dx, xelems * 4);
+                if (e == hipSuccess) e = hipMemcpy(dx, xf.data(), xelems * 4, hipMemcpyHostToDevice);
+            }
+            if (e == hipSuccess) e = hipMalloc(&dy, xelems * 4);
+            if (e == hipSuccess) e = hipMalloc(&dws, wsb);
+            if (e != hipSuccess) rc = fail_hip(nullptr, e, "lstm_latency_sweep: device buffers");
+        }
+        std::vector<double> times;
+        for (int it = 0; it < warmup + iters && rc == LSTM_OK; ++it) {
+            e = hipEventRecord(e0, s);
+            rc = lstm_forward(m, T, B, dx, nullptr, nullptr, (float*)dy, nullptr, nullptr, dws, wsb, s);
+            if (rc != LSTM_OK) { g_create_error = lstm_last_error(m); break; }
+            if (e == hipSuccess) e = hipEventRecord(e1, s);
+            if (e == hipSuccess) e = hipEventSynchronize(e1);
+            float ms = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+            if (e != hipSuccess) { rc = fail_hip(nullptr, e, "lstm_latency_sweep: timing"); break; }
+            if (it >= warmup) times.push_back((double)ms * 1000.0);
+        }
+        if (rc == LSTM_OK) {
+            rc = lstm_check(m);
+            if (rc != LSTM_OK) g_create_error = lstm_last_error(m);
+        }
+        if (rc == LSTM_OK) {
+            med_us[idx] = percentile(times, 0.5);
+            if (p10_us) p10_us[idx] = percentile(times, 0.1);
+            if (p90_us) p90_us[idx] = percentile(times, 0.9);
+        }
+        if (dx) (void)hipFree(dx);
+        if (dy) (void)hipFree(dy);
+        if (dws) (void)hipFree(dws);
+        lstm_destroy(m);
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc == LSTM_OK && is_lhp && nH > 0) rc = lstm_find_lhp(Hs, med_us, nH, 0.0, is_lhp, nullptr);
+    return rc;
+}
+
+int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double* avg_us, void* stream)
+{
+    if (!dst || !src || !avg_us || iters < 1 || bytes == 0 || (bytes & 15))
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_copy: bad arguments (bytes must be a multiple of 16)");
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    HIP_TRY(nullptr, hipEventCreate(&e0));
+    HIP_TRY(nullptr, hipEventCreate(&e1));
+    HIP_TRY(nullptr, launch_copy(dst, src, bytes, s));
+    HIP_TRY(nullptr, hipEventRecord(e0, s));
+    for (int i = 0; i < iters; ++i) HIP_TRY(nullptr, launch_copy(dst, src, bytes, s));
+    HIP_TRY(nullptr, hipEventRecord(e1, s));
+    HIP_TRY(nullptr, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(nullptr, hipEventElapsedTime(&ms, e0, e1));
+    *avg_us = (double)ms * 1000.0 / iters;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return LSTM_OK;
+}
+
+int lstm_bench_exchange(int hidden, int waves, int steps, int iters, double* avg_us_per_step, void* stream)
+{
+    if (hidden < 1 || hidden > 8192 || waves < 0 || waves > 16 || steps < 2 || iters < 1 || !avg_us_per_step)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_exchange: bad arguments");
+    hipStream_t s = (hipStream_t)stream;
+    unsigned long long* xchg = nullptr;
+    int* flag = nullptr;
+    HIP_TRY(nullptr, hipMalloc((void**)&xchg, (size_t)2 * hidden * 8));
+    HIP_TRY(nullptr, hipMemset(xchg, 0, (size_t)2 * hidden * 8));
+    HIP_TRY(nullptr, hipMalloc((void**)&flag, 4));
+    HIP_TRY(nullptr, hipMemset(flag, 0, 4));
+    hipEvent_t e0, e1;
+    HIP_TRY(nullptr, hipEventCreate(&e0));
+    HIP_TRY(nullptr, hipEventCreate(&e1));
+    unsigned tag = 0;
+    int rc = LSTM_OK;
+    hipError_t e = launch_exchange_only(xchg, tag, hidden, waves, steps, flag, 1u << 22, s);
+    tag += (unsigned)steps;
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int i = 0; i < iters && e == hipSuccess; ++i) {
+        e = launch_exchange_only(xchg, tag, hidden, waves, steps, flag, 1u << 22, s);
+        tag += (unsigned)steps;
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    int f = 0;
+    if (e == hipSuccess) e = hipMemcpy(&f, flag, 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) rc = fail_hip(nullptr, e, "lstm_bench_exchange");
+    else if (f) rc = fail(nullptr, LSTM_ERR_TIMEOUT, "lstm_bench_exchange: bounded wait expired");
+    else *avg_us_per_step = (double)ms * 1000.0 / iters / steps;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipFree(xchg);
+    (void)hipFree(flag);
+    return rc;
+}
+
+}  // extern "C"
