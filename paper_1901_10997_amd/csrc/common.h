@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -66,7 +67,18 @@ hipError_t launch_step_csr(const StepArgs& a, const int32_t* row_ptr, const uint
                            hipStream_t s);
 
 struct PersistB1Args {
-    const float* P;        // [T][4H]
+    // recurrent weights, dense packed rows [4H][H], fp32 or bf16 bits
+    const void* Wh;
+    int w_bf16;
+    // input side: either P (projection done by a separate kernel, bias included) or, fused,
+    // Wx [4H][D] + bias [4H] + the input sequence x [T][D]
+    const float* P;        // [T][4H] or nullptr
+    const void* Wx;        // nullptr = not fused
+    const float* bias;
+    const void* x;
+    int x_bf16;            // x holds bf16 bits
+    int round_x_bf16;      // x is fp32 but the operand is rounded to bf16 (bf16 model, layer > 0)
+    int D;
     const float* h0;       // [H] or nullptr
     const float* c0;       // [H] or nullptr
     float* y;              // h_t -> y[t*y_ld + j]
@@ -81,14 +93,40 @@ struct PersistB1Args {
     int* timeout_flag;         // set to 1 if a bounded wait expired
     unsigned spin_limit;
 };
-// Dense, weights resident in registers.  Wh: [4H][H] fp32 or bf16 in packed row order.
-hipError_t launch_persist_b1_dense(const PersistB1Args& a, const void* Wh, bool w_bf16, int waves_per_group,
-                                   hipStream_t s);
-// Row-compressed, (value, column) slices resident in registers.
-hipError_t launch_persist_b1_sparse(const PersistB1Args& a, const float* ell_val, const uint16_t* ell_col, int slots,
-                                    int waves_per_group, hipStream_t s);
+hipError_t launch_persist_b1_dense(const PersistB1Args& a, int waves_per_group, hipStream_t s);
 bool persist_b1_dense_supported(int H);
-bool persist_b1_sparse_supported(int H, int slots);
+bool persist_b1_dense_fusable(int H, int D);
+
+// Row-compressed batch-1 recurrence, one or two stacked layers per launch (unidirectional when two).
+struct SparseLayerArgs {
+    const float* ell_val_x;     // [4H][slots_x][64]
+    const uint16_t* ell_col_x;
+    const float* ell_val_h;     // [4H][slots_h][64]
+    const uint16_t* ell_col_h;
+    int slots_x, slots_h;
+    const float* bias;          // [4H] packed order
+    const float* h0;            // [H] or nullptr
+    const float* c0;
+    float* y;                   // h_t -> y[t*y_ld + j]; nullptr = hidden sequence of this layer not wanted
+    int y_ld;
+    float* hT;
+    float* cT;
+};
+struct SparseStackArgs {
+    SparseLayerArgs layer[2];
+    const void* x;              // input sequence of the first layer, [T][D0]
+    int x_bf16, round_x_bf16;
+    int D0;
+    int T, H;
+    int reverse;                // only with one layer
+    int round_h_bf16;
+    unsigned long long* xchg;   // [layers][2][H]
+    unsigned tag_base;
+    int* timeout_flag;
+    unsigned spin_limit;
+};
+hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int layers, int waves_per_group, hipStream_t s);
+bool persist_b1_sparse_supported(int H, int D0, int slots_x, int slots_h, int layers);
 
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);

@@ -5,10 +5,18 @@
 
 namespace l355 {
 
-__device__ __forceinline__ float sigmoidf_fast(float z) { return 1.0f / (1.0f + __expf(-z)); }
-
+// Gate nonlinearities from the hardware exp2 and reciprocal (each accurate to about 1 ulp, which keeps the
+// absolute error of sigmoid and tanh near 1e-7).
+// sigmoid(z) = 1 / (1 + 2^(-z log2 e))
+__device__ __forceinline__ float sigmoidf_fast(float z)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
+}
 // tanh(z) = 1 - 2 / (1 + e^{2z}); saturates cleanly to +-1 when e^{2z} overflows or underflows.
-__device__ __forceinline__ float tanhf_fast(float z) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * z)); }
+__device__ __forceinline__ float tanhf_fast(float z)
+{
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.8853900817779268f * z));
+}
 
 // nearest-even rounding of an fp32 value to bf16 precision, result kept in fp32 (finite inputs)
 __device__ __forceinline__ float round_bf16(float f)
@@ -32,30 +40,34 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Sum four per-lane values over the wavefront with 7 exchanges instead of 24: lanes first split the four
-// values between the two halves (and then the quarters) of the wave, then finish with a 16-lane butterfly.
-// On return every lane of quarter q = lane/16 holds the total of value q; r[0..3] receive all four totals
-// (wave-uniform) through lane reads.
+// Sum four per-lane values over the wavefront; r[0..3] receive the four totals (wave-uniform).
+// The four values are first distributed over the four 16-lane rows with the gfx950 lane-swap instructions
+// (upper/lower 32 lanes, then odd/even rows), each swap halving the number of lanes a value occupies while
+// adding the halves; one register then holds value q in row q, a 16-lane DPP butterfly finishes it, and
+// four lane reads fetch the totals.  About a dozen vector instructions, no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
 __device__ __forceinline__ void wave_sum4(float a0, float a1, float a2, float a3, float r[4])
 {
-    const int lane = __lane_id();
-    const bool hi32 = (lane & 32) != 0;
-    // halves: lower keeps (a0,a1), upper keeps (a2,a3)
-    float keep0 = hi32 ? a2 : a0, keep1 = hi32 ? a3 : a1;
-    float send0 = hi32 ? a0 : a2, send1 = hi32 ? a1 : a3;
-    keep0 += __shfl_xor(send0, 32, 64);
-    keep1 += __shfl_xor(send1, 32, 64);
-    // quarters: within a half, lanes with bit 4 clear keep the first value
-    const bool hi16 = (lane & 16) != 0;
-    float keep = hi16 ? keep1 : keep0;
-    float send = hi16 ? keep0 : keep1;
-    keep += __shfl_xor(send, 16, 64);
-#pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) keep += __shfl_xor(keep, off, 64);
-    r[0] = __shfl(keep, 0, 64);
-    r[1] = __shfl(keep, 16, 64);
-    r[2] = __shfl(keep, 32, 64);
-    r[3] = __shfl(keep, 48, 64);
+    // lanes 32..63 of the first operand swap with lanes 0..31 of the second
+    const auto s02 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a0), __float_as_uint(a2), false, false);
+    const auto s13 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a1), __float_as_uint(a3), false, false);
+    const float k02 = __uint_as_float(s02[0]) + __uint_as_float(s02[1]);  // rows 0,1: a0   rows 2,3: a2
+    const float k13 = __uint_as_float(s13[0]) + __uint_as_float(s13[1]);  // rows 0,1: a1   rows 2,3: a3
+    // odd rows of the first operand swap with even rows of the second
+    const auto sr = __builtin_amdgcn_permlane16_swap(__float_as_uint(k02), __float_as_uint(k13), false, false);
+    float v = __uint_as_float(sr[0]) + __uint_as_float(sr[1]);            // row q: value q
+    v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);  // row_half_mirror
+    v = dpp_add<0x140>(v);  // row_mirror
+    r[0] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    r[1] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    r[2] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    r[3] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
 }
 
 }  // namespace l355

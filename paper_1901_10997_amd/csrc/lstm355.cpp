@@ -20,7 +20,7 @@ struct lstm355 {
     int device = 0;
     std::vector<LayerDir> ld;  // index l*Dn + d
     mutable std::string err;
-    unsigned long long* xchg = nullptr;  // [Dn][2][H] tagged exchange slots of the persistent batch-1 kernels
+    unsigned long long* xchg = nullptr;  // [2][2][H] tagged exchange slots of the persistent batch-1 kernels
     unsigned tag_base = 0;               // tags <= tag_base have been used
     int* timeout_flag = nullptr;         // device int
     unsigned spin_limit = 1u << 22;
@@ -218,7 +218,7 @@ int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, in
         if (v > 0) m->spin_limit = (unsigned)v;
     }
     hipError_t e = hipGetDevice(&m->device);
-    const size_t slots = (size_t)m->Dn * 2 * m->H;
+    const size_t slots = (size_t)4 * m->H;  // two cells (directions, or two stacked layers) x two parities
     if (e == hipSuccess) e = hipMalloc((void**)&m->xchg, slots * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(m->xchg, 0, slots * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMalloc((void**)&m->timeout_flag, sizeof(int));
@@ -404,15 +404,75 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
     float* cbuf[2] = {(float*)(base + ws.c_off[0]), (float*)(base + ws.c_off[1])};
     m->last_plan.clear();
 
+    auto take_tags = [&](int T_) -> int {
+        if (m->tag_base > 0xFFFFFFFFu - (unsigned)T_ - 2u) {
+            // tag space exhausted: restart from a clean slate
+            hipError_t e = launch_fill_u64(m->xchg, (size_t)4 * H, 0ull, s);
+            if (e != hipSuccess) return fail_hip(m, e, "launch_fill_u64");
+            m->tag_base = 0;
+        }
+        return LSTM_OK;
+    };
+    auto sparse_ok = [&](const LayerDir& w, int D_in, int nl) {
+        return w.wx.compressed && w.wh.compressed && w.wx.ell_val && w.wh.ell_val &&
+               persist_b1_sparse_supported(H, D_in, w.wx.slots, w.wh.slots, nl);
+    };
+    auto fill_sparse_layer = [&](SparseLayerArgs& a, const LayerDir& w, size_t n, float* yout, int y_ld) {
+        a.ell_val_x = w.wx.ell_val; a.ell_col_x = w.wx.ell_col; a.slots_x = w.wx.slots;
+        a.ell_val_h = w.wh.ell_val; a.ell_col_h = w.wh.ell_col; a.slots_h = w.wh.slots;
+        a.bias = w.bias;
+        a.h0 = h0 ? h0 + n * H : nullptr;   // B == 1 on this path
+        a.c0 = c0 ? c0 + n * H : nullptr;
+        a.y = yout; a.y_ld = y_ld;
+        a.hT = hT ? hT + n * H : nullptr;
+        a.cT = cT ? cT + n * H : nullptr;
+    };
+
     for (int l = 0; l < L; ++l) {
         const int D = m->in_dim(l);
         const void* X = (l == 0) ? x : (const void*)Ybuf[(l - 1) & 1];
         const bool x_is_bf16 = (l == 0) && bf16;
         float* Yout = (l == L - 1) ? y : Ybuf[l & 1];
         const int y_ld = Dn * H;
-        // ---- input projection for every timestep, both directions
+        const bool try_persist = (B == 1 && m->plan != LSTM_PLAN_STEPWISE);
+        char tag[128];
+
+        // ---- batch 1, row-compressed, two stacked unidirectional layers in one launch (diagonal wavefront)
+        if (try_persist && Dn == 1 && l + 1 < L && sparse_ok(m->ld[l], D, 2) && sparse_ok(m->ld[l + 1], D, 2)) {
+            ProfSpan span(m, s, 1);
+            int rc = take_tags(T);
+            if (rc != LSTM_OK) return rc;
+            SparseStackArgs a{};
+            float* Yout2 = (l + 1 == L - 1) ? y : Ybuf[(l + 1) & 1];
+            fill_sparse_layer(a.layer[0], m->ld[l], (size_t)l, nullptr, H);
+            fill_sparse_layer(a.layer[1], m->ld[l + 1], (size_t)l + 1, Yout2, H);
+            a.x = X; a.x_bf16 = x_is_bf16; a.round_x_bf16 = (bf16 && !x_is_bf16); a.D0 = D;
+            a.T = T; a.H = H; a.reverse = 0; a.round_h_bf16 = bf16;
+            a.xchg = m->xchg; a.tag_base = m->tag_base; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+            m->tag_base += (unsigned)T;
+            HIP_TRY(m, launch_persist_b1_sparse(a, 2, m->waves_per_group, s));
+            std::snprintf(tag, sizeof tag, "l%d+l%d.d0:proj=fused-csr,rec=persist_b1-csr-wavefront;", l, l + 1);
+            m->last_plan += tag;
+            ++l;
+            continue;
+        }
+
+        // ---- decide per direction
+        int mode[2] = {0, 0};  // 0 stepwise, 1 persistent sparse (fused), 2 persistent dense fused, 3 persistent dense + projection kernel
+        for (int d = 0; d < Dn; ++d) {
+            const LayerDir& w = m->ld[(size_t)l * Dn + d];
+            if (try_persist) {
+                if (w.wh.compressed) mode[d] = sparse_ok(w, D, 1) ? 1 : 0;
+                else if (persist_b1_dense_fusable(H, D)) mode[d] = 2;
+                else if (persist_b1_dense_supported(H)) mode[d] = 3;
+            }
+            if (m->plan == LSTM_PLAN_PERSISTENT && mode[d] == 0)
+                return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
+        }
+        // ---- input projection for every timestep (only the modes that need P)
         bool xt_ready = false;
         for (int d = 0; d < Dn; ++d) {
+            if (mode[d] == 1 || mode[d] == 2) continue;
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             ProfSpan span(m, s, 0);
             if (w.wx.compressed) {
@@ -433,45 +493,41 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             const float* c0n = c0 ? c0 + n * B * H : nullptr;
             float* hTn = hT ? hT + n * B * H : nullptr;
             float* cTn = cT ? cT + n * B * H : nullptr;
-            bool persistent = false;
-            if (B == 1 && m->plan != LSTM_PLAN_STEPWISE) {
-                persistent = w.wh.compressed ? (w.wh.ell_val && persist_b1_sparse_supported(H, w.wh.slots) && H <= 8192)
-                                             : persist_b1_dense_supported(H);
-            }
-            if (m->plan == LSTM_PLAN_PERSISTENT && !persistent)
-                return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
-            char tag[96];
-            std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=%s-%s;", l, d, w.wx.compressed ? "csr" : "dense",
-                          persistent ? "persist_b1" : "stepwise", w.wh.compressed ? "csr" : "dense");
+            static const char* const names[4] = {"stepwise", "persist_b1", "persist_b1", "persist_b1"};
+            std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s%s,rec=%s-%s;", l, d, (mode[d] == 1 || mode[d] == 2) ? "fused-" : "",
+                          w.wx.compressed ? "csr" : "dense", names[mode[d]], w.wh.compressed ? "csr" : "dense");
             m->last_plan += tag;
             ProfSpan span(m, s, 1);
-            if (persistent) {
-                if (m->tag_base > 0xFFFFFFFFu - (unsigned)T - 2u) {
-                    // tag space exhausted: restart from a clean slate
-                    HIP_TRY(m, launch_fill_u64(m->xchg, (size_t)Dn * 2 * H, 0ull, s));
-                    m->tag_base = 0;
-                }
-                PersistB1Args a{};
-                a.P = P[d];
-                a.h0 = h0n;
-                a.c0 = c0n;
-                a.y = Yout + (size_t)d * H;
-                a.y_ld = y_ld;
-                a.hT = hTn;
-                a.cT = cTn;
-                a.T = T;
-                a.H = H;
-                a.reverse = d;
-                a.round_h_bf16 = bf16 ? 1 : 0;
-                a.xchg = m->xchg + (size_t)d * 2 * H;
-                a.tag_base = m->tag_base;
-                a.timeout_flag = m->timeout_flag;
-                a.spin_limit = m->spin_limit;
+            if (mode[d] == 1) {
+                int rc = take_tags(T);
+                if (rc != LSTM_OK) return rc;
+                SparseStackArgs a{};
+                fill_sparse_layer(a.layer[0], w, n, Yout + (size_t)d * H, y_ld);
+                a.x = X; a.x_bf16 = x_is_bf16; a.round_x_bf16 = (bf16 && !x_is_bf16); a.D0 = D;
+                a.T = T; a.H = H; a.reverse = d; a.round_h_bf16 = bf16;
+                a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = m->tag_base;
+                a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 m->tag_base += (unsigned)T;
-                if (w.wh.compressed)
-                    HIP_TRY(m, launch_persist_b1_sparse(a, w.wh.ell_val, w.wh.ell_col, w.wh.slots, m->waves_per_group, s));
-                else
-                    HIP_TRY(m, launch_persist_b1_dense(a, w.wh.dense, bf16, m->waves_per_group, s));
+                HIP_TRY(m, launch_persist_b1_sparse(a, 1, m->waves_per_group, s));
+            } else if (mode[d] == 2 || mode[d] == 3) {
+                int rc = take_tags(T);
+                if (rc != LSTM_OK) return rc;
+                PersistB1Args a{};
+                a.Wh = w.wh.dense; a.w_bf16 = bf16;
+                if (mode[d] == 2) {
+                    a.Wx = w.wx.dense; a.bias = w.bias; a.x = X; a.x_bf16 = x_is_bf16;
+                    a.round_x_bf16 = (bf16 && !x_is_bf16); a.D = D;
+                } else {
+                    a.P = P[d];
+                }
+                a.h0 = h0n; a.c0 = c0n;
+                a.y = Yout + (size_t)d * H; a.y_ld = y_ld;
+                a.hT = hTn; a.cT = cTn;
+                a.T = T; a.H = H; a.reverse = d; a.round_h_bf16 = bf16;
+                a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = m->tag_base;
+                a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                m->tag_base += (unsigned)T;
+                HIP_TRY(m, launch_persist_b1_dense(a, m->waves_per_group, s));
             } else {
                 const size_t state_bytes = (size_t)B * H * sizeof(float);
                 if (c0n)

@@ -1,19 +1,27 @@
-// Batch-1 recurrence with the time loop on the device (one launch per layer and direction).
+// Batch-1 recurrence with the time loop on the device.
 //
-// Per timestep (paper Section 4, cell equations): a = P[t] + W_h.h_{t-1}; f,i,o = sigmoid, g = tanh;
+// Per timestep (paper Section 4, cell equations): a = b + W_x.x_t + W_h.h_{t-1}; f,i,o = sigmoid, g = tanh;
 // c_t = f*c_{t-1} + i*g; h_t = o*tanh(c_t).
 //
-// Design: every wavefront owns one hidden unit j (packed rows 4j..4j+3) and keeps that slice of W_h in
-// registers for the whole sequence, so after the first step no weight is read from memory again.
-// The only cross-workgroup traffic is h_t itself.  It is exchanged through a small library-owned buffer of
-// 64-bit slots (low word: h value, high word: a step tag).  A slot is written with ONE 8-byte store, so the
-// tag and the value arrive together; consumers poll the slots they need until the tag equals the step
-// they are waiting for.  There is no separate grid barrier: data arrival is the synchronisation.
-// Two slot arrays alternate by step parity; a producer can only overwrite array p two steps later, after it
-// has consumed every value of the step in between, which every other wave had to finish reading array p to
-// produce -- so no slot is overwritten while still needed.
+// Design: every wavefront owns one hidden unit j of one layer (packed rows 4j..4j+3) and keeps its slices of
+// the weight matrices in registers for the whole sequence, so after the prologue no weight is read from
+// memory again.  The only cross-workgroup traffic is h_t itself.  It is exchanged through a small
+// library-owned buffer of 64-bit slots (low word: h value, high word: a step tag).  A slot is written with ONE
+// 8-byte store, so tag and value arrive together; consumers poll the slots until the tag equals the step they
+// wait for.  There is no separate grid barrier: data arrival is the synchronisation, which costs one memory
+// round trip per step instead of two.  A workgroup collects the h values of its units in LDS and publishes
+// them with one coalesced store.
+// Two slot arrays per layer alternate by time parity.  h_t overwrites h_{t-2}; whoever publishes h_t has
+// received every value of h_{t-1}, and each of those was published only after its workgroup had finished
+// reading h_{t-2} -- so no slot is overwritten while still needed.
 // Tags grow monotonically over the life of the handle (the host advances tag_base by T per launch), so
-// leftovers from earlier launches never match.
+// leftovers of earlier launches never match.
+//
+// Where the input-side product W_x.x_t fits in registers too it is computed inside the same kernel, before
+// the wait for h_{t-1} (x_t does not depend on the recurrence), which removes the separate projection launch.
+// The row-compressed kernel can host two stacked layers in one launch: the waves of layer 1 consume h of
+// layer 0 one step behind it (a diagonal wavefront over layers and time), which halves the number of
+// sequential exchanges of a 2-layer stack.
 //
 // All waits are bounded: on expiry a device flag is raised, every wave stops waiting and the kernel drains.
 #include "common.h"
@@ -21,18 +29,29 @@
 
 namespace l355 {
 
-__device__ __forceinline__ unsigned long long pack_slot(float v, unsigned tag)
+typedef unsigned long long u64;
+
+__device__ __forceinline__ u64 pack_slot(float v, unsigned tag)
 {
-    return ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(v);
+    return ((u64)tag << 32) | (u64)__float_as_uint(v);
 }
 
-// Fetch h (tagged `want`) for elements tid, tid+nthreads, ... < H into dst[].  Up to four slots are polled
-// together so their memory latencies overlap.
-__device__ __forceinline__ void gather_tagged(const unsigned long long* slots, int H, unsigned want, float* dst,
-                                              int tid, int nthreads, int* timeout_flag, unsigned spin_limit)
+// One polled slot array: n slots tagged `want` go to dst[0..n).  n = 0 switches the array off.
+struct PollSrc {
+    const u64* slots;
+    float* dst;
+    unsigned want;
+    int n;
+};
+
+// Fetch the tagged values of up to two slot arrays into LDS.  The two arrays are treated as one index space
+// so that all outstanding loads of a thread (up to four) are in flight together, whichever array they hit.
+__device__ __forceinline__ void gather_tagged2(const PollSrc& A, const PollSrc& Bs, int tid, int nthreads,
+                                               int* timeout_flag, unsigned spin_limit)
 {
-    for (int e0 = tid; e0 < H; e0 += 4 * nthreads) {
-        unsigned long long v[4];
+    const int total = A.n + Bs.n;
+    for (int e0 = tid; e0 < total; e0 += 4 * nthreads) {
+        u64 v[4];
         unsigned spins = 0;
         bool ok;
         do {
@@ -40,11 +59,12 @@ __device__ __forceinline__ void gather_tagged(const unsigned long long* slots, i
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int e = e0 + u * nthreads;
-                v[u] = (e < H) ? __hip_atomic_load(slots + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                               : ((unsigned long long)want << 32);
+                const bool second = e >= A.n;
+                const u64* p = second ? (Bs.slots + (e - A.n)) : (A.slots + e);
+                const unsigned want = second ? Bs.want : A.want;
+                v[u] = (e < total) ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ((u64)want << 32);
+                ok = ok && ((unsigned)(v[u] >> 32) == want);
             }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) ok = ok && ((unsigned)(v[u] >> 32) == want);
             if (!ok) {
                 ++spins;
                 if (spins > spin_limit) {
@@ -59,60 +79,57 @@ __device__ __forceinline__ void gather_tagged(const unsigned long long* slots, i
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int e = e0 + u * nthreads;
-            if (e < H) dst[e] = __uint_as_float((unsigned)v[u]);
+            if (e < total) {
+                if (e >= A.n) Bs.dst[e - A.n] = __uint_as_float((unsigned)v[u]);
+                else A.dst[e] = __uint_as_float((unsigned)v[u]);
+            }
         }
     }
 }
 
-// Shared tail of a step: nonlinearities, state update, outputs, publication of h_t.
-__device__ __forceinline__ void finish_step(const PersistB1Args& a, int j, int t, int s, bool active, int lane,
-                                            const float r[4], const float4& p, float& c)
+__device__ __forceinline__ void gather_tagged(const u64* slots, int H, unsigned want, float* dst, int tid,
+                                              int nthreads, int* timeout_flag, unsigned spin_limit)
 {
-    const float f = sigmoidf_fast(r[0] + p.x);
-    const float i = sigmoidf_fast(r[1] + p.y);
-    const float o = sigmoidf_fast(r[2] + p.z);
-    const float g = tanhf_fast(r[3] + p.w);
-    c = f * c + i * g;
-    const float h = o * tanhf_fast(c);
-    if (active && lane == 0) {
-        a.y[(size_t)t * a.y_ld + j] = h;
-        if (s + 1 < a.T) {
-            const float hx = a.round_h_bf16 ? round_bf16(h) : h;
-            __hip_atomic_store(a.xchg + (size_t)((s + 1) & 1) * a.H + j, pack_slot(hx, a.tag_base + (unsigned)s + 1u),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            if (a.hT) a.hT[j] = h;
-            if (a.cT) a.cT[j] = c;
-        }
+    const PollSrc A{slots, dst, want, H}, none{nullptr, nullptr, 0u, 0};
+    gather_tagged2(A, none, tid, nthreads, timeout_flag, spin_limit);
+}
+
+__device__ __forceinline__ float uniform_f32(float v)
+{
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+}
+
+__device__ __forceinline__ void stage_initial(const float* h0, int H, float* dst, int tid, int nthreads, int round_bf)
+{
+    for (int e = tid; e < H; e += nthreads) {
+        float v = h0 ? h0[e] : 0.f;
+        if (round_bf) v = round_bf16(v);
+        dst[e] = v;
     }
 }
 
-// Stage h_{s-1} into LDS buffer `dst` (step 0: from h0 / zeros; later: from the tagged slots).
-__device__ __forceinline__ void stage_h(const PersistB1Args& a, int s, float* dst, int tid, int nthreads)
+__device__ __forceinline__ float load_x(const void* x, int x_bf16, size_t idx)
 {
-    if (s == 0) {
-        for (int e = tid; e < a.H; e += nthreads) {
-            float v = a.h0 ? a.h0[e] : 0.f;
-            if (a.round_h_bf16) v = round_bf16(v);
-            dst[e] = v;
-        }
-    } else {
-        gather_tagged(a.xchg + (size_t)(s & 1) * a.H, a.H, a.tag_base + (unsigned)s, dst, tid, nthreads,
-                      a.timeout_flag, a.spin_limit);
-    }
+    return x_bf16 ? bf16_bits_to_f32(((const uint16_t*)x)[idx]) : ((const float*)x)[idx];
 }
 
-template <int KI, int MAXT>
-__global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a, const void* __restrict__ Wh, int w_bf16)
+// ------------------------------------------------------------------------------------------------------------
+// Dense: W_h (and, when FUSEX, W_x) slices in registers.  One cell (layer, direction) per launch.
+// ------------------------------------------------------------------------------------------------------------
+template <int KI, bool FUSEX, int MAXT>
+__global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
 {
-    extern __shared__ float hs[];  // [2][KI*64]
+    extern __shared__ float lds[];  // hbuf[KI*64] | pub[waves]
     constexpr int HP = KI * 64;
+    float* hbuf = lds;
+    float* pub = lds + HP;
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int j = blockIdx.x * (nthreads >> 6) + wave;
+    const int lane = tid & 63, wave = tid >> 6, upb = nthreads >> 6;
+    const int j = blockIdx.x * upb + wave;
     const bool active = j < a.H;
 
-    float w[4][KI];
+    float wh[4][KI];
+    float wx[FUSEX ? 4 : 1][FUSEX ? KI : 1];
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -121,101 +138,278 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a,
             float v = 0.f;
             if (active && k < a.H) {
                 const size_t idx = (size_t)(4 * j + q) * a.H + k;
-                v = w_bf16 ? bf16_bits_to_f32(((const uint16_t*)Wh)[idx]) : ((const float*)Wh)[idx];
+                v = a.w_bf16 ? bf16_bits_to_f32(((const uint16_t*)a.Wh)[idx]) : ((const float*)a.Wh)[idx];
             }
-            w[q][i] = v;
+            wh[q][i] = v;
+            if (FUSEX) {
+                float u = 0.f;
+                if (active && k < a.D) {
+                    const size_t idx = (size_t)(4 * j + q) * a.D + k;
+                    u = a.w_bf16 ? bf16_bits_to_f32(((const uint16_t*)a.Wx)[idx]) : ((const float*)a.Wx)[idx];
+                }
+                wx[q][i] = u;
+            }
         }
-    for (int e = tid; e < 2 * HP; e += nthreads) hs[e] = 0.f;  // padding beyond H must be finite
+    float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (FUSEX && active) bias4 = *reinterpret_cast<const float4*>(a.bias + 4 * j);
+    for (int e = tid; e < HP; e += nthreads) hbuf[e] = 0.f;  // padding beyond H must stay finite
     float c = (active && a.c0) ? a.c0[j] : 0.f;
     __syncthreads();
 
     for (int s = 0; s < a.T; ++s) {
         const int t = a.reverse ? (a.T - 1 - s) : s;
-        float* hb = hs + (s & 1) * HP;
-        float4 p = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (active) p = *reinterpret_cast<const float4*>(a.P + (size_t)t * 4 * a.H + 4 * j);
-        stage_h(a, s, hb, tid, nthreads);
-        __syncthreads();
         float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+        float4 p = bias4;
+        // operands that do not depend on the recurrence are requested before the wait for h_{t-1} and
+        // consumed after it, so their memory latency overlaps the wait
+        float xv[FUSEX ? KI : 1];
+        if (FUSEX) {
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const int k = lane + 64 * i;
+                xv[i] = (k < a.D) ? load_x(a.x, a.x_bf16, (size_t)t * a.D + k) : 0.f;
+            }
+        } else {
+            if (active) p = *reinterpret_cast<const float4*>(a.P + (size_t)t * 4 * a.H + 4 * j);
+        }
+        if (s == 0)
+            stage_initial(a.h0, a.H, hbuf, tid, nthreads, a.round_h_bf16);
+        else
+            gather_tagged(a.xchg + (size_t)(s & 1) * a.H, a.H, a.tag_base + (unsigned)s, hbuf, tid, nthreads,
+                          a.timeout_flag, a.spin_limit);
+        __syncthreads();
+        if (FUSEX) {
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const float v = a.round_x_bf16 ? round_bf16(xv[i]) : xv[i];
+                acc0 = fmaf(wx[0][i], v, acc0);
+                acc1 = fmaf(wx[1][i], v, acc1);
+                acc2 = fmaf(wx[2][i], v, acc2);
+                acc3 = fmaf(wx[3][i], v, acc3);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < KI; ++i) {
-            const float hv = hb[lane + 64 * i];
-            acc0 = fmaf(w[0][i], hv, acc0);
-            acc1 = fmaf(w[1][i], hv, acc1);
-            acc2 = fmaf(w[2][i], hv, acc2);
-            acc3 = fmaf(w[3][i], hv, acc3);
+            const float hv = hbuf[lane + 64 * i];
+            acc0 = fmaf(wh[0][i], hv, acc0);
+            acc1 = fmaf(wh[1][i], hv, acc1);
+            acc2 = fmaf(wh[2][i], hv, acc2);
+            acc3 = fmaf(wh[3][i], hv, acc3);
         }
         float r[4];
         wave_sum4(acc0, acc1, acc2, acc3, r);
-        finish_step(a, j, t, s, active, lane, r, p, c);
+        const float f = sigmoidf_fast(r[0] + p.x);
+        const float ig = sigmoidf_fast(r[1] + p.y);
+        const float o = sigmoidf_fast(r[2] + p.z);
+        const float g = tanhf_fast(r[3] + p.w);
+        c = f * c + ig * g;
+        const float h = o * tanhf_fast(c);
+        if (lane == 0) {
+            pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
+            if (active) {
+                a.y[(size_t)t * a.y_ld + j] = h;
+                if (s + 1 == a.T) {
+                    if (a.hT) a.hT[j] = h;
+                    if (a.cT) a.cT[j] = c;
+                }
+            }
+        }
+        __syncthreads();
+        if (s + 1 < a.T && tid < upb) {
+            const int ju = blockIdx.x * upb + tid;
+            if (ju < a.H)
+                __hip_atomic_store(a.xchg + (size_t)((s + 1) & 1) * a.H + ju,
+                                   pack_slot(pub[tid], a.tag_base + (unsigned)s + 1u), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
-template <int NZ>
-__global__ __launch_bounds__(1024) void persist_b1_sparse_kernel(PersistB1Args a, const float* __restrict__ ell_val,
-                                                                 const uint16_t* __restrict__ ell_col)
+// ------------------------------------------------------------------------------------------------------------
+// Row-compressed: (value, column) slices of W_x and W_h in registers; NL stacked layers per launch.
+// Wave w of a workgroup serves layer w / upb, unit blockIdx*upb + w % upb.  Global step s advances layer l
+// at time index s - l.
+// ------------------------------------------------------------------------------------------------------------
+template <int NZ, int NL, int MAXT>
+__global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs a)
 {
-    extern __shared__ float hs[];  // [2][H]
+    extern __shared__ float lds[];  // hbuf[NL][H] | xbuf[D0] | pub[waves]
+    const int H = a.H;
+    float* xbuf = lds + (size_t)NL * H;
+    float* pub = xbuf + a.D0;
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int j = blockIdx.x * (nthreads >> 6) + wave;
-    const bool active = j < a.H;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int upb = nwaves / NL;
+    const int l = wave / upb;                       // layer served by this wave
+    const int j = blockIdx.x * upb + (wave % upb);  // hidden unit
+    const bool active = j < H;
+    const SparseLayerArgs& L = a.layer[l];
 
-    float wv[4][NZ];
-    int wc[4][NZ];
+    // values in fp32 registers; the 16-bit column indices two to a register (slot i in half i&1 of word i/2)
+    constexpr int NZP = (NZ + 1) / 2;
+    float vx[4][NZ], vh[4][NZ];
+    unsigned cxp[4][NZP], chp[4][NZP];
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int i = 0; i < NZP; ++i) cxp[q][i] = chp[q][i] = 0u;
 #pragma unroll
         for (int i = 0; i < NZ; ++i) {
-            float v = 0.f;
-            int k = 0;
+            float v = 0.f, u = 0.f;
+            unsigned kv = 0, ku = 0;
             if (active) {
-                const size_t idx = ((size_t)(4 * j + q) * NZ + i) * 64 + lane;
-                v = ell_val[idx];
-                k = ell_col[idx];
+                if (i < L.slots_x) {
+                    const size_t idx = ((size_t)(4 * j + q) * L.slots_x + i) * 64 + lane;
+                    u = L.ell_val_x[idx];
+                    ku = L.ell_col_x[idx];
+                }
+                if (i < L.slots_h) {
+                    const size_t idx = ((size_t)(4 * j + q) * L.slots_h + i) * 64 + lane;
+                    v = L.ell_val_h[idx];
+                    kv = L.ell_col_h[idx];
+                }
             }
-            wv[q][i] = v;
-            wc[q][i] = k;
+            vx[q][i] = u;
+            vh[q][i] = v;
+            cxp[q][i >> 1] |= ku << (16 * (i & 1));
+            chp[q][i >> 1] |= kv << (16 * (i & 1));
         }
-    float c = (active && a.c0) ? a.c0[j] : 0.f;
+    }
+#define COLX(q, i) ((cxp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
+#define COLH(q, i) ((chp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
+    float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (active) bias4 = *reinterpret_cast<const float4*>(L.bias + 4 * j);
+    // wave-uniform: keep the four biases in scalar registers
+    bias4.x = uniform_f32(bias4.x);
+    bias4.y = uniform_f32(bias4.y);
+    bias4.z = uniform_f32(bias4.z);
+    bias4.w = uniform_f32(bias4.w);
+    float c = (active && L.c0) ? L.c0[j] : 0.f;
+    const int total_steps = a.T + NL - 1;
 
-    for (int s = 0; s < a.T; ++s) {
-        const int t = a.reverse ? (a.T - 1 - s) : s;
-        float* hb = hs + (size_t)(s & 1) * a.H;
-        float4 p = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (active) p = *reinterpret_cast<const float4*>(a.P + (size_t)t * 4 * a.H + 4 * j);
-        stage_h(a, s, hb, tid, nthreads);
-        __syncthreads();
+    for (int s = 0; s < total_steps; ++s) {
+        const int ts = s - l;                        // time index this wave's layer works on
+        const bool live = ts >= 0 && ts < a.T;
+        const int t = a.reverse ? (a.T - 1 - ts) : ts;  // position in the sequence
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        // The input vector of the first layer (time index s) comes from the external sequence and does not
+        // depend on the recurrence: the whole workgroup requests it with coalesced loads before the wait for
+        // h, and parks it in LDS after the wait, where the first layer's waves gather from it.
+        constexpr int XPT = 4;  // x elements per thread and pass
+        const bool have_x = s < a.T;
+        const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s) : s) * a.D0;
+        float xr[XPT];
+        if (have_x) {
 #pragma unroll
-        for (int i = 0; i < NZ; ++i)
+            for (int u = 0; u < XPT; ++u) {
+                const int e = tid + u * nthreads;
+                xr[u] = (e < a.D0) ? load_x(a.x, a.x_bf16, xrow + e) : 0.f;
+            }
+        }
+        // stage, for every layer m, h^m at time index s-m-1 (the operand of layer m's recurrence at time s-m
+        // and of layer m+1's input side at time s-m-1)
+        PollSrc src[2] = {{nullptr, nullptr, 0u, 0}, {nullptr, nullptr, 0u, 0}};
 #pragma unroll
-            for (int q = 0; q < 4; ++q) acc[q] = fmaf(wv[q][i], hb[wc[q][i]], acc[q]);
-        float r[4];
-        wave_sum4(acc[0], acc[1], acc[2], acc[3], r);
-        finish_step(a, j, t, s, active, lane, r, p, c);
+        for (int m = 0; m < NL; ++m) {
+            const int tm = s - m - 1;
+            float* dst = lds + (size_t)m * H;
+            if (tm == -1)
+                stage_initial(a.layer[m].h0, H, dst, tid, nthreads, a.round_h_bf16);
+            else if (tm >= 0 && tm < a.T - 1 + (m + 1 < NL ? 1 : 0))
+                src[m] = PollSrc{a.xchg + ((size_t)m * 2 + ((tm + 1) & 1)) * H, dst, a.tag_base + (unsigned)tm + 1u, H};
+        }
+        gather_tagged2(src[0], src[1], tid, nthreads, a.timeout_flag, a.spin_limit);
+        if (have_x) {
+#pragma unroll
+            for (int u = 0; u < XPT; ++u) {
+                const int e = tid + u * nthreads;
+                if (e < a.D0) xbuf[e] = a.round_x_bf16 ? round_bf16(xr[u]) : xr[u];
+            }
+            for (int e = tid + XPT * nthreads; e < a.D0; e += nthreads) {   // wider inputs: the rest, directly
+                const float v = load_x(a.x, a.x_bf16, xrow + e);
+                xbuf[e] = a.round_x_bf16 ? round_bf16(v) : v;
+            }
+        }
+        __syncthreads();
+        if (l == 0 && live) {
+#pragma unroll
+            for (int i = 0; i < NZ; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] = fmaf(vx[q][i], xbuf[COLX(q, i)], acc[q]);
+        }
+        float h = 0.f;
+        if (live) {
+            const float* hrec = lds + (size_t)l * H;
+            if (l > 0) {
+                const float* hin = lds + (size_t)(l - 1) * H;
+#pragma unroll
+                for (int i = 0; i < NZ; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) acc[q] = fmaf(vx[q][i], hin[COLX(q, i)], acc[q]);
+            }
+#pragma unroll
+            for (int i = 0; i < NZ; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc[q] = fmaf(vh[q][i], hrec[COLH(q, i)], acc[q]);
+            float r[4];
+            wave_sum4(acc[0], acc[1], acc[2], acc[3], r);
+            const float f = sigmoidf_fast(r[0] + bias4.x);
+            const float ig = sigmoidf_fast(r[1] + bias4.y);
+            const float o = sigmoidf_fast(r[2] + bias4.z);
+            const float g = tanhf_fast(r[3] + bias4.w);
+            c = f * c + ig * g;
+            h = o * tanhf_fast(c);
+            if (lane == 0 && active) {
+                if (L.y) L.y[(size_t)t * L.y_ld + j] = h;
+                if (ts + 1 == a.T) {
+                    if (L.hT) L.hT[j] = h;
+                    if (L.cT) L.cT[j] = c;
+                }
+            }
+        }
+        if (lane == 0) pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
+        __syncthreads();
+        if (tid < nwaves) {
+            // thread `tid` publishes the value wave `tid` produced
+            const int lm = tid / upb, ju = blockIdx.x * upb + (tid % upb);
+            const int tsm = s - lm;
+            // the last time index of the last layer has no consumer
+            const bool wanted = tsm >= 0 && tsm < a.T && !(tsm == a.T - 1 && lm == NL - 1);
+            if (wanted && ju < H)
+                __hip_atomic_store(a.xchg + ((size_t)lm * 2 + ((tsm + 1) & 1)) * H + ju,
+                                   pack_slot(pub[tid], a.tag_base + (unsigned)tsm + 1u), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
+#undef COLX
+#undef COLH
+
 // Exchange with no arithmetic: the yardstick for the per-step cost of the persistent kernels.
-__global__ __launch_bounds__(1024) void exchange_only_kernel(unsigned long long* xchg, unsigned tag_base, int H,
-                                                             int steps, int* timeout_flag, unsigned spin_limit)
+__global__ __launch_bounds__(1024) void exchange_only_kernel(u64* xchg, unsigned tag_base, int H, int steps,
+                                                             int* timeout_flag, unsigned spin_limit)
 {
-    extern __shared__ float hs[];
+    extern __shared__ float lds[];  // hbuf[H] | pub[waves]
+    float* pub = lds + H;
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    const int lane = tid & 63;
-    const int j = blockIdx.x * (nthreads >> 6) + (tid >> 6);
+    const int lane = tid & 63, wave = tid >> 6, upb = nthreads >> 6;
+    const int j = blockIdx.x * upb + wave;
     float acc = 0.f;
     for (int s = 0; s < steps; ++s) {
-        float* hb = hs + (size_t)(s & 1) * H;
         if (s > 0)
-            gather_tagged(xchg + (size_t)(s & 1) * H, H, tag_base + (unsigned)s, hb, tid, nthreads, timeout_flag,
+            gather_tagged(xchg + (size_t)(s & 1) * H, H, tag_base + (unsigned)s, lds, tid, nthreads, timeout_flag,
                           spin_limit);
         __syncthreads();
-        if (s > 0) acc += hb[j < H ? j : 0];
-        if (j < H && lane == 0 && s + 1 < steps)
-            __hip_atomic_store(xchg + (size_t)((s + 1) & 1) * H + j, pack_slot(acc * 1e-30f, tag_base + (unsigned)s + 1u),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (s > 0) acc += lds[j < H ? j : 0];
+        if (lane == 0) pub[wave] = acc * 1e-30f;
+        __syncthreads();
+        if (s + 1 < steps && tid < upb) {
+            const int ju = blockIdx.x * upb + tid;
+            if (ju < H)
+                __hip_atomic_store(xchg + (size_t)((s + 1) & 1) * H + ju, pack_slot(pub[tid], tag_base + (unsigned)s + 1u),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -233,51 +427,64 @@ static int num_cu()
     return g_num_cu;
 }
 
-static int pick_waves(int H, int requested, int max_waves)
-{
-    int w = requested;
-    if (w <= 0) {
-        w = 4;
-        while (w < max_waves && (H + w - 1) / w > num_cu()) w *= 2;
-    }
-    if (w > max_waves) w = max_waves;
-    if (w < 1) w = 1;
-    return w;
-}
-
 template <typename K>
 static hipError_t coop_launch(K kernel, int blocks, int threads, size_t lds, void** args, hipStream_t s)
 {
-    int per_cu = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, lds);
-    if (e != hipSuccess) return e;
-    if ((long long)per_cu * num_cu() < blocks) return hipErrorCooperativeLaunchTooLarge;
+    if (blocks > num_cu() * 8) return hipErrorCooperativeLaunchTooLarge;
     return hipLaunchCooperativeKernel((const void*)kernel, dim3(blocks), dim3(threads), args, (unsigned)lds, s);
 }
 
-bool persist_b1_dense_supported(int H) { return H >= 1 && H <= 2048; }
-bool persist_b1_sparse_supported(int H, int slots) { return H >= 1 && H <= 16384 && slots >= 1 && slots <= 8; }
-
-template <int KI>
-static hipError_t launch_dense_ki(PersistB1Args a, const void* Wh, int w_bf16, int wpg_req, hipStream_t s)
+// waves per workgroup: the largest allowed that still leaves at most one workgroup per compute unit
+static int pick_waves(int H, int requested, int max_waves, int divisor)
 {
-    constexpr int MAXT = (KI <= 16) ? 1024 : 512;
-    const int wpg = pick_waves(a.H, wpg_req, MAXT / 64);
-    const int blocks = (a.H + wpg - 1) / wpg;
-    const size_t lds = 2 * (size_t)KI * 64 * sizeof(float);
-    void* args[] = {(void*)&a, (void*)&Wh, (void*)&w_bf16};
-    return coop_launch(persist_b1_dense_kernel<KI, MAXT>, blocks, wpg * 64, lds, args, s);
+    int w = requested > 0 ? requested : max_waves;
+    if (w > max_waves) w = max_waves;
+    w -= w % divisor;
+    if (w < divisor) w = divisor;
+    // never more workgroups than compute units: every workgroup must be resident for the exchange to progress
+    while (w + divisor <= max_waves && (H + w / divisor - 1) / (w / divisor) > num_cu()) w += divisor;
+    return w;
 }
 
-hipError_t launch_persist_b1_dense(const PersistB1Args& a, const void* Wh, bool w_bf16, int wpg, hipStream_t s)
+// threads per workgroup allowed by the register budget: the weight slices (and staged inputs) take (fused ? 9 : 4)*KI registers
+// per lane, the rest of the kernel about 60; a compute unit gives 512 registers per lane and SIMD.
+constexpr int dense_maxt(int KI, bool fusex)
+{
+    return ((fusex ? 9 : 4) * KI <= 64) ? 1024 : ((fusex ? 9 : 4) * KI <= 96) ? 768 : 512;
+}
+constexpr int kDenseFuseMaxKI = 17;
+constexpr int sparse_maxt(int NZ) { return NZ <= 1 ? 1024 : NZ <= 4 ? 768 : 512; }
+
+bool persist_b1_dense_supported(int H) { return H >= 1 && H <= 2048; }
+bool persist_b1_dense_fusable(int H, int D)
+{
+    const int KI = (H + 63) / 64;
+    return persist_b1_dense_supported(H) && D <= 64 * KI && KI <= kDenseFuseMaxKI;
+}
+
+template <int KI, bool FUSEX>
+static hipError_t launch_dense_ki(PersistB1Args a, int wpg_req, hipStream_t s)
+{
+    constexpr int MAXT = dense_maxt(KI, FUSEX);
+    const int wpg = pick_waves(a.H, wpg_req, MAXT / 64, 1);
+    const int blocks = (a.H + wpg - 1) / wpg;
+    const size_t lds = ((size_t)KI * 64 + wpg) * sizeof(float);
+    void* args[] = {(void*)&a};
+    return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT>, blocks, wpg * 64, lds, args, s);
+}
+
+hipError_t launch_persist_b1_dense(const PersistB1Args& a, int wpg, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
     if (!persist_b1_dense_supported(a.H)) return hipErrorInvalidValue;
     const int KI = (a.H + 63) / 64;
-    const int wb = w_bf16 ? 1 : 0;
+    const bool fuse = a.Wx != nullptr;
+    if (fuse && !persist_b1_dense_fusable(a.H, a.D)) return hipErrorInvalidValue;
     switch (KI) {
-#define CASE_KI(n) \
-    case n: return launch_dense_ki<n>(a, Wh, wb, wpg, s);
+#define CASE_KI(n)                                                     \
+    case n:                                                            \
+        if (n <= kDenseFuseMaxKI && fuse) return launch_dense_ki<(n <= kDenseFuseMaxKI ? n : 1), true>(a, wpg, s); \
+        return launch_dense_ki<n, false>(a, wpg, s);
         CASE_KI(1) CASE_KI(2) CASE_KI(3) CASE_KI(4) CASE_KI(5) CASE_KI(6) CASE_KI(7) CASE_KI(8)
         CASE_KI(9) CASE_KI(10) CASE_KI(11) CASE_KI(12) CASE_KI(13) CASE_KI(14) CASE_KI(15) CASE_KI(16)
         CASE_KI(17) CASE_KI(18) CASE_KI(19) CASE_KI(20) CASE_KI(21) CASE_KI(22) CASE_KI(23) CASE_KI(24)
@@ -287,42 +494,51 @@ hipError_t launch_persist_b1_dense(const PersistB1Args& a, const void* Wh, bool 
     return hipErrorInvalidValue;
 }
 
-template <int NZ>
-static hipError_t launch_sparse_nz(PersistB1Args a, const float* ev, const uint16_t* ec, int wpg_req, hipStream_t s)
+bool persist_b1_sparse_supported(int H, int D0, int slots_x, int slots_h, int nl)
 {
-    const int wpg = pick_waves(a.H, wpg_req, 16);
-    const int blocks = (a.H + wpg - 1) / wpg;
-    const size_t lds = 2 * (size_t)a.H * sizeof(float);
-    void* args[] = {(void*)&a, (void*)&ev, (void*)&ec};
-    return coop_launch(persist_b1_sparse_kernel<NZ>, blocks, wpg * 64, lds, args, s);
+    if (((size_t)nl * H + D0 + 16) * sizeof(float) > 64 * 1024) return false;
+    if (H < 1 || nl < 1 || nl > 2 || slots_x < 1 || slots_h < 1 || slots_x > 7 || slots_h > 7) return false;
+    const int nz = slots_x > slots_h ? slots_x : slots_h;
+    const int maxt = nz <= 1 ? 1024 : nz <= 4 ? 768 : 512;
+    const int upb = (maxt / 64) / nl;
+    return (H + upb - 1) / upb <= num_cu();
 }
 
-hipError_t launch_persist_b1_sparse(const PersistB1Args& a, const float* ell_val, const uint16_t* ell_col, int slots,
-                                    int wpg, hipStream_t s)
+template <int NZ, int NL>
+static hipError_t launch_sparse_nz(SparseStackArgs a, int wpg_req, hipStream_t s)
+{
+    constexpr int MAXT = sparse_maxt(NZ);
+    const int wpg = pick_waves(a.H, wpg_req, MAXT / 64, NL);
+    const int upb = wpg / NL;
+    const int blocks = (a.H + upb - 1) / upb;
+    const size_t lds = ((size_t)NL * a.H + a.D0 + wpg) * sizeof(float);
+    void* args[] = {(void*)&a};
+    return coop_launch(persist_b1_sparse_kernel<NZ, NL, MAXT>, blocks, wpg * 64, lds, args, s);
+}
+
+hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int nl, int wpg, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
-    if (!persist_b1_sparse_supported(a.H, slots)) return hipErrorInvalidValue;
-    if (2 * (size_t)a.H * sizeof(float) > 64 * 1024) return hipErrorInvalidValue;
-    switch (slots) {
-        case 1: return launch_sparse_nz<1>(a, ell_val, ell_col, wpg, s);
-        case 2: return launch_sparse_nz<2>(a, ell_val, ell_col, wpg, s);
-        case 3: return launch_sparse_nz<3>(a, ell_val, ell_col, wpg, s);
-        case 4: return launch_sparse_nz<4>(a, ell_val, ell_col, wpg, s);
-        case 5: return launch_sparse_nz<5>(a, ell_val, ell_col, wpg, s);
-        case 6: return launch_sparse_nz<6>(a, ell_val, ell_col, wpg, s);
-        case 7: return launch_sparse_nz<7>(a, ell_val, ell_col, wpg, s);
-        case 8: return launch_sparse_nz<8>(a, ell_val, ell_col, wpg, s);
+    int nz = 1;
+    for (int l = 0; l < nl; ++l) nz = std::max(nz, std::max(a.layer[l].slots_x, a.layer[l].slots_h));
+    if (!persist_b1_sparse_supported(a.H, a.D0, nz, nz, nl)) return hipErrorInvalidValue;
+#define CASE_NZ(n)                                               \
+    case n:                                                      \
+        return nl == 1 ? launch_sparse_nz<n, 1>(a, wpg, s) : launch_sparse_nz<n, 2>(a, wpg, s);
+    switch (nz) {
+        CASE_NZ(1) CASE_NZ(2) CASE_NZ(3) CASE_NZ(4) CASE_NZ(5) CASE_NZ(6) CASE_NZ(7)
     }
+#undef CASE_NZ
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_exchange_only(unsigned long long* xchg, unsigned tag_base, int H, int waves, int steps,
-                                int* timeout_flag, unsigned spin_limit, hipStream_t s)
+hipError_t launch_exchange_only(u64* xchg, unsigned tag_base, int H, int waves, int steps, int* timeout_flag,
+                                unsigned spin_limit, hipStream_t s)
 {
     if (H <= 0 || steps <= 0) return hipSuccess;
-    const int wpg = pick_waves(H, waves, 16);
+    const int wpg = pick_waves(H, waves, 16, 1);
     const int blocks = (H + wpg - 1) / wpg;
-    const size_t lds = 2 * (size_t)H * sizeof(float);
+    const size_t lds = ((size_t)H + wpg) * sizeof(float);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     void* args[] = {(void*)&xchg, (void*)&tag_base, (void*)&H, (void*)&steps, (void*)&timeout_flag, (void*)&spin_limit};
     return coop_launch(exchange_only_kernel, blocks, wpg * 64, lds, args, s);

@@ -49,6 +49,16 @@ def test_persistent_group_sizes(waves, fmt):
     assert "persist_b1" in desc
 
 
+@pytest.mark.parametrize("L", [2, 3, 4])
+@pytest.mark.parametrize("H,D,keep", [(150, 90, 0.3), (64, 200, 0.9), (700, 300, 0.05)])
+def test_layer_wavefront_stacks(L, H, D, keep):
+    """Unidirectional row-compressed stacks at batch 1 run two layers per launch (diagonal wavefront)."""
+    case = inputs.make_case(_wl(99, L, False, D, H, 11, 1, keep=keep), k=L, random_state=True)
+    desc, _ = check_case(case, CSR, PERSIST)
+    assert "wavefront" in desc
+    check_case(inputs.make_case(_wl(99, L, False, D, H, 1, 1, keep=keep), k=L), CSR, PERSIST)   # T = 1
+
+
 def test_bf16_small():
     for Bn, keep in ((1, None), (3, 0.3), (9, None)):
         case = inputs.make_case(_wl(92, 2, False, 48, 96, 6, Bn, dtype="bf16", a=0.2, keep=keep), k=Bn, random_state=True)
