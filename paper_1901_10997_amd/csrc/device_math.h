@@ -50,6 +50,43 @@ __device__ __forceinline__ float dpp_add(float v)
 {
     return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
+// Returns a register in which every lane of row q (lanes 16q..16q+15) holds the wave-wide total of a_q.
+__device__ __forceinline__ float wave_sum4_rows(float a0, float a1, float a2, float a3)
+{
+    const auto s02 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a0), __float_as_uint(a2), false, false);
+    const auto s13 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a1), __float_as_uint(a3), false, false);
+    const float k02 = __uint_as_float(s02[0]) + __uint_as_float(s02[1]);
+    const float k13 = __uint_as_float(s13[0]) + __uint_as_float(s13[1]);
+    const auto sr = __builtin_amdgcn_permlane16_swap(__float_as_uint(k02), __float_as_uint(k13), false, false);
+    float v = __uint_as_float(sr[0]) + __uint_as_float(sr[1]);
+    v = dpp_add<0xB1>(v);
+    v = dpp_add<0x4E>(v);
+    v = dpp_add<0x141>(v);
+    v = dpp_add<0x140>(v);
+    return v;
+}
+
+__device__ __forceinline__ float lane_read(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// Gate nonlinearities with the four gates of one hidden unit spread over the four 16-lane rows of a wave
+// (row 0 forget, 1 input, 2 output: sigmoid; row 3 candidate: tanh), so that one exp2 and one reciprocal
+// serve all four.  gate = A + Bm / (1 + 2^(sc * pre)) with (sc, A, Bm) = (-log2 e, 0, 1) for the sigmoid rows
+// and (2 log2 e, 1, -2) for the tanh row.  Then the cell update of the paper's Section 4:
+// c <- f*c + i*g, h = o*tanh(c).  pre: per-lane pre-activation (row q: gate q).  Returns h; c is updated.
+__device__ __forceinline__ float lstm_cell_rows(float pre, int lane, float& c)
+{
+    const bool cand = lane >= 48;
+    const float sc = cand ? 2.8853900817779268f : -1.4426950408889634f;
+    const float rr = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc * pre));
+    const float gate = cand ? fmaf(-2.0f, rr, 1.0f) : rr;
+    const float f = lane_read(gate, 0), i = lane_read(gate, 16), o = lane_read(gate, 32), g = lane_read(gate, 48);
+    c = fmaf(f, c, i * g);
+    return o * tanhf_fast(c);
+}
+
 __device__ __forceinline__ void wave_sum4(float a0, float a1, float a2, float a3, float r[4])
 {
     // lanes 32..63 of the first operand swap with lanes 0..31 of the second

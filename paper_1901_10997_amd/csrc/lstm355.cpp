@@ -173,15 +173,41 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
     HIP_TRY(m, upload(&out.row_ptr, rp32));
     HIP_TRY(m, upload(&out.col16, c16));
     HIP_TRY(m, upload(&out.val, out.h_val));
-    // 64-lane slices for the register-resident batch-1 kernel: entry i of a row -> slot i/64, lane i%64
+    // 64-lane slices for the register-resident batch-1 kernel.  The kernel gathers h[col] from LDS, whose 32
+    // four-byte banks serve the lanes 0..31 and 32..63 of a wave in two passes; an entry with column c is
+    // therefore placed, where room allows, in a lane congruent to c modulo 32, so that the lanes of a pass hit
+    // distinct banks.  Entries that do not fit their bank's lanes fill the remaining positions.  (The order of
+    // the entries inside a row is free: it only fixes the order of a sum.)
     out.slots = std::max(1, (max_nnz + 63) / 64);
     if (out.slots <= 8) {
-        std::vector<float> ev((size_t)rows * out.slots * 64, 0.0f);
-        std::vector<uint16_t> ec((size_t)rows * out.slots * 64, 0);
+        const int S = out.slots;
+        std::vector<float> ev((size_t)rows * S * 64, 0.0f);
+        std::vector<uint16_t> ec((size_t)rows * S * 64, 0);
+        std::vector<char> used((size_t)S * 64);
+        std::vector<int64_t> leftover;
         for (int rp = 0; rp < rows; ++rp) {
             const int64_t beg = out.h_row_ptr[rp], end = out.h_row_ptr[rp + 1];
+            std::fill(used.begin(), used.end(), 0);
+            leftover.clear();
+            int fill[32] = {0};  // positions already taken in each bank's lanes (slot-major: lane b, lane b+32)
             for (int64_t e = beg; e < end; ++e) {
-                const size_t idx = (size_t)rp * out.slots * 64 + (size_t)(e - beg);
+                const int bank = out.h_col[e] & 31;
+                if (fill[bank] < 2 * S) {
+                    const int slot = fill[bank] >> 1, lane = bank + 32 * (fill[bank] & 1);
+                    ++fill[bank];
+                    used[(size_t)slot * 64 + lane] = 1;
+                    const size_t idx = ((size_t)rp * S + slot) * 64 + lane;
+                    ev[idx] = out.h_val[e];
+                    ec[idx] = (uint16_t)out.h_col[e];
+                } else {
+                    leftover.push_back(e);
+                }
+            }
+            size_t pos = 0;
+            for (int64_t e : leftover) {
+                while (used[pos]) ++pos;
+                used[pos] = 1;
+                const size_t idx = (size_t)rp * S * 64 + pos;
                 ev[idx] = out.h_val[e];
                 ec[idx] = (uint16_t)out.h_col[e];
             }

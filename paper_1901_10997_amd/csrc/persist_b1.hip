@@ -119,10 +119,11 @@ __device__ __forceinline__ float load_x(const void* x, int x_bf16, size_t idx)
 template <int KI, bool FUSEX, int MAXT>
 __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
 {
-    extern __shared__ float lds[];  // hbuf[KI*64] | pub[waves]
+    extern __shared__ float lds[];  // hbuf[KI*64] | pub[16] | xbuf[2][KI*64] (fused only)
     constexpr int HP = KI * 64;
     float* hbuf = lds;
     float* pub = lds + HP;
+    float* xbuf = pub + 16;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, upb = nthreads >> 6;
     const int j = blockIdx.x * upb + wave;
@@ -150,44 +151,80 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
                 wx[q][i] = u;
             }
         }
-    float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (FUSEX && active) bias4 = *reinterpret_cast<const float4*>(a.bias + 4 * j);
+    const int row = lane >> 4;                       // gate handled by this lane after the reduction
+    float bias_l = 0.f;                              // fused: bias of gate `row`
+    if (FUSEX && active) bias_l = a.bias[4 * j + row];
     for (int e = tid; e < HP; e += nthreads) hbuf[e] = 0.f;  // padding beyond H must stay finite
     float c = (active && a.c0) ? a.c0[j] : 0.f;
     __syncthreads();
 
-    for (int s = 0; s < a.T; ++s) {
-        const int t = a.reverse ? (a.T - 1 - s) : s;
-        float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
-        float4 p = bias4;
-        // operands that do not depend on the recurrence are requested before the wait for h_{t-1} and
-        // consumed after it, so their memory latency overlaps the wait
-        float xv[FUSEX ? KI : 1];
-        if (FUSEX) {
+    // Input side: x_t does not depend on the recurrence.  The workgroup requests row s+1 with coalesced loads
+    // before the wait of step s, parks it in LDS right after the wait (when every outstanding memory
+    // operation has completed anyway), and each wave accumulates its products for step s+1 after h_s has
+    // been published -- the time in which the wave would otherwise idle until that h has travelled.
+    constexpr int XPT = (HP + MAXT - 1) / MAXT > 4 ? (HP + MAXT - 1) / MAXT : 4;
+    float xr[FUSEX ? XPT : 1];
+    float xa0 = 0.f, xa1 = 0.f, xa2 = 0.f, xa3 = 0.f;
+    auto request_x = [&](int s_) {
+        const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s_) : s_) * a.D;
+        if (a.x_bf16) {
 #pragma unroll
-            for (int i = 0; i < KI; ++i) {
-                const int k = lane + 64 * i;
-                xv[i] = (k < a.D) ? load_x(a.x, a.x_bf16, (size_t)t * a.D + k) : 0.f;
+            for (int u = 0; u < XPT; ++u) {
+                const int e = tid + u * nthreads;
+                xr[FUSEX ? u : 0] = (e < a.D) ? bf16_bits_to_f32(((const uint16_t*)a.x)[xrow + e]) : 0.f;
             }
         } else {
-            if (active) p = *reinterpret_cast<const float4*>(a.P + (size_t)t * 4 * a.H + 4 * j);
+#pragma unroll
+            for (int u = 0; u < XPT; ++u) {
+                const int e = tid + u * nthreads;
+                xr[FUSEX ? u : 0] = (e < a.D) ? ((const float*)a.x)[xrow + e] : 0.f;
+            }
+        }
+    };
+    auto park_x = [&](int s_) {
+        float* xb = xbuf + (s_ & 1) * HP;
+#pragma unroll
+        for (int u = 0; u < XPT; ++u) {
+            const int e = tid + u * nthreads;
+            if (e < HP) xb[e] = a.round_x_bf16 ? round_bf16(xr[FUSEX ? u : 0]) : xr[FUSEX ? u : 0];
+        }
+    };
+    auto x_products = [&](int s_) {
+        const float* xb = xbuf + (s_ & 1) * HP;
+        xa0 = xa1 = xa2 = xa3 = 0.f;
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+            const float v = xb[lane + 64 * i];
+            xa0 = fmaf(wx[FUSEX ? 0 : 0][FUSEX ? i : 0], v, xa0);
+            xa1 = fmaf(wx[FUSEX ? 1 : 0][FUSEX ? i : 0], v, xa1);
+            xa2 = fmaf(wx[FUSEX ? 2 : 0][FUSEX ? i : 0], v, xa2);
+            xa3 = fmaf(wx[FUSEX ? 3 : 0][FUSEX ? i : 0], v, xa3);
+        }
+    };
+    if (FUSEX) {
+        request_x(0);
+        park_x(0);
+        __syncthreads();
+        x_products(0);
+    }
+
+    for (int s = 0; s < a.T; ++s) {
+        const int t = a.reverse ? (a.T - 1 - s) : s;
+        float pl = bias_l;
+        const bool more_x = FUSEX && s + 1 < a.T;
+        if (FUSEX) {
+            if (more_x) request_x(s + 1);            // in flight during the wait below
+        } else if (active) {
+            pl = a.P[(size_t)t * 4 * a.H + 4 * j + row];
         }
         if (s == 0)
             stage_initial(a.h0, a.H, hbuf, tid, nthreads, a.round_h_bf16);
         else
             gather_tagged(a.xchg + (size_t)(s & 1) * a.H, a.H, a.tag_base + (unsigned)s, hbuf, tid, nthreads,
                           a.timeout_flag, a.spin_limit);
+        if (more_x) park_x(s + 1);
         __syncthreads();
-        if (FUSEX) {
-#pragma unroll
-            for (int i = 0; i < KI; ++i) {
-                const float v = a.round_x_bf16 ? round_bf16(xv[i]) : xv[i];
-                acc0 = fmaf(wx[0][i], v, acc0);
-                acc1 = fmaf(wx[1][i], v, acc1);
-                acc2 = fmaf(wx[2][i], v, acc2);
-                acc3 = fmaf(wx[3][i], v, acc3);
-            }
-        }
+        float acc0 = xa0, acc1 = xa1, acc2 = xa2, acc3 = xa3;
 #pragma unroll
         for (int i = 0; i < KI; ++i) {
             const float hv = hbuf[lane + 64 * i];
@@ -196,14 +233,8 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
             acc2 = fmaf(wh[2][i], hv, acc2);
             acc3 = fmaf(wh[3][i], hv, acc3);
         }
-        float r[4];
-        wave_sum4(acc0, acc1, acc2, acc3, r);
-        const float f = sigmoidf_fast(r[0] + p.x);
-        const float ig = sigmoidf_fast(r[1] + p.y);
-        const float o = sigmoidf_fast(r[2] + p.z);
-        const float g = tanhf_fast(r[3] + p.w);
-        c = f * c + ig * g;
-        const float h = o * tanhf_fast(c);
+        const float pre = wave_sum4_rows(acc0, acc1, acc2, acc3) + pl;
+        const float h = lstm_cell_rows(pre, lane, c);
         if (lane == 0) {
             pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
             if (active) {
@@ -222,6 +253,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
                                    pack_slot(pub[tid], a.tag_base + (unsigned)s + 1u), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
+        if (more_x) x_products(s + 1);               // for step s+1, off the critical path
     }
 }
 
@@ -233,10 +265,10 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
 template <int NZ, int NL, int MAXT>
 __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs a)
 {
-    extern __shared__ float lds[];  // hbuf[NL][H] | xbuf[D0] | pub[waves]
+    extern __shared__ float lds[];  // hbuf[NL][H] | xbuf[2][D0] | pub[waves]
     const int H = a.H;
     float* xbuf = lds + (size_t)NL * H;
-    float* pub = xbuf + a.D0;
+    float* pub = xbuf + 2 * (size_t)a.D0;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
     const int upb = nwaves / NL;
@@ -277,35 +309,70 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
     }
 #define COLX(q, i) ((cxp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
 #define COLH(q, i) ((chp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
-    float4 bias4 = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (active) bias4 = *reinterpret_cast<const float4*>(L.bias + 4 * j);
-    // wave-uniform: keep the four biases in scalar registers
-    bias4.x = uniform_f32(bias4.x);
-    bias4.y = uniform_f32(bias4.y);
-    bias4.z = uniform_f32(bias4.z);
-    bias4.w = uniform_f32(bias4.w);
+    const int row = lane >> 4;                       // gate handled by this lane after the reduction
+    const float bias_l = active ? L.bias[4 * j + row] : 0.f;
     float c = (active && L.c0) ? L.c0[j] : 0.f;
     const int total_steps = a.T + NL - 1;
+
+    // The input vector of the first layer comes from the external sequence and does not depend on the
+    // recurrence.  The whole workgroup requests row s+1 with coalesced loads before the wait of step s, parks it
+    // in LDS right after the wait (when every outstanding memory operation has completed anyway), and the
+    // first layer's waves gather their products for step s+1 from it after h_s has been published -- the time
+    // in which they would otherwise idle until that h has travelled.
+    constexpr int XPT = 2;  // x elements per thread held in registers
+    float xr[XPT];
+    auto request_x = [&](int s_) {
+        const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s_) : s_) * a.D0;
+        if (a.x_bf16) {
+#pragma unroll
+            for (int u = 0; u < XPT; ++u) {
+                const int e = tid + u * nthreads;
+                xr[u] = (e < a.D0) ? bf16_bits_to_f32(((const uint16_t*)a.x)[xrow + e]) : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < XPT; ++u) {
+                const int e = tid + u * nthreads;
+                xr[u] = (e < a.D0) ? ((const float*)a.x)[xrow + e] : 0.f;
+            }
+        }
+    };
+    auto park_x = [&](int s_) {
+        const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s_) : s_) * a.D0;
+        float* xb = xbuf + (size_t)(s_ & 1) * a.D0;
+#pragma unroll
+        for (int u = 0; u < XPT; ++u) {
+            const int e = tid + u * nthreads;
+            if (e < a.D0) xb[e] = a.round_x_bf16 ? round_bf16(xr[u]) : xr[u];
+        }
+        for (int e = tid + XPT * nthreads; e < a.D0; e += nthreads) {  // wider inputs: the rest, directly
+            const float v = load_x(a.x, a.x_bf16, xrow + e);
+            xb[e] = a.round_x_bf16 ? round_bf16(v) : v;
+        }
+    };
+    float xacc[4] = {0.f, 0.f, 0.f, 0.f};
+    auto x_products = [&](int s_) {
+        const float* xb = xbuf + (size_t)(s_ & 1) * a.D0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xacc[q] = 0.f;
+        if (l == 0) {
+#pragma unroll
+            for (int i = 0; i < NZ; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) xacc[q] = fmaf(vx[q][i], xb[COLX(q, i)], xacc[q]);
+        }
+    };
+    request_x(0);
+    park_x(0);
+    __syncthreads();
+    x_products(0);
 
     for (int s = 0; s < total_steps; ++s) {
         const int ts = s - l;                        // time index this wave's layer works on
         const bool live = ts >= 0 && ts < a.T;
         const int t = a.reverse ? (a.T - 1 - ts) : ts;  // position in the sequence
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        // The input vector of the first layer (time index s) comes from the external sequence and does not
-        // depend on the recurrence: the whole workgroup requests it with coalesced loads before the wait for
-        // h, and parks it in LDS after the wait, where the first layer's waves gather from it.
-        constexpr int XPT = 4;  // x elements per thread and pass
-        const bool have_x = s < a.T;
-        const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s) : s) * a.D0;
-        float xr[XPT];
-        if (have_x) {
-#pragma unroll
-            for (int u = 0; u < XPT; ++u) {
-                const int e = tid + u * nthreads;
-                xr[u] = (e < a.D0) ? load_x(a.x, a.x_bf16, xrow + e) : 0.f;
-            }
-        }
+        const bool more_x = s + 1 < a.T;
+        if (more_x) request_x(s + 1);                // in flight during the wait below
         // stage, for every layer m, h^m at time index s-m-1 (the operand of layer m's recurrence at time s-m
         // and of layer m+1's input side at time s-m-1)
         PollSrc src[2] = {{nullptr, nullptr, 0u, 0}, {nullptr, nullptr, 0u, 0}};
@@ -319,26 +386,11 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
                 src[m] = PollSrc{a.xchg + ((size_t)m * 2 + ((tm + 1) & 1)) * H, dst, a.tag_base + (unsigned)tm + 1u, H};
         }
         gather_tagged2(src[0], src[1], tid, nthreads, a.timeout_flag, a.spin_limit);
-        if (have_x) {
-#pragma unroll
-            for (int u = 0; u < XPT; ++u) {
-                const int e = tid + u * nthreads;
-                if (e < a.D0) xbuf[e] = a.round_x_bf16 ? round_bf16(xr[u]) : xr[u];
-            }
-            for (int e = tid + XPT * nthreads; e < a.D0; e += nthreads) {   // wider inputs: the rest, directly
-                const float v = load_x(a.x, a.x_bf16, xrow + e);
-                xbuf[e] = a.round_x_bf16 ? round_bf16(v) : v;
-            }
-        }
+        if (more_x) park_x(s + 1);
         __syncthreads();
-        if (l == 0 && live) {
-#pragma unroll
-            for (int i = 0; i < NZ; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) acc[q] = fmaf(vx[q][i], xbuf[COLX(q, i)], acc[q]);
-        }
         float h = 0.f;
         if (live) {
+            float acc[4] = {xacc[0], xacc[1], xacc[2], xacc[3]};
             const float* hrec = lds + (size_t)l * H;
             if (l > 0) {
                 const float* hin = lds + (size_t)(l - 1) * H;
@@ -351,14 +403,8 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
             for (int i = 0; i < NZ; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) acc[q] = fmaf(vh[q][i], hrec[COLH(q, i)], acc[q]);
-            float r[4];
-            wave_sum4(acc[0], acc[1], acc[2], acc[3], r);
-            const float f = sigmoidf_fast(r[0] + bias4.x);
-            const float ig = sigmoidf_fast(r[1] + bias4.y);
-            const float o = sigmoidf_fast(r[2] + bias4.z);
-            const float g = tanhf_fast(r[3] + bias4.w);
-            c = f * c + ig * g;
-            h = o * tanhf_fast(c);
+            const float pre = wave_sum4_rows(acc[0], acc[1], acc[2], acc[3]) + bias_l;
+            h = lstm_cell_rows(pre, lane, c);
             if (lane == 0 && active) {
                 if (L.y) L.y[(size_t)t * L.y_ld + j] = h;
                 if (ts + 1 == a.T) {
@@ -380,6 +426,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
                                    pack_slot(pub[tid], a.tag_base + (unsigned)tsm + 1u), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
+        if (more_x) x_products(s + 1);               // input side of step s+1, off the critical path
     }
 }
 
@@ -446,13 +493,13 @@ static int pick_waves(int H, int requested, int max_waves, int divisor)
     return w;
 }
 
-// threads per workgroup allowed by the register budget: the weight slices (and staged inputs) take (fused ? 9 : 4)*KI registers
+// threads per workgroup allowed by the register budget: the weight slices take (fused ? 8 : 4)*KI registers
 // per lane, the rest of the kernel about 60; a compute unit gives 512 registers per lane and SIMD.
 constexpr int dense_maxt(int KI, bool fusex)
 {
-    return ((fusex ? 9 : 4) * KI <= 64) ? 1024 : ((fusex ? 9 : 4) * KI <= 96) ? 768 : 512;
+    return fusex ? (8 * KI <= 48 ? 1024 : 8 * KI <= 88 ? 768 : 512) : (4 * KI <= 64 ? 1024 : 4 * KI <= 96 ? 768 : 512);
 }
-constexpr int kDenseFuseMaxKI = 17;
+constexpr int kDenseFuseMaxKI = 20;
 constexpr int sparse_maxt(int NZ) { return NZ <= 1 ? 1024 : NZ <= 4 ? 768 : 512; }
 
 bool persist_b1_dense_supported(int H) { return H >= 1 && H <= 2048; }
@@ -468,7 +515,7 @@ static hipError_t launch_dense_ki(PersistB1Args a, int wpg_req, hipStream_t s)
     constexpr int MAXT = dense_maxt(KI, FUSEX);
     const int wpg = pick_waves(a.H, wpg_req, MAXT / 64, 1);
     const int blocks = (a.H + wpg - 1) / wpg;
-    const size_t lds = ((size_t)KI * 64 + wpg) * sizeof(float);
+    const size_t lds = ((size_t)KI * 64 * (FUSEX ? 3 : 1) + 16) * sizeof(float);
     void* args[] = {(void*)&a};
     return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT>, blocks, wpg * 64, lds, args, s);
 }
@@ -496,7 +543,7 @@ hipError_t launch_persist_b1_dense(const PersistB1Args& a, int wpg, hipStream_t 
 
 bool persist_b1_sparse_supported(int H, int D0, int slots_x, int slots_h, int nl)
 {
-    if (((size_t)nl * H + D0 + 16) * sizeof(float) > 64 * 1024) return false;
+    if (((size_t)nl * H + 2 * (size_t)D0 + 16) * sizeof(float) > 64 * 1024) return false;
     if (H < 1 || nl < 1 || nl > 2 || slots_x < 1 || slots_h < 1 || slots_x > 7 || slots_h > 7) return false;
     const int nz = slots_x > slots_h ? slots_x : slots_h;
     const int maxt = nz <= 1 ? 1024 : nz <= 4 ? 768 : 512;
@@ -511,7 +558,7 @@ static hipError_t launch_sparse_nz(SparseStackArgs a, int wpg_req, hipStream_t s
     const int wpg = pick_waves(a.H, wpg_req, MAXT / 64, NL);
     const int upb = wpg / NL;
     const int blocks = (a.H + upb - 1) / upb;
-    const size_t lds = ((size_t)NL * a.H + a.D0 + wpg) * sizeof(float);
+    const size_t lds = ((size_t)NL * a.H + 2 * (size_t)a.D0 + wpg) * sizeof(float);
     void* args[] = {(void*)&a};
     return coop_launch(persist_b1_sparse_kernel<NZ, NL, MAXT>, blocks, wpg * 64, lds, args, s);
 }
