@@ -41,6 +41,10 @@ struct LayerDir {
 // P[m][n] = bias[n] + sum_k X[m][k] * W[n][k];  X fp32 or bf16 (x_bf16), W fp32 or bf16 (w_bf16).
 hipError_t launch_proj_dense(const void* X, bool x_bf16, int ldx, const void* W, bool w_bf16, const float* bias,
                              float* P, int M, int N, int K, hipStream_t s);
+// Same product on the matrix cores (needs proj_mfma_supported); fp32 X with bf16 W is rounded to bf16 on load.
+bool proj_mfma_supported(bool w_bf16, int K, int ldx);
+hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, bool w_bf16, const float* bias, float* P,
+                            int M, int N, int K, hipStream_t s);
 // XT[k][m] = (float) X[m][k]   (optionally rounding fp32 -> bf16 -> fp32 on the way)
 hipError_t launch_transpose_to_f32(const void* X, bool x_bf16, int ldx, float* XT, int M, int K, bool round_bf16,
                                    hipStream_t s);

@@ -507,6 +507,8 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                     xt_ready = true;
                 }
                 HIP_TRY(m, launch_proj_csr(XT, w.wx.row_ptr, w.wx.col16, w.wx.val, w.bias, P[d], M, 4 * H, s));
+            } else if (proj_mfma_supported(bf16, D, D)) {
+                HIP_TRY(m, launch_proj_mfma(X, x_is_bf16, D, w.wx.dense, bf16, w.bias, P[d], M, 4 * H, D, s));
             } else {
                 HIP_TRY(m, launch_proj_dense(X, x_is_bf16, D, w.wx.dense, bf16, w.bias, P[d], M, 4 * H, D, s));
             }
