@@ -70,6 +70,30 @@ hipError_t launch_step_dense(const StepArgs& a, const void* Wh, bool w_bf16, hip
 hipError_t launch_step_csr(const StepArgs& a, const int32_t* row_ptr, const uint16_t* col, const float* val,
                            hipStream_t s);
 
+// bf16 step on the matrix cores (large batch, dense W_h): recurrent product + fused cell update.
+struct StepMfmaArgs {
+    const float* P;            // [T*B][4H]
+    const uint16_t* Wh;        // [4H][H] bf16, packed rows
+    const uint16_t* hb_prev;   // h_{t-1} in bf16, (b,k) at hb_prev[b*hb_prev_ld + k]; nullptr = zeros
+    int hb_prev_ld;
+    float* c;                  // [B][H] fp32, in place
+    float* y_t;                // h_t fp32 -> y_t[b*y_ld + j]
+    int y_ld;
+    uint16_t* hb_t;            // h_t bf16 -> hb_t[b*hb_ld + j]
+    int hb_ld;
+    float* hT;
+    float* cT;
+    int last, t, B, H;
+};
+bool step_mfma_supported(int B, int H);
+hipError_t launch_step_mfma_bf16(const StepMfmaArgs& a, hipStream_t s);
+hipError_t launch_f32_to_bf16(const float* src, int src_ld, uint16_t* dst, int dst_ld, int rows, int cols, hipStream_t s);
+
+// Row-compressed step for small batches: one or both directions of a layer per launch (H <= 2048).
+bool step_csr_pair_supported(int H, int slots);
+hipError_t launch_step_csr_pair(const StepArgs* a, const float* const* ell_val, const uint16_t* const* ell_col,
+                                const int* slots, int ndir, hipStream_t s);
+
 struct PersistB1Args {
     // recurrent weights, dense packed rows [4H][H], fp32 or bf16 bits
     const void* Wh;

@@ -112,7 +112,7 @@ static hipError_t upload(T** dst, const std::vector<T>& src)
 
 // Pack one matrix W[4H][cols] (ABI row order q*H + j) with its optional mask into device storage.
 static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t* mask, int H, int cols, bool compressed,
-                       bool bf16)
+                       bool bf16, bool keep_dense)
 {
     free_mat(out);
     const int rows = 4 * H;
@@ -120,7 +120,7 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
     out.cols = cols;
     out.compressed = compressed;
     auto abi_row = [H](int rp) { return (rp & 3) * H + (rp >> 2); };
-    if (!compressed) {
+    if (!compressed || keep_dense) {
         const size_t n = (size_t)rows * cols;
         if (bf16) {
             std::vector<uint16_t> buf(n);
@@ -142,7 +142,7 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
             HIP_TRY(m, upload(&d, buf));
             out.dense = d;
         }
-        return LSTM_OK;
+        if (!compressed) return LSTM_OK;
     }
     // row-compressed: structure = the mask (every position when there is no mask), columns ascending
     out.h_row_ptr.assign(rows + 1, 0);
@@ -307,9 +307,10 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     LayerDir& x = m->ld[(size_t)layer * m->Dn + direction];
     x.set = false;
     const bool bf16 = (m->dtype == LSTM_BF16);
-    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16);
+    // W_x is kept in both forms when compressed: large T*B projections run dense on the matrix cores
+    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16, true);
     if (rc != LSTM_OK) return rc;
-    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16);
+    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16, false);
     if (rc != LSTM_OK) return rc;
     std::vector<float> bp(rows);
     for (int rp = 0; rp < rows; ++rp) bp[rp] = b[(rp & 3) * H + (rp >> 2)];
@@ -321,7 +322,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
 
 // ---- workspace carve-up --------------------------------------------------------------------------------
 struct Workspace {
-    size_t P_off[2], XT_off, Y_off[2], c_off[2], total;
+    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, total;
 };
 static Workspace carve(const lstm_t* m, int T, int B)
 {
@@ -344,6 +345,14 @@ static Workspace carve(const lstm_t* m, int T, int B)
         w.c_off[d] = off;
         if (d < m->Dn) off += align256((size_t)B * H * sizeof(float));
     }
+    // bf16 models: bf16 copy of each layer's hidden sequence (matrix-core operand of the next step and of the
+    // next layer's projection) and a bf16 copy of h0
+    for (int i = 0; i < 2; ++i) {
+        w.Yb_off[i] = off;
+        if (m->dtype == LSTM_BF16) off += align256(M * m->Dn * H * sizeof(uint16_t));
+    }
+    w.hb0_off = off;
+    if (m->dtype == LSTM_BF16) off += align256((size_t)m->Dn * B * H * sizeof(uint16_t));
     w.total = off;
     return w;
 }
@@ -428,6 +437,9 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
     float* XT = (float*)(base + ws.XT_off);
     float* Ybuf[2] = {(float*)(base + ws.Y_off[0]), (float*)(base + ws.Y_off[1])};
     float* cbuf[2] = {(float*)(base + ws.c_off[0]), (float*)(base + ws.c_off[1])};
+    uint16_t* Ybf[2] = {(uint16_t*)(base + ws.Yb_off[0]), (uint16_t*)(base + ws.Yb_off[1])};
+    uint16_t* hb0 = (uint16_t*)(base + ws.hb0_off);
+    bool prev_has_bf16 = false;  // the layer below left a bf16 copy of its hidden sequence in Ybf[(l-1)&1]
     m->last_plan.clear();
 
     auto take_tags = [&](int T_) -> int {
@@ -456,8 +468,9 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
 
     for (int l = 0; l < L; ++l) {
         const int D = m->in_dim(l);
-        const void* X = (l == 0) ? x : (const void*)Ybuf[(l - 1) & 1];
-        const bool x_is_bf16 = (l == 0) && bf16;
+        const void* X = (l == 0) ? x : (prev_has_bf16 ? (const void*)Ybf[(l - 1) & 1] : (const void*)Ybuf[(l - 1) & 1]);
+        const bool x_is_bf16 = bf16 && (l == 0 || prev_has_bf16);
+        prev_has_bf16 = false;
         float* Yout = (l == L - 1) ? y : Ybuf[l & 1];
         const int y_ld = Dn * H;
         const bool try_persist = (B == 1 && m->plan != LSTM_PLAN_STEPWISE);
@@ -501,7 +514,10 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             if (mode[d] == 1 || mode[d] == 2) continue;
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             ProfSpan span(m, s, 0);
-            if (w.wx.compressed) {
+            // measured on MI355X: at 10-15 % density the dense MFMA product beats the compressed one once
+            // T*B reaches a few hundred rows; below that the compressed product reads far fewer bytes
+            const bool dense_proj = w.wx.dense && (!w.wx.compressed || (M >= 256 && proj_mfma_supported(bf16, D, D)));
+            if (!dense_proj) {
                 if (!xt_ready) {
                     HIP_TRY(m, launch_transpose_to_f32(X, x_is_bf16, D, XT, M, D, bf16 && !x_is_bf16, s));
                     xt_ready = true;
@@ -513,6 +529,101 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 HIP_TRY(m, launch_proj_dense(X, x_is_bf16, D, w.wx.dense, bf16, w.bias, P[d], M, 4 * H, D, s));
             }
         }
+        // ---- recurrence, bf16 dense at large batch: one matrix-core launch per step with the cell update fused
+        bool mfma_ok = bf16 && step_mfma_supported(B, H);
+        for (int d = 0; d < Dn; ++d) mfma_ok = mfma_ok && mode[d] == 0 && !m->ld[(size_t)l * Dn + d].wh.compressed;
+        if (mfma_ok) {
+            uint16_t* Yb = Ybf[l & 1];
+            for (int d = 0; d < Dn; ++d) {
+                const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                const size_t n = (size_t)l * Dn + d;
+                ProfSpan span(m, s, 1);
+                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
+                else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
+                uint16_t* hb0d = hb0 + (size_t)d * B * H;
+                if (h0) HIP_TRY(m, launch_f32_to_bf16(h0 + n * B * H, H, hb0d, H, B, H, s));
+                std::snprintf(tag, sizeof tag, "l%d.d%d:proj=dense,rec=stepwise-mfma-bf16;", l, d);
+                m->last_plan += tag;
+                for (int step = 0; step < T; ++step) {
+                    const int t = d ? (T - 1 - step) : step;
+                    StepMfmaArgs a{};
+                    a.P = P[d];
+                    a.Wh = (const uint16_t*)w.wh.dense;
+                    if (step == 0) {
+                        a.hb_prev = h0 ? hb0d : nullptr;
+                        a.hb_prev_ld = H;
+                    } else {
+                        const int tp = d ? t + 1 : t - 1;
+                        a.hb_prev = Yb + (size_t)tp * B * y_ld + (size_t)d * H;
+                        a.hb_prev_ld = y_ld;
+                    }
+                    a.c = cbuf[d];
+                    a.y_t = Yout + (size_t)t * B * y_ld + (size_t)d * H;
+                    a.y_ld = y_ld;
+                    a.hb_t = Yb + (size_t)t * B * y_ld + (size_t)d * H;
+                    a.hb_ld = y_ld;
+                    a.hT = hT ? hT + n * B * H : nullptr;
+                    a.cT = cT ? cT + n * B * H : nullptr;
+                    a.last = (step == T - 1);
+                    a.t = t;
+                    a.B = B;
+                    a.H = H;
+                    HIP_TRY(m, launch_step_mfma_bf16(a, s));
+                }
+            }
+            prev_has_bf16 = true;
+            continue;
+        }
+        // ---- recurrence, small-batch row-compressed: every direction of the layer advances in the same launch
+        bool pair_ok = true;
+        for (int d = 0; d < Dn; ++d) {
+            const LayerDir& w = m->ld[(size_t)l * Dn + d];
+            pair_ok = pair_ok && mode[d] == 0 && w.wh.compressed && w.wh.ell_val && step_csr_pair_supported(H, w.wh.slots);
+        }
+        if (pair_ok) {
+            const float* ev[2] = {nullptr, nullptr};
+            const uint16_t* ec[2] = {nullptr, nullptr};
+            int sl[2] = {0, 0};
+            ProfSpan span(m, s, 1);
+            for (int d = 0; d < Dn; ++d) {
+                const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                const size_t n = (size_t)l * Dn + d;
+                ev[d] = w.wh.ell_val; ec[d] = w.wh.ell_col; sl[d] = w.wh.slots;
+                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
+                else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
+                std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=stepwise-csr-paired;", l, d,
+                              (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr");
+                m->last_plan += tag;
+            }
+            for (int step = 0; step < T; ++step) {
+                StepArgs a[2] = {};
+                for (int d = 0; d < Dn; ++d) {
+                    const size_t n = (size_t)l * Dn + d;
+                    const int t = d ? (T - 1 - step) : step;
+                    a[d].P = P[d];
+                    if (step == 0) {
+                        a[d].h_prev = h0 ? h0 + n * B * H : nullptr;
+                        a[d].h_prev_ld = H;
+                    } else {
+                        const int tp = d ? t + 1 : t - 1;
+                        a[d].h_prev = Yout + (size_t)tp * B * y_ld + (size_t)d * H;
+                        a[d].h_prev_ld = y_ld;
+                    }
+                    a[d].c = cbuf[d];
+                    a[d].y_t = Yout + (size_t)t * B * y_ld + (size_t)d * H;
+                    a[d].y_ld = y_ld;
+                    a[d].hT = hT ? hT + n * B * H : nullptr;
+                    a[d].cT = cT ? cT + n * B * H : nullptr;
+                    a[d].last = (step == T - 1);
+                    a[d].t = t;
+                    a[d].B = B;
+                    a[d].H = H;
+                    a[d].round_h_bf16 = bf16 ? 1 : 0;
+                }
+                HIP_TRY(m, launch_step_csr_pair(a, ev, ec, sl, Dn, s));
+            }
+            continue;
+        }
         // ---- recurrence
         for (int d = 0; d < Dn; ++d) {
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
@@ -523,7 +634,8 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             float* cTn = cT ? cT + n * B * H : nullptr;
             static const char* const names[4] = {"stepwise", "persist_b1", "persist_b1", "persist_b1"};
             std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s%s,rec=%s-%s;", l, d, (mode[d] == 1 || mode[d] == 2) ? "fused-" : "",
-                          w.wx.compressed ? "csr" : "dense", names[mode[d]], w.wh.compressed ? "csr" : "dense");
+                          (w.wx.compressed && !(w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ) ? "csr" : "dense",
+                          names[mode[d]], w.wh.compressed ? "csr" : "dense");
             m->last_plan += tag;
             ProfSpan span(m, s, 1);
             if (mode[d] == 1) {

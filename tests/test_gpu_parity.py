@@ -66,6 +66,14 @@ def test_bf16_small():
             check_case(case, fmt, PAUTO)
 
 
+@pytest.mark.parametrize("Bn", [32, 40, 130])
+def test_bf16_matrix_core_step(Bn):
+    """bf16 dense stacks at batch >= 32 with H % 256 == 0 take the MFMA step kernel (batch tail included)."""
+    case = inputs.make_case(_wl(89, 2, False, 64, 256, 5, Bn, dtype="bf16", a=0.1), k=Bn, random_state=True)
+    desc, _ = check_case(case, DENSE, PAUTO)
+    assert "mfma" in desc
+
+
 def test_empty_sequences_are_noops():
     m = B.Lstm(1, 4, 4)
     case = inputs.make_case(_wl(93, 1, False, 4, 4, 2, 1), 0)
