@@ -31,8 +31,14 @@ def parse():
     ap.add_argument("--format", default="auto", choices=["auto", "dense", "csr"])
     ap.add_argument("--plan", default="auto", choices=["auto", "stepwise", "persistent"])
     ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--launch", default="ordinary", choices=["ordinary", "cooperative"],
+                    help="launch mode of the persistent kernels (ordinary: residency by grid <= compute units on an "
+                         "otherwise idle device; cooperative: guaranteed by the runtime, slower dispatch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--compare-launch-modes", action="store_true", help="also time the loop in the other launch mode")
     ap.add_argument("--sweep", action="store_true", help="also run the hidden-size latency sweep (written to --out)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run the 1 GiB device copy kernel (known traffic, for scaling profiler byte counters)")
     ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"))
     return ap.parse_args()
 
@@ -51,6 +57,14 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.load(build_if_missing=True)
     dev = torch.device("cuda:0")
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.zeros(n, dtype=torch.uint8, device=dev)
+        dst = torch.empty(n, dtype=torch.uint8, device=dev)
+        us = B.lstm_bench_copy(dst.data_ptr(), src.data_ptr(), n, 10)
+        print(json.dumps({"metric": "device_copy_bandwidth", "value": 2 * n / us / 1e3, "unit": "GB/s",
+                          "bytes_read": n, "bytes_written": n, "avg_us": us}))
+        return
     wl = {"c1": inputs.c1(), "c2_b1": inputs.c2(1), "c2_b20": inputs.c2(20), "c4": inputs.c4(), "c5": inputs.c5()}[args.workload]
     case = inputs.make_case(wl, 0)
     dtype = B.LSTM_BF16 if wl.dtype == "bf16" else B.LSTM_F32
@@ -59,6 +73,7 @@ def main():
     m = B.Lstm(wl.layers, wl.input_dim, wl.hidden, wl.bidirectional, dtype)
     m.set_weights_from(case.weights, fmt)
     B.lstm_set_plan(m.handle, plan, args.waves)
+    B.lstm_set_launch_mode(m.handle, args.launch == "cooperative")
     x = torch.from_numpy(case.x).to(dev)
     if dtype == B.LSTM_BF16:
         x = x.to(torch.bfloat16)
@@ -90,6 +105,21 @@ def main():
     us_per_seq = ms_per_step * 1e3 / Bn
     plan_desc = B.lstm_describe_plan(m.handle)
 
+    other_mode = None
+    if args.compare_launch_modes:
+        other = "cooperative" if args.launch == "ordinary" else "ordinary"
+        B.lstm_set_launch_mode(m.handle, other == "cooperative")
+        for _ in range(min(args.warmup, 5)):
+            step()
+        torch.cuda.synchronize(dev)
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize(dev)
+        other_mode = {other: (time.perf_counter() - t0) * 1e6 / args.steps / Bn}
+        B.lstm_check(m.handle)
+        B.lstm_set_launch_mode(m.handle, args.launch == "cooperative")
+
     # per-kernel durations from events the library records on the same stream (separate pass: the event
     # pairs perturb the stream, so they stay out of the latency figure above)
     B.lstm_set_profiling(m.handle, True)
@@ -101,30 +131,58 @@ def main():
     rec_us = prof["rec_us"] / max(prof["rec_launches"], 1)      # average per recurrence launch (one layer-direction)
     proj_us = prof["proj_us"] / max(prof["proj_launches"], 1)
 
-    # algorithmic bytes of one recurrence launch (one layer, one direction, all T steps)
+    # Algorithmic bytes of one recurrence launch, for the plan that ran:
+    #  * on-chip-resident plans (persistent kernels) read each kept weight once per launch:
+    #    row-compressed: nnz * (4 B value + 2 B column); dense: 4H*K * sizeof(w);
+    #    plus, per timestep, the input row (fused input side) or the projected row P[t], and the h_t written;
+    #  * stepwise plans read W_h once per timestep.
     persistent = "persist" in plan_desc
-    compressed = "rec=persist_b1-csr" in plan_desc or "rec=stepwise-csr" in plan_desc
+    wavefront = "wavefront" in plan_desc
     wsize = 2 if dtype == B.LSTM_BF16 else 4
-    if compressed:
-        nnz_h = float(np.mean([int(case.weights[k]["Mh"].sum()) if case.weights[k]["Mh"] is not None else 4 * H * H
-                               for k in case.weights]))
-        w_bytes = nnz_h * (4 + 2) + (4 * H + 1) * 4
-    else:
-        w_bytes = 4.0 * H * H * wsize
-    io_bytes = T * Bn * (4 * H * 4 + H * 4)             # read P[t], write y[t]
-    alg_bytes = (w_bytes if persistent else w_bytes * T) + io_bytes
+
+    def mat_bytes(p, wn, mn, compressed):
+        Wm = p[wn]
+        if compressed:
+            nnz = int(p[mn].sum()) if p[mn] is not None else Wm.size
+            return nnz * (4 + 2) + (Wm.shape[0] + 1) * 4
+        return Wm.size * wsize
+
+    layers_per_launch = 2 if wavefront else 1
+    rec_launches_per_fwd = max(prof["rec_launches"] // max(args.steps, 1), 1)
+    alg_bytes = 0.0
+    keys = sorted(case.weights.keys())
+    for (l, d) in keys:
+        p = case.weights[(l, d)]
+        rec_compressed = B.lstm_is_compressed(m.handle, l, d, 1)
+        wh = mat_bytes(p, "Wh", "Mh", rec_compressed)
+        fused = "fused" in plan_desc
+        wx = mat_bytes(p, "Wx", "Mx", rec_compressed) if fused else 0
+        D_l = p["Wx"].shape[1]
+        per_step_in = D_l * 4 if (fused and (l == 0 or not wavefront)) else (0 if fused else 4 * H * 4)
+        per_step_out = H * 4 if not (wavefront and l == 0) else 0
+        if persistent:
+            alg_bytes += wh + wx + T * Bn * (per_step_in + per_step_out)
+        else:
+            alg_bytes += T * (wh + Bn * (4 * H * 4 + H * 4 + H * 4))
+    alg_bytes /= rec_launches_per_fwd
     achieved = alg_bytes / (rec_us * 1e-6) / 1e9 if rec_us > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": "recurrence (" + ("persistent, weights resident on chip" if persistent else "one launch per step") + ")",
+    roofline = {"bound": "hbm",
+                "kernel": "recurrence (" + ("persistent, weights resident on chip" + (", 2-layer wavefront" if wavefront else "")
+                                            if persistent else "one launch per step") + ")",
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": None, "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": rec_us,
-                "proj_avg_launch_us": proj_us}
+                "launches_per_forward": rec_launches_per_fwd, "proj_avg_launch_us": proj_us}
     if persistent and Bn == 1:
-        # latency criterion for the on-chip-resident plan: step time against the bare hidden-state exchange
+        # latency criterion of the on-chip-resident plan: time per sequential step against the bare exchange of
+        # the same number of hidden values between the same number of workgroups
         try:
-            ex_us = B.lstm_bench_exchange(H, args.waves, 200, 5, stream)
-            roofline["step_us"] = rec_us / T
+            slots = H * layers_per_launch
+            ex_us = B.lstm_bench_exchange(slots, 12 if wavefront else 0, 200, 5, stream, args.launch == "cooperative")
+            steps_seq = T + layers_per_launch - 1
+            roofline["sequential_steps_per_launch"] = steps_seq
+            roofline["step_us"] = rec_us / steps_seq
             roofline["exchange_only_step_us"] = ex_us
-            roofline["step_over_exchange"] = (rec_us / T) / ex_us if ex_us > 0 else None
+            roofline["step_over_exchange"] = (rec_us / steps_seq) / ex_us if ex_us > 0 else None
         except B.LstmError as e:
             roofline["exchange_only_step_us"] = None
             roofline["exchange_error"] = str(e)
@@ -132,37 +190,43 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import lstm_oracle
-        cols = list(range(min(Bn, 2)))
-        sub = inputs.select_batch(case, cols)
+        import dataclasses
+        # bounded sample of the same workload: a few sequences (batch columns are independent), all T steps
+        # except for the 1500-step bidirectional stack, which is cut to T'=30 and scaled (cost is linear in T)
+        nseq = {1: 64, 2: 8, 4: 2, 5: 8}.get(wl.cid, 4)
+        big = inputs.make_case(dataclasses.replace(wl, B=max(nseq, 1)), 0) if Bn < nseq else case
+        sub = inputs.select_batch(big, list(range(nseq)))
         Tc = T
         if wl.cid == 4:
-            import dataclasses
             Tc = 30
             sub = dataclasses.replace(sub, x=sub.x[:Tc].copy())
         t1 = time.perf_counter()
         lstm_oracle.forward_case(sub)
         cpu_s = time.perf_counter() - t1
-        cpu_us_per_seq = cpu_s * 1e6 / len(cols) * (T / Tc)
+        cpu_us_per_seq = cpu_s * 1e6 / nseq * (T / Tc)
         cpu = {"value": cpu_us_per_seq, "unit": "us/seq", "cores": lstm_oracle.max_threads(), "kind": "oracle",
-               "sample": f"{len(cols)} sequence(s) of the same workload, T={Tc} of {T}" + (" (scaled linearly in T)" if Tc != T else "")}
+               "sample": f"{nseq} sequence(s) of the same workload, T={Tc} of {T}" + (" (scaled linearly in T)" if Tc != T else ""),
+               "wall_s": cpu_s}
 
     out = {
         "metric": "lstm_fwd_latency_us_per_seq", "value": us_per_seq, "unit": "us/seq", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if dtype == B.LSTM_BF16 else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.layers, "bidirectional": wl.bidirectional, "input_dim": wl.input_dim,
-                   "hidden": H, "T": T, "batch": Bn, "mask_keep": wl.keep, "format": args.format, "plan": plan_desc},
+                   "hidden": H, "T": T, "batch": Bn, "mask_keep": wl.keep, "format": args.format, "plan": plan_desc, "launch": args.launch},
+        "us_per_seq_other_launch_mode": other_mode,
         "timestep_batch_per_s": T * Bn / (ms_per_step * 1e-3),
         "roofline": roofline, "cpu_baseline": cpu,
     }
     if args.sweep:
         os.makedirs(args.out, exist_ok=True)
         Hs = inputs.c3_hidden_sizes()
+        B.lstm_set_default_launch_mode(args.launch == "cooperative")
         med, p10, p90, flags = B.lstm_latency_sweep(Hs, 35, 1, B.LSTM_F32, 1, 10, 100, stream)
         f2, red2 = B.lstm_find_lhp(Hs, med, 0.02)
         f0, red0 = B.lstm_find_lhp(Hs, med, 0.0)
         with open(os.path.join(args.out, "latency_sweep.json"), "w") as fh:
-            json.dump({"H": Hs, "median_us": list(med), "p10_us": list(p10), "p90_us": list(p90),
+            json.dump({"launch": args.launch, "T": 35, "batch": 1, "H": Hs, "median_us": list(med), "p10_us": list(p10), "p90_us": list(p90),
                        "is_lhp_eps0": [int(v) for v in f0], "is_lhp_eps2pct": [int(v) for v in f2],
                        "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2}, fh)
         out["sweep"] = {"points": len(Hs), "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2,

@@ -123,6 +123,18 @@ int lstm_check(lstm_t* m);
 int lstm_set_plan(lstm_t* m, int plan, int waves_per_group);
 
 /*
+ * How the persistent kernels are launched.  cooperative = 1 (default): hipLaunchCooperativeKernel, which
+ * guarantees that every workgroup is resident (the hidden-state exchange needs all of them to make progress)
+ * at the price of a slower dispatch.  cooperative = 0: an ordinary launch; residency then rests on the grid
+ * never exceeding one workgroup per compute unit AND on the device not being shared with other kernels at
+ * that moment.  If that assumption is violated the bounded waits expire and lstm_check reports
+ * LSTM_ERR_TIMEOUT; nothing hangs.
+ */
+int lstm_set_launch_mode(lstm_t* m, int cooperative);
+/* Process-wide default that lstm_create gives to new handles (including those lstm_latency_sweep creates). */
+int lstm_set_default_launch_mode(int cooperative);
+
+/*
  * Kernel timing for measurement.  With profiling enabled every forward brackets each of its kernels (or, for
  * the stepwise plan, each run of per-step launches) with a pair of events on the caller's stream; this
  * perturbs the stream slightly, so end-to-end latency is quoted with profiling off.
@@ -170,9 +182,10 @@ int lstm_find_lhp(const int* dims, const double* lat, int n, double eps, uint8_t
 /* Measurement helpers (used by the benchmark to quote achievable peaks next to spec-sheet ones).
  * copy: device-to-device copy kernel of `bytes` bytes, `iters` times, returns the average microseconds.
  * barrier: `steps` rounds of the hidden-state exchange with no arithmetic, for `hidden` units and `groups`
- * workgroups of `waves` waves; returns the average microseconds per round.  DEVICE pointers where named. */
+ * workgroups of `waves` waves (launched cooperatively or not, see lstm_set_launch_mode); returns the average
+ * microseconds per round.  DEVICE pointers where named. */
 int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double* avg_us, void* stream);
-int lstm_bench_exchange(int hidden, int waves, int steps, int iters, double* avg_us_per_step, void* stream);
+int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream);
 
 #ifdef __cplusplus
 }

@@ -24,7 +24,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblstm355.
 # every symbol include/lstm355.h declares
 EXPORTS = [
     "lstm_create", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_workspace_bytes",
-    "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
+    "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
     "lstm_latency_sweep", "lstm_find_lhp", "lstm_bench_copy", "lstm_bench_exchange",
 ]
 
@@ -66,6 +66,10 @@ def load(build_if_missing: bool = True):
     lib.lstm_check.argtypes = [vp]
     lib.lstm_set_plan.restype = ci
     lib.lstm_set_plan.argtypes = [vp, ci, ci]
+    lib.lstm_set_launch_mode.restype = ci
+    lib.lstm_set_launch_mode.argtypes = [vp, ci]
+    lib.lstm_set_default_launch_mode.restype = ci
+    lib.lstm_set_default_launch_mode.argtypes = [ci]
     lib.lstm_set_profiling.restype = ci
     lib.lstm_set_profiling.argtypes = [vp, ci]
     lib.lstm_get_profile.restype = ci
@@ -81,7 +85,7 @@ def load(build_if_missing: bool = True):
     lib.lstm_bench_copy.restype = ci
     lib.lstm_bench_copy.argtypes = [vp, vp, c.c_size_t, ci, c.POINTER(c.c_double), vp]
     lib.lstm_bench_exchange.restype = ci
-    lib.lstm_bench_exchange.argtypes = [ci, ci, ci, ci, c.POINTER(c.c_double), vp]
+    lib.lstm_bench_exchange.argtypes = [ci, ci, ci, ci, ci, c.POINTER(c.c_double), vp]
     _lib = lib
     return lib
 
@@ -140,6 +144,14 @@ def lstm_set_plan(handle, plan: int, waves_per_group: int = 0) -> None:
     _check(load().lstm_set_plan(handle, plan, waves_per_group), handle)
 
 
+def lstm_set_launch_mode(handle, cooperative: bool) -> None:
+    _check(load().lstm_set_launch_mode(handle, int(bool(cooperative))), handle)
+
+
+def lstm_set_default_launch_mode(cooperative: bool) -> None:
+    _check(load().lstm_set_default_launch_mode(int(bool(cooperative))))
+
+
 def lstm_set_profiling(handle, enable: bool) -> None:
     _check(load().lstm_set_profiling(handle, int(bool(enable))), handle)
 
@@ -170,6 +182,17 @@ def lstm_get_compressed(handle, layer: int, direction: int, which: int, rows: in
     return row_ptr, col[:nnz.value], val[:nnz.value]
 
 
+def lstm_is_compressed(handle, layer: int, direction: int, which: int) -> bool:
+    """True when that matrix is held in row-compressed form (asks lstm_get_compressed for the count only)."""
+    nnz = ctypes.c_int64()
+    rc = load().lstm_get_compressed(handle, layer, direction, which, ctypes.byref(nnz), None, None, None)
+    if rc == LSTM_OK:
+        return True
+    if rc == LSTM_ERR_STATE:
+        return False
+    raise LstmError(rc, _err(handle))
+
+
 def lstm_latency_sweep(Hs: Sequence[int], T: int, B: int, dtype: int = LSTM_F32, seed: int = 1, warmup: int = 10,
                        iters: int = 100, stream: Optional[int] = None):
     Hs = np.ascontiguousarray(Hs, dtype=np.int32)
@@ -196,9 +219,10 @@ def lstm_bench_copy(dst_ptr: int, src_ptr: int, nbytes: int, iters: int = 20, st
     return us.value
 
 
-def lstm_bench_exchange(hidden: int, waves: int = 0, steps: int = 200, iters: int = 5, stream: Optional[int] = None) -> float:
+def lstm_bench_exchange(hidden: int, waves: int = 0, steps: int = 200, iters: int = 5, stream: Optional[int] = None,
+                        cooperative: bool = True) -> float:
     us = ctypes.c_double()
-    _check(load().lstm_bench_exchange(hidden, waves, steps, iters, ctypes.byref(us), stream))
+    _check(load().lstm_bench_exchange(hidden, waves, steps, iters, int(bool(cooperative)), ctypes.byref(us), stream))
     return us.value
 
 

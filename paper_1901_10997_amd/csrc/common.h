@@ -121,7 +121,7 @@ struct PersistB1Args {
     int* timeout_flag;         // set to 1 if a bounded wait expired
     unsigned spin_limit;
 };
-hipError_t launch_persist_b1_dense(const PersistB1Args& a, int waves_per_group, hipStream_t s);
+hipError_t launch_persist_b1_dense(const PersistB1Args& a, int waves_per_group, int cooperative, hipStream_t s);
 bool persist_b1_dense_supported(int H);
 bool persist_b1_dense_fusable(int H, int D);
 
@@ -153,13 +153,13 @@ struct SparseStackArgs {
     int* timeout_flag;
     unsigned spin_limit;
 };
-hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int layers, int waves_per_group, hipStream_t s);
+hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int layers, int waves_per_group, int cooperative, hipStream_t s);
 bool persist_b1_sparse_supported(int H, int D0, int slots_x, int slots_h, int layers);
 
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_exchange_only(unsigned long long* xchg, unsigned tag_base, int H, int waves, int steps,
-                                int* timeout_flag, unsigned spin_limit, hipStream_t s);
+                                int* timeout_flag, unsigned spin_limit, int cooperative, hipStream_t s);
 
 }  // namespace l355

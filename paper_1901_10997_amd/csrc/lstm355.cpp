@@ -26,6 +26,7 @@ struct lstm355 {
     unsigned spin_limit = 1u << 22;
     int plan = LSTM_PLAN_AUTO;
     int waves_per_group = 0;
+    int cooperative = 1;
     std::string last_plan;
     bool profiling = false;
     struct Span { hipEvent_t e0, e1; int kind; };
@@ -35,6 +36,7 @@ struct lstm355 {
 };
 
 static thread_local std::string g_create_error;
+static int g_default_cooperative = 1;
 
 static int fail(const lstm_t* m, int code, const std::string& msg)
 {
@@ -239,6 +241,7 @@ int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, in
     m->Dn = bidirectional ? 2 : 1;
     m->dtype = dtype;
     m->ld.resize((size_t)m->L * m->Dn);
+    m->cooperative = g_default_cooperative;
     if (const char* sl = std::getenv("LSTM355_SPIN_LIMIT")) {
         const long v = std::atol(sl);
         if (v > 0) m->spin_limit = (unsigned)v;
@@ -376,6 +379,19 @@ int lstm_set_plan(lstm_t* m, int plan, int waves_per_group)
     return LSTM_OK;
 }
 
+int lstm_set_launch_mode(lstm_t* m, int cooperative)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_set_launch_mode: handle is NULL");
+    m->cooperative = cooperative ? 1 : 0;
+    return LSTM_OK;
+}
+
+int lstm_set_default_launch_mode(int cooperative)
+{
+    g_default_cooperative = cooperative ? 1 : 0;
+    return LSTM_OK;
+}
+
 int lstm_set_profiling(lstm_t* m, int enable)
 {
     if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_set_profiling: handle is NULL");
@@ -489,7 +505,7 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             a.T = T; a.H = H; a.reverse = 0; a.round_h_bf16 = bf16;
             a.xchg = m->xchg; a.tag_base = m->tag_base; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
             m->tag_base += (unsigned)T;
-            HIP_TRY(m, launch_persist_b1_sparse(a, 2, m->waves_per_group, s));
+            HIP_TRY(m, launch_persist_b1_sparse(a, 2, m->waves_per_group, m->cooperative, s));
             std::snprintf(tag, sizeof tag, "l%d+l%d.d0:proj=fused-csr,rec=persist_b1-csr-wavefront;", l, l + 1);
             m->last_plan += tag;
             ++l;
@@ -648,7 +664,7 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = m->tag_base;
                 a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 m->tag_base += (unsigned)T;
-                HIP_TRY(m, launch_persist_b1_sparse(a, 1, m->waves_per_group, s));
+                HIP_TRY(m, launch_persist_b1_sparse(a, 1, m->waves_per_group, m->cooperative, s));
             } else if (mode[d] == 2 || mode[d] == 3) {
                 int rc = take_tags(T);
                 if (rc != LSTM_OK) return rc;
@@ -667,7 +683,7 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = m->tag_base;
                 a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 m->tag_base += (unsigned)T;
-                HIP_TRY(m, launch_persist_b1_dense(a, m->waves_per_group, s));
+                HIP_TRY(m, launch_persist_b1_dense(a, m->waves_per_group, m->cooperative, s));
             } else {
                 const size_t state_bytes = (size_t)B * H * sizeof(float);
                 if (c0n)
@@ -890,7 +906,7 @@ int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double*
     return LSTM_OK;
 }
 
-int lstm_bench_exchange(int hidden, int waves, int steps, int iters, double* avg_us_per_step, void* stream)
+int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream)
 {
     if (hidden < 1 || hidden > 8192 || waves < 0 || waves > 16 || steps < 2 || iters < 1 || !avg_us_per_step)
         return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_exchange: bad arguments");
@@ -906,11 +922,11 @@ int lstm_bench_exchange(int hidden, int waves, int steps, int iters, double* avg
     HIP_TRY(nullptr, hipEventCreate(&e1));
     unsigned tag = 0;
     int rc = LSTM_OK;
-    hipError_t e = launch_exchange_only(xchg, tag, hidden, waves, steps, flag, 1u << 22, s);
+    hipError_t e = launch_exchange_only(xchg, tag, hidden, waves, steps, flag, 1u << 22, cooperative, s);
     tag += (unsigned)steps;
     if (e == hipSuccess) e = hipEventRecord(e0, s);
     for (int i = 0; i < iters && e == hipSuccess; ++i) {
-        e = launch_exchange_only(xchg, tag, hidden, waves, steps, flag, 1u << 22, s);
+        e = launch_exchange_only(xchg, tag, hidden, waves, steps, flag, 1u << 22, cooperative, s);
         tag += (unsigned)steps;
     }
     if (e == hipSuccess) e = hipEventRecord(e1, s);

@@ -474,11 +474,16 @@ static int num_cu()
     return g_num_cu;
 }
 
+// Every workgroup of these kernels must be resident at the same time.  A cooperative launch makes the runtime
+// guarantee it; the ordinary launch relies on at most one workgroup per compute unit on an otherwise idle
+// device (the waits inside the kernels are bounded either way).
 template <typename K>
-static hipError_t coop_launch(K kernel, int blocks, int threads, size_t lds, void** args, hipStream_t s)
+static hipError_t coop_launch(K kernel, int blocks, int threads, size_t lds, void** args, bool cooperative, hipStream_t s)
 {
-    if (blocks > num_cu() * 8) return hipErrorCooperativeLaunchTooLarge;
-    return hipLaunchCooperativeKernel((const void*)kernel, dim3(blocks), dim3(threads), args, (unsigned)lds, s);
+    if (blocks > num_cu()) return hipErrorCooperativeLaunchTooLarge;
+    if (cooperative)
+        return hipLaunchCooperativeKernel((const void*)kernel, dim3(blocks), dim3(threads), args, (unsigned)lds, s);
+    return hipLaunchKernel((const void*)kernel, dim3(blocks), dim3(threads), args, lds, s);
 }
 
 // waves per workgroup: the largest allowed that still leaves at most one workgroup per compute unit
@@ -510,17 +515,17 @@ bool persist_b1_dense_fusable(int H, int D)
 }
 
 template <int KI, bool FUSEX>
-static hipError_t launch_dense_ki(PersistB1Args a, int wpg_req, hipStream_t s)
+static hipError_t launch_dense_ki(PersistB1Args a, int wpg_req, bool coop, hipStream_t s)
 {
     constexpr int MAXT = dense_maxt(KI, FUSEX);
     const int wpg = pick_waves(a.H, wpg_req, MAXT / 64, 1);
     const int blocks = (a.H + wpg - 1) / wpg;
     const size_t lds = ((size_t)KI * 64 * (FUSEX ? 3 : 1) + 16) * sizeof(float);
     void* args[] = {(void*)&a};
-    return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT>, blocks, wpg * 64, lds, args, s);
+    return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT>, blocks, wpg * 64, lds, args, coop, s);
 }
 
-hipError_t launch_persist_b1_dense(const PersistB1Args& a, int wpg, hipStream_t s)
+hipError_t launch_persist_b1_dense(const PersistB1Args& a, int wpg, int cooperative, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
     if (!persist_b1_dense_supported(a.H)) return hipErrorInvalidValue;
@@ -530,8 +535,8 @@ hipError_t launch_persist_b1_dense(const PersistB1Args& a, int wpg, hipStream_t 
     switch (KI) {
 #define CASE_KI(n)                                                     \
     case n:                                                            \
-        if (n <= kDenseFuseMaxKI && fuse) return launch_dense_ki<(n <= kDenseFuseMaxKI ? n : 1), true>(a, wpg, s); \
-        return launch_dense_ki<n, false>(a, wpg, s);
+        if (n <= kDenseFuseMaxKI && fuse) return launch_dense_ki<(n <= kDenseFuseMaxKI ? n : 1), true>(a, wpg, cooperative != 0, s); \
+        return launch_dense_ki<n, false>(a, wpg, cooperative != 0, s);
         CASE_KI(1) CASE_KI(2) CASE_KI(3) CASE_KI(4) CASE_KI(5) CASE_KI(6) CASE_KI(7) CASE_KI(8)
         CASE_KI(9) CASE_KI(10) CASE_KI(11) CASE_KI(12) CASE_KI(13) CASE_KI(14) CASE_KI(15) CASE_KI(16)
         CASE_KI(17) CASE_KI(18) CASE_KI(19) CASE_KI(20) CASE_KI(21) CASE_KI(22) CASE_KI(23) CASE_KI(24)
@@ -552,7 +557,7 @@ bool persist_b1_sparse_supported(int H, int D0, int slots_x, int slots_h, int nl
 }
 
 template <int NZ, int NL>
-static hipError_t launch_sparse_nz(SparseStackArgs a, int wpg_req, hipStream_t s)
+static hipError_t launch_sparse_nz(SparseStackArgs a, int wpg_req, bool coop, hipStream_t s)
 {
     constexpr int MAXT = sparse_maxt(NZ);
     const int wpg = pick_waves(a.H, wpg_req, MAXT / 64, NL);
@@ -560,10 +565,10 @@ static hipError_t launch_sparse_nz(SparseStackArgs a, int wpg_req, hipStream_t s
     const int blocks = (a.H + upb - 1) / upb;
     const size_t lds = ((size_t)NL * a.H + 2 * (size_t)a.D0 + wpg) * sizeof(float);
     void* args[] = {(void*)&a};
-    return coop_launch(persist_b1_sparse_kernel<NZ, NL, MAXT>, blocks, wpg * 64, lds, args, s);
+    return coop_launch(persist_b1_sparse_kernel<NZ, NL, MAXT>, blocks, wpg * 64, lds, args, coop, s);
 }
 
-hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int nl, int wpg, hipStream_t s)
+hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int nl, int wpg, int cooperative, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
     int nz = 1;
@@ -571,7 +576,7 @@ hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int nl, int wpg, h
     if (!persist_b1_sparse_supported(a.H, a.D0, nz, nz, nl)) return hipErrorInvalidValue;
 #define CASE_NZ(n)                                               \
     case n:                                                      \
-        return nl == 1 ? launch_sparse_nz<n, 1>(a, wpg, s) : launch_sparse_nz<n, 2>(a, wpg, s);
+        return nl == 1 ? launch_sparse_nz<n, 1>(a, wpg, cooperative != 0, s) : launch_sparse_nz<n, 2>(a, wpg, cooperative != 0, s);
     switch (nz) {
         CASE_NZ(1) CASE_NZ(2) CASE_NZ(3) CASE_NZ(4) CASE_NZ(5) CASE_NZ(6) CASE_NZ(7)
     }
@@ -580,7 +585,7 @@ hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int nl, int wpg, h
 }
 
 hipError_t launch_exchange_only(u64* xchg, unsigned tag_base, int H, int waves, int steps, int* timeout_flag,
-                                unsigned spin_limit, hipStream_t s)
+                                unsigned spin_limit, int cooperative, hipStream_t s)
 {
     if (H <= 0 || steps <= 0) return hipSuccess;
     const int wpg = pick_waves(H, waves, 16, 1);
@@ -588,7 +593,7 @@ hipError_t launch_exchange_only(u64* xchg, unsigned tag_base, int H, int waves, 
     const size_t lds = ((size_t)H + wpg) * sizeof(float);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
     void* args[] = {(void*)&xchg, (void*)&tag_base, (void*)&H, (void*)&steps, (void*)&timeout_flag, (void*)&spin_limit};
-    return coop_launch(exchange_only_kernel, blocks, wpg * 64, lds, args, s);
+    return coop_launch(exchange_only_kernel, blocks, wpg * 64, lds, args, cooperative != 0, s);
 }
 
 }  // namespace l355
