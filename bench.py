@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="also run the hidden-size latency sweep (written to --out)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run the 1 GiB device copy kernel (known traffic, for scaling profiler byte counters)")
-    ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out"))
+    ap.add_argument("--out", default=os.path.join(ROOT, "bench_out"))
     return ap.parse_args()
 
 

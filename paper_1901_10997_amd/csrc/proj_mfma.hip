@@ -291,6 +291,156 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_bf16_dlds_kernel(const uint1
 }
 
 // ---------------------------------------------------------------------------------------------------------
+// Large-M bf16 variant: 256 x 256 tile, eight waves (2 x 4, wave tile 128 x 64), 32-wide K slabs brought straight
+// into LDS through a four-deep ring (128 KB of LDS, one workgroup per compute unit), so that three slabs are
+// in flight while one is consumed: the L2 round trip (about 1.3 us under load) is longer than the MFMA work of
+// one slab.  Fragment reads are issued as explicit ds_read_b128 instructions: the compiler cannot see that an
+// LDS read depends on a particular direct-to-LDS load and would otherwise wait for ALL outstanding loads before
+// every read, which collapses the ring to depth one.  The dependency is kept by hand instead: a counted
+// s_waitcnt on the vector-memory counter (slab kt has landed once only the loads of the younger slabs are
+// outstanding), then the workgroup barrier, then the reads.
+// Chunk kc of row r lives at position kc ^ ((r >> 1) & 3) of its 64-byte row (bank-conflict-free 16-byte reads).
+// Needs K % 32 == 0.
+// ---------------------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+__device__ __forceinline__ u32x4 lds_read_b128(unsigned addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+    return v;
+}
+
+template <int NWN>  // waves along n: 4 -> eight waves of 128 x 64, 2 -> four waves of 128 x 128
+__global__ __launch_bounds__(128 * NWN) void proj_mfma_bf16_big_kernel(const uint16_t* __restrict__ X, int ldx,
+                                                                 const uint16_t* __restrict__ W,
+                                                                 const float* __restrict__ bias, float* __restrict__ P,
+                                                                 int M, int N, int K, int gm, int gn)
+{
+    constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
+    constexpr int NW = 2 * NWN;                           // waves per workgroup
+    constexpr int TM = 4, TN = 8 / NWN;                   // 32x32 tiles per wave
+    constexpr int ROWB = BK * 2;                          // 64 bytes per LDS row
+    constexpr int STAGE = (BM + BN) * ROWB;               // 32 KB
+    constexpr int LI = (BM + BN) / 16 / NW;               // direct-load instructions per wave and slab (16 rows each)
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
+
+    int tile_m, tile_n;
+    if (!tile_of_block(blockIdx.x, gm, gn, tile_m, tile_n)) return;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / NWN, wn = wave % NWN;           // 2 x NWN waves: rows wm*128, cols wn*32*TN
+    const int fr = lane & 31, fk = lane >> 5;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // direct loads: instruction q (0..31) of a slab covers LDS rows 16q..16q+15 of the combined [X rows | W rows]
+    const uint16_t* src[LI];
+#pragma unroll
+    for (int i = 0; i < LI; ++i) {
+        const int q = wave * LI + i;
+        const int row = q * 16 + (lane >> 2);             // 0..511: X rows then W rows
+        const int kc = (lane & 3) ^ ((row >> 1) & 3);
+        if (row < BM) {
+            int m = m0 + row;
+            if (m > M - 1) m = M - 1;
+            src[i] = X + (size_t)m * ldx + 8 * kc;
+        } else {
+            int n = n0 + row - BM;
+            if (n > N - 1) n = N - 1;
+            src[i] = W + (size_t)n * K + 8 * kc;
+        }
+    }
+    auto issue_slab = [&](int kt) {
+        unsigned char* st = smem + (size_t)(kt % NST) * STAGE;
+        const size_t koff = (size_t)kt * BK;
+#pragma unroll
+        for (int i = 0; i < LI; ++i)
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[i] + koff),
+                                             (void __attribute__((address_space(3)))*)(st + (size_t)(wave * LI + i) * 16 * ROWB),
+                                             16, 0, 0);
+    };
+    // byte offsets of this lane's fragments inside a stage (two k16 steps per slab)
+    unsigned offa[2][TM], offb[2][TN];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rr = (wm * TM + i) * 32 + fr;
+            offa[ks][i] = (unsigned)(rr * ROWB + (((ks * 2 + fk) ^ ((rr >> 1) & 3)) * 16));
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int rr = (wn * TN + j) * 32 + fr;
+            offb[ks][j] = (unsigned)(BM * ROWB + rr * ROWB + (((ks * 2 + fk) ^ ((rr >> 1) & 3)) * 16));
+        }
+    }
+
+    const int nslab = K / BK;
+    issue_slab(0);
+    if (nslab > 1) issue_slab(1);
+    if (nslab > 2) issue_slab(2);
+    for (int kt = 0; kt < nslab; ++kt) {
+        // slab kt has landed once only the loads of slabs kt+1 and kt+2 (LI each) can still be outstanding
+        const int younger = (nslab - 1 - kt) < 2 ? (nslab - 1 - kt) : 2;
+        if (younger == 2) wait_vmcnt(2 * LI); else if (younger == 1) wait_vmcnt(LI); else wait_vmcnt(0);
+        // bare barrier: __syncthreads() carries a workgroup fence, for which the compiler drains every outstanding
+        // direct-to-LDS load; the ordering needed here is exactly the counted wait above plus the barrier
+        __builtin_amdgcn_s_barrier();
+        if (kt + 3 < nslab) issue_slab(kt + 3);          // refills the buffer consumed in iteration kt-1
+        const unsigned st = lds0 + (unsigned)((kt % NST) * STAGE);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            u32x4 fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = lds_read_b128(st + offa[ks][i]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = lds_read_b128(st + offb[ks][j]);
+            // wait for the LDS reads; the fragments are operands of the wait so that no MFMA can move above it
+            if constexpr (TN == 2)
+                asm volatile("s_waitcnt lgkmcnt(0)"
+                             : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1])
+                             :
+                             : "memory");
+            else
+                asm volatile("s_waitcnt lgkmcnt(0)"
+                             : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]),
+                               "+v"(fb[3])
+                             :
+                             : "memory");
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
+                                                                       __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = n0 + (wn * TN + j) * 32 + fr;
+        if (n >= N) continue;
+        const float bn = bias[n];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int mb = m0 + (wm * TM + i) * 32 + 4 * fk;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int m = mb + 8 * (v >> 2) + (v & 3);
+                if (m < M) P[(size_t)m * N + n] = acc[i][j][v] + bn;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
 // fp32 operands on the fp32 matrix instruction (32x32x2).  Requires K % 4 == 0 (16-byte chunks along k).
 // Each lane reads four consecutive k of its fragment row at once and feeds them to four MFMAs; which k a lane
 // contributes to which MFMA is the same for both operands, which is all a sum over k needs.
@@ -440,6 +590,24 @@ static hipError_t launch_bf16_dlds(const uint16_t* X, int ldx, const uint16_t* W
     return hipGetLastError();
 }
 
+static hipError_t launch_bf16_big(const uint16_t* X, int ldx, const uint16_t* W, const float* bias, float* P, int M,
+                                  int N, int K, hipStream_t s)
+{
+    const int gm = (M + 255) / 256, gn = (N + 255) / 256;
+    const int grid = ((gm * gn + kXcds - 1) / kXcds) * kXcds;
+    const size_t lds = 4 * (size_t)512 * 64;
+    // eight waves of 128 x 64 measured 1.4x faster than four waves of 128 x 128 (whose 256 accumulator registers
+    // leave one wave per SIMD and force accumulator/vector register shuffling)
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)proj_mfma_bf16_big_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(proj_mfma_bf16_big_kernel<4>, dim3(grid), dim3(512), lds, s, X, ldx, W, bias, P, M, N, K, gm, gn);
+    return hipGetLastError();
+}
+
 template <int TM, int TN>
 static hipError_t launch_f32(const float* X, int ldx, const float* W, const float* bias, float* P, int M, int N, int K,
                              hipStream_t s)
@@ -472,6 +640,8 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
             return x_bf16 ? launch_bf16<2, 2, false>(X, ldx, Wb, bias, P, M, N, K, s)
                           : launch_bf16<2, 2, true>(X, ldx, Wb, bias, P, M, N, K, s);
         }
+        if (x_bf16 && K % 32 == 0 && M >= 2048 && N >= 512)
+            return launch_bf16_big((const uint16_t*)X, ldx, Wb, bias, P, M, N, K, s);
         if (x_bf16 && K % 32 == 0)
             return launch_bf16_dlds<4, 2>((const uint16_t*)X, ldx, Wb, bias, P, M, N, K, s);
         return x_bf16 ? launch_bf16<4, 2, false>(X, ldx, Wb, bias, P, M, N, K, s)
