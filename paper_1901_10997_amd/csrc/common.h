@@ -156,6 +156,33 @@ struct SparseStackArgs {
 hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int layers, int waves_per_group, int cooperative, hipStream_t s);
 bool persist_b1_sparse_supported(int H, int D0, int slots_x, int slots_h, int layers);
 
+// Small-batch row-compressed recurrence with the time loop on the device (all directions of a layer per launch).
+struct PersistBatchedDir {
+    const float* P;            // [T*B][4H] projection incl. bias
+    const float* ell_val;      // [4H][slots][64]
+    const uint16_t* ell_col;
+    int slots;
+    const float* h0;           // [B][H] or nullptr
+    const float* c0;
+    float* y;                  // h_t -> y[(t*B + b)*y_ld + j]  (already offset to this direction's columns)
+    int y_ld;
+    float* hT;                 // [B][H] or nullptr
+    float* cT;
+    int reverse;
+};
+struct PersistBatchedArgs {
+    PersistBatchedDir d[2];
+    int T, B, H;
+    int ug, bg;                // unit groups / batch groups per direction (filled by the launcher)
+    int round_h_bf16;
+    unsigned long long* xchg;  // [ndir][2][B][H] slots, zero or older tags only
+    unsigned tag_base;
+    int* timeout_flag;
+    unsigned spin_limit;
+};
+bool persist_batched_plan(int B, int H, int nz, int ndir, int* upw, int* bw, int* ug, int* bg);
+hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int cooperative, hipStream_t s);
+
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);

@@ -325,7 +325,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
 
 // ---- workspace carve-up --------------------------------------------------------------------------------
 struct Workspace {
-    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, total;
+    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, slot_off, total;
 };
 static Workspace carve(const lstm_t* m, int T, int B)
 {
@@ -356,6 +356,9 @@ static Workspace carve(const lstm_t* m, int T, int B)
     }
     w.hb0_off = off;
     if (m->dtype == LSTM_BF16) off += align256((size_t)m->Dn * B * H * sizeof(uint16_t));
+    // tagged exchange slots of the small-batch persistent recurrence: [Dn][2][B][H]
+    w.slot_off = off;
+    if (B >= 2) off += align256((size_t)m->Dn * 2 * B * H * sizeof(unsigned long long));
     w.total = off;
     return w;
 }
@@ -455,6 +458,9 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
     float* cbuf[2] = {(float*)(base + ws.c_off[0]), (float*)(base + ws.c_off[1])};
     uint16_t* Ybf[2] = {(uint16_t*)(base + ws.Yb_off[0]), (uint16_t*)(base + ws.Yb_off[1])};
     uint16_t* hb0 = (uint16_t*)(base + ws.hb0_off);
+    unsigned long long* bslots = (unsigned long long*)(base + ws.slot_off);
+    bool bslots_clean = false;   // zeroed during this forward (tags then restart at 1)
+    unsigned btag = 0;
     bool prev_has_bf16 = false;  // the layer below left a bf16 copy of its hidden sequence in Ybf[(l-1)&1]
     m->last_plan.clear();
 
@@ -521,7 +527,7 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 else if (persist_b1_dense_fusable(H, D)) mode[d] = 2;
                 else if (persist_b1_dense_supported(H)) mode[d] = 3;
             }
-            if (m->plan == LSTM_PLAN_PERSISTENT && mode[d] == 0)
+            if (m->plan == LSTM_PLAN_PERSISTENT && mode[d] == 0 && B == 1)
                 return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
         }
         // ---- input projection for every timestep (only the modes that need P)
@@ -589,6 +595,46 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             }
             prev_has_bf16 = true;
             continue;
+        }
+        // ---- recurrence, small-batch row-compressed, time loop on the device (all directions in one launch)
+        {
+            int nzmax = 0, upw, bw, ug, bg;
+            bool pb_ok = B >= 2 && m->plan != LSTM_PLAN_STEPWISE;
+            for (int d = 0; d < Dn && pb_ok; ++d) {
+                const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                pb_ok = w.wh.compressed && w.wh.ell_val != nullptr && w.wh.slots <= 4;
+                nzmax = std::max(nzmax, w.wh.slots);
+            }
+            pb_ok = pb_ok && persist_batched_plan(B, H, nzmax, Dn, &upw, &bw, &ug, &bg);
+            if (pb_ok) {
+                if (!bslots_clean) {
+                    HIP_TRY(m, launch_fill_u64(bslots, (size_t)Dn * 2 * B * H, 0ull, s));
+                    bslots_clean = true;
+                    btag = 0;
+                }
+                PersistBatchedArgs a{};
+                for (int d = 0; d < Dn; ++d) {
+                    const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                    const size_t n = (size_t)l * Dn + d;
+                    a.d[d].P = P[d];
+                    a.d[d].ell_val = w.wh.ell_val; a.d[d].ell_col = w.wh.ell_col; a.d[d].slots = w.wh.slots;
+                    a.d[d].h0 = h0 ? h0 + n * B * H : nullptr;
+                    a.d[d].c0 = c0 ? c0 + n * B * H : nullptr;
+                    a.d[d].y = Yout + (size_t)d * H; a.d[d].y_ld = y_ld;
+                    a.d[d].hT = hT ? hT + n * B * H : nullptr;
+                    a.d[d].cT = cT ? cT + n * B * H : nullptr;
+                    a.d[d].reverse = d;
+                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-csr(u%d,b%d);", l, d,
+                                  (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr", upw, bw);
+                    m->last_plan += tag;
+                }
+                a.T = T; a.B = B; a.H = H; a.round_h_bf16 = bf16;
+                a.xchg = bslots; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                btag += (unsigned)T;
+                ProfSpan span(m, s, 1);
+                HIP_TRY(m, launch_persist_batched(a, Dn, nzmax, m->cooperative, s));
+                continue;
+            }
         }
         // ---- recurrence, small-batch row-compressed: every direction of the layer advances in the same launch
         bool pair_ok = true;

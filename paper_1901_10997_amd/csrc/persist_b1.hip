@@ -26,73 +26,9 @@
 // All waits are bounded: on expiry a device flag is raised, every wave stops waiting and the kernel drains.
 #include "common.h"
 #include "device_math.h"
+#include "exchange.h"
 
 namespace l355 {
-
-typedef unsigned long long u64;
-
-__device__ __forceinline__ u64 pack_slot(float v, unsigned tag)
-{
-    return ((u64)tag << 32) | (u64)__float_as_uint(v);
-}
-
-// One polled slot array: n slots tagged `want` go to dst[0..n).  n = 0 switches the array off.
-struct PollSrc {
-    const u64* slots;
-    float* dst;
-    unsigned want;
-    int n;
-};
-
-// Fetch the tagged values of up to two slot arrays into LDS.  The two arrays are treated as one index space
-// so that all outstanding loads of a thread (up to four) are in flight together, whichever array they hit.
-__device__ __forceinline__ void gather_tagged2(const PollSrc& A, const PollSrc& Bs, int tid, int nthreads,
-                                               int* timeout_flag, unsigned spin_limit)
-{
-    const int total = A.n + Bs.n;
-    for (int e0 = tid; e0 < total; e0 += 4 * nthreads) {
-        u64 v[4];
-        unsigned spins = 0;
-        bool ok;
-        do {
-            ok = true;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int e = e0 + u * nthreads;
-                const bool second = e >= A.n;
-                const u64* p = second ? (Bs.slots + (e - A.n)) : (A.slots + e);
-                const unsigned want = second ? Bs.want : A.want;
-                v[u] = (e < total) ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ((u64)want << 32);
-                ok = ok && ((unsigned)(v[u] >> 32) == want);
-            }
-            if (!ok) {
-                ++spins;
-                if (spins > spin_limit) {
-                    __hip_atomic_store(timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-                if ((spins & 63u) == 0 &&
-                    __hip_atomic_load(timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
-                    break;
-            }
-        } while (!ok);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int e = e0 + u * nthreads;
-            if (e < total) {
-                if (e >= A.n) Bs.dst[e - A.n] = __uint_as_float((unsigned)v[u]);
-                else A.dst[e] = __uint_as_float((unsigned)v[u]);
-            }
-        }
-    }
-}
-
-__device__ __forceinline__ void gather_tagged(const u64* slots, int H, unsigned want, float* dst, int tid,
-                                              int nthreads, int* timeout_flag, unsigned spin_limit)
-{
-    const PollSrc A{slots, dst, want, H}, none{nullptr, nullptr, 0u, 0};
-    gather_tagged2(A, none, tid, nthreads, timeout_flag, spin_limit);
-}
 
 __device__ __forceinline__ float uniform_f32(float v)
 {

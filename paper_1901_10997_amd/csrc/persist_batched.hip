@@ -1,0 +1,237 @@
+// Small-batch row-compressed recurrence with the time loop on the device: one launch per layer, every
+// direction of the layer in the same grid.
+//
+// Per timestep (paper Section 4, cell equations): a = P[t] + W_h.h_{t-1} (P = input projection with bias);
+// f,i,o = sigmoid, g = tanh; c_t = f*c_{t-1} + i*g; h_t = o*tanh(c_t).
+//
+// The grid is a 2-D partition per direction: unit groups x batch groups.  A workgroup owns UPB hidden units
+// and BW batch columns; it needs only the h values of its own batch columns (all H of them), which keeps the
+// polled volume per workgroup at BW*H slots however large the batch is.  Each wave keeps the kept weights of
+// its UPW units in registers (64-lane slices, as the batch-1 kernel), gathers h from LDS, reduces the 4 x BW
+// partial sums of a unit with the lane-swap reduction so that lane 16*gate + pair holds a gate total
+// (pair = local unit * BW + column), evaluates all gates of all its pairs with one exp2 and one reciprocal,
+// and updates c and h in lanes 0..pairs-1.  h travels between workgroups through tagged 64-bit slots (value
+// and step tag published by one store; consumers poll until the tag matches), laid out [parity][B][H] per
+// direction so that a batch group's columns are contiguous.  All waits are bounded.
+#include "common.h"
+#include "device_math.h"
+#include "exchange.h"
+
+namespace l355 {
+
+template <int NZ, int UPW, int BW>
+__global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatchedArgs a)
+{
+    extern __shared__ float lds[];  // hbuf[H][BW] (the BW batch values of one k adjacent) | pub[BW][UPB]
+    constexpr int NZP = (NZ + 1) / 2;
+    constexpr int PAIRS = UPW * BW;
+    static_assert(PAIRS <= 16, "pairs must fit one 16-lane row");
+    const int H = a.H, B = a.B;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int upb = nwaves * UPW;
+    float* hbuf = lds;
+    float* pub = lds + (size_t)BW * H;
+    // block -> (direction, batch group, unit group)
+    const int per_dir = a.ug * a.bg;
+    const int dir = blockIdx.x / per_dir;
+    const int rem = blockIdx.x % per_dir;
+    const int bgi = rem / a.ug, ugi = rem % a.ug;
+    const PersistBatchedDir& D = a.d[dir];
+    const int b0 = bgi * BW;
+    const int bw = (B - b0) < BW ? (B - b0) : BW;         // columns actually present
+    const int u0 = ugi * upb + wave * UPW;                // first unit of this wave
+    u64* xchg = a.xchg + (size_t)dir * 2 * B * H;
+
+    // kept weights of this wave's units: values in fp32 registers; the column is kept as the 16-bit LDS byte
+    // offset of its h values, two to a register
+    float wv[UPW][4][NZ];
+    unsigned wc[UPW][4][NZP];
+#pragma unroll
+    for (int u = 0; u < UPW; ++u)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int i = 0; i < NZP; ++i) wc[u][q][i] = 0u;
+#pragma unroll
+            for (int i = 0; i < NZ; ++i) {
+                float v = 0.f;
+                unsigned k = 0;
+                if (u0 + u < H && i < D.slots) {
+                    const size_t idx = ((size_t)(4 * (u0 + u) + q) * D.slots + i) * 64 + lane;
+                    v = D.ell_val[idx];
+                    k = D.ell_col[idx];
+                }
+                wv[u][q][i] = v;
+                wc[u][q][i >> 1] |= (k * (BW * 4u)) << (16 * (i & 1));   // byte offset of h[k][0] in LDS (< 65536)
+            }
+        }
+    // lane 16*gate + pair: pair = local unit * BW + column
+    const int lp = lane & 15, row = lane >> 4;
+    const int pu = lp / BW, pb = lp % BW;
+    const bool pair_ok = lp < PAIRS && pb < bw && (u0 + pu) < H;
+    const int unit_l = u0 + pu;
+    float c = 0.f;
+    if (lane < 16 && pair_ok && D.c0) c = D.c0[(size_t)(b0 + pb) * H + unit_l];
+
+    for (int s = 0; s < a.T; ++s) {
+        const int t = D.reverse ? (a.T - 1 - s) : s;
+        float pin = 0.f;
+        if (pair_ok) pin = D.P[((size_t)t * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row];
+        if (s == 0) {
+            for (int e = tid; e < BW * H; e += nthreads) {
+                const int b = e / H, k = e - b * H;
+                float v = (D.h0 && b < bw) ? D.h0[(size_t)(b0 + b) * H + k] : 0.f;
+                if (a.round_h_bf16) v = round_bf16(v);
+                hbuf[k * BW + b] = v;
+            }
+        } else {
+            gather_tagged_interleave(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H, BW,
+                                     tid, nthreads, a.timeout_flag, a.spin_limit);
+        }
+        __syncthreads();
+        float G = 0.f;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            float acc[4][BW];
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int b = 0; b < BW; ++b) acc[q][b] = 0.f;
+#pragma unroll
+            for (int i = 0; i < NZ; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float w = wv[u][q][i];
+                    const unsigned off = (wc[u][q][i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
+                    const float* hp = reinterpret_cast<const float*>(reinterpret_cast<const char*>(hbuf) + off);
+                    if constexpr (BW == 2) {
+                        const float2 hv = *reinterpret_cast<const float2*>(hp);
+                        acc[q][0] = fmaf(w, hv.x, acc[q][0]);
+                        acc[q][1] = fmaf(w, hv.y, acc[q][1]);
+                    } else {
+                        const float4 hv = *reinterpret_cast<const float4*>(hp);
+                        acc[q][0] = fmaf(w, hv.x, acc[q][0]);
+                        acc[q][1] = fmaf(w, hv.y, acc[q][1]);
+                        acc[q][2] = fmaf(w, hv.z, acc[q][2]);
+                        acc[q][3] = fmaf(w, hv.w, acc[q][3]);
+                    }
+                }
+#pragma unroll
+            for (int b = 0; b < BW; ++b) {
+                const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
+                G = (lp == u * BW + b) ? r : G;
+            }
+        }
+        G += pin;
+        const bool cand = row == 3;
+        const float sc = cand ? 2.8853900817779268f : -1.4426950408889634f;
+        const float rr = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc * G));
+        const float gate = cand ? fmaf(-2.0f, rr, 1.0f) : rr;
+        const float gi = __shfl(gate, 16 + lp, 64), go = __shfl(gate, 32 + lp, 64), gg = __shfl(gate, 48 + lp, 64);
+        if (lane < 16) {
+            c = fmaf(gate, c, gi * gg);
+            const float h = go * tanhf_fast(c);
+            if (lp < PAIRS) pub[pb * upb + wave * UPW + pu] = a.round_h_bf16 ? round_bf16(h) : h;
+            if (pair_ok) {
+                D.y[((size_t)t * B + b0 + pb) * D.y_ld + unit_l] = h;
+                if (s + 1 == a.T) {
+                    const size_t ci = (size_t)(b0 + pb) * H + unit_l;
+                    if (D.hT) D.hT[ci] = h;
+                    if (D.cT) D.cT[ci] = c;
+                }
+            }
+        }
+        __syncthreads();
+        if (s + 1 < a.T) {
+            for (int e = tid; e < BW * upb; e += nthreads) {
+                const int b = e / upb, ul = e - b * upb;
+                const int unit = ugi * upb + ul;
+                if (b < bw && unit < H)
+                    __hip_atomic_store(xchg + ((size_t)((s + 1) & 1) * B + b0 + b) * H + unit,
+                                       pack_slot(pub[e], a.tag_base + (unsigned)s + 1u), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ planning
+static int g_cu = 0;
+static int cu_count()
+{
+    if (g_cu == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            g_cu = prop.multiProcessorCount;
+        if (g_cu <= 0) g_cu = 256;
+    }
+    return g_cu;
+}
+
+// Choose (UPW, BW): the most workgroups that still fit one per compute unit, within the register budget
+// (6*NZ registers per unit for the weights; 512-thread workgroups leave 256 registers per lane) and PAIRS <= 16.
+constexpr int kWaves = 8;
+constexpr int kWeightRegs = 150;
+bool persist_batched_plan(int B, int H, int nz, int ndir, int* upw_out, int* bw_out, int* ug_out, int* bg_out)
+{
+    if (B < 2 || nz < 1 || nz > 4 || H < 1 || H > 4096) return false;
+    int best = -1;
+    for (int bw = 2; bw <= 4; bw *= 2) {
+        for (int upw = 2; upw <= 8; ++upw) {
+            if (upw * bw > 16 || 6 * nz * upw > kWeightRegs) continue;
+            if (((size_t)bw * H + (size_t)bw * kWaves * upw) * sizeof(float) > 64 * 1024) continue;
+            const int ug = (H + kWaves * upw - 1) / (kWaves * upw), bg = (B + bw - 1) / bw;
+            const int blocks = ug * bg * ndir;
+            if (blocks > cu_count()) continue;
+            if (blocks > best) {
+                best = blocks;
+                *upw_out = upw; *bw_out = bw; *ug_out = ug; *bg_out = bg;
+            }
+        }
+    }
+    return best > 0;
+}
+
+template <int NZ, int UPW, int BW>
+static hipError_t launch_cfg(PersistBatchedArgs& a, int blocks, bool cooperative, hipStream_t s)
+{
+    const size_t lds = ((size_t)BW * a.H + (size_t)BW * kWaves * UPW) * sizeof(float);
+    void* args[] = {(void*)&a};
+    auto kern = persist_batched_sparse_kernel<NZ, UPW, BW>;
+    if (cooperative) return hipLaunchCooperativeKernel((const void*)kern, dim3(blocks), dim3(64 * kWaves), args, (unsigned)lds, s);
+    return hipLaunchKernel((const void*)kern, dim3(blocks), dim3(64 * kWaves), args, lds, s);
+}
+
+template <int NZ>
+static hipError_t launch_nz(PersistBatchedArgs& a, int upw, int bw, int blocks, bool coop, hipStream_t s)
+{
+#define CFG(U, W) if (upw == U && bw == W) return launch_cfg<NZ, U, W>(a, blocks, coop, s);
+    CFG(2, 2) CFG(3, 2) CFG(4, 2) CFG(2, 4) CFG(3, 4) CFG(4, 4)
+    if constexpr (6 * NZ * 5 <= kWeightRegs) { CFG(5, 2) }
+    if constexpr (6 * NZ * 6 <= kWeightRegs) { CFG(6, 2) }
+    if constexpr (6 * NZ * 7 <= kWeightRegs) { CFG(7, 2) }
+    if constexpr (6 * NZ * 8 <= kWeightRegs) { CFG(8, 2) }
+#undef CFG
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int cooperative, hipStream_t s)
+{
+    if (a.T <= 0) return hipSuccess;
+    int upw, bw, ug, bg;
+    if (!persist_batched_plan(a.B, a.H, nz, ndir, &upw, &bw, &ug, &bg)) return hipErrorInvalidValue;
+    a.ug = ug;
+    a.bg = bg;
+    const int blocks = ug * bg * ndir;
+    switch (nz) {
+        case 1: return launch_nz<1>(a, upw, bw, blocks, cooperative != 0, s);
+        case 2: return launch_nz<2>(a, upw, bw, blocks, cooperative != 0, s);
+        case 3: return launch_nz<3>(a, upw, bw, blocks, cooperative != 0, s);
+        case 4: return launch_nz<4>(a, upw, bw, blocks, cooperative != 0, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace l355

@@ -50,25 +50,37 @@ __global__ __launch_bounds__(256) void step_mfma_bf16_kernel(StepMfmaArgs a)
             arow[i] = a.hb_prev + (size_t)m * a.hb_prev_ld + wave * Kq + fk * 32;
             brow[i] = a.Wh + (size_t)(n0 + i * 32 + fr) * K + wave * Kq + fk * 32;
         }
-#pragma unroll 2
-        for (int kb = 0; kb < Kq; kb += 64) {
-            uint4 fa[2][4], fb[2][4];
+        // software pipeline over 64-wide k blocks: the fragments of block kb+64 are requested before the MFMAs
+        // of block kb are issued, so one memory round trip is exposed per wave instead of one per block
+        uint4 fa[2][2][4], fb[2][2][4];
+        auto request = [&](int buf, int kb) {
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
-                    fa[i][s] = *reinterpret_cast<const uint4*>(arow[i] + kb + s * 8);
-                    fb[i][s] = *reinterpret_cast<const uint4*>(brow[i] + kb + s * 8);
+                    fa[buf][i][s] = *reinterpret_cast<const uint4*>(arow[i] + kb + s * 8);
+                    fb[buf][i][s] = *reinterpret_cast<const uint4*>(brow[i] + kb + s * 8);
                 }
+        };
+        auto consume = [&](int buf) {
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][s]),
-                                                                           __builtin_bit_cast(bf16x8, fb[j][s]),
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[buf][i][s]),
+                                                                           __builtin_bit_cast(bf16x8, fb[buf][j][s]),
                                                                            acc[i][j], 0, 0, 0);
+        };
+        request(0, 0);
+        for (int kb = 0; kb < Kq; kb += 128) {
+            if (kb + 64 < Kq) request(1, kb + 64);
+            consume(0);
+            if (kb + 64 < Kq) {
+                if (kb + 128 < Kq) request(0, kb + 128);
+                consume(1);
+            }
         }
     }
     // partial tiles -> LDS.  Accumulator register v of lane l is element (8*(v/4) + 4*(l/32) + v%4, l%32).

@@ -59,6 +59,22 @@ def test_layer_wavefront_stacks(L, H, D, keep):
     check_case(inputs.make_case(_wl(99, L, False, D, H, 1, 1, keep=keep), k=L), CSR, PERSIST)   # T = 1
 
 
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, T, B, keep  -- small-batch row-compressed stacks: time loop on the device
+    (2, True, 64, 200, 9, 16, 0.15),
+    (1, False, 40, 333, 7, 20, 0.10),
+    (2, False, 48, 130, 6, 3, 0.5),
+    (1, True, 32, 96, 5, 33, 0.3),
+])
+def test_small_batch_persistent(shape):
+    L, bidir, D, H, T, Bn, keep = shape
+    case = inputs.make_case(_wl(88, L, bidir, D, H, T, Bn, keep=keep), k=H + Bn, random_state=True)
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "persist_batched" in desc
+    desc, _ = check_case(case, CSR, STEP)
+    assert "stepwise" in desc
+
+
 def test_bf16_small():
     for Bn, keep in ((1, None), (3, 0.3), (9, None)):
         case = inputs.make_case(_wl(92, 2, False, 48, 96, 6, Bn, dtype="bf16", a=0.2, keep=keep), k=Bn, random_state=True)
