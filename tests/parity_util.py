@@ -18,7 +18,7 @@ F32_REL_L2 = 1e-4
 BF16_REL = 2e-2
 
 
-def run_gpu(case, fmt=B.LSTM_FMT_AUTO, plan=B.LSTM_PLAN_AUTO, waves=0, model=None, return_model=False):
+def run_gpu(case, fmt=B.LSTM_FMT_AUTO, plan=B.LSTM_PLAN_AUTO, waves=0, model=None, return_model=False, cooperative=True):
     import torch
     w = case.w
     dtype = B.LSTM_BF16 if w.dtype == "bf16" else B.LSTM_F32
@@ -27,6 +27,7 @@ def run_gpu(case, fmt=B.LSTM_FMT_AUTO, plan=B.LSTM_PLAN_AUTO, waves=0, model=Non
         model = B.Lstm(w.layers, w.input_dim, w.hidden, w.bidirectional, dtype)
         model.set_weights_from(case.weights, fmt)
     B.lstm_set_plan(model.handle, plan, waves)
+    B.lstm_set_launch_mode(model.handle, cooperative)
     dev = torch.device("cuda:0")
     x = torch.from_numpy(case.x).to(dev)
     if dtype == B.LSTM_BF16:
@@ -65,12 +66,12 @@ def compare(gpu, ref, dtype: str, label: str = ""):
     return worst
 
 
-def check_case(case, fmt=B.LSTM_FMT_AUTO, plan=B.LSTM_PLAN_AUTO, waves=0, oracle_cols=None, label=""):
+def check_case(case, fmt=B.LSTM_FMT_AUTO, plan=B.LSTM_PLAN_AUTO, waves=0, oracle_cols=None, label="", cooperative=True):
     """GPU on the whole case; oracle on the whole case or on the sampled batch columns `oracle_cols`."""
     print(f"[parity] {label or case.w.name} seed={case.seed} fmt={fmt} plan={plan} waves={waves} "
           f"L={case.w.layers} Dn={case.w.ndir} D={case.w.input_dim} H={case.w.hidden} T={case.w.T} B={case.w.B}",
           flush=True)
-    gpu, desc = run_gpu(case, fmt, plan, waves)
+    gpu, desc = run_gpu(case, fmt, plan, waves, cooperative=cooperative)
     if oracle_cols is None:
         ref = orc.forward_case(case)
     else:

@@ -197,6 +197,21 @@ def test_repeated_forwards_on_one_handle_and_long_sequence():
     model.close()
 
 
+def test_long_sequence_small_batch_persistent():
+    """1500 steps through the per-batch-group exchange of the small-batch persistent kernel."""
+    case = inputs.make_case(_wl(87, 1, True, 24, 96, 1500, 4, a=0.2, keep=0.4), 0)
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "persist_batched" in desc
+
+
+@pytest.mark.parametrize("wl", ["c1", "c2_b1", "c2_b20", "c3_1312"])
+def test_ordinary_launch_mode_full_size(wl):
+    """The launch configuration the benchmark times: persistent kernels started with an ordinary launch."""
+    w = {"c1": inputs.c1(), "c2_b1": inputs.c2(1), "c2_b20": inputs.c2(20), "c3_1312": inputs.c3(1312)}[wl]
+    desc, _ = check_case(inputs.make_case(w, 1), AUTO, PAUTO, cooperative=False)
+    assert "persist" in desc
+
+
 # ---- the five configurations at full size ------------------------------------------------------------------
 @pytest.mark.parametrize("k", [0, 1, 2])
 @pytest.mark.parametrize("plan", [PAUTO, STEP])
