@@ -45,6 +45,8 @@ hipError_t launch_proj_dense(const void* X, bool x_bf16, int ldx, const void* W,
 bool proj_mfma_supported(bool w_bf16, int K, int ldx);
 hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, bool w_bf16, const float* bias, float* P,
                             int M, int N, int K, hipStream_t s);
+hipError_t launch_proj_mfma_f32_pair(const float* X, int ldx, const float* W0, const float* bias0, float* P0,
+                                     const float* W1, const float* bias1, float* P1, int M, int N, int K, hipStream_t s);
 // XT[k][m] = (float) X[m][k]   (optionally rounding fp32 -> bf16 -> fp32 on the way)
 hipError_t launch_transpose_to_f32(const void* X, bool x_bf16, int ldx, float* XT, int M, int K, bool round_bf16,
                                    hipStream_t s);

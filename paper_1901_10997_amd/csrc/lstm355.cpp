@@ -532,7 +532,21 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
         }
         // ---- input projection for every timestep (only the modes that need P)
         bool xt_ready = false;
-        for (int d = 0; d < Dn; ++d) {
+        bool pair_done = false;
+        if (Dn == 2 && !bf16 && mode[0] != 1 && mode[0] != 2 && mode[1] != 1 && mode[1] != 2) {
+            // fp32, both directions dense on the matrix cores: one launch (they read the same X)
+            const LayerDir& w0 = m->ld[(size_t)l * Dn], & w1 = m->ld[(size_t)l * Dn + 1];
+            auto dense_ok = [&](const LayerDir& w) {
+                return w.wx.dense && (!w.wx.compressed || M >= 256) && proj_mfma_supported(false, D, D);
+            };
+            if (dense_ok(w0) && dense_ok(w1)) {
+                ProfSpan span(m, s, 0);
+                HIP_TRY(m, launch_proj_mfma_f32_pair((const float*)X, D, (const float*)w0.wx.dense, w0.bias, P[0],
+                                                     (const float*)w1.wx.dense, w1.bias, P[1], M, 4 * H, D, s));
+                pair_done = true;
+            }
+        }
+        for (int d = 0; d < Dn && !pair_done; ++d) {
             if (mode[d] == 1 || mode[d] == 2) continue;
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             ProfSpan span(m, s, 0);

@@ -447,9 +447,16 @@ __global__ __launch_bounds__(128 * NWN) void proj_mfma_bf16_big_kernel(const uin
 // ---------------------------------------------------------------------------------------------------------
 template <int TM, int TN>
 __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restrict__ X, int ldx,
-                                                            const float* __restrict__ W, const float* __restrict__ bias,
-                                                            float* __restrict__ P, int M, int N, int K, int gm, int gn)
+                                                            const float* __restrict__ W0, const float* __restrict__ bias0,
+                                                            float* __restrict__ P0, const float* __restrict__ W1,
+                                                            const float* __restrict__ bias1, float* __restrict__ P1,
+                                                            int M, int N, int K, int gm, int gn)
 {
+    // blockIdx.y selects the direction: both directions of a layer read the same X, so one launch covers both
+    // and the second direction's tiles fill the tail of the first
+    const float* __restrict__ W = blockIdx.y ? W1 : W0;
+    const float* __restrict__ bias = blockIdx.y ? bias1 : bias0;
+    float* __restrict__ P = blockIdx.y ? P1 : P0;
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32, BK = 16;
     constexpr int LDR = BK + 4;                      // padded row length in floats (80 bytes)
     constexpr int ACH = (BM * (BK / 4) + 255) / 256;
@@ -552,6 +559,8 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
 }
 
 // ------------------------------------------------------------------------------------------------ launchers
+bool proj_mfma_supported(bool w_bf16, int K, int ldx);
+
 template <int TM, int TN, bool X_F32>
 static hipError_t launch_bf16(const void* X, int ldx, const uint16_t* W, const float* bias, float* P, int M, int N,
                               int K, hipStream_t s)
@@ -609,15 +618,26 @@ static hipError_t launch_bf16_big(const uint16_t* X, int ldx, const uint16_t* W,
 }
 
 template <int TM, int TN>
-static hipError_t launch_f32(const float* X, int ldx, const float* W, const float* bias, float* P, int M, int N, int K,
-                             hipStream_t s)
+static hipError_t launch_f32(const float* X, int ldx, const float* W, const float* bias, float* P, const float* W1,
+                             const float* bias1, float* P1, int M, int N, int K, hipStream_t s)
 {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
     const int gm = (M + BM - 1) / BM, gn = (N + BN - 1) / BN;
     const int grid = ((gm * gn + kXcds - 1) / kXcds) * kXcds;
     const size_t lds = 2 * (size_t)(BM + BN) * (16 + 4) * sizeof(float);
-    hipLaunchKernelGGL((proj_mfma_f32_kernel<TM, TN>), dim3(grid), dim3(256), lds, s, X, ldx, W, bias, P, M, N, K, gm, gn);
+    hipLaunchKernelGGL((proj_mfma_f32_kernel<TM, TN>), dim3(grid, W1 ? 2 : 1), dim3(256), lds, s, X, ldx, W, bias, P, W1,
+                       bias1, P1, M, N, K, gm, gn);
     return hipGetLastError();
+}
+
+// fp32, two directions of one layer (same X) in one launch
+hipError_t launch_proj_mfma_f32_pair(const float* X, int ldx, const float* W0, const float* bias0, float* P0,
+                                     const float* W1, const float* bias1, float* P1, int M, int N, int K, hipStream_t s)
+{
+    if (M <= 0 || N <= 0) return hipSuccess;
+    if (!proj_mfma_supported(false, K, ldx)) return hipErrorInvalidValue;
+    if (M <= 64) return launch_f32<1, 1>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
+    return launch_f32<2, 2>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
 }
 
 bool proj_mfma_supported(bool w_bf16, int K, int ldx)
@@ -648,8 +668,8 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
                       : launch_bf16<4, 2, true>(X, ldx, Wb, bias, P, M, N, K, s);
     }
     if (x_bf16) return hipErrorInvalidValue;
-    if (M <= 64) return launch_f32<1, 1>((const float*)X, ldx, (const float*)W, bias, P, M, N, K, s);
-    return launch_f32<2, 2>((const float*)X, ldx, (const float*)W, bias, P, M, N, K, s);
+    if (M <= 64) return launch_f32<1, 1>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
+    return launch_f32<2, 2>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
 }
 
 }  // namespace l355
