@@ -22,6 +22,23 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+def counter_traffic_bytes(workload_name):
+    """HBM bytes per launch of the dominant kernel from the committed profiler counters, or None when the kernel
+    sources have changed since they were taken (or none were taken for this workload)."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", "traffic_counters.txt")
+    try:
+        kv = dict(line.strip().split("=", 1) for line in open(path) if "=" in line and not line.startswith("#"))
+        h = hashlib.sha256()
+        for f in ("persist_b1.hip", "exchange.h", "device_math.h", "common.h"):
+            h.update(open(os.path.join(ROOT, "paper_1901_10997_amd", "csrc", f), "rb").read())
+        if kv.get("workload") != workload_name or kv.get("source_sha256") != h.hexdigest():
+            return None
+        return (float(kv["fetch_kib"]) * float(kv["fetch_scale"]) + float(kv["write_kib"]) * float(kv["write_scale"])) * 1024.0
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -170,7 +187,8 @@ def main():
                 "kernel": "recurrence (" + ("persistent, weights resident on chip" + (", 2-layer wavefront" if wavefront else "")
                                             if persistent else "one launch per step") + ")",
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": None, "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": rec_us,
+                "traffic": counter_traffic_bytes(wl.name) if (args.format == "auto" and args.plan == "auto") else None,
+                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": rec_us,
                 "launches_per_forward": rec_launches_per_fwd, "proj_avg_launch_us": proj_us}
     if persistent and Bn == 1:
         # latency criterion of the on-chip-resident plan: time per sequential step against the bare exchange of
