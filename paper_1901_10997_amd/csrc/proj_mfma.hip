@@ -558,6 +558,73 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// fp32, at most 64 rows of X (batch-1 sequences: M = T).  The product is a stream over W (read once, 4H*K*4
+// bytes) with X resident in L2, so there is no LDS pipeline: a workgroup owns 32 packed rows of W for all of
+// X, its four waves split K and stream their operand fragments from global memory straight into registers
+// (16 bytes per lane and row, eight k-blocks in flight), and the four partial 64 x 32 tiles are summed through
+// LDS in a fixed order.  Requires K % 16 == 0.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void proj_mfma_f32_skinny_kernel(const float* __restrict__ X, int ldx,
+                                                                   const float* __restrict__ W,
+                                                                   const float* __restrict__ bias, float* __restrict__ P,
+                                                                   int M, int N, int K)
+{
+    __shared__ float part[4][64][33];
+    const int n0 = blockIdx.x * 32;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 31, fk = lane >> 5;
+    // K is cut into four contiguous quarters (multiples of 8), one per wave
+    const int kq = ((K / 8 + 3) / 4) * 8;
+    const int kbeg = wave * kq, kend = (kbeg + kq) < K ? (kbeg + kq) : K;
+    f32x16 acc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    int m0r = fr, m1r = 32 + fr;
+    if (m0r > M - 1) m0r = M - 1;   // rows beyond M are computed on a valid row and never stored
+    if (m1r > M - 1) m1r = M - 1;
+    int nr = n0 + fr;
+    if (nr > N - 1) nr = N - 1;
+    const float* a0 = X + (size_t)m0r * ldx + fk * 4;
+    const float* a1 = X + (size_t)m1r * ldx + fk * 4;
+    const float* bw = W + (size_t)nr * K + fk * 4;
+    constexpr int UN = 8;            // k-blocks of 8 requested together
+    for (int k0 = kbeg; k0 < kend; k0 += 8 * UN) {
+        float4 fa0[UN], fa1[UN], fb[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = k0 + 8 * u;
+            const bool ok = k < kend;
+            fa0[u] = ok ? *reinterpret_cast<const float4*>(a0 + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            fa1[u] = ok ? *reinterpret_cast<const float4*>(a1 + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            fb[u] = ok ? *reinterpret_cast<const float4*>(bw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa0[u].x, fb[u].x, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa1[u].x, fb[u].x, acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa0[u].y, fb[u].y, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa1[u].y, fb[u].y, acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa0[u].z, fb[u].z, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa1[u].z, fb[u].z, acc[1], 0, 0, 0);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa0[u].w, fb[u].w, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa1[u].w, fb[u].w, acc[1], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) part[wave][i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3)][fr] = acc[i][v];
+    __syncthreads();
+    for (int e = tid; e < 64 * 32; e += 256) {
+        const int m = e >> 5, n = e & 31;
+        if (m < M && n0 + n < N)
+            P[(size_t)m * N + n0 + n] = ((part[0][m][n] + part[1][m][n]) + (part[2][m][n] + part[3][m][n])) + bias[n0 + n];
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ launchers
 bool proj_mfma_supported(bool w_bf16, int K, int ldx);
 
@@ -668,6 +735,11 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
                       : launch_bf16<4, 2, true>(X, ldx, Wb, bias, P, M, N, K, s);
     }
     if (x_bf16) return hipErrorInvalidValue;
+    if (M <= 64 && K % 16 == 0 && ldx % 4 == 0) {
+        hipLaunchKernelGGL(proj_mfma_f32_skinny_kernel, dim3((N + 31) / 32), dim3(256), 0, s, (const float*)X, ldx,
+                           (const float*)W, bias, P, M, N, K);
+        return hipGetLastError();
+    }
     if (M <= 64) return launch_f32<1, 1>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
     return launch_f32<2, 2>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
 }
