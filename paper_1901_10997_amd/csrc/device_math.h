@@ -40,17 +40,17 @@ __device__ __forceinline__ float wave_sum(float v)
     return v;
 }
 
-// Sum four per-lane values over the wavefront; r[0..3] receive the four totals (wave-uniform).
-// The four values are first distributed over the four 16-lane rows with the gfx950 lane-swap instructions
-// (upper/lower 32 lanes, then odd/even rows), each swap halving the number of lanes a value occupies while
-// adding the halves; one register then holds value q in row q, a 16-lane DPP butterfly finishes it, and
-// four lane reads fetch the totals.  About a dozen vector instructions, no LDS traffic.
+// v + (v moved by the DPP control CTRL): one step of a butterfly inside a 16-lane row
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v)
 {
     return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
-// Returns a register in which every lane of row q (lanes 16q..16q+15) holds the wave-wide total of a_q.
+// Sum four per-lane values over the wavefront: returns a register in which every lane of row q (lanes
+// 16q..16q+15) holds the wave-wide total of a_q.  The four values are first distributed over the four 16-lane
+// rows with the gfx950 lane-swap instructions (lanes 32..63 of one register against lanes 0..31 of another, then
+// odd rows against even rows), each swap halving the number of lanes a value occupies while adding the halves; a
+// 16-lane DPP butterfly (quad swaps, half-row mirror, row mirror) finishes it.  Ten vector instructions, no LDS.
 __device__ __forceinline__ float wave_sum4_rows(float a0, float a1, float a2, float a3)
 {
     const auto s02 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a0), __float_as_uint(a2), false, false);
@@ -85,26 +85,6 @@ __device__ __forceinline__ float lstm_cell_rows(float pre, int lane, float& c)
     const float f = lane_read(gate, 0), i = lane_read(gate, 16), o = lane_read(gate, 32), g = lane_read(gate, 48);
     c = fmaf(f, c, i * g);
     return o * tanhf_fast(c);
-}
-
-__device__ __forceinline__ void wave_sum4(float a0, float a1, float a2, float a3, float r[4])
-{
-    // lanes 32..63 of the first operand swap with lanes 0..31 of the second
-    const auto s02 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a0), __float_as_uint(a2), false, false);
-    const auto s13 = __builtin_amdgcn_permlane32_swap(__float_as_uint(a1), __float_as_uint(a3), false, false);
-    const float k02 = __uint_as_float(s02[0]) + __uint_as_float(s02[1]);  // rows 0,1: a0   rows 2,3: a2
-    const float k13 = __uint_as_float(s13[0]) + __uint_as_float(s13[1]);  // rows 0,1: a1   rows 2,3: a3
-    // odd rows of the first operand swap with even rows of the second
-    const auto sr = __builtin_amdgcn_permlane16_swap(__float_as_uint(k02), __float_as_uint(k13), false, false);
-    float v = __uint_as_float(sr[0]) + __uint_as_float(sr[1]);            // row q: value q
-    v = dpp_add<0xB1>(v);   // quad_perm [1,0,3,2]
-    v = dpp_add<0x4E>(v);   // quad_perm [2,3,0,1]
-    v = dpp_add<0x141>(v);  // row_half_mirror
-    v = dpp_add<0x140>(v);  // row_mirror
-    r[0] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-    r[1] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-    r[2] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-    r[3] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
 }
 
 }  // namespace l355
