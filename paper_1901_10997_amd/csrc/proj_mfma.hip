@@ -35,6 +35,13 @@ __device__ __forceinline__ bool tile_of_block(int pid, int gm, int gn, int& tm, 
     return true;
 }
 
+// Permutation of the 16-byte chunks of an unpadded LDS row r holding `ch` chunks (4: 64-byte rows, 8: 128-byte
+// rows).  A 16-byte read by 16 consecutive rows at the same logical chunk then covers all 64 four-byte banks
+// (256 bytes): with 128-byte rows bit 0 of r already selects the half of the bank space, with 64-byte rows bits
+// 0-1 select the quarter, and the row bits above them are folded into the chunk position.  Measured at the full
+// LDS read rate (256 bytes per cycle); folding in bits 1-2 of 64-byte rows instead reads at half of it.
+__device__ __forceinline__ constexpr int chunk_swizzle(int r, int ch) { return ch == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
     return (uint32_t)f32_to_bf16_bits(lo) | ((uint32_t)f32_to_bf16_bits(hi) << 16);
@@ -44,6 +51,55 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 // bf16 operands, fp32 accumulation.  X_F32: the operand X is stored as fp32 and rounded to bf16 on the way in.
 // Requires K % 8 == 0 (16-byte chunks of bf16 along k).
 // ---------------------------------------------------------------------------------------------------------
+// Epilogue shared by the MFMA projections: P = acc + bias for a wave's TM x TN grid of 32x32 tiles whose first
+// element is (mw0, nw0).  Accumulator register v of lane l is element (8*(v/4) + 4*(l/32) + v%4, l%32) of its
+// tile.  The bias is added to every accumulator before the first store, outside any bounds check: stores count on
+// the same outstanding-memory counter as loads, so a wait for the bias placed inside each guarded store would
+// also wait for the previous store to be acknowledged and serialise the whole epilogue.  Interior tiles take a
+// path with no per-row checks.
+template <int TM, int TN>
+__device__ __forceinline__ void store_acc_tiles(f32x16 (&acc)[TM][TN], const float* __restrict__ bias,
+                                                float* __restrict__ P, int M, int N, int mw0, int nw0, int fr, int fk)
+{
+    float bn[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = nw0 + j * 32 + fr;
+        bn[j] = bias[n < N ? n : N - 1];
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] += bn[j];
+    if (mw0 + TM * 32 <= M && nw0 + TN * 32 <= N) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                float* dst = P + (size_t)(mw0 + i * 32 + 4 * fk) * N + (nw0 + j * 32 + fr);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) dst[(size_t)(8 * (v >> 2) + (v & 3)) * N] = acc[i][j][v];
+            }
+    } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = nw0 + j * 32 + fr;
+            if (n >= N) continue;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int mb = mw0 + i * 32 + 4 * fk;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = mb + 8 * (v >> 2) + (v & 3);
+                    if (m < M) P[(size_t)m * N + n] = acc[i][j][v];
+                }
+            }
+        }
+    }
+}
+
 template <int TM, int TN, bool X_F32>
 __global__ __launch_bounds__(256, 2) void proj_mfma_bf16_kernel(const void* __restrict__ Xv, int ldx,
                                                              const uint16_t* __restrict__ W, const float* __restrict__ bias,
@@ -143,41 +199,23 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_bf16_kernel(const void* __re
         if (kt + 1 < nslab) store_slab(buf ^ 1);
         __syncthreads();
     }
-    // epilogue: accumulator register v of lane l is element (8*(v/4) + 4*(l/32) + v%4, l%32) of its 32x32 tile
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + (wn * TN + j) * 32 + fr;
-        if (n >= N) continue;
-        const float bn = bias[n];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mb = m0 + (wm * TM + i) * 32 + 4 * fk;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mb + 8 * (v >> 2) + (v & 3);
-                if (m < M) P[(size_t)m * N + n] = acc[i][j][v] + bn;
-            }
-        }
-    }
+    store_acc_tiles<TM, TN>(acc, bias, P, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, fr, fk);
 }
 
 // ---------------------------------------------------------------------------------------------------------
 // bf16 operands, slabs brought from global memory straight into LDS (no register staging), double-buffered.
 // A direct load writes the 16 bytes of lane i at LDS offset base + 16*i, so one wave instruction fills 16 rows
 // of 64 bytes; rows are not padded.  Bank conflicts are avoided by permuting the four 16-byte chunks of a row:
-// chunk kc of row r is kept at position kc ^ ((r >> 1) & 3), both when a lane picks the global chunk that belongs
-// at its LDS position and when a fragment is read.  Needs K % 32 == 0; rows beyond M / N are clamped to the
+// chunk kc of row r is kept at position kc ^ chunk_swizzle(r, 4), both when a lane picks the global chunk that
+// belongs at its LDS position and when a fragment is read.  Needs K % 32 == 0; rows beyond M / N are clamped to the
 // last valid row (their products are never stored).
 // ---------------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void wait_vmcnt(int n)
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
 {
     // s_waitcnt on gfx9: vmcnt = bits [3:0] and [15:14]; expcnt [6:4] and lgkmcnt [11:8] left unconstrained
-    if (n <= 0) __builtin_amdgcn_s_waitcnt(0x0F70);
-    else if (n == 4) __builtin_amdgcn_s_waitcnt(0x0F74);
-    else if (n == 6) __builtin_amdgcn_s_waitcnt(0x0F76);
-    else if (n == 8) __builtin_amdgcn_s_waitcnt(0x0F78);
-    else if (n == 12) __builtin_amdgcn_s_waitcnt(0x0F7C);
-    else __builtin_amdgcn_s_waitcnt(0x0F70);
+    static_assert(N >= 0 && N < 64, "six-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 template <int TM, int TN>
@@ -213,7 +251,7 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_bf16_dlds_kernel(const uint1
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
         const int row = (wave * AI + i) * 16 + (lane >> 2);   // row inside the X slab
-        const int kc = (lane & 3) ^ ((row >> 1) & 3);
+        const int kc = (lane & 3) ^ chunk_swizzle(row, 4);
         int m = m0 + row;
         if (m > M - 1) m = M - 1;
         asrc[i] = X + (size_t)m * ldx + 8 * kc;
@@ -221,7 +259,7 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_bf16_dlds_kernel(const uint1
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
         const int row = (wave * BI + i) * 16 + (lane >> 2);
-        const int kc = (lane & 3) ^ ((row >> 1) & 3);
+        const int kc = (lane & 3) ^ chunk_swizzle(row, 4);
         int n = n0 + row;
         if (n > N - 1) n = N - 1;
         bsrc[i] = W + (size_t)n * K + 8 * kc;
@@ -246,7 +284,7 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_bf16_dlds_kernel(const uint1
     for (int kt = 0; kt < nslab; ++kt) {
         // slab kt must have landed; the compiler also waits for every outstanding direct load before LDS is
         // read, so the prefetch distance is one slab and latency is hidden by the other resident workgroups
-        wait_vmcnt(0);
+        wait_vmcnt<0>();
         __syncthreads();
         if (kt + 1 < nslab) issue_slab(kt + 1);      // refills the buffer every wave finished reading before the barrier
         const unsigned char* As = smem + (size_t)(kt % NST) * STAGE;
@@ -257,13 +295,13 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_bf16_dlds_kernel(const uint1
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int rr = (wm * TM + i) * 32 + fr;
-                const int pos = (ks * 2 + fk) ^ ((rr >> 1) & 3);
+                const int pos = (ks * 2 + fk) ^ chunk_swizzle(rr, 4);
                 fa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(As + (size_t)rr * ROWB + pos * 16));
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int rr = (wn * TN + j) * 32 + fr;
-                const int pos = (ks * 2 + fk) ^ ((rr >> 1) & 3);
+                const int pos = (ks * 2 + fk) ^ chunk_swizzle(rr, 4);
                 fb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(Bs + (size_t)rr * ROWB + pos * 16));
             }
 #pragma unroll
@@ -273,34 +311,20 @@ __global__ __launch_bounds__(256, 2) void proj_mfma_bf16_dlds_kernel(const uint1
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
         }
     }
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + (wn * TN + j) * 32 + fr;
-        if (n >= N) continue;
-        const float bn = bias[n];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mb = m0 + (wm * TM + i) * 32 + 4 * fk;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mb + 8 * (v >> 2) + (v & 3);
-                if (m < M) P[(size_t)m * N + n] = acc[i][j][v] + bn;
-            }
-        }
-    }
+    store_acc_tiles<TM, TN>(acc, bias, P, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, fr, fk);
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Large-M bf16 variant: 256 x 256 tile, eight waves (2 x 4, wave tile 128 x 64), 32-wide K slabs brought straight
-// into LDS through a four-deep ring (128 KB of LDS, one workgroup per compute unit), so that three slabs are
-// in flight while one is consumed: the L2 round trip (about 1.3 us under load) is longer than the MFMA work of
-// one slab.  Fragment reads are issued as explicit ds_read_b128 instructions: the compiler cannot see that an
+// Large-M bf16 variant: 256 x 256 tile, eight waves (2 x 4, wave tile 128 x 64), K slabs brought straight into
+// LDS through a ring of 128 KB (one workgroup per compute unit): four 32-wide slabs, three in flight while one is
+// consumed, or two 64-wide slabs whose rows are whole 128-byte lines (a 32-wide slab uses half of every line it
+// touches, and the other half has left the 32 KB vector cache by the time the next slab asks for it).  Fragment reads are issued as explicit ds_read_b128 instructions: the compiler cannot see that an
 // LDS read depends on a particular direct-to-LDS load and would otherwise wait for ALL outstanding loads before
 // every read, which collapses the ring to depth one.  The dependency is kept by hand instead: a counted
 // s_waitcnt on the vector-memory counter (slab kt has landed once only the loads of the younger slabs are
 // outstanding), then the workgroup barrier, then the reads.
-// Chunk kc of row r lives at position kc ^ ((r >> 1) & 3) of its 64-byte row (bank-conflict-free 16-byte reads).
-// Needs K % 32 == 0.
+// Chunk kc of row r lives at position kc ^ chunk_swizzle(r, chunks per row) of its row (bank-conflict-free
+// 16-byte reads).  Needs K % BK == 0.
 // ---------------------------------------------------------------------------------------------------------
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
@@ -311,27 +335,60 @@ __device__ __forceinline__ u32x4 lds_read_b128(unsigned addr)
     return v;
 }
 
-template <int NWN>  // waves along n: 4 -> eight waves of 128 x 64, 2 -> four waves of 128 x 128
-__global__ __launch_bounds__(128 * NWN) void proj_mfma_bf16_big_kernel(const uint16_t* __restrict__ X, int ldx,
+template <int BK>  // K extent of a slab: 32 (four-deep ring) or 64 (two-deep ring of whole 128-byte lines)
+__global__ __launch_bounds__(512) void proj_mfma_bf16_big_kernel(const uint16_t* __restrict__ X, int ldx,
                                                                  const uint16_t* __restrict__ W,
                                                                  const float* __restrict__ bias, float* __restrict__ P,
-                                                                 int M, int N, int K, int gm, int gn)
+                                                                 int M, int N, int K, int gm, int gn, int npid)
 {
-    constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
-    constexpr int NW = 2 * NWN;                           // waves per workgroup
-    constexpr int TM = 4, TN = 8 / NWN;                   // 32x32 tiles per wave
-    constexpr int ROWB = BK * 2;                          // 64 bytes per LDS row
-    constexpr int STAGE = (BM + BN) * ROWB;               // 32 KB
-    constexpr int LI = (BM + BN) / 16 / NW;               // direct-load instructions per wave and slab (16 rows each)
+    constexpr int BM = 256, BN = 256;
+    constexpr int NWN = 4, NW = 8;                        // eight waves, 2 (m) x 4 (n)
+    constexpr int TM = 4, TN = 2;                         // 32x32 tiles per wave: wave tile 128 x 64
+    constexpr int ROWB = BK * 2;                          // bytes per LDS row
+    constexpr int CH = ROWB / 16;                         // 16-byte chunks per row
+    constexpr int KS = BK / 16;                           // k16 steps per slab
+    constexpr int STAGE = (BM + BN) * ROWB;               // 32 or 64 KB
+    constexpr int NST = 131072 / STAGE;                   // ring depth: 4 or 2
+    constexpr int RPI = 1024 / ROWB;                      // rows covered by one direct-load instruction
+    constexpr int LI = (BM + BN) / RPI / NW;              // direct-load instructions per wave and slab
+    static_assert(BK == 32 || BK == 64, "slab extent");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-    int tile_m, tile_n;
-    if (!tile_of_block(blockIdx.x, gm, gn, tile_m, tile_n)) return;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / NWN, wn = wave % NWN;           // 2 x NWN waves: rows wm*128, cols wn*32*TN
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);   // same value, known to be wave-uniform
+    const int wm = wave / NWN, wn = wave % NWN;           // rows wm*128, cols wn*64
     const int fr = lane & 31, fk = lane >> 5;
+
+    // byte offsets of this lane's fragments inside a stage for the first k16 step; step ks flips chunk bits:
+    // chunk (2 ks + fk) ^ swizzle = ((fk ^ swizzle) ^ 2 ks), i.e. offset ^ (ks << 5)
+    unsigned offa[TM], offb[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int rr = (wm * TM + i) * 32 + fr;
+        offa[i] = (unsigned)(rr * ROWB + ((fk ^ chunk_swizzle(rr, CH)) * 16));
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int rr = (wn * TN + j) * 32 + fr;
+        offb[j] = (unsigned)(BM * ROWB + rr * ROWB + ((fk ^ chunk_swizzle(rr, CH)) * 16));
+    }
+    const int nslab = K / BK;
+    // slab `target` has landed once only the loads of the (at most NST - 2) younger slabs can still be outstanding
+    auto wait_slab = [&](int target) {
+        const int y = (nslab - 1 - target) < (NST - 2) ? (nslab - 1 - target) : (NST - 2);
+        if (NST == 4 && y == 2) wait_vmcnt<2 * LI>();
+        else if (NST == 4 && y == 1) wait_vmcnt<LI>();
+        else wait_vmcnt<0>();
+    };
+
+  // one workgroup per compute unit walks over its share of the tiles
+  for (int pid = blockIdx.x; pid < npid; pid += gridDim.x) {
+    int tile_m, tile_n;
+    if (!tile_of_block(pid, gm, gn, tile_m, tile_n)) continue;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    // every wave has finished reading the previous tile's last slab before the ring is refilled
+    if (pid != (int)blockIdx.x) __builtin_amdgcn_s_barrier();
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -341,103 +398,115 @@ __global__ __launch_bounds__(128 * NWN) void proj_mfma_bf16_big_kernel(const uin
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // direct loads: instruction q (0..31) of a slab covers LDS rows 16q..16q+15 of the combined [X rows | W rows]
-    const uint16_t* src[LI];
+    // direct loads: instruction q of a slab covers LDS rows RPI*q .. RPI*q + RPI-1 of the combined [X rows | W rows];
+    // the CH lanes of a row fetch its chunks in swizzled order, so a row's lanes read one contiguous piece of a line
+    // (the whole 128-byte line when BK = 64).  A wave's 64 rows all belong to one operand: scalar base pointer
+    // plus one 32-bit element offset per instruction.
+    const bool wave_loads_x = wave_s * 64 < BM;
+    const uint16_t* opnd = wave_loads_x ? X + (size_t)m0 * ldx : W + (size_t)n0 * K;
+    const int opnd_ld = wave_loads_x ? ldx : K;
+    const int last_row = wave_loads_x ? (M - 1 - m0) : (N - 1 - n0);   // rows past the matrix re-read its last row
+    unsigned soff[LI];
 #pragma unroll
     for (int i = 0; i < LI; ++i) {
-        const int q = wave * LI + i;
-        const int row = q * 16 + (lane >> 2);             // 0..511: X rows then W rows
-        const int kc = (lane & 3) ^ ((row >> 1) & 3);
-        if (row < BM) {
-            int m = m0 + row;
-            if (m > M - 1) m = M - 1;
-            src[i] = X + (size_t)m * ldx + 8 * kc;
-        } else {
-            int n = n0 + row - BM;
-            if (n > N - 1) n = N - 1;
-            src[i] = W + (size_t)n * K + 8 * kc;
-        }
+        const int row = wave_s * 64 + i * RPI + lane / CH;   // 0..511: X rows then W rows
+        const int kc = (lane % CH) ^ chunk_swizzle(row, CH);
+        int r = wave_loads_x ? row : row - BM;
+        if (r > last_row) r = last_row;
+        soff[i] = (unsigned)(r * opnd_ld + 8 * kc);
     }
     auto issue_slab = [&](int kt) {
-        unsigned char* st = smem + (size_t)(kt % NST) * STAGE;
-        const size_t koff = (size_t)kt * BK;
+        unsigned char* st = smem + (size_t)(kt % NST) * STAGE + (size_t)wave_s * LI * 1024;
+        const uint16_t* from = opnd + (size_t)kt * BK;
 #pragma unroll
         for (int i = 0; i < LI; ++i)
-            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(src[i] + koff),
-                                             (void __attribute__((address_space(3)))*)(st + (size_t)(wave * LI + i) * 16 * ROWB),
-                                             16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(from + soff[i]),
+                                             (void __attribute__((address_space(3)))*)(st + (size_t)i * 1024), 16, 0, 0);
     };
-    // byte offsets of this lane's fragments inside a stage (two k16 steps per slab)
-    unsigned offa[2][TM], offb[2][TN];
+    // Two fragment register sets, software-pipelined inside the wave: the LDS reads of the next k16 step are in
+    // flight while the eight MFMAs of the current one execute, and the slab hand-over (counted wait on the
+    // direct loads, workgroup barrier, refill of the freed ring buffer) sits in front of a slab's last MFMA
+    // group, so the matrix pipe still has work queued while the wave waits there.
+    u32x4 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+    auto read_set0 = [&](unsigned st, int ks) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+        for (int i = 0; i < TM; ++i) fa0[i] = lds_read_b128(st + (offa[i] ^ (unsigned)(ks << 5)));
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int rr = (wm * TM + i) * 32 + fr;
-            offa[ks][i] = (unsigned)(rr * ROWB + (((ks * 2 + fk) ^ ((rr >> 1) & 3)) * 16));
-        }
+        for (int j = 0; j < TN; ++j) fb0[j] = lds_read_b128(st + (offb[j] ^ (unsigned)(ks << 5)));
+    };
+    auto read_set1 = [&](unsigned st, int ks) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int rr = (wn * TN + j) * 32 + fr;
-            offb[ks][j] = (unsigned)(BM * ROWB + rr * ROWB + (((ks * 2 + fk) ^ ((rr >> 1) & 3)) * 16));
-        }
-    }
+        for (int i = 0; i < TM; ++i) fa1[i] = lds_read_b128(st + (offa[i] ^ (unsigned)(ks << 5)));
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb1[j] = lds_read_b128(st + (offb[j] ^ (unsigned)(ks << 5)));
+    };
+    auto mfma_set0 = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa0[i]),
+                                                                   __builtin_bit_cast(bf16x8, fb0[j]), acc[i][j], 0, 0, 0);
+    };
+    auto mfma_set1 = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa1[i]),
+                                                                   __builtin_bit_cast(bf16x8, fb1[j]), acc[i][j], 0, 0, 0);
+    };
 
-    const int nslab = K / BK;
-    issue_slab(0);
-    if (nslab > 1) issue_slab(1);
-    if (nslab > 2) issue_slab(2);
+#pragma unroll
+    for (int q = 0; q < NST - 1; ++q)
+        if (q < nslab) issue_slab(q);
+    wait_slab(0);
+    // bare barrier: __syncthreads() carries a workgroup fence, for which the compiler drains every outstanding
+    // direct-to-LDS load; the ordering needed here is exactly the counted wait above plus the barrier
+    __builtin_amdgcn_s_barrier();
+    if (NST - 1 < nslab) issue_slab(NST - 1);
+    read_set0(lds0, 0);
     for (int kt = 0; kt < nslab; ++kt) {
-        // slab kt has landed once only the loads of slabs kt+1 and kt+2 (LI each) can still be outstanding
-        const int younger = (nslab - 1 - kt) < 2 ? (nslab - 1 - kt) : 2;
-        if (younger == 2) wait_vmcnt(2 * LI); else if (younger == 1) wait_vmcnt(LI); else wait_vmcnt(0);
-        // bare barrier: __syncthreads() carries a workgroup fence, for which the compiler drains every outstanding
-        // direct-to-LDS load; the ordering needed here is exactly the counted wait above plus the barrier
-        __builtin_amdgcn_s_barrier();
-        if (kt + 3 < nslab) issue_slab(kt + 3);          // refills the buffer consumed in iteration kt-1
         const unsigned st = lds0 + (unsigned)((kt % NST) * STAGE);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            u32x4 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = lds_read_b128(st + offa[ks][i]);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = lds_read_b128(st + offb[ks][j]);
-            // wait for the LDS reads; the fragments are operands of the wait so that no MFMA can move above it
-            if constexpr (TN == 2)
-                asm volatile("s_waitcnt lgkmcnt(0)"
-                             : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1])
+        for (int ks = 0; ks < KS - 1; ++ks) {
+            // LDS returns in order: all but the six youngest reads done = the current set is complete.  The
+            // fragments are operands of the wait so that no MFMA can move above it.
+            if ((ks & 1) == 0) {
+                read_set1(st, ks + 1);
+                asm volatile("s_waitcnt lgkmcnt(6)"
+                             : "+v"(fa0[0]), "+v"(fa0[1]), "+v"(fa0[2]), "+v"(fa0[3]), "+v"(fb0[0]), "+v"(fb0[1])
                              :
                              : "memory");
-            else
-                asm volatile("s_waitcnt lgkmcnt(0)"
-                             : "+v"(fa[0]), "+v"(fa[1]), "+v"(fa[2]), "+v"(fa[3]), "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]),
-                               "+v"(fb[3])
+                mfma_set0();
+            } else {
+                read_set0(st, ks + 1);
+                asm volatile("s_waitcnt lgkmcnt(6)"
+                             : "+v"(fa1[0]), "+v"(fa1[1]), "+v"(fa1[2]), "+v"(fa1[3]), "+v"(fb1[0]), "+v"(fb1[1])
                              :
                              : "memory");
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
-                                                                       __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + (wn * TN + j) * 32 + fr;
-        if (n >= N) continue;
-        const float bn = bias[n];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mb = m0 + (wm * TM + i) * 32 + 4 * fk;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mb + 8 * (v >> 2) + (v & 3);
-                if (m < M) P[(size_t)m * N + n] = acc[i][j][v] + bn;
+                mfma_set1();
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        // last step of the slab (set 1): once its reads have returned this wave is done with slab kt, so after
+        // the barrier below the slab's ring buffer may be refilled
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(fa1[0]), "+v"(fa1[1]), "+v"(fa1[2]), "+v"(fa1[3]), "+v"(fb1[0]), "+v"(fb1[1])
+                     :
+                     : "memory");
+        if (kt + 1 < nslab) {
+            wait_slab(kt + 1);
+            __builtin_amdgcn_s_barrier();
+            if (kt + NST < nslab) issue_slab(kt + NST);  // into the buffer of slab kt
+            read_set0(lds0 + (unsigned)(((kt + 1) % NST) * STAGE), 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_set1();
+        __builtin_amdgcn_sched_barrier(0);
     }
+    store_acc_tiles<TM, TN>(acc, bias, P, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, fr, fk);
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -541,21 +610,7 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
         if (kt + 1 < nslab) store_slab(buf ^ 1);
         __syncthreads();
     }
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + (wn * TN + j) * 32 + fr;
-        if (n >= N) continue;
-        const float bn = bias[n];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int mb = m0 + (wm * TM + i) * 32 + 4 * fk;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int m = mb + 8 * (v >> 2) + (v & 3);
-                if (m < M) P[(size_t)m * N + n] = acc[i][j][v] + bn;
-            }
-        }
-    }
+    store_acc_tiles<TM, TN>(acc, bias, P, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, fr, fk);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -671,16 +726,25 @@ static hipError_t launch_bf16_big(const uint16_t* X, int ldx, const uint16_t* W,
 {
     const int gm = (M + 255) / 256, gn = (N + 255) / 256;
     const int grid = ((gm * gn + kXcds - 1) / kXcds) * kXcds;
-    const size_t lds = 4 * (size_t)512 * 64;
-    // eight waves of 128 x 64 measured 1.4x faster than four waves of 128 x 128 (whose 256 accumulator registers
-    // leave one wave per SIMD and force accumulator/vector register shuffling)
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)proj_mfma_bf16_big_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    const size_t lds = 131072;
+    static int num_cus = 0;
+    if (num_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            return hipErrorInvalidDevice;
+        hipError_t e = hipFuncSetAttribute((const void*)proj_mfma_bf16_big_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        e = hipFuncSetAttribute((const void*)proj_mfma_bf16_big_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        num_cus = (n / kXcds) * kXcds;
+        if (num_cus == 0) num_cus = kXcds;
     }
-    hipLaunchKernelGGL(proj_mfma_bf16_big_kernel<4>, dim3(grid), dim3(512), lds, s, X, ldx, W, bias, P, M, N, K, gm, gn);
+    const int blocks = grid < num_cus ? grid : num_cus;
+    if (K % 64 == 0)
+        hipLaunchKernelGGL(proj_mfma_bf16_big_kernel<64>, dim3(blocks), dim3(512), lds, s, X, ldx, W, bias, P, M, N, K, gm, gn, grid);
+    else
+        hipLaunchKernelGGL(proj_mfma_bf16_big_kernel<32>, dim3(blocks), dim3(512), lds, s, X, ldx, W, bias, P, M, N, K, gm, gn, grid);
     return hipGetLastError();
 }
 

@@ -4,10 +4,13 @@
 //   R[b][n] = sum_k hb[b][k] * W_h[n][k]     (hb = h_{t-1} rounded to bf16, W_h packed rows n = 4*unit + gate)
 //   a = P[t][b][n] + R[b][n];  f,i,o = sigmoid, g = tanh;  c <- f*c + i*g;  h = o*tanh(c)
 //
-// A 256-thread workgroup owns a 64 (batch) x 64 (packed rows = 16 hidden units) tile.  The step is short and
-// latency-bound, so there is no LDS pipeline: the four waves split K, each streams its operand fragments from
+// A workgroup of NW waves owns a 64 (batch) x 64 (packed rows = 16 hidden units) tile.  The step is short and
+// latency-bound, so there is no LDS pipeline: the NW waves split K, each streams its operand fragments from
 // global memory straight into registers (every lane reads 64 contiguous bytes of its row per 64-wide k block,
-// so a pair of lanes consumes a whole 128-byte line once), and the four partial tiles are summed through LDS.
+// so a pair of lanes consumes a whole 128-byte line once), and the NW partial tiles are summed through LDS.
+// With eight waves and H = 1024 a wave's whole share of K is two blocks, both requested before the first MFMA,
+// so the kernel pays one operand round trip; the epilogue's P and c values are requested before the product
+// as well, which hides their (HBM) latency behind it.
 // Which 8 k a lane contributes to which MFMA is the same for both operands, which is all a sum over k needs.
 #include "common.h"
 #include "device_math.h"
@@ -17,10 +20,13 @@ namespace l355 {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-__global__ __launch_bounds__(256) void step_mfma_bf16_kernel(StepMfmaArgs a)
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void step_mfma_bf16_kernel(StepMfmaArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) float part[];  // [4][64][68]
+    extern __shared__ __attribute__((aligned(16))) float part[];  // [NW][64][68]
     constexpr int LDP = 68;
+    constexpr int NT = 64 * NW;
+    constexpr int PAIRS = 1024 / NT;  // (batch row, hidden unit) pairs each thread finishes
     const int gm = (a.B + 63) / 64, gn = (4 * a.H) / 64;
     const int nblk = gm * gn;
     const int per_xcd = (nblk + 7) / 8;
@@ -30,7 +36,20 @@ __global__ __launch_bounds__(256) void step_mfma_bf16_kernel(StepMfmaArgs a)
     const int m0 = tile_m * 64, n0 = tile_n * 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, fk = lane >> 5;
-    const int K = a.H, Kq = K / 4;
+    const int K = a.H, Kq = K / NW;
+
+    // epilogue operands, requested first
+    float4 pre[PAIRS];
+    float cold[PAIRS];
+#pragma unroll
+    for (int r = 0; r < PAIRS; ++r) {
+        const int p = tid + NT * r;
+        int b = m0 + (p >> 4);
+        if (b > a.B - 1) b = a.B - 1;
+        const int jn = n0 + 4 * (p & 15);
+        pre[r] = *reinterpret_cast<const float4*>(a.P + ((size_t)a.t * a.B + b) * (4 * (size_t)a.H) + jn);
+        cold[r] = a.c[(size_t)b * a.H + (jn >> 2)];
+    }
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -97,16 +116,16 @@ __global__ __launch_bounds__(256) void step_mfma_bf16_kernel(StepMfmaArgs a)
     __syncthreads();
     // epilogue: each thread finishes four (batch row, hidden unit) pairs
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int p = tid + 256 * r;
+    for (int r = 0; r < PAIRS; ++r) {
+        const int p = tid + NT * r;
         const int m = p >> 4, u = p & 15;
         const int b = m0 + m;
         if (b >= a.B) continue;
         const int jn = n0 + 4 * u;       // first packed row of the unit
         const int j = jn >> 2;           // hidden unit
-        float4 sum = *reinterpret_cast<const float4*>(a.P + ((size_t)a.t * a.B + b) * (4 * (size_t)a.H) + jn);
+        float4 sum = pre[r];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < NW; ++w) {
             const float4 q = *reinterpret_cast<const float4*>(part + ((size_t)w * 64 + m) * LDP + 4 * u);
             sum.x += q.x;
             sum.y += q.y;
@@ -115,7 +134,7 @@ __global__ __launch_bounds__(256) void step_mfma_bf16_kernel(StepMfmaArgs a)
         }
         const float f = sigmoidf_fast(sum.x), ig = sigmoidf_fast(sum.y), o = sigmoidf_fast(sum.z), g = tanhf_fast(sum.w);
         const size_t ci = (size_t)b * a.H + j;
-        const float cn = fmaf(f, a.c[ci], ig * g);
+        const float cn = fmaf(f, cold[r], ig * g);
         const float hn = o * tanhf_fast(cn);
         a.c[ci] = cn;
         a.y_t[(size_t)b * a.y_ld + j] = hn;
@@ -146,14 +165,24 @@ hipError_t launch_step_mfma_bf16(const StepMfmaArgs& a, hipStream_t s)
     if (!step_mfma_supported(a.B, a.H)) return hipErrorInvalidValue;
     const int gm = (a.B + 63) / 64, gn = (4 * a.H) / 64;
     const int grid = ((gm * gn + 7) / 8) * 8;
-    const size_t lds = 4 * 64 * 68 * sizeof(float);
+    // eight waves when K divides into whole 64-wide blocks per wave and the grid does not need several
+    // workgroups per compute unit to fill the device
+    const bool wide = a.H % 512 == 0 && grid <= 512;
+    const size_t lds = (size_t)(wide ? 8 : 4) * 64 * 68 * sizeof(float);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)step_mfma_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute((const void*)step_mfma_bf16_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           4 * 64 * 68 * (int)sizeof(float));
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void*)step_mfma_bf16_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                8 * 64 * 68 * (int)sizeof(float));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(step_mfma_bf16_kernel, dim3(grid), dim3(256), lds, s, a);
+    if (wide)
+        hipLaunchKernelGGL(step_mfma_bf16_kernel<8>, dim3(grid), dim3(512), lds, s, a);
+    else
+        hipLaunchKernelGGL(step_mfma_bf16_kernel<4>, dim3(grid), dim3(256), lds, s, a);
     return hipGetLastError();
 }
 

@@ -90,6 +90,15 @@ def test_bf16_matrix_core_step(Bn):
     assert "mfma" in desc
 
 
+@pytest.mark.parametrize("D", [192, 96, 320])
+def test_bf16_large_projection_ragged_tiles(D):
+    """bf16 projections with T*B >= 2048 rows and 4H >= 512 columns take the 256 x 256 persistent-tile kernel
+    (64-wide K slabs when D % 64 == 0, 32-wide otherwise); 2100 rows and 544 columns leave partial tiles on
+    both axes, and more tiles than one pass over the device's compute units is not needed for that."""
+    case = inputs.make_case(_wl(87, 1, False, D, 136, 7, 300, dtype="bf16", a=0.1), k=D, random_state=True)
+    check_case(case, DENSE, PAUTO)
+
+
 def test_empty_sequences_are_noops():
     m = B.Lstm(1, 4, 4)
     case = inputs.make_case(_wl(93, 1, False, 4, 4, 2, 1), 0)
