@@ -91,6 +91,30 @@ bool step_mfma_supported(int B, int H);
 hipError_t launch_step_mfma_bf16(const StepMfmaArgs& a, hipStream_t s);
 hipError_t launch_f32_to_bf16(const float* src, int src_ld, uint16_t* dst, int dst_ld, int rows, int cols, hipStream_t s);
 
+// bf16 dense recurrence at large batch with the time loop on the device (one launch per layer and direction).
+struct PersistMfmaArgs {
+    const float* P;            // [T*B][4H]
+    const uint16_t* Wh;        // [4H][H] bf16, packed rows
+    const float* c0;           // [B][H] or nullptr
+    float* y;                  // h_t fp32 -> y[(t*B + b)*y_ld + j], or nullptr
+    int y_ld;
+    uint16_t* yb;              // h_t bf16 -> yb[(t*B + b)*yb_ld + j], or nullptr
+    int yb_ld;
+    float* hT;
+    float* cT;
+    uint16_t* hx;              // two exchange buffers of H * Bp bf16 each, Bp = B rounded up to 64
+    unsigned* flags;           // one per tile, [ceil(B/64)][4H/64]; every value below tag_base + 1
+    unsigned tag_base;         // step s publishes tag_base + s + 1
+    int* timeout_flag;
+    unsigned spin_limit;
+    int has_h0;                // exchange buffer 0 holds h0 (set by the launcher)
+    int T, B, H, reverse;
+};
+bool persist_mfma_supported(int B, int H);
+size_t persist_mfma_exchange_bytes(int B, int H);
+size_t persist_mfma_flag_count(int B, int H);
+hipError_t launch_persist_mfma_bf16(const PersistMfmaArgs& a, const float* h0, bool cooperative, hipStream_t s);
+
 // Row-compressed step for small batches: one or both directions of a layer per launch (H <= 2048).
 bool step_csr_pair_supported(int H, int slots);
 hipError_t launch_step_csr_pair(const StepArgs* a, const float* const* ell_val, const uint16_t* const* ell_col,

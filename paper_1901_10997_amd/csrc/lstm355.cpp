@@ -325,7 +325,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
 
 // ---- workspace carve-up --------------------------------------------------------------------------------
 struct Workspace {
-    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, slot_off, total;
+    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, slot_off, hx_off, mflag_off, total;
 };
 static Workspace carve(const lstm_t* m, int T, int B)
 {
@@ -359,6 +359,14 @@ static Workspace carve(const lstm_t* m, int T, int B)
     // tagged exchange slots of the small-batch persistent recurrence: [Dn][2][B][H]
     w.slot_off = off;
     if (B >= 2) off += align256((size_t)m->Dn * 2 * B * H * sizeof(unsigned long long));
+    // bf16 large-batch persistent recurrence: two exchange buffers of h_t and one flag per tile
+    w.hx_off = off;
+    w.mflag_off = off;
+    if (m->dtype == LSTM_BF16 && persist_mfma_supported(B, (int)H)) {
+        off += align256(persist_mfma_exchange_bytes(B, (int)H));
+        w.mflag_off = off;
+        off += align256(persist_mfma_flag_count(B, (int)H) * sizeof(unsigned));
+    }
     w.total = off;
     return w;
 }
@@ -461,6 +469,10 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
     unsigned long long* bslots = (unsigned long long*)(base + ws.slot_off);
     bool bslots_clean = false;   // zeroed during this forward (tags then restart at 1)
     unsigned btag = 0;
+    uint16_t* hx = (uint16_t*)(base + ws.hx_off);
+    unsigned* mflags = (unsigned*)(base + ws.mflag_off);
+    bool mflags_clean = false;   // zeroed during this forward (tags then restart at 1)
+    unsigned mtag = 0;
     bool prev_has_bf16 = false;  // the layer below left a bf16 copy of its hidden sequence in Ybf[(l-1)&1]
     m->last_plan.clear();
 
@@ -566,8 +578,45 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             }
         }
         // ---- recurrence, bf16 dense at large batch: one matrix-core launch per step with the cell update fused
-        bool mfma_ok = bf16 && step_mfma_supported(B, H);
-        for (int d = 0; d < Dn; ++d) mfma_ok = mfma_ok && mode[d] == 0 && !m->ld[(size_t)l * Dn + d].wh.compressed;
+        bool dense_bf16 = bf16;
+        for (int d = 0; d < Dn; ++d) dense_bf16 = dense_bf16 && mode[d] == 0 && !m->ld[(size_t)l * Dn + d].wh.compressed;
+        const bool mfma_ok = dense_bf16 && step_mfma_supported(B, H);
+        if (dense_bf16 && m->plan != LSTM_PLAN_STEPWISE && persist_mfma_supported(B, H)) {
+            // time loop on the device: W_h stays in registers, h_t travels through flagged exchange buffers
+            uint16_t* Yb = Ybf[l & 1];
+            if (!mflags_clean) {
+                HIP_TRY(m, launch_fill_f32((float*)mflags, persist_mfma_flag_count(B, H), 0.0f, s));
+                mflags_clean = true;
+                mtag = 0;
+            }
+            for (int d = 0; d < Dn; ++d) {
+                const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                const size_t n = (size_t)l * Dn + d;
+                ProfSpan span(m, s, 1);
+                PersistMfmaArgs a{};
+                a.P = P[d];
+                a.Wh = (const uint16_t*)w.wh.dense;
+                a.c0 = c0 ? c0 + n * B * H : nullptr;
+                a.y = Yout + (size_t)d * H;
+                a.y_ld = y_ld;
+                a.yb = Yb + (size_t)d * H;
+                a.yb_ld = y_ld;
+                a.hT = hT ? hT + n * B * H : nullptr;
+                a.cT = cT ? cT + n * B * H : nullptr;
+                a.hx = hx;
+                a.flags = mflags;
+                a.tag_base = mtag;
+                a.timeout_flag = m->timeout_flag;
+                a.spin_limit = m->spin_limit;
+                a.T = T; a.B = B; a.H = H; a.reverse = d;
+                mtag += (unsigned)T;
+                std::snprintf(tag, sizeof tag, "l%d.d%d:proj=dense,rec=persist-mfma-bf16;", l, d);
+                m->last_plan += tag;
+                HIP_TRY(m, launch_persist_mfma_bf16(a, h0 ? h0 + n * B * H : nullptr, m->cooperative != 0, s));
+            }
+            prev_has_bf16 = true;
+            continue;
+        }
         if (mfma_ok) {
             uint16_t* Yb = Ybf[l & 1];
             for (int d = 0; d < Dn; ++d) {

@@ -1,0 +1,269 @@
+// Recurrence of a bf16 dense layer at large batch with the time loop on the device (paper Section 4, cell
+// equations; Section 5.1 for the stack this serves).  One launch per (layer, direction).
+//
+//   R[b][n] = sum_k hb[b][k] * W_h[n][k]      (hb = h_{t-1} rounded to bf16, W_h packed rows n = 4*unit + gate)
+//   a = P[t][b][n] + R[b][n];  f,i,o = sigmoid, g = tanh;  c <- f*c + i*g;  h = o*tanh(c)
+//
+// A 512-thread workgroup owns a 64 (batch) x 64 (packed rows = 16 hidden units) tile for the whole sequence, one
+// workgroup per compute unit.  Its eight waves split K; each wave's slice of W_h (64 rows x H/8) stays in
+// registers as MFMA operand fragments for all T steps, and each thread keeps the cell state of its two
+// (batch row, unit) pairs in registers.  What a launch per step re-reads from memory every step (W_h: the L2
+// does not keep it across launches) is read once.
+//
+// Hidden-state exchange.  h_t (B x H bf16, 512 KB at B = 256, H = 1024) is too large for the tagged 8-byte slots
+// the small-batch kernels use, so data and readiness travel separately:
+//   producer  the tile's 64 x 16 block of h_t is stored as one contiguous 2 KB piece of a [H/16][Bp][16] buffer
+//             with device-scope write-through stores; once the wave's stores have been acknowledged
+//             (outstanding-memory counter at zero) and the workgroup has met at a barrier, one thread publishes
+//             the step number in the tile's flag, again with a device-scope store.
+//   consumer  one wave polls the flags of the tiles that produce its batch rows (device-scope loads, bounded),
+//             then executes a device-scope acquire fence, which drops stale lines of the exchange buffer from
+//             this compute unit's vector cache and this XCD's L2; after a workgroup barrier every wave reads
+//             its operand fragments with ordinary cached loads, so the 32 compute units of an XCD share one
+//             fetch of each line.
+// Two exchange buffers alternate: h_{t+1} can only be written after every tile has published h_t, which each
+// did after it had finished reading h_{t-1} from the buffer h_{t+1} goes to.
+// Flags carry monotonically growing tags, so they are never cleared between steps or launches of one forward.
+// Every wait is bounded; an expired wait raises the timeout flag and the kernel runs to its end.
+#include "common.h"
+#include "device_math.h"
+
+namespace l355 {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+namespace {
+
+int g_num_cu_pm = 0;
+int num_cu_pm()
+{
+    if (g_num_cu_pm == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            g_num_cu_pm = n;
+        if (g_num_cu_pm <= 0) g_num_cu_pm = 256;
+    }
+    return g_num_cu_pm;
+}
+
+}  // namespace
+
+template <int KS>  // k16 steps of a wave's K slice: H = 128 * KS
+__global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) float part[];  // [8][64][68]
+    constexpr int LDP = 68;
+    constexpr int NW = 8, NT = 512, PAIRS = 2;
+    const int gm = (a.B + 63) / 64, gn = (4 * a.H) / 64;
+    const int nblk = gm * gn;
+    const int per_xcd = (nblk + 7) / 8;
+    const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (logical >= nblk) return;                               // padding ids take no part in the exchange
+    const int tile_n = logical / gm, tile_m = logical % gm;    // tiles that share a W_h panel stay on one XCD
+    const int m0 = tile_m * 64, n0 = tile_n * 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 31, fk = lane >> 5;
+    const int H = a.H, Bp = gm * 64;
+    const int kbase = wave * (H / NW);
+
+    // W_h fragments of this wave: rows n0 + 32 j + fr, k = kbase + 16 s + 8 fk .. + 8
+    uint4 fb[2][KS];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            fb[j][s] = *reinterpret_cast<const uint4*>(a.Wh + (size_t)(n0 + j * 32 + fr) * H + kbase + 16 * s + 8 * fk);
+
+    // this thread's (batch row, unit) pairs
+    int pb[PAIRS], pu[PAIRS];
+    float c[PAIRS];
+#pragma unroll
+    for (int r = 0; r < PAIRS; ++r) {
+        const int p = tid + NT * r;
+        pb[r] = m0 + (p >> 4);
+        pu[r] = p & 15;
+        const int bc = pb[r] < a.B ? pb[r] : a.B - 1;
+        c[r] = a.c0 ? a.c0[(size_t)bc * H + (n0 >> 2) + pu[r]] : 0.0f;
+    }
+    // operand offsets (in bf16 elements) inside an exchange buffer: unit block kbase/16 + s, row m0 + 32 i + fr
+    const size_t xbuf = (size_t)H * Bp;                        // elements per exchange buffer
+    unsigned aoff[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) aoff[i] = (unsigned)(((kbase >> 4) * Bp + m0 + i * 32 + fr) * 16 + 8 * fk);
+    unsigned* const myflag = a.flags + (size_t)tile_m * gn + tile_n;
+    const unsigned* const pollflag = a.flags + (size_t)tile_m * gn + (lane < gn ? lane : gn - 1);
+
+    for (int s = 0; s < a.T; ++s) {
+        const int t = a.reverse ? a.T - 1 - s : s;
+        // epilogue operand, requested first
+        float4 pre[PAIRS];
+#pragma unroll
+        for (int r = 0; r < PAIRS; ++r) {
+            const int bc = pb[r] < a.B ? pb[r] : a.B - 1;
+            pre[r] = *reinterpret_cast<const float4*>(a.P + ((size_t)t * a.B + bc) * (4 * (size_t)H) + n0 + 4 * pu[r]);
+        }
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+        if (s > 0 || a.has_h0) {
+            if (s > 0) {
+                if (wave == 0) {
+                    const unsigned want = a.tag_base + (unsigned)s;
+                    unsigned spins = 0;
+                    while (__hip_atomic_load(pollflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want) {
+                        if (++spins > a.spin_limit) {
+                            __hip_atomic_store(a.timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        if ((spins & 255u) == 0 &&
+                            __hip_atomic_load(a.timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+                            break;
+                    }
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                }
+                __syncthreads();
+            }
+            const uint16_t* hx = a.hx + (size_t)(s & 1) * xbuf;
+            uint4 fa[2][KS];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int q = 0; q < KS; ++q)
+                    fa[i][q] = *reinterpret_cast<const uint4*>(hx + aoff[i] + (size_t)q * Bp * 16);
+#pragma unroll
+            for (int q = 0; q < KS; ++q)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][q]),
+                                                                           __builtin_bit_cast(bf16x8, fb[j][q]),
+                                                                           acc[i][j], 0, 0, 0);
+        }
+        // partial tiles -> LDS.  Accumulator register v of lane l is element (8*(v/4) + 4*(l/32) + v%4, l%32).
+        float* mine = part + (size_t)wave * 64 * LDP;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int m = i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
+                    mine[m * LDP + j * 32 + fr] = acc[i][j][v];
+                }
+        __syncthreads();
+        uint16_t* hxo = a.hx + (size_t)((s + 1) & 1) * xbuf;
+        const bool last = (s == a.T - 1);
+#pragma unroll
+        for (int r = 0; r < PAIRS; ++r) {
+            const int m = pb[r] - m0, u = pu[r];
+            float4 sum = pre[r];
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float4 q = *reinterpret_cast<const float4*>(part + ((size_t)w * 64 + m) * LDP + 4 * u);
+                sum.x += q.x;
+                sum.y += q.y;
+                sum.z += q.z;
+                sum.w += q.w;
+            }
+            const float f = sigmoidf_fast(sum.x), ig = sigmoidf_fast(sum.y), o = sigmoidf_fast(sum.z), g = tanhf_fast(sum.w);
+            const float cn = fmaf(f, c[r], ig * g);
+            const float hn = o * tanhf_fast(cn);
+            c[r] = cn;
+            // two neighbouring units per 32-bit word of the exchange buffer (rows beyond the batch included: they
+            // are only ever multiplied into accumulator rows that are never stored)
+            const unsigned hbits = f32_to_bf16_bits(hn);
+            const unsigned other = (unsigned)__builtin_amdgcn_update_dpp(0, (int)hbits, 0xB1, 0xF, 0xF, true);
+            if ((u & 1) == 0 && !last)
+                __hip_atomic_store(reinterpret_cast<unsigned*>(hxo + ((size_t)tile_n * Bp + pb[r]) * 16 + u),
+                                   hbits | (other << 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (pb[r] < a.B) {
+                const int j = (n0 >> 2) + u;
+                const size_t row = (size_t)t * a.B + pb[r];
+                if (a.y) a.y[row * a.y_ld + j] = hn;
+                if (a.yb) a.yb[row * a.yb_ld + j] = (uint16_t)hbits;
+                if (last) {
+                    if (a.hT) a.hT[(size_t)pb[r] * H + j] = hn;
+                    if (a.cT) a.cT[(size_t)pb[r] * H + j] = cn;
+                }
+            }
+        }
+        if (!last) {
+            // stores acknowledged by every wave, then the tile's flag; the barrier also keeps the next step's
+            // partial tiles out of LDS until every thread has read this step's
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+            __syncthreads();
+            if (tid == 0) __hip_atomic_store(myflag, a.tag_base + (unsigned)s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// h0 (fp32 [B][H]) -> exchange buffer 0 in the [H/16][Bp][16] bf16 layout
+__global__ void h0_to_exchange_kernel(const float* __restrict__ h0, uint16_t* __restrict__ hx, int B, int H, int Bp)
+{
+    const size_t n = (size_t)B * H;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t b = i / H, k = i % H;
+        hx[((k >> 4) * Bp + b) * 16 + (k & 15)] = f32_to_bf16_bits(h0[i]);
+    }
+}
+
+bool persist_mfma_supported(int B, int H)
+{
+    if (B < 32 || H % 128 != 0 || H > 1024) return false;
+    const int tiles = ((B + 63) / 64) * (4 * H / 64);
+    return ((tiles + 7) / 8) * 8 <= num_cu_pm();
+}
+
+size_t persist_mfma_exchange_bytes(int B, int H)
+{
+    const size_t Bp = (size_t)((B + 63) / 64) * 64;
+    return 2 * (size_t)H * Bp * sizeof(uint16_t);
+}
+size_t persist_mfma_flag_count(int B, int H) { return (size_t)((B + 63) / 64) * (4 * H / 64); }
+
+hipError_t launch_persist_mfma_bf16(const PersistMfmaArgs& a, const float* h0, bool cooperative, hipStream_t s)
+{
+    if (a.B <= 0 || a.H <= 0 || a.T <= 0) return hipSuccess;
+    if (!persist_mfma_supported(a.B, a.H)) return hipErrorInvalidValue;
+    const int gm = (a.B + 63) / 64, gn = (4 * a.H) / 64;
+    const int grid = ((gm * gn + 7) / 8) * 8;
+    const size_t lds = 8 * 64 * 68 * sizeof(float);
+    PersistMfmaArgs args = a;
+    args.has_h0 = h0 != nullptr;
+    if (h0) {
+        const size_t n = (size_t)a.B * a.H;
+        int g = (int)((n + 255) / 256);
+        if (g > 2048) g = 2048;
+        hipLaunchKernelGGL(h0_to_exchange_kernel, dim3(g), dim3(256), 0, s, h0, a.hx, a.B, a.H, gm * 64);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const void* kern = nullptr;
+    switch (a.H / 128) {
+        case 1: kern = (const void*)persist_mfma_bf16_kernel<1>; break;
+        case 2: kern = (const void*)persist_mfma_bf16_kernel<2>; break;
+        case 3: kern = (const void*)persist_mfma_bf16_kernel<3>; break;
+        case 4: kern = (const void*)persist_mfma_bf16_kernel<4>; break;
+        case 5: kern = (const void*)persist_mfma_bf16_kernel<5>; break;
+        case 6: kern = (const void*)persist_mfma_bf16_kernel<6>; break;
+        case 7: kern = (const void*)persist_mfma_bf16_kernel<7>; break;
+        case 8: kern = (const void*)persist_mfma_bf16_kernel<8>; break;
+        default: return hipErrorInvalidValue;
+    }
+    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    void* kargs[] = {(void*)&args};
+    // every workgroup must be resident at the same time: at most one per compute unit (139 KB of LDS each)
+    if (cooperative) return hipLaunchCooperativeKernel(kern, dim3(grid), dim3(512), kargs, (unsigned)lds, s);
+    return hipLaunchKernel(kern, dim3(grid), dim3(512), kargs, lds, s);
+}
+
+}  // namespace l355

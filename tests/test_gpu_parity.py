@@ -83,11 +83,36 @@ def test_bf16_small():
 
 
 @pytest.mark.parametrize("Bn", [32, 40, 130])
-def test_bf16_matrix_core_step(Bn):
-    """bf16 dense stacks at batch >= 32 with H % 256 == 0 take the MFMA step kernel (batch tail included)."""
+@pytest.mark.parametrize("plan", [PAUTO, STEP])
+def test_bf16_matrix_core_recurrence(Bn, plan):
+    """bf16 dense stacks at batch >= 32 run the recurrence on the matrix cores (batch tail included): with the time
+    loop on the device when H % 128 == 0, H <= 1024 and the tiles fit one per compute unit, else (or when the
+    stepwise plan is forced) with one launch per step (H % 256 == 0)."""
     case = inputs.make_case(_wl(89, 2, False, 64, 256, 5, Bn, dtype="bf16", a=0.1), k=Bn, random_state=True)
+    desc, _ = check_case(case, DENSE, plan)
+    assert ("persist-mfma" if plan == PAUTO else "stepwise-mfma") in desc
+
+
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, T, B, random initial state, cooperative launch
+    (1, False, 64, 128, 1, 64, False, True),     # one step, no exchange at all
+    (2, False, 96, 384, 9, 70, True, True),      # three k16 steps per wave, batch tail
+    (1, True, 64, 256, 7, 100, True, True),      # both directions (one launch each)
+    (2, False, 64, 512, 12, 33, False, False),   # zero initial state, ordinary launch
+    (1, False, 128, 1024, 6, 64, True, False),   # widest supported hidden size: 64 tiles along the gate rows
+])
+def test_bf16_persistent_matrix_core_shapes(shape):
+    L, bidir, D, H, T, Bn, rs, coop = shape
+    case = inputs.make_case(_wl(86, L, bidir, D, H, T, Bn, dtype="bf16", a=0.08), k=H + T, random_state=rs)
+    desc, _ = check_case(case, DENSE, PAUTO, cooperative=coop)
+    assert "persist-mfma" in desc
+
+
+def test_bf16_persistent_matrix_core_long_sequence():
+    """Many steps: the flag tags keep growing across steps and across the two layers' launches."""
+    case = inputs.make_case(_wl(85, 2, False, 64, 256, 400, 64, dtype="bf16", a=0.06), k=1, random_state=True)
     desc, _ = check_case(case, DENSE, PAUTO)
-    assert "mfma" in desc
+    assert "persist-mfma" in desc
 
 
 @pytest.mark.parametrize("D", [192, 96, 320])
