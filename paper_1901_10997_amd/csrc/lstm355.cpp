@@ -597,9 +597,10 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 a.P = P[d];
                 a.Wh = (const uint16_t*)w.wh.dense;
                 a.c0 = c0 ? c0 + n * B * H : nullptr;
-                a.y = Yout + (size_t)d * H;
+                // the layer above reads the bf16 copy; only the last layer's fp32 sequence leaves the library
+                a.y = (l == L - 1) ? Yout + (size_t)d * H : nullptr;
                 a.y_ld = y_ld;
-                a.yb = Yb + (size_t)d * H;
+                a.yb = (l == L - 1) ? nullptr : Yb + (size_t)d * H;
                 a.yb_ld = y_ld;
                 a.hT = hT ? hT + n * B * H : nullptr;
                 a.cT = cT ? cT + n * B * H : nullptr;

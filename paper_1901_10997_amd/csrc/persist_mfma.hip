@@ -258,8 +258,12 @@ hipError_t launch_persist_mfma_bf16(const PersistMfmaArgs& a, const float* h0, b
         case 8: kern = (const void*)persist_mfma_bf16_kernel<8>; break;
         default: return hipErrorInvalidValue;
     }
-    hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
+    static bool attr_set[9] = {};
+    if (!attr_set[a.H / 128]) {
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set[a.H / 128] = true;
+    }
     void* kargs[] = {(void*)&args};
     // every workgroup must be resident at the same time: at most one per compute unit (139 KB of LDS each)
     if (cooperative) return hipLaunchCooperativeKernel(kern, dim3(grid), dim3(512), kargs, (unsigned)lds, s);
