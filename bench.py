@@ -30,7 +30,7 @@ def counter_traffic_bytes(workload_name):
     try:
         kv = dict(line.strip().split("=", 1) for line in open(path) if "=" in line and not line.startswith("#"))
         h = hashlib.sha256()
-        for f in ("persist_b1.hip", "exchange.h", "device_math.h", "common.h"):
+        for f in ("persist_b1.hip", "exchange.h", "device_math.h"):
             h.update(open(os.path.join(ROOT, "paper_1901_10997_amd", "csrc", f), "rb").read())
         if kv.get("workload") != workload_name or kv.get("source_sha256") != h.hexdigest():
             return None
