@@ -110,7 +110,7 @@ size_t lstm_workspace_bytes(const lstm_t* m, int T, int B);
  *   stream              hipStream_t passed as void*; NULL = the default stream
  * Asynchronous on `stream`: no host synchronisation and no allocation inside.  T = 0 or B = 0 is a
  * no-op that returns LSTM_OK.  Two forwards on the same handle must not overlap in time.  The persistent kernels
- * (batch 1, and small-batch row-compressed) occupy every compute unit for the duration of a layer: forwards issued
+ * (batch 1, small-batch row-compressed, and large-batch bf16) occupy every compute unit for the duration of a layer: forwards issued
  * on other streams at the same time wait for them (cooperative launch) or, with ordinary launches, may make the
  * bounded waits expire (LSTM_ERR_TIMEOUT from lstm_check).
  */

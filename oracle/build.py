@@ -1,18 +1,18 @@
-"""Compile the C oracle with the host compiler (gcc, -O2, OpenMP).  Test infrastructure only."""
+"""Compile the C oracles (LSTM and H-LSTM) with the host compiler (gcc, -O2, OpenMP).  Test infrastructure only."""
 from __future__ import annotations
 
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "lstm_oracle.c")
+SRCS = [os.path.join(HERE, "lstm_oracle.c"), os.path.join(HERE, "hlstm_oracle.c")]
 LIB = os.path.join(HERE, "liblstm_oracle.so")
 
 
 def build(force: bool = False) -> str:
-    if force or not os.path.exists(LIB) or os.path.getmtime(LIB) < os.path.getmtime(SRC):
+    if force or not os.path.exists(LIB) or os.path.getmtime(LIB) < max(os.path.getmtime(s) for s in SRCS):
         cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
-               SRC, "-o", LIB, "-lm"]
+               *SRCS, "-o", LIB, "-lm"]
         subprocess.run(cmd, check=True)
     return LIB
 

@@ -38,6 +38,7 @@ class Workload:
     a: float = 0.1           # weights ~ U(-a, a)
     keep: Optional[float] = None   # Bernoulli keep-probability of the masks; None = dense (no masks)
     bias: str = "forget1"    # "forget1": 0 except forget gate 1.0 ; "uniform": U(-a, a)
+    gate_hidden: int = 0     # > 0: H-LSTM cell, width of the hidden layer inside each gate
 
     @property
     def ndir(self) -> int:
@@ -71,6 +72,18 @@ def c5() -> Workload:
     return Workload(5, "c5_throughput_2x1024_bf16", 2, False, 1024, 1024, 128, 256, "bf16", 0.03, None, "uniform")
 
 
+def h1() -> Workload:
+    """Language-model H-LSTM of the paper's Section 5.1: one layer, hidden state 1500, one hidden layer of width
+    1500 per gate, word embeddings of width 400; masks keep 10 % (the pruned models keep 4-17 %)."""
+    return Workload(6, "h1_lm_hlstm_1x1500_b1", 1, False, 400, 1500, 35, 1, "f32", 0.04, 0.10, "uniform", 1500)
+
+
+def h2() -> Workload:
+    """Speech H-LSTM of the paper's Section 5.2: three bidirectional layers, hidden state and gate hidden layers 800
+    wide, batch 16; masks keep 25 % (the pruned models keep about 27 %)."""
+    return Workload(7, "h2_speech_hlstm_3x800_bidir", 3, True, 640, 800, 300, 16, "f32", 0.035, 0.25, "uniform", 800)
+
+
 def shrink(w: Workload, **kw) -> Workload:
     """Same recipe at other sizes (used by tests that need the oracle to finish quickly)."""
     return replace(w, **kw)
@@ -90,6 +103,8 @@ class Case:
     """Host arrays of one seeded instance of a workload.
 
     weights[(l, d)] = dict(Wx[4H,D_l] f32, Mx u8 or None, Wh[4H,H] f32, Mh u8 or None, b[4H] f32)
+    H-LSTM workloads (gate_hidden = G > 0) instead hold
+    weights[(l, d)] = dict(W1x[4G,D_l], M1x, W1h[4G,H], M1h, b1[4G], W2[4H,G], M2, b2[4H])
     x[T,B,D0] f32 ; h0, c0 [L*ndir, B, H] f32 or None (= zeros)
     """
     w: Workload
@@ -104,8 +119,9 @@ def make_case(w: Workload, k: int = 0, random_state: bool = False) -> Case:
     """Draw instance `k` of workload `w`.
 
     Draw order (fixed, so that a case is reproducible from (cid, k) alone):
-    for each layer, for each direction: Wx, mask_x, Wh, mask_h, b; then x; then,
-    if `random_state`, h0 and c0 ~ U(-0.5, 0.5).
+    for each layer, for each direction: Wx, mask_x, Wh, mask_h, b (H-LSTM: W1x, mask_1x, W1h, mask_1h, b1, W2,
+    mask_2, b2; forget-gate bias 1 applies to b2 when bias == "forget1"); then x; then, if `random_state`, h0 and
+    c0 ~ U(-0.5, 0.5).
     """
     seed = SEED_BASE + 1000 * w.cid + k
     rng = np.random.Generator(np.random.PCG64(seed))
@@ -115,6 +131,25 @@ def make_case(w: Workload, k: int = 0, random_state: bool = False) -> Case:
     for l in range(w.layers):
         D = w.layer_input_dim(l)
         for d in range(w.ndir):
+            if w.gate_hidden > 0:
+                R1 = 4 * w.gate_hidden
+
+                def draw(shape):
+                    Wm = rng.uniform(-w.a, w.a, shape).astype(np.float32)
+                    Mm = (rng.random(shape) < w.keep).astype(np.uint8) if w.keep is not None else None
+                    return Wm, Mm
+
+                W1x, M1x = draw((R1, D))
+                W1h, M1h = draw((R1, H))
+                b1 = rng.uniform(-w.a, w.a, R1).astype(np.float32)
+                W2, M2 = draw((G, w.gate_hidden))
+                if w.bias == "forget1":
+                    b2 = np.zeros(G, dtype=np.float32)
+                    b2[0:H] = 1.0
+                else:
+                    b2 = rng.uniform(-w.a, w.a, G).astype(np.float32)
+                weights[(l, d)] = dict(W1x=W1x, M1x=M1x, W1h=W1h, M1h=M1h, b1=b1, W2=W2, M2=M2, b2=b2)
+                continue
             Wx = rng.uniform(-w.a, w.a, (G, D)).astype(np.float32)
             Mx = (rng.random((G, D)) < w.keep).astype(np.uint8) if w.keep is not None else None
             Wh = rng.uniform(-w.a, w.a, (G, H)).astype(np.float32)
