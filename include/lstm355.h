@@ -72,6 +72,21 @@ enum {
  */
 int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, int dtype, lstm_t** out);
 
+/*
+ * Create a model whose cells are H-LSTM cells (paper Section 4: the same equation block with hidden layers inside
+ * the control gates; Sections 5.1 and 5.2: one hidden layer per gate, as wide as the hidden state, in the models
+ * the paper reports).  One hidden layer H per gate with ReLU activation:
+ *
+ *     u_q = relu( W1_q . [x_t, h_{t-1}] + b1_q )     q in {f, i, o, g}; width gate_hidden_dim = G
+ *     [f; i; o; g] = [sigmoid; sigmoid; sigmoid; tanh]( W2_q . u_q + b2_q )
+ *     c_t = f (x) c_{t-1} + i (x) g          h_t = o (x) tanh(c_t)
+ *
+ * Each gate has its own hidden layer.  gate_hidden_dim >= 1; dtype must be LSTM_F32 (LSTM_ERR_ARG otherwise).
+ * Everything else as lstm_create; weights are set with lstm_set_weights_h, all other calls are shared.
+ */
+int lstm_create_h(int layers, int input_dim, int hidden_dim, int gate_hidden_dim, int bidirectional, int dtype,
+                  lstm_t** out);
+
 /* Frees the handle and every device buffer it owns.  NULL is accepted. */
 int lstm_destroy(lstm_t* m);
 
@@ -94,6 +109,19 @@ int lstm_set_weights(lstm_t* m, int layer, int direction,
                      const float* Wx, const uint8_t* mask_x,
                      const float* Wh, const uint8_t* mask_h,
                      const float* b, int format);
+
+/*
+ * Weights of one (layer, direction) of an H-LSTM model (handle from lstm_create_h; LSTM_ERR_STATE on a handle from
+ * lstm_create, and lstm_set_weights returns LSTM_ERR_STATE on an H-LSTM handle).  All pointers HOST, row-major, fp32.
+ *   W1x[4G, D_l], W1h[4G, H], b1[4G]: the hidden layers, gate-major rows: row q*G + g is hidden unit g of gate q
+ *   W2[4H, G], b2[4H]: the gate outputs, row q*H + j is output j of gate q and multiplies the hidden layer of gate q
+ *   mask_1x, mask_1h, mask_2: uint8 in {0,1} of the matrix's shape, or NULL for "keep everything"
+ * Masks select, formats and copying as in lstm_set_weights.
+ */
+int lstm_set_weights_h(lstm_t* m, int layer, int direction,
+                       const float* W1x, const uint8_t* mask_1x,
+                       const float* W1h, const uint8_t* mask_1h, const float* b1,
+                       const float* W2, const uint8_t* mask_2, const float* b2, int format);
 
 /* Bytes of DEVICE workspace lstm_forward needs for (T, B); 0 on bad arguments. */
 size_t lstm_workspace_bytes(const lstm_t* m, int T, int B);
@@ -153,7 +181,8 @@ int lstm_describe_plan(const lstm_t* m, char* buf, size_t buf_bytes);
 
 /*
  * Read back the row-compressed structure of one matrix as the library stores it, translated to the
- * ABI row order (row r = q*H + j).  which: 0 = W_x, 1 = W_h.  All pointers HOST.
+ * ABI row order (row r = q*H + j).  which: 0 = W_x, 1 = W_h; on an H-LSTM handle 0 = W1x, 1 = W1h (rows
+ * r = q*G + g, 4G+1 row_ptr entries), 2 = W2.  All pointers HOST.
  * Call with row_ptr = col = val = NULL to obtain *nnz only.  row_ptr has 4H+1 entries.
  * LSTM_ERR_STATE if that matrix is not held in compressed form.
  */

@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblstm355.
 
 # every symbol include/lstm355.h declares
 EXPORTS = [
-    "lstm_create", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_workspace_bytes",
+    "lstm_create", "lstm_create_h", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_set_weights_h",
+    "lstm_workspace_bytes",
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
     "lstm_latency_sweep", "lstm_find_lhp", "lstm_bench_copy", "lstm_bench_exchange",
 ]
@@ -52,12 +53,16 @@ def load(build_if_missing: bool = True):
     vp, ci = c.c_void_p, c.c_int
     lib.lstm_create.restype = ci
     lib.lstm_create.argtypes = [ci, ci, ci, ci, ci, c.POINTER(vp)]
+    lib.lstm_create_h.restype = ci
+    lib.lstm_create_h.argtypes = [ci, ci, ci, ci, ci, ci, c.POINTER(vp)]
     lib.lstm_destroy.restype = ci
     lib.lstm_destroy.argtypes = [vp]
     lib.lstm_last_error.restype = c.c_char_p
     lib.lstm_last_error.argtypes = [vp]
     lib.lstm_set_weights.restype = ci
     lib.lstm_set_weights.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, ci]
+    lib.lstm_set_weights_h.restype = ci
+    lib.lstm_set_weights_h.argtypes = [vp, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, ci]
     lib.lstm_workspace_bytes.restype = c.c_size_t
     lib.lstm_workspace_bytes.argtypes = [vp, ci, ci]
     lib.lstm_forward.restype = ci
@@ -114,6 +119,14 @@ def lstm_create(layers: int, input_dim: int, hidden_dim: int, bidirectional: boo
     return h
 
 
+def lstm_create_h(layers: int, input_dim: int, hidden_dim: int, gate_hidden_dim: int, bidirectional: bool,
+                  dtype: int = LSTM_F32):
+    h = ctypes.c_void_p()
+    _check(load().lstm_create_h(layers, input_dim, hidden_dim, gate_hidden_dim, int(bool(bidirectional)), dtype,
+                                ctypes.byref(h)))
+    return h
+
+
 def lstm_destroy(handle) -> None:
     _check(load().lstm_destroy(handle))
 
@@ -124,6 +137,18 @@ def lstm_set_weights(handle, layer: int, direction: int, Wx, mask_x, Wh, mask_h,
     if mx is not None and mx.shape != Wx.shape or mh is not None and mh.shape != Wh.shape:
         raise ValueError("mask shape differs from its weight matrix")
     _check(load().lstm_set_weights(handle, layer, direction, _p(Wx), _p(mx), _p(Wh), _p(mh), _p(b), fmt), handle)
+
+
+def lstm_set_weights_h(handle, layer: int, direction: int, W1x, mask_1x, W1h, mask_1h, b1, W2, mask_2, b2,
+                       fmt: int = LSTM_FMT_AUTO) -> None:
+    W1x, W1h, b1 = _host(W1x, np.float32), _host(W1h, np.float32), _host(b1, np.float32)
+    W2, b2 = _host(W2, np.float32), _host(b2, np.float32)
+    m1x, m1h, m2 = _host(mask_1x, np.uint8), _host(mask_1h, np.uint8), _host(mask_2, np.uint8)
+    for mk, wm in ((m1x, W1x), (m1h, W1h), (m2, W2)):
+        if mk is not None and mk.shape != wm.shape:
+            raise ValueError("mask shape differs from its weight matrix")
+    _check(load().lstm_set_weights_h(handle, layer, direction, _p(W1x), _p(m1x), _p(W1h), _p(m1h), _p(b1),
+                                     _p(W2), _p(m2), _p(b2), fmt), handle)
 
 
 def lstm_workspace_bytes(handle, T: int, B: int) -> int:
@@ -230,11 +255,16 @@ def lstm_bench_exchange(hidden: int, waves: int = 0, steps: int = 200, iters: in
 # Convenience wrapper for tests and the benchmark: owns a handle plus torch device buffers.
 # ------------------------------------------------------------------------------------------------------------
 class Lstm:
-    def __init__(self, layers: int, input_dim: int, hidden: int, bidirectional: bool = False, dtype: int = LSTM_F32):
+    def __init__(self, layers: int, input_dim: int, hidden: int, bidirectional: bool = False, dtype: int = LSTM_F32,
+                 gate_hidden: int = 0):
         self.layers, self.input_dim, self.hidden = layers, input_dim, hidden
         self.ndir = 2 if bidirectional else 1
         self.dtype = dtype
-        self.handle = lstm_create(layers, input_dim, hidden, bidirectional, dtype)
+        self.gate_hidden = gate_hidden
+        if gate_hidden > 0:
+            self.handle = lstm_create_h(layers, input_dim, hidden, gate_hidden, bidirectional, dtype)
+        else:
+            self.handle = lstm_create(layers, input_dim, hidden, bidirectional, dtype)
         self._ws = None
 
     def close(self):
@@ -250,7 +280,11 @@ class Lstm:
 
     def set_weights_from(self, weights, fmt: int = LSTM_FMT_AUTO):
         for (l, d), p in weights.items():
-            lstm_set_weights(self.handle, l, d, p["Wx"], p.get("Mx"), p["Wh"], p.get("Mh"), p["b"], fmt)
+            if self.gate_hidden > 0:
+                lstm_set_weights_h(self.handle, l, d, p["W1x"], p.get("M1x"), p["W1h"], p.get("M1h"), p["b1"],
+                                   p["W2"], p.get("M2"), p["b2"], fmt)
+            else:
+                lstm_set_weights(self.handle, l, d, p["Wx"], p.get("Mx"), p["Wh"], p.get("Mh"), p["b"], fmt)
 
     def forward(self, x, h0=None, c0=None, want_state: bool = True, stream=None, check: bool = True):
         """x: torch device tensor [T,B,D0] (float32, or bfloat16 for bf16 models).  Returns (y, hT, cT)."""

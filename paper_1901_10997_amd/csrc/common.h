@@ -34,6 +34,10 @@ struct LayerDir {
     bool set = false;
     PackedMat wx, wh;
     float* bias = nullptr;  // device [4H], packed row order, fp32
+    // H-LSTM cell: wx, wh and bias are the hidden layers of the four gates (W1x [4G][D], W1h [4G][H], b1 [4G],
+    // packed row 4g+q = hidden unit g of gate q); w2 [4H][G] and bias2 [4H] are the gate outputs (packed row 4j+q)
+    PackedMat w2;
+    float* bias2 = nullptr;
 };
 
 // ---- kernel launchers (all asynchronous on `s`; return hipError_t of the launch) ----
@@ -71,6 +75,35 @@ struct StepArgs {
 hipError_t launch_step_dense(const StepArgs& a, const void* Wh, bool w_bf16, hipStream_t s);
 hipError_t launch_step_csr(const StepArgs& a, const int32_t* row_ptr, const uint16_t* col, const float* val,
                            hipStream_t s);
+
+// H-LSTM, one timestep in two launches (any shape): hidden layers of the gates, then gate outputs + cell update.
+struct HStage1Args {
+    const float* P1;        // [T*B][4G] hidden-layer pre-activations from the input projection (b1 included)
+    const float* h_prev;    // (b,k) at h_prev[b*h_prev_ld + k]; nullptr = zeros
+    int h_prev_ld;
+    const float* w_dense;   // W1h [4G][H] fp32 packed rows, or nullptr when row-compressed
+    const int32_t* row_ptr; // row-compressed W1h
+    const uint16_t* col;
+    const float* val;
+    float* u;               // [B][4G], packed: u[b][4g+q]
+    int t, B, H, G;
+};
+struct HStage2Args {
+    const float* u;         // [B][4G]
+    const float* w_dense;   // W2 [4H][G] fp32 packed rows, or nullptr when row-compressed
+    const int32_t* row_ptr;
+    const uint16_t* col;
+    const float* val;
+    const float* bias2;     // [4H] packed
+    float* c;               // [B][H] in place
+    float* y_t;             // h_t -> y_t[b*y_ld + j]
+    int y_ld;
+    float* hT;
+    float* cT;
+    int last, B, H, G;
+};
+hipError_t launch_hstage1(const HStage1Args& a, hipStream_t s);
+hipError_t launch_hstage2(const HStage2Args& a, hipStream_t s);
 
 // bf16 step on the matrix cores (large batch, dense W_h): recurrent product + fused cell update.
 struct StepMfmaArgs {

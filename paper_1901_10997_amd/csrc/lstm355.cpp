@@ -17,6 +17,7 @@ using namespace l355;
 
 struct lstm355 {
     int L = 0, D0 = 0, H = 0, Dn = 1, dtype = LSTM_F32;
+    int G = 0;                 // > 0: H-LSTM cell, width of the hidden layer inside each gate
     int device = 0;
     std::vector<LayerDir> ld;  // index l*Dn + d
     mutable std::string err;
@@ -222,7 +223,8 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
 
 extern "C" {
 
-int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, int dtype, lstm_t** out)
+static int create_model(int layers, int input_dim, int hidden_dim, int gate_hidden_dim, int bidirectional, int dtype,
+                        lstm_t** out)
 {
     if (!out) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: out is NULL");
     *out = nullptr;
@@ -240,6 +242,7 @@ int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, in
     m->H = hidden_dim;
     m->Dn = bidirectional ? 2 : 1;
     m->dtype = dtype;
+    m->G = gate_hidden_dim;
     m->ld.resize((size_t)m->L * m->Dn);
     m->cooperative = g_default_cooperative;
     if (const char* sl = std::getenv("LSTM355_SPIN_LIMIT")) {
@@ -261,13 +264,29 @@ int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, in
     return LSTM_OK;
 }
 
+int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, int dtype, lstm_t** out)
+{
+    return create_model(layers, input_dim, hidden_dim, 0, bidirectional, dtype, out);
+}
+
+int lstm_create_h(int layers, int input_dim, int hidden_dim, int gate_hidden_dim, int bidirectional, int dtype, lstm_t** out)
+{
+    if (out) *out = nullptr;
+    if (gate_hidden_dim < 1 || (long long)gate_hidden_dim * 4 > (1 << 28))
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_create_h: gate_hidden_dim must be >= 1");
+    if (dtype != LSTM_F32) return fail(nullptr, LSTM_ERR_ARG, "lstm_create_h: the H-LSTM cell is implemented for LSTM_F32 only");
+    return create_model(layers, input_dim, hidden_dim, gate_hidden_dim, bidirectional, dtype, out);
+}
+
 int lstm_destroy(lstm_t* m)
 {
     if (!m) return LSTM_OK;
     for (auto& x : m->ld) {
         free_mat(x.wx);
         free_mat(x.wh);
+        free_mat(x.w2);
         if (x.bias) (void)hipFree(x.bias);
+        if (x.bias2) (void)hipFree(x.bias2);
     }
     for (auto& sp : m->spans) { (void)hipEventDestroy(sp.e0); (void)hipEventDestroy(sp.e1); }
     for (auto& e : m->event_pool) (void)hipEventDestroy(e);
@@ -285,6 +304,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_set_weights: handle is NULL");
     if (layer < 0 || layer >= m->L || direction < 0 || direction >= m->Dn)
         return fail(m, LSTM_ERR_SHAPE, "lstm_set_weights: layer/direction outside the model");
+    if (m->G > 0) return fail(m, LSTM_ERR_STATE, "lstm_set_weights: this handle is an H-LSTM, use lstm_set_weights_h");
     if (!Wx || !Wh || !b) return fail(m, LSTM_ERR_ARG, "lstm_set_weights: Wx, Wh and b are required");
     if (format != LSTM_FMT_AUTO && format != LSTM_FMT_DENSE_MASKED && format != LSTM_FMT_ROW_COMPRESSED)
         return fail(m, LSTM_ERR_ARG, "lstm_set_weights: unknown format");
@@ -323,18 +343,71 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     return LSTM_OK;
 }
 
+int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, const uint8_t* mask_1x, const float* W1h,
+                       const uint8_t* mask_1h, const float* b1, const float* W2, const uint8_t* mask_2, const float* b2,
+                       int format)
+{
+    if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_set_weights_h: handle is NULL");
+    if (m->G <= 0) return fail(m, LSTM_ERR_STATE, "lstm_set_weights_h: this handle is a conventional LSTM, use lstm_set_weights");
+    if (layer < 0 || layer >= m->L || direction < 0 || direction >= m->Dn)
+        return fail(m, LSTM_ERR_SHAPE, "lstm_set_weights_h: layer/direction outside the model");
+    if (!W1x || !W1h || !b1 || !W2 || !b2) return fail(m, LSTM_ERR_ARG, "lstm_set_weights_h: W1x, W1h, b1, W2 and b2 are required");
+    if (format != LSTM_FMT_AUTO && format != LSTM_FMT_DENSE_MASKED && format != LSTM_FMT_ROW_COMPRESSED)
+        return fail(m, LSTM_ERR_ARG, "lstm_set_weights_h: unknown format");
+    const int H = m->H, G = m->G, D = m->in_dim(layer);
+    const size_t sizes[3] = {(size_t)4 * G * D, (size_t)4 * G * H, (size_t)4 * H * G};
+    const uint8_t* masks[3] = {mask_1x, mask_1h, mask_2};
+    size_t kept = 0, total = 0;
+    for (int i = 0; i < 3; ++i) {
+        total += sizes[i];
+        if (!masks[i]) { kept += sizes[i]; continue; }
+        for (size_t e = 0; e < sizes[i]; ++e) {
+            if (masks[i][e] > 1) return fail(m, LSTM_ERR_ARG, "lstm_set_weights_h: mask bytes must be 0 or 1");
+            kept += masks[i][e];
+        }
+    }
+    bool compressed;
+    if (format == LSTM_FMT_AUTO)
+        compressed = (mask_1x || mask_1h || mask_2) && (double)kept <= 0.25 * (double)total;
+    else
+        compressed = (format == LSTM_FMT_ROW_COMPRESSED);
+    if (compressed && (D > 65536 || H > 65536 || G > 65536))
+        return fail(m, LSTM_ERR_ARG, "lstm_set_weights_h: row-compressed form needs dimensions <= 65536");
+    HIP_TRY(m, hipSetDevice(m->device));
+    LayerDir& x = m->ld[(size_t)layer * m->Dn + direction];
+    x.set = false;
+    // hidden layers: 4G rows, packed row 4g+q; kept dense as well for the projection on the matrix cores
+    int rc = pack_matrix(m, x.wx, W1x, mask_1x, G, D, compressed, false, true);
+    if (rc != LSTM_OK) return rc;
+    rc = pack_matrix(m, x.wh, W1h, mask_1h, G, H, compressed, false, false);
+    if (rc != LSTM_OK) return rc;
+    // gate outputs: 4H rows, packed row 4j+q, columns = hidden units of the row's own gate
+    rc = pack_matrix(m, x.w2, W2, mask_2, H, G, compressed, false, false);
+    if (rc != LSTM_OK) return rc;
+    std::vector<float> bp1((size_t)4 * G), bp2((size_t)4 * H);
+    for (int rp = 0; rp < 4 * G; ++rp) bp1[rp] = b1[(size_t)(rp & 3) * G + (rp >> 2)];
+    for (int rp = 0; rp < 4 * H; ++rp) bp2[rp] = b2[(size_t)(rp & 3) * H + (rp >> 2)];
+    if (x.bias) { (void)hipFree(x.bias); x.bias = nullptr; }
+    if (x.bias2) { (void)hipFree(x.bias2); x.bias2 = nullptr; }
+    HIP_TRY(m, upload(&x.bias, bp1));
+    HIP_TRY(m, upload(&x.bias2, bp2));
+    x.set = true;
+    return LSTM_OK;
+}
+
 // ---- workspace carve-up --------------------------------------------------------------------------------
 struct Workspace {
-    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, slot_off, hx_off, mflag_off, total;
+    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, slot_off, hx_off, mflag_off, U_off[2], total;
 };
 static Workspace carve(const lstm_t* m, int T, int B)
 {
     Workspace w{};
     size_t off = 0;
     const size_t M = (size_t)T * B, H = m->H;
+    const size_t prow = m->G > 0 ? (size_t)m->G : H;   // H-LSTM: the projection feeds the 4G hidden-layer rows
     for (int d = 0; d < 2; ++d) {
         w.P_off[d] = off;
-        if (d < m->Dn) off += align256(M * 4 * H * sizeof(float));
+        if (d < m->Dn) off += align256(M * 4 * prow * sizeof(float));
     }
     size_t Dmax = (size_t)m->D0;
     if (m->L > 1) Dmax = std::max(Dmax, (size_t)m->Dn * H);
@@ -366,6 +439,11 @@ static Workspace carve(const lstm_t* m, int T, int B)
         off += align256(persist_mfma_exchange_bytes(B, (int)H));
         w.mflag_off = off;
         off += align256(persist_mfma_flag_count(B, (int)H) * sizeof(unsigned));
+    }
+    // H-LSTM, stepwise path: hidden-layer activations of the current step, [B][4G] per direction
+    for (int d = 0; d < 2; ++d) {
+        w.U_off[d] = off;
+        if (m->G > 0 && d < m->Dn) off += align256((size_t)B * 4 * m->G * sizeof(float));
     }
     w.total = off;
     return w;
@@ -441,6 +519,89 @@ int lstm_describe_plan(const lstm_t* m, char* buf, size_t buf_bytes)
     return LSTM_OK;
 }
 
+// H-LSTM stack (fp32).  Per layer and direction: the hidden layers' input side for all timesteps as one projection
+// (P1 = W1x.x + b1, 4G rows), then per step the hidden layers (stage 1) and the gate outputs with the cell update
+// (stage 2).
+static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0, float* y, float* hT,
+                         float* cT, const Workspace& ws, char* base, hipStream_t s)
+{
+    const int H = m->H, G = m->G, Dn = m->Dn, L = m->L;
+    const int M = T * B;
+    float* P[2] = {(float*)(base + ws.P_off[0]), (float*)(base + ws.P_off[1])};
+    float* XT = (float*)(base + ws.XT_off);
+    float* Ybuf[2] = {(float*)(base + ws.Y_off[0]), (float*)(base + ws.Y_off[1])};
+    float* cbuf[2] = {(float*)(base + ws.c_off[0]), (float*)(base + ws.c_off[1])};
+    float* U[2] = {(float*)(base + ws.U_off[0]), (float*)(base + ws.U_off[1])};
+    char tag[96];
+    for (int l = 0; l < L; ++l) {
+        const int D = m->in_dim(l);
+        const void* X = (l == 0) ? x : (const void*)Ybuf[(l - 1) & 1];
+        float* Yout = (l == L - 1) ? y : Ybuf[l & 1];
+        const int y_ld = Dn * H;
+        bool xt_ready = false;
+        bool proj_dense[2] = {false, false};
+        for (int d = 0; d < Dn; ++d) {
+            const LayerDir& w = m->ld[(size_t)l * Dn + d];
+            ProfSpan span(m, s, 0);
+            const bool dense_proj = w.wx.dense && (!w.wx.compressed || (M >= 256 && proj_mfma_supported(false, D, D)));
+            proj_dense[d] = dense_proj;
+            if (!dense_proj) {
+                if (!xt_ready) {
+                    HIP_TRY(m, launch_transpose_to_f32(X, false, D, XT, M, D, false, s));
+                    xt_ready = true;
+                }
+                HIP_TRY(m, launch_proj_csr(XT, w.wx.row_ptr, w.wx.col16, w.wx.val, w.bias, P[d], M, 4 * G, s));
+            } else if (proj_mfma_supported(false, D, D)) {
+                HIP_TRY(m, launch_proj_mfma(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s));
+            } else {
+                HIP_TRY(m, launch_proj_dense(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s));
+            }
+        }
+        for (int d = 0; d < Dn; ++d) {
+            const LayerDir& w = m->ld[(size_t)l * Dn + d];
+            const size_t n = (size_t)l * Dn + d;
+            ProfSpan span(m, s, 1);
+            if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
+            else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
+            std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=hlstm-stepwise-%s;", l, d,
+                          proj_dense[d] ? "dense" : "csr", w.wh.compressed ? "csr" : "dense");
+            m->last_plan += tag;
+            for (int step = 0; step < T; ++step) {
+                const int t = d ? (T - 1 - step) : step;
+                HStage1Args a1{};
+                a1.P1 = P[d];
+                if (step == 0) {
+                    a1.h_prev = h0 ? h0 + n * B * H : nullptr;
+                    a1.h_prev_ld = H;
+                } else {
+                    const int tp = d ? t + 1 : t - 1;
+                    a1.h_prev = Yout + (size_t)tp * B * y_ld + (size_t)d * H;
+                    a1.h_prev_ld = y_ld;
+                }
+                if (w.wh.compressed) { a1.row_ptr = w.wh.row_ptr; a1.col = w.wh.col16; a1.val = w.wh.val; }
+                else a1.w_dense = (const float*)w.wh.dense;
+                a1.u = U[d];
+                a1.t = t; a1.B = B; a1.H = H; a1.G = G;
+                HIP_TRY(m, launch_hstage1(a1, s));
+                HStage2Args a2{};
+                a2.u = U[d];
+                if (w.w2.compressed) { a2.row_ptr = w.w2.row_ptr; a2.col = w.w2.col16; a2.val = w.w2.val; }
+                else a2.w_dense = (const float*)w.w2.dense;
+                a2.bias2 = w.bias2;
+                a2.c = cbuf[d];
+                a2.y_t = Yout + (size_t)t * B * y_ld + (size_t)d * H;
+                a2.y_ld = y_ld;
+                a2.hT = hT ? hT + n * B * H : nullptr;
+                a2.cT = cT ? cT + n * B * H : nullptr;
+                a2.last = (step == T - 1);
+                a2.B = B; a2.H = H; a2.G = G;
+                HIP_TRY(m, launch_hstage2(a2, s));
+            }
+        }
+    }
+    return LSTM_OK;
+}
+
 int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0, float* y, float* hT,
                  float* cT, void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -475,6 +636,7 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
     unsigned mtag = 0;
     bool prev_has_bf16 = false;  // the layer below left a bf16 copy of its hidden sequence in Ybf[(l-1)&1]
     m->last_plan.clear();
+    if (m->G > 0) return forward_hlstm(m, T, B, x, h0, c0, y, hT, cT, ws, base, s);
 
     auto take_tags = [&](int T_) -> int {
         if (m->tag_base > 0xFFFFFFFFu - (unsigned)T_ - 2u) {
@@ -849,16 +1011,16 @@ int lstm_get_compressed(const lstm_t* m, int layer, int direction, int which, in
                         int32_t* col, float* val)
 {
     if (!m) return fail(nullptr, LSTM_ERR_ARG, "lstm_get_compressed: handle is NULL");
-    if (layer < 0 || layer >= m->L || direction < 0 || direction >= m->Dn || (which != 0 && which != 1))
+    if (layer < 0 || layer >= m->L || direction < 0 || direction >= m->Dn || which < 0 || which > (m->G > 0 ? 2 : 1))
         return fail(m, LSTM_ERR_SHAPE, "lstm_get_compressed: index outside the model");
     const LayerDir& x = m->ld[(size_t)layer * m->Dn + direction];
-    const PackedMat& p = which ? x.wh : x.wx;
+    const PackedMat& p = which == 2 ? x.w2 : (which ? x.wh : x.wx);
     if (!x.set || !p.compressed) return fail(m, LSTM_ERR_STATE, "lstm_get_compressed: matrix not held in compressed form");
     if (nnz) *nnz = p.nnz;
     if (!row_ptr && !col && !val) return LSTM_OK;
     if (!row_ptr || !col || !val) return fail(m, LSTM_ERR_ARG, "lstm_get_compressed: pass all of row_ptr, col, val or none");
-    // translate packed row order (4j+q) back to the ABI order (q*H + j)
-    const int H = m->H;
+    // translate packed row order (4j+q) back to the ABI order (q*H + j); the hidden layers of an H-LSTM have G units
+    const int H = (m->G > 0 && which != 2) ? m->G : m->H;
     int64_t pos = 0;
     for (int r = 0; r < 4 * H; ++r) {
         const int rp = 4 * (r % H) + (r / H);

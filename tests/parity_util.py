@@ -9,6 +9,7 @@ from __future__ import annotations
 
 import numpy as np
 
+from oracle import hlstm_oracle as horc
 from oracle import lstm_oracle as orc
 from paper_1901_10997_amd import binding as B
 from paper_1901_10997_amd import inputs
@@ -24,7 +25,7 @@ def run_gpu(case, fmt=B.LSTM_FMT_AUTO, plan=B.LSTM_PLAN_AUTO, waves=0, model=Non
     dtype = B.LSTM_BF16 if w.dtype == "bf16" else B.LSTM_F32
     own = model is None
     if own:
-        model = B.Lstm(w.layers, w.input_dim, w.hidden, w.bidirectional, dtype)
+        model = B.Lstm(w.layers, w.input_dim, w.hidden, w.bidirectional, dtype, gate_hidden=w.gate_hidden)
         model.set_weights_from(case.weights, fmt)
     B.lstm_set_plan(model.handle, plan, waves)
     B.lstm_set_launch_mode(model.handle, cooperative)
@@ -69,14 +70,16 @@ def compare(gpu, ref, dtype: str, label: str = ""):
 def check_case(case, fmt=B.LSTM_FMT_AUTO, plan=B.LSTM_PLAN_AUTO, waves=0, oracle_cols=None, label="", cooperative=True):
     """GPU on the whole case; oracle on the whole case or on the sampled batch columns `oracle_cols`."""
     print(f"[parity] {label or case.w.name} seed={case.seed} fmt={fmt} plan={plan} waves={waves} "
-          f"L={case.w.layers} Dn={case.w.ndir} D={case.w.input_dim} H={case.w.hidden} T={case.w.T} B={case.w.B}",
+          f"L={case.w.layers} Dn={case.w.ndir} D={case.w.input_dim} H={case.w.hidden} G={case.w.gate_hidden} "
+          f"T={case.w.T} B={case.w.B}",
           flush=True)
     gpu, desc = run_gpu(case, fmt, plan, waves, cooperative=cooperative)
+    oracle_forward = horc.forward_case if case.w.gate_hidden > 0 else orc.forward_case
     if oracle_cols is None:
-        ref = orc.forward_case(case)
+        ref = oracle_forward(case)
     else:
         sub = inputs.select_batch(case, oracle_cols)
-        ref = orc.forward_case(sub)
+        ref = oracle_forward(sub)
         gpu = (gpu[0][:, oracle_cols], gpu[1][:, oracle_cols], gpu[2][:, oracle_cols])
     worst = compare(gpu, ref, case.w.dtype, label or case.w.name)
     print(f"[parity]   plan={desc} worst={worst}", flush=True)
