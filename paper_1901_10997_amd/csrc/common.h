@@ -105,6 +105,35 @@ struct HStage2Args {
 hipError_t launch_hstage1(const HStage1Args& a, hipStream_t s);
 hipError_t launch_hstage2(const HStage2Args& a, hipStream_t s);
 
+// H-LSTM at batch 1, all three matrices row-compressed and register-resident, time loop on the device.
+struct PersistHArgs {
+    const float* ell_val_1x;    // W1x [4G][slots_1x][64]
+    const uint16_t* ell_col_1x;
+    const float* ell_val_1h;    // W1h [4G][slots_1h][64]
+    const uint16_t* ell_col_1h;
+    const float* ell_val_2;     // W2 [4H][slots_2][64], columns = hidden units of the row's own gate
+    const uint16_t* ell_col_2;
+    int slots_1x, slots_1h, slots_2;
+    const float* bias1;         // [4G] packed
+    const float* bias2;         // [4H] packed
+    const float* x;             // input sequence [T][x_ld], fp32
+    int x_ld, D;
+    const float* h0;            // [H] or nullptr
+    const float* c0;
+    float* y;                   // h_t -> y[t*y_ld + j]
+    int y_ld;
+    float* hT;
+    float* cT;
+    int T, H, G, reverse;
+    unsigned long long* xchg_h; // [H] tagged slots
+    unsigned long long* xchg_u; // [4G] tagged slots, gate-major
+    unsigned tag_base;          // step s publishes tag_base + s + 1 in both arrays
+    int* timeout_flag;
+    unsigned spin_limit;
+};
+bool persist_b1_hlstm_supported(int H, int G, int D, int slots_1x, int slots_1h, int slots_2);
+hipError_t launch_persist_b1_hlstm(const PersistHArgs& a, int cooperative, hipStream_t s);
+
 // bf16 step on the matrix cores (large batch, dense W_h): recurrent product + fused cell update.
 struct StepMfmaArgs {
     const float* P;            // [T*B][4H]

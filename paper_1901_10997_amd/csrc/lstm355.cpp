@@ -250,7 +250,8 @@ static int create_model(int layers, int input_dim, int hidden_dim, int gate_hidd
         if (v > 0) m->spin_limit = (unsigned)v;
     }
     hipError_t e = hipGetDevice(&m->device);
-    const size_t slots = (size_t)4 * m->H;  // two cells (directions, or two stacked layers) x two parities
+    // two cells (directions, or two stacked layers) x two parities; H-LSTM: h slots, then the 4G hidden-layer slots
+    const size_t slots = m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H;
     if (e == hipSuccess) e = hipMalloc((void**)&m->xchg, slots * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(m->xchg, 0, slots * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMalloc((void**)&m->timeout_flag, sizeof(int));
@@ -538,9 +539,20 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
         const void* X = (l == 0) ? x : (const void*)Ybuf[(l - 1) & 1];
         float* Yout = (l == L - 1) ? y : Ybuf[l & 1];
         const int y_ld = Dn * H;
+        // batch 1 with all three matrices row-compressed and small enough for registers: time loop on the device
+        bool persist[2] = {false, false};
+        for (int d = 0; d < Dn; ++d) {
+            const LayerDir& w = m->ld[(size_t)l * Dn + d];
+            persist[d] = B == 1 && m->plan != LSTM_PLAN_STEPWISE && w.wx.compressed && w.wh.compressed && w.w2.compressed &&
+                         w.wx.ell_val && w.wh.ell_val && w.w2.ell_val &&
+                         persist_b1_hlstm_supported(H, G, D, w.wx.slots, w.wh.slots, w.w2.slots);
+            if (m->plan == LSTM_PLAN_PERSISTENT && !persist[d])
+                return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
+        }
         bool xt_ready = false;
         bool proj_dense[2] = {false, false};
         for (int d = 0; d < Dn; ++d) {
+            if (persist[d]) continue;
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             ProfSpan span(m, s, 0);
             const bool dense_proj = w.wx.dense && (!w.wx.compressed || (M >= 256 && proj_mfma_supported(false, D, D)));
@@ -561,6 +573,33 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             const size_t n = (size_t)l * Dn + d;
             ProfSpan span(m, s, 1);
+            if (persist[d]) {
+                if (m->tag_base > 0xFFFFFFFFu - (unsigned)T - 2u) {
+                    // tag space exhausted: restart from a clean slate
+                    HIP_TRY(m, launch_fill_u64(m->xchg, (size_t)H + 4 * (size_t)G, 0ull, s));
+                    m->tag_base = 0;
+                }
+                PersistHArgs a{};
+                a.ell_val_1x = w.wx.ell_val; a.ell_col_1x = w.wx.ell_col; a.slots_1x = w.wx.slots;
+                a.ell_val_1h = w.wh.ell_val; a.ell_col_1h = w.wh.ell_col; a.slots_1h = w.wh.slots;
+                a.ell_val_2 = w.w2.ell_val; a.ell_col_2 = w.w2.ell_col; a.slots_2 = w.w2.slots;
+                a.bias1 = w.bias; a.bias2 = w.bias2;
+                a.x = (const float*)X; a.x_ld = D; a.D = D;
+                a.h0 = h0 ? h0 + n * H : nullptr;
+                a.c0 = c0 ? c0 + n * H : nullptr;
+                a.y = Yout + (size_t)d * H; a.y_ld = y_ld;
+                a.hT = hT ? hT + n * H : nullptr;
+                a.cT = cT ? cT + n * H : nullptr;
+                a.T = T; a.H = H; a.G = G; a.reverse = d;
+                a.xchg_h = m->xchg; a.xchg_u = m->xchg + H;
+                a.tag_base = m->tag_base;
+                a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                m->tag_base += (unsigned)T + 1u;
+                std::snprintf(tag, sizeof tag, "l%d.d%d:proj=fused,rec=persist_b1-hlstm-csr;", l, d);
+                m->last_plan += tag;
+                HIP_TRY(m, launch_persist_b1_hlstm(a, m->cooperative, s));
+                continue;
+            }
             if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
             else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
             std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=hlstm-stepwise-%s;", l, d,

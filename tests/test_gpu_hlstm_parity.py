@@ -93,3 +93,56 @@ def test_hlstm_garbage_under_mask_is_invisible_and_runs_are_deterministic():
         for a, b in zip(got, ref):
             assert np.all(np.isfinite(a))
             np.testing.assert_array_equal(a, b)
+
+
+# ---- batch 1, row-compressed: both products and both exchanges of a step inside one persistent kernel ----------
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, G, T, keep, cooperative
+    (1, False, 40, 150, 150, 11, 0.3, True),
+    (1, False, 33, 64, 200, 9, 0.9, True),       # more hidden-layer units than outputs, three slices per row
+    (2, False, 90, 200, 70, 8, 0.25, True),      # fewer hidden-layer units than outputs; second layer reads the first
+    (1, True, 50, 130, 90, 7, 0.5, False),       # both directions, ordinary launch
+    (3, True, 31, 96, 96, 5, 0.15, True),
+    (1, False, 20, 333, 257, 1, 0.4, True),      # T = 1: no exchange of h at all
+    (1, False, 700, 64, 64, 6, 0.2, True),       # input wider than two elements per thread
+])
+def test_hlstm_persistent_batch1(shape):
+    L, bidir, D, H, G, T, keep, coop = shape
+    case = inputs.make_case(_hw(83, L, bidir, D, H, G, T, 1, keep=keep), k=H + G + T, random_state=True)
+    desc, _ = check_case(case, CSR, PERSIST, cooperative=coop)
+    assert "persist_b1-hlstm" in desc
+    desc, _ = check_case(case, CSR, STEP)
+    assert "hlstm-stepwise" in desc
+
+
+def test_hlstm_persistent_long_sequence_and_state_chaining():
+    case = inputs.make_case(_hw(84, 1, False, 48, 300, 300, 1200, 1, a=0.3, keep=0.15), k=0, random_state=True)
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "persist_b1-hlstm" in desc
+    # two halves chained through (hT, cT) on one handle equal one run over the whole sequence
+    import torch
+    full, _, model = run_gpu(case, CSR, PAUTO, return_model=True)
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(case.x).to(dev)
+    h0 = torch.from_numpy(case.h0).to(dev); c0 = torch.from_numpy(case.c0).to(dev)
+    y1, h1, c1 = model.forward(x[:500].contiguous(), h0, c0)
+    y2, h2, c2 = model.forward(x[500:].contiguous(), h1, c1)
+    model.close()
+    np.testing.assert_array_equal(torch.cat([y1, y2]).cpu().numpy(), full[0])
+    np.testing.assert_array_equal(h2.cpu().numpy(), full[1])
+    np.testing.assert_array_equal(c2.cpu().numpy(), full[2])
+
+
+def test_hlstm_full_size_language_model():
+    """The paper's language-model H-LSTM shape (one layer, 1500 / 1500, embeddings of 400), batch 1, 10 % kept."""
+    case = inputs.make_case(inputs.h1(), 0)
+    desc, _ = check_case(case, AUTO, PAUTO, cooperative=False)
+    assert "persist_b1-hlstm" in desc
+
+
+@pytest.mark.slow
+def test_hlstm_full_size_speech_sampled_columns():
+    """The paper's speech H-LSTM shape (3 bidirectional layers, 800 / 800, batch 16); the oracle runs two of the
+    sixteen sequences (sequences are independent)."""
+    case = inputs.make_case(inputs.h2(), 0)
+    check_case(case, AUTO, PAUTO, oracle_cols=[3, 12])
