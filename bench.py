@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2_b1", choices=["c1", "c2_b1", "c2_b20", "c4", "c5"])
+    ap.add_argument("--workload", default="c2_b1", choices=["c1", "c2_b1", "c2_b20", "c4", "c5", "h1", "h2"])
     ap.add_argument("--format", default="auto", choices=["auto", "dense", "csr"])
     ap.add_argument("--plan", default="auto", choices=["auto", "stepwise", "persistent"])
     ap.add_argument("--waves", type=int, default=0)
@@ -82,12 +82,14 @@ def main():
         print(json.dumps({"metric": "device_copy_bandwidth", "value": 2 * n / us / 1e3, "unit": "GB/s",
                           "bytes_read": n, "bytes_written": n, "avg_us": us}))
         return
-    wl = {"c1": inputs.c1(), "c2_b1": inputs.c2(1), "c2_b20": inputs.c2(20), "c4": inputs.c4(), "c5": inputs.c5()}[args.workload]
+    wl = {"c1": inputs.c1(), "c2_b1": inputs.c2(1), "c2_b20": inputs.c2(20), "c4": inputs.c4(), "c5": inputs.c5(),
+          "h1": inputs.h1(), "h2": inputs.h2()}[args.workload]
+    hl = wl.gate_hidden > 0     # H-LSTM cell: one hidden layer of that width inside each gate
     case = inputs.make_case(wl, 0)
     dtype = B.LSTM_BF16 if wl.dtype == "bf16" else B.LSTM_F32
     fmt = {"auto": B.LSTM_FMT_AUTO, "dense": B.LSTM_FMT_DENSE_MASKED, "csr": B.LSTM_FMT_ROW_COMPRESSED}[args.format]
     plan = {"auto": B.LSTM_PLAN_AUTO, "stepwise": B.LSTM_PLAN_STEPWISE, "persistent": B.LSTM_PLAN_PERSISTENT}[args.plan]
-    m = B.Lstm(wl.layers, wl.input_dim, wl.hidden, wl.bidirectional, dtype)
+    m = B.Lstm(wl.layers, wl.input_dim, wl.hidden, wl.bidirectional, dtype, gate_hidden=wl.gate_hidden)
     m.set_weights_from(case.weights, fmt)
     B.lstm_set_plan(m.handle, plan, args.waves)
     B.lstm_set_launch_mode(m.handle, args.launch == "cooperative")
@@ -168,7 +170,18 @@ def main():
     rec_launches_per_fwd = max(prof["rec_launches"] // max(args.steps, 1), 1)
     alg_bytes = 0.0
     keys = sorted(case.weights.keys())
-    for (l, d) in keys:
+    G = wl.gate_hidden
+    for (l, d) in keys if hl else []:
+        # H-LSTM: hidden layers (W1x fused at batch 1, W1h) and gate outputs (W2); stepwise also moves the
+        # projected rows P1[t] and the hidden activations u_t (written by stage 1, read by stage 2)
+        p = case.weights[(l, d)]
+        comp = B.lstm_is_compressed(m.handle, l, d, 1)
+        w1h, w2 = mat_bytes(p, "W1h", "M1h", comp), mat_bytes(p, "W2", "M2", comp)
+        if persistent:
+            alg_bytes += mat_bytes(p, "W1x", "M1x", comp) + w1h + w2 + T * Bn * (p["W1x"].shape[1] * 4 + H * 4)
+        else:
+            alg_bytes += T * (w1h + w2 + Bn * (4 * G * 4 * 3 + H * 4 * 3))
+    for (l, d) in [] if hl else keys:
         p = case.weights[(l, d)]
         rec_compressed = B.lstm_is_compressed(m.handle, l, d, 1)
         wh = mat_bytes(p, "Wh", "Mh", rec_compressed)
@@ -196,6 +209,8 @@ def main():
         try:
             slots = H * layers_per_launch
             ex_us = B.lstm_bench_exchange(slots, 12 if wavefront else 0, 200, 5, stream, args.launch == "cooperative")
+            if hl:   # a step of the H-LSTM kernel has two exchanges (h: H values; hidden activations: 4G values);
+                ex_us *= 2.0   # the yardstick counts both at the size of the smaller one, i.e. it is a lower bound
             steps_seq = T + layers_per_launch - 1
             roofline["sequential_steps_per_launch"] = steps_seq
             roofline["step_us"] = rec_us / steps_seq
@@ -207,19 +222,19 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import lstm_oracle
+        from oracle import hlstm_oracle, lstm_oracle
         import dataclasses
         # bounded sample of the same workload: a few sequences (batch columns are independent), all T steps
         # except for the 1500-step bidirectional stack, which is cut to T'=30 and scaled (cost is linear in T)
-        nseq = {1: 64, 2: 8, 4: 2, 5: 8}.get(wl.cid, 4)
+        nseq = {1: 64, 2: 8, 4: 2, 5: 8, 6: 32, 7: 2}.get(wl.cid, 4)
         big = inputs.make_case(dataclasses.replace(wl, B=max(nseq, 1)), 0) if Bn < nseq else case
         sub = inputs.select_batch(big, list(range(nseq)))
         Tc = T
-        if wl.cid == 4:
+        if wl.cid in (4, 7):
             Tc = 30
             sub = dataclasses.replace(sub, x=sub.x[:Tc].copy())
         t1 = time.perf_counter()
-        lstm_oracle.forward_case(sub)
+        (hlstm_oracle if hl else lstm_oracle).forward_case(sub)
         cpu_s = time.perf_counter() - t1
         cpu_us_per_seq = cpu_s * 1e6 / nseq * (T / Tc)
         cpu = {"value": cpu_us_per_seq, "unit": "us/seq", "cores": lstm_oracle.max_threads(), "kind": "oracle",
@@ -231,7 +246,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if dtype == B.LSTM_BF16 else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.layers, "bidirectional": wl.bidirectional, "input_dim": wl.input_dim,
-                   "hidden": H, "T": T, "batch": Bn, "mask_keep": wl.keep, "format": args.format, "plan": plan_desc, "launch": args.launch},
+                   "hidden": H, "gate_hidden": wl.gate_hidden, "T": T, "batch": Bn, "mask_keep": wl.keep, "format": args.format, "plan": plan_desc, "launch": args.launch},
         "us_per_seq_other_launch_mode": other_mode,
         "timestep_batch_per_s": T * Bn / (ms_per_step * 1e-3),
         "roofline": roofline, "cpu_baseline": cpu,

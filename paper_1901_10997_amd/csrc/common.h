@@ -102,6 +102,32 @@ struct HStage2Args {
     float* cT;
     int last, B, H, G;
 };
+// Row-compressed H-LSTM step for small batches: both stages, one or both directions of a layer per launch pair.
+// The hidden activations travel between the stages gate-major: u[b][q*G + g].
+struct HStepDir {
+    const float* P1;         // [T*B][4G] packed rows
+    const float* h_prev;     // (b,k) at h_prev[b*h_prev_ld + k]; nullptr = zeros
+    int h_prev_ld;
+    float* u;                // [B][4G] gate-major scratch of this direction
+    const float* ell_val_1h; // W1h [4G][slots_1h][64]
+    const uint16_t* ell_col_1h;
+    const float* ell_val_2;  // W2 [4H][slots_2][64]
+    const uint16_t* ell_col_2;
+    int slots_1h, slots_2;
+    const float* bias2;      // [4H] packed
+    float* c;                // [B][H]
+    float* y_t;              // h_t -> y_t[b*y_ld + j]
+    int y_ld;
+    float* hT;
+    float* cT;
+    int t;
+};
+struct HStepPairArgs {
+    HStepDir d[2];
+    int B, H, G, last;
+};
+bool hstep_pair_supported(int H, int G, int slots_1h, int slots_2);
+hipError_t launch_hstep_pair(const HStepPairArgs& p, int ndir, hipStream_t s);
 hipError_t launch_hstage1(const HStage1Args& a, hipStream_t s);
 hipError_t launch_hstage2(const HStage2Args& a, hipStream_t s);
 

@@ -569,6 +569,59 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 HIP_TRY(m, launch_proj_dense(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s));
             }
         }
+        // small batch, every direction row-compressed: both stages of a step for all directions in two launches
+        bool pair_ok = B >= 1;
+        {
+            int nz1 = 1, nz2 = 1;
+            for (int d = 0; d < Dn; ++d) {
+                const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                pair_ok = pair_ok && !persist[d] && w.wh.compressed && w.w2.compressed && w.wh.ell_val && w.w2.ell_val;
+                nz1 = std::max(nz1, w.wh.slots);
+                nz2 = std::max(nz2, w.w2.slots);
+            }
+            pair_ok = pair_ok && hstep_pair_supported(H, G, nz1, nz2);
+        }
+        if (pair_ok) {
+            ProfSpan span(m, s, 1);
+            for (int d = 0; d < Dn; ++d) {
+                const size_t n = (size_t)l * Dn + d;
+                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
+                else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
+                std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=hlstm-stepwise-pair-csr;", l, d, proj_dense[d] ? "dense" : "csr");
+                m->last_plan += tag;
+            }
+            for (int step = 0; step < T; ++step) {
+                HStepPairArgs a{};
+                for (int d = 0; d < Dn; ++d) {
+                    const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                    const size_t n = (size_t)l * Dn + d;
+                    const int t = d ? (T - 1 - step) : step;
+                    HStepDir& q = a.d[d];
+                    q.P1 = P[d];
+                    if (step == 0) {
+                        q.h_prev = h0 ? h0 + n * B * H : nullptr;
+                        q.h_prev_ld = H;
+                    } else {
+                        const int tp = d ? t + 1 : t - 1;
+                        q.h_prev = Yout + (size_t)tp * B * y_ld + (size_t)d * H;
+                        q.h_prev_ld = y_ld;
+                    }
+                    q.u = U[d];
+                    q.ell_val_1h = w.wh.ell_val; q.ell_col_1h = w.wh.ell_col; q.slots_1h = w.wh.slots;
+                    q.ell_val_2 = w.w2.ell_val; q.ell_col_2 = w.w2.ell_col; q.slots_2 = w.w2.slots;
+                    q.bias2 = w.bias2;
+                    q.c = cbuf[d];
+                    q.y_t = Yout + (size_t)t * B * y_ld + (size_t)d * H;
+                    q.y_ld = y_ld;
+                    q.hT = hT ? hT + n * B * H : nullptr;
+                    q.cT = cT ? cT + n * B * H : nullptr;
+                    q.t = t;
+                }
+                a.B = B; a.H = H; a.G = G; a.last = (step == T - 1);
+                HIP_TRY(m, launch_hstep_pair(a, Dn, s));
+            }
+            continue;
+        }
         for (int d = 0; d < Dn; ++d) {
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             const size_t n = (size_t)l * Dn + d;

@@ -36,7 +36,14 @@ def test_hlstm_odd_shapes_stepwise(shape, fmt):
     L, bidir, D, H, G, T, Bn, keep = shape
     case = inputs.make_case(_hw(80, L, bidir, D, H, G, T, Bn, keep=keep), k=L + H + G, random_state=True)
     desc, _ = check_case(case, fmt, STEP)
-    assert "hlstm-stepwise" in desc
+    assert ("hlstm-stepwise-pair-csr" if fmt == CSR else "hlstm-stepwise-dense") in desc
+
+
+def test_hlstm_generic_compressed_kernels_for_long_rows():
+    """Rows with more than six 64-entry slices fall back from the paired small-batch kernels to the generic ones."""
+    case = inputs.make_case(_hw(80, 1, True, 30, 450, 420, 4, 3, a=0.1), k=9, random_state=True)
+    desc, _ = check_case(case, CSR, STEP)
+    assert "hlstm-stepwise-csr" in desc
 
 
 def test_hlstm_handle_kinds_do_not_mix():
