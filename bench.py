@@ -52,6 +52,12 @@ def parse():
                     help="launch mode of the persistent kernels (ordinary: residency by grid <= compute units on an "
                          "otherwise idle device; cooperative: guaranteed by the runtime, slower dispatch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-fine", action="store_true",
+                    help="fine-grained batch-1 latency profile around the register-tier boundaries (writes "
+                         "latency_sweep_fine.json into --out) and the growth targets of a few pruned dimensions")
+    ap.add_argument("--sweep-speech", action="store_true",
+                    help="model-level latency profile of the bidirectional speech stack at batch 16 over the hidden "
+                         "width (writes latency_sweep_speech.json into --out)")
     ap.add_argument("--compare-launch-modes", action="store_true", help="also time the loop in the other launch mode")
     ap.add_argument("--sweep", action="store_true", help="also run the hidden-size latency sweep (written to --out)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -264,6 +270,42 @@ def main():
                        "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2}, fh)
         out["sweep"] = {"points": len(Hs), "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2,
                         "min_us": float(min(med)), "max_us": float(max(med))}
+    if args.sweep_fine:
+        # batch 1, dense, step 4 around the tier boundaries of the fused persistent kernel, plus the language-model
+        # pair (hidden, input) = (H, H * 4 / 15) of the paper's pruned gates (1197 / 317 -> 1200 / 320)
+        os.makedirs(args.out, exist_ok=True)
+        B.lstm_set_default_launch_mode(args.launch == "cooperative")
+        res = {"launch": args.launch, "T": 35, "batch": 1, "curves": {}}
+        for name, Hs in (("dense_1x_H", list(range(960, 1089, 4)) + list(range(1216, 1377, 4))),
+                         ("dense_1x_H_in_4H15", list(range(1100, 1301, 4)) + [1197])):
+            Hs = sorted(set(Hs))
+            Ds = None if name == "dense_1x_H" else [max(1, round(h * 4 / 15)) for h in Hs]
+            med, p10, p90, _ = B.lstm_latency_sweep_model(Hs, Ds, T=35, B=1, warmup=10, iters=100, stream=stream)
+            f2, red2 = B.lstm_find_lhp(Hs, med, 0.02)
+            res["curves"][name] = {"H": Hs, "D": Ds, "median_us": list(med), "p10_us": list(p10), "p90_us": list(p90),
+                                   "is_lhp_eps2pct": [int(v) for v in f2], "redundancy_pct_eps2pct": red2}
+            if name == "dense_1x_H_in_4H15":
+                res["growth_targets_eps2pct"] = {str(d): B.lstm_grow_to_lhp(Hs, med, d, 0.02) for d in (1197, 1150, 1262)}
+        with open(os.path.join(args.out, "latency_sweep_fine.json"), "w") as fh:
+            json.dump(res, fh)
+        out["sweep_fine"] = {k: {"points": len(v["H"]), "redundancy_pct_eps2pct": v["redundancy_pct_eps2pct"]}
+                             for k, v in res["curves"].items()}
+        out["sweep_fine"]["growth_targets_eps2pct"] = res["growth_targets_eps2pct"]
+    if args.sweep_speech:
+        # the paper's model-level figure: latency of the bidirectional speech stack at batch 16 against the hidden
+        # width (here: 5 layers, 15 % kept weights as in workload c4, T = 100)
+        os.makedirs(args.out, exist_ok=True)
+        B.lstm_set_default_launch_mode(args.launch == "cooperative")
+        Hs = list(range(512, 1025, 32))
+        Ds = [640] * len(Hs)
+        med, p10, p90, _ = B.lstm_latency_sweep_model(Hs, Ds, layers=5, bidirectional=True, keep=0.15, T=100, B=16,
+                                                      warmup=2, iters=10, stream=stream)
+        f2, red2 = B.lstm_find_lhp(Hs, med, 0.02)
+        with open(os.path.join(args.out, "latency_sweep_speech.json"), "w") as fh:
+            json.dump({"launch": args.launch, "layers": 5, "bidirectional": True, "keep": 0.15, "T": 100, "batch": 16,
+                       "H": Hs, "median_us": list(med), "p10_us": list(p10), "p90_us": list(p90),
+                       "is_lhp_eps2pct": [int(v) for v in f2], "redundancy_pct_eps2pct": red2}, fh)
+        out["sweep_speech"] = {"points": len(Hs), "redundancy_pct_eps2pct": red2, "min_us": float(min(med)), "max_us": float(max(med))}
     m.close()
     print(json.dumps(out))
 

@@ -203,6 +203,20 @@ int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t 
                        uint8_t* is_lhp, void* stream);
 
 /*
+ * The same profile for a whole model family (paper Section 3, the model-level latency figure: latency against the
+ * model size set by the hidden-state width at batch 16; Section 5.1 step (c): the hysteresis points are located on
+ * the target device before the row/column growth).  Point i is a stack of `layers` layers, `bidirectional` in {0,1},
+ * hidden width Hs[i], input width Ds[i] (Ds = NULL: input width = hidden width); gate_hidden = 1 makes the cells
+ * H-LSTM cells whose gate hidden layers are as wide as the hidden state (fp32 only), 0 conventional cells.
+ * keep in (0,1): every matrix gets a seeded Bernoulli mask of that density and LSTM_FMT_AUTO; 0 or 1: dense.
+ * Weights ~ U(-0.1, 0.1), forget-gate output bias 1, x ~ N(0,1).  Outputs and timing protocol as
+ * lstm_latency_sweep.  All pointers HOST.
+ */
+int lstm_latency_sweep_model(const int* Hs, const int* Ds, int n, int layers, int bidirectional, int gate_hidden,
+                             double keep, int T, int B, int dtype, uint64_t seed, int warmup, int iters,
+                             double* med_us, double* p10_us, double* p90_us, uint8_t* is_lhp, void* stream);
+
+/*
  * Latency hysteresis points of a measured curve (paper Section 3).  A dimension is a latency
  * hysteresis point iff it is faster, by the relative margin eps, than every larger dimension:
  * lat[i] < (1 - eps) * lat[j] for all j with dims[j] > dims[i]; the largest dimension always is one.
@@ -210,6 +224,17 @@ int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t 
  * All pointers HOST; dims need not be sorted.  No GPU needed.
  */
 int lstm_find_lhp(const int* dims, const double* lat, int n, double eps, uint8_t* is_lhp, double* redundancy_pct);
+
+/*
+ * Growth target of the hardware-guided step (paper Section 4, row/column grow-and-prune: growth recovers the model
+ * to its hysteresis point; Section 5.1 step (c): a layer pruned to 1197 is grown back to the 1200 the device
+ * favours).  Among the measured dimensions, *target_dim receives the smallest latency hysteresis point (margin eps,
+ * as lstm_find_lhp) that is >= from_dim; *latency_gain_pct (may be NULL) the latency reduction in percent against
+ * the smallest measured dimension >= from_dim (from_dim itself when it was measured; 0 when that is the target).
+ * LSTM_ERR_ARG when from_dim exceeds every measured dimension.  All pointers HOST.  No GPU needed.
+ */
+int lstm_grow_to_lhp(const int* dims, const double* lat, int n, double eps, int from_dim, int* target_dim,
+                     double* latency_gain_pct);
 
 /* Measurement helpers (used by the benchmark to quote achievable peaks next to spec-sheet ones).
  * copy: device-to-device copy kernel of `bytes` bytes, `iters` times, returns the average microseconds.

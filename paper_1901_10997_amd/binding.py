@@ -26,7 +26,8 @@ EXPORTS = [
     "lstm_create", "lstm_create_h", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_set_weights_h",
     "lstm_workspace_bytes",
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
-    "lstm_latency_sweep", "lstm_find_lhp", "lstm_bench_copy", "lstm_bench_exchange",
+    "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_bench_copy",
+    "lstm_bench_exchange",
 ]
 
 _lib = None
@@ -85,6 +86,11 @@ def load(build_if_missing: bool = True):
     lib.lstm_get_compressed.argtypes = [vp, ci, ci, ci, c.POINTER(c.c_int64), vp, vp, vp]
     lib.lstm_latency_sweep.restype = ci
     lib.lstm_latency_sweep.argtypes = [vp, ci, ci, ci, ci, c.c_uint64, ci, ci, vp, vp, vp, vp, vp]
+    lib.lstm_latency_sweep_model.restype = ci
+    lib.lstm_latency_sweep_model.argtypes = [vp, vp, ci, ci, ci, ci, c.c_double, ci, ci, ci, c.c_uint64, ci, ci,
+                                             vp, vp, vp, vp, vp]
+    lib.lstm_grow_to_lhp.restype = ci
+    lib.lstm_grow_to_lhp.argtypes = [vp, vp, ci, c.c_double, ci, c.POINTER(ci), c.POINTER(c.c_double)]
     lib.lstm_find_lhp.restype = ci
     lib.lstm_find_lhp.argtypes = [vp, vp, ci, c.c_double, vp, c.POINTER(c.c_double)]
     lib.lstm_bench_copy.restype = ci
@@ -227,6 +233,34 @@ def lstm_latency_sweep(Hs: Sequence[int], T: int, B: int, dtype: int = LSTM_F32,
     _check(load().lstm_latency_sweep(Hs.ctypes.data, n, T, B, dtype, seed, warmup, iters, med.ctypes.data,
                                      p10.ctypes.data, p90.ctypes.data, flags.ctypes.data, stream))
     return med, p10, p90, flags
+
+
+def lstm_latency_sweep_model(Hs: Sequence[int], Ds: Optional[Sequence[int]] = None, *, layers: int = 1,
+                             bidirectional: bool = False, gate_hidden: bool = False, keep: float = 0.0, T: int = 35,
+                             B: int = 1, dtype: int = LSTM_F32, seed: int = 1, warmup: int = 10, iters: int = 100,
+                             stream: Optional[int] = None):
+    Hs = np.ascontiguousarray(Hs, dtype=np.int32)
+    n = len(Hs)
+    if Ds is not None:
+        Ds = np.ascontiguousarray(Ds, dtype=np.int32)
+        assert len(Ds) == n
+    med, p10, p90 = np.zeros(n), np.zeros(n), np.zeros(n)
+    flags = np.zeros(n, np.uint8)
+    _check(load().lstm_latency_sweep_model(Hs.ctypes.data, None if Ds is None else Ds.ctypes.data, n, layers,
+                                           int(bool(bidirectional)), int(bool(gate_hidden)), float(keep), T, B, dtype,
+                                           seed, warmup, iters, med.ctypes.data, p10.ctypes.data, p90.ctypes.data,
+                                           flags.ctypes.data, stream))
+    return med, p10, p90, flags
+
+
+def lstm_grow_to_lhp(dims: Sequence[int], lat: Sequence[float], from_dim: int, eps: float = 0.0):
+    dims = np.ascontiguousarray(dims, dtype=np.int32)
+    lat = np.ascontiguousarray(lat, dtype=np.float64)
+    target = ctypes.c_int()
+    gain = ctypes.c_double()
+    _check(load().lstm_grow_to_lhp(dims.ctypes.data, lat.ctypes.data, len(dims), eps, from_dim, ctypes.byref(target),
+                                   ctypes.byref(gain)))
+    return target.value, gain.value
 
 
 def lstm_find_lhp(dims: Sequence[int], lat: Sequence[float], eps: float = 0.0):

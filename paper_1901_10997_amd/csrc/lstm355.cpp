@@ -1176,30 +1176,63 @@ double percentile(std::vector<double> v, double p)
 }
 }  // namespace
 
-int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t seed, int warmup, int iters,
-                       double* med_us, double* p10_us, double* p90_us, uint8_t* is_lhp, void* stream)
+int lstm_latency_sweep_model(const int* Hs, const int* Ds, int n, int layers, int bidirectional, int gate_hidden,
+                             double keep, int T, int B, int dtype, uint64_t seed, int warmup, int iters,
+                             double* med_us, double* p10_us, double* p90_us, uint8_t* is_lhp, void* stream)
 {
-    if (nH < 0 || (nH > 0 && (!Hs || !med_us)) || T < 1 || B < 1 || warmup < 0 || iters < 1)
-        return fail(nullptr, LSTM_ERR_ARG, "lstm_latency_sweep: bad arguments");
+    if (n < 0 || (n > 0 && (!Hs || !med_us)) || layers < 1 || (bidirectional != 0 && bidirectional != 1) || T < 1 ||
+        B < 1 || warmup < 0 || iters < 1 || !(keep >= 0.0) || keep > 1.0 || (gate_hidden != 0 && gate_hidden != 1))
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_latency_sweep_model: bad arguments");
+    const bool masked = keep > 0.0 && keep < 1.0;
+    const int Dn = bidirectional ? 2 : 1;
     hipStream_t s = (hipStream_t)stream;
     hipEvent_t e0, e1;
     HIP_TRY(nullptr, hipEventCreate(&e0));
     HIP_TRY(nullptr, hipEventCreate(&e1));
     int rc = LSTM_OK;
-    for (int idx = 0; idx < nH && rc == LSTM_OK; ++idx) {
-        const int H = Hs[idx];
+    for (int idx = 0; idx < n && rc == LSTM_OK; ++idx) {
+        const int H = Hs[idx], D0 = Ds ? Ds[idx] : H, G = gate_hidden ? H : 0;
         lstm_t* m = nullptr;
-        rc = lstm_create(1, H, H, 0, dtype, &m);
+        rc = G ? lstm_create_h(layers, D0, H, G, bidirectional, dtype, &m) : lstm_create(layers, D0, H, bidirectional, dtype, &m);
         if (rc != LSTM_OK) break;
         SplitMix rng{seed + 0x1000ull * (uint64_t)idx};
-        std::vector<float> Wx((size_t)4 * H * H), Wh((size_t)4 * H * H), b((size_t)4 * H, 0.0f);
-        for (auto& v : Wx) v = (float)(0.2 * rng.uniform() - 0.1);
-        for (auto& v : Wh) v = (float)(0.2 * rng.uniform() - 0.1);
-        for (int j = 0; j < H; ++j) b[j] = 1.0f;
-        rc = lstm_set_weights(m, 0, 0, Wx.data(), nullptr, Wh.data(), nullptr, b.data(), LSTM_FMT_DENSE_MASKED);
+        auto draw = [&](std::vector<float>& W, std::vector<uint8_t>& M, size_t count) {
+            W.resize(count);
+            for (auto& v : W) v = (float)(0.2 * rng.uniform() - 0.1);
+            M.clear();
+            if (masked) {
+                M.resize(count);
+                for (auto& v : M) v = rng.uniform() < keep ? 1 : 0;
+            }
+        };
+        std::vector<float> A, Bm, C, b1, b2;
+        std::vector<uint8_t> MA, MB, MC;
+        for (int l = 0; l < layers && rc == LSTM_OK; ++l) {
+            const int D = l == 0 ? D0 : Dn * H;
+            for (int d = 0; d < Dn && rc == LSTM_OK; ++d) {
+                if (G) {
+                    draw(A, MA, (size_t)4 * G * D);
+                    draw(Bm, MB, (size_t)4 * G * H);
+                    draw(C, MC, (size_t)4 * H * G);
+                    b1.assign((size_t)4 * G, 0.0f);
+                    b2.assign((size_t)4 * H, 0.0f);
+                    for (int j = 0; j < H; ++j) b2[j] = 1.0f;
+                    rc = lstm_set_weights_h(m, l, d, A.data(), masked ? MA.data() : nullptr, Bm.data(), masked ? MB.data() : nullptr,
+                                            b1.data(), C.data(), masked ? MC.data() : nullptr, b2.data(), LSTM_FMT_AUTO);
+                } else {
+                    draw(A, MA, (size_t)4 * H * D);
+                    draw(Bm, MB, (size_t)4 * H * H);
+                    b1.assign((size_t)4 * H, 0.0f);
+                    for (int j = 0; j < H; ++j) b1[j] = 1.0f;
+                    rc = lstm_set_weights(m, l, d, A.data(), masked ? MA.data() : nullptr, Bm.data(), masked ? MB.data() : nullptr,
+                                          b1.data(), masked ? LSTM_FMT_AUTO : LSTM_FMT_DENSE_MASKED);
+                }
+                if (rc != LSTM_OK) g_create_error = lstm_last_error(m);
+            }
+        }
         void *dx = nullptr, *dy = nullptr, *dws = nullptr;
-        const size_t xelems = (size_t)T * B * H;
-        const size_t wsb = lstm_workspace_bytes(m, T, B);
+        const size_t xelems = (size_t)T * B * D0, yelems = (size_t)T * B * Dn * H;
+        const size_t wsb = rc == LSTM_OK ? lstm_workspace_bytes(m, T, B) : 0;
         hipError_t e = hipSuccess;
         if (rc == LSTM_OK) {
             std::vector<float> xf(xelems);
@@ -1213,9 +1246,9 @@ int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t 
                 e = hipMalloc(&dx, xelems * 4);
                 if (e == hipSuccess) e = hipMemcpy(dx, xf.data(), xelems * 4, hipMemcpyHostToDevice);
             }
-            if (e == hipSuccess) e = hipMalloc(&dy, xelems * 4);
+            if (e == hipSuccess) e = hipMalloc(&dy, yelems * 4);
             if (e == hipSuccess) e = hipMalloc(&dws, wsb);
-            if (e != hipSuccess) rc = fail_hip(nullptr, e, "lstm_latency_sweep: device buffers");
+            if (e != hipSuccess) rc = fail_hip(nullptr, e, "lstm_latency_sweep_model: device buffers");
         }
         std::vector<double> times;
         for (int it = 0; it < warmup + iters && rc == LSTM_OK; ++it) {
@@ -1226,7 +1259,7 @@ int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t 
             if (e == hipSuccess) e = hipEventSynchronize(e1);
             float ms = 0.f;
             if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-            if (e != hipSuccess) { rc = fail_hip(nullptr, e, "lstm_latency_sweep: timing"); break; }
+            if (e != hipSuccess) { rc = fail_hip(nullptr, e, "lstm_latency_sweep_model: timing"); break; }
             if (it >= warmup) times.push_back((double)ms * 1000.0);
         }
         if (rc == LSTM_OK) {
@@ -1245,8 +1278,39 @@ int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t 
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
-    if (rc == LSTM_OK && is_lhp && nH > 0) rc = lstm_find_lhp(Hs, med_us, nH, 0.0, is_lhp, nullptr);
+    if (rc == LSTM_OK && is_lhp && n > 0) rc = lstm_find_lhp(Hs, med_us, n, 0.0, is_lhp, nullptr);
     return rc;
+}
+
+int lstm_latency_sweep(const int* Hs, int nH, int T, int B, int dtype, uint64_t seed, int warmup, int iters,
+                       double* med_us, double* p10_us, double* p90_us, uint8_t* is_lhp, void* stream)
+{
+    return lstm_latency_sweep_model(Hs, nullptr, nH, 1, 0, 0, 0.0, T, B, dtype, seed, warmup, iters, med_us, p10_us,
+                                    p90_us, is_lhp, stream);
+}
+
+int lstm_grow_to_lhp(const int* dims, const double* lat, int n, double eps, int from_dim, int* target_dim,
+                     double* latency_gain_pct)
+{
+    if (n < 1 || !dims || !lat || !target_dim || !(eps >= 0.0) || eps >= 1.0)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_grow_to_lhp: bad arguments");
+    std::vector<uint8_t> flags((size_t)n);
+    const int rc = lstm_find_lhp(dims, lat, n, eps, flags.data(), nullptr);
+    if (rc != LSTM_OK) return rc;
+    // the smallest measured hysteresis point that is not below from_dim
+    int best = -1;
+    for (int i = 0; i < n; ++i)
+        if (flags[i] && dims[i] >= from_dim && (best < 0 || dims[i] < dims[best])) best = i;
+    if (best < 0) return fail(nullptr, LSTM_ERR_ARG, "lstm_grow_to_lhp: from_dim is above every measured dimension");
+    *target_dim = dims[best];
+    if (latency_gain_pct) {
+        // against the smallest measured dimension that is not below from_dim (from_dim itself when it was measured)
+        int ref = -1;
+        for (int i = 0; i < n; ++i)
+            if (dims[i] >= from_dim && (ref < 0 || dims[i] < dims[ref])) ref = i;
+        *latency_gain_pct = (1.0 - lat[best] / lat[ref]) * 100.0;
+    }
+    return LSTM_OK;
 }
 
 int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double* avg_us, void* stream)

@@ -285,3 +285,20 @@ def test_c4_full_sampled_columns():
 def test_c5_full_sampled_columns():
     for k in (0, 1, 2):
         check_case(inputs.make_case(inputs.c5(), k, random_state=(k == 2)), AUTO, oracle_cols=[0, 131, 255] if k == 0 else [77])
+
+
+def test_model_level_latency_sweep_runs_every_family():
+    """lstm_latency_sweep_model: stacked / bidirectional / masked / H-LSTM points all produce a positive latency and
+    flags that agree with lstm_find_lhp on the returned curve."""
+    Hs = [96, 64, 128]
+    for kw in (dict(layers=1), dict(layers=2, bidirectional=True, keep=0.3, B=3, T=6),
+               dict(layers=1, gate_hidden=True, keep=0.2, T=5), dict(layers=2, gate_hidden=True, B=2, T=4),
+               dict(layers=2, dtype=B.LSTM_BF16, B=40, T=3)):
+        args = dict(T=8, B=1, warmup=1, iters=3)
+        args.update(kw)
+        med, p10, p90, flags = B.lstm_latency_sweep_model(Hs, [48, 32, 200], **args)
+        assert np.all(med > 0) and np.all(p10 <= med + 1e-9) and np.all(med <= p90 + 1e-9)
+        ref, _ = B.lstm_find_lhp(Hs, med, 0.0)
+        np.testing.assert_array_equal(flags, ref)
+    with pytest.raises(B.LstmError):
+        B.lstm_latency_sweep_model(Hs, None, gate_hidden=True, dtype=B.LSTM_BF16, warmup=0, iters=1)

@@ -75,3 +75,35 @@ def test_lhp_hand_example():
     assert abs(red - (1 - 2 / 7) * 100) < 1e-12
     with pytest.raises(B.LstmError):
         B.lstm_find_lhp(dims, lat, 1.5)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+@pytest.mark.parametrize("eps", [0.0, 0.03])
+def test_grow_to_lhp_matches_definition(seed, eps):
+    rng = np.random.default_rng(50 + seed)
+    n = 40
+    dims = rng.permutation(np.arange(64, 64 + 8 * n, 8)).astype(np.int32)
+    lat = 20.0 + 0.01 * dims + rng.choice([0.0, 0.5, 2.0], size=n) + rng.uniform(0, 0.3, n)
+    for from_dim in (int(dims.min()) - 3, int(np.sort(dims)[n // 2]), int(np.sort(dims)[n // 2]) + 1, int(dims.max())):
+        target, gain = B.lstm_grow_to_lhp(dims, lat, from_dim, eps)
+        ref_target, ref_gain = olhp.grow_to_lhp(list(dims), list(lat), from_dim, eps)
+        assert target == ref_target
+        assert abs(gain - ref_gain) < 1e-9
+        assert target >= from_dim
+        if eps == 0.0:
+            assert gain >= -1e-12      # the target is faster than everything above it, the reference included
+    with pytest.raises(B.LstmError):
+        B.lstm_grow_to_lhp(dims, lat, int(dims.max()) + 1, eps)
+
+
+def test_grow_to_lhp_hand_example():
+    """A staircase: 1197 sits on the same tier as 1200 (cost set by the tier), so growing to 1200 costs nothing and the
+    target of everything in (1168, 1200] is 1200; a point that is itself a hysteresis point stays where it is."""
+    dims = [1136, 1168, 1197, 1200, 1232, 1264]
+    lat = [70.0, 70.1, 75.2, 75.0, 75.1, 80.0]
+    assert B.lstm_grow_to_lhp(dims, lat, 1197)[0] == 1200
+    t, gain = B.lstm_grow_to_lhp(dims, lat, 1197)
+    assert abs(gain - (1 - 75.0 / 75.2) * 100) < 1e-9
+    assert B.lstm_grow_to_lhp(dims, lat, 1169)[0] == 1200
+    assert B.lstm_grow_to_lhp(dims, lat, 1168) == (1168, 0.0)
+    assert B.lstm_grow_to_lhp(dims, lat, 1201)[0] == 1232    # only larger dimensions count: 1232 beats 1264
