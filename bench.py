@@ -55,6 +55,9 @@ def parse():
     ap.add_argument("--sweep-fine", action="store_true",
                     help="fine-grained batch-1 latency profile around the register-tier boundaries (writes "
                          "latency_sweep_fine.json into --out) and the growth targets of a few pruned dimensions")
+    ap.add_argument("--sweep-matmul", action="store_true",
+                    help="stand-alone product latency against the dimension for dense and row-compressed weights at "
+                         "batch 16 (writes matmul_sweep.json into --out)")
     ap.add_argument("--sweep-speech", action="store_true",
                     help="model-level latency profile of the bidirectional speech stack at batch 16 over the hidden "
                          "width (writes latency_sweep_speech.json into --out)")
@@ -291,6 +294,19 @@ def main():
         out["sweep_fine"] = {k: {"points": len(v["H"]), "redundancy_pct_eps2pct": v["redundancy_pct_eps2pct"]}
                              for k, v in res["curves"].items()}
         out["sweep_fine"]["growth_targets_eps2pct"] = res["growth_targets_eps2pct"]
+    if args.sweep_matmul:
+        os.makedirs(args.out, exist_ok=True)
+        ns = list(range(256, 4097, 128))
+        keeps = [0.5, 0.3, 0.1, 0.05]
+        res = {"batch": 16, "n": ns, "dense_us": [B.lstm_bench_matmul(n, 16, 1.0, B.LSTM_FMT_DENSE_MASKED, iters=50, stream=stream) for n in ns],
+               "compressed_us": {str(k): [B.lstm_bench_matmul(n, 16, k, B.LSTM_FMT_ROW_COMPRESSED, iters=50, stream=stream) for n in ns]
+                                 for k in keeps}}
+        f2, red2 = B.lstm_find_lhp(ns, res["dense_us"], 0.02)
+        res["dense_is_lhp_eps2pct"] = [int(v) for v in f2]
+        res["dense_redundancy_pct_eps2pct"] = red2
+        with open(os.path.join(args.out, "matmul_sweep.json"), "w") as fh:
+            json.dump(res, fh)
+        out["sweep_matmul"] = {"points": len(ns), "dense_redundancy_pct_eps2pct": red2}
     if args.sweep_speech:
         # the paper's model-level figure: latency of the bidirectional speech stack at batch 16 against the hidden
         # width (here: 5 layers, 15 % kept weights as in workload c4, T = 100)

@@ -242,6 +242,19 @@ int lstm_grow_to_lhp(const int* dims, const double* lat, int n, double eps, int 
  * workgroups of `waves` waves (launched cooperatively or not, see lstm_set_launch_mode); returns the average
  * microseconds per round.  DEVICE pointers where named. */
 int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double* avg_us, void* stream);
+
+/*
+ * Stand-alone product Y[batch, n] = X[batch, n] . W[n, n]^T with a dense input batch and a square weight matrix of
+ * which a fraction `keep` in (0, 1] is kept (paper Section 3, the two matrix-multiplication latency figures: latency
+ * against the dimension for dense and sparse operands).  format LSTM_FMT_DENSE_MASKED runs the library's dense
+ * projection (zeros stored), LSTM_FMT_ROW_COMPRESSED its row-compressed one (including the transpose of X that
+ * product needs).  W ~ U(-0.1, 0.1), mask Bernoulli(keep), X ~ N(0,1), all from `seed` with one fixed generator, so
+ * both formats see the same operands.  n a multiple of 4.  *avg_us: average over `iters` launches after 3 warm-up
+ * launches.  y_host (HOST, [batch, n], may be NULL) receives the product.  Allocates and frees its own device
+ * buffers; synchronises the stream.
+ */
+int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, double* avg_us,
+                      float* y_host, void* stream);
 int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream);
 
 #ifdef __cplusplus

@@ -27,7 +27,7 @@ EXPORTS = [
     "lstm_workspace_bytes",
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
     "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_bench_copy",
-    "lstm_bench_exchange",
+    "lstm_bench_matmul", "lstm_bench_exchange",
 ]
 
 _lib = None
@@ -91,6 +91,8 @@ def load(build_if_missing: bool = True):
                                              vp, vp, vp, vp, vp]
     lib.lstm_grow_to_lhp.restype = ci
     lib.lstm_grow_to_lhp.argtypes = [vp, vp, ci, c.c_double, ci, c.POINTER(ci), c.POINTER(c.c_double)]
+    lib.lstm_bench_matmul.restype = ci
+    lib.lstm_bench_matmul.argtypes = [ci, ci, c.c_double, ci, c.c_uint64, ci, c.POINTER(c.c_double), vp, vp]
     lib.lstm_find_lhp.restype = ci
     lib.lstm_find_lhp.argtypes = [vp, vp, ci, c.c_double, vp, c.POINTER(c.c_double)]
     lib.lstm_bench_copy.restype = ci
@@ -276,6 +278,15 @@ def lstm_bench_copy(dst_ptr: int, src_ptr: int, nbytes: int, iters: int = 20, st
     us = ctypes.c_double()
     _check(load().lstm_bench_copy(dst_ptr, src_ptr, nbytes, iters, ctypes.byref(us), stream))
     return us.value
+
+
+def lstm_bench_matmul(n: int, batch: int, keep: float, fmt: int, seed: int = 1, iters: int = 20, want_product: bool = False,
+                      stream: Optional[int] = None):
+    us = ctypes.c_double()
+    y = np.zeros((batch, n), np.float32) if want_product else None
+    _check(load().lstm_bench_matmul(n, batch, float(keep), fmt, seed, iters, ctypes.byref(us),
+                                    None if y is None else y.ctypes.data, stream))
+    return (us.value, y) if want_product else us.value
 
 
 def lstm_bench_exchange(hidden: int, waves: int = 0, steps: int = 200, iters: int = 5, stream: Optional[int] = None,

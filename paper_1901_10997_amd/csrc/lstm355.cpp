@@ -1313,6 +1313,73 @@ int lstm_grow_to_lhp(const int* dims, const double* lat, int n, double eps, int 
     return LSTM_OK;
 }
 
+int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, double* avg_us,
+                      float* y_host, void* stream)
+{
+    if (n < 4 || n > 65536 || (n & 3) || batch < 1 || batch > 4096 || !(keep > 0.0) || keep > 1.0 || iters < 1 || !avg_us ||
+        (format != LSTM_FMT_DENSE_MASKED && format != LSTM_FMT_ROW_COMPRESSED))
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_matmul: bad arguments (n must be a multiple of 4)");
+    hipStream_t s = (hipStream_t)stream;
+    SplitMix rng{seed};
+    const size_t nn = (size_t)n * n;
+    std::vector<float> W(nn), X((size_t)batch * n), bias((size_t)n, 0.0f);
+    for (auto& v : X) v = (float)rng.normal();
+    std::vector<int32_t> rp((size_t)n + 1, 0);
+    std::vector<uint16_t> col;
+    std::vector<float> val;
+    for (int r = 0; r < n; ++r) {
+        for (int k = 0; k < n; ++k) {
+            const float w = (float)(0.2 * rng.uniform() - 0.1);
+            const bool kept = keep >= 1.0 || rng.uniform() < keep;
+            W[(size_t)r * n + k] = kept ? w : 0.0f;
+            if (kept && format == LSTM_FMT_ROW_COMPRESSED) { col.push_back((uint16_t)k); val.push_back(w); }
+        }
+        rp[(size_t)r + 1] = (int32_t)col.size();
+    }
+    float *dX = nullptr, *dW = nullptr, *dB = nullptr, *dY = nullptr, *dXT = nullptr, *dval = nullptr;
+    int32_t* drp = nullptr;
+    uint16_t* dcol = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = LSTM_OK;
+    auto run = [&]() -> hipError_t {
+        if (format == LSTM_FMT_ROW_COMPRESSED) {
+            hipError_t e = launch_transpose_to_f32(dX, false, n, dXT, batch, n, false, s);
+            if (e != hipSuccess) return e;
+            return launch_proj_csr(dXT, drp, dcol, dval, dB, dY, batch, n, s);
+        }
+        if (proj_mfma_supported(false, n, n)) return launch_proj_mfma(dX, false, n, dW, false, dB, dY, batch, n, n, s);
+        return launch_proj_dense(dX, false, n, dW, false, dB, dY, batch, n, n, s);
+    };
+    hipError_t e = upload(&dX, X);
+    if (e == hipSuccess) e = upload(&dB, bias);
+    if (e == hipSuccess) e = hipMalloc((void**)&dY, (size_t)batch * n * sizeof(float));
+    if (e == hipSuccess && format == LSTM_FMT_ROW_COMPRESSED) {
+        e = upload(&drp, rp);
+        if (e == hipSuccess) e = upload(&dcol, col);
+        if (e == hipSuccess) e = upload(&dval, val);
+        if (e == hipSuccess) e = hipMalloc((void**)&dXT, (size_t)batch * n * sizeof(float));
+    } else if (e == hipSuccess) {
+        e = upload(&dW, W);
+    }
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    for (int i = 0; i < 3 && e == hipSuccess; ++i) e = run();
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int i = 0; i < iters && e == hipSuccess; ++i) e = run();
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess && y_host) e = hipMemcpy(y_host, dY, (size_t)batch * n * sizeof(float), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) rc = fail_hip(nullptr, e, "lstm_bench_matmul");
+    else *avg_us = (double)ms * 1000.0 / iters;
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    for (void* p_ : {(void*)dX, (void*)dW, (void*)dB, (void*)dY, (void*)dXT, (void*)dval, (void*)drp, (void*)dcol})
+        if (p_) (void)hipFree(p_);
+    return rc;
+}
+
 int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double* avg_us, void* stream)
 {
     if (!dst || !src || !avg_us || iters < 1 || bytes == 0 || (bytes & 15))

@@ -302,3 +302,17 @@ def test_model_level_latency_sweep_runs_every_family():
         np.testing.assert_array_equal(flags, ref)
     with pytest.raises(B.LstmError):
         B.lstm_latency_sweep_model(Hs, None, gate_hidden=True, dtype=B.LSTM_BF16, warmup=0, iters=1)
+
+
+@pytest.mark.parametrize("n,batch,keep", [(64, 16, 0.5), (260, 16, 0.1), (512, 5, 1.0), (1000, 16, 0.05), (132, 70, 0.3)])
+def test_standalone_product_dense_and_compressed_agree(n, batch, keep):
+    """lstm_bench_matmul: both formats multiply the same seeded operands; the products agree to fp32 summation order
+    and have the scale the operand distributions imply (variance n * keep * E[w^2] * E[x^2] = n * keep / 300)."""
+    _, yd = B.lstm_bench_matmul(n, batch, keep, DENSE, seed=7, iters=2, want_product=True)
+    _, yc = B.lstm_bench_matmul(n, batch, keep, CSR, seed=7, iters=2, want_product=True)
+    assert np.all(np.isfinite(yd))
+    np.testing.assert_allclose(yc, yd, rtol=0, atol=2e-5)
+    var = float(np.mean(yd.astype(np.float64) ** 2))
+    assert 0.6 * n * keep / 300 < var < 1.6 * n * keep / 300
+    _, other = B.lstm_bench_matmul(n, batch, keep, DENSE, seed=8, iters=1, want_product=True)
+    assert np.max(np.abs(other - yd)) > 1e-3
