@@ -236,6 +236,32 @@ int lstm_find_lhp(const int* dims, const double* lat, int n, double eps, uint8_t
 int lstm_grow_to_lhp(const int* dims, const double* lat, int n, double eps, int from_dim, int* target_dim,
                      double* latency_gain_pct);
 
+/*
+ * Mask updates of the pruning phases, on DEVICE arrays (paper Section 4).
+ *
+ * lstm_prune_weights: one iteration of magnitude-based weight pruning ("Msk(w) = 0 iff |w| <= the (100 p_w)-th
+ * percentile of |W|").  W fp32 [count], mask uint8 [count] in {0,1}, updated in place; W is not changed.  The
+ * percentile is taken over the connections that are still active (mask 1): with k = ceil(p_w * active), every active
+ * entry whose magnitude is at or below the k-th smallest active magnitude is switched off (ties go together; k = 0
+ * prunes nothing).  What lies under a zero mask byte is never looked at.  *kept_before / *kept_after (HOST, may be
+ * NULL) receive the number of active entries before and after.  count < 2^32 - 1.
+ *
+ * lstm_prune_rows_cols: one iteration of the paper's row/column pruning algorithm on one matrix W [M, N] (row-major)
+ * with its mask.  Importance of a row / column = sum of the magnitudes of its active entries.  Thresholds: the
+ * ceil(p_r * M)-th smallest row sum and the ceil(p_c * N)-th smallest column sum, both of the matrix as passed in.
+ * Rows at or below the row threshold are removed first (mask bytes and weights set to zero), then the columns whose
+ * sum over the matrix as the row pass left it is at or below the column threshold.  A ratio of 0 removes nothing
+ * along that axis.  Sums are accumulated in fp32.  *rows_removed / *cols_removed (HOST, may be NULL) receive how many
+ * rows / columns this call zeroed.
+ *
+ * Both allocate and free their own scratch and synchronise the stream.  The packed form of a model is not touched:
+ * pass the new masks to lstm_set_weights / lstm_set_weights_h to run the pruned model.
+ */
+int lstm_prune_weights(const float* W, uint8_t* mask, size_t count, double p_w, size_t* kept_before, size_t* kept_after,
+                       void* stream);
+int lstm_prune_rows_cols(float* W, uint8_t* mask, int M, int N, double p_r, double p_c, int* rows_removed,
+                         int* cols_removed, void* stream);
+
 /* Measurement helpers (used by the benchmark to quote achievable peaks next to spec-sheet ones).
  * copy: device-to-device copy kernel of `bytes` bytes, `iters` times, returns the average microseconds.
  * barrier: `steps` rounds of the hidden-state exchange with no arithmetic, for `hidden` units and `groups`

@@ -26,8 +26,8 @@ EXPORTS = [
     "lstm_create", "lstm_create_h", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_set_weights_h",
     "lstm_workspace_bytes",
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
-    "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_bench_copy",
-    "lstm_bench_matmul", "lstm_bench_exchange",
+    "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_prune_weights", "lstm_prune_rows_cols",
+    "lstm_bench_copy", "lstm_bench_matmul", "lstm_bench_exchange",
 ]
 
 _lib = None
@@ -91,6 +91,10 @@ def load(build_if_missing: bool = True):
                                              vp, vp, vp, vp, vp]
     lib.lstm_grow_to_lhp.restype = ci
     lib.lstm_grow_to_lhp.argtypes = [vp, vp, ci, c.c_double, ci, c.POINTER(ci), c.POINTER(c.c_double)]
+    lib.lstm_prune_weights.restype = ci
+    lib.lstm_prune_weights.argtypes = [vp, vp, c.c_size_t, c.c_double, c.POINTER(c.c_size_t), c.POINTER(c.c_size_t), vp]
+    lib.lstm_prune_rows_cols.restype = ci
+    lib.lstm_prune_rows_cols.argtypes = [vp, vp, ci, ci, c.c_double, c.c_double, c.POINTER(ci), c.POINTER(ci), vp]
     lib.lstm_bench_matmul.restype = ci
     lib.lstm_bench_matmul.argtypes = [ci, ci, c.c_double, ci, c.c_uint64, ci, c.POINTER(c.c_double), vp, vp]
     lib.lstm_find_lhp.restype = ci
@@ -278,6 +282,20 @@ def lstm_bench_copy(dst_ptr: int, src_ptr: int, nbytes: int, iters: int = 20, st
     us = ctypes.c_double()
     _check(load().lstm_bench_copy(dst_ptr, src_ptr, nbytes, iters, ctypes.byref(us), stream))
     return us.value
+
+
+def lstm_prune_weights(W_ptr: int, mask_ptr: int, count: int, p_w: float, stream: Optional[int] = None):
+    """Device pointers; returns (active before, active after)."""
+    before, after = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load().lstm_prune_weights(W_ptr, mask_ptr, count, float(p_w), ctypes.byref(before), ctypes.byref(after), stream))
+    return before.value, after.value
+
+
+def lstm_prune_rows_cols(W_ptr: int, mask_ptr: int, M: int, N: int, p_r: float, p_c: float, stream: Optional[int] = None):
+    """Device pointers; returns (rows removed, columns removed)."""
+    r, cc = ctypes.c_int(), ctypes.c_int()
+    _check(load().lstm_prune_rows_cols(W_ptr, mask_ptr, M, N, float(p_r), float(p_c), ctypes.byref(r), ctypes.byref(cc), stream))
+    return r.value, cc.value
 
 
 def lstm_bench_matmul(n: int, batch: int, keep: float, fmt: int, seed: int = 1, iters: int = 20, want_product: bool = False,

@@ -297,6 +297,12 @@ struct PersistBatchedArgs {
 bool persist_batched_plan(int B, int H, int nz, int ndir, int* upw, int* bw, int* ug, int* bg);
 hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int cooperative, hipStream_t s);
 
+// Pruning mask updates (device arrays; scratch supplied by the caller of the launcher).
+size_t prune_state_bytes();
+hipError_t launch_prune_weights(const float* W, uint8_t* mask, size_t count, double p_w, unsigned* keys, void* state,
+                                unsigned long long* counters, hipStream_t s);
+hipError_t launch_prune_rows_cols(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols, float* sums,
+                                  unsigned* keys, void* state_r, void* state_c, int* removed, hipStream_t s);
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);

@@ -1313,6 +1313,59 @@ int lstm_grow_to_lhp(const int* dims, const double* lat, int n, double eps, int 
     return LSTM_OK;
 }
 
+int lstm_prune_weights(const float* W, uint8_t* mask, size_t count, double p_w, size_t* kept_before, size_t* kept_after,
+                       void* stream)
+{
+    if (!W || !mask || count == 0 || count > ((size_t)1 << 32) - 2 || !(p_w >= 0.0) || p_w > 1.0)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_prune_weights: bad arguments");
+    hipStream_t s = (hipStream_t)stream;
+    unsigned* keys = nullptr;
+    char* small = nullptr;   // state | two counters
+    const size_t st_bytes = align256(prune_state_bytes());
+    hipError_t e = hipMalloc((void**)&keys, count * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMalloc((void**)&small, st_bytes + 256);
+    unsigned long long host_cnt[2] = {0, 0};
+    if (e == hipSuccess) e = launch_prune_weights(W, mask, count, p_w, keys, small, (unsigned long long*)(small + st_bytes), s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipMemcpy(host_cnt, small + st_bytes, sizeof host_cnt, hipMemcpyDeviceToHost);
+    if (keys) (void)hipFree(keys);
+    if (small) (void)hipFree(small);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "lstm_prune_weights");
+    if (kept_before) *kept_before = (size_t)host_cnt[0];
+    if (kept_after) *kept_after = (size_t)host_cnt[1];
+    return LSTM_OK;
+}
+
+int lstm_prune_rows_cols(float* W, uint8_t* mask, int M, int N, double p_r, double p_c, int* rows_removed,
+                         int* cols_removed, void* stream)
+{
+    if (!W || !mask || M < 1 || N < 1 || (long long)M * N > (1ll << 31) || !(p_r >= 0.0) || p_r > 1.0 || !(p_c >= 0.0) ||
+        p_c > 1.0)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_prune_rows_cols: bad arguments");
+    hipStream_t s = (hipStream_t)stream;
+    const unsigned kr = (unsigned)std::min<double>(std::ceil(p_r * M), M), kc = (unsigned)std::min<double>(std::ceil(p_c * N), N);
+    const size_t st_bytes = align256(prune_state_bytes());
+    const size_t big = (size_t)std::max(M, N);
+    float* sums = nullptr;
+    unsigned* keys = nullptr;
+    char* small = nullptr;   // two states | two ints
+    hipError_t e = hipMalloc((void**)&sums, ((size_t)M + N) * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&keys, big * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMalloc((void**)&small, 2 * st_bytes + 256);
+    int host_removed[2] = {0, 0};
+    if (e == hipSuccess)
+        e = launch_prune_rows_cols(W, mask, M, N, kr, kc, sums, keys, small, small + st_bytes, (int*)(small + 2 * st_bytes), s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipMemcpy(host_removed, small + 2 * st_bytes, sizeof host_removed, hipMemcpyDeviceToHost);
+    if (sums) (void)hipFree(sums);
+    if (keys) (void)hipFree(keys);
+    if (small) (void)hipFree(small);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "lstm_prune_rows_cols");
+    if (rows_removed) *rows_removed = host_removed[0];
+    if (cols_removed) *cols_removed = host_removed[1];
+    return LSTM_OK;
+}
+
 int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, double* avg_us,
                       float* y_host, void* stream)
 {
