@@ -40,6 +40,10 @@ struct LayerDir {
     float* bias2 = nullptr;
 };
 
+// Number of compute units of the current device (cached; 256 if the query fails).  The persistent kernels need
+// every workgroup resident at once, i.e. at most one per compute unit.
+int device_num_cus();
+
 // ---- kernel launchers (all asynchronous on `s`; return hipError_t of the launch) ----
 
 // P[m][n] = bias[n] + sum_k X[m][k] * W[n][k];  X fp32 or bf16 (x_bf16), W fp32 or bf16 (w_bf16).

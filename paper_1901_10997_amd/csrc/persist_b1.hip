@@ -397,26 +397,13 @@ __global__ __launch_bounds__(1024) void exchange_only_kernel(u64* xchg, unsigned
 }
 
 // ------------------------------------------------------------------------------------------------ launchers
-static int g_num_cu = 0;
-static int num_cu()
-{
-    if (g_num_cu == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            g_num_cu = prop.multiProcessorCount;
-        if (g_num_cu <= 0) g_num_cu = 256;
-    }
-    return g_num_cu;
-}
-
 // Every workgroup of these kernels must be resident at the same time.  A cooperative launch makes the runtime
 // guarantee it; the ordinary launch relies on at most one workgroup per compute unit on an otherwise idle
 // device (the waits inside the kernels are bounded either way).
 template <typename K>
 static hipError_t coop_launch(K kernel, int blocks, int threads, size_t lds, void** args, bool cooperative, hipStream_t s)
 {
-    if (blocks > num_cu()) return hipErrorCooperativeLaunchTooLarge;
+    if (blocks > device_num_cus()) return hipErrorCooperativeLaunchTooLarge;
     if (cooperative)
         return hipLaunchCooperativeKernel((const void*)kernel, dim3(blocks), dim3(threads), args, (unsigned)lds, s);
     return hipLaunchKernel((const void*)kernel, dim3(blocks), dim3(threads), args, lds, s);
@@ -430,7 +417,7 @@ static int pick_waves(int H, int requested, int max_waves, int divisor)
     w -= w % divisor;
     if (w < divisor) w = divisor;
     // never more workgroups than compute units: every workgroup must be resident for the exchange to progress
-    while (w + divisor <= max_waves && (H + w / divisor - 1) / (w / divisor) > num_cu()) w += divisor;
+    while (w + divisor <= max_waves && (H + w / divisor - 1) / (w / divisor) > device_num_cus()) w += divisor;
     return w;
 }
 
@@ -489,7 +476,7 @@ bool persist_b1_sparse_supported(int H, int D0, int slots_x, int slots_h, int nl
     const int nz = slots_x > slots_h ? slots_x : slots_h;
     const int maxt = nz <= 1 ? 1024 : nz <= 4 ? 768 : 512;
     const int upb = (maxt / 64) / nl;
-    return (H + upb - 1) / upb <= num_cu();
+    return (H + upb - 1) / upb <= device_num_cus();
 }
 
 template <int NZ, int NL>

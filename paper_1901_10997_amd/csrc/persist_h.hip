@@ -27,19 +27,6 @@ namespace l355 {
 
 namespace {
 
-int g_num_cu_ph = 0;
-int num_cu_ph()
-{
-    if (g_num_cu_ph == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            g_num_cu_ph = n;
-        if (g_num_cu_ph <= 0) g_num_cu_ph = 256;
-    }
-    return g_num_cu_ph;
-}
-
 constexpr int hl_maxt(int nz) { return nz <= 2 ? 1024 : nz <= 4 ? 768 : 512; }
 
 }  // namespace
@@ -206,7 +193,7 @@ bool persist_b1_hlstm_supported(int H, int G, int D, int slots_1x, int slots_1h,
     const int waves = hl_maxt(nz) / 64;
     if (((size_t)H + 4 * (size_t)G + 2 * (size_t)D + 4 * waves) * sizeof(float) > 64 * 1024) return false;
     const int units = std::max(H, G);
-    return (units + waves - 1) / waves <= num_cu_ph();
+    return (units + waves - 1) / waves <= device_num_cus();
 }
 
 template <int NZ>
@@ -216,7 +203,7 @@ static hipError_t launch_hl_nz(PersistHArgs a, bool coop, hipStream_t s)
     const int waves = MAXT / 64;
     const int units = std::max(a.H, a.G);
     const int blocks = (units + waves - 1) / waves;
-    if (blocks > num_cu_ph()) return hipErrorCooperativeLaunchTooLarge;
+    if (blocks > device_num_cus()) return hipErrorCooperativeLaunchTooLarge;
     const size_t lds = ((size_t)a.H + 4 * (size_t)a.G + 2 * (size_t)a.D + 4 * waves) * sizeof(float);
     void* args[] = {(void*)&a};
     const void* kern = (const void*)persist_b1_hlstm_kernel<NZ, MAXT>;

@@ -33,23 +33,6 @@ namespace l355 {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-namespace {
-
-int g_num_cu_pm = 0;
-int num_cu_pm()
-{
-    if (g_num_cu_pm == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
-            g_num_cu_pm = n;
-        if (g_num_cu_pm <= 0) g_num_cu_pm = 256;
-    }
-    return g_num_cu_pm;
-}
-
-}  // namespace
-
 template <int KS>  // k16 steps of a wave's K slice: H = 128 * KS
 __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs a)
 {
@@ -219,7 +202,7 @@ bool persist_mfma_supported(int B, int H)
 {
     if (B < 32 || H % 128 != 0 || H > 1024) return false;
     const int tiles = ((B + 63) / 64) * (4 * H / 64);
-    return ((tiles + 7) / 8) * 8 <= num_cu_pm();
+    return ((tiles + 7) / 8) * 8 <= device_num_cus();
 }
 
 size_t persist_mfma_exchange_bytes(int B, int H)

@@ -727,19 +727,16 @@ static hipError_t launch_bf16_big(const uint16_t* X, int ldx, const uint16_t* W,
     const int gm = (M + 255) / 256, gn = (N + 255) / 256;
     const int grid = ((gm * gn + kXcds - 1) / kXcds) * kXcds;
     const size_t lds = 131072;
-    static int num_cus = 0;
-    if (num_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-            return hipErrorInvalidDevice;
+    static bool attr_set = false;
+    if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)proj_mfma_bf16_big_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute((const void*)proj_mfma_bf16_big_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        num_cus = (n / kXcds) * kXcds;
-        if (num_cus == 0) num_cus = kXcds;
+        attr_set = true;
     }
+    int num_cus = (device_num_cus() / kXcds) * kXcds;
+    if (num_cus == 0) num_cus = kXcds;
     const int blocks = grid < num_cus ? grid : num_cus;
     if (K % 64 == 0)
         hipLaunchKernelGGL(proj_mfma_bf16_big_kernel<64>, dim3(blocks), dim3(512), lds, s, X, ldx, W, bias, P, M, N, K, gm, gn, grid);

@@ -46,4 +46,18 @@ hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s)
     return hipGetLastError();
 }
 
+int device_num_cus()
+{
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            cached = n;
+        else
+            cached = 256;
+    }
+    return cached;
+}
+
 }  // namespace l355
