@@ -273,8 +273,9 @@ int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double*
  * Stand-alone product Y[batch, n] = X[batch, n] . W[n, n]^T with a dense input batch and a square weight matrix of
  * which a fraction `keep` in (0, 1] is kept (paper Section 3, the two matrix-multiplication latency figures: latency
  * against the dimension for dense and sparse operands).  format LSTM_FMT_DENSE_MASKED runs the library's dense
- * projection (zeros stored), LSTM_FMT_ROW_COMPRESSED its row-compressed one (including the transpose of X that
- * product needs).  W ~ U(-0.1, 0.1), mask Bernoulli(keep), X ~ N(0,1), all from `seed` with one fixed generator, so
+ * projection (zeros stored), LSTM_FMT_ROW_COMPRESSED its row-compressed one (for batch <= 64 and n <= 5120 the
+ * kernel that splits a row's kept entries over the lanes; otherwise the transpose of X plus the kernel that puts
+ * the input rows on the lanes).  W ~ U(-0.1, 0.1), mask Bernoulli(keep), X ~ N(0,1), all from `seed` with one fixed generator, so
  * both formats see the same operands.  n a multiple of 4.  *avg_us: average over `iters` launches after 3 warm-up
  * launches.  y_host (HOST, [batch, n], may be NULL) receives the product.  Allocates and frees its own device
  * buffers; synchronises the stream.

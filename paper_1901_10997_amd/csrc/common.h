@@ -62,6 +62,12 @@ hipError_t launch_transpose_to_f32(const void* X, bool x_bf16, int ldx, float* X
 hipError_t launch_proj_csr(const float* XT, const int32_t* row_ptr, const uint16_t* col, const float* val,
                            const float* bias, float* P, int M, int rows, hipStream_t s);
 
+// Row-compressed projection for M <= 64 input rows from the 64-lane slices (no transpose of X needed).
+bool proj_ell_small_supported(int M, int rows, int K, int slots);
+hipError_t launch_proj_ell_small(const void* X, bool x_bf16, int ldx, bool round_x_bf16, const float* ell_val,
+                                 const uint16_t* ell_col, int slots, const float* bias, float* P, int M, int rows, int K,
+                                 hipStream_t s);
+
 struct StepArgs {
     const float* P;        // [T*B][4H] pre-activations from the input projection (bias included)
     const float* h_prev;   // h_{t-1}: element (b,k) at h_prev[b*h_prev_ld + k]; nullptr = zeros

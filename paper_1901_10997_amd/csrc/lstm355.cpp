@@ -557,7 +557,10 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
             ProfSpan span(m, s, 0);
             const bool dense_proj = w.wx.dense && (!w.wx.compressed || (M >= 256 && proj_mfma_supported(false, D, D)));
             proj_dense[d] = dense_proj;
-            if (!dense_proj) {
+            if (!dense_proj && w.wx.ell_val && proj_ell_small_supported(M, 4 * G, D, w.wx.slots)) {
+                HIP_TRY(m, launch_proj_ell_small(X, false, D, false, w.wx.ell_val, w.wx.ell_col, w.wx.slots, w.bias, P[d], M,
+                                                 4 * G, D, s));
+            } else if (!dense_proj) {
                 if (!xt_ready) {
                     HIP_TRY(m, launch_transpose_to_f32(X, false, D, XT, M, D, false, s));
                     xt_ready = true;
@@ -819,7 +822,11 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             // measured on MI355X: at 10-15 % density the dense MFMA product beats the compressed one once
             // T*B reaches a few hundred rows; below that the compressed product reads far fewer bytes
             const bool dense_proj = w.wx.dense && (!w.wx.compressed || (M >= 256 && proj_mfma_supported(bf16, D, D)));
-            if (!dense_proj) {
+            if (!dense_proj && w.wx.ell_val && proj_ell_small_supported(M, 4 * H, D, w.wx.slots)) {
+                // few input rows: lanes over the kept entries of a row (no transpose of X)
+                HIP_TRY(m, launch_proj_ell_small(X, x_is_bf16, D, bf16 && !x_is_bf16, w.wx.ell_val, w.wx.ell_col, w.wx.slots,
+                                                 w.bias, P[d], M, 4 * H, D, s));
+            } else if (!dense_proj) {
                 if (!xt_ready) {
                     HIP_TRY(m, launch_transpose_to_f32(X, x_is_bf16, D, XT, M, D, bf16 && !x_is_bf16, s));
                     xt_ready = true;
@@ -1389,12 +1396,29 @@ int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, 
         }
         rp[(size_t)r + 1] = (int32_t)col.size();
     }
-    float *dX = nullptr, *dW = nullptr, *dB = nullptr, *dY = nullptr, *dXT = nullptr, *dval = nullptr;
+    // 64-lane slices of the kept entries (entry e of a row in slice e / 64, lane e % 64), used when the input batch is
+    // small enough for the lanes-over-entries projection
+    int slots = 1;
+    for (int r = 0; r < n && format == LSTM_FMT_ROW_COMPRESSED; ++r) slots = std::max(slots, (rp[(size_t)r + 1] - rp[r] + 63) / 64);
+    const bool use_ell = format == LSTM_FMT_ROW_COMPRESSED && proj_ell_small_supported(batch, n, n, slots);
+    std::vector<float> ev;
+    std::vector<uint16_t> ec;
+    if (use_ell) {
+        ev.assign((size_t)n * slots * 64, 0.0f);
+        ec.assign((size_t)n * slots * 64, 0);
+        for (int r = 0; r < n; ++r)
+            for (int e = rp[r]; e < rp[(size_t)r + 1]; ++e) {
+                ev[(size_t)r * slots * 64 + (size_t)(e - rp[r])] = val[(size_t)e];
+                ec[(size_t)r * slots * 64 + (size_t)(e - rp[r])] = col[(size_t)e];
+            }
+    }
+    float *dX = nullptr, *dW = nullptr, *dB = nullptr, *dY = nullptr, *dXT = nullptr, *dval = nullptr, *dev_ = nullptr;
     int32_t* drp = nullptr;
-    uint16_t* dcol = nullptr;
+    uint16_t *dcol = nullptr, *dec = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     int rc = LSTM_OK;
     auto run = [&]() -> hipError_t {
+        if (use_ell) return launch_proj_ell_small(dX, false, n, false, dev_, dec, slots, dB, dY, batch, n, n, s);
         if (format == LSTM_FMT_ROW_COMPRESSED) {
             hipError_t e = launch_transpose_to_f32(dX, false, n, dXT, batch, n, false, s);
             if (e != hipSuccess) return e;
@@ -1406,7 +1430,10 @@ int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, 
     hipError_t e = upload(&dX, X);
     if (e == hipSuccess) e = upload(&dB, bias);
     if (e == hipSuccess) e = hipMalloc((void**)&dY, (size_t)batch * n * sizeof(float));
-    if (e == hipSuccess && format == LSTM_FMT_ROW_COMPRESSED) {
+    if (e == hipSuccess && use_ell) {
+        e = upload(&dev_, ev);
+        if (e == hipSuccess) e = upload(&dec, ec);
+    } else if (e == hipSuccess && format == LSTM_FMT_ROW_COMPRESSED) {
         e = upload(&drp, rp);
         if (e == hipSuccess) e = upload(&dcol, col);
         if (e == hipSuccess) e = upload(&dval, val);
@@ -1428,7 +1455,7 @@ int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, 
     else *avg_us = (double)ms * 1000.0 / iters;
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
-    for (void* p_ : {(void*)dX, (void*)dW, (void*)dB, (void*)dY, (void*)dXT, (void*)dval, (void*)drp, (void*)dcol})
+    for (void* p_ : {(void*)dX, (void*)dW, (void*)dB, (void*)dY, (void*)dXT, (void*)dval, (void*)drp, (void*)dcol, (void*)dev_, (void*)dec})
         if (p_) (void)hipFree(p_);
     return rc;
 }

@@ -178,6 +178,104 @@ __global__ __launch_bounds__(256) void proj_csr_kernel(const float* __restrict__
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Row-compressed projection for few input rows (M <= 64: batch-1 sequences, small T*B).  The kernel above gives a
+// wave one output row and walks its kept entries one after the other with the input rows on the lanes, which is
+// bound by dependent-load latency when M is small.  Here the lanes split a row's kept entries (the 64-lane slices
+// built at weight set-up, streamed once, coalesced): a 1024-thread workgroup serves 16 units (4 packed rows each)
+// for a tile of 8 input rows, the tile of X is staged in LDS with the 8 values of one k adjacent (one kept weight
+// costs two 16-byte LDS reads and eight FMAs), and the 4 x 8 sums are reduced with the lane-swap reduction.
+// ---------------------------------------------------------------------------------------------
+template <typename TX>
+__global__ __launch_bounds__(1024) void proj_ell_small_kernel(const TX* __restrict__ X, int ldx, int round_x_bf16,
+                                                              const float* __restrict__ ell_val,
+                                                              const uint16_t* __restrict__ ell_col, int slots,
+                                                              const float* __restrict__ bias, float* __restrict__ P,
+                                                              int M, int rows, int K)
+{
+    extern __shared__ float xbuf[];  // [K][8]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int unit = blockIdx.x * 16 + wave;
+    const int m0 = blockIdx.y * 8;
+    const int lb = lane & 15, row = lane >> 4;
+    for (int k = tid; k < K; k += 1024) {
+        float v[8];
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            float xv = (m0 + b < M) ? load_elem(X, (size_t)(m0 + b) * ldx + k) : 0.f;
+            if (round_x_bf16) xv = round_bf16(xv);
+            v[b] = xv;
+        }
+        // the two 16-byte halves of row k swap places when bit 2 of k is set, so that gathers of random k spread
+        // over all bank groups
+        const int sw = (k >> 2) & 1;
+        *reinterpret_cast<float4*>(xbuf + k * 8 + 4 * sw) = make_float4(v[0], v[1], v[2], v[3]);
+        *reinterpret_cast<float4*>(xbuf + k * 8 + 4 * (sw ^ 1)) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+    __syncthreads();
+    if (4 * unit >= rows) return;  // whole wave; no barrier follows
+    float acc[4][8];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int b = 0; b < 8; ++b) acc[q][b] = 0.f;
+    for (int i = 0; i < slots; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const size_t idx = ((size_t)(4 * unit + q) * slots + i) * 64 + lane;
+            const float w = ell_val[idx];
+            const int k = ell_col[idx];
+            const int sw = (k >> 2) & 1;
+            const float4 lo = *reinterpret_cast<const float4*>(xbuf + k * 8 + 4 * sw);
+            const float4 hi = *reinterpret_cast<const float4*>(xbuf + k * 8 + 4 * (sw ^ 1));
+            acc[q][0] = fmaf(w, lo.x, acc[q][0]);
+            acc[q][1] = fmaf(w, lo.y, acc[q][1]);
+            acc[q][2] = fmaf(w, lo.z, acc[q][2]);
+            acc[q][3] = fmaf(w, lo.w, acc[q][3]);
+            acc[q][4] = fmaf(w, hi.x, acc[q][4]);
+            acc[q][5] = fmaf(w, hi.y, acc[q][5]);
+            acc[q][6] = fmaf(w, hi.z, acc[q][6]);
+            acc[q][7] = fmaf(w, hi.w, acc[q][7]);
+        }
+    }
+    // lane 16*q + b  <-  total of packed row 4*unit + q, input row m0 + b
+    float S = 0.f;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+        const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
+        S = (lb == b) ? r : S;
+    }
+    if (lb < 8 && m0 + lb < M) P[(size_t)(m0 + lb) * rows + 4 * unit + row] = S + bias[4 * unit + row];
+}
+
+bool proj_ell_small_supported(int M, int rows, int K, int slots)
+{
+    return M >= 1 && M <= 64 && rows >= 4 && (rows & 3) == 0 && slots >= 1 && (size_t)K * 8 * sizeof(float) <= 160 * 1024;
+}
+
+hipError_t launch_proj_ell_small(const void* X, bool x_bf16, int ldx, bool round_x_bf16, const float* ell_val,
+                                 const uint16_t* ell_col, int slots, const float* bias, float* P, int M, int rows, int K,
+                                 hipStream_t s)
+{
+    if (M <= 0 || rows <= 0) return hipSuccess;
+    if (!proj_ell_small_supported(M, rows, K, slots)) return hipErrorInvalidValue;
+    const size_t lds = (size_t)K * 8 * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)proj_ell_small_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute((const void*)proj_ell_small_kernel<uint16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid((rows / 4 + 15) / 16, (M + 7) / 8), block(1024);
+    if (x_bf16)
+        hipLaunchKernelGGL(proj_ell_small_kernel<uint16_t>, grid, block, lds, s, (const uint16_t*)X, ldx, 0, ell_val, ell_col, slots, bias, P, M, rows, K);
+    else
+        hipLaunchKernelGGL(proj_ell_small_kernel<float>, grid, block, lds, s, (const float*)X, ldx, round_x_bf16 ? 1 : 0, ell_val, ell_col, slots, bias, P, M, rows, K);
+    return hipGetLastError();
+}
+
 hipError_t launch_proj_csr(const float* XT, const int32_t* row_ptr, const uint16_t* col, const float* val,
                            const float* bias, float* P, int M, int rows, hipStream_t s)
 {
