@@ -616,67 +616,98 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
 // ---------------------------------------------------------------------------------------------------------
 // fp32, at most 64 rows of X (batch-1 sequences: M = T).  The product is a stream over W (read once, 4H*K*4
 // bytes) with X resident in L2, so there is no LDS pipeline: a workgroup owns 32 packed rows of W for all of
-// X, its four waves split K and stream their operand fragments from global memory straight into registers
-// (16 bytes per lane and row, eight k-blocks in flight), and the four partial 64 x 32 tiles are summed through
-// LDS in a fixed order.  Requires K % 16 == 0.
+// X, its eight waves split K and stream their operand fragments from global memory straight into registers
+// (16 bytes per lane and row), and the eight partial tiles are summed through LDS in a fixed order.  Two
+// register sets of four k-blocks alternate, so the loads of the next 32 k are in flight while the MFMAs of the
+// current ones execute (an MFMA issue blocks the wave, so without this every block of k paid a memory round
+// trip), and two waves share a SIMD.  MT = 1 when M <= 32: half the MFMAs.  Requires K % 16 == 0.
 // ---------------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void proj_mfma_f32_skinny_kernel(const float* __restrict__ X, int ldx,
+template <int MT>
+__global__ __launch_bounds__(512) void proj_mfma_f32_skinny_kernel(const float* __restrict__ X, int ldx,
                                                                    const float* __restrict__ W,
                                                                    const float* __restrict__ bias, float* __restrict__ P,
                                                                    int M, int N, int K)
 {
-    __shared__ float part[4][64][33];
+    constexpr int NW = 8, UN = 4;    // waves splitting K; k-blocks of 8 per register set
+    __shared__ float part[NW][32 * MT][32];   // lanes write and read along the last index: no padding needed
     const int n0 = blockIdx.x * 32;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, fk = lane >> 5;
-    // K is cut into four contiguous quarters (multiples of 8), one per wave
-    const int kq = ((K / 8 + 3) / 4) * 8;
+    // K is cut into eight contiguous pieces (multiples of 8), one per wave
+    const int kq = ((K / 8 + NW - 1) / NW) * 8;
     const int kbeg = wave * kq, kend = (kbeg + kq) < K ? (kbeg + kq) : K;
-    f32x16 acc[2];
+    f32x16 acc[MT];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-    int m0r = fr, m1r = 32 + fr;
-    if (m0r > M - 1) m0r = M - 1;   // rows beyond M are computed on a valid row and never stored
-    if (m1r > M - 1) m1r = M - 1;
+    const float* arow[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        int mr = 32 * i + fr;
+        if (mr > M - 1) mr = M - 1;   // rows beyond M are computed on a valid row and never stored
+        arow[i] = X + (size_t)mr * ldx + fk * 4;
+    }
     int nr = n0 + fr;
     if (nr > N - 1) nr = N - 1;
-    const float* a0 = X + (size_t)m0r * ldx + fk * 4;
-    const float* a1 = X + (size_t)m1r * ldx + fk * 4;
     const float* bw = W + (size_t)nr * K + fk * 4;
-    constexpr int UN = 8;            // k-blocks of 8 requested together
-    for (int k0 = kbeg; k0 < kend; k0 += 8 * UN) {
-        float4 fa0[UN], fa1[UN], fb[UN];
+    float4 fa0[MT][UN], fb0[UN], fa1[MT][UN], fb1[UN];
+    auto load0 = [&](int k0) {
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int k = k0 + 8 * u;
             const bool ok = k < kend;
-            fa0[u] = ok ? *reinterpret_cast<const float4*>(a0 + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-            fa1[u] = ok ? *reinterpret_cast<const float4*>(a1 + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-            fb[u] = ok ? *reinterpret_cast<const float4*>(bw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) fa0[i][u] = ok ? *reinterpret_cast<const float4*>(arow[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            fb0[u] = ok ? *reinterpret_cast<const float4*>(bw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
+    };
+    auto load1 = [&](int k0) {
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa0[u].x, fb[u].x, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa1[u].x, fb[u].x, acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa0[u].y, fb[u].y, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa1[u].y, fb[u].y, acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa0[u].z, fb[u].z, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa1[u].z, fb[u].z, acc[1], 0, 0, 0);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa0[u].w, fb[u].w, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa1[u].w, fb[u].w, acc[1], 0, 0, 0);
+            const int k = k0 + 8 * u;
+            const bool ok = k < kend;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) fa1[i][u] = ok ? *reinterpret_cast<const float4*>(arow[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            fb1[u] = ok ? *reinterpret_cast<const float4*>(bw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto mma = [&](const float4 (&fa)[MT][UN], const float4 (&fb)[UN]) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][u].x, fb[u].x, acc[i], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][u].y, fb[u].y, acc[i], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][u].z, fb[u].z, acc[i], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][u].w, fb[u].w, acc[i], 0, 0, 0);
+        }
+    };
+    constexpr int KSTEP = 8 * UN;
+    if (kbeg < kend) load0(kbeg);
+    for (int k0 = kbeg; k0 < kend; k0 += 2 * KSTEP) {
+        if (k0 + KSTEP < kend) load1(k0 + KSTEP);
+        mma(fa0, fb0);
+        if (k0 + KSTEP < kend) {
+            if (k0 + 2 * KSTEP < kend) load0(k0 + 2 * KSTEP);
+            mma(fa1, fb1);
         }
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MT; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) part[wave][i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3)][fr] = acc[i][v];
     __syncthreads();
-    for (int e = tid; e < 64 * 32; e += 256) {
+    for (int e = tid; e < 32 * MT * 32; e += 512) {
         const int m = e >> 5, n = e & 31;
-        if (m < M && n0 + n < N)
-            P[(size_t)m * N + n0 + n] = ((part[0][m][n] + part[1][m][n]) + (part[2][m][n] + part[3][m][n])) + bias[n0 + n];
+        if (m < M && n0 + n < N) {
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) sum += part[w][m][n];
+            P[(size_t)m * N + n0 + n] = sum + bias[n0 + n];
+        }
     }
 }
 
@@ -797,8 +828,12 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
     }
     if (x_bf16) return hipErrorInvalidValue;
     if (M <= 64 && K % 16 == 0 && ldx % 4 == 0) {
-        hipLaunchKernelGGL(proj_mfma_f32_skinny_kernel, dim3((N + 31) / 32), dim3(256), 0, s, (const float*)X, ldx,
-                           (const float*)W, bias, P, M, N, K);
+        if (M <= 32)
+            hipLaunchKernelGGL(proj_mfma_f32_skinny_kernel<1>, dim3((N + 31) / 32), dim3(512), 0, s, (const float*)X, ldx,
+                               (const float*)W, bias, P, M, N, K);
+        else
+            hipLaunchKernelGGL(proj_mfma_f32_skinny_kernel<2>, dim3((N + 31) / 32), dim3(512), 0, s, (const float*)X, ldx,
+                               (const float*)W, bias, P, M, N, K);
         return hipGetLastError();
     }
     if (M <= 64) return launch_f32<1, 1>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
