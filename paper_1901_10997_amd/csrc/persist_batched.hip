@@ -157,19 +157,6 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
 }
 
 // ------------------------------------------------------------------------------------------------ planning
-static int g_cu = 0;
-static int cu_count()
-{
-    if (g_cu == 0) {
-        int dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-            g_cu = prop.multiProcessorCount;
-        if (g_cu <= 0) g_cu = 256;
-    }
-    return g_cu;
-}
-
 // Choose (UPW, BW): the most workgroups that still fit one per compute unit, within the register budget
 // (6*NZ registers per unit for the weights; 512-thread workgroups leave 256 registers per lane) and PAIRS <= 16.
 constexpr int kWaves = 8;
@@ -184,7 +171,7 @@ bool persist_batched_plan(int B, int H, int nz, int ndir, int* upw_out, int* bw_
             if (((size_t)bw * H + (size_t)bw * kWaves * upw) * sizeof(float) > 64 * 1024) continue;
             const int ug = (H + kWaves * upw - 1) / (kWaves * upw), bg = (B + bw - 1) / bw;
             const int blocks = ug * bg * ndir;
-            if (blocks > cu_count()) continue;
+            if (blocks > device_num_cus()) continue;
             if (blocks > best) {
                 best = blocks;
                 *upw_out = upw; *bw_out = bw; *ug_out = ug; *bg_out = bg;

@@ -316,3 +316,37 @@ def test_standalone_product_dense_and_compressed_agree(n, batch, keep):
     assert 0.6 * n * keep / 300 < var < 1.6 * n * keep / 300
     _, other = B.lstm_bench_matmul(n, batch, keep, DENSE, seed=8, iters=1, want_product=True)
     assert np.max(np.abs(other - yd)) > 1e-3
+
+
+def test_expired_waits_are_reported_and_nothing_hangs(monkeypatch):
+    """Every wait inside the persistent kernels is bounded.  With the bound forced down to two polls (environment
+    variable read at lstm_create) a forward either completes correctly (the values happened to be there) or drains
+    and reports LSTM_ERR_TIMEOUT from the check that follows; in both cases it returns, the flag is cleared by the
+    check, and a handle created afterwards with the normal bound works."""
+    import torch
+    families = [
+        (_wl(70, 1, False, 40, 300, 40, 1), DENSE, "persist_b1-dense"),
+        (_wl(70, 2, False, 60, 500, 40, 1, keep=0.2), CSR, "wavefront"),
+        (_wl(70, 1, True, 48, 400, 30, 12, keep=0.15), CSR, "persist_batched"),
+        (_wl(70, 1, False, 64, 512, 30, 128, dtype="bf16", a=0.05), DENSE, "persist-mfma"),
+        (inputs.Workload(70, "hl", 1, False, 40, 400, 30, 1, "f32", 0.3, 0.2, "uniform", 400), CSR, "persist_b1-hlstm"),
+    ]
+    monkeypatch.setenv("LSTM355_SPIN_LIMIT", "1")
+    timeouts = 0
+    for w, fmt, want in families:
+        case = inputs.make_case(w, 0)
+        try:
+            gpu, desc = run_gpu(case, fmt, PAUTO)
+        except B.LstmError as e:
+            assert e.code == B.LSTM_ERR_TIMEOUT
+            timeouts += 1
+            continue
+        assert want in desc
+        from oracle import hlstm_oracle as horc
+        ref = (horc if w.gate_hidden else orc).forward_case(case)
+        compare(gpu, ref, w.dtype, w.name)
+    monkeypatch.delenv("LSTM355_SPIN_LIMIT")
+    assert timeouts >= 1      # exchanging across the whole device within two polls every step does not happen
+    for w, fmt, want in families:
+        desc, _ = check_case(inputs.make_case(w, 0), fmt, PAUTO)
+        assert want in desc
