@@ -24,6 +24,15 @@ struct PackedMat {
     int slots = 0;               // ceil(max_row_nnz / 64)
     float* ell_val = nullptr;    // device [rows*slots*64]
     uint16_t* ell_col = nullptr; // device [rows*slots*64]
+    // The same slices cut to fewer slots for the batch-1 kernel, when only a few rows are longer than the rest: rows
+    // keep their first 64*slots_trim entries in the slices, the remainder of a unit's four rows (at most 64 entries
+    // per unit) goes to a per-unit overflow list: entry = (gate << 16) | column.  slots_trim == 0: not built.
+    int slots_trim = 0;
+    float* ell_val_trim = nullptr;
+    uint16_t* ell_col_trim = nullptr;
+    int32_t* ovf_ptr = nullptr;   // device [rows/4 + 1]
+    uint32_t* ovf_ent = nullptr;  // device [overflow entries]
+    float* ovf_val = nullptr;
     // host copy of the compressed structure in packed row order (for read-back)
     std::vector<int64_t> h_row_ptr;
     std::vector<int32_t> h_col;
@@ -256,6 +265,13 @@ struct SparseLayerArgs {
     const float* ell_val_h;     // [4H][slots_h][64]
     const uint16_t* ell_col_h;
     int slots_x, slots_h;
+    // per-unit overflow lists of rows longer than 64*slots entries (nullptr: none); entry = (gate << 16) | column
+    const int32_t* ovf_ptr_x;
+    const uint32_t* ovf_ent_x;
+    const float* ovf_val_x;
+    const int32_t* ovf_ptr_h;
+    const uint32_t* ovf_ent_h;
+    const float* ovf_val_h;
     const float* bias;          // [4H] packed order
     const float* h0;            // [H] or nullptr
     const float* c0;

@@ -99,6 +99,11 @@ static void free_mat(PackedMat& p)
     if (p.val) (void)hipFree(p.val);
     if (p.ell_val) (void)hipFree(p.ell_val);
     if (p.ell_col) (void)hipFree(p.ell_col);
+    if (p.ell_val_trim) (void)hipFree(p.ell_val_trim);
+    if (p.ell_col_trim) (void)hipFree(p.ell_col_trim);
+    if (p.ovf_ptr) (void)hipFree(p.ovf_ptr);
+    if (p.ovf_ent) (void)hipFree(p.ovf_ent);
+    if (p.ovf_val) (void)hipFree(p.ovf_val);
     p = PackedMat();
 }
 
@@ -182,14 +187,15 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
     // distinct banks.  Entries that do not fit their bank's lanes fill the remaining positions.  (The order of
     // the entries inside a row is free: it only fixes the order of a sum.)
     out.slots = std::max(1, (max_nnz + 63) / 64);
-    if (out.slots <= 8) {
-        const int S = out.slots;
-        std::vector<float> ev((size_t)rows * S * 64, 0.0f);
-        std::vector<uint16_t> ec((size_t)rows * S * 64, 0);
+    // slices of S slots holding the first min(nnz, 64 S) entries of every row
+    auto build_slices = [&](int S, std::vector<float>& ev, std::vector<uint16_t>& ec) {
+        ev.assign((size_t)rows * S * 64, 0.0f);
+        ec.assign((size_t)rows * S * 64, 0);
         std::vector<char> used((size_t)S * 64);
         std::vector<int64_t> leftover;
         for (int rp = 0; rp < rows; ++rp) {
-            const int64_t beg = out.h_row_ptr[rp], end = out.h_row_ptr[rp + 1];
+            const int64_t beg = out.h_row_ptr[rp];
+            const int64_t end = std::min<int64_t>(out.h_row_ptr[rp + 1], beg + (int64_t)64 * S);
             std::fill(used.begin(), used.end(), 0);
             leftover.clear();
             int fill[32] = {0};  // positions already taken in each bank's lanes (slot-major: lane b, lane b+32)
@@ -215,8 +221,51 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
                 ec[idx] = (uint16_t)out.h_col[e];
             }
         }
+    };
+    if (out.slots <= 8) {
+        std::vector<float> ev;
+        std::vector<uint16_t> ec;
+        build_slices(out.slots, ev, ec);
         HIP_TRY(m, upload(&out.ell_val, ev));
         HIP_TRY(m, upload(&out.ell_col, ec));
+    }
+    // Trimmed form: the slot count is set by the longest row, and with random masks a handful of rows are a few
+    // entries longer than all others.  Take the smallest slot count that leaves at most 64 overflow entries per unit
+    // (one per lane: a wave then pays one extra gather per step, against four per slot saved).
+    if (out.slots >= 2 && out.slots <= 9) {
+        const int units = rows / 4;
+        for (int S = 1; S < out.slots; ++S) {
+            int64_t worst = 0;
+            for (int u = 0; u < units; ++u) {
+                int64_t per_unit = 0;
+                for (int q = 0; q < 4; ++q)
+                    per_unit += std::max<int64_t>(0, out.h_row_ptr[4 * u + q + 1] - out.h_row_ptr[4 * u + q] - (int64_t)64 * S);
+                worst = std::max(worst, per_unit);
+            }
+            if (worst > 64) continue;
+            std::vector<float> ev, ov;
+            std::vector<uint16_t> ec;
+            std::vector<int32_t> optr((size_t)units + 1, 0);
+            std::vector<uint32_t> oe;
+            build_slices(S, ev, ec);
+            for (int u = 0; u < units; ++u) {
+                for (int q = 0; q < 4; ++q) {
+                    const int rp = 4 * u + q;
+                    for (int64_t e = out.h_row_ptr[rp] + (int64_t)64 * S; e < out.h_row_ptr[rp + 1]; ++e) {
+                        oe.push_back(((uint32_t)q << 16) | (uint32_t)out.h_col[e]);
+                        ov.push_back(out.h_val[e]);
+                    }
+                }
+                optr[(size_t)u + 1] = (int32_t)oe.size();
+            }
+            out.slots_trim = S;
+            HIP_TRY(m, upload(&out.ell_val_trim, ev));
+            HIP_TRY(m, upload(&out.ell_col_trim, ec));
+            HIP_TRY(m, upload(&out.ovf_ptr, optr));
+            HIP_TRY(m, upload(&out.ovf_ent, oe));
+            HIP_TRY(m, upload(&out.ovf_val, ov));
+            break;
+        }
     }
     return LSTM_OK;
 }
@@ -742,13 +791,25 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
         }
         return LSTM_OK;
     };
+    // slot count the batch-1 kernel will hold in registers: the trimmed slices where they exist
+    auto b1_slots = [](const PackedMat& p) { return p.slots_trim > 0 ? p.slots_trim : p.slots; };
     auto sparse_ok = [&](const LayerDir& w, int D_in, int nl) {
-        return w.wx.compressed && w.wh.compressed && w.wx.ell_val && w.wh.ell_val &&
-               persist_b1_sparse_supported(H, D_in, w.wx.slots, w.wh.slots, nl);
+        return w.wx.compressed && w.wh.compressed && (w.wx.ell_val || w.wx.slots_trim) && (w.wh.ell_val || w.wh.slots_trim) &&
+               persist_b1_sparse_supported(H, D_in, b1_slots(w.wx), b1_slots(w.wh), nl);
     };
     auto fill_sparse_layer = [&](SparseLayerArgs& a, const LayerDir& w, size_t n, float* yout, int y_ld) {
-        a.ell_val_x = w.wx.ell_val; a.ell_col_x = w.wx.ell_col; a.slots_x = w.wx.slots;
-        a.ell_val_h = w.wh.ell_val; a.ell_col_h = w.wh.ell_col; a.slots_h = w.wh.slots;
+        if (w.wx.slots_trim > 0) {
+            a.ell_val_x = w.wx.ell_val_trim; a.ell_col_x = w.wx.ell_col_trim; a.slots_x = w.wx.slots_trim;
+            a.ovf_ptr_x = w.wx.ovf_ptr; a.ovf_ent_x = w.wx.ovf_ent; a.ovf_val_x = w.wx.ovf_val;
+        } else {
+            a.ell_val_x = w.wx.ell_val; a.ell_col_x = w.wx.ell_col; a.slots_x = w.wx.slots;
+        }
+        if (w.wh.slots_trim > 0) {
+            a.ell_val_h = w.wh.ell_val_trim; a.ell_col_h = w.wh.ell_col_trim; a.slots_h = w.wh.slots_trim;
+            a.ovf_ptr_h = w.wh.ovf_ptr; a.ovf_ent_h = w.wh.ovf_ent; a.ovf_val_h = w.wh.ovf_val;
+        } else {
+            a.ell_val_h = w.wh.ell_val; a.ell_col_h = w.wh.ell_col; a.slots_h = w.wh.slots;
+        }
         a.bias = w.bias;
         a.h0 = h0 ? h0 + n * H : nullptr;   // B == 1 on this path
         a.c0 = c0 ? c0 + n * H : nullptr;
@@ -781,7 +842,8 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             a.xchg = m->xchg; a.tag_base = m->tag_base; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
             m->tag_base += (unsigned)T;
             HIP_TRY(m, launch_persist_b1_sparse(a, 2, m->waves_per_group, m->cooperative, s));
-            std::snprintf(tag, sizeof tag, "l%d+l%d.d0:proj=fused-csr,rec=persist_b1-csr-wavefront;", l, l + 1);
+            const bool ovf = m->ld[l].wx.slots_trim || m->ld[l].wh.slots_trim || m->ld[l + 1].wx.slots_trim || m->ld[l + 1].wh.slots_trim;
+            std::snprintf(tag, sizeof tag, "l%d+l%d.d0:proj=fused-csr,rec=persist_b1-csr-wavefront%s;", l, l + 1, ovf ? "+ovf" : "");
             m->last_plan += tag;
             ++l;
             continue;
@@ -1020,9 +1082,10 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             float* hTn = hT ? hT + n * B * H : nullptr;
             float* cTn = cT ? cT + n * B * H : nullptr;
             static const char* const names[4] = {"stepwise", "persist_b1", "persist_b1", "persist_b1"};
-            std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s%s,rec=%s-%s;", l, d, (mode[d] == 1 || mode[d] == 2) ? "fused-" : "",
+            std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s%s,rec=%s-%s%s;", l, d, (mode[d] == 1 || mode[d] == 2) ? "fused-" : "",
                           (w.wx.compressed && !(w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ) ? "csr" : "dense",
-                          names[mode[d]], w.wh.compressed ? "csr" : "dense");
+                          names[mode[d]], w.wh.compressed ? "csr" : "dense",
+                          (mode[d] == 1 && (w.wx.slots_trim || w.wh.slots_trim)) ? "+ovf" : "");
             m->last_plan += tag;
             ProfSpan span(m, s, 1);
             if (mode[d] == 1) {

@@ -243,6 +243,31 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
             chp[q][i >> 1] |= kv << (16 * (i & 1));
         }
     }
+    // overflow entries of this unit's rows (rows longer than 64*slots; rare): lane e holds entry e
+    int nox = 0, noh = 0;
+    unsigned oex = 0u, oeh = 0u;
+    float ovx = 0.f, ovh = 0.f;
+    if (active && L.ovf_ptr_x) {
+        const int b = L.ovf_ptr_x[j];
+        nox = L.ovf_ptr_x[j + 1] - b;
+        if (lane < nox) { oex = L.ovf_ent_x[b + lane]; ovx = L.ovf_val_x[b + lane]; }
+    }
+    if (active && L.ovf_ptr_h) {
+        const int b = L.ovf_ptr_h[j];
+        noh = L.ovf_ptr_h[j + 1] - b;
+        if (lane < noh) { oeh = L.ovf_ent_h[b + lane]; ovh = L.ovf_val_h[b + lane]; }
+    }
+    nox = __builtin_amdgcn_readfirstlane(nox);
+    noh = __builtin_amdgcn_readfirstlane(noh);
+    // lane e adds its overflow product to the partial sum of the gate its entry belongs to
+    auto add_overflow = [&](float (&acc)[4], int n, unsigned ent, float val, const float* vec) {
+        if (n > 0) {
+            const float t = lane < n ? val * vec[ent & 0xFFFFu] : 0.f;
+            const unsigned q = ent >> 16;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) acc[g] += (q == (unsigned)g) ? t : 0.f;
+        }
+    };
 #define COLX(q, i) ((cxp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
 #define COLH(q, i) ((chp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
     const int row = lane >> 4;                       // gate handled by this lane after the reduction
@@ -296,6 +321,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
             for (int i = 0; i < NZ; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) xacc[q] = fmaf(vx[q][i], xb[COLX(q, i)], xacc[q]);
+            add_overflow(xacc, nox, oex, ovx, xb);
         }
     };
     request_x(0);
@@ -334,11 +360,13 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
                 for (int i = 0; i < NZ; ++i)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) acc[q] = fmaf(vx[q][i], hin[COLX(q, i)], acc[q]);
+                add_overflow(acc, nox, oex, ovx, hin);
             }
 #pragma unroll
             for (int i = 0; i < NZ; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) acc[q] = fmaf(vh[q][i], hrec[COLH(q, i)], acc[q]);
+            add_overflow(acc, noh, oeh, ovh, hrec);
             const float pre = wave_sum4_rows(acc[0], acc[1], acc[2], acc[3]) + bias_l;
             h = lstm_cell_rows(pre, lane, c);
             if (lane == 0 && active) {

@@ -60,6 +60,23 @@ def test_layer_wavefront_stacks(L, H, D, keep):
 
 
 @pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, keep -- a few rows a little longer than a multiple of 64 kept entries: the batch-1 kernel holds
+    # the common row length in registers and takes the remainder from per-unit overflow lists
+    (1, False, 400, 400, 0.12),
+    (2, False, 400, 400, 0.12),
+    (1, True, 300, 520, 0.10),
+    (3, False, 410, 410, 0.27),
+    (2, False, 900, 600, 0.18),
+])
+def test_batch1_overflow_rows(shape):
+    L, bidir, D, H, keep = shape
+    case = inputs.make_case(_wl(98, L, bidir, D, H, 9, 1, keep=keep), k=L, random_state=True)
+    desc, _ = check_case(case, CSR, PERSIST)
+    assert "+ovf" in desc
+    check_case(case, CSR, PERSIST, 4)   # another workgroup size
+
+
+@pytest.mark.parametrize("shape", [
     # L, bidir, D, H, T, B, keep  -- small-batch row-compressed stacks: time loop on the device
     (2, True, 64, 200, 9, 16, 0.15),
     (1, False, 40, 333, 7, 20, 0.10),
