@@ -33,6 +33,7 @@ struct PackedMat {
     int32_t* ovf_ptr = nullptr;   // device [rows/4 + 1]
     uint32_t* ovf_ent = nullptr;  // device [overflow entries]
     float* ovf_val = nullptr;
+    std::vector<int32_t> h_ovf_ptr;   // host copy of ovf_ptr
     // host copy of the compressed structure in packed row order (for read-back)
     std::vector<int64_t> h_row_ptr;
     std::vector<int32_t> h_col;
@@ -322,6 +323,47 @@ struct PersistBatchedArgs {
 };
 bool persist_batched_plan(int B, int H, int nz, int ndir, int* upw, int* bw, int* ug, int* bg);
 hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int cooperative, hipStream_t s);
+
+// H-LSTM at small batch (B >= 2), W1h and W2 row-compressed and register-resident, time loop on the device, every
+// direction of a layer in one launch.
+struct PersistBatchedHDir {
+    const float* P1;            // [T*B][4G] packed rows (4g + q): b1 + W1x . x_t
+    const float* ell_val_1h;    // W1h [4G][slots_1h][64]
+    const uint16_t* ell_col_1h;
+    const float* ell_val_2;     // W2 [4H][slots_2][64]
+    const uint16_t* ell_col_2;
+    int slots_1h, slots_2;
+    // per-unit overflow lists of rows longer than 64*slots entries (nullptr: none); entry = (gate << 16) | column;
+    // the entries of the units one wave owns must not exceed 64
+    const int32_t* ovf_ptr_1h;
+    const uint32_t* ovf_ent_1h;
+    const float* ovf_val_1h;
+    const int32_t* ovf_ptr_2;
+    const uint32_t* ovf_ent_2;
+    const float* ovf_val_2;
+    const float* bias2;         // [4H] packed
+    const float* h0;            // [B][H] or nullptr
+    const float* c0;
+    float* y;                   // h_t(b, j) -> y[(t*B + b)*y_ld + j]
+    int y_ld;
+    float* hT;                  // [B][H] or nullptr
+    float* cT;
+    int reverse;
+};
+struct PersistBatchedHArgs {
+    PersistBatchedHDir d[2];
+    int T, B, H, G;
+    int ug, bg;                 // unit groups / batch groups per direction (filled by the launcher)
+    size_t h_stride, u_stride;  // elements per (direction, batch group) in xchg_h / xchg_u (filled by the launcher)
+    unsigned long long* xchg_h; // tagged slots, zero or older tags only
+    float* xchg_u;              // plain values
+    unsigned* flags;            // [ndir * bg][64], zero or older tags only
+    unsigned tag_base;
+    int* timeout_flag;
+    unsigned spin_limit;
+};
+bool persist_batched_h_plan(int B, int H, int G, int nz, int ndir, int* upw, int* bw, int* ug, int* bg);
+hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int nz, int cooperative, hipStream_t s);
 
 // Pruning mask updates (device arrays; scratch supplied by the caller of the launcher).
 size_t prune_state_bytes();

@@ -261,6 +261,7 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
             out.slots_trim = S;
             HIP_TRY(m, upload(&out.ell_val_trim, ev));
             HIP_TRY(m, upload(&out.ell_col_trim, ec));
+            out.h_ovf_ptr = optr;
             HIP_TRY(m, upload(&out.ovf_ptr, optr));
             HIP_TRY(m, upload(&out.ovf_ent, oe));
             HIP_TRY(m, upload(&out.ovf_val, ov));
@@ -447,7 +448,7 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
 
 // ---- workspace carve-up --------------------------------------------------------------------------------
 struct Workspace {
-    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, slot_off, hx_off, mflag_off, U_off[2], total;
+    size_t P_off[2], XT_off, Y_off[2], c_off[2], Yb_off[2], hb0_off, slot_off, slot_bytes, hx_off, mflag_off, U_off[2], total;
 };
 static Workspace carve(const lstm_t* m, int T, int B)
 {
@@ -480,8 +481,16 @@ static Workspace carve(const lstm_t* m, int T, int B)
     w.hb0_off = off;
     if (m->dtype == LSTM_BF16) off += align256((size_t)m->Dn * B * H * sizeof(uint16_t));
     // tagged exchange slots of the small-batch persistent recurrence: [Dn][2][B][H]
+    // (H-LSTM: h slots in [k][columns of a batch group] blocks padded to 256 bytes, ragged last group filled up,
+    // then one flag per unit group, 64 per batch group)
     w.slot_off = off;
-    if (B >= 2) off += align256((size_t)m->Dn * 2 * B * H * sizeof(unsigned long long));
+    if (B >= 2) {
+        const size_t groups = (size_t)B / 2 + 1;
+        w.slot_bytes = m->G > 0 ? (size_t)m->Dn * (((size_t)B + 3) * H * sizeof(unsigned long long) + groups * 256 +
+                                                   groups * 64 * sizeof(unsigned))
+                                : (size_t)m->Dn * 2 * B * H * sizeof(unsigned long long);
+        off += align256(w.slot_bytes);
+    }
     // bf16 large-batch persistent recurrence: two exchange buffers of h_t and one flag per tile
     w.hx_off = off;
     w.mflag_off = off;
@@ -490,10 +499,11 @@ static Workspace carve(const lstm_t* m, int T, int B)
         w.mflag_off = off;
         off += align256(persist_mfma_flag_count(B, (int)H) * sizeof(unsigned));
     }
-    // H-LSTM, stepwise path: hidden-layer activations of the current step, [B][4G] per direction
+    // H-LSTM: hidden-layer activations of the current step, [B][4G] per direction (stepwise paths); the small-batch
+    // persistent kernel uses both directions' storage as one array of [k][columns of a batch group] blocks
     for (int d = 0; d < 2; ++d) {
         w.U_off[d] = off;
-        if (m->G > 0 && d < m->Dn) off += align256((size_t)B * 4 * m->G * sizeof(float));
+        if (m->G > 0 && d < m->Dn) off += align256(((size_t)B + 3) * 4 * m->G * sizeof(float) + ((size_t)B / 2 + 1) * 256);
     }
     w.total = off;
     return w;
@@ -583,6 +593,8 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
     float* cbuf[2] = {(float*)(base + ws.c_off[0]), (float*)(base + ws.c_off[1])};
     float* U[2] = {(float*)(base + ws.U_off[0]), (float*)(base + ws.U_off[1])};
     char tag[96];
+    bool hslots_clean = false;   // exchange slots and flags zeroed during this forward (tags then restart at 1)
+    unsigned htag = 0;
     for (int l = 0; l < L; ++l) {
         const int D = m->in_dim(l);
         const void* X = (l == 0) ? x : (const void*)Ybuf[(l - 1) & 1];
@@ -595,7 +607,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
             persist[d] = B == 1 && m->plan != LSTM_PLAN_STEPWISE && w.wx.compressed && w.wh.compressed && w.w2.compressed &&
                          w.wx.ell_val && w.wh.ell_val && w.w2.ell_val &&
                          persist_b1_hlstm_supported(H, G, D, w.wx.slots, w.wh.slots, w.w2.slots);
-            if (m->plan == LSTM_PLAN_PERSISTENT && !persist[d])
+            if (m->plan == LSTM_PLAN_PERSISTENT && B == 1 && !persist[d])
                 return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
         }
         bool xt_ready = false;
@@ -619,6 +631,95 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 HIP_TRY(m, launch_proj_mfma(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s));
             } else {
                 HIP_TRY(m, launch_proj_dense(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s));
+            }
+        }
+        // small batch, W1h and W2 of every direction row-compressed and small enough for registers: one launch per
+        // layer with the time loop on the device
+        {
+            int nz = 1, upw = 0, bw = 0, ug = 0, bg = 0;
+            bool pb_ok = B >= 2 && m->plan != LSTM_PLAN_STEPWISE;
+            bool trimmed = false;
+            if (pb_ok) {
+                // first with the slices cut to the common row length (a wave takes at most 64 overflow entries over
+                // the units it owns), then with the full slices
+                auto slots_of = [&](const PackedMat& p, bool trim) { return trim && p.slots_trim > 0 ? p.slots_trim : p.slots; };
+                auto wave_fits = [&](const PackedMat& p, int upw_) {
+                    if (p.slots_trim == 0) return true;
+                    const int units = (int)p.h_ovf_ptr.size() - 1;
+                    for (int u = 0; u < units; u += upw_)
+                        if (p.h_ovf_ptr[(size_t)std::min(u + upw_, units)] - p.h_ovf_ptr[(size_t)u] > 64) return false;
+                    return true;
+                };
+                bool found = false;
+                for (int pass = 0; pass < 2 && !found; ++pass) {
+                    const bool trim = pass == 0;
+                    bool ok = true, any_trim = false;
+                    nz = 1;
+                    for (int d = 0; d < Dn && ok; ++d) {
+                        const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                        ok = w.wh.compressed && w.w2.compressed && (w.wh.ell_val || (trim && w.wh.slots_trim)) &&
+                             (w.w2.ell_val || (trim && w.w2.slots_trim));
+                        nz = std::max(nz, std::max(slots_of(w.wh, trim), slots_of(w.w2, trim)));
+                        any_trim = any_trim || (trim && (w.wh.slots_trim || w.w2.slots_trim));
+                    }
+                    if (trim && !any_trim) continue;
+                    ok = ok && persist_batched_h_plan(B, H, G, nz, Dn, &upw, &bw, &ug, &bg);
+                    for (int d = 0; d < Dn && ok && trim; ++d) {
+                        const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                        ok = wave_fits(w.wh, upw) && wave_fits(w.w2, upw);
+                    }
+                    if (ok) { found = true; trimmed = trim; }
+                }
+                pb_ok = found;
+            }
+            if (m->plan == LSTM_PLAN_PERSISTENT && B >= 2 && !pb_ok)
+                return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
+            if (pb_ok) {
+                unsigned long long* hslots = (unsigned long long*)(base + ws.slot_off);
+                const size_t groups = (size_t)B / 2 + 1;
+                const size_t hslot_bytes = (size_t)Dn * (((size_t)B + 3) * H * sizeof(unsigned long long) + groups * 256);
+                unsigned* hflags = (unsigned*)(base + ws.slot_off + hslot_bytes);
+                if (!hslots_clean) {
+                    HIP_TRY(m, launch_fill_u64(hslots, align256(ws.slot_bytes) / sizeof(unsigned long long), 0ull, s));
+                    hslots_clean = true;
+                    htag = 0;
+                }
+                PersistBatchedHArgs a{};
+                for (int d = 0; d < Dn; ++d) {
+                    const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                    const size_t n = (size_t)l * Dn + d;
+                    PersistBatchedHDir& q = a.d[d];
+                    q.P1 = P[d];
+                    if (trimmed && w.wh.slots_trim > 0) {
+                        q.ell_val_1h = w.wh.ell_val_trim; q.ell_col_1h = w.wh.ell_col_trim; q.slots_1h = w.wh.slots_trim;
+                        q.ovf_ptr_1h = w.wh.ovf_ptr; q.ovf_ent_1h = w.wh.ovf_ent; q.ovf_val_1h = w.wh.ovf_val;
+                    } else {
+                        q.ell_val_1h = w.wh.ell_val; q.ell_col_1h = w.wh.ell_col; q.slots_1h = w.wh.slots;
+                    }
+                    if (trimmed && w.w2.slots_trim > 0) {
+                        q.ell_val_2 = w.w2.ell_val_trim; q.ell_col_2 = w.w2.ell_col_trim; q.slots_2 = w.w2.slots_trim;
+                        q.ovf_ptr_2 = w.w2.ovf_ptr; q.ovf_ent_2 = w.w2.ovf_ent; q.ovf_val_2 = w.w2.ovf_val;
+                    } else {
+                        q.ell_val_2 = w.w2.ell_val; q.ell_col_2 = w.w2.ell_col; q.slots_2 = w.w2.slots;
+                    }
+                    q.bias2 = w.bias2;
+                    q.h0 = h0 ? h0 + n * B * H : nullptr;
+                    q.c0 = c0 ? c0 + n * B * H : nullptr;
+                    q.y = Yout + (size_t)d * H; q.y_ld = y_ld;
+                    q.hT = hT ? hT + n * B * H : nullptr;
+                    q.cT = cT ? cT + n * B * H : nullptr;
+                    q.reverse = d;
+                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-hlstm-csr%s(u%d,b%d);", l, d,
+                                  proj_dense[d] ? "dense" : "csr", trimmed ? "+ovf" : "", upw, bw);
+                    m->last_plan += tag;
+                }
+                a.T = T; a.B = B; a.H = H; a.G = G;
+                a.xchg_h = hslots; a.xchg_u = U[0]; a.flags = hflags;
+                a.tag_base = htag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                htag += (unsigned)T + 1u;
+                ProfSpan span(m, s, 1);
+                HIP_TRY(m, launch_persist_batched_h(a, Dn, nz, m->cooperative, s));
+                continue;
             }
         }
         // small batch, every direction row-compressed: both stages of a step for all directions in two launches

@@ -140,6 +140,60 @@ def test_hlstm_persistent_long_sequence_and_state_chaining():
     np.testing.assert_array_equal(c2.cpu().numpy(), full[2])
 
 
+# ---- small batches, row-compressed: one persistent launch per layer, 2-D grid of unit groups x batch groups -------
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, G, T, B, keep, cooperative
+    (1, False, 40, 150, 150, 11, 2, 0.3, True),
+    (1, False, 33, 64, 200, 9, 3, 0.9, True),       # more hidden-layer units than outputs; ragged batch group
+    (2, False, 90, 200, 70, 8, 5, 0.25, True),      # fewer hidden-layer units than outputs; two layers share the slots
+    (1, True, 50, 130, 90, 7, 16, 0.5, False),      # both directions in one grid, ordinary launch
+    (3, True, 31, 96, 96, 5, 17, 0.15, True),
+    (1, False, 20, 333, 257, 1, 4, 0.4, True),      # T = 1: no exchange of h at all
+    (1, True, 64, 400, 400, 6, 16, 0.35, True),     # three slices per row, 4 units per wave and 4 columns
+    (1, False, 30, 37, 41, 9, 33, 0.6, True),       # many batch groups, few units
+])
+def test_hlstm_persistent_small_batch(shape):
+    L, bidir, D, H, G, T, Bn, keep, coop = shape
+    case = inputs.make_case(_hw(85, L, bidir, D, H, G, T, Bn, keep=keep), k=H + G + T + Bn, random_state=True)
+    desc, _ = check_case(case, CSR, PERSIST, cooperative=coop)
+    assert "persist_batched-hlstm" in desc
+    desc, _ = check_case(case, CSR, PAUTO, cooperative=coop)
+    assert "persist_batched-hlstm" in desc
+
+
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, G, T, B, keep -- a few rows a little longer than a multiple of 64 kept entries: the slices hold
+    # the common row length, the remainder comes from per-unit overflow lists
+    (1, True, 100, 400, 400, 7, 4, 0.12),
+    (2, False, 120, 410, 380, 6, 7, 0.27),
+    (1, False, 64, 600, 520, 5, 16, 0.18),
+])
+def test_hlstm_persistent_small_batch_overflow_rows(shape):
+    L, bidir, D, H, G, T, Bn, keep = shape
+    case = inputs.make_case(_hw(87, L, bidir, D, H, G, T, Bn, keep=keep), k=L, random_state=True)
+    desc, _ = check_case(case, CSR, PERSIST)
+    assert "persist_batched-hlstm-csr+ovf" in desc
+
+
+def test_hlstm_persistent_small_batch_long_sequence_and_state_chaining():
+    case = inputs.make_case(_hw(86, 1, True, 48, 200, 160, 700, 6, a=0.3, keep=0.2), k=0, random_state=True)
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "persist_batched-hlstm" in desc
+    import torch
+    full, _, model = run_gpu(case, CSR, PAUTO, return_model=True)
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(case.x).to(dev)
+    h0 = torch.from_numpy(case.h0).to(dev); c0 = torch.from_numpy(case.c0).to(dev)
+    # repeated forwards on one handle give the same bits (slots and flags restart cleanly)
+    ya, ha, ca = model.forward(x, h0, c0)
+    yb, hb, cb = model.forward(x, h0, c0)
+    model.close()
+    np.testing.assert_array_equal(ya.cpu().numpy(), full[0])
+    np.testing.assert_array_equal(yb.cpu().numpy(), full[0])
+    np.testing.assert_array_equal(hb.cpu().numpy(), full[1])
+    np.testing.assert_array_equal(cb.cpu().numpy(), full[2])
+
+
 def test_hlstm_full_size_language_model():
     """The paper's language-model H-LSTM shape (one layer, 1500 / 1500, embeddings of 400), batch 1, 10 % kept."""
     case = inputs.make_case(inputs.h1(), 0)
@@ -152,4 +206,5 @@ def test_hlstm_full_size_speech_sampled_columns():
     """The paper's speech H-LSTM shape (3 bidirectional layers, 800 / 800, batch 16); the oracle runs two of the
     sixteen sequences (sequences are independent)."""
     case = inputs.make_case(inputs.h2(), 0)
-    check_case(case, AUTO, PAUTO, oracle_cols=[3, 12])
+    desc, _ = check_case(case, AUTO, PAUTO, oracle_cols=[3, 12])
+    assert "persist_batched-hlstm" in desc
