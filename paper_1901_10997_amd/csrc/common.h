@@ -354,6 +354,7 @@ struct PersistBatchedHArgs {
     PersistBatchedHDir d[2];
     int T, B, H, G;
     int ug, bg;                 // unit groups / batch groups per direction (filled by the launcher)
+    int ndir, xcd_local;        // directions in the grid; block ids grouped by XCD (filled by the launcher)
     size_t h_stride, u_stride;  // elements per (direction, batch group) in xchg_h / xchg_u (filled by the launcher)
     unsigned long long* xchg_h; // tagged slots, zero or older tags only
     float* xchg_u;              // plain values

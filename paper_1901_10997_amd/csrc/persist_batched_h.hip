@@ -19,12 +19,13 @@
 //         the tag matches), laid out [k][BW] per batch group so that the poll is a straight copy into LDS;
 //   u_t   (4G values per column, four times as many) as plain fp32 in the same [k][BW] layout (k = q*G + g), written
 //         with device-scope write-through stores; when a workgroup's stores have been acknowledged it raises its
-//         flag to the step tag.  A consumer's first wave polls the flags of its batch group, executes one
-//         device-scope acquire fence (stale lines leave this compute unit's vector cache and this XCD's L2), and
-//         after a barrier the workgroup copies the vector with ordinary 16-byte loads.
+//         flag to the step tag.  A consumer's first wave polls the flags of its batch group; after a barrier the
+//         workgroup copies the vector with device-scope 8-byte loads, all of a thread's loads in flight at once.
+//         (An acquire fence followed by ordinary cached loads measured three times slower for these 50 KB.)
 // One array per vector is enough: u_{t+1} is written only after its producer has received every h_t of the batch
 // group, and each of those was published after its producer had finished reading u_t (and the same with the roles
 // swapped).  All waits are bounded: on expiry a device flag is raised, every wave stops waiting, the kernel drains.
+#include <type_traits>
 #include "common.h"
 #include "device_math.h"
 #include "exchange.h"
@@ -43,7 +44,7 @@ template <int NZ, int UPW, int BW>
 __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatchedHArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];  // hbuf[H][BW] | ubuf[4G][BW]
-    constexpr int NZP = (NZ + 1) / 2;
+    constexpr int NZP = (4 * NZ + 1) / 2;   // packed 16-bit offsets of a unit's 4*NZ slices, two to a register
     constexpr int PAIRS = UPW * BW;
     static_assert(PAIRS <= 16, "pairs must fit one 16-lane row");
     const int H = a.H, G = a.G, B = a.B;
@@ -52,11 +53,22 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
     constexpr int upb = kWaves * UPW;
     float* hbuf = lds;
     float* ubuf = lds + (((size_t)BW * H + 3) & ~(size_t)3);   // 16-byte aligned for the row copy
-    // block -> (direction, batch group, unit group)
-    const int per_dir = a.ug * a.bg;
-    const int dir = blockIdx.x / per_dir;
-    const int rem = blockIdx.x % per_dir;
-    const int bgi = rem / a.ug, ugi = rem % a.ug;
+    // block -> (direction, batch group, unit group).  Workgroups are dealt to the eight XCDs in turn; when the
+    // groups fit, all workgroups of one (direction, batch group) -- the only ones that exchange data -- take ids of
+    // one residue modulo 8 and so share an L2: a vector is then fetched from memory once per step instead of once per
+    // XCD.  (Only speed depends on that dealing order.)
+    int dir, bgi, ugi;
+    if (a.xcd_local) {
+        const int j = blockIdx.x >> 3;
+        const int g = (blockIdx.x & 7) + 8 * (j / a.ug);
+        if (g >= a.ndir * a.bg) return;     // padding ids take no part in the exchange
+        ugi = j % a.ug; dir = g / a.bg; bgi = g % a.bg;
+    } else {
+        const int per_dir = a.ug * a.bg;
+        dir = blockIdx.x / per_dir;
+        const int rem = blockIdx.x % per_dir;
+        bgi = rem / a.ug; ugi = rem % a.ug;
+    }
     const PersistBatchedHDir& D = a.d[dir];
     const int b0 = bgi * BW;
     const int bw = (B - b0) < BW ? (B - b0) : BW;         // columns actually present
@@ -68,13 +80,13 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
 
     // kept weights of this wave's units; the column is kept as the 16-bit LDS byte offset of its BW values
     float w1[UPW][4][NZ], w2[UPW][4][NZ];
-    unsigned o1[UPW][4][NZP], o2[UPW][4][NZP];
+    unsigned o1[UPW][NZP], o2[UPW][NZP];
 #pragma unroll
-    for (int u = 0; u < UPW; ++u)
+    for (int u = 0; u < UPW; ++u) {
+#pragma unroll
+        for (int i = 0; i < NZP; ++i) o1[u][i] = o2[u][i] = 0u;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-#pragma unroll
-            for (int i = 0; i < NZP; ++i) o1[u][q][i] = o2[u][q][i] = 0u;
 #pragma unroll
             for (int i = 0; i < NZ; ++i) {
                 float v1 = 0.f, v2 = 0.f;
@@ -91,10 +103,12 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
                 }
                 w1[u][q][i] = v1;
                 w2[u][q][i] = v2;
-                o1[u][q][i >> 1] |= (k1 * (BW * 4u)) << (16 * (i & 1));                       // h[k][0]
-                o2[u][q][i >> 1] |= (((unsigned)q * G + k2) * (BW * 4u)) << (16 * (i & 1));   // u[q*G + k][0]
+                const int n = q * NZ + i;
+                o1[u][n >> 1] |= (k1 * (BW * 4u)) << (16 * (n & 1));                       // h[k][0]
+                o2[u][n >> 1] |= (((unsigned)q * G + k2) * (BW * 4u)) << (16 * (n & 1));   // u[q*G + k][0]
             }
         }
+    }
     // lane 16*gate + pair: pair = local unit * BW + column
     const int lp = lane & 15, row = lane >> 4;
     const int pu = lp / BW, pb = lp % BW;
@@ -138,59 +152,73 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
     load_overflow(D.ovf_ptr_2, D.ovf_ent_2, D.ovf_val_2, H, true, e2, ev2, n2);
 
     // gathers of one stage: acc over the NZ slices of every unit, reduced into lane 16*gate + pair
-    auto products = [&](const float (&wv)[UPW][4][NZ], const unsigned (&wo)[UPW][4][NZP], const int (&cnt)[UPW], unsigned eo,
+    // The gathers are software-pipelined by hand in groups of GS (gates q0..q0+GS-1 of slice i of one unit): the next
+    // group's reads are issued before the current group's multiply-adds, so that LDS latency overlaps arithmetic (left
+    // to itself the compiler waits for every read on its own).  Two groups of read results are live at a time; the
+    // configurations with the most weight registers take the smaller group.
+    using VT = typename std::conditional<BW == 2, float2, float4>::type;
+    constexpr int GS = (12 * NZ * UPW > 128 && BW == 4) ? 2 : 4;
+    auto products = [&](const float (&wv)[UPW][4][NZ], const unsigned (&wo)[UPW][NZP], const int (&cnt)[UPW], unsigned eo,
                         float evv, const float* vec) -> float {
+        constexpr int GPS = 4 / GS;            // groups per slice
+        constexpr int NG = UPW * NZ * GPS;
+        auto read_group = [&](int g, VT (&dst)[GS]) {
+            const int u = g / (NZ * GPS), i = (g / GPS) % NZ, q0 = (g % GPS) * GS;
+#pragma unroll
+            for (int k = 0; k < GS; ++k) {
+                const int n = (q0 + k) * NZ + i;
+                const unsigned off = (wo[u][n >> 1] >> (16 * (n & 1))) & 0xFFFFu;
+                dst[k] = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(vec) + off);
+            }
+        };
         float Gv = 0.f;
+        VT hv[2][GS];
+        float acc[4][BW];
+        read_group(0, hv[0]);
 #pragma unroll
-        for (int u = 0; u < UPW; ++u) {
-            float acc[4][BW];
+        for (int g = 0; g < NG; ++g) {
+            const int u = g / (NZ * GPS), i = (g / GPS) % NZ, q0 = (g % GPS) * GS;
+            if (g + 1 < NG) read_group(g + 1, hv[(g + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i == 0 && q0 == 0) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int b = 0; b < BW; ++b) acc[q][b] = 0.f;
-#pragma unroll
-            for (int i = 0; i < NZ; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float w = wv[u][q][i];
-                    const unsigned off = (wo[u][q][i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
-                    const float* vp = reinterpret_cast<const float*>(reinterpret_cast<const char*>(vec) + off);
-                    if constexpr (BW == 2) {
-                        const float2 hv = *reinterpret_cast<const float2*>(vp);
-                        acc[q][0] = fmaf(w, hv.x, acc[q][0]);
-                        acc[q][1] = fmaf(w, hv.y, acc[q][1]);
-                    } else {
-                        const float4 hv = *reinterpret_cast<const float4*>(vp);
-                        acc[q][0] = fmaf(w, hv.x, acc[q][0]);
-                        acc[q][1] = fmaf(w, hv.y, acc[q][1]);
-                        acc[q][2] = fmaf(w, hv.z, acc[q][2]);
-                        acc[q][3] = fmaf(w, hv.w, acc[q][3]);
-                    }
-                }
-            if (cnt[u] > 0) {
-                // this unit's overflow entries, one per lane, into the partial sum of the gate each belongs to
-                const float v = ((eo >> 18) & 15u) == (unsigned)u ? evv : 0.f;
-                const unsigned g = (eo >> 16) & 3u;
-                const float* vp = reinterpret_cast<const float*>(reinterpret_cast<const char*>(vec) + (eo & 0xFFFFu));
-                float hv[BW];
-                if constexpr (BW == 2) {
-                    const float2 t = *reinterpret_cast<const float2*>(vp);
-                    hv[0] = t.x; hv[1] = t.y;
-                } else {
-                    const float4 t = *reinterpret_cast<const float4*>(vp);
-                    hv[0] = t.x; hv[1] = t.y; hv[2] = t.z; hv[3] = t.w;
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float vq = (g == (unsigned)q) ? v : 0.f;
-#pragma unroll
-                    for (int b = 0; b < BW; ++b) acc[q][b] = fmaf(vq, hv[b], acc[q][b]);
-                }
+                    for (int b = 0; b < BW; ++b) acc[q][b] = 0.f;
             }
 #pragma unroll
-            for (int b = 0; b < BW; ++b) {
-                const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
-                Gv = (lp == u * BW + b) ? r : Gv;
+            for (int k = 0; k < GS; ++k) {
+                const int q = q0 + k;
+                const float w = wv[u][q][i];
+                const VT& x = hv[g & 1][k];
+                acc[q][0] = fmaf(w, x.x, acc[q][0]);
+                acc[q][1] = fmaf(w, x.y, acc[q][1]);
+                if constexpr (BW == 4) {
+                    acc[q][2] = fmaf(w, x.z, acc[q][2]);
+                    acc[q][3] = fmaf(w, x.w, acc[q][3]);
+                }
+            }
+            if (i == NZ - 1 && q0 + GS == 4) {
+                if (cnt[u] > 0) {
+                    // this unit's overflow entries, one per lane, into the partial sum of the gate each belongs to
+                    const float v = ((eo >> 18) & 15u) == (unsigned)u ? evv : 0.f;
+                    const unsigned gq = (eo >> 16) & 3u;
+                    const VT t = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(vec) + (eo & 0xFFFFu));
+                    float xv[BW];
+                    xv[0] = t.x; xv[1] = t.y;
+                    if constexpr (BW == 4) { xv[2] = t.z; xv[3] = t.w; }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float vq = (gq == (unsigned)q) ? v : 0.f;
+#pragma unroll
+                        for (int b = 0; b < BW; ++b) acc[q][b] = fmaf(vq, xv[b], acc[q][b]);
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < BW; ++b) {
+                    const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
+                    Gv = (lp == u * BW + b) ? r : Gv;
+                }
             }
         }
         return Gv;
@@ -204,12 +232,10 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
 #pragma unroll
         for (int u = 0; u < UPW; ++u)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int i = 0; i < NZP; ++i) {
-                    asm volatile("" : "+v"(o1[u][q][i]));
-                    asm volatile("" : "+v"(o2[u][q][i]));
-                }
+            for (int i = 0; i < NZP; ++i) {
+                asm volatile("" : "+v"(o1[u][i]));
+                asm volatile("" : "+v"(o2[u][i]));
+            }
         asm volatile("" : "+v"(e1), "+v"(e2));   // likewise the per-gate selections of the overflow entry
         float pin = 0.f;
         if (ok1) pin = D.P1[((size_t)t * B + b0 + pb) * (4 * (size_t)G) + 4 * unit_l + row];
@@ -245,14 +271,28 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
                 if ((spins & 255u) == 0 && __hip_atomic_load(a.timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
                     break;
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
         __syncthreads();
         {
-            const float4* src = reinterpret_cast<const float4*>(xu);
-            float4* dst = reinterpret_cast<float4*>(ubuf);
-            const int n4 = G * BW;   // 4G*BW floats
-            for (int e = tid; e < n4; e += nthreads) dst[e] = src[e];
+            // the flags say every producer's stores have reached memory: device-scope loads (which do not hit stale
+            // lines of this compute unit's vector cache or this XCD's L2) fetch them, sixteen 8-byte loads per thread in
+            // flight at once
+            const u64* src = reinterpret_cast<const u64*>(xu);
+            u64* dst = reinterpret_cast<u64*>(ubuf);
+            const int nw = 2 * G * BW;   // 4G*BW floats, two to a load
+            for (int e0 = tid; e0 < nw; e0 += 16 * nthreads) {
+                u64 v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int e = e0 + u * nthreads;
+                    v[u] = e < nw ? __hip_atomic_load(src + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int e = e0 + u * nthreads;
+                    if (e < nw) dst[e] = v[u];
+                }
+            }
         }
         __syncthreads();
         {
@@ -347,7 +387,11 @@ hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int nz, in
     a.bg = bg;
     a.h_stride = persist_batched_h_hstride(a.H, bw);
     a.u_stride = persist_batched_h_ustride(a.G, bw);
-    const int blocks = ug * bg * ndir;
+    // one XCD holds an eighth of the compute units; its share of the groups must fit there
+    const int per_xcd = (ndir * bg + 7) / 8;
+    a.ndir = ndir;
+    a.xcd_local = per_xcd * ug <= device_num_cus() / 8;
+    const int blocks = a.xcd_local ? 8 * per_xcd * ug : ug * bg * ndir;
     switch (nz) {
         case 1: return launch_nz<1>(a, upw, bw, blocks, cooperative != 0, s);
         case 2: return launch_nz<2>(a, upw, bw, blocks, cooperative != 0, s);
