@@ -303,6 +303,11 @@ struct PersistBatchedDir {
     const float* ell_val;      // [4H][slots][64]
     const uint16_t* ell_col;
     int slots;
+    // per-unit overflow lists of rows longer than 64*slots entries (nullptr: none); entry = (gate << 16) | column;
+    // the entries of the units one wave owns must not exceed 64
+    const int32_t* ovf_ptr;
+    const uint32_t* ovf_ent;
+    const float* ovf_val;
     const float* h0;           // [B][H] or nullptr
     const float* c0;
     float* y;                  // h_t -> y[(t*B + b)*y_ld + j]  (already offset to this direction's columns)

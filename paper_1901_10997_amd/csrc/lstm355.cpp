@@ -1086,14 +1086,37 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
         }
         // ---- recurrence, small-batch row-compressed, time loop on the device (all directions in one launch)
         {
-            int nzmax = 0, upw, bw, ug, bg;
+            int nzmax = 0, upw = 0, bw = 0, ug = 0, bg = 0;
             bool pb_ok = B >= 2 && m->plan != LSTM_PLAN_STEPWISE;
-            for (int d = 0; d < Dn && pb_ok; ++d) {
-                const LayerDir& w = m->ld[(size_t)l * Dn + d];
-                pb_ok = w.wh.compressed && w.wh.ell_val != nullptr && w.wh.slots <= 4;
-                nzmax = std::max(nzmax, w.wh.slots);
+            bool trimmed = false;
+            if (pb_ok) {
+                // first with the slices cut to the common row length (a wave takes at most 64 overflow entries over
+                // the units it owns), then with the full slices
+                bool found = false;
+                for (int pass = 0; pass < 2 && !found; ++pass) {
+                    const bool trim = pass == 0;
+                    bool ok = true, any_trim = false;
+                    nzmax = 0;
+                    for (int d = 0; d < Dn && ok; ++d) {
+                        const PackedMat& p = m->ld[(size_t)l * Dn + d].wh;
+                        const bool use_trim = trim && p.slots_trim > 0;
+                        ok = p.compressed && (use_trim || p.ell_val != nullptr);
+                        nzmax = std::max(nzmax, use_trim ? p.slots_trim : p.slots);
+                        any_trim = any_trim || use_trim;
+                    }
+                    if (trim && !any_trim) continue;
+                    ok = ok && nzmax <= 4 && persist_batched_plan(B, H, nzmax, Dn, &upw, &bw, &ug, &bg);
+                    for (int d = 0; d < Dn && ok && trim; ++d) {
+                        const PackedMat& p = m->ld[(size_t)l * Dn + d].wh;
+                        if (p.slots_trim == 0) continue;
+                        const int units = (int)p.h_ovf_ptr.size() - 1;
+                        for (int u = 0; u < units && ok; u += upw)
+                            ok = p.h_ovf_ptr[(size_t)std::min(u + upw, units)] - p.h_ovf_ptr[(size_t)u] <= 64;
+                    }
+                    if (ok) { found = true; trimmed = trim; }
+                }
+                pb_ok = found;
             }
-            pb_ok = pb_ok && persist_batched_plan(B, H, nzmax, Dn, &upw, &bw, &ug, &bg);
             if (pb_ok) {
                 if (!bslots_clean) {
                     HIP_TRY(m, launch_fill_u64(bslots, (size_t)Dn * 2 * B * H, 0ull, s));
@@ -1105,15 +1128,21 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                     const LayerDir& w = m->ld[(size_t)l * Dn + d];
                     const size_t n = (size_t)l * Dn + d;
                     a.d[d].P = P[d];
-                    a.d[d].ell_val = w.wh.ell_val; a.d[d].ell_col = w.wh.ell_col; a.d[d].slots = w.wh.slots;
+                    if (trimmed && w.wh.slots_trim > 0) {
+                        a.d[d].ell_val = w.wh.ell_val_trim; a.d[d].ell_col = w.wh.ell_col_trim; a.d[d].slots = w.wh.slots_trim;
+                        a.d[d].ovf_ptr = w.wh.ovf_ptr; a.d[d].ovf_ent = w.wh.ovf_ent; a.d[d].ovf_val = w.wh.ovf_val;
+                    } else {
+                        a.d[d].ell_val = w.wh.ell_val; a.d[d].ell_col = w.wh.ell_col; a.d[d].slots = w.wh.slots;
+                    }
                     a.d[d].h0 = h0 ? h0 + n * B * H : nullptr;
                     a.d[d].c0 = c0 ? c0 + n * B * H : nullptr;
                     a.d[d].y = Yout + (size_t)d * H; a.d[d].y_ld = y_ld;
                     a.d[d].hT = hT ? hT + n * B * H : nullptr;
                     a.d[d].cT = cT ? cT + n * B * H : nullptr;
                     a.d[d].reverse = d;
-                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-csr(u%d,b%d);", l, d,
-                                  (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr", upw, bw);
+                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-csr%s(u%d,b%d);", l, d,
+                                  (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
+                                  trimmed ? "+ovf" : "", upw, bw);
                     m->last_plan += tag;
                 }
                 a.T = T; a.B = B; a.H = H; a.round_h_bf16 = bf16;

@@ -13,6 +13,7 @@
 // and updates c and h in lanes 0..pairs-1.  h travels between workgroups through tagged 64-bit slots (value
 // and step tag published by one store; consumers poll until the tag matches), laid out [parity][B][H] per
 // direction so that a batch group's columns are contiguous.  All waits are bounded.
+#include <type_traits>
 #include "common.h"
 #include "device_math.h"
 #include "exchange.h"
@@ -23,7 +24,6 @@ template <int NZ, int UPW, int BW>
 __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatchedArgs a)
 {
     extern __shared__ float lds[];  // hbuf[H][BW] (the BW batch values of one k adjacent) | pub[BW][UPB]
-    constexpr int NZP = (NZ + 1) / 2;
     constexpr int PAIRS = UPW * BW;
     static_assert(PAIRS <= 16, "pairs must fit one 16-lane row");
     const int H = a.H, B = a.B;
@@ -44,15 +44,16 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
     u64* xchg = a.xchg + (size_t)dir * 2 * B * H;
 
     // kept weights of this wave's units: values in fp32 registers; the column is kept as the 16-bit LDS byte
-    // offset of its h values, two to a register
+    // offset of its h values, the 4*NZ offsets of a unit packed two to a register
+    constexpr int NZP = (4 * NZ + 1) / 2;
     float wv[UPW][4][NZ];
-    unsigned wc[UPW][4][NZP];
+    unsigned wc[UPW][NZP];
 #pragma unroll
-    for (int u = 0; u < UPW; ++u)
+    for (int u = 0; u < UPW; ++u) {
+#pragma unroll
+        for (int i = 0; i < NZP; ++i) wc[u][i] = 0u;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-#pragma unroll
-            for (int i = 0; i < NZP; ++i) wc[u][q][i] = 0u;
 #pragma unroll
             for (int i = 0; i < NZ; ++i) {
                 float v = 0.f;
@@ -63,9 +64,35 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
                     k = D.ell_col[idx];
                 }
                 wv[u][q][i] = v;
-                wc[u][q][i >> 1] |= (k * (BW * 4u)) << (16 * (i & 1));   // byte offset of h[k][0] in LDS (< 65536)
+                const int n = q * NZ + i;
+                wc[u][n >> 1] |= (k * (BW * 4u)) << (16 * (n & 1));   // byte offset of h[k][0] in LDS (< 65536)
             }
         }
+    }
+    // Overflow entries of this wave's units (rows longer than 64*slots; rare): the lists of consecutive units are
+    // adjacent, lane e holds entry e of the wave's run, packed as LDS byte offset | gate << 16 | local unit << 18
+    // (local unit 15: no entry).  The per-unit counts are wave-uniform.
+    unsigned eo = 15u << 18;
+    float evv = 0.f;
+    int cnt[UPW];
+#pragma unroll
+    for (int u = 0; u < UPW; ++u) cnt[u] = 0;
+    if (D.ovf_ptr != nullptr && u0 < H) {
+        const int first = D.ovf_ptr[u0];
+        int pos = first;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            const int nxt = (u0 + u < H) ? D.ovf_ptr[u0 + u + 1] : pos;
+            cnt[u] = __builtin_amdgcn_readfirstlane(nxt - pos);
+            const int idx = first + lane;
+            if (idx >= pos && idx < nxt) {
+                const unsigned e = D.ovf_ent[idx];
+                eo = ((e & 0xFFFFu) * (BW * 4u)) | ((e >> 16) << 16) | ((unsigned)u << 18);
+                evv = D.ovf_val[idx];
+            }
+            pos = nxt;
+        }
+    }
     // lane 16*gate + pair: pair = local unit * BW + column
     const int lp = lane & 15, row = lane >> 4;
     const int pu = lp / BW, pb = lp % BW;
@@ -90,37 +117,77 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
                                      tid, nthreads, a.timeout_flag, a.spin_limit);
         }
         __syncthreads();
+        // The gathers are software-pipelined by hand in groups of GS (gates q0..q0+GS-1 of slice i of one unit): the
+        // next group's reads are issued before the current group's multiply-adds, so that LDS latency overlaps
+        // arithmetic (left to itself the compiler waits for every read on its own).
+        asm volatile("" : "+v"(eo));   // keeps the selections derived from it out of loop-invariant registers
+#pragma unroll
+        for (int u = 0; u < UPW; ++u)
+#pragma unroll
+            for (int i = 0; i < NZP; ++i) asm volatile("" : "+v"(wc[u][i]));   // offsets stay packed
         float G = 0.f;
+        {
+            using VT = typename std::conditional<BW == 2, float2, float4>::type;
+            constexpr int GS = (6 * NZ * UPW > 128) ? 2 : 4;
+            constexpr int GPS = 4 / GS;            // groups per slice
+            constexpr int NG = UPW * NZ * GPS;
+            auto read_group = [&](int g, VT (&dst)[GS]) {
+                const int u = g / (NZ * GPS), i = (g / GPS) % NZ, q0 = (g % GPS) * GS;
 #pragma unroll
-        for (int u = 0; u < UPW; ++u) {
+                for (int k = 0; k < GS; ++k) {
+                    const int n = (q0 + k) * NZ + i;
+                    const unsigned off = (wc[u][n >> 1] >> (16 * (n & 1))) & 0xFFFFu;
+                    dst[k] = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + off);
+                }
+            };
+            VT hv[2][GS];
             float acc[4][BW];
+            read_group(0, hv[0]);
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int g = 0; g < NG; ++g) {
+                const int u = g / (NZ * GPS), i = (g / GPS) % NZ, q0 = (g % GPS) * GS;
+                if (g + 1 < NG) read_group(g + 1, hv[(g + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (i == 0 && q0 == 0) {
 #pragma unroll
-                for (int b = 0; b < BW; ++b) acc[q][b] = 0.f;
+                    for (int q = 0; q < 4; ++q)
 #pragma unroll
-            for (int i = 0; i < NZ; ++i)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float w = wv[u][q][i];
-                    const unsigned off = (wc[u][q][i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
-                    const float* hp = reinterpret_cast<const float*>(reinterpret_cast<const char*>(hbuf) + off);
-                    if constexpr (BW == 2) {
-                        const float2 hv = *reinterpret_cast<const float2*>(hp);
-                        acc[q][0] = fmaf(w, hv.x, acc[q][0]);
-                        acc[q][1] = fmaf(w, hv.y, acc[q][1]);
-                    } else {
-                        const float4 hv = *reinterpret_cast<const float4*>(hp);
-                        acc[q][0] = fmaf(w, hv.x, acc[q][0]);
-                        acc[q][1] = fmaf(w, hv.y, acc[q][1]);
-                        acc[q][2] = fmaf(w, hv.z, acc[q][2]);
-                        acc[q][3] = fmaf(w, hv.w, acc[q][3]);
-                    }
+                        for (int b = 0; b < BW; ++b) acc[q][b] = 0.f;
                 }
 #pragma unroll
-            for (int b = 0; b < BW; ++b) {
-                const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
-                G = (lp == u * BW + b) ? r : G;
+                for (int k = 0; k < GS; ++k) {
+                    const int q = q0 + k;
+                    const float w = wv[u][q][i];
+                    const VT& x = hv[g & 1][k];
+                    acc[q][0] = fmaf(w, x.x, acc[q][0]);
+                    acc[q][1] = fmaf(w, x.y, acc[q][1]);
+                    if constexpr (BW == 4) {
+                        acc[q][2] = fmaf(w, x.z, acc[q][2]);
+                        acc[q][3] = fmaf(w, x.w, acc[q][3]);
+                    }
+                }
+                if (i == NZ - 1 && q0 + GS == 4) {
+                    if (cnt[u] > 0) {
+                        // this unit's overflow entries, one per lane, into the partial sum of the gate each belongs to
+                        const float v = ((eo >> 18) & 15u) == (unsigned)u ? evv : 0.f;
+                        const unsigned gq = (eo >> 16) & 3u;
+                        const VT t = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + (eo & 0xFFFFu));
+                        float xv[BW];
+                        xv[0] = t.x; xv[1] = t.y;
+                        if constexpr (BW == 4) { xv[2] = t.z; xv[3] = t.w; }
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const float vq = (gq == (unsigned)q) ? v : 0.f;
+#pragma unroll
+                            for (int b = 0; b < BW; ++b) acc[q][b] = fmaf(vq, xv[b], acc[q][b]);
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < BW; ++b) {
+                        const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
+                        G = (lp == u * BW + b) ? r : G;
+                    }
+                }
             }
         }
         G += pin;

@@ -92,6 +92,20 @@ def test_small_batch_persistent(shape):
     assert "stepwise" in desc
 
 
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, T, B, keep -- recurrent rows a little longer than a multiple of 64 kept entries: slices cut to
+    # the common row length plus per-unit overflow lists
+    (2, True, 100, 400, 7, 6, 0.12),
+    (1, False, 120, 600, 5, 20, 0.18),
+    (1, False, 64, 410, 6, 3, 0.27),
+])
+def test_small_batch_persistent_overflow_rows(shape):
+    L, bidir, D, H, T, Bn, keep = shape
+    case = inputs.make_case(_wl(89, L, bidir, D, H, T, Bn, keep=keep), k=H + Bn, random_state=True)
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "persist_batched-csr+ovf" in desc
+
+
 def test_bf16_small():
     for Bn, keep in ((1, None), (3, 0.3), (9, None)):
         case = inputs.make_case(_wl(92, 2, False, 48, 96, 6, Bn, dtype="bf16", a=0.2, keep=keep), k=Bn, random_state=True)
