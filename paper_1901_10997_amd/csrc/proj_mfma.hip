@@ -789,13 +789,27 @@ static hipError_t launch_f32(const float* X, int ldx, const float* W, const floa
     return hipGetLastError();
 }
 
+// Tile choice of the fp32 kernel.  The product is bound by the matrix instruction, so its time is the work of the
+// busiest compute unit: (tiles it receives) x (tile area).  128 x 128 tiles are the more efficient ones, but a grid of
+// a few hundred leaves most compute units with one tile while some have two; 64 x 64 tiles spread evenly.  The
+// smaller tile is taken when it shortens that estimate by more than a tenth.
+static bool f32_small_tiles(int M, int N, int ndir)
+{
+    if (M <= 64) return true;
+    const long cus = device_num_cus();
+    const long big = (long)((M + 127) / 128) * ((N + 127) / 128) * ndir;
+    const long small = (long)((M + 63) / 64) * ((N + 63) / 64) * ndir;
+    const long t_big = ((big + cus - 1) / cus) * 4, t_small = (small + cus - 1) / cus;
+    return t_small * 10 < t_big * 9;
+}
+
 // fp32, two directions of one layer (same X) in one launch
 hipError_t launch_proj_mfma_f32_pair(const float* X, int ldx, const float* W0, const float* bias0, float* P0,
                                      const float* W1, const float* bias1, float* P1, int M, int N, int K, hipStream_t s)
 {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (!proj_mfma_supported(false, K, ldx)) return hipErrorInvalidValue;
-    if (M <= 64) return launch_f32<1, 1>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
+    if (f32_small_tiles(M, N, W1 ? 2 : 1)) return launch_f32<1, 1>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
     return launch_f32<2, 2>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
 }
 
@@ -836,7 +850,7 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
                                (const float*)W, bias, P, M, N, K);
         return hipGetLastError();
     }
-    if (M <= 64) return launch_f32<1, 1>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
+    if (f32_small_tiles(M, N, 1)) return launch_f32<1, 1>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
     return launch_f32<2, 2>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
 }
 
