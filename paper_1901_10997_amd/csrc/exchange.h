@@ -22,19 +22,20 @@ struct PollSrc {
 };
 
 // Fetch the tagged values of up to two slot arrays into LDS.  The two arrays are treated as one index space
-// so that all outstanding loads of a thread (up to four) are in flight together, whichever array they hit.
+// so that all outstanding loads of a thread (up to NF) are in flight together, whichever array they hit.
+template <int NF = 4>
 __device__ __forceinline__ void gather_tagged2(const PollSrc& A, const PollSrc& Bs, int tid, int nthreads,
                                                int* timeout_flag, unsigned spin_limit)
 {
     const int total = A.n + Bs.n;
-    for (int e0 = tid; e0 < total; e0 += 4 * nthreads) {
-        u64 v[4];
+    for (int e0 = tid; e0 < total; e0 += NF * nthreads) {
+        u64 v[NF];
         unsigned spins = 0;
         bool ok;
         do {
             ok = true;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < NF; ++u) {
                 const int e = e0 + u * nthreads;
                 const bool second = e >= A.n;
                 const u64* p = second ? (Bs.slots + (e - A.n)) : (A.slots + e);
@@ -54,7 +55,7 @@ __device__ __forceinline__ void gather_tagged2(const PollSrc& A, const PollSrc& 
             }
         } while (!ok);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < NF; ++u) {
             const int e = e0 + u * nthreads;
             if (e < total) {
                 if (e >= A.n) Bs.dst[e - A.n] = __uint_as_float((unsigned)v[u]);
@@ -64,27 +65,30 @@ __device__ __forceinline__ void gather_tagged2(const PollSrc& A, const PollSrc& 
     }
 }
 
+// One array; a thread with more than four slots to fetch keeps eight loads in flight (one polling round less).
 __device__ __forceinline__ void gather_tagged(const u64* slots, int H, unsigned want, float* dst, int tid,
                                               int nthreads, int* timeout_flag, unsigned spin_limit)
 {
     const PollSrc A{slots, dst, want, H}, none{nullptr, nullptr, 0u, 0};
-    gather_tagged2(A, none, tid, nthreads, timeout_flag, spin_limit);
+    if (H > 4 * nthreads) gather_tagged2<8>(A, none, tid, nthreads, timeout_flag, spin_limit);
+    else gather_tagged2<4>(A, none, tid, nthreads, timeout_flag, spin_limit);
 }
 
 // As gather_tagged for `n` slots that hold cols = n / rows consecutive columns of `rows` values each, but the
 // values are stored interleaved: value (col, k) goes to dst[k * stride + col].
-__device__ __forceinline__ void gather_tagged_interleave(const u64* slots, int n, unsigned want, float* dst, int rows,
-                                                         int stride, int tid, int nthreads, int* timeout_flag,
-                                                         unsigned spin_limit)
+template <int NF>
+__device__ __forceinline__ void gather_tagged_interleave_nf(const u64* slots, int n, unsigned want, float* dst, int rows,
+                                                            int stride, int tid, int nthreads, int* timeout_flag,
+                                                            unsigned spin_limit)
 {
-    for (int e0 = tid; e0 < n; e0 += 4 * nthreads) {
-        u64 v[4];
+    for (int e0 = tid; e0 < n; e0 += NF * nthreads) {
+        u64 v[NF];
         unsigned spins = 0;
         bool ok;
         do {
             ok = true;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < NF; ++u) {
                 const int e = e0 + u * nthreads;
                 v[u] = (e < n) ? __hip_atomic_load(slots + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ((u64)want << 32);
                 ok = ok && ((unsigned)(v[u] >> 32) == want);
@@ -101,7 +105,7 @@ __device__ __forceinline__ void gather_tagged_interleave(const u64* slots, int n
             }
         } while (!ok);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < NF; ++u) {
             const int e = e0 + u * nthreads;
             if (e < n) {
                 const int col = e / rows, k = e - col * rows;
@@ -109,6 +113,14 @@ __device__ __forceinline__ void gather_tagged_interleave(const u64* slots, int n
             }
         }
     }
+}
+
+__device__ __forceinline__ void gather_tagged_interleave(const u64* slots, int n, unsigned want, float* dst, int rows,
+                                                         int stride, int tid, int nthreads, int* timeout_flag,
+                                                         unsigned spin_limit)
+{
+    if (n > 4 * nthreads) gather_tagged_interleave_nf<8>(slots, n, want, dst, rows, stride, tid, nthreads, timeout_flag, spin_limit);
+    else gather_tagged_interleave_nf<4>(slots, n, want, dst, rows, stride, tid, nthreads, timeout_flag, spin_limit);
 }
 
 }  // namespace l355

@@ -71,27 +71,26 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
     }
     // Overflow entries of this wave's units (rows longer than 64*slots; rare): the lists of consecutive units are
     // adjacent, lane e holds entry e of the wave's run, packed as LDS byte offset | gate << 16 | local unit << 18
-    // (local unit 15: no entry).  The per-unit counts are wave-uniform.
+    // (local unit 15: no entry).  Their products are added after the main loop, in waves that have any.
     unsigned eo = 15u << 18;
     float evv = 0.f;
-    int cnt[UPW];
-#pragma unroll
-    for (int u = 0; u < UPW; ++u) cnt[u] = 0;
+    unsigned ovf_units = 0u;   // bit u: local unit u has entries (wave-uniform)
     if (D.ovf_ptr != nullptr && u0 < H) {
         const int first = D.ovf_ptr[u0];
         int pos = first;
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
             const int nxt = (u0 + u < H) ? D.ovf_ptr[u0 + u + 1] : pos;
-            cnt[u] = __builtin_amdgcn_readfirstlane(nxt - pos);
             const int idx = first + lane;
             if (idx >= pos && idx < nxt) {
                 const unsigned e = D.ovf_ent[idx];
                 eo = ((e & 0xFFFFu) * (BW * 4u)) | ((e >> 16) << 16) | ((unsigned)u << 18);
                 evv = D.ovf_val[idx];
             }
+            ovf_units |= (nxt > pos ? 1u : 0u) << u;
             pos = nxt;
         }
+        ovf_units = __builtin_amdgcn_readfirstlane(ovf_units);
     }
     // lane 16*gate + pair: pair = local unit * BW + column
     const int lp = lane & 15, row = lane >> 4;
@@ -113,18 +112,18 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
                 hbuf[k * BW + b] = v;
             }
         } else {
-            gather_tagged_interleave(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H, BW,
-                                     tid, nthreads, a.timeout_flag, a.spin_limit);
+            // (eight polling loads in flight need sixteen registers: not in the configurations at the register limit)
+            if constexpr (NZ * UPW >= 20)
+                gather_tagged_interleave_nf<4>(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H,
+                                               BW, tid, nthreads, a.timeout_flag, a.spin_limit);
+            else
+                gather_tagged_interleave(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H, BW,
+                                         tid, nthreads, a.timeout_flag, a.spin_limit);
         }
         __syncthreads();
         // The gathers are software-pipelined by hand in groups of GS (gates q0..q0+GS-1 of slice i of one unit): the
         // next group's reads are issued before the current group's multiply-adds, so that LDS latency overlaps
-        // arithmetic (left to itself the compiler waits for every read on its own).
-        asm volatile("" : "+v"(eo));   // keeps the selections derived from it out of loop-invariant registers
-#pragma unroll
-        for (int u = 0; u < UPW; ++u)
-#pragma unroll
-            for (int i = 0; i < NZP; ++i) asm volatile("" : "+v"(wc[u][i]));   // offsets stay packed
+        // arithmetic.
         float G = 0.f;
         {
             using VT = typename std::conditional<BW == 2, float2, float4>::type;
@@ -167,25 +166,32 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
                     }
                 }
                 if (i == NZ - 1 && q0 + GS == 4) {
-                    if (cnt[u] > 0) {
-                        // this unit's overflow entries, one per lane, into the partial sum of the gate each belongs to
-                        const float v = ((eo >> 18) & 15u) == (unsigned)u ? evv : 0.f;
-                        const unsigned gq = (eo >> 16) & 3u;
-                        const VT t = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + (eo & 0xFFFFu));
-                        float xv[BW];
-                        xv[0] = t.x; xv[1] = t.y;
-                        if constexpr (BW == 4) { xv[2] = t.z; xv[3] = t.w; }
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const float vq = (gq == (unsigned)q) ? v : 0.f;
-#pragma unroll
-                            for (int b = 0; b < BW; ++b) acc[q][b] = fmaf(vq, xv[b], acc[q][b]);
-                        }
-                    }
 #pragma unroll
                     for (int b = 0; b < BW; ++b) {
                         const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
                         G = (lp == u * BW + b) ? r : G;
+                    }
+                }
+            }
+            if (ovf_units != 0u) {
+                // overflow entries: lane e multiplies entry e; a unit that has entries reduces them per gate and column
+                unsigned e = eo;
+                asm volatile("" : "+v"(e));   // the selections derived from it are made here, not kept in registers
+                const VT t = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + (e & 0xFFFFu));
+                float xe[BW];
+                xe[0] = t.x * evv; xe[1] = t.y * evv;
+                if constexpr (BW == 4) { xe[2] = t.z * evv; xe[3] = t.w * evv; }
+                const unsigned eu = (e >> 18) & 15u, eg = (e >> 16) & 3u;
+#pragma unroll 1
+                for (int u = 0; u < UPW; ++u) {
+                    if ((ovf_units >> u) & 1u) {
+#pragma unroll
+                        for (int b = 0; b < BW; ++b) {
+                            const float tb = eu == (unsigned)u ? xe[b] : 0.f;
+                            const float r = wave_sum4_rows(eg == 0u ? tb : 0.f, eg == 1u ? tb : 0.f, eg == 2u ? tb : 0.f,
+                                                           eg == 3u ? tb : 0.f);
+                            G += (lp == u * BW + b) ? r : 0.f;
+                        }
                     }
                 }
             }
