@@ -65,9 +65,16 @@ __device__ __forceinline__ void gather_tagged2(const PollSrc& A, const PollSrc& 
     }
 }
 
-// One array; a thread with more than four slots to fetch keeps eight loads in flight (one polling round less).
 __device__ __forceinline__ void gather_tagged(const u64* slots, int H, unsigned want, float* dst, int tid,
                                               int nthreads, int* timeout_flag, unsigned spin_limit)
+{
+    const PollSrc A{slots, dst, want, H}, none{nullptr, nullptr, 0u, 0};
+    gather_tagged2<4>(A, none, tid, nthreads, timeout_flag, spin_limit);
+}
+// For kernels with sixteen registers to spare: a thread with more than four slots to fetch keeps eight loads in
+// flight (one polling round less).
+__device__ __forceinline__ void gather_tagged_wide(const u64* slots, int H, unsigned want, float* dst, int tid,
+                                                   int nthreads, int* timeout_flag, unsigned spin_limit)
 {
     const PollSrc A{slots, dst, want, H}, none{nullptr, nullptr, 0u, 0};
     if (H > 4 * nthreads) gather_tagged2<8>(A, none, tid, nthreads, timeout_flag, spin_limit);

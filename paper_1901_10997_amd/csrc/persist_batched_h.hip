@@ -246,7 +246,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
                 hbuf[e] = (D.h0 && b < bw) ? D.h0[(size_t)(b0 + b) * H + k] : 0.f;
             }
         } else {
-            gather_tagged(xh, BW * H, tag - 1u, hbuf, tid, nthreads, a.timeout_flag, a.spin_limit);
+            gather_tagged_wide(xh, BW * H, tag - 1u, hbuf, tid, nthreads, a.timeout_flag, a.spin_limit);
         }
         __syncthreads();
         {

@@ -153,7 +153,9 @@ __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
                                    __HIP_MEMORY_SCOPE_AGENT);
         }
         // ---- stage 2: gate outputs from u_t, cell update
-        gather_tagged(a.xchg_u, 4 * G, tag, ubuf, tid, nthreads, a.timeout_flag, a.spin_limit);
+        // (the variants with an odd slice count have the registers for eight polling loads in flight)
+        if constexpr (NZ & 1) gather_tagged_wide(a.xchg_u, 4 * G, tag, ubuf, tid, nthreads, a.timeout_flag, a.spin_limit);
+        else gather_tagged(a.xchg_u, 4 * G, tag, ubuf, tid, nthreads, a.timeout_flag, a.spin_limit);
         __syncthreads();
         float h = 0.f;
         {
