@@ -16,11 +16,11 @@
 //             with device-scope write-through stores; once the wave's stores have been acknowledged
 //             (outstanding-memory counter at zero) and the workgroup has met at a barrier, one thread publishes
 //             the step number in the tile's flag, again with a device-scope store.
-//   consumer  one wave polls the flags of the tiles that produce its batch rows (device-scope loads, bounded),
-//             then executes a device-scope acquire fence, which drops stale lines of the exchange buffer from
-//             this compute unit's vector cache and this XCD's L2; after a workgroup barrier every wave reads
-//             its operand fragments with ordinary cached loads, so the 32 compute units of an XCD share one
-//             fetch of each line.
+//   consumer  one wave polls the flags of the tiles that produce its batch rows (device-scope loads, bounded);
+//             after a workgroup barrier every wave reads its operand fragments with device-scope 8-byte loads,
+//             which do not hit stale lines of this compute unit's vector cache or this XCD's L2.  (An acquire
+//             fence followed by ordinary cached loads, which lets the 32 compute units of an XCD share one fetch
+//             of each line, measured 0.9 us per step slower: the invalidate makes all of them miss first.)
 // Two exchange buffers alternate: h_{t+1} can only be written after every tile has published h_t, which each
 // did after it had finished reading h_{t-1} from the buffer h_{t+1} goes to.
 // Flags carry monotonically growing tags, so they are never cleared between steps or launches of one forward.
@@ -109,7 +109,6 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
                             __hip_atomic_load(a.timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
                             break;
                     }
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                 }
                 __syncthreads();
             }
@@ -119,7 +118,14 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int q = 0; q < KS; ++q)
-                    fa[i][q] = *reinterpret_cast<const uint4*>(hx + aoff[i] + (size_t)q * Bp * 16);
+                {
+                    // device-scope loads: they do not hit stale lines of this compute unit's vector cache or this XCD's
+                    // L2, so no acquire fence (which would make every cached line of the workgroup miss) is needed
+                    const unsigned long long* p8 = reinterpret_cast<const unsigned long long*>(hx + aoff[i] + (size_t)q * Bp * 16);
+                    const unsigned long long lo = __hip_atomic_load(p8, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const unsigned long long hi = __hip_atomic_load(p8 + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    fa[i][q] = make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
+                }
 #pragma unroll
             for (int q = 0; q < KS; ++q)
 #pragma unroll
