@@ -513,8 +513,10 @@ __global__ __launch_bounds__(512) void proj_mfma_bf16_big_kernel(const uint16_t*
 // fp32 operands on the fp32 matrix instruction (32x32x2).  Requires K % 4 == 0 (16-byte chunks along k).
 // Each lane reads four consecutive k of its fragment row at once and feeds them to four MFMAs; which k a lane
 // contributes to which MFMA is the same for both operands, which is all a sum over k needs.
+// BK: k extent of a slab (16 or 32).  The 128 x 128 tile runs with 32 (half the barriers, twice the prefetch distance:
+// 5-7 % faster on the 4800-row speech projections), the 64 x 64 tile with 16.
 // ---------------------------------------------------------------------------------------------------------
-template <int TM, int TN>
+template <int TM, int TN, int BK>
 __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restrict__ X, int ldx,
                                                             const float* __restrict__ W0, const float* __restrict__ bias0,
                                                             float* __restrict__ P0, const float* __restrict__ W1,
@@ -526,10 +528,11 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
     const float* __restrict__ W = blockIdx.y ? W1 : W0;
     const float* __restrict__ bias = blockIdx.y ? bias1 : bias0;
     float* __restrict__ P = blockIdx.y ? P1 : P0;
-    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32, BK = 16;
+    constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
+    constexpr int CPR = BK / 4;                      // 16-byte chunks per slab row
     constexpr int LDR = BK + 4;                      // padded row length in floats (80 bytes)
-    constexpr int ACH = (BM * (BK / 4) + 255) / 256;
-    constexpr int BCH = (BN * (BK / 4) + 255) / 256;
+    constexpr int ACH = (BM * CPR + 255) / 256;
+    constexpr int BCH = (BN * CPR + 255) / 256;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* As = reinterpret_cast<float*>(smem);                    // [2][BM][LDR]
     float* Bs = As + 2 * BM * LDR;                                 // [2][BN][LDR]
@@ -553,7 +556,7 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
     auto load_slab = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < ACH; ++i) {
-            const int c = tid + 256 * i, row = c >> 2, kc = c & 3;
+            const int c = tid + 256 * i, row = c / CPR, kc = c % CPR;
             const int m = m0 + row, k = k0 + 4 * kc;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (row < BM && m < M && k < K) v = *reinterpret_cast<const float4*>(X + (size_t)m * ldx + k);
@@ -561,7 +564,7 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
         }
 #pragma unroll
         for (int i = 0; i < BCH; ++i) {
-            const int c = tid + 256 * i, row = c >> 2, kc = c & 3;
+            const int c = tid + 256 * i, row = c / CPR, kc = c % CPR;
             const int n = n0 + row, k = k0 + 4 * kc;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (row < BN && n < N && k < K) v = *reinterpret_cast<const float4*>(W + (size_t)n * K + k);
@@ -571,12 +574,12 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
     auto store_slab = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < ACH; ++i) {
-            const int c = tid + 256 * i, row = c >> 2, kc = c & 3;
+            const int c = tid + 256 * i, row = c / CPR, kc = c % CPR;
             if (row < BM) *reinterpret_cast<float4*>(As + ((size_t)buf * BM + row) * LDR + 4 * kc) = ra[i];
         }
 #pragma unroll
         for (int i = 0; i < BCH; ++i) {
-            const int c = tid + 256 * i, row = c >> 2, kc = c & 3;
+            const int c = tid + 256 * i, row = c / CPR, kc = c % CPR;
             if (row < BN) *reinterpret_cast<float4*>(Bs + ((size_t)buf * BN + row) * LDR + 4 * kc) = rb[i];
         }
     };
@@ -776,15 +779,23 @@ static hipError_t launch_bf16_big(const uint16_t* X, int ldx, const uint16_t* W,
     return hipGetLastError();
 }
 
-template <int TM, int TN>
+template <int TM, int TN, int BK = 16>
 static hipError_t launch_f32(const float* X, int ldx, const float* W, const float* bias, float* P, const float* W1,
                              const float* bias1, float* P1, int M, int N, int K, hipStream_t s)
 {
     constexpr int BM = 2 * TM * 32, BN = 2 * TN * 32;
     const int gm = (M + BM - 1) / BM, gn = (N + BN - 1) / BN;
     const int grid = ((gm * gn + kXcds - 1) / kXcds) * kXcds;
-    const size_t lds = 2 * (size_t)(BM + BN) * (16 + 4) * sizeof(float);
-    hipLaunchKernelGGL((proj_mfma_f32_kernel<TM, TN>), dim3(grid, W1 ? 2 : 1), dim3(256), lds, s, X, ldx, W, bias, P, W1,
+    const size_t lds = 2 * (size_t)(BM + BN) * (BK + 4) * sizeof(float);
+    if (lds > 64 * 1024) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void*)proj_mfma_f32_kernel<TM, TN, BK>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+    }
+    hipLaunchKernelGGL((proj_mfma_f32_kernel<TM, TN, BK>), dim3(grid, W1 ? 2 : 1), dim3(256), lds, s, X, ldx, W, bias, P, W1,
                        bias1, P1, M, N, K, gm, gn);
     return hipGetLastError();
 }
@@ -810,7 +821,7 @@ hipError_t launch_proj_mfma_f32_pair(const float* X, int ldx, const float* W0, c
     if (M <= 0 || N <= 0) return hipSuccess;
     if (!proj_mfma_supported(false, K, ldx)) return hipErrorInvalidValue;
     if (f32_small_tiles(M, N, W1 ? 2 : 1)) return launch_f32<1, 1>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
-    return launch_f32<2, 2>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
+    return launch_f32<2, 2, 32>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
 }
 
 bool proj_mfma_supported(bool w_bf16, int K, int ldx)
@@ -851,7 +862,7 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
         return hipGetLastError();
     }
     if (f32_small_tiles(M, N, 1)) return launch_f32<1, 1>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
-    return launch_f32<2, 2>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
+    return launch_f32<2, 2, 32>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
 }
 
 }  // namespace l355
