@@ -4,15 +4,15 @@
 //   R[b][n] = sum_k hb[b][k] * W_h[n][k]      (hb = h_{t-1} rounded to bf16, W_h packed rows n = 4*unit + gate)
 //   a = P[t][b][n] + R[b][n];  f,i,o = sigmoid, g = tanh;  c <- f*c + i*g;  h = o*tanh(c)
 //
-// A 512-thread workgroup owns a 64 (batch) x 64 (packed rows = 16 hidden units) tile for the whole sequence, one
-// workgroup per compute unit.  Its eight waves split K; each wave's slice of W_h (64 rows x H/8) stays in
-// registers as MFMA operand fragments for all T steps, and each thread keeps the cell state of its two
-// (batch row, unit) pairs in registers.  What a launch per step re-reads from memory every step (W_h: the L2
-// does not keep it across launches) is read once.
+// A 512-thread workgroup owns a 32 (batch) x 128 (packed rows = 32 hidden units) tile for the whole sequence, one
+// workgroup per compute unit.  Its eight waves split K; each wave's slice of W_h (128 rows x H/8) stays in
+// registers as MFMA operand fragments for all T steps (128 registers at H = 1024), and each thread keeps the cell
+// state of its two (batch row, unit) pairs in registers.  What a launch per step re-reads from memory every step
+// (W_h: the L2 does not keep it across launches) is read once.
 //
 // Hidden-state exchange.  h_t (B x H bf16, 512 KB at B = 256, H = 1024) is too large for the tagged 8-byte slots
 // the small-batch kernels use, so data and readiness travel separately:
-//   producer  the tile's 64 x 16 block of h_t is stored as one contiguous 2 KB piece of a [H/16][Bp][16] buffer
+//   producer  the tile's 32 x 32 block of h_t is stored as two contiguous 1 KB pieces of a [H/16][Bp][16] buffer
 //             with device-scope write-through stores; once the wave's stores have been acknowledged
 //             (outstanding-memory counter at zero) and the workgroup has met at a barrier, one thread publishes
 //             the step number in the tile's flag, again with a device-scope store.
@@ -33,28 +33,31 @@ namespace l355 {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-template <int KS>  // k16 steps of a wave's K slice: H = 128 * KS
+// KS: k16 steps of a wave's K slice (H = 128 * KS); MT x NT: the tile in 32 x 32 blocks (batch rows x packed rows)
+template <int KS, int MT, int NT>
 __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) float part[];  // [8][64][68]
-    constexpr int LDP = 68;
-    constexpr int NW = 8, NT = 512, PAIRS = 2;
-    const int gm = (a.B + 63) / 64, gn = (4 * a.H) / 64;
+    extern __shared__ __attribute__((aligned(16))) float part[];  // [8][RM][LDP]
+    constexpr int RM = 32 * MT, RN = 32 * NT, UT = RN / 4;       // tile rows (batch), packed rows, hidden units
+    constexpr int LDP = RN + 4;
+    constexpr int NW = 8, NTH = 512, PAIRS = RM * UT / NTH;
+    static_assert(RM * UT % NTH == 0 && PAIRS >= 1, "pairs must divide evenly over the threads");
+    const int gm = (a.B + RM - 1) / RM, gn = (4 * a.H) / RN;
     const int nblk = gm * gn;
     const int per_xcd = (nblk + 7) / 8;
     const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
     if (logical >= nblk) return;                               // padding ids take no part in the exchange
     const int tile_n = logical / gm, tile_m = logical % gm;    // tiles that share a W_h panel stay on one XCD
-    const int m0 = tile_m * 64, n0 = tile_n * 64;
+    const int m0 = tile_m * RM, n0 = tile_n * RN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, fk = lane >> 5;
-    const int H = a.H, Bp = gm * 64;
+    const int H = a.H, Bp = gm * RM;
     const int kbase = wave * (H / NW);
 
     // W_h fragments of this wave: rows n0 + 32 j + fr, k = kbase + 16 s + 8 fk .. + 8
-    uint4 fb[2][KS];
+    uint4 fb[NT][KS];
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
         for (int s = 0; s < KS; ++s)
             fb[j][s] = *reinterpret_cast<const uint4*>(a.Wh + (size_t)(n0 + j * 32 + fr) * H + kbase + 16 * s + 8 * fk);
@@ -64,17 +67,17 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
     float c[PAIRS];
 #pragma unroll
     for (int r = 0; r < PAIRS; ++r) {
-        const int p = tid + NT * r;
-        pb[r] = m0 + (p >> 4);
-        pu[r] = p & 15;
+        const int p = tid + NTH * r;
+        pb[r] = m0 + p / UT;
+        pu[r] = p % UT;
         const int bc = pb[r] < a.B ? pb[r] : a.B - 1;
         c[r] = a.c0 ? a.c0[(size_t)bc * H + (n0 >> 2) + pu[r]] : 0.0f;
     }
     // operand offsets (in bf16 elements) inside an exchange buffer: unit block kbase/16 + s, row m0 + 32 i + fr
     const size_t xbuf = (size_t)H * Bp;                        // elements per exchange buffer
-    unsigned aoff[2];
+    unsigned aoff[MT];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) aoff[i] = (unsigned)(((kbase >> 4) * Bp + m0 + i * 32 + fr) * 16 + 8 * fk);
+    for (int i = 0; i < MT; ++i) aoff[i] = (unsigned)(((kbase >> 4) * Bp + m0 + i * 32 + fr) * 16 + 8 * fk);
     unsigned* const myflag = a.flags + (size_t)tile_m * gn + tile_n;
     const unsigned* const pollflag = a.flags + (size_t)tile_m * gn + (lane < gn ? lane : gn - 1);
 
@@ -87,11 +90,11 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
             const int bc = pb[r] < a.B ? pb[r] : a.B - 1;
             pre[r] = *reinterpret_cast<const float4*>(a.P + ((size_t)t * a.B + bc) * (4 * (size_t)H) + n0 + 4 * pu[r]);
         }
-        f32x16 acc[2][2];
+        f32x16 acc[MT][NT];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NT; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
@@ -113,9 +116,9 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
                 __syncthreads();
             }
             const uint16_t* hx = a.hx + (size_t)(s & 1) * xbuf;
-            uint4 fa[2][KS];
+            uint4 fa[MT][KS];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MT; ++i)
 #pragma unroll
                 for (int q = 0; q < KS; ++q)
                 {
@@ -129,19 +132,19 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
 #pragma unroll
             for (int q = 0; q < KS; ++q)
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int i = 0; i < MT; ++i)
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                    for (int j = 0; j < NT; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][q]),
                                                                            __builtin_bit_cast(bf16x8, fb[j][q]),
                                                                            acc[i][j], 0, 0, 0);
         }
         // partial tiles -> LDS.  Accumulator register v of lane l is element (8*(v/4) + 4*(l/32) + v%4, l%32).
-        float* mine = part + (size_t)wave * 64 * LDP;
+        float* mine = part + (size_t)wave * RM * LDP;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MT; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NT; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int m = i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
             float4 sum = pre[r];
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
-                const float4 q = *reinterpret_cast<const float4*>(part + ((size_t)w * 64 + m) * LDP + 4 * u);
+                const float4 q = *reinterpret_cast<const float4*>(part + ((size_t)w * RM + m) * LDP + 4 * u);
                 sum.x += q.x;
                 sum.y += q.y;
                 sum.z += q.z;
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
             const unsigned hbits = f32_to_bf16_bits(hn);
             const unsigned other = (unsigned)__builtin_amdgcn_update_dpp(0, (int)hbits, 0xB1, 0xF, 0xF, true);
             if ((u & 1) == 0 && !last)
-                __hip_atomic_store(reinterpret_cast<unsigned*>(hxo + ((size_t)tile_n * Bp + pb[r]) * 16 + u),
+                __hip_atomic_store(reinterpret_cast<unsigned*>(hxo + ((size_t)(((n0 >> 2) + u) >> 4) * Bp + pb[r]) * 16 + (u & 15)),
                                    hbits | (other << 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (pb[r] < a.B) {
                 const int j = (n0 >> 2) + u;
@@ -204,59 +207,77 @@ __global__ void h0_to_exchange_kernel(const float* __restrict__ h0, uint16_t* __
     }
 }
 
+// The tile is 32 batch rows x 128 packed rows (32 hidden units): a compute unit pulls 64 KB of h per step.  (The first
+// version used 64 x 64 tiles, 128 KB per step; the step is bound by that read, and the 32-row shape never needs more
+// tiles than the 64-row one.)
+constexpr int kMT = 1, kNT = 4;
+
 bool persist_mfma_supported(int B, int H)
 {
     if (B < 32 || H % 128 != 0 || H > 1024) return false;
-    const int tiles = ((B + 63) / 64) * (4 * H / 64);
-    return ((tiles + 7) / 8) * 8 <= device_num_cus();
+    const int gn = 4 * H / (32 * kNT);
+    const int tiles = ((B + 32 * kMT - 1) / (32 * kMT)) * gn;
+    return ((tiles + 7) / 8) * 8 <= device_num_cus() && gn <= 64;
 }
 
 size_t persist_mfma_exchange_bytes(int B, int H)
 {
-    const size_t Bp = (size_t)((B + 63) / 64) * 64;
+    const size_t Bp = (size_t)((B + 32 * kMT - 1) / (32 * kMT)) * (32 * kMT);
     return 2 * (size_t)H * Bp * sizeof(uint16_t);
 }
-size_t persist_mfma_flag_count(int B, int H) { return (size_t)((B + 63) / 64) * (4 * H / 64); }
+size_t persist_mfma_flag_count(int B, int H) { return (size_t)((B + 32 * kMT - 1) / (32 * kMT)) * (4 * H / (32 * kNT)); }
 
-hipError_t launch_persist_mfma_bf16(const PersistMfmaArgs& a, const float* h0, bool cooperative, hipStream_t s)
+template <int KS, int MT, int NT>
+static hipError_t launch_shape(const PersistMfmaArgs& a, const float* h0, bool cooperative, hipStream_t s)
 {
-    if (a.B <= 0 || a.H <= 0 || a.T <= 0) return hipSuccess;
-    if (!persist_mfma_supported(a.B, a.H)) return hipErrorInvalidValue;
-    const int gm = (a.B + 63) / 64, gn = (4 * a.H) / 64;
+    constexpr int RM = 32 * MT, RN = 32 * NT;
+    const int gm = (a.B + RM - 1) / RM, gn = (4 * a.H) / RN;
     const int grid = ((gm * gn + 7) / 8) * 8;
-    const size_t lds = 8 * 64 * 68 * sizeof(float);
+    const size_t lds = (size_t)8 * RM * (RN + 4) * sizeof(float);
     PersistMfmaArgs args = a;
     args.has_h0 = h0 != nullptr;
     if (h0) {
         const size_t n = (size_t)a.B * a.H;
         int g = (int)((n + 255) / 256);
         if (g > 2048) g = 2048;
-        hipLaunchKernelGGL(h0_to_exchange_kernel, dim3(g), dim3(256), 0, s, h0, a.hx, a.B, a.H, gm * 64);
+        hipLaunchKernelGGL(h0_to_exchange_kernel, dim3(g), dim3(256), 0, s, h0, a.hx, a.B, a.H, gm * RM);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    const void* kern = nullptr;
-    switch (a.H / 128) {
-        case 1: kern = (const void*)persist_mfma_bf16_kernel<1>; break;
-        case 2: kern = (const void*)persist_mfma_bf16_kernel<2>; break;
-        case 3: kern = (const void*)persist_mfma_bf16_kernel<3>; break;
-        case 4: kern = (const void*)persist_mfma_bf16_kernel<4>; break;
-        case 5: kern = (const void*)persist_mfma_bf16_kernel<5>; break;
-        case 6: kern = (const void*)persist_mfma_bf16_kernel<6>; break;
-        case 7: kern = (const void*)persist_mfma_bf16_kernel<7>; break;
-        case 8: kern = (const void*)persist_mfma_bf16_kernel<8>; break;
-        default: return hipErrorInvalidValue;
-    }
-    static bool attr_set[9] = {};
-    if (!attr_set[a.H / 128]) {
+    const void* kern = (const void*)persist_mfma_bf16_kernel<KS, MT, NT>;
+    static bool attr_set = false;
+    if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_set[a.H / 128] = true;
+        attr_set = true;
     }
     void* kargs[] = {(void*)&args};
-    // every workgroup must be resident at the same time: at most one per compute unit (139 KB of LDS each)
+    // every workgroup must be resident at the same time: at most one per compute unit (135-139 KB of LDS each)
     if (cooperative) return hipLaunchCooperativeKernel(kern, dim3(grid), dim3(512), kargs, (unsigned)lds, s);
     return hipLaunchKernel(kern, dim3(grid), dim3(512), kargs, lds, s);
+}
+
+template <int KS>
+static hipError_t launch_ks(const PersistMfmaArgs& a, const float* h0, bool cooperative, hipStream_t s)
+{
+    return launch_shape<KS, kMT, kNT>(a, h0, cooperative, s);
+}
+
+hipError_t launch_persist_mfma_bf16(const PersistMfmaArgs& a, const float* h0, bool cooperative, hipStream_t s)
+{
+    if (a.B <= 0 || a.H <= 0 || a.T <= 0) return hipSuccess;
+    if (!persist_mfma_supported(a.B, a.H)) return hipErrorInvalidValue;
+    switch (a.H / 128) {
+        case 1: return launch_ks<1>(a, h0, cooperative, s);
+        case 2: return launch_ks<2>(a, h0, cooperative, s);
+        case 3: return launch_ks<3>(a, h0, cooperative, s);
+        case 4: return launch_ks<4>(a, h0, cooperative, s);
+        case 5: return launch_ks<5>(a, h0, cooperative, s);
+        case 6: return launch_ks<6>(a, h0, cooperative, s);
+        case 7: return launch_ks<7>(a, h0, cooperative, s);
+        case 8: return launch_ks<8>(a, h0, cooperative, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace l355
