@@ -361,6 +361,7 @@ def test_expired_waits_are_reported_and_nothing_hangs(monkeypatch):
         (_wl(70, 1, True, 48, 400, 30, 12, keep=0.15), CSR, "persist_batched"),
         (_wl(70, 1, False, 64, 512, 30, 128, dtype="bf16", a=0.05), DENSE, "persist-mfma"),
         (inputs.Workload(70, "hl", 1, False, 40, 400, 30, 1, "f32", 0.3, 0.2, "uniform", 400), CSR, "persist_b1-hlstm"),
+        (inputs.Workload(70, "hlb", 1, True, 40, 300, 20, 6, "f32", 0.3, 0.2, "uniform", 260), CSR, "persist_batched-hlstm"),
     ]
     monkeypatch.setenv("LSTM355_SPIN_LIMIT", "1")
     timeouts = 0
