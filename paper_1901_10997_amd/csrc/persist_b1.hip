@@ -274,6 +274,12 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
     const float bias_l = active ? L.bias[4 * j + row] : 0.f;
     float c = (active && L.c0) ? L.c0[j] : 0.f;
     const int total_steps = a.T + NL - 1;
+    // The layer is chosen by the wave index, so the compiler addresses `L` through memory; taken inside the time loop
+    // these fields cost a load and a wait on the critical path of every step.  Copies made once:
+    float* const out_y = (active && L.y) ? L.y + j : nullptr;
+    const size_t out_ld = (size_t)L.y_ld;
+    float* const out_hT = (active && L.hT) ? L.hT + j : nullptr;
+    float* const out_cT = (active && L.cT) ? L.cT + j : nullptr;
 
     // The input vector of the first layer comes from the external sequence and does not depend on the
     // recurrence.  The whole workgroup requests row s+1 with coalesced loads before the wait of step s, parks it
@@ -369,16 +375,17 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
             add_overflow(acc, noh, oeh, ovh, hrec);
             const float pre = wave_sum4_rows(acc[0], acc[1], acc[2], acc[3]) + bias_l;
             h = lstm_cell_rows(pre, lane, c);
-            if (lane == 0 && active) {
-                if (L.y) L.y[(size_t)t * L.y_ld + j] = h;
-                if (ts + 1 == a.T) {
-                    if (L.hT) L.hT[j] = h;
-                    if (L.cT) L.cT[j] = c;
-                }
-            }
         }
         if (lane == 0) pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
         __syncthreads();
+        // outputs after the hand-over to the publishing threads: nothing on the way of h_t
+        if (live && lane == 0) {
+            if (out_y) out_y[(size_t)t * out_ld] = h;
+            if (ts + 1 == a.T) {
+                if (out_hT) *out_hT = h;
+                if (out_cT) *out_cT = c;
+            }
+        }
         if (tid < nwaves) {
             // thread `tid` publishes the value wave `tid` produced
             const int lm = tid / upb, ju = blockIdx.x * upb + (tid % upb);
