@@ -171,16 +171,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
         }
         const float pre = wave_sum4_rows(acc0, acc1, acc2, acc3) + pl;
         const float h = lstm_cell_rows(pre, lane, c);
-        if (lane == 0) {
-            pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
-            if (active) {
-                a.y[(size_t)t * a.y_ld + j] = h;
-                if (s + 1 == a.T) {
-                    if (a.hT) a.hT[j] = h;
-                    if (a.cT) a.cT[j] = c;
-                }
-            }
-        }
+        if (lane == 0) pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
         __syncthreads();
         if (s + 1 < a.T && tid < upb) {
             const int ju = blockIdx.x * upb + tid;
@@ -188,6 +179,14 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
                 __hip_atomic_store(a.xchg + (size_t)((s + 1) & 1) * a.H + ju,
                                    pack_slot(pub[tid], a.tag_base + (unsigned)s + 1u), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // outputs after the publication: nothing on the way of h_t
+        if (lane == 0 && active) {
+            a.y[(size_t)t * a.y_ld + j] = h;
+            if (s + 1 == a.T) {
+                if (a.hT) a.hT[j] = h;
+                if (a.cT) a.cT[j] = c;
+            }
         }
         if (more_x) x_products(s + 1);               // for step s+1, off the critical path
     }
@@ -378,14 +377,6 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
         }
         if (lane == 0) pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
         __syncthreads();
-        // outputs after the hand-over to the publishing threads: nothing on the way of h_t
-        if (live && lane == 0) {
-            if (out_y) out_y[(size_t)t * out_ld] = h;
-            if (ts + 1 == a.T) {
-                if (out_hT) *out_hT = h;
-                if (out_cT) *out_cT = c;
-            }
-        }
         if (tid < nwaves) {
             // thread `tid` publishes the value wave `tid` produced
             const int lm = tid / upb, ju = blockIdx.x * upb + (tid % upb);
@@ -396,6 +387,14 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
                 __hip_atomic_store(a.xchg + ((size_t)lm * 2 + ((tsm + 1) & 1)) * H + ju,
                                    pack_slot(pub[tid], a.tag_base + (unsigned)tsm + 1u), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // outputs after the publication: nothing on the way of h_t
+        if (live && lane == 0) {
+            if (out_y) out_y[(size_t)t * out_ld] = h;
+            if (ts + 1 == a.T) {
+                if (out_hT) *out_hT = h;
+                if (out_cT) *out_cT = c;
+            }
         }
         if (more_x) x_products(s + 1);               // input side of step s+1, off the critical path
     }

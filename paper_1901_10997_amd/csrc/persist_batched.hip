@@ -100,10 +100,24 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
     float c = 0.f;
     if (lane < 16 && pair_ok && D.c0) c = D.c0[(size_t)(b0 + pb) * H + unit_l];
 
+    // The direction is chosen by the block index, so `D` is addressed through memory: taken inside the time loop its
+    // fields cost a load and a wait per step, some of them in front of the publication.  Where registers allow
+    // (kCopy) they are copied once and the outputs are written after the publication.
+    constexpr bool kCopy = NZ * UPW < 24;
+    const float* Pd_c = nullptr;
+    float *y_c = nullptr, *hT_c = nullptr, *cT_c = nullptr;
+    size_t y_ld_c = 0;
+    if constexpr (kCopy) {
+        Pd_c = D.P; y_c = D.y; y_ld_c = (size_t)D.y_ld; hT_c = D.hT; cT_c = D.cT;
+    }
     for (int s = 0; s < a.T; ++s) {
         const int t = D.reverse ? (a.T - 1 - s) : s;
         float pin = 0.f;
-        if (pair_ok) pin = D.P[((size_t)t * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row];
+        if constexpr (kCopy) {
+            if (pair_ok) pin = Pd_c[((size_t)t * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row];
+        } else {
+            if (pair_ok) pin = D.P[((size_t)t * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row];
+        }
         if (s == 0) {
             for (int e = tid; e < BW * H; e += nthreads) {
                 const int b = e / H, k = e - b * H;
@@ -202,11 +216,14 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
         const float rr = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc * G));
         const float gate = cand ? fmaf(-2.0f, rr, 1.0f) : rr;
         const float gi = __shfl(gate, 16 + lp, 64), go = __shfl(gate, 32 + lp, 64), gg = __shfl(gate, 48 + lp, 64);
+        float h_keep = 0.f;
         if (lane < 16) {
             c = fmaf(gate, c, gi * gg);
             const float h = go * tanhf_fast(c);
             if (lp < PAIRS) pub[pb * upb + wave * UPW + pu] = a.round_h_bf16 ? round_bf16(h) : h;
-            if (pair_ok) {
+            if constexpr (kCopy) {
+                h_keep = h;
+            } else if (pair_ok) {
                 D.y[((size_t)t * B + b0 + pb) * D.y_ld + unit_l] = h;
                 if (s + 1 == a.T) {
                     const size_t ci = (size_t)(b0 + pb) * H + unit_l;
@@ -224,6 +241,17 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
                     __hip_atomic_store(xchg + ((size_t)((s + 1) & 1) * B + b0 + b) * H + unit,
                                        pack_slot(pub[e], a.tag_base + (unsigned)s + 1u), __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        if constexpr (kCopy) {
+            // outputs after the publication: nothing on the way of h_t
+            if (lane < 16 && pair_ok) {
+                y_c[((size_t)t * B + b0 + pb) * y_ld_c + unit_l] = h_keep;
+                if (s + 1 == a.T) {
+                    const size_t ci = (size_t)(b0 + pb) * H + unit_l;
+                    if (hT_c) hT_c[ci] = h_keep;
+                    if (cT_c) cT_c[ci] = c;
+                }
             }
         }
     }

@@ -224,6 +224,15 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
         return Gv;
     };
 
+    // The direction is chosen by the block index, so `D` is addressed through memory: taken inside the time loop its
+    // fields cost a load and a wait per step.  Where registers allow (kCopy) they are copied once.
+    constexpr bool kCopy = NZ * UPW < 12;
+    const float* P1_c = nullptr;
+    float *y_c = nullptr, *hT_c = nullptr, *cT_c = nullptr;
+    size_t y_ld_c = 0;
+    if constexpr (kCopy) {
+        P1_c = D.P1; y_c = D.y; y_ld_c = (size_t)D.y_ld; hT_c = D.hT; cT_c = D.cT;
+    }
     for (int s = 0; s < a.T; ++s) {
         const int t = D.reverse ? (a.T - 1 - s) : s;
         const unsigned tag = a.tag_base + (unsigned)s + 1u;
@@ -238,7 +247,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
             }
         asm volatile("" : "+v"(e1), "+v"(e2));   // likewise the per-gate selections of the overflow entry
         float pin = 0.f;
-        if (ok1) pin = D.P1[((size_t)t * B + b0 + pb) * (4 * (size_t)G) + 4 * unit_l + row];
+        if (ok1) pin = (kCopy ? P1_c : D.P1)[((size_t)t * B + b0 + pb) * (4 * (size_t)G) + 4 * unit_l + row];
         // ---- stage 1: hidden layers from h_{t-1}
         if (s == 0) {
             for (int e = tid; e < BW * H; e += nthreads) {
@@ -309,11 +318,13 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
                     __hip_atomic_store(xh + (size_t)unit_l * BW + pb, pack_slot(pb < bw ? h : 0.f, tag), __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
                 if (ok2) {
-                    D.y[((size_t)t * B + b0 + pb) * D.y_ld + unit_l] = h;
+                    (kCopy ? y_c : D.y)[((size_t)t * B + b0 + pb) * (kCopy ? y_ld_c : (size_t)D.y_ld) + unit_l] = h;
                     if (s + 1 == a.T) {
                         const size_t ci = (size_t)(b0 + pb) * H + unit_l;
-                        if (D.hT) D.hT[ci] = h;
-                        if (D.cT) D.cT[ci] = c;
+                        float* const hT_out = kCopy ? hT_c : D.hT;
+                        float* const cT_out = kCopy ? cT_c : D.cT;
+                        if (hT_out) hT_out[ci] = h;
+                        if (cT_out) cT_out[ci] = c;
                     }
                 }
             }

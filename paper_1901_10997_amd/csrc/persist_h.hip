@@ -166,13 +166,6 @@ __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
                 for (int q = 0; q < 4; ++q) acc[q] = fmaf(v2[q][i], ubuf[q * G + HCOL(c2, q, i)], acc[q]);
             const float pre = wave_sum4_rows(acc[0], acc[1], acc[2], acc[3]) + bias2;
             h = lstm_cell_rows(pre, lane, c);
-            if (lane == 0 && act2) {
-                a.y[(size_t)t * a.y_ld + unit] = h;
-                if (s + 1 == a.T) {
-                    if (a.hT) a.hT[unit] = h;
-                    if (a.cT) a.cT[unit] = c;
-                }
-            }
         }
         // pub is free again: every thread passed the barrier after the stage-1 publication read it
         if (lane == 0) pub[wave] = h;
@@ -181,6 +174,14 @@ __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
             const int j = blockIdx.x * nwaves + tid;
             if (j < H)
                 __hip_atomic_store(a.xchg_h + j, pack_slot(pub[tid], tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // outputs after the publication: nothing on the way of h_t
+        if (lane == 0 && act2) {
+            a.y[(size_t)t * a.y_ld + unit] = h;
+            if (s + 1 == a.T) {
+                if (a.hT) a.hT[unit] = h;
+                if (a.cT) a.cT[unit] = c;
+            }
         }
         if (more_x) x_products(s + 1);               // input side of step s+1, off the critical path
     }
