@@ -94,10 +94,10 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
     float c = (active && a.c0) ? a.c0[j] : 0.f;
     __syncthreads();
 
-    // Input side: x_t does not depend on the recurrence.  The workgroup requests row s+1 with coalesced loads
-    // before the wait of step s, parks it in LDS right after the wait (when every outstanding memory
-    // operation has completed anyway), and each wave accumulates its products for step s+1 after h_s has
-    // been published -- the time in which the wave would otherwise idle until that h has travelled.
+    // Input side: x_t does not depend on the recurrence.  The workgroup requests row s+2 with coalesced loads at
+    // the top of step s, parks it in LDS at the top of step s+1 (before the wait, so that nothing but h stands
+    // between the arrival of h and the products), and each wave accumulates its products for step s+1 after h_s
+    // has been published -- the time in which the wave would otherwise idle until that h has travelled.
     constexpr int XPT = (HP + MAXT - 1) / MAXT > 4 ? (HP + MAXT - 1) / MAXT : 4;
     float xr[FUSEX ? XPT : 1];
     float xa0 = 0.f, xa1 = 0.f, xa2 = 0.f, xa3 = 0.f;
@@ -142,6 +142,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
         park_x(0);
         __syncthreads();
         x_products(0);
+        if (1 < a.T) request_x(1);
     }
 
     for (int s = 0; s < a.T; ++s) {
@@ -149,7 +150,8 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
         float pl = bias_l;
         const bool more_x = FUSEX && s + 1 < a.T;
         if (FUSEX) {
-            if (more_x) request_x(s + 1);            // in flight during the wait below
+            if (more_x) park_x(s + 1);               // requested a whole step ago: nothing to wait for
+            if (s + 2 < a.T) request_x(s + 2);       // in flight during this step
         } else if (active) {
             pl = a.P[(size_t)t * 4 * a.H + 4 * j + row];
         }
@@ -158,7 +160,6 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
         else
             gather_tagged(a.xchg + (size_t)(s & 1) * a.H, a.H, a.tag_base + (unsigned)s, hbuf, tid, nthreads,
                           a.timeout_flag, a.spin_limit);
-        if (more_x) park_x(s + 1);
         __syncthreads();
         float acc0 = xa0, acc1 = xa1, acc2 = xa2, acc3 = xa3;
 #pragma unroll
@@ -281,10 +282,10 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
     float* const out_cT = (active && L.cT) ? L.cT + j : nullptr;
 
     // The input vector of the first layer comes from the external sequence and does not depend on the
-    // recurrence.  The whole workgroup requests row s+1 with coalesced loads before the wait of step s, parks it
-    // in LDS right after the wait (when every outstanding memory operation has completed anyway), and the
-    // first layer's waves gather their products for step s+1 from it after h_s has been published -- the time
-    // in which they would otherwise idle until that h has travelled.
+    // recurrence.  The whole workgroup requests row s+2 with coalesced loads at the top of step s, parks it in LDS
+    // at the top of step s+1 (before the wait, so that nothing but h stands between the arrival of h and the
+    // products), and the first layer's waves gather their products for step s+1 after h_s has been published --
+    // the time in which they would otherwise idle until that h has travelled.
     constexpr int XPT = 2;  // x elements per thread held in registers
     float xr[XPT];
     auto request_x = [&](int s_) {
@@ -333,13 +334,15 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
     park_x(0);
     __syncthreads();
     x_products(0);
+    if (1 < a.T) request_x(1);
 
     for (int s = 0; s < total_steps; ++s) {
         const int ts = s - l;                        // time index this wave's layer works on
         const bool live = ts >= 0 && ts < a.T;
         const int t = a.reverse ? (a.T - 1 - ts) : ts;  // position in the sequence
         const bool more_x = s + 1 < a.T;
-        if (more_x) request_x(s + 1);                // in flight during the wait below
+        if (more_x) park_x(s + 1);                   // requested a whole step ago: nothing to wait for
+        if (s + 2 < a.T) request_x(s + 2);           // in flight during this step
         // stage, for every layer m, h^m at time index s-m-1 (the operand of layer m's recurrence at time s-m
         // and of layer m+1's input side at time s-m-1)
         PollSrc src[2] = {{nullptr, nullptr, 0u, 0}, {nullptr, nullptr, 0u, 0}};
@@ -353,7 +356,6 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
                 src[m] = PollSrc{a.xchg + ((size_t)m * 2 + ((tm + 1) & 1)) * H, dst, a.tag_base + (unsigned)tm + 1u, H};
         }
         gather_tagged2(src[0], src[1], tid, nthreads, a.timeout_flag, a.spin_limit);
-        if (more_x) park_x(s + 1);
         __syncthreads();
         float h = 0.f;
         if (live) {

@@ -16,8 +16,8 @@
 // one contiguous run of slots per gate.
 // One slot array per vector is enough: u_{t+1} is published only after its producer has received every h_t, and
 // each h_t was published only after its producer had finished reading u_t (and the same with the roles swapped).
-// The input row x_{t+1} is requested before the first wait of step t, parked in LDS after it, and its products are
-// accumulated after h_t has been published, off the critical path.
+// The input row x_{t+2} is requested at the top of step t, parked in LDS at the top of step t+1 (before the wait), and
+// its products are accumulated after h_{t+1} has been published, off the critical path.
 // All waits are bounded: on expiry a device flag is raised, every wave stops waiting and the kernel drains.
 #include "common.h"
 #include "device_math.h"
@@ -119,19 +119,20 @@ __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
     park_x(0);
     __syncthreads();
     x_products(0);
+    if (1 < a.T) request_x(1);
 
     for (int s = 0; s < a.T; ++s) {
         const int t = a.reverse ? (a.T - 1 - s) : s;
         const unsigned tag = a.tag_base + (unsigned)s + 1u;
         const bool more_x = s + 1 < a.T;
-        if (more_x) request_x(s + 1);                // in flight during the wait below
+        if (more_x) park_x(s + 1);                   // requested a whole step ago: nothing to wait for
+        if (s + 2 < a.T) request_x(s + 2);           // in flight during this step
         // ---- stage 1: hidden layers from h_{t-1}
         if (s == 0) {
             for (int e = tid; e < H; e += nthreads) hbuf[e] = a.h0 ? a.h0[e] : 0.f;
         } else {
             gather_tagged(a.xchg_h, H, tag - 1u, hbuf, tid, nthreads, a.timeout_flag, a.spin_limit);
         }
-        if (more_x) park_x(s + 1);
         __syncthreads();
         {
             float acc[4] = {xacc[0], xacc[1], xacc[2], xacc[3]};
