@@ -513,8 +513,8 @@ __global__ __launch_bounds__(512) void proj_mfma_bf16_big_kernel(const uint16_t*
 // fp32 operands on the fp32 matrix instruction (32x32x2).  Requires K % 4 == 0 (16-byte chunks along k).
 // Each lane reads four consecutive k of its fragment row at once and feeds them to four MFMAs; which k a lane
 // contributes to which MFMA is the same for both operands, which is all a sum over k needs.
-// BK: k extent of a slab (16 or 32).  The 128 x 128 tile runs with 32 (half the barriers, twice the prefetch distance:
-// 5-7 % faster on the 4800-row speech projections), the 64 x 64 tile with 16.
+// BK: k extent of a slab.  Both tile sizes run with 32 (half the barriers and twice the prefetch distance of 16:
+// 5-7 % faster on the 4800-row speech projections, 15 % on products of a few hundred rows).
 // ---------------------------------------------------------------------------------------------------------
 template <int TM, int TN, int BK>
 __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restrict__ X, int ldx,
@@ -820,7 +820,7 @@ hipError_t launch_proj_mfma_f32_pair(const float* X, int ldx, const float* W0, c
 {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (!proj_mfma_supported(false, K, ldx)) return hipErrorInvalidValue;
-    if (f32_small_tiles(M, N, W1 ? 2 : 1)) return launch_f32<1, 1>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
+    if (f32_small_tiles(M, N, W1 ? 2 : 1)) return launch_f32<1, 1, 32>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
     return launch_f32<2, 2, 32>(X, ldx, W0, bias0, P0, W1, bias1, P1, M, N, K, s);
 }
 
@@ -861,7 +861,7 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
                                (const float*)W, bias, P, M, N, K);
         return hipGetLastError();
     }
-    if (f32_small_tiles(M, N, 1)) return launch_f32<1, 1>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
+    if (f32_small_tiles(M, N, 1)) return launch_f32<1, 1, 32>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
     return launch_f32<2, 2, 32>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
 }
 
