@@ -623,7 +623,7 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
 // (16 bytes per lane and row), and the eight partial tiles are summed through LDS in a fixed order.  Two
 // register sets of four k-blocks alternate, so the loads of the next 32 k are in flight while the MFMAs of the
 // current ones execute (an MFMA issue blocks the wave, so without this every block of k paid a memory round
-// trip), and two waves share a SIMD.  MT = 1 when M <= 32: half the MFMAs.  Requires K % 16 == 0.
+// trip), and two waves share a SIMD.  MT = 1 when M <= 32: half the MFMAs.  Requires K % 4 == 0 and ldx % 4 == 0.
 // ---------------------------------------------------------------------------------------------------------
 template <int MT>
 __global__ __launch_bounds__(512) void proj_mfma_f32_skinny_kernel(const float* __restrict__ X, int ldx,
@@ -636,8 +636,9 @@ __global__ __launch_bounds__(512) void proj_mfma_f32_skinny_kernel(const float* 
     const int n0 = blockIdx.x * 32;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, fk = lane >> 5;
-    // K is cut into eight contiguous pieces (multiples of 8), one per wave
-    const int kq = ((K / 8 + NW - 1) / NW) * 8;
+    // K is cut into eight contiguous pieces (multiples of 8), one per wave; K itself only needs to be a multiple of 4:
+    // in the last block of 8 the lanes of the upper half (k + 4 .. k + 7) then have nothing to read
+    const int kq = (((K + 7) / 8 + NW - 1) / NW) * 8;
     const int kbeg = wave * kq, kend = (kbeg + kq) < K ? (kbeg + kq) : K;
     f32x16 acc[MT];
 #pragma unroll
@@ -659,7 +660,7 @@ __global__ __launch_bounds__(512) void proj_mfma_f32_skinny_kernel(const float* 
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int k = k0 + 8 * u;
-            const bool ok = k < kend;
+            const bool ok = k + 4 * fk < kend;
 #pragma unroll
             for (int i = 0; i < MT; ++i) fa0[i][u] = ok ? *reinterpret_cast<const float4*>(arow[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
             fb0[u] = ok ? *reinterpret_cast<const float4*>(bw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -669,7 +670,7 @@ __global__ __launch_bounds__(512) void proj_mfma_f32_skinny_kernel(const float* 
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int k = k0 + 8 * u;
-            const bool ok = k < kend;
+            const bool ok = k + 4 * fk < kend;
 #pragma unroll
             for (int i = 0; i < MT; ++i) fa1[i][u] = ok ? *reinterpret_cast<const float4*>(arow[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
             fb1[u] = ok ? *reinterpret_cast<const float4*>(bw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -852,7 +853,7 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
                       : launch_bf16<4, 2, true>(X, ldx, Wb, bias, P, M, N, K, s);
     }
     if (x_bf16) return hipErrorInvalidValue;
-    if (M <= 64 && K % 16 == 0 && ldx % 4 == 0) {
+    if (M <= 64 && K % 4 == 0 && ldx % 4 == 0) {
         if (M <= 32)
             hipLaunchKernelGGL(proj_mfma_f32_skinny_kernel<1>, dim3((N + 31) / 32), dim3(512), 0, s, (const float*)X, ldx,
                                (const float*)W, bias, P, M, N, K);

@@ -300,7 +300,7 @@ def test_c2_random_state():
     check_case(inputs.make_case(inputs.c2(20), 0, random_state=True))
 
 
-@pytest.mark.parametrize("H", [64, 96, 160, 512, 1056, 1504, 2048])
+@pytest.mark.parametrize("H", [64, 96, 160, 512, 1056, 1284, 1300, 1504, 2048])
 def test_c3_points(H):
     desc, _ = check_case(inputs.make_case(inputs.c3(H), 0))
     assert "persist_b1" in desc
