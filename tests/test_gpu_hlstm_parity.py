@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 
 from oracle import hlstm_oracle as horc
+from oracle import lstm_oracle as lorc
 from paper_1901_10997_amd import binding as B
 from paper_1901_10997_amd import inputs
 from parity_util import check_case, compare, run_gpu
@@ -192,6 +193,26 @@ def test_hlstm_persistent_small_batch_long_sequence_and_state_chaining():
     np.testing.assert_array_equal(yb.cpu().numpy(), full[0])
     np.testing.assert_array_equal(hb.cpu().numpy(), full[1])
     np.testing.assert_array_equal(cb.cpu().numpy(), full[2])
+
+
+@pytest.mark.parametrize("gate_hidden", [0, 170])
+def test_one_handle_alternating_batch_sizes(gate_hidden):
+    """One handle and one (reused) workspace serve forwards of different batch sizes in turn: the exchange slots, flags
+    and activation buffers move inside the workspace with the batch size and must not see each other's leftovers."""
+    mk = _hw(88, 2, True, 48, 160, gate_hidden, 9, 6, keep=0.3) if gate_hidden else \
+        inputs.Workload(88, "alt_lstm", 2, True, 48, 160, 9, 6, "f32", 0.3, 0.3, "uniform")
+    big = inputs.make_case(mk, k=1, random_state=True)
+    small = inputs.select_batch(big, [4, 0, 5])
+    oracle = horc.forward_case if gate_hidden else lorc.forward_case
+    model = None
+    try:
+        for case in (big, small, big, small):
+            out, desc, model = run_gpu(case, CSR, PAUTO, model=model, return_model=True)
+            assert "persist_batched" in desc
+            compare(out, oracle(case), "f32", f"alternating B={case.w.B}")
+    finally:
+        if model is not None:
+            model.close()
 
 
 def test_hlstm_full_size_language_model():
