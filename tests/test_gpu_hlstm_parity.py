@@ -215,6 +215,35 @@ def test_one_handle_alternating_batch_sizes(gate_hidden):
             model.close()
 
 
+def _random_small_batch_shapes(seed, n, hlstm):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    shapes = []
+    for _ in range(n):
+        H = int(rng.integers(40, 640))
+        G = int(rng.integers(40, 640)) if hlstm else 0
+        D = int(rng.integers(8, 200))
+        Bn = int(rng.integers(2, 40))
+        # kept entries per row between a few and about 250: one to four 64-entry slices
+        K = max(H, G) if hlstm else H
+        keep = float(min(0.95, max(0.02, rng.uniform(10, 250) / K)))
+        shapes.append((int(rng.integers(1, 3)), bool(rng.integers(0, 2)), D, H, G, int(rng.integers(2, 7)), Bn, round(keep, 3)))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _random_small_batch_shapes(2024, 12, True) + _random_small_batch_shapes(2025, 12, False))
+def test_small_batch_persistent_random_shapes(shape):
+    """Seeded random shapes over the (slices per row, units per wave, batch columns) choices of the small-batch kernels."""
+    L, bidir, D, H, G, T, Bn, keep = shape
+    # weight range tied to the kept fan-in, so that pre-activations stay of order one as in a trained model (the absolute
+    # tolerance is stated for that regime)
+    a = min(0.4, 1.5 / float(np.sqrt(keep * max(H, G))))
+    w = _hw(89, L, bidir, D, H, G, T, Bn, a=a, keep=keep) if G else \
+        inputs.Workload(89, f"rnd_L{L}_D{D}_H{H}_T{T}_B{Bn}", L, bidir, D, H, T, Bn, "f32", a, keep, "uniform")
+    case = inputs.make_case(w, k=H + Bn, random_state=True)
+    desc, _ = check_case(case, CSR, PAUTO)
+    print(f"[random-shape] {shape} -> {desc}", flush=True)
+
+
 def test_hlstm_full_size_language_model():
     """The paper's language-model H-LSTM shape (one layer, 1500 / 1500, embeddings of 400), batch 1, 10 % kept."""
     case = inputs.make_case(inputs.h1(), 0)
