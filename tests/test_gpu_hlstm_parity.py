@@ -244,6 +244,34 @@ def test_small_batch_persistent_random_shapes(shape):
     print(f"[random-shape] {shape} -> {desc}", flush=True)
 
 
+def _random_batch1_shapes(seed, n, kind):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    shapes = []
+    for _ in range(n):
+        H = int(rng.integers(30, 1400))
+        G = int(rng.integers(30, 1400)) if kind == "hlstm" else 0
+        D = int(rng.integers(8, 1400))
+        K = max(H, G, D)
+        keep = None if kind == "dense" else round(float(min(0.95, max(0.02, rng.uniform(10, 400) / K))), 3)
+        shapes.append((int(rng.integers(1, 4)), bool(rng.integers(0, 2)), D, H, G, int(rng.integers(1, 8)), keep))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _random_batch1_shapes(2026, 10, "hlstm") + _random_batch1_shapes(2027, 14, "csr") +
+                         _random_batch1_shapes(2028, 8, "dense"))
+def test_batch1_random_shapes(shape):
+    """Seeded random shapes over the register tiers and slice counts of the batch-1 kernels (dense, row-compressed with
+    and without the two-layer wavefront, H-LSTM)."""
+    L, bidir, D, H, G, T, keep = shape
+    fan = (keep if keep is not None else 1.0) * max(H, G, D)
+    a = min(0.4, 1.5 / float(np.sqrt(fan)))
+    w = _hw(90, L, bidir, D, H, G, T, 1, a=a, keep=keep) if G else \
+        inputs.Workload(90, f"rnd1_L{L}_D{D}_H{H}_T{T}", L, bidir, D, H, T, 1, "f32", a, keep, "uniform")
+    case = inputs.make_case(w, k=H + T, random_state=True)
+    desc, _ = check_case(case, DENSE if keep is None else CSR, PAUTO)
+    print(f"[random-shape] {shape} -> {desc}", flush=True)
+
+
 def test_hlstm_full_size_language_model():
     """The paper's language-model H-LSTM shape (one layer, 1500 / 1500, embeddings of 400), batch 1, 10 % kept."""
     case = inputs.make_case(inputs.h1(), 0)
