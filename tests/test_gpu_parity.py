@@ -139,6 +139,28 @@ def test_bf16_persistent_matrix_core_shapes(shape):
     assert "persist-mfma" in desc
 
 
+def _random_bf16_shapes(seed, n):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for _ in range(n):
+        H = 128 * int(rng.integers(1, 9))
+        out.append((int(rng.integers(1, 3)), bool(rng.integers(0, 2)), 8 * int(rng.integers(2, 40)), H,
+                    int(rng.integers(2, 8)), int(rng.integers(32, 300))))
+    return out
+
+
+@pytest.mark.parametrize("shape", _random_bf16_shapes(2029, 8))
+def test_bf16_persistent_matrix_core_random_shapes(shape):
+    """Seeded random batch sizes (ragged 32-row tiles) and hidden widths over the bf16 persistent recurrence."""
+    L, bidir, D, H, T, Bn = shape
+    if ((Bn + 31) // 32) * (H // 32) > 256:
+        pytest.skip("more tiles than compute units: served by the stepwise kernel, covered elsewhere")
+    case = inputs.make_case(_wl(87, L, bidir, D, H, T, Bn, dtype="bf16", a=min(0.08, 1.5 / float(np.sqrt(H)))), k=H + Bn,
+                            random_state=True)
+    desc, _ = check_case(case, DENSE, PAUTO)
+    assert "persist-mfma" in desc
+
+
 def test_bf16_persistent_matrix_core_long_sequence():
     """Many steps: the flag tags keep growing across steps and across the two layers' launches."""
     case = inputs.make_case(_wl(85, 2, False, 64, 256, 400, 64, dtype="bf16", a=0.06), k=1, random_state=True)
