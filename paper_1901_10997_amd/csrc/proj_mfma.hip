@@ -584,15 +584,12 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
         }
     };
 
-    const int nslab = (K + BK - 1) / BK;
-    load_slab(0);
-    store_slab(0);
-    __syncthreads();
-    for (int kt = 0; kt < nslab; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nslab) load_slab((kt + 1) * BK);
+    // Slab kt+1 is requested one slab ahead and written to the other LDS buffer between the two halves of slab kt's
+    // MFMAs (nobody reads that buffer any more: its last readers passed the barrier that ended slab kt-1), so the
+    // refill and the request for slab kt+2 sit in the shadow of the matrix instructions instead of behind them.
+    auto mma_groups = [&](int buf, int kg0, int kg1) {
 #pragma unroll
-        for (int kg = 0; kg < BK / 8; ++kg) {
+        for (int kg = kg0; kg < kg1; ++kg) {
             float4 fa[TM], fb[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -610,7 +607,21 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i].w, fb[j].w, acc[i][j], 0, 0, 0);
                 }
         }
-        if (kt + 1 < nslab) store_slab(buf ^ 1);
+    };
+    const int nslab = (K + BK - 1) / BK;
+    constexpr int KG = BK / 8;
+    load_slab(0);
+    store_slab(0);
+    if (nslab > 1) load_slab(BK);
+    __syncthreads();
+    for (int kt = 0; kt < nslab; ++kt) {
+        const int buf = kt & 1;
+        mma_groups(buf, 0, KG / 2);
+        if (kt + 1 < nslab) {
+            store_slab(buf ^ 1);                                   // slab kt+1, requested during slab kt-1
+            if (kt + 2 < nslab) load_slab((kt + 2) * BK);
+        }
+        mma_groups(buf, KG / 2, KG);
         __syncthreads();
     }
     store_acc_tiles<TM, TN>(acc, bias, P, M, N, m0 + wm * TM * 32, n0 + wn * TN * 32, fr, fk);
