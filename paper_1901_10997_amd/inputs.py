@@ -184,3 +184,48 @@ def select_batch(case: Case, cols: List[int]) -> Case:
     h0 = None if case.h0 is None else np.ascontiguousarray(case.h0[:, cols, :])
     c0 = None if case.c0 is None else np.ascontiguousarray(case.c0[:, cols, :])
     return Case(w, case.seed, case.weights, x, h0, c0)
+
+
+def structure_masks(case: Case, unit_frac: float, input_frac: float, k: int = 0):
+    """The same case after a row/column pruning outcome has been stamped onto its masks (plain LSTM workloads).
+
+    In every (layer, direction) a random subset of round(unit_frac * H) hidden units survives (all of them of one
+    size, the sets differ), and round(input_frac * D0) of the input features.  A connection stays active iff the
+    case's own mask keeps it (dense workloads: every connection), its row belongs to a surviving unit and its column to
+    a surviving source (input feature, unit of the layer below, or the layer's own unit for the recurrent matrix) -
+    the pattern of the paper's figure on the mask of an input-to-hidden matrix after the row/column phase.
+    Returns (case with the new masks, units[(l, d)] sorted int arrays, inputs sorted int array).
+    """
+    w = case.w
+    assert w.gate_hidden == 0
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 7777 * w.cid + 31 * k + 5))
+    H, D0 = w.hidden, w.input_dim
+    Hc = max(1, int(round(unit_frac * H)))
+    Dc = max(1, int(round(input_frac * D0)))
+    feats = np.sort(rng.permutation(D0)[:Dc]).astype(np.int64)
+    units = {}
+    for l in range(w.layers):
+        for d in range(w.ndir):
+            units[(l, d)] = np.sort(rng.permutation(H)[:Hc]).astype(np.int64)
+    weights = {}
+    for l in range(w.layers):
+        D = w.layer_input_dim(l)
+        src = np.zeros(D, dtype=bool)
+        if l == 0:
+            src[feats] = True
+        else:
+            for d in range(w.ndir):
+                src[d * H + units[(l - 1, d)]] = True
+        for d in range(w.ndir):
+            cur = case.weights[(l, d)]
+            rows = np.zeros(H, dtype=bool)
+            rows[units[(l, d)]] = True
+            rows4 = np.tile(rows, 4)
+            Mx = np.ones((4 * H, D), np.uint8) if cur["Mx"] is None else cur["Mx"].copy()
+            Mh = np.ones((4 * H, H), np.uint8) if cur["Mh"] is None else cur["Mh"].copy()
+            Mx[~rows4, :] = 0
+            Mx[:, ~src] = 0
+            Mh[~rows4, :] = 0
+            Mh[:, ~rows] = 0
+            weights[(l, d)] = dict(Wx=cur["Wx"], Mx=Mx, Wh=cur["Wh"], Mh=Mh, b=cur["b"])
+    return Case(w, case.seed, weights, case.x, case.h0, case.c0), units, feats
