@@ -262,6 +262,33 @@ int lstm_prune_weights(const float* W, uint8_t* mask, size_t count, double p_w, 
 int lstm_prune_rows_cols(float* W, uint8_t* mask, int M, int N, double p_r, double p_c, int* rows_removed,
                          int* cols_removed, void* stream);
 
+/*
+ * Dimension compaction after row/column pruning (paper Section 4, "Row/column growth & pruning": the pruning shrinks
+ * the dimensions of the weight matrices; Section 5.1 step (b): each control-gate matrix goes from 1500/400 to
+ * 1197/317, Section 5.2 step (b): from 800/800 to 626/626).  All array pointers DEVICE, owned by the caller.
+ *
+ *   W [gates*R, N] fp32 row-major, mask uint8 in {0,1} of the same shape (not NULL): `gates` blocks of R rows, row
+ *   q*R + r is unit r of gate q (gates = 4 for a packed LSTM matrix, 1 for a plain matrix).
+ *   A unit is kept iff at least one of its `gates` rows has an active connection (mask byte 1), a column iff at least
+ *   one row has an active connection in it (the paper removes a neuron once all of its connections are pruned).
+ *   row_index [R], col_index [N] int32: the kept units / columns, ascending, in the first *Rc / *Nc entries; the rest
+ *   is set to -1.
+ *   Wc: capacity gates*R*N floats; receives the compacted matrix [gates * *Rc, *Nc] row-major in its first elements
+ *   (same block layout): the weight where the mask byte is 1, +0 where it is 0 - what lies under a zero mask byte is
+ *   never read into the result.  mask_c: same capacity in bytes, receives the compacted mask; may be NULL.
+ *   *Rc, *Nc HOST.  Either may come back 0 (nothing is written to Wc then).
+ *
+ * A dropped unit or column had no active connection, so every product with the kept part is unchanged and a second
+ * call on the result keeps everything.  Whether a unit may also leave a *model* is the caller's to decide from the
+ * matrices that consume it: a hidden unit of an LSTM layer can go without changing any kept output when its column in
+ * the layer's own recurrent matrix and in the next layer's input matrices is dropped too; its bias entries and its
+ * rows of every matrix of the layer then go with it (row_index names them).
+ * The outputs must not overlap the inputs.  Allocates and frees its own scratch and synchronises the stream.
+ * LSTM_ERR_ARG: NULL where required, a non-positive size, or gates*R*N > 2^31.
+ */
+int lstm_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R, int N, int32_t* row_index,
+                           int32_t* col_index, float* Wc, uint8_t* mask_c, int* Rc, int* Nc, void* stream);
+
 /* Measurement helpers (used by the benchmark to quote achievable peaks next to spec-sheet ones).
  * copy: device-to-device copy kernel of `bytes` bytes, `iters` times, returns the average microseconds.
  * barrier: `steps` rounds of the hidden-state exchange with no arithmetic, for `hidden` units and `groups`

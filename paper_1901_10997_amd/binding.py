@@ -27,6 +27,7 @@ EXPORTS = [
     "lstm_workspace_bytes",
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
     "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_prune_weights", "lstm_prune_rows_cols",
+    "lstm_compact_rows_cols",
     "lstm_bench_copy", "lstm_bench_matmul", "lstm_bench_exchange",
 ]
 
@@ -95,6 +96,8 @@ def load(build_if_missing: bool = True):
     lib.lstm_prune_weights.argtypes = [vp, vp, c.c_size_t, c.c_double, c.POINTER(c.c_size_t), c.POINTER(c.c_size_t), vp]
     lib.lstm_prune_rows_cols.restype = ci
     lib.lstm_prune_rows_cols.argtypes = [vp, vp, ci, ci, c.c_double, c.c_double, c.POINTER(ci), c.POINTER(ci), vp]
+    lib.lstm_compact_rows_cols.restype = ci
+    lib.lstm_compact_rows_cols.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, c.POINTER(ci), c.POINTER(ci), vp]
     lib.lstm_bench_matmul.restype = ci
     lib.lstm_bench_matmul.argtypes = [ci, ci, c.c_double, ci, c.c_uint64, ci, c.POINTER(c.c_double), vp, vp]
     lib.lstm_find_lhp.restype = ci
@@ -296,6 +299,15 @@ def lstm_prune_rows_cols(W_ptr: int, mask_ptr: int, M: int, N: int, p_r: float, 
     r, cc = ctypes.c_int(), ctypes.c_int()
     _check(load().lstm_prune_rows_cols(W_ptr, mask_ptr, M, N, float(p_r), float(p_c), ctypes.byref(r), ctypes.byref(cc), stream))
     return r.value, cc.value
+
+
+def lstm_compact_rows_cols(W_ptr: int, mask_ptr: int, gates: int, R: int, N: int, row_index_ptr: int, col_index_ptr: int,
+                           Wc_ptr: int, mask_c_ptr: Optional[int], stream: Optional[int] = None):
+    """Device pointers; returns (units kept, columns kept)."""
+    rc, nc = ctypes.c_int(), ctypes.c_int()
+    _check(load().lstm_compact_rows_cols(W_ptr, mask_ptr, gates, R, N, row_index_ptr, col_index_ptr, Wc_ptr, mask_c_ptr,
+                                         ctypes.byref(rc), ctypes.byref(nc), stream))
+    return rc.value, nc.value
 
 
 def lstm_bench_matmul(n: int, batch: int, keep: float, fmt: int, seed: int = 1, iters: int = 20, want_product: bool = False,

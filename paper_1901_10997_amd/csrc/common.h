@@ -377,6 +377,9 @@ hipError_t launch_prune_weights(const float* W, uint8_t* mask, size_t count, dou
                                 unsigned long long* counters, hipStream_t s);
 hipError_t launch_prune_rows_cols(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols, float* sums,
                                   unsigned* keys, void* state_r, void* state_c, int* removed, hipStream_t s);
+size_t compact_scratch_bytes(int gates, int R, int N);
+hipError_t launch_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R, int N, int* row_index,
+                                    int* col_index, float* Wc, uint8_t* mask_c, void* scratch, int** counts_out, hipStream_t s);
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);

@@ -1566,6 +1566,27 @@ int lstm_prune_rows_cols(float* W, uint8_t* mask, int M, int N, double p_r, doub
     return LSTM_OK;
 }
 
+int lstm_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R, int N, int32_t* row_index, int32_t* col_index,
+                           float* Wc, uint8_t* mask_c, int* Rc, int* Nc, void* stream)
+{
+    if (!W || !mask || !row_index || !col_index || !Wc || !Rc || !Nc || gates < 1 || R < 1 || N < 1 ||
+        (long long)gates * R > (1ll << 31) / N)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_compact_rows_cols: bad arguments");
+    hipStream_t s = (hipStream_t)stream;
+    char* scratch = nullptr;
+    int* counts = nullptr;
+    int host_counts[2] = {0, 0};
+    hipError_t e = hipMalloc((void**)&scratch, compact_scratch_bytes(gates, R, N));
+    if (e == hipSuccess) e = launch_compact_rows_cols(W, mask, gates, R, N, row_index, col_index, Wc, mask_c, scratch, &counts, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipMemcpy(host_counts, counts, sizeof host_counts, hipMemcpyDeviceToHost);
+    if (scratch) (void)hipFree(scratch);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "lstm_compact_rows_cols");
+    *Rc = host_counts[0];
+    *Nc = host_counts[1];
+    return LSTM_OK;
+}
+
 int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, double* avg_us,
                       float* y_host, void* stream)
 {
