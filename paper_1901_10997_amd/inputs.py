@@ -186,20 +186,22 @@ def select_batch(case: Case, cols: List[int]) -> Case:
     return Case(w, case.seed, case.weights, x, h0, c0)
 
 
-def structure_masks(case: Case, unit_frac: float, input_frac: float, k: int = 0):
-    """The same case after a row/column pruning outcome has been stamped onto its masks (plain LSTM workloads).
+def structure_masks(case: Case, unit_frac: float, input_frac: float, k: int = 0, gate_unit_frac: Optional[float] = None):
+    """The same case after a row/column pruning outcome has been stamped onto its masks.
 
     In every (layer, direction) a random subset of round(unit_frac * H) hidden units survives (all of them of one
-    size, the sets differ), and round(input_frac * D0) of the input features.  A connection stays active iff the
-    case's own mask keeps it (dense workloads: every connection), its row belongs to a surviving unit and its column to
-    a surviving source (input feature, unit of the layer below, or the layer's own unit for the recurrent matrix) -
-    the pattern of the paper's figure on the mask of an input-to-hidden matrix after the row/column phase.
-    Returns (case with the new masks, units[(l, d)] sorted int arrays, inputs sorted int array).
+    size, the sets differ), and round(input_frac * D0) of the input features; in an H-LSTM workload also
+    round(gate_unit_frac * G) of the hidden-layer units inside the gates (the same index set for the four gates of a
+    cell; default: unit_frac).  A connection stays active iff the case's own mask keeps it (dense workloads: every
+    connection), its row belongs to a surviving unit and its column to a surviving source (input feature, unit of
+    the layer below, the layer's own unit for a recurrent matrix, hidden-layer unit of the same gate for a gate-output
+    matrix) - the pattern of the paper's figure on the mask of an input-to-hidden matrix after the row/column phase.
+    Returns (case with the new masks, units[(l, d)] sorted int arrays, inputs sorted int array); H-LSTM workloads:
+    (case, units, inputs, gate_units[(l, d)]).
     """
     w = case.w
-    assert w.gate_hidden == 0
     rng = np.random.Generator(np.random.PCG64(SEED_BASE + 7777 * w.cid + 31 * k + 5))
-    H, D0 = w.hidden, w.input_dim
+    H, D0, G = w.hidden, w.input_dim, w.gate_hidden
     Hc = max(1, int(round(unit_frac * H)))
     Dc = max(1, int(round(input_frac * D0)))
     feats = np.sort(rng.permutation(D0)[:Dc]).astype(np.int64)
@@ -207,6 +209,19 @@ def structure_masks(case: Case, unit_frac: float, input_frac: float, k: int = 0)
     for l in range(w.layers):
         for d in range(w.ndir):
             units[(l, d)] = np.sort(rng.permutation(H)[:Hc]).astype(np.int64)
+    gate_units = {}
+    if G > 0:
+        Gc = max(1, int(round((unit_frac if gate_unit_frac is None else gate_unit_frac) * G)))
+        for l in range(w.layers):
+            for d in range(w.ndir):
+                gate_units[(l, d)] = np.sort(rng.permutation(G)[:Gc]).astype(np.int64)
+
+    def stamp(M, shape, rows, cols):
+        out = np.ones(shape, np.uint8) if M is None else M.copy()
+        out[~rows, :] = 0
+        out[:, ~cols] = 0
+        return out
+
     weights = {}
     for l in range(w.layers):
         D = w.layer_input_dim(l)
@@ -221,11 +236,17 @@ def structure_masks(case: Case, unit_frac: float, input_frac: float, k: int = 0)
             rows = np.zeros(H, dtype=bool)
             rows[units[(l, d)]] = True
             rows4 = np.tile(rows, 4)
-            Mx = np.ones((4 * H, D), np.uint8) if cur["Mx"] is None else cur["Mx"].copy()
-            Mh = np.ones((4 * H, H), np.uint8) if cur["Mh"] is None else cur["Mh"].copy()
-            Mx[~rows4, :] = 0
-            Mx[:, ~src] = 0
-            Mh[~rows4, :] = 0
-            Mh[:, ~rows] = 0
-            weights[(l, d)] = dict(Wx=cur["Wx"], Mx=Mx, Wh=cur["Wh"], Mh=Mh, b=cur["b"])
-    return Case(w, case.seed, weights, case.x, case.h0, case.c0), units, feats
+            if G > 0:
+                grow = np.zeros(G, dtype=bool)
+                grow[gate_units[(l, d)]] = True
+                grow4 = np.tile(grow, 4)
+                weights[(l, d)] = dict(W1x=cur["W1x"], M1x=stamp(cur["M1x"], (4 * G, D), grow4, src),
+                                       W1h=cur["W1h"], M1h=stamp(cur["M1h"], (4 * G, H), grow4, rows), b1=cur["b1"],
+                                       W2=cur["W2"], M2=stamp(cur["M2"], (4 * H, G), rows4, grow), b2=cur["b2"])
+            else:
+                weights[(l, d)] = dict(Wx=cur["Wx"], Mx=stamp(cur["Mx"], (4 * H, D), rows4, src),
+                                       Wh=cur["Wh"], Mh=stamp(cur["Mh"], (4 * H, H), rows4, rows), b=cur["b"])
+    out = Case(w, case.seed, weights, case.x, case.h0, case.c0)
+    if G > 0:
+        return out, units, feats, gate_units
+    return out, units, feats

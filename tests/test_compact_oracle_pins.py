@@ -133,3 +133,27 @@ def test_compacted_lstm_computes_the_pruned_models_outputs(bidir, layers):
     # and the kept units do depend on what was kept: the unpruned model gives something else
     other = restrict_outputs(orc.forward_case(case), w, units)
     assert np.max(np.abs(other[0] - ref[0])) > 1e-3
+
+
+@pytest.mark.parametrize("bidir,layers", [(False, 1), (True, 2)])
+def test_compacted_hlstm_computes_the_pruned_models_outputs(bidir, layers):
+    """The same statement for the H-LSTM cell: hidden units, input features and the hidden-layer units inside the gates
+    all leave, and the kept outputs do not change."""
+    from oracle import hlstm_oracle as horc
+    w = inputs.shrink(inputs.h1(), layers=layers, bidirectional=bidir, input_dim=20, hidden=24, gate_hidden=28, T=5, B=2,
+                      keep=0.6, a=0.4)
+    case = inputs.make_case(w, k=4, random_state=True)
+    pruned, units, feats, gunits = inputs.structure_masks(case, 0.75, 0.8, k=3, gate_unit_frac=0.5)
+    small, found_units, found_feats, found_gunits = compact_case(pruned, ocompact.compact_rows_cols)
+    np.testing.assert_array_equal(found_feats, feats)
+    for key in units:
+        np.testing.assert_array_equal(found_units[key], units[key])
+        np.testing.assert_array_equal(found_gunits[key], gunits[key])
+    assert (small.w.hidden, small.w.input_dim, small.w.gate_hidden) == (18, 16, 14)
+    ref = restrict_outputs(horc.forward_case(pruned), w, units)
+    got = horc.forward_case(small)
+    for a, b in zip(got, ref):
+        assert a.shape == b.shape
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-13)
+    other = restrict_outputs(horc.forward_case(case), w, units)
+    assert np.max(np.abs(other[0] - ref[0])) > 1e-3

@@ -120,3 +120,26 @@ def test_pruned_model_runs_at_its_compacted_dimensions(bidir, layers, H, D, T, B
     # the full-size pruned model through the library gives the same (the two routes agree with each other)
     gpu_full, _ = run_gpu(pruned)
     compare(restrict_outputs(gpu_full, w, units), ref, "f32", "pruned full size")
+
+
+@pytest.mark.parametrize("bidir,layers,H,G,D,T,Bsz", [
+    (False, 1, 96, 80, 40, 10, 1),
+    (True, 2, 64, 64, 48, 7, 4),
+    (False, 1, 1500, 1500, 400, 6, 1),       # the paper's language model: 1500/400 -> 1197/317, gates' hidden layers too
+])
+def test_pruned_hlstm_runs_at_its_compacted_dimensions(bidir, layers, H, G, D, T, Bsz):
+    from oracle import hlstm_oracle as horc
+    w = inputs.shrink(inputs.h1(), layers=layers, bidirectional=bidir, input_dim=D, hidden=H, gate_hidden=G, T=T, B=Bsz,
+                      keep=0.5, a=min(0.4, 1.5 / np.sqrt(max(H, G))))
+    case = inputs.make_case(w, k=6, random_state=True)
+    pruned, units, feats, gunits = inputs.structure_masks(case, 0.798, 0.7925, k=4)
+    small, found_units, found_feats, found_gunits = compact_case(pruned, gpu_compact)
+    np.testing.assert_array_equal(found_feats, feats)
+    for key in units:
+        np.testing.assert_array_equal(found_units[key], units[key])
+        np.testing.assert_array_equal(found_gunits[key], gunits[key])
+    if H == 1500:
+        assert (small.w.hidden, small.w.gate_hidden, small.w.input_dim) == (1197, 1197, 317)
+    ref = restrict_outputs(horc.forward_case(pruned), w, units)
+    gpu, desc = run_gpu(small)
+    compare(gpu, ref, "f32", f"compacted {w.name} {desc}")
