@@ -284,6 +284,31 @@ def test_repeated_forwards_on_one_handle_and_long_sequence():
     model.close()
 
 
+@pytest.mark.parametrize("layers,bidir,D,H,T,Bn,keep", [(2, False, 40, 96, 12, 1, 0.3), (1, True, 24, 96, 15, 4, 0.4),
+                                                     (1, False, 64, 128, 9, 64, None)])
+def test_forward_on_a_side_stream(layers, bidir, D, H, T, Bn, keep):
+    """Every kernel and every clearing of exchange state goes to the caller's stream: a forward issued on a stream other
+    than the default one (default priority), with nothing ordering it against the default stream, gives the same bits
+    as on the default stream - twice, so that the second run starts from the slots the first one left."""
+    import torch
+    case = inputs.make_case(_wl(96, layers, bidir, D, H, T, Bn, keep=keep), 1, random_state=True)
+    ref = orc.forward_case(case)
+    base, desc, model = run_gpu(case, return_model=True)
+    compare(base, ref, "f32", f"default stream {desc}")
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(case.x).to(dev)
+    h0, c0 = torch.from_numpy(case.h0).to(dev), torch.from_numpy(case.c0).to(dev)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream(device=dev)
+    for _ in range(2):
+        with torch.cuda.stream(side):
+            y, hT, cT = model.forward(x, h0, c0)
+        side.synchronize()
+        for a, b in zip(base, (y, hT, cT)):
+            assert np.array_equal(a, b.cpu().numpy())
+    model.close()
+
+
 def test_long_sequence_small_batch_persistent():
     """1500 steps through the per-batch-group exchange of the small-batch persistent kernel."""
     case = inputs.make_case(_wl(87, 1, True, 24, 96, 1500, 4, a=0.2, keep=0.4), 0)
