@@ -141,6 +141,13 @@ size_t lstm_workspace_bytes(const lstm_t* m, int T, int B);
  * (batch 1, small-batch row-compressed, and large-batch bf16) occupy every compute unit for the duration of a layer: forwards issued
  * on other streams at the same time wait for them (cooperative launch) or, with ordinary launches, may make the
  * bounded waits expire (LSTM_ERR_TIMEOUT from lstm_check).
+ * Graph capture: a forward may be issued on a stream that is being captured (hipStreamBeginCapture); the library
+ * notices and records a form that can be replayed any number of times, between eager forwards or other graphs of the
+ * same handle: exchange state is cleared by fill kernels inside the graph (no memset nodes), the step tags of the
+ * exchange start from zero in every replay, persistent kernels are recorded as ordinary launches whatever the launch
+ * mode (a graph holds no cooperative launches; the residency condition of lstm_set_launch_mode applies to a replay),
+ * and profiling records nothing.  Run one eager forward of the same (T, B) on the handle before capturing it, so
+ * that one-time kernel attributes are set outside the capture.  A replay uses the pointers of the capture.
  */
 int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0,
                  float* y, float* hT, float* cT, void* workspace, size_t workspace_bytes, void* stream);

@@ -28,6 +28,11 @@ struct lstm355 {
     int plan = LSTM_PLAN_AUTO;
     int waves_per_group = 0;
     int cooperative = 1;
+    // set for the duration of a forward whose stream is being captured into a graph
+    bool capturing = false;
+    bool cap_cleared = false;            // the batch-1 exchange slots have been cleared inside this capture
+    unsigned cap_tag = 0;                // tags <= cap_tag have been used inside this capture
+    int launch_mode() const { return capturing ? 0 : cooperative; }   // a captured launch is an ordinary one
     std::string last_plan;
     bool profiling = false;
     struct Span { hipEvent_t e0, e1; int kind; };
@@ -60,7 +65,7 @@ struct ProfSpan {
     lstm_t* m; hipStream_t s; int idx = -1;
     ProfSpan(lstm_t* m_, hipStream_t s_, int kind) : m(m_), s(s_)
     {
-        if (!m->profiling) return;
+        if (!m->profiling || m->capturing) return;   // event pairs of a captured forward could not be read back
         hipEvent_t ev[2];
         for (auto& e : ev) {
             if (!m->event_pool.empty()) { e = m->event_pool.back(); m->event_pool.pop_back(); }
@@ -579,6 +584,35 @@ int lstm_describe_plan(const lstm_t* m, char* buf, size_t buf_bytes)
     return LSTM_OK;
 }
 
+// Step tags of the batch-1 exchange (slots owned by the handle): `n` fresh tags, the first one being *base + 1.
+// An eager call draws them from a counter that lives in the handle, so the slots never need clearing between calls.
+// A call that is being captured into a graph cannot do that - every replay would repeat the tags of the capture and
+// match what the previous replay left in the slots - so it clears the slots inside the graph (a fill kernel, once per
+// forward), counts from zero, and leaves the handle's counter above everything a replay will ever write, which keeps
+// later eager calls from matching a replay's left-overs.
+static int take_b1_tags(lstm_t* m, unsigned n, size_t slots, hipStream_t s, unsigned* base)
+{
+    if (m->capturing) {
+        if (!m->cap_cleared) {
+            HIP_TRY(m, launch_fill_u64(m->xchg, slots, 0ull, s));
+            m->cap_cleared = true;
+            m->cap_tag = 0;
+        }
+        *base = m->cap_tag;
+        m->cap_tag += n;
+        if (m->tag_base < m->cap_tag) m->tag_base = m->cap_tag;
+        return LSTM_OK;
+    }
+    if (m->tag_base > 0xFFFFFFFFu - n - 2u) {
+        // tag space exhausted: restart from a clean slate
+        HIP_TRY(m, launch_fill_u64(m->xchg, slots, 0ull, s));
+        m->tag_base = 0;
+    }
+    *base = m->tag_base;
+    m->tag_base += n;
+    return LSTM_OK;
+}
+
 // H-LSTM stack (fp32).  Per layer and direction: the hidden layers' input side for all timesteps as one projection
 // (P1 = W1x.x + b1, 4G rows), then per step the hidden layers (stage 1) and the gate outputs with the cell update
 // (stage 2).
@@ -718,7 +752,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 a.tag_base = htag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 htag += (unsigned)T + 1u;
                 ProfSpan span(m, s, 1);
-                HIP_TRY(m, launch_persist_batched_h(a, Dn, nz, m->cooperative, s));
+                HIP_TRY(m, launch_persist_batched_h(a, Dn, nz, m->launch_mode(), s));
                 continue;
             }
         }
@@ -780,11 +814,9 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
             const size_t n = (size_t)l * Dn + d;
             ProfSpan span(m, s, 1);
             if (persist[d]) {
-                if (m->tag_base > 0xFFFFFFFFu - (unsigned)T - 2u) {
-                    // tag space exhausted: restart from a clean slate
-                    HIP_TRY(m, launch_fill_u64(m->xchg, (size_t)H + 4 * (size_t)G, 0ull, s));
-                    m->tag_base = 0;
-                }
+                unsigned tag0 = 0;
+                const int trc = take_b1_tags(m, (unsigned)T + 1u, (size_t)H + 4 * (size_t)G, s, &tag0);
+                if (trc != LSTM_OK) return trc;
                 PersistHArgs a{};
                 a.ell_val_1x = w.wx.ell_val; a.ell_col_1x = w.wx.ell_col; a.slots_1x = w.wx.slots;
                 a.ell_val_1h = w.wh.ell_val; a.ell_col_1h = w.wh.ell_col; a.slots_1h = w.wh.slots;
@@ -798,12 +830,11 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 a.cT = cT ? cT + n * H : nullptr;
                 a.T = T; a.H = H; a.G = G; a.reverse = d;
                 a.xchg_h = m->xchg; a.xchg_u = m->xchg + H;
-                a.tag_base = m->tag_base;
+                a.tag_base = tag0;
                 a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
-                m->tag_base += (unsigned)T + 1u;
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=fused,rec=persist_b1-hlstm-csr;", l, d);
                 m->last_plan += tag;
-                HIP_TRY(m, launch_persist_b1_hlstm(a, m->cooperative, s));
+                HIP_TRY(m, launch_persist_b1_hlstm(a, m->launch_mode(), s));
                 continue;
             }
             if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
@@ -847,6 +878,9 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
     return LSTM_OK;
 }
 
+static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0, float* y, float* hT,
+                       float* cT, const Workspace& ws, char* base, hipStream_t s);
+
 int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0, float* y, float* hT,
                  float* cT, void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -862,7 +896,19 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
     const Workspace ws = carve(m, T, B);
     if (workspace_bytes < ws.total) return fail(m, LSTM_ERR_NOMEM, "lstm_forward: workspace too small");
     hipStream_t s = (hipStream_t)stream;
-    char* base = (char*)workspace;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    HIP_TRY(m, hipStreamIsCapturing(s, &cap));
+    m->capturing = (cap != hipStreamCaptureStatusNone);
+    m->cap_cleared = false;
+    m->cap_tag = 0;
+    const int rc_run = run_forward(m, T, B, x, h0, c0, y, hT, cT, ws, (char*)workspace, s);
+    m->capturing = false;
+    return rc_run;
+}
+
+static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0, float* y, float* hT,
+                       float* cT, const Workspace& ws, char* base, hipStream_t s)
+{
     const int H = m->H, Dn = m->Dn, L = m->L;
     const int M = T * B;
     const bool bf16 = (m->dtype == LSTM_BF16);
@@ -883,15 +929,8 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
     m->last_plan.clear();
     if (m->G > 0) return forward_hlstm(m, T, B, x, h0, c0, y, hT, cT, ws, base, s);
 
-    auto take_tags = [&](int T_) -> int {
-        if (m->tag_base > 0xFFFFFFFFu - (unsigned)T_ - 2u) {
-            // tag space exhausted: restart from a clean slate
-            hipError_t e = launch_fill_u64(m->xchg, (size_t)4 * H, 0ull, s);
-            if (e != hipSuccess) return fail_hip(m, e, "launch_fill_u64");
-            m->tag_base = 0;
-        }
-        return LSTM_OK;
-    };
+    unsigned tag0 = 0;   // base of the tags the next batch-1 launch uses
+    auto take_tags = [&](int T_) -> int { return take_b1_tags(m, (unsigned)T_, (size_t)4 * H, s, &tag0); };
     // slot count the batch-1 kernel will hold in registers: the trimmed slices where they exist
     auto b1_slots = [](const PackedMat& p) { return p.slots_trim > 0 ? p.slots_trim : p.slots; };
     auto sparse_ok = [&](const LayerDir& w, int D_in, int nl) {
@@ -940,9 +979,8 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
             fill_sparse_layer(a.layer[1], m->ld[l + 1], (size_t)l + 1, Yout2, H);
             a.x = X; a.x_bf16 = x_is_bf16; a.round_x_bf16 = (bf16 && !x_is_bf16); a.D0 = D;
             a.T = T; a.H = H; a.reverse = 0; a.round_h_bf16 = bf16;
-            a.xchg = m->xchg; a.tag_base = m->tag_base; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
-            m->tag_base += (unsigned)T;
-            HIP_TRY(m, launch_persist_b1_sparse(a, 2, m->waves_per_group, m->cooperative, s));
+            a.xchg = m->xchg; a.tag_base = tag0; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+            HIP_TRY(m, launch_persist_b1_sparse(a, 2, m->waves_per_group, m->launch_mode(), s));
             const bool ovf = m->ld[l].wx.slots_trim || m->ld[l].wh.slots_trim || m->ld[l + 1].wx.slots_trim || m->ld[l + 1].wh.slots_trim;
             std::snprintf(tag, sizeof tag, "l%d+l%d.d0:proj=fused-csr,rec=persist_b1-csr-wavefront%s;", l, l + 1, ovf ? "+ovf" : "");
             m->last_plan += tag;
@@ -1037,7 +1075,7 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 mtag += (unsigned)T;
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=dense,rec=persist-mfma-bf16;", l, d);
                 m->last_plan += tag;
-                HIP_TRY(m, launch_persist_mfma_bf16(a, h0 ? h0 + n * B * H : nullptr, m->cooperative != 0, s));
+                HIP_TRY(m, launch_persist_mfma_bf16(a, h0 ? h0 + n * B * H : nullptr, m->launch_mode() != 0, s));
             }
             prev_has_bf16 = true;
             continue;
@@ -1149,7 +1187,7 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 a.xchg = bslots; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 btag += (unsigned)T;
                 ProfSpan span(m, s, 1);
-                HIP_TRY(m, launch_persist_batched(a, Dn, nzmax, m->cooperative, s));
+                HIP_TRY(m, launch_persist_batched(a, Dn, nzmax, m->launch_mode(), s));
                 continue;
             }
         }
@@ -1225,10 +1263,9 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 fill_sparse_layer(a.layer[0], w, n, Yout + (size_t)d * H, y_ld);
                 a.x = X; a.x_bf16 = x_is_bf16; a.round_x_bf16 = (bf16 && !x_is_bf16); a.D0 = D;
                 a.T = T; a.H = H; a.reverse = d; a.round_h_bf16 = bf16;
-                a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = m->tag_base;
+                a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = tag0;
                 a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
-                m->tag_base += (unsigned)T;
-                HIP_TRY(m, launch_persist_b1_sparse(a, 1, m->waves_per_group, m->cooperative, s));
+                HIP_TRY(m, launch_persist_b1_sparse(a, 1, m->waves_per_group, m->launch_mode(), s));
             } else if (mode[d] == 2 || mode[d] == 3) {
                 int rc = take_tags(T);
                 if (rc != LSTM_OK) return rc;
@@ -1244,10 +1281,9 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                 a.y = Yout + (size_t)d * H; a.y_ld = y_ld;
                 a.hT = hTn; a.cT = cTn;
                 a.T = T; a.H = H; a.reverse = d; a.round_h_bf16 = bf16;
-                a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = m->tag_base;
+                a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = tag0;
                 a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
-                m->tag_base += (unsigned)T;
-                HIP_TRY(m, launch_persist_b1_dense(a, m->waves_per_group, m->cooperative, s));
+                HIP_TRY(m, launch_persist_b1_dense(a, m->waves_per_group, m->launch_mode(), s));
             } else {
                 const size_t state_bytes = (size_t)B * H * sizeof(float);
                 if (c0n)
