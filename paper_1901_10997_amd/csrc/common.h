@@ -251,6 +251,8 @@ struct PersistB1Args {
     int reverse;           // 1: walk t = T-1 .. 0
     int round_h_bf16;
     unsigned long long* xchg;  // [2][H] (value, tag) slots, library-owned
+    unsigned long long* xcc_ids;  // [64] tagged slots for the XCD ids of the workgroups, library-owned
+    int one_xcd;               // every workgroup on one XCD: only block ids = 0 mod 8 work (filled by the launcher)
     unsigned tag_base;         // tags tag_base+1 .. tag_base+T are used by this launch
     int* timeout_flag;         // set to 1 if a bounded wait expired
     unsigned spin_limit;
@@ -320,8 +322,10 @@ struct PersistBatchedArgs {
     PersistBatchedDir d[2];
     int T, B, H;
     int ug, bg;                // unit groups / batch groups per direction (filled by the launcher)
+    int ndir, xcd_local;       // directions in the grid; block ids grouped by XCD (filled by the launcher)
     int round_h_bf16;
     unsigned long long* xchg;  // [ndir][2][B][H] slots, zero or older tags only
+    unsigned long long* xcc_ids;  // [ndir * bg][64] tagged slots (XCD id of each unit group's workgroup), zero or older tags only
     unsigned tag_base;
     int* timeout_flag;
     unsigned spin_limit;
@@ -364,6 +368,7 @@ struct PersistBatchedHArgs {
     unsigned long long* xchg_h; // tagged slots, zero or older tags only
     float* xchg_u;              // plain values
     unsigned* flags;            // [ndir * bg][64], zero or older tags only
+    unsigned long long* xcc_ids; // [ndir * bg][64] tagged slots (XCD id of each unit group's workgroup), zero or older tags only
     unsigned tag_base;
     int* timeout_flag;
     unsigned spin_limit;

@@ -130,4 +130,40 @@ __device__ __forceinline__ void gather_tagged_interleave(const u64* slots, int n
     else gather_tagged_interleave_nf<4>(slots, n, want, dst, rows, stride, tid, nthreads, timeout_flag, spin_limit);
 }
 
+// ---- exchange inside one XCD -------------------------------------------------------------------------------------
+// The compute units of an XCD share one L2.  A store at workgroup scope is written through the compute unit's vector
+// cache into that L2 and stays there; an agent-scope load from any compute unit of the same XCD bypasses its vector
+// cache and finds it in the L2.  For workgroups that all run on one XCD this hand-over measured 35-50 % faster than
+// agent-scope stores, which travel to memory before anybody sees them (32 workgroups: 1.19 -> 0.78 us per round;
+// 16: 1.71 -> 0.86 us).  A workgroup on another XCD would never see such a store, so a group uses it only after it has
+// checked, in the launch itself, that its members do share an XCD.  (The loads stay at agent scope: polling loads at
+// workgroup scope may be served by the compute unit's own cache and never see anything.)
+
+// id of the XCD this wave runs on (hardware register XCC_ID, bits 3:0)
+__device__ __forceinline__ unsigned xcc_id() { return __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)); }
+
+// publish v at p for the other workgroups of the group
+template <class T>
+__device__ __forceinline__ void exchange_store(T* p, T v, bool same_xcd)
+{
+    if (same_xcd) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    else __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Do the `members` (<= 64) workgroups of this group all run on one XCD?  Every member publishes its XCD id in
+// ids[me] (agent scope, tagged `tag`), polls the whole list and compares; all of them read the same list and so
+// agree on the answer.  tmp: LDS, `members` floats, free for other use on return.  Called by the whole workgroup.
+__device__ __forceinline__ bool group_shares_xcd(u64* ids, int members, int me, unsigned tag, float* tmp, int tid,
+                                                 int nthreads, int* timeout_flag, unsigned spin_limit)
+{
+    if (tid == 0) __hip_atomic_store(ids + me, pack_slot((float)xcc_id(), tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    gather_tagged(ids, members, tag, tmp, tid, nthreads, timeout_flag, spin_limit);
+    __syncthreads();
+    bool same = true;
+    const float first = tmp[0];
+    for (int i = 1; i < members; ++i) same = same && (tmp[i] == first);
+    __syncthreads();
+    return same;
+}
+
 }  // namespace l355

@@ -306,7 +306,7 @@ static int create_model(int layers, int input_dim, int hidden_dim, int gate_hidd
     }
     hipError_t e = hipGetDevice(&m->device);
     // two cells (directions, or two stacked layers) x two parities; H-LSTM: h slots, then the 4G hidden-layer slots
-    const size_t slots = m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H;
+    const size_t slots = (m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H) + 64;   // + XCD ids of a launch's workgroups
     if (e == hipSuccess) e = hipMalloc((void**)&m->xchg, slots * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMemset(m->xchg, 0, slots * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMalloc((void**)&m->timeout_flag, sizeof(int));
@@ -485,15 +485,16 @@ static Workspace carve(const lstm_t* m, int T, int B)
     }
     w.hb0_off = off;
     if (m->dtype == LSTM_BF16) off += align256((size_t)m->Dn * B * H * sizeof(uint16_t));
-    // tagged exchange slots of the small-batch persistent recurrence: [Dn][2][B][H]
+    // tagged exchange slots of the small-batch persistent recurrence: [Dn][2][B][H], then one slot per workgroup for
+    // the XCD ids, 64 per batch group
     // (H-LSTM: h slots in [k][columns of a batch group] blocks padded to 256 bytes, ragged last group filled up,
-    // then one flag per unit group, 64 per batch group)
+    // then one flag per unit group, 64 per batch group, then the XCD id slots)
     w.slot_off = off;
     if (B >= 2) {
         const size_t groups = (size_t)B / 2 + 1;
         w.slot_bytes = m->G > 0 ? (size_t)m->Dn * (((size_t)B + 3) * H * sizeof(unsigned long long) + groups * 256 +
-                                                   groups * 64 * sizeof(unsigned))
-                                : (size_t)m->Dn * 2 * B * H * sizeof(unsigned long long);
+                                                   groups * 64 * (sizeof(unsigned) + sizeof(unsigned long long)))
+                                : (size_t)m->Dn * (2 * (size_t)B * H + groups * 64) * sizeof(unsigned long long);
         off += align256(w.slot_bytes);
     }
     // bf16 large-batch persistent recurrence: two exchange buffers of h_t and one flag per tile
@@ -713,6 +714,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 const size_t groups = (size_t)B / 2 + 1;
                 const size_t hslot_bytes = (size_t)Dn * (((size_t)B + 3) * H * sizeof(unsigned long long) + groups * 256);
                 unsigned* hflags = (unsigned*)(base + ws.slot_off + hslot_bytes);
+                unsigned long long* hxcc = (unsigned long long*)(hflags + (size_t)Dn * groups * 64);
                 if (!hslots_clean) {
                     HIP_TRY(m, launch_fill_u64(hslots, align256(ws.slot_bytes) / sizeof(unsigned long long), 0ull, s));
                     hslots_clean = true;
@@ -748,7 +750,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                     m->last_plan += tag;
                 }
                 a.T = T; a.B = B; a.H = H; a.G = G;
-                a.xchg_h = hslots; a.xchg_u = U[0]; a.flags = hflags;
+                a.xchg_h = hslots; a.xchg_u = U[0]; a.flags = hflags; a.xcc_ids = hxcc;
                 a.tag_base = htag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 htag += (unsigned)T + 1u;
                 ProfSpan span(m, s, 1);
@@ -930,7 +932,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
     if (m->G > 0) return forward_hlstm(m, T, B, x, h0, c0, y, hT, cT, ws, base, s);
 
     unsigned tag0 = 0;   // base of the tags the next batch-1 launch uses
-    auto take_tags = [&](int T_) -> int { return take_b1_tags(m, (unsigned)T_, (size_t)4 * H, s, &tag0); };
+    auto take_tags = [&](int T_) -> int { return take_b1_tags(m, (unsigned)T_, (size_t)4 * H + 64, s, &tag0); };
     // slot count the batch-1 kernel will hold in registers: the trimmed slices where they exist
     auto b1_slots = [](const PackedMat& p) { return p.slots_trim > 0 ? p.slots_trim : p.slots; };
     auto sparse_ok = [&](const LayerDir& w, int D_in, int nl) {
@@ -1157,7 +1159,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             }
             if (pb_ok) {
                 if (!bslots_clean) {
-                    HIP_TRY(m, launch_fill_u64(bslots, (size_t)Dn * 2 * B * H, 0ull, s));
+                    HIP_TRY(m, launch_fill_u64(bslots, align256(ws.slot_bytes) / sizeof(unsigned long long), 0ull, s));
                     bslots_clean = true;
                     btag = 0;
                 }
@@ -1184,7 +1186,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     m->last_plan += tag;
                 }
                 a.T = T; a.B = B; a.H = H; a.round_h_bf16 = bf16;
-                a.xchg = bslots; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                a.xchg = bslots; a.xcc_ids = bslots + (size_t)Dn * 2 * B * H; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 btag += (unsigned)T;
                 ProfSpan span(m, s, 1);
                 HIP_TRY(m, launch_persist_batched(a, Dn, nzmax, m->launch_mode(), s));
@@ -1281,7 +1283,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 a.y = Yout + (size_t)d * H; a.y_ld = y_ld;
                 a.hT = hTn; a.cT = cTn;
                 a.T = T; a.H = H; a.reverse = d; a.round_h_bf16 = bf16;
-                a.xchg = m->xchg + (size_t)d * 2 * H; a.tag_base = tag0;
+                a.xchg = m->xchg + (size_t)d * 2 * H; a.xcc_ids = m->xchg + (size_t)4 * H; a.tag_base = tag0;
                 a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 HIP_TRY(m, launch_persist_b1_dense(a, m->waves_per_group, m->launch_mode(), s));
             } else {

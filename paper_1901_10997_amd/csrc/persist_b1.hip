@@ -62,7 +62,14 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
     float* xbuf = pub + 16;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, upb = nthreads >> 6;
-    const int j = blockIdx.x * upb + wave;
+    // Workgroups are dealt to the eight XCDs in turn.  A grid small enough for one XCD is launched eight times as
+    // large and only the ids of residue 0 work, so that all of them can meet in one L2 (checked below).
+    int bid = blockIdx.x;
+    if (a.one_xcd) {
+        if (blockIdx.x & 7) return;
+        bid = blockIdx.x >> 3;
+    }
+    const int j = bid * upb + wave;
     const bool active = j < a.H;
 
     float wh[4][KI];
@@ -93,6 +100,10 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
     for (int e = tid; e < HP; e += nthreads) hbuf[e] = 0.f;  // padding beyond H must stay finite
     float c = (active && a.c0) ? a.c0[j] : 0.f;
     __syncthreads();
+    bool same_xcd = false;
+    if (a.one_xcd)
+        same_xcd = group_shares_xcd(a.xcc_ids, (int)(gridDim.x >> 3), bid, a.tag_base + 1u, hbuf, tid, nthreads,
+                                    a.timeout_flag, a.spin_limit);
 
     // Input side: x_t does not depend on the recurrence.  The workgroup requests row s+2 with coalesced loads at
     // the top of step s, parks it in LDS at the top of step s+1 (before the wait, so that nothing but h stands
@@ -175,11 +186,10 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
         if (lane == 0) pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
         __syncthreads();
         if (s + 1 < a.T && tid < upb) {
-            const int ju = blockIdx.x * upb + tid;
+            const int ju = bid * upb + tid;
             if (ju < a.H)
-                __hip_atomic_store(a.xchg + (size_t)((s + 1) & 1) * a.H + ju,
-                                   pack_slot(pub[tid], a.tag_base + (unsigned)s + 1u), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+                exchange_store(a.xchg + (size_t)((s + 1) & 1) * a.H + ju, pack_slot(pub[tid], a.tag_base + (unsigned)s + 1u),
+                               same_xcd);
         }
         // outputs after the publication: nothing on the way of h_t
         if (lane == 0 && active) {
@@ -478,7 +488,10 @@ static hipError_t launch_dense_ki(PersistB1Args a, int wpg_req, bool coop, hipSt
 {
     constexpr int MAXT = dense_maxt(KI, FUSEX);
     const int wpg = pick_waves(a.H, wpg_req, MAXT / 64, 1);
-    const int blocks = (a.H + wpg - 1) / wpg;
+    int blocks = (a.H + wpg - 1) / wpg;
+    // a grid that fits one XCD (an eighth of the compute units) is placed on one
+    a.one_xcd = (a.xcc_ids != nullptr && blocks > 1 && blocks <= device_num_cus() / 8) ? 1 : 0;
+    if (a.one_xcd) blocks *= 8;
     const size_t lds = ((size_t)KI * 64 * (FUSEX ? 3 : 1) + 16) * sizeof(float);
     void* args[] = {(void*)&a};
     return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT>, blocks, wpg * 64, lds, args, coop, s);

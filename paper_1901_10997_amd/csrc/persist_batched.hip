@@ -20,6 +20,9 @@
 
 namespace l355 {
 
+// configurations with registers to spare for the XCD-local hand-over
+constexpr bool persist_batched_xcd_capable(int nz, int upw) { return nz * upw < 24; }
+
 template <int NZ, int UPW, int BW>
 __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatchedArgs a)
 {
@@ -32,11 +35,23 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
     const int upb = nwaves * UPW;
     float* hbuf = lds;
     float* pub = lds + (size_t)BW * H;
-    // block -> (direction, batch group, unit group)
-    const int per_dir = a.ug * a.bg;
-    const int dir = blockIdx.x / per_dir;
-    const int rem = blockIdx.x % per_dir;
-    const int bgi = rem / a.ug, ugi = rem % a.ug;
+    // block -> (direction, batch group, unit group).  Workgroups are dealt to the eight XCDs in turn; when the groups
+    // fit, all workgroups of one (direction, batch group) -- the only ones that exchange data -- take ids of one
+    // residue modulo 8, so that they can meet in one XCD's L2 (checked below; only speed depends on the dealing order).
+    // (Not in the configurations at the register limit, where the extra state would spill; the launcher knows.)
+    constexpr bool kXcd = persist_batched_xcd_capable(NZ, UPW);
+    int dir, bgi, ugi;
+    if (kXcd && a.xcd_local) {
+        const int j = blockIdx.x >> 3;
+        const int g = (blockIdx.x & 7) + 8 * (j / a.ug);
+        if (g >= a.ndir * a.bg) return;     // padding ids take no part in the exchange
+        ugi = j % a.ug; dir = g / a.bg; bgi = g % a.bg;
+    } else {
+        const int per_dir = a.ug * a.bg;
+        dir = blockIdx.x / per_dir;
+        const int rem = blockIdx.x % per_dir;
+        bgi = rem / a.ug; ugi = rem % a.ug;
+    }
     const PersistBatchedDir& D = a.d[dir];
     const int b0 = bgi * BW;
     const int bw = (B - b0) < BW ? (B - b0) : BW;         // columns actually present
@@ -110,6 +125,12 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
     if constexpr (kCopy) {
         Pd_c = D.P; y_c = D.y; y_ld_c = (size_t)D.y_ld; hT_c = D.hT; cT_c = D.cT;
     }
+    // With the group's workgroups placed on one XCD (checked here, per launch, from the hardware's own id) h is handed
+    // over through that XCD's L2.
+    bool same_xcd = false;
+    if (kXcd && a.xcd_local)
+        same_xcd = group_shares_xcd(a.xcc_ids + ((size_t)dir * a.bg + bgi) * 64, a.ug, ugi, a.tag_base + 1u, hbuf, tid,
+                                    nthreads, a.timeout_flag, a.spin_limit);
     for (int s = 0; s < a.T; ++s) {
         const int t = D.reverse ? (a.T - 1 - s) : s;
         float pin = 0.f;
@@ -238,9 +259,8 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
                 const int b = e / upb, ul = e - b * upb;
                 const int unit = ugi * upb + ul;
                 if (b < bw && unit < H)
-                    __hip_atomic_store(xchg + ((size_t)((s + 1) & 1) * B + b0 + b) * H + unit,
-                                       pack_slot(pub[e], a.tag_base + (unsigned)s + 1u), __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+                    exchange_store(xchg + ((size_t)((s + 1) & 1) * B + b0 + b) * H + unit,
+                                   pack_slot(pub[e], a.tag_base + (unsigned)s + 1u), kXcd && same_xcd);
             }
         }
         if constexpr (kCopy) {
@@ -312,7 +332,11 @@ hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int c
     if (!persist_batched_plan(a.B, a.H, nz, ndir, &upw, &bw, &ug, &bg)) return hipErrorInvalidValue;
     a.ug = ug;
     a.bg = bg;
-    const int blocks = ug * bg * ndir;
+    // one XCD holds an eighth of the compute units; its share of the groups must fit there
+    const int per_xcd = (ndir * bg + 7) / 8;
+    a.ndir = ndir;
+    a.xcd_local = (persist_batched_xcd_capable(nz, upw) && ug <= 64 && per_xcd * ug <= device_num_cus() / 8) ? 1 : 0;
+    const int blocks = a.xcd_local ? 8 * per_xcd * ug : ug * bg * ndir;
     switch (nz) {
         case 1: return launch_nz<1>(a, upw, bw, blocks, cooperative != 0, s);
         case 2: return launch_nz<2>(a, upw, bw, blocks, cooperative != 0, s);

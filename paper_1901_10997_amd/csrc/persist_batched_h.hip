@@ -233,6 +233,12 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
     if constexpr (kCopy) {
         P1_c = D.P1; y_c = D.y; y_ld_c = (size_t)D.y_ld; hT_c = D.hT; cT_c = D.cT;
     }
+    // With the group's workgroups placed on one XCD (checked here, per launch, from the hardware's own id) the vectors
+    // are handed over through that XCD's L2.
+    bool same_xcd = false;
+    if (a.xcd_local)
+        same_xcd = group_shares_xcd(a.xcc_ids + grp * 64, a.ug, ugi, a.tag_base + 1u, hbuf, tid, nthreads, a.timeout_flag,
+                                    a.spin_limit);
     for (int s = 0; s < a.T; ++s) {
         const int t = D.reverse ? (a.T - 1 - s) : s;
         const unsigned tag = a.tag_base + (unsigned)s + 1u;
@@ -263,12 +269,12 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
             // dead columns of a ragged batch group are written as zeros: the consumers copy whole rows
             const float uval = (pb < bw && pre > 0.f) ? pre : 0.f;
             if (in_pairs && unit_l < G)
-                __hip_atomic_store(xu + ((size_t)row * G + unit_l) * BW + pb, uval, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                exchange_store(xu + ((size_t)row * G + unit_l) * BW + pb, uval, same_xcd);
         }
         // stores acknowledged by every wave, then the workgroup's flag
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
         __syncthreads();
-        if (tid == 0) __hip_atomic_store(flags + ugi, tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) exchange_store(flags + ugi, tag, same_xcd);
         // ---- stage 2: gate outputs from u_t, cell update
         if (wave == 0) {
             unsigned spins = 0;
@@ -315,8 +321,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
                 c = fmaf(gate, c, gi * gg);
                 const float h = go * tanhf_fast(c);
                 if (in_pairs && unit_l < H && s + 1 < a.T)
-                    __hip_atomic_store(xh + (size_t)unit_l * BW + pb, pack_slot(pb < bw ? h : 0.f, tag), __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+                    exchange_store(xh + (size_t)unit_l * BW + pb, pack_slot(pb < bw ? h : 0.f, tag), same_xcd);
                 if (ok2) {
                     (kCopy ? y_c : D.y)[((size_t)t * B + b0 + pb) * (kCopy ? y_ld_c : (size_t)D.y_ld) + unit_l] = h;
                     if (s + 1 == a.T) {
