@@ -212,6 +212,8 @@ struct PersistMfmaArgs {
     float* cT;
     uint16_t* hx;              // two exchange buffers of H * Bp bf16 each, Bp = B rounded up to 64
     unsigned* flags;           // one per tile, [ceil(B/64)][4H/64]; every value below tag_base + 1
+    unsigned long long* xcc_ids;  // [row blocks][64] tagged slots for the XCD ids of the tiles' workgroups, or nullptr
+    int xcd_local;             // block ids grouped by XCD (set by the launcher)
     unsigned tag_base;         // step s publishes tag_base + s + 1
     int* timeout_flag;
     unsigned spin_limit;
@@ -220,7 +222,8 @@ struct PersistMfmaArgs {
 };
 bool persist_mfma_supported(int B, int H);
 size_t persist_mfma_exchange_bytes(int B, int H);
-size_t persist_mfma_flag_count(int B, int H);
+size_t persist_mfma_flag_count(int B, int H);   // 32-bit words of flag storage, XCD id slots included
+size_t persist_mfma_ids_offset(int B, int H);   // word offset of the XCD id slots inside it
 hipError_t launch_persist_mfma_bf16(const PersistMfmaArgs& a, const float* h0, bool cooperative, hipStream_t s);
 
 // Row-compressed step for small batches: one or both directions of a layer per launch (H <= 2048).

@@ -1070,6 +1070,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 a.cT = cT ? cT + n * B * H : nullptr;
                 a.hx = hx;
                 a.flags = mflags;
+                a.xcc_ids = (unsigned long long*)(mflags + persist_mfma_ids_offset(B, H));
                 a.tag_base = mtag;
                 a.timeout_flag = m->timeout_flag;
                 a.spin_limit = m->spin_limit;

@@ -27,6 +27,7 @@
 // Every wait is bounded; an expired wait raises the timeout flag and the kernel runs to its end.
 #include "common.h"
 #include "device_math.h"
+#include "exchange.h"
 
 namespace l355 {
 
@@ -44,10 +45,21 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
     static_assert(RM * UT % NTH == 0 && PAIRS >= 1, "pairs must divide evenly over the threads");
     const int gm = (a.B + RM - 1) / RM, gn = (4 * a.H) / RN;
     const int nblk = gm * gn;
-    const int per_xcd = (nblk + 7) / 8;
-    const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-    if (logical >= nblk) return;                               // padding ids take no part in the exchange
-    const int tile_n = logical / gm, tile_m = logical % gm;    // tiles that share a W_h panel stay on one XCD
+    // Workgroups are dealt to the eight XCDs in turn.  The tiles of one block of batch rows -- the only ones that
+    // exchange h among themselves -- take ids of one residue modulo 8 when the groups fit, so that they can hand h over
+    // through one XCD's L2 (checked below); otherwise the tiles that share a W_h panel stay on one XCD.
+    int tile_m, tile_n;
+    if (a.xcd_local) {
+        const int jj = blockIdx.x >> 3;
+        tile_m = (blockIdx.x & 7) + 8 * (jj / gn);
+        tile_n = jj % gn;
+        if (tile_m >= gm) return;                              // padding ids take no part in the exchange
+    } else {
+        const int per_xcd = (nblk + 7) / 8;
+        const int logical = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+        if (logical >= nblk) return;
+        tile_n = logical / gm; tile_m = logical % gm;
+    }
     const int m0 = tile_m * RM, n0 = tile_n * RN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, fk = lane >> 5;
@@ -80,6 +92,11 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
     for (int i = 0; i < MT; ++i) aoff[i] = (unsigned)(((kbase >> 4) * Bp + m0 + i * 32 + fr) * 16 + 8 * fk);
     unsigned* const myflag = a.flags + (size_t)tile_m * gn + tile_n;
     const unsigned* const pollflag = a.flags + (size_t)tile_m * gn + (lane < gn ? lane : gn - 1);
+
+    bool same_xcd = false;
+    if (a.xcd_local)
+        same_xcd = group_shares_xcd(a.xcc_ids + (size_t)tile_m * 64, gn, tile_n, a.tag_base + 1u, part, tid, NTH,
+                                    a.timeout_flag, a.spin_limit);
 
     for (int s = 0; s < a.T; ++s) {
         const int t = a.reverse ? a.T - 1 - s : s;
@@ -174,8 +191,8 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
             const unsigned hbits = f32_to_bf16_bits(hn);
             const unsigned other = (unsigned)__builtin_amdgcn_update_dpp(0, (int)hbits, 0xB1, 0xF, 0xF, true);
             if ((u & 1) == 0 && !last)
-                __hip_atomic_store(reinterpret_cast<unsigned*>(hxo + ((size_t)(((n0 >> 2) + u) >> 4) * Bp + pb[r]) * 16 + (u & 15)),
-                                   hbits | (other << 16), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                exchange_store(reinterpret_cast<unsigned*>(hxo + ((size_t)(((n0 >> 2) + u) >> 4) * Bp + pb[r]) * 16 + (u & 15)),
+                               hbits | (other << 16), same_xcd);
             if (pb[r] < a.B) {
                 const int j = (n0 >> 2) + u;
                 const size_t row = (size_t)t * a.B + pb[r];
@@ -192,7 +209,7 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
             // partial tiles out of LDS until every thread has read this step's
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
             __syncthreads();
-            if (tid == 0) __hip_atomic_store(myflag, a.tag_base + (unsigned)s + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid == 0) exchange_store(myflag, a.tag_base + (unsigned)s + 1u, same_xcd);
         }
     }
 }
@@ -225,17 +242,29 @@ size_t persist_mfma_exchange_bytes(int B, int H)
     const size_t Bp = (size_t)((B + 32 * kMT - 1) / (32 * kMT)) * (32 * kMT);
     return 2 * (size_t)H * Bp * sizeof(uint16_t);
 }
-size_t persist_mfma_flag_count(int B, int H) { return (size_t)((B + 32 * kMT - 1) / (32 * kMT)) * (4 * H / (32 * kNT)); }
+// flags (one per tile, rounded up to an even count), then 64 two-word slots per block of batch rows for the XCD ids
+size_t persist_mfma_ids_offset(int B, int H)
+{
+    const size_t tiles = (size_t)((B + 32 * kMT - 1) / (32 * kMT)) * (4 * H / (32 * kNT));
+    return (tiles + 1) & ~(size_t)1;
+}
+size_t persist_mfma_flag_count(int B, int H)
+{
+    return persist_mfma_ids_offset(B, H) + (size_t)((B + 32 * kMT - 1) / (32 * kMT)) * 64 * 2;
+}
 
 template <int KS, int MT, int NT>
 static hipError_t launch_shape(const PersistMfmaArgs& a, const float* h0, bool cooperative, hipStream_t s)
 {
     constexpr int RM = 32 * MT, RN = 32 * NT;
     const int gm = (a.B + RM - 1) / RM, gn = (4 * a.H) / RN;
-    const int grid = ((gm * gn + 7) / 8) * 8;
     const size_t lds = (size_t)8 * RM * (RN + 4) * sizeof(float);
     PersistMfmaArgs args = a;
     args.has_h0 = h0 != nullptr;
+    // one XCD holds an eighth of the compute units; its share of the row blocks (gn tiles each) must fit there
+    const int groups_per_xcd = (gm + 7) / 8;
+    args.xcd_local = (a.xcc_ids != nullptr && gn <= 64 && groups_per_xcd * gn <= device_num_cus() / 8) ? 1 : 0;
+    const int grid = args.xcd_local ? 8 * groups_per_xcd * gn : ((gm * gn + 7) / 8) * 8;
     if (h0) {
         const size_t n = (size_t)a.B * a.H;
         int g = (int)((n + 255) / 256);
