@@ -13,9 +13,10 @@
 // Hidden-state exchange.  h_t (B x H bf16, 512 KB at B = 256, H = 1024) is too large for the tagged 8-byte slots
 // the small-batch kernels use, so data and readiness travel separately:
 //   producer  the tile's 32 x 32 block of h_t is stored as two contiguous 1 KB pieces of a [H/16][Bp][16] buffer
-//             with device-scope write-through stores; once the wave's stores have been acknowledged
+//             with device-scope write-through stores (workgroup-scope stores, which stay in the XCD's L2, when the
+//             tiles of the row block have been found to share an XCD); once the wave's stores have been acknowledged
 //             (outstanding-memory counter at zero) and the workgroup has met at a barrier, one thread publishes
-//             the step number in the tile's flag, again with a device-scope store.
+//             the step number in the tile's flag, with a store of the same scope.
 //   consumer  one wave polls the flags of the tiles that produce its batch rows (device-scope loads, bounded);
 //             after a workgroup barrier every wave reads its operand fragments with device-scope 8-byte loads,
 //             which do not hit stale lines of this compute unit's vector cache or this XCD's L2.  (An acquire
@@ -120,7 +121,10 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
                 if (wave == 0) {
                     const unsigned want = a.tag_base + (unsigned)s;
                     unsigned spins = 0;
-                    while (__hip_atomic_load(pollflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != want) {
+                    // "at least": a producer that has seen everybody's flag of this step may finish the step and raise its
+                    // flag to the next tag before a slower poller has looked; what that poller needs is still there (the
+                    // next h goes to the other buffer, and nobody can get two steps ahead of it)
+                    while ((int)(__hip_atomic_load(pollflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - want) < 0) {
                         if (++spins > a.spin_limit) {
                             __hip_atomic_store(a.timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                             break;

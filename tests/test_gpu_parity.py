@@ -168,6 +168,27 @@ def test_bf16_persistent_matrix_core_long_sequence():
     assert "persist-mfma" in desc
 
 
+def test_bf16_persistent_full_size_many_forwards_back_to_back():
+    """The throughput configuration, 60 forwards issued without a synchronisation in between (15 000 exchange rounds of
+    256 tiles): a tile that has seen every flag of a step may raise its own flag to the next tag before a slower tile
+    has looked, so the pollers must accept "at least" the tag they wait for.  No bounded wait may expire, and every
+    forward gives the same bits."""
+    import torch
+    case = inputs.make_case(inputs.c5(), 0)
+    first, desc, model = run_gpu(case, cooperative=False, return_model=True)
+    assert "persist-mfma" in desc
+    dev = torch.device("cuda:0")
+    x = torch.from_numpy(case.x).to(dev).to(torch.bfloat16)
+    outs = None
+    for _ in range(60):
+        outs = model.forward(x, check=False)
+    torch.cuda.synchronize()
+    B.lstm_check(model.handle)
+    for a, b in zip(first, outs):
+        assert np.array_equal(a, b.cpu().numpy())
+    model.close()
+
+
 @pytest.mark.parametrize("D", [192, 96, 320])
 def test_bf16_large_projection_ragged_tiles(D):
     """bf16 projections with T*B >= 2048 rows and 4H >= 512 columns take the 256 x 256 persistent-tile kernel
