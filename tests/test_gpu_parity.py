@@ -189,6 +189,26 @@ def test_bf16_persistent_full_size_many_forwards_back_to_back():
     model.close()
 
 
+@pytest.mark.parametrize("name", ["c1", "c4", "h2"])
+def test_full_size_forwards_back_to_back_give_the_same_bits(name):
+    """The workloads whose exchange goes through one XCD's L2, 20 forwards issued without a synchronisation in between:
+    no bounded wait expires and every forward reproduces the first one bit for bit (a hand-over that let a flag or a
+    tag overtake its data would show up as a difference)."""
+    import torch
+    case = inputs.make_case({"c1": inputs.c1, "c4": inputs.c4, "h2": inputs.h2}[name](), 0)
+    first, desc, model = run_gpu(case, cooperative=False, return_model=True)
+    assert "persist" in desc
+    x = torch.from_numpy(case.x).to(torch.device("cuda:0"))
+    outs = None
+    for _ in range(20):
+        outs = model.forward(x, check=False)
+    torch.cuda.synchronize()
+    B.lstm_check(model.handle)
+    for a, b in zip(first, outs):
+        assert np.array_equal(a, b.cpu().numpy())
+    model.close()
+
+
 @pytest.mark.parametrize("D", [192, 96, 320])
 def test_bf16_large_projection_ragged_tiles(D):
     """bf16 projections with T*B >= 2048 rows and 4H >= 512 columns take the 256 x 256 persistent-tile kernel
