@@ -74,26 +74,32 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
 
     float wh[4][KI];
     float wx[FUSEX ? 4 : 1][FUSEX ? KI : 1];
+    {
+        // Every load is issued whatever the shape (idle waves and columns past the width read a valid element and are
+        // zeroed afterwards) and the element type is decided once, outside: with a branch per element the loads went
+        // out one at a time, each waiting for the one before it.
+        const int jr = active ? j : a.H - 1;
+        auto fill = [&](auto* W, int K, auto& dst) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int i = 0; i < KI; ++i) {
-            const int k = lane + 64 * i;
-            float v = 0.f;
-            if (active && k < a.H) {
-                const size_t idx = (size_t)(4 * j + q) * a.H + k;
-                v = a.w_bf16 ? bf16_bits_to_f32(((const uint16_t*)a.Wh)[idx]) : ((const float*)a.Wh)[idx];
-            }
-            wh[q][i] = v;
-            if (FUSEX) {
-                float u = 0.f;
-                if (active && k < a.D) {
-                    const size_t idx = (size_t)(4 * j + q) * a.D + k;
-                    u = a.w_bf16 ? bf16_bits_to_f32(((const uint16_t*)a.Wx)[idx]) : ((const float*)a.Wx)[idx];
+                for (int i = 0; i < KI; ++i) {
+                    const int k = lane + 64 * i;
+                    const auto raw = W[(size_t)(4 * jr + q) * K + (k < K ? k : K - 1)];
+                    float v;
+                    if constexpr (sizeof(raw) == 2) v = bf16_bits_to_f32(raw);
+                    else v = raw;
+                    dst[q][i] = (active && k < K) ? v : 0.f;
                 }
-                wx[q][i] = u;
-            }
+        };
+        if (a.w_bf16) {
+            fill((const uint16_t*)a.Wh, a.H, wh);
+            if constexpr (FUSEX) fill((const uint16_t*)a.Wx, a.D, wx);
+        } else {
+            fill((const float*)a.Wh, a.H, wh);
+            if constexpr (FUSEX) fill((const float*)a.Wx, a.D, wx);
         }
+    }
     const int row = lane >> 4;                       // gate handled by this lane after the reduction
     float bias_l = 0.f;                              // fused: bias of gate `row`
     if (FUSEX && active) bias_l = a.bias[4 * j + row];
@@ -225,48 +231,67 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
 
     // values in fp32 registers; the 16-bit column indices two to a register (slot i in half i&1 of word i/2)
     constexpr int NZP = (NZ + 1) / 2;
+    // copies of the layer's remaining fields, taken together with the ones below (one round trip for all of them)
+    const int32_t* const opx = L.ovf_ptr_x;
+    const int32_t* const oph = L.ovf_ptr_h;
+    const uint32_t* const oenx = L.ovf_ent_x;
+    const uint32_t* const oenh = L.ovf_ent_h;
+    const float* const ovlx = L.ovf_val_x;
+    const float* const ovlh = L.ovf_val_h;
+    const float* const pbias = L.bias;
+    const float* const pc0 = L.c0;
+    const int jj = active ? j : H - 1;
+    // first entry and count of this unit's overflow lists, requested ahead of the weights
+    int obx = 0, obh = 0, nox = 0, noh = 0;
+    if (opx) { obx = opx[jj]; nox = opx[jj + 1]; }
+    if (oph) { obh = oph[jj]; noh = oph[jj + 1]; }
     float vx[4][NZ], vh[4][NZ];
     unsigned cxp[4][NZP], chp[4][NZP];
+    {
+        // The layer's fields are copied once (the layer is chosen by the wave index, so `L` lives in memory), and every
+        // load is issued whatever the shape -- idle waves and slices past the slot count read a valid element and are
+        // zeroed afterwards.  With a reload of the fields and a branch per element the loads went out one at a time,
+        // each behind two dependent round trips.
+        const float* const pvx = L.ell_val_x;
+        const float* const pvh = L.ell_val_h;
+        const uint16_t* const pcx = L.ell_col_x;
+        const uint16_t* const pch = L.ell_col_h;
+        const int sx = L.slots_x, sh = L.slots_h;
+        float tu[4][NZ], tv[4][NZ];
+        unsigned tku[4][NZ], tkv[4][NZ];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 4; ++q) {
 #pragma unroll
-        for (int i = 0; i < NZP; ++i) cxp[q][i] = chp[q][i] = 0u;
-#pragma unroll
-        for (int i = 0; i < NZ; ++i) {
-            float v = 0.f, u = 0.f;
-            unsigned kv = 0, ku = 0;
-            if (active) {
-                if (i < L.slots_x) {
-                    const size_t idx = ((size_t)(4 * j + q) * L.slots_x + i) * 64 + lane;
-                    u = L.ell_val_x[idx];
-                    ku = L.ell_col_x[idx];
-                }
-                if (i < L.slots_h) {
-                    const size_t idx = ((size_t)(4 * j + q) * L.slots_h + i) * 64 + lane;
-                    v = L.ell_val_h[idx];
-                    kv = L.ell_col_h[idx];
-                }
+            for (int i = 0; i < NZ; ++i) {
+                const size_t ix = ((size_t)(4 * jj + q) * sx + (i < sx ? i : sx - 1)) * 64 + lane;
+                const size_t ih = ((size_t)(4 * jj + q) * sh + (i < sh ? i : sh - 1)) * 64 + lane;
+                tu[q][i] = pvx[ix];
+                tku[q][i] = pcx[ix];
+                tv[q][i] = pvh[ih];
+                tkv[q][i] = pch[ih];
             }
-            vx[q][i] = u;
-            vh[q][i] = v;
-            cxp[q][i >> 1] |= ku << (16 * (i & 1));
-            chp[q][i >> 1] |= kv << (16 * (i & 1));
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int i = 0; i < NZP; ++i) cxp[q][i] = chp[q][i] = 0u;
+#pragma unroll
+            for (int i = 0; i < NZ; ++i) {
+                const bool lx = active && i < sx, lh = active && i < sh;
+                vx[q][i] = lx ? tu[q][i] : 0.f;
+                vh[q][i] = lh ? tv[q][i] : 0.f;
+                cxp[q][i >> 1] |= (lx ? tku[q][i] : 0u) << (16 * (i & 1));
+                chp[q][i >> 1] |= (lh ? tkv[q][i] : 0u) << (16 * (i & 1));
+            }
         }
     }
     // overflow entries of this unit's rows (rows longer than 64*slots; rare): lane e holds entry e
-    int nox = 0, noh = 0;
     unsigned oex = 0u, oeh = 0u;
     float ovx = 0.f, ovh = 0.f;
-    if (active && L.ovf_ptr_x) {
-        const int b = L.ovf_ptr_x[j];
-        nox = L.ovf_ptr_x[j + 1] - b;
-        if (lane < nox) { oex = L.ovf_ent_x[b + lane]; ovx = L.ovf_val_x[b + lane]; }
-    }
-    if (active && L.ovf_ptr_h) {
-        const int b = L.ovf_ptr_h[j];
-        noh = L.ovf_ptr_h[j + 1] - b;
-        if (lane < noh) { oeh = L.ovf_ent_h[b + lane]; ovh = L.ovf_val_h[b + lane]; }
-    }
+    nox = active ? nox - obx : 0;
+    noh = active ? noh - obh : 0;
+    if (lane < nox) { oex = oenx[obx + lane]; ovx = ovlx[obx + lane]; }
+    if (lane < noh) { oeh = oenh[obh + lane]; ovh = ovlh[obh + lane]; }
     nox = __builtin_amdgcn_readfirstlane(nox);
     noh = __builtin_amdgcn_readfirstlane(noh);
     // lane e adds its overflow product to the partial sum of the gate its entry belongs to
@@ -281,8 +306,8 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
 #define COLX(q, i) ((cxp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
 #define COLH(q, i) ((chp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
     const int row = lane >> 4;                       // gate handled by this lane after the reduction
-    const float bias_l = active ? L.bias[4 * j + row] : 0.f;
-    float c = (active && L.c0) ? L.c0[j] : 0.f;
+    const float bias_l = active ? pbias[4 * j + row] : 0.f;
+    float c = (active && pc0) ? pc0[j] : 0.f;
     const int total_steps = a.T + NL - 1;
     // The layer is chosen by the wave index, so the compiler addresses `L` through memory; taken inside the time loop
     // these fields cost a load and a wait on the critical path of every step.  Copies made once:

@@ -63,24 +63,38 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
     constexpr int NZP = (4 * NZ + 1) / 2;
     float wv[UPW][4][NZ];
     unsigned wc[UPW][NZP];
+    {
+        // Every load is issued whatever the shape (units past H and slices past `slots` read a valid element and are
+        // zeroed afterwards): with a branch per element the loads went out one at a time, each waiting for the one
+        // before it, and filling the registers took 30 us.
+        const int slots = D.slots;
+        float tv[4 * NZ];
+        unsigned tk[4 * NZ];
 #pragma unroll
-    for (int u = 0; u < UPW; ++u) {
+        for (int u = 0; u < UPW; ++u) {
+            const int unit = (u0 + u < H) ? (u0 + u) : (H - 1);
 #pragma unroll
-        for (int i = 0; i < NZP; ++i) wc[u][i] = 0u;
+            for (int q = 0; q < 4; ++q) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-#pragma unroll
-            for (int i = 0; i < NZ; ++i) {
-                float v = 0.f;
-                unsigned k = 0;
-                if (u0 + u < H && i < D.slots) {
-                    const size_t idx = ((size_t)(4 * (u0 + u) + q) * D.slots + i) * 64 + lane;
-                    v = D.ell_val[idx];
-                    k = D.ell_col[idx];
+                for (int i = 0; i < NZ; ++i) {
+                    const int ii = i < slots ? i : slots - 1;
+                    const size_t idx = ((size_t)(4 * unit + q) * slots + ii) * 64 + lane;
+                    tv[q * NZ + i] = D.ell_val[idx];
+                    tk[q * NZ + i] = D.ell_col[idx];
                 }
-                wv[u][q][i] = v;
-                const int n = q * NZ + i;
-                wc[u][n >> 1] |= (k * (BW * 4u)) << (16 * (n & 1));   // byte offset of h[k][0] in LDS (< 65536)
+            }
+#pragma unroll
+            for (int i = 0; i < NZP; ++i) wc[u][i] = 0u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                for (int i = 0; i < NZ; ++i) {
+                    const bool live = (u0 + u < H) && i < slots;
+                    const int n = q * NZ + i;
+                    wv[u][q][i] = live ? tv[n] : 0.f;
+                    // byte offset of h[k][0] in LDS (< 65536)
+                    wc[u][n >> 1] |= ((live ? tk[n] : 0u) * (BW * 4u)) << (16 * (n & 1));
+                }
             }
         }
     }
@@ -147,8 +161,12 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
                 hbuf[k * BW + b] = v;
             }
         } else {
-            // (eight polling loads in flight need sixteen registers: not in the configurations at the register limit)
-            if constexpr (NZ * UPW >= 20)
+            // (eight polling loads in flight need sixteen registers: not in the configurations at the register limit;
+            // the heaviest ones serve the widest layers and take six, which covers 3072 slots in one polling round)
+            if constexpr (NZ * UPW >= 24)
+                gather_tagged_interleave_nf<6>(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H,
+                                               BW, tid, nthreads, a.timeout_flag, a.spin_limit);
+            else if constexpr (NZ * UPW >= 20)
                 gather_tagged_interleave_nf<4>(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H,
                                                BW, tid, nthreads, a.timeout_flag, a.spin_limit);
             else

@@ -81,31 +81,41 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
     // kept weights of this wave's units; the column is kept as the 16-bit LDS byte offset of its BW values
     float w1[UPW][4][NZ], w2[UPW][4][NZ];
     unsigned o1[UPW][NZP], o2[UPW][NZP];
+    {
+        // Every load is issued whatever the shape (units past the width and slices past a matrix's slot count read a
+        // valid element and are zeroed afterwards): with a branch per element the loads went out one at a time, each
+        // waiting for the one before it.
+        const int s1 = D.slots_1h, s2 = D.slots_2;
+        float t1[4 * NZ], t2[4 * NZ];
+        unsigned k1[4 * NZ], k2[4 * NZ];
 #pragma unroll
-    for (int u = 0; u < UPW; ++u) {
+        for (int u = 0; u < UPW; ++u) {
+            const int g1 = (u0 + u < G) ? (u0 + u) : (G - 1), j2 = (u0 + u < H) ? (u0 + u) : (H - 1);
 #pragma unroll
-        for (int i = 0; i < NZP; ++i) o1[u][i] = o2[u][i] = 0u;
+            for (int q = 0; q < 4; ++q) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-#pragma unroll
-            for (int i = 0; i < NZ; ++i) {
-                float v1 = 0.f, v2 = 0.f;
-                unsigned k1 = 0, k2 = 0;
-                if (u0 + u < G && i < D.slots_1h) {
-                    const size_t idx = ((size_t)(4 * (u0 + u) + q) * D.slots_1h + i) * 64 + lane;
-                    v1 = D.ell_val_1h[idx];
-                    k1 = D.ell_col_1h[idx];
+                for (int i = 0; i < NZ; ++i) {
+                    const size_t i1 = ((size_t)(4 * g1 + q) * s1 + (i < s1 ? i : s1 - 1)) * 64 + lane;
+                    const size_t i2 = ((size_t)(4 * j2 + q) * s2 + (i < s2 ? i : s2 - 1)) * 64 + lane;
+                    t1[q * NZ + i] = D.ell_val_1h[i1];
+                    k1[q * NZ + i] = D.ell_col_1h[i1];
+                    t2[q * NZ + i] = D.ell_val_2[i2];
+                    k2[q * NZ + i] = D.ell_col_2[i2];
                 }
-                if (u0 + u < H && i < D.slots_2) {
-                    const size_t idx = ((size_t)(4 * (u0 + u) + q) * D.slots_2 + i) * 64 + lane;
-                    v2 = D.ell_val_2[idx];
-                    k2 = D.ell_col_2[idx];
+            }
+#pragma unroll
+            for (int i = 0; i < NZP; ++i) o1[u][i] = o2[u][i] = 0u;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                for (int i = 0; i < NZ; ++i) {
+                    const bool l1 = (u0 + u < G) && i < s1, l2 = (u0 + u < H) && i < s2;
+                    const int n = q * NZ + i;
+                    w1[u][q][i] = l1 ? t1[n] : 0.f;
+                    w2[u][q][i] = l2 ? t2[n] : 0.f;
+                    o1[u][n >> 1] |= ((l1 ? k1[n] : 0u) * (BW * 4u)) << (16 * (n & 1));                       // h[k][0]
+                    o2[u][n >> 1] |= (((unsigned)q * G + (l2 ? k2[n] : 0u)) * (BW * 4u)) << (16 * (n & 1));   // u[q*G + k][0]
                 }
-                w1[u][q][i] = v1;
-                w2[u][q][i] = v2;
-                const int n = q * NZ + i;
-                o1[u][n >> 1] |= (k1 * (BW * 4u)) << (16 * (n & 1));                       // h[k][0]
-                o2[u][n >> 1] |= (((unsigned)q * G + k2) * (BW * 4u)) << (16 * (n & 1));   // u[q*G + k][0]
             }
         }
     }

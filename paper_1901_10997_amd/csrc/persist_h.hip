@@ -48,37 +48,37 @@ __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
     constexpr int NZP = (NZ + 1) / 2;
     float v1x[4][NZ], v1h[4][NZ], v2[4][NZ];
     unsigned c1x[4][NZP], c1h[4][NZP], c2[4][NZP];
+    // Every load of a matrix is issued whatever the shape (idle waves and slices past the slot count read a valid element
+    // and are zeroed afterwards), one matrix at a time: with a branch per element the loads went out one by one, each
+    // waiting for the one before it.
+    auto load_matrix = [&](const float* val, const uint16_t* col, int slots, int rows, bool act, float (&v)[4][NZ],
+                           unsigned (&c)[4][NZP]) {
+        const int un = act ? unit : rows - 1;
+        float tv[4][NZ];
+        unsigned tk[4][NZ];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int i = 0; i < NZP; ++i) c1x[q][i] = c1h[q][i] = c2[q][i] = 0u;
+            for (int i = 0; i < NZ; ++i) {
+                const size_t idx = ((size_t)(4 * un + q) * slots + (i < slots ? i : slots - 1)) * 64 + lane;
+                tv[q][i] = val[idx];
+                tk[q][i] = col[idx];
+            }
 #pragma unroll
-        for (int i = 0; i < NZ; ++i) {
-            float fx = 0.f, fh = 0.f, f2 = 0.f;
-            unsigned kx = 0, kh = 0, k2 = 0;
-            if (act1 && i < a.slots_1x) {
-                const size_t idx = ((size_t)(4 * unit + q) * a.slots_1x + i) * 64 + lane;
-                fx = a.ell_val_1x[idx];
-                kx = a.ell_col_1x[idx];
+        for (int q = 0; q < 4; ++q) {
+#pragma unroll
+            for (int i = 0; i < NZP; ++i) c[q][i] = 0u;
+#pragma unroll
+            for (int i = 0; i < NZ; ++i) {
+                const bool live = act && i < slots;
+                v[q][i] = live ? tv[q][i] : 0.f;
+                c[q][i >> 1] |= (live ? tk[q][i] : 0u) << (16 * (i & 1));
             }
-            if (act1 && i < a.slots_1h) {
-                const size_t idx = ((size_t)(4 * unit + q) * a.slots_1h + i) * 64 + lane;
-                fh = a.ell_val_1h[idx];
-                kh = a.ell_col_1h[idx];
-            }
-            if (act2 && i < a.slots_2) {
-                const size_t idx = ((size_t)(4 * unit + q) * a.slots_2 + i) * 64 + lane;
-                f2 = a.ell_val_2[idx];
-                k2 = a.ell_col_2[idx];
-            }
-            v1x[q][i] = fx;
-            v1h[q][i] = fh;
-            v2[q][i] = f2;
-            c1x[q][i >> 1] |= kx << (16 * (i & 1));
-            c1h[q][i >> 1] |= kh << (16 * (i & 1));
-            c2[q][i >> 1] |= k2 << (16 * (i & 1));
         }
-    }
+    };
+    load_matrix(a.ell_val_1x, a.ell_col_1x, a.slots_1x, G, act1, v1x, c1x);
+    load_matrix(a.ell_val_1h, a.ell_col_1h, a.slots_1h, G, act1, v1h, c1h);
+    load_matrix(a.ell_val_2, a.ell_col_2, a.slots_2, H, act2, v2, c2);
 #define HCOL(arr, q, i) ((arr[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
     const int row = lane >> 4;                       // gate held by this lane after the reduction
     const float bias1 = act1 ? a.bias1[4 * unit + row] : 0.f;
