@@ -231,6 +231,25 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
 
     // values in fp32 registers; the 16-bit column indices two to a register (slot i in half i&1 of word i/2)
     constexpr int NZP = (NZ + 1) / 2;
+    constexpr int XPT = 2;  // x elements per thread held in registers
+    float xr[XPT];
+    auto request_x = [&](int s_) {
+        const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s_) : s_) * a.D0;
+        if (a.x_bf16) {
+#pragma unroll
+            for (int u = 0; u < XPT; ++u) {
+                const int e = tid + u * nthreads;
+                xr[u] = (e < a.D0) ? bf16_bits_to_f32(((const uint16_t*)a.x)[xrow + e]) : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < XPT; ++u) {
+                const int e = tid + u * nthreads;
+                xr[u] = (e < a.D0) ? ((const float*)a.x)[xrow + e] : 0.f;
+            }
+        }
+    };
+    request_x(0);   // first of everything: the row is in flight while the weights are fetched
     // copies of the layer's remaining fields, taken together with the ones below (one round trip for all of them)
     const int32_t* const opx = L.ovf_ptr_x;
     const int32_t* const oph = L.ovf_ptr_h;
@@ -321,24 +340,6 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
     // at the top of step s+1 (before the wait, so that nothing but h stands between the arrival of h and the
     // products), and the first layer's waves gather their products for step s+1 after h_s has been published --
     // the time in which they would otherwise idle until that h has travelled.
-    constexpr int XPT = 2;  // x elements per thread held in registers
-    float xr[XPT];
-    auto request_x = [&](int s_) {
-        const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s_) : s_) * a.D0;
-        if (a.x_bf16) {
-#pragma unroll
-            for (int u = 0; u < XPT; ++u) {
-                const int e = tid + u * nthreads;
-                xr[u] = (e < a.D0) ? bf16_bits_to_f32(((const uint16_t*)a.x)[xrow + e]) : 0.f;
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < XPT; ++u) {
-                const int e = tid + u * nthreads;
-                xr[u] = (e < a.D0) ? ((const float*)a.x)[xrow + e] : 0.f;
-            }
-        }
-    };
     auto park_x = [&](int s_) {
         const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s_) : s_) * a.D0;
         float* xb = xbuf + (size_t)(s_ & 1) * a.D0;
@@ -365,7 +366,6 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
             add_overflow(xacc, nox, oex, ovx, xb);
         }
     };
-    request_x(0);
     park_x(0);
     __syncthreads();
     x_products(0);
