@@ -74,32 +74,26 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
 
     float wh[4][KI];
     float wx[FUSEX ? 4 : 1][FUSEX ? KI : 1];
-    {
-        // Every load is issued whatever the shape (idle waves and columns past the width read a valid element and are
-        // zeroed afterwards) and the element type is decided once, outside: with a branch per element the loads went
-        // out one at a time, each waiting for the one before it.
-        const int jr = active ? j : a.H - 1;
-        auto fill = [&](auto* W, int K, auto& dst) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+    for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int i = 0; i < KI; ++i) {
-                    const int k = lane + 64 * i;
-                    const auto raw = W[(size_t)(4 * jr + q) * K + (k < K ? k : K - 1)];
-                    float v;
-                    if constexpr (sizeof(raw) == 2) v = bf16_bits_to_f32(raw);
-                    else v = raw;
-                    dst[q][i] = (active && k < K) ? v : 0.f;
+        for (int i = 0; i < KI; ++i) {
+            const int k = lane + 64 * i;
+            float v = 0.f;
+            if (active && k < a.H) {
+                const size_t idx = (size_t)(4 * j + q) * a.H + k;
+                v = a.w_bf16 ? bf16_bits_to_f32(((const uint16_t*)a.Wh)[idx]) : ((const float*)a.Wh)[idx];
+            }
+            wh[q][i] = v;
+            if (FUSEX) {
+                float u = 0.f;
+                if (active && k < a.D) {
+                    const size_t idx = (size_t)(4 * j + q) * a.D + k;
+                    u = a.w_bf16 ? bf16_bits_to_f32(((const uint16_t*)a.Wx)[idx]) : ((const float*)a.Wx)[idx];
                 }
-        };
-        if (a.w_bf16) {
-            fill((const uint16_t*)a.Wh, a.H, wh);
-            if constexpr (FUSEX) fill((const uint16_t*)a.Wx, a.D, wx);
-        } else {
-            fill((const float*)a.Wh, a.H, wh);
-            if constexpr (FUSEX) fill((const float*)a.Wx, a.D, wx);
+                wx[q][i] = u;
+            }
         }
-    }
     const int row = lane >> 4;                       // gate handled by this lane after the reduction
     float bias_l = 0.f;                              // fused: bias of gate `row`
     if (FUSEX && active) bias_l = a.bias[4 * j + row];
