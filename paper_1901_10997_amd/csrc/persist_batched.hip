@@ -12,7 +12,10 @@
 // (pair = local unit * BW + column), evaluates all gates of all its pairs with one exp2 and one reciprocal,
 // and updates c and h in lanes 0..pairs-1.  h travels between workgroups through tagged 64-bit slots (value
 // and step tag published by one store; consumers poll until the tag matches), laid out [parity][B][H] per
-// direction so that a batch group's columns are contiguous.  All waits are bounded.
+// direction so that a batch group's columns are contiguous.  Only the workgroups of one (direction, batch group)
+// exchange anything; where the groups fit they are placed on one XCD each and, once the launch has verified that
+// from the hardware's XCD ids, publish h with workgroup-scope stores that stay in that XCD's L2 (exchange.h).
+// All waits are bounded.
 #include <type_traits>
 #include "common.h"
 #include "device_math.h"

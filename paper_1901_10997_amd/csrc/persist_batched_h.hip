@@ -24,7 +24,9 @@
 //         (An acquire fence followed by ordinary cached loads measured three times slower for these 50 KB.)
 // One array per vector is enough: u_{t+1} is written only after its producer has received every h_t of the batch
 // group, and each of those was published after its producer had finished reading u_t (and the same with the roles
-// swapped).  All waits are bounded: on expiry a device flag is raised, every wave stops waiting, the kernel drains.
+// swapped).  Where the batch groups fit one XCD each and the launch has verified the placement from the hardware's
+// XCD ids, h, u and the flags are stored at workgroup scope and meet in that XCD's L2 (exchange.h).
+// All waits are bounded: on expiry a device flag is raised, every wave stops waiting, the kernel drains.
 #include <type_traits>
 #include "common.h"
 #include "device_math.h"
