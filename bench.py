@@ -61,6 +61,10 @@ def parse():
     ap.add_argument("--sweep-speech", action="store_true",
                     help="model-level latency profile of the bidirectional speech stack at batch 16 over the hidden "
                          "width (writes latency_sweep_speech.json into --out)")
+    ap.add_argument("--sweep-exchange", action="store_true",
+                    help="the exchange inside groups of workgroups with no arithmetic: groups dealt over all XCDs, groups "
+                         "placed on one XCD each, and those with workgroup-scope stores (writes exchange_groups.json "
+                         "into --out)")
     ap.add_argument("--compare-launch-modes", action="store_true", help="also time the loop in the other launch mode")
     ap.add_argument("--sweep", action="store_true", help="also run the hidden-size latency sweep (written to --out)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -307,6 +311,24 @@ def main():
         with open(os.path.join(args.out, "matmul_sweep.json"), "w") as fh:
             json.dump(res, fh)
         out["sweep_matmul"] = {"points": len(ns), "dense_redundancy_pct_eps2pct": red2}
+    if args.sweep_exchange:
+        os.makedirs(args.out, exist_ok=True)
+        coop = args.launch == "cooperative"
+        # (slots, members, groups): the shapes of the kernels that exchange inside groups
+        shapes = [(200, 13, 1), (1024, 32, 8), (1600, 16, 16), (3200, 25, 8), (6000, 30, 8), (800, 8, 8), (3000, 24, 10)]
+        rows = []
+        for slots, members, groups in shapes:
+            row = {"slots": slots, "members": members, "groups": groups}
+            row["spread_us"], _ = B.lstm_bench_group_exchange(slots, members, groups, False, False, cooperative=coop, stream=stream)
+            if ((groups + 7) // 8) * members <= 32:
+                row["placed_us"], row["verified"] = B.lstm_bench_group_exchange(slots, members, groups, True, False,
+                                                                                cooperative=coop, stream=stream)
+                row["placed_l2_us"], _ = B.lstm_bench_group_exchange(slots, members, groups, True, True, cooperative=coop,
+                                                                     stream=stream)
+            rows.append(row)
+        with open(os.path.join(args.out, "exchange_groups.json"), "w") as fh:
+            json.dump({"launch": args.launch, "rows": rows}, fh)
+        out["sweep_exchange"] = rows
     if args.sweep_speech:
         # the paper's model-level figure: latency of the bidirectional speech stack at batch 16 against the hidden
         # width (here: 5 layers, 15 % kept weights as in workload c4, T = 100)

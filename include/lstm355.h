@@ -317,6 +317,20 @@ int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double*
 int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, double* avg_us,
                       float* y_host, void* stream);
 int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream);
+/*
+ * The exchange inside groups of workgroups, with no arithmetic (yardstick of the kernels whose workgroups exchange only
+ * inside one (direction, batch group), and the measurement behind the hand-over through one XCD's L2): `groups` groups
+ * of `members` (<= 64) workgroups, each group passing `slots` (<= 16384) tagged 8-byte slots round among its members for
+ * `steps` rounds; groups * members must not exceed the number of compute units.
+ *   placed = 0: block ids in order, so a group's members are dealt over all XCDs; device-scope stores.
+ *   placed = 1: a group's members take block ids of one residue modulo 8 (LSTM_ERR_ARG when an XCD's share of the groups
+ *   does not fit its compute units); each group checks from the hardware's XCD ids that it shares an XCD, and only then,
+ *   and only if workgroup_stores = 1, publishes with workgroup-scope stores.
+ * *avg_us_per_round (HOST): average microseconds per round; *groups_verified (HOST, may be NULL): groups whose check
+ * succeeded in the warm-up launch (0 when placed = 0).  Allocates its own buffers and synchronises the stream.
+ */
+int lstm_bench_group_exchange(int slots, int members, int groups, int placed, int workgroup_stores, int steps, int iters,
+                              int cooperative, double* avg_us_per_round, int* groups_verified, void* stream);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,7 @@ EXPORTS = [
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
     "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_prune_weights", "lstm_prune_rows_cols",
     "lstm_compact_rows_cols",
-    "lstm_bench_copy", "lstm_bench_matmul", "lstm_bench_exchange",
+    "lstm_bench_copy", "lstm_bench_matmul", "lstm_bench_exchange", "lstm_bench_group_exchange",
 ]
 
 _lib = None
@@ -106,6 +106,8 @@ def load(build_if_missing: bool = True):
     lib.lstm_bench_copy.argtypes = [vp, vp, c.c_size_t, ci, c.POINTER(c.c_double), vp]
     lib.lstm_bench_exchange.restype = ci
     lib.lstm_bench_exchange.argtypes = [ci, ci, ci, ci, ci, c.POINTER(c.c_double), vp]
+    lib.lstm_bench_group_exchange.restype = ci
+    lib.lstm_bench_group_exchange.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, c.POINTER(c.c_double), c.POINTER(ci), vp]
     _lib = lib
     return lib
 
@@ -317,6 +319,15 @@ def lstm_bench_matmul(n: int, batch: int, keep: float, fmt: int, seed: int = 1, 
     _check(load().lstm_bench_matmul(n, batch, float(keep), fmt, seed, iters, ctypes.byref(us),
                                     None if y is None else y.ctypes.data, stream))
     return (us.value, y) if want_product else us.value
+
+
+def lstm_bench_group_exchange(slots: int, members: int, groups: int, placed: bool, workgroup_stores: bool, steps: int = 200,
+                              iters: int = 5, cooperative: bool = True, stream: Optional[int] = None):
+    """Returns (microseconds per round, groups whose one-XCD check succeeded)."""
+    us, ver = ctypes.c_double(), ctypes.c_int()
+    _check(load().lstm_bench_group_exchange(slots, members, groups, int(bool(placed)), int(bool(workgroup_stores)), steps, iters,
+                                            int(bool(cooperative)), ctypes.byref(us), ctypes.byref(ver), stream))
+    return us.value, ver.value
 
 
 def lstm_bench_exchange(hidden: int, waves: int = 0, steps: int = 200, iters: int = 5, stream: Optional[int] = None,

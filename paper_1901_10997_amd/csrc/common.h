@@ -393,5 +393,8 @@ hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_exchange_only(unsigned long long* xchg, unsigned tag_base, int H, int waves, int steps,
                                 int* timeout_flag, unsigned spin_limit, int cooperative, hipStream_t s);
+hipError_t launch_group_exchange(unsigned long long* slots, unsigned long long* ids, unsigned tag_base, int n, int members,
+                                 int groups, int placed, int workgroup_stores, int steps, int* timeout_flag,
+                                 unsigned spin_limit, int* verified, int cooperative, hipStream_t s);
 
 }  // namespace l355

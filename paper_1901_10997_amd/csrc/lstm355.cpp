@@ -1773,4 +1773,56 @@ int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int coopera
     return rc;
 }
 
+int lstm_bench_group_exchange(int slots, int members, int groups, int placed, int workgroup_stores, int steps, int iters,
+                              int cooperative, double* avg_us_per_round, int* groups_verified, void* stream)
+{
+    if (slots < 1 || slots > 16384 || members < 1 || members > 64 || groups < 1 || groups > 64 || steps < 2 || iters < 1 ||
+        !avg_us_per_round || (long long)groups * members > device_num_cus())
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_group_exchange: bad arguments");
+    if (placed && ((groups + 7) / 8) * members > device_num_cus() / 8)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_group_exchange: the groups of one XCD do not fit its compute units");
+    hipStream_t s = (hipStream_t)stream;
+    const size_t nslot = (size_t)groups * 2 * slots + (size_t)groups * 64;
+    unsigned long long* buf = nullptr;
+    int* small = nullptr;   // timeout flag | verified count
+    HIP_TRY(nullptr, hipMalloc((void**)&buf, nslot * 8));
+    hipError_t e = hipMemset(buf, 0, nslot * 8);
+    if (e == hipSuccess) e = hipMalloc((void**)&small, 8);
+    if (e == hipSuccess) e = hipMemset(small, 0, 8);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    unsigned tag = 0;
+    auto run = [&]() {
+        hipError_t r = launch_group_exchange(buf, buf + (size_t)groups * 2 * slots, tag, slots, members, groups, placed,
+                                             workgroup_stores, steps, small, 1u << 22, small + 1, cooperative, s);
+        tag += (unsigned)steps + 1u;
+        return r;
+    };
+    if (e == hipSuccess) e = run();                       // warm-up, also the one whose verified count is reported
+    int host_small[2] = {0, 0};
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e == hipSuccess) e = hipMemcpy(host_small, small, 8, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int i = 0; i < iters && e == hipSuccess; ++i) e = run();
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    int f = 0;
+    if (e == hipSuccess) e = hipMemcpy(&f, small, 4, hipMemcpyDeviceToHost);
+    int rc = LSTM_OK;
+    if (e != hipSuccess) rc = fail_hip(nullptr, e, "lstm_bench_group_exchange");
+    else if (f) rc = fail(nullptr, LSTM_ERR_TIMEOUT, "lstm_bench_group_exchange: bounded wait expired");
+    else {
+        *avg_us_per_round = (double)ms * 1000.0 / iters / steps;
+        if (groups_verified) *groups_verified = host_small[1];
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (buf) (void)hipFree(buf);
+    if (small) (void)hipFree(small);
+    return rc;
+}
+
 }  // extern "C"

@@ -470,3 +470,20 @@ def test_expired_waits_are_reported_and_nothing_hangs(monkeypatch):
     for w, fmt, want in families:
         desc, _ = check_case(inputs.make_case(w, 0), fmt, PAUTO)
         assert want in desc
+
+
+def test_group_exchange_yardstick_and_the_one_xcd_check():
+    """The exchange yardstick inside groups: spread over the XCDs, placed on one XCD each (every group must then pass the
+    check made from the hardware's XCD ids), and with workgroup-scope stores on top (what the product kernels do);
+    argument errors for shapes that cannot be placed."""
+    spread, ver0 = B.lstm_bench_group_exchange(1024, 32, 8, False, False, steps=50, iters=2)
+    placed, ver1 = B.lstm_bench_group_exchange(1024, 32, 8, True, False, steps=50, iters=2)
+    local, ver2 = B.lstm_bench_group_exchange(1024, 32, 8, True, True, steps=50, iters=2)
+    assert ver0 == 0 and ver1 == 8 and ver2 == 8
+    assert 0.1 < local < 20 and 0.1 < placed < 20 and 0.1 < spread < 20
+    us, ver = B.lstm_bench_group_exchange(70, 3, 5, True, True, steps=20, iters=1)     # padding block ids, ragged shares
+    assert ver == 5 and us > 0
+    with pytest.raises(B.LstmError):
+        B.lstm_bench_group_exchange(3000, 24, 10, True, True)                              # two groups of 24 per XCD
+    with pytest.raises(B.LstmError):
+        B.lstm_bench_group_exchange(100, 65, 1, False, False)
