@@ -490,7 +490,7 @@ static int pick_waves(int H, int requested, int max_waves, int divisor)
 // per lane, the rest of the kernel about 60; a compute unit gives 512 registers per lane and SIMD.
 constexpr int dense_maxt(int KI, bool fusex)
 {
-    return fusex ? (8 * KI <= 48 ? 1024 : 8 * KI <= 88 ? 768 : 512) : (4 * KI <= 64 ? 1024 : 4 * KI <= 96 ? 768 : 512);
+    return fusex ? (8 * KI <= 56 ? 1024 : 8 * KI <= 88 ? 768 : 512) : (4 * KI <= 64 ? 1024 : 4 * KI <= 96 ? 768 : 512);
 }
 constexpr int kDenseFuseMaxKI = 20;
 constexpr int sparse_maxt(int NZ) { return NZ <= 1 ? 1024 : NZ <= 4 ? 768 : 512; }
