@@ -258,7 +258,10 @@ int lstm_grow_to_lhp(const int* dims, const double* lat, int n, double eps, int 
  * ceil(p_r * M)-th smallest row sum and the ceil(p_c * N)-th smallest column sum, both of the matrix as passed in.
  * Rows at or below the row threshold are removed first (mask bytes and weights set to zero), then the columns whose
  * sum over the matrix as the row pass left it is at or below the column threshold.  A ratio of 0 removes nothing
- * along that axis.  Sums are accumulated in fp32.  *rows_removed / *cols_removed (HOST, may be NULL) receive how many
+ * along that axis.  (Because the column threshold is the one of the matrix as passed in, a call that removes many rows
+ * lowers every column sum against it: on a matrix without structure, removing a fifth of the rows and asking for a fifth
+ * of the columns in the same call removes all columns.  Use one call per axis for independent ratios.)
+ * Sums are accumulated in fp32.  *rows_removed / *cols_removed (HOST, may be NULL) receive how many
  * rows / columns this call zeroed.
  *
  * Both allocate and free their own scratch and synchronise the stream.  The packed form of a model is not touched:

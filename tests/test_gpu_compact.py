@@ -143,3 +143,29 @@ def test_pruned_hlstm_runs_at_its_compacted_dimensions(bidir, layers, H, G, D, T
     ref = restrict_outputs(horc.forward_case(pruned), w, units)
     gpu, desc = run_gpu(small)
     compare(gpu, ref, "f32", f"compacted {w.name} {desc}")
+
+
+@pytest.mark.parametrize("M,N,p,seed", [(320, 200, 0.2, 0), (6000, 400, 0.2, 1), (800, 800, 0.1, 2)])
+def test_row_column_pruning_then_compaction_on_the_device(M, N, p, seed):
+    """The paper's step (b) on one matrix, device end to end: a row pruning iteration and a column pruning iteration
+    with equal ratios (two calls: in one call the column threshold is the one of the matrix as passed in, and after a
+    fifth of the rows has gone every column sum of a random matrix lies below it), then the compaction.  The
+    dimensions shrink by exactly what the pruning removed, and the compacted matrix is the oracle's compaction of the
+    pruned mask."""
+    import torch
+    rng = np.random.default_rng(300 + seed)
+    W = rng.standard_normal((M, N)).astype(np.float32)
+    dev = torch.device("cuda:0")
+    dW = torch.from_numpy(W).to(dev)
+    dm = torch.ones((M, N), dtype=torch.uint8, device=dev)
+    rows, none = B.lstm_prune_rows_cols(dW.data_ptr(), dm.data_ptr(), M, N, p, 0.0)
+    none2, cols = B.lstm_prune_rows_cols(dW.data_ptr(), dm.data_ptr(), M, N, 0.0, p)
+    assert none == 0 and none2 == 0
+    assert rows == int(np.ceil(p * M)) and cols == int(np.ceil(p * N))        # no ties in random data: exactly the ratio
+    Wp, mp = dW.cpu().numpy(), dm.cpu().numpy()
+    got = gpu_compact(Wp, mp, 1)
+    ref = ocompact.compact_rows_cols(Wp, mp, 1)
+    for g, r in zip(got, ref):
+        np.testing.assert_array_equal(g, r)
+    assert got[0].size == M - rows and got[1].size == N - cols
+    assert got[3].all()                                                       # what is left is dense
