@@ -261,7 +261,8 @@ int lstm_grow_to_lhp(const int* dims, const double* lat, int n, double eps, int 
  * along that axis.  (Because the column threshold is the one of the matrix as passed in, a call that removes many rows
  * lowers every column sum against it: on a matrix without structure, removing a fifth of the rows and asking for a fifth
  * of the columns in the same call removes all columns.  Use one call per axis for independent ratios.)
- * Sums are accumulated in fp32.  *rows_removed / *cols_removed (HOST, may be NULL) receive how many
+ * Every sum is accumulated in fp64 in index order (from +0, adding the entries of the row / column one after the
+ * other), and sums are compared as fp64: the result does not depend on the launch shape.  *rows_removed / *cols_removed (HOST, may be NULL) receive how many
  * rows / columns this call zeroed.
  *
  * Both allocate and free their own scratch and synchronise the stream.  The packed form of a model is not touched:
@@ -307,18 +308,21 @@ int lstm_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R
 int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double* avg_us, void* stream);
 
 /*
- * Stand-alone product Y[batch, n] = X[batch, n] . W[n, n]^T with a dense input batch and a square weight matrix of
- * which a fraction `keep` in (0, 1] is kept (paper Section 3, the two matrix-multiplication latency figures: latency
- * against the dimension for dense and sparse operands).  format LSTM_FMT_DENSE_MASKED runs the library's dense
- * projection (zeros stored), LSTM_FMT_ROW_COMPRESSED its row-compressed one (for batch <= 64 and n <= 5120 the
- * kernel that splits a row's kept entries over the lanes; otherwise the transpose of X plus the kernel that puts
- * the input rows on the lanes).  W ~ U(-0.1, 0.1), mask Bernoulli(keep), X ~ N(0,1), all from `seed` with one fixed generator, so
- * both formats see the same operands.  n a multiple of 4.  *avg_us: average over `iters` launches after 3 warm-up
- * launches.  y_host (HOST, [batch, n], may be NULL) receives the product.  Allocates and frees its own device
- * buffers; synchronises the stream.
+ * Stand-alone product Y[batch, n] = X[batch, n] . (W (x) Msk)[n, n]^T with a dense input batch and a square weight
+ * matrix (paper Section 3, the two matrix-multiplication latency figures: latency against the dimension for dense and
+ * sparse operands).  format LSTM_FMT_DENSE_MASKED runs the library's dense projection (+0 stored where Msk = 0),
+ * LSTM_FMT_ROW_COMPRESSED its row-compressed one (for batch <= 64 and n <= 5120 the kernel that splits a row's kept
+ * entries over the lanes; otherwise the transpose of X plus the kernel that puts the input rows on the lanes).
+ * Operands, all HOST, row-major:
+ *   X_host [batch, n], W_host [n, n] fp32, mask_host [n, n] uint8 in {0,1} or NULL for "keep everything"; the mask
+ *   selects (what lies under a zero byte is never read into the product); `keep` and `seed` are then ignored.
+ *   X_host = W_host = mask_host = NULL: W ~ U(-0.1, 0.1), mask Bernoulli(keep), keep in (0, 1], X ~ N(0,1), all from
+ *   `seed` with one fixed generator, so both formats see the same operands.
+ * n a multiple of 4.  *avg_us: average over `iters` launches after 3 warm-up launches.  y_host (HOST, [batch, n],
+ * may be NULL) receives the product.  Allocates and frees its own device buffers; synchronises the stream.
  */
-int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, double* avg_us,
-                      float* y_host, void* stream);
+int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, const float* X_host,
+                      const float* W_host, const uint8_t* mask_host, double* avg_us, float* y_host, void* stream);
 int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream);
 /*
  * The exchange inside groups of workgroups, with no arithmetic (yardstick of the kernels whose workgroups exchange only

@@ -16,7 +16,11 @@ before anything is removed; then rows at or below the row threshold are zeroed (
 whose sum over the matrix as the row loop left it is at or below the column threshold.  k = ceil(p * count);
 k = 0 removes nothing along that axis.
 
-Everything is plain numpy on float64 sums of float32 magnitudes, in index order.
+Sums: each row / column sum is accumulated in float64 in index order, s = (((0 + e_0) + e_1) + ...) + e_last with
+e_k = |w| for an active entry and 0 otherwise (written as an explicit loop below; numpy's own sum is pairwise and
+would round differently).  The paper's algorithm does not give an order; one has to be fixed because a float64 sum
+of thousands of float32 magnitudes is not exact, and the order-statistic comparison that follows decides whole rows
+and columns.
 """
 from __future__ import annotations
 
@@ -42,24 +46,48 @@ def prune_weights(W: np.ndarray, mask: np.ndarray, p_w: float) -> np.ndarray:
     return out
 
 
-def prune_rows_cols(W: np.ndarray, mask: np.ndarray, p_r: float, p_c: float) -> Tuple[np.ndarray, np.ndarray]:
-    """(W, mask) after one row/column pruning iteration."""
-    W = np.array(W, dtype=np.float32, copy=True)
-    mask = np.array(mask, dtype=np.uint8, copy=True)
+def _row_sums_in_index_order(eff: np.ndarray) -> np.ndarray:
+    acc = np.zeros(eff.shape[0], np.float64)
+    for k in range(eff.shape[1]):        # column after column: every row's sum grows by its k-th entry
+        acc = acc + eff[:, k]
+    return acc
+
+
+def _col_sums_in_index_order(eff: np.ndarray) -> np.ndarray:
+    acc = np.zeros(eff.shape[1], np.float64)
+    for r in range(eff.shape[0]):
+        acc = acc + eff[r, :]
+    return acc
+
+
+def prune_rows_cols_lines(W: np.ndarray, mask: np.ndarray, p_r: float, p_c: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Which rows and which columns one row/column pruning iteration removes (two boolean vectors)."""
+    W = np.asarray(W, dtype=np.float32)
+    mask = np.asarray(mask, dtype=np.uint8)
     M, N = W.shape
     eff = np.where(mask == 1, np.abs(W).astype(np.float64), 0.0)
-    row_sum = eff.sum(axis=1)
-    col_sum = eff.sum(axis=0)
+    row_sum = _row_sums_in_index_order(eff)
+    col_sum = _col_sums_in_index_order(eff)
     kr, kc = math.ceil(p_r * M), math.ceil(p_c * N)
-    th_r = np.sort(row_sum)[kr - 1] if kr > 0 else None
-    th_c = np.sort(col_sum)[kc - 1] if kc > 0 else None
-    if th_r is not None:
+    rows = np.zeros(M, bool)
+    cols = np.zeros(N, bool)
+    if kr > 0:
+        th_r = np.sort(row_sum)[kr - 1]
         rows = row_sum <= th_r
-        mask[rows, :] = 0
-        W[rows, :] = 0.0
-    if th_c is not None:
-        eff = np.where(mask == 1, np.abs(W).astype(np.float64), 0.0)
-        cols = eff.sum(axis=0) <= th_c
-        mask[:, cols] = 0
-        W[:, cols] = 0.0
+    if kc > 0:
+        th_c = np.sort(col_sum)[kc - 1]          # threshold of the matrix as passed in
+        eff[rows, :] = 0.0                       # the column loop sees what the row loop left
+        cols = _col_sums_in_index_order(eff) <= th_c
+    return rows, cols
+
+
+def prune_rows_cols(W: np.ndarray, mask: np.ndarray, p_r: float, p_c: float) -> Tuple[np.ndarray, np.ndarray]:
+    """(W, mask) after one row/column pruning iteration: the removed lines are zeroed in both."""
+    W = np.array(W, dtype=np.float32, copy=True)
+    mask = np.array(mask, dtype=np.uint8, copy=True)
+    rows, cols = prune_rows_cols_lines(W, mask, p_r, p_c)
+    mask[rows, :] = 0
+    W[rows, :] = 0.0
+    mask[:, cols] = 0
+    W[:, cols] = 0.0
     return W, mask

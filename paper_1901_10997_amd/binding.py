@@ -99,7 +99,7 @@ def load(build_if_missing: bool = True):
     lib.lstm_compact_rows_cols.restype = ci
     lib.lstm_compact_rows_cols.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, c.POINTER(ci), c.POINTER(ci), vp]
     lib.lstm_bench_matmul.restype = ci
-    lib.lstm_bench_matmul.argtypes = [ci, ci, c.c_double, ci, c.c_uint64, ci, c.POINTER(c.c_double), vp, vp]
+    lib.lstm_bench_matmul.argtypes = [ci, ci, c.c_double, ci, c.c_uint64, ci, vp, vp, vp, c.POINTER(c.c_double), vp, vp]
     lib.lstm_find_lhp.restype = ci
     lib.lstm_find_lhp.argtypes = [vp, vp, ci, c.c_double, vp, c.POINTER(c.c_double)]
     lib.lstm_bench_copy.restype = ci
@@ -313,10 +313,20 @@ def lstm_compact_rows_cols(W_ptr: int, mask_ptr: int, gates: int, R: int, N: int
 
 
 def lstm_bench_matmul(n: int, batch: int, keep: float, fmt: int, seed: int = 1, iters: int = 20, want_product: bool = False,
-                      stream: Optional[int] = None):
+                      stream: Optional[int] = None, X: Optional[np.ndarray] = None, W: Optional[np.ndarray] = None,
+                      mask: Optional[np.ndarray] = None):
+    """X [batch, n], W [n, n] fp32 and mask [n, n] uint8 (host arrays) replace the library's seeded operands when given."""
     us = ctypes.c_double()
     y = np.zeros((batch, n), np.float32) if want_product else None
-    _check(load().lstm_bench_matmul(n, batch, float(keep), fmt, seed, iters, ctypes.byref(us),
+    Xc = None if X is None else np.ascontiguousarray(X, np.float32)
+    Wc = None if W is None else np.ascontiguousarray(W, np.float32)
+    mc = None if mask is None else np.ascontiguousarray(mask, np.uint8)
+    for a, shape in ((Xc, (batch, n)), (Wc, (n, n)), (mc, (n, n))):
+        if a is not None and a.shape != shape:
+            raise ValueError(f"lstm_bench_matmul: operand of shape {a.shape}, expected {shape}")
+    _check(load().lstm_bench_matmul(n, batch, float(keep), fmt, seed, iters,
+                                    None if Xc is None else Xc.ctypes.data, None if Wc is None else Wc.ctypes.data,
+                                    None if mc is None else mc.ctypes.data, ctypes.byref(us),
                                     None if y is None else y.ctypes.data, stream))
     return (us.value, y) if want_product else us.value
 

@@ -383,8 +383,9 @@ hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int nz, in
 size_t prune_state_bytes();
 hipError_t launch_prune_weights(const float* W, uint8_t* mask, size_t count, double p_w, unsigned* keys, void* state,
                                 unsigned long long* counters, hipStream_t s);
-hipError_t launch_prune_rows_cols(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols, float* sums,
-                                  unsigned* keys, void* state_r, void* state_c, int* removed, hipStream_t s);
+size_t prune_rows_cols_scratch_bytes(int M, int N);
+hipError_t launch_prune_rows_cols(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols, void* scratch,
+                                  int** removed_out, hipStream_t s);
 size_t compact_scratch_bytes(int gates, int R, int N);
 hipError_t launch_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R, int N, int* row_index,
                                     int* col_index, float* Wc, uint8_t* mask_c, void* scratch, int** counts_out, hipStream_t s);

@@ -1583,22 +1583,14 @@ int lstm_prune_rows_cols(float* W, uint8_t* mask, int M, int N, double p_r, doub
         return fail(nullptr, LSTM_ERR_ARG, "lstm_prune_rows_cols: bad arguments");
     hipStream_t s = (hipStream_t)stream;
     const unsigned kr = (unsigned)std::min<double>(std::ceil(p_r * M), M), kc = (unsigned)std::min<double>(std::ceil(p_c * N), N);
-    const size_t st_bytes = align256(prune_state_bytes());
-    const size_t big = (size_t)std::max(M, N);
-    float* sums = nullptr;
-    unsigned* keys = nullptr;
-    char* small = nullptr;   // two states | two ints
-    hipError_t e = hipMalloc((void**)&sums, ((size_t)M + N) * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc((void**)&keys, big * sizeof(unsigned));
-    if (e == hipSuccess) e = hipMalloc((void**)&small, 2 * st_bytes + 256);
+    char* scratch = nullptr;
+    int* removed = nullptr;
     int host_removed[2] = {0, 0};
-    if (e == hipSuccess)
-        e = launch_prune_rows_cols(W, mask, M, N, kr, kc, sums, keys, small, small + st_bytes, (int*)(small + 2 * st_bytes), s);
+    hipError_t e = hipMalloc((void**)&scratch, prune_rows_cols_scratch_bytes(M, N));
+    if (e == hipSuccess) e = launch_prune_rows_cols(W, mask, M, N, kr, kc, scratch, &removed, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
-    if (e == hipSuccess) e = hipMemcpy(host_removed, small + 2 * st_bytes, sizeof host_removed, hipMemcpyDeviceToHost);
-    if (sums) (void)hipFree(sums);
-    if (keys) (void)hipFree(keys);
-    if (small) (void)hipFree(small);
+    if (e == hipSuccess) e = hipMemcpy(host_removed, removed, sizeof host_removed, hipMemcpyDeviceToHost);
+    if (scratch) (void)hipFree(scratch);
     if (e != hipSuccess) return fail_hip(nullptr, e, "lstm_prune_rows_cols");
     if (rows_removed) *rows_removed = host_removed[0];
     if (cols_removed) *cols_removed = host_removed[1];
@@ -1626,24 +1618,38 @@ int lstm_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R
     return LSTM_OK;
 }
 
-int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, double* avg_us,
-                      float* y_host, void* stream)
+int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, const float* X_host,
+                      const float* W_host, const uint8_t* mask_host, double* avg_us, float* y_host, void* stream)
 {
-    if (n < 4 || n > 65536 || (n & 3) || batch < 1 || batch > 4096 || !(keep > 0.0) || keep > 1.0 || iters < 1 || !avg_us ||
-        (format != LSTM_FMT_DENSE_MASKED && format != LSTM_FMT_ROW_COMPRESSED))
-        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_matmul: bad arguments (n must be a multiple of 4)");
+    const bool given = X_host || W_host || mask_host;
+    if (n < 4 || n > 65536 || (n & 3) || batch < 1 || batch > 4096 || iters < 1 || !avg_us ||
+        (format != LSTM_FMT_DENSE_MASKED && format != LSTM_FMT_ROW_COMPRESSED) || (given && (!X_host || !W_host)) ||
+        (!given && (!(keep > 0.0) || keep > 1.0)))
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_matmul: bad arguments (n must be a multiple of 4; X and W come together)");
     hipStream_t s = (hipStream_t)stream;
     SplitMix rng{seed};
     const size_t nn = (size_t)n * n;
+    if (mask_host)
+        for (size_t i = 0; i < nn; ++i)
+            if (mask_host[i] > 1) return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_matmul: mask byte not in {0,1}");
     std::vector<float> W(nn), X((size_t)batch * n), bias((size_t)n, 0.0f);
-    for (auto& v : X) v = (float)rng.normal();
+    if (given) std::copy(X_host, X_host + X.size(), X.begin());
+    else for (auto& v : X) v = (float)rng.normal();
     std::vector<int32_t> rp((size_t)n + 1, 0);
     std::vector<uint16_t> col;
     std::vector<float> val;
     for (int r = 0; r < n; ++r) {
         for (int k = 0; k < n; ++k) {
-            const float w = (float)(0.2 * rng.uniform() - 0.1);
-            const bool kept = keep >= 1.0 || rng.uniform() < keep;
+            float w;
+            bool kept;
+            if (given) {
+                // the mask selects: what lies under a zero byte is never read into the product
+                kept = !mask_host || mask_host[(size_t)r * n + k] != 0;
+                w = kept ? W_host[(size_t)r * n + k] : 0.0f;
+            } else {
+                w = (float)(0.2 * rng.uniform() - 0.1);
+                kept = keep >= 1.0 || rng.uniform() < keep;
+            }
             W[(size_t)r * n + k] = kept ? w : 0.0f;
             if (kept && format == LSTM_FMT_ROW_COMPRESSED) { col.push_back((uint16_t)k); val.push_back(w); }
         }

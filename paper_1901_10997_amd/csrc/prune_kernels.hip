@@ -2,11 +2,12 @@
 // "Msk(w) = 0 iff |w| <= the (100 p_w)-th percentile of |W|"; row/column pruning algorithm: rows / columns whose
 // magnitude sum is at or below an order statistic of the row / column sums are removed).
 //
-// Both need a k-th smallest value.  Magnitudes and magnitude sums are non-negative floats, whose bit patterns order
-// like unsigned integers, so the selection is a four-pass radix select on 32-bit keys: each pass histograms one
-// byte of the keys that still match the prefix found so far (LDS histogram per workgroup, then 256 global atomics),
-// and a one-thread kernel walks the 256 bins to fix the next byte of the answer.  Nothing returns to the host
-// between the passes.  Entries that do not take part (mask byte 0) get the key 0xFFFFFFFF, above every magnitude.
+// Both need a k-th smallest value of non-negative floating-point numbers, whose bit patterns order like unsigned
+// integers, so the selection is a byte-wise radix select.  Weight pruning: 32-bit keys (the magnitudes), four passes,
+// each histogramming one byte of the keys that still match the prefix found so far (LDS histogram per workgroup, then
+// 256 global atomics), and a one-thread kernel that walks the 256 bins to fix the next byte of the answer; entries that
+// do not take part (mask byte 0) get the key 0xFFFFFFFF, above every magnitude.  Row/column pruning: 64-bit keys (fp64
+// sums), a few thousand of them, eight passes inside one workgroup.  Nothing returns to the host between the passes.
 #include "common.h"
 
 namespace l355 {
@@ -94,46 +95,146 @@ __global__ void apply_weight_threshold_kernel(const unsigned* __restrict__ keys,
     if ((threadIdx.x & 63) == 0 && cnt) atomicAdd(kept_after, cnt);
 }
 
-// sums[r] = sum_k mask ? |W[r][k]| : 0, one wave per row, lanes over columns, fp32 accumulation
-__global__ __launch_bounds__(256) void row_abs_sum_kernel(const float* __restrict__ W, const uint8_t* __restrict__ mask,
-                                                          int M, int N, float* __restrict__ sums, unsigned* __restrict__ keys)
+// ---- row / column pruning -------------------------------------------------------------------------------------
+// Importance of a line (row or column) = sum of the magnitudes of its active entries, accumulated in fp64 in index
+// order: s = (...((+0 + e_0) + e_1) + ...) + e_last, where e_k = |W| for an active entry and +0 otherwise (adding
+// +0 to a non-negative double changes nothing).  The order is part of the definition: an fp64 sum of several
+// thousand fp32 magnitudes is not exact in general, and the decision "sum <= threshold" must come out the same on
+// every implementation for the masks to be reproducible bit for bit.
+//
+// Both kernels stage tiles in LDS so that the global reads are coalesced whatever the direction of the sum, and one
+// wave then adds a tile's values line by line; the loads of the next tile are in flight meanwhile.
+constexpr int kSumTile = 128;   // positions of a line per tile
+
+// sums[c], 64 columns per workgroup; a wave reads 64 consecutive columns of one row per load
+__global__ __launch_bounds__(256) void col_abs_sum_f64_kernel(const float* __restrict__ W, const uint8_t* __restrict__ mask,
+                                                              int M, int N, double* __restrict__ sums)
 {
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (r >= M) return;
-    float acc = 0.f;
-    for (int k = lane; k < N; k += 64) {
-        const size_t i = (size_t)r * N + k;
-        acc += mask[i] ? fabsf(W[i]) : 0.f;
+    __shared__ float tile[kSumTile][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + lane;
+    const bool col_ok = c < N;
+    float v[kSumTile / 4];
+    auto fetch = [&](int r0) {
+#pragma unroll
+        for (int i = 0; i < kSumTile / 4; ++i) {
+            const int r = r0 + wave + 4 * i;
+            const bool ok = col_ok && r < M;
+            const size_t idx = ok ? (size_t)r * N + c : 0;
+            const float w = W[idx];
+            const uint8_t on = mask[idx];
+            v[i] = (ok && on) ? fabsf(w) : 0.f;
+        }
+    };
+    double acc = 0.0;
+    fetch(0);
+    for (int r0 = 0; r0 < M; r0 += kSumTile) {
+#pragma unroll
+        for (int i = 0; i < kSumTile / 4; ++i) tile[wave + 4 * i][lane] = v[i];
+        __syncthreads();
+        if (r0 + kSumTile < M) fetch(r0 + kSumTile);
+        if (wave == 0) {
+#pragma unroll 16
+            for (int i = 0; i < kSumTile; ++i) acc += (double)tile[i][lane];
+        }
+        __syncthreads();
     }
-    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-    if (lane == 0) {
-        sums[r] = acc;
-        if (keys) keys[r] = __float_as_uint(acc);
+    if (wave == 0 && col_ok) sums[c] = acc;
+}
+
+// sums[r], 64 rows per workgroup; a wave reads 64 consecutive columns of one row per load and parks them transposed
+__global__ __launch_bounds__(256) void row_abs_sum_f64_kernel(const float* __restrict__ W, const uint8_t* __restrict__ mask,
+                                                              int M, int N, double* __restrict__ sums)
+{
+    constexpr int kRowsPerWave = 16, kChunks = kSumTile / 64;
+    __shared__ float tile[kSumTile][65];   // [position][row], odd stride: both the parking and the summing are conflict-free
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rbase = blockIdx.x * 64;
+    float v[kRowsPerWave * kChunks];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i)
+#pragma unroll
+            for (int j = 0; j < kChunks; ++j) {
+                const int r = rbase + wave * kRowsPerWave + i, k = k0 + 64 * j + lane;
+                const bool ok = r < M && k < N;
+                const size_t idx = ok ? (size_t)r * N + k : 0;
+                const float w = W[idx];
+                const uint8_t on = mask[idx];
+                v[i * kChunks + j] = (ok && on) ? fabsf(w) : 0.f;
+            }
+    };
+    double acc = 0.0;
+    fetch(0);
+    for (int k0 = 0; k0 < N; k0 += kSumTile) {
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i)
+#pragma unroll
+            for (int j = 0; j < kChunks; ++j) tile[64 * j + lane][wave * kRowsPerWave + i] = v[i * kChunks + j];
+        __syncthreads();
+        if (k0 + kSumTile < N) fetch(k0 + kSumTile);
+        if (wave == 0) {
+#pragma unroll 16
+            for (int i = 0; i < kSumTile; ++i) acc += (double)tile[i][lane];
+        }
+        __syncthreads();
+    }
+    const int r = rbase + lane;
+    if (wave == 0 && r < M) sums[r] = acc;
+}
+
+struct LineThreshold {
+    double value;   // the k-th smallest sum
+    unsigned any;   // 0: rank 0 was asked for, nothing is removed along this axis
+    unsigned pad;
+};
+
+// k-th smallest (1-based) of n non-negative doubles, whose bit patterns order like 64-bit unsigned integers: eight
+// byte-wide radix passes by one workgroup, histogram in LDS.  n is a row or column count, a few thousand.
+__global__ __launch_bounds__(1024) void select_kth_f64_kernel(const double* __restrict__ sums, int n, unsigned k,
+                                                              LineThreshold* __restrict__ out)
+{
+    __shared__ unsigned hist[256];
+    __shared__ unsigned long long prefix_s;
+    __shared__ unsigned k_s;
+    if (threadIdx.x == 0) { prefix_s = 0ull; k_s = k; }
+    __syncthreads();
+    for (int shift = 56; shift >= 0 && k > 0; shift -= 8) {
+        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+        __syncthreads();
+        const unsigned long long prefix = prefix_s;
+        const unsigned long long high_mask = shift == 56 ? 0ull : (~0ull << (shift + 8));
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            const unsigned long long key = (unsigned long long)__double_as_longlong(sums[i]);
+            if ((key & high_mask) == prefix) atomicAdd(&hist[(unsigned)(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned kk = k_s, cum = 0;
+            int b = 0;
+            for (; b < 255; ++b) {
+                if (cum + hist[b] >= kk) break;
+                cum += hist[b];
+            }
+            prefix_s = prefix | ((unsigned long long)b << shift);
+            k_s = kk - cum;
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        out->value = __longlong_as_double((long long)prefix_s);
+        out->any = k > 0 ? 1u : 0u;
+        out->pad = 0u;
     }
 }
 
-// sums[c] = sum_r mask ? |W[r][c]| : 0, one thread per column (coalesced across a wave), rows in index order
-__global__ void col_abs_sum_kernel(const float* __restrict__ W, const uint8_t* __restrict__ mask, int M, int N,
-                                   float* __restrict__ sums, unsigned* __restrict__ keys)
-{
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= N) return;
-    float acc = 0.f;
-    for (int r = 0; r < M; ++r) {
-        const size_t i = (size_t)r * N + c;
-        acc += mask[i] ? fabsf(W[i]) : 0.f;
-    }
-    sums[c] = acc;
-    if (keys) keys[c] = __float_as_uint(acc);
-}
-
-// rows whose sum is at or below the selected row threshold are removed (mask and weights zeroed)
+// rows whose sum is at or below the row threshold are removed (mask and weights zeroed)
 __global__ void apply_row_threshold_kernel(float* __restrict__ W, uint8_t* __restrict__ mask, int M, int N,
-                                           const float* __restrict__ sums, const SelectState* st, int* __restrict__ removed)
+                                           const double* __restrict__ sums, const LineThreshold* __restrict__ th,
+                                           int* __restrict__ removed)
 {
     const int r = blockIdx.x;
-    if (st->k == 0 || !(__float_as_uint(sums[r]) <= st->prefix)) return;
+    if (th->any == 0 || !(sums[r] <= th->value)) return;
     for (int k = threadIdx.x; k < N; k += blockDim.x) {
         mask[(size_t)r * N + k] = 0;
         W[(size_t)r * N + k] = 0.f;
@@ -141,16 +242,25 @@ __global__ void apply_row_threshold_kernel(float* __restrict__ W, uint8_t* __res
     if (threadIdx.x == 0) atomicAdd(removed, 1);
 }
 
+// columns likewise; lanes over columns, blockIdx.y over row chunks
 __global__ void apply_col_threshold_kernel(float* __restrict__ W, uint8_t* __restrict__ mask, int M, int N,
-                                           const float* __restrict__ sums, const SelectState* st, int* __restrict__ removed)
+                                           const double* __restrict__ sums, const LineThreshold* __restrict__ th,
+                                           int* __restrict__ removed)
 {
     const int c = blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= N || st->k == 0 || !(__float_as_uint(sums[c]) <= st->prefix)) return;
-    for (int r = 0; r < M; ++r) {
+    if (c >= N || th->any == 0 || !(sums[c] <= th->value)) return;
+    const int rows_per = (M + gridDim.y - 1) / gridDim.y;
+    const int r0 = blockIdx.y * rows_per, r1 = min(M, r0 + rows_per);
+    for (int r = r0; r < r1; ++r) {
         mask[(size_t)r * N + c] = 0;
         W[(size_t)r * N + c] = 0.f;
     }
-    atomicAdd(removed, 1);
+    if (blockIdx.y == 0) atomicAdd(removed, 1);
+}
+
+__global__ void clear_removed_kernel(int* removed)
+{
+    if (threadIdx.x < 2) removed[threadIdx.x] = 0;
 }
 
 static int grid_for(size_t n)
@@ -186,28 +296,31 @@ hipError_t launch_prune_weights(const float* W, uint8_t* mask, size_t count, dou
 }
 size_t prune_state_bytes() { return sizeof(SelectState); }
 
-// scratch: sums [max(M,N)] f32, keys [max(M,N)] u32, two states, removed 2 x int
-hipError_t launch_prune_rows_cols(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols, float* sums,
-                                  unsigned* keys, void* state_r, void* state_c, int* removed, hipStream_t s)
+// scratch (prune_rows_cols_scratch_bytes): row sums [M] f64 | column sums [N] f64 | two thresholds | removed 2 x int
+size_t prune_rows_cols_scratch_bytes(int M, int N)
 {
-    SelectState* sr = (SelectState*)state_r;
-    SelectState* sc = (SelectState*)state_c;
-    hipError_t e = launch_fill_u64((unsigned long long*)removed, 1, 0ull, s);   // two ints, 8-byte aligned
-    if (e != hipSuccess) return e;
+    return ((size_t)M + (size_t)N) * sizeof(double) + 2 * sizeof(LineThreshold) + 2 * sizeof(int);
+}
+
+hipError_t launch_prune_rows_cols(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols, void* scratch,
+                                  int** removed_out, hipStream_t s)
+{
+    double* rsums = (double*)scratch;
+    double* csums = rsums + M;
+    LineThreshold* th = (LineThreshold*)(csums + N);
+    int* removed = (int*)(th + 2);
+    if (removed_out) *removed_out = removed;
+    hipLaunchKernelGGL(clear_removed_kernel, dim3(1), dim3(64), 0, s, removed);
     // both thresholds from the matrix as it came in
-    hipLaunchKernelGGL(row_abs_sum_kernel, dim3((M + 3) / 4), dim3(256), 0, s, W, mask, M, N, sums, keys);
-    hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(1), 0, s, sr, (const unsigned long long*)nullptr, 0.0, k_rows);
-    e = radix_select(keys, (size_t)M, sr, s);
-    if (e != hipSuccess) return e;
-    float* csums = sums + M;
-    hipLaunchKernelGGL(col_abs_sum_kernel, dim3((N + 255) / 256), dim3(256), 0, s, W, mask, M, N, csums, keys);
-    hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(1), 0, s, sc, (const unsigned long long*)nullptr, 0.0, k_cols);
-    e = radix_select(keys, (size_t)N, sc, s);
-    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(row_abs_sum_f64_kernel, dim3((M + 63) / 64), dim3(256), 0, s, W, mask, M, N, rsums);
+    hipLaunchKernelGGL(col_abs_sum_f64_kernel, dim3((N + 63) / 64), dim3(256), 0, s, W, mask, M, N, csums);
+    hipLaunchKernelGGL(select_kth_f64_kernel, dim3(1), dim3(1024), 0, s, rsums, M, k_rows, th);
+    hipLaunchKernelGGL(select_kth_f64_kernel, dim3(1), dim3(1024), 0, s, csums, N, k_cols, th + 1);
     // rows first, then columns judged on what the row pass left
-    hipLaunchKernelGGL(apply_row_threshold_kernel, dim3(M), dim3(256), 0, s, W, mask, M, N, sums, sr, removed);
-    hipLaunchKernelGGL(col_abs_sum_kernel, dim3((N + 255) / 256), dim3(256), 0, s, W, mask, M, N, csums, (unsigned*)nullptr);
-    hipLaunchKernelGGL(apply_col_threshold_kernel, dim3((N + 255) / 256), dim3(256), 0, s, W, mask, M, N, csums, sc, removed + 1);
+    hipLaunchKernelGGL(apply_row_threshold_kernel, dim3(M), dim3(256), 0, s, W, mask, M, N, rsums, th, removed);
+    hipLaunchKernelGGL(col_abs_sum_f64_kernel, dim3((N + 63) / 64), dim3(256), 0, s, W, mask, M, N, csums);
+    hipLaunchKernelGGL(apply_col_threshold_kernel, dim3((N + 255) / 256, std::min(64, (M + 63) / 64)), dim3(256), 0, s, W, mask,
+                       M, N, csums, th + 1, removed + 1);
     return hipGetLastError();
 }
 

@@ -250,3 +250,14 @@ def structure_masks(case: Case, unit_frac: float, input_frac: float, k: int = 0,
     if G > 0:
         return out, units, feats, gate_units
     return out, units, feats
+
+
+def matmul_operands(n: int, batch: int, keep: Optional[float], seed: int = 0):
+    """Operands of the stand-alone product of the paper's Section 3 (dense input batch times a square weight matrix
+    of dimension n, of which a fraction `keep` is kept): X [batch, n] ~ N(0,1), W [n, n] ~ U(-0.1, 0.1), mask
+    Bernoulli(keep) as uint8, or None for a dense matrix.  Draw order: W, mask, X."""
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 1000 * 8 + seed))
+    W = rng.uniform(-0.1, 0.1, (n, n)).astype(np.float32)
+    M = None if keep is None else (rng.random((n, n)) < keep).astype(np.uint8)
+    X = rng.standard_normal((batch, n)).astype(np.float32)
+    return X, W, M

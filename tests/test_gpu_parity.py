@@ -388,10 +388,28 @@ def test_c2_random_state():
     check_case(inputs.make_case(inputs.c2(20), 0, random_state=True))
 
 
-@pytest.mark.parametrize("H", [64, 96, 160, 512, 1056, 1284, 1300, 1504, 2048])
+@pytest.mark.parametrize("H", inputs.c3_hidden_sizes() + [1284, 1300, 1900])
 def test_c3_points(H):
-    desc, _ = check_case(inputs.make_case(inputs.c3(H), 0))
-    assert "persist_b1" in desc
+    """Every width of the latency-hysteresis sweep (H = 64..2048 step 32, Section 3) plus three widths off the grid:
+    each width selects its own registers-per-row count, workgroup size, fused or separate input projection and
+    placement, and each of them is compared with the oracle."""
+    desc, _ = check_case(inputs.make_case(inputs.c3(H), 0), cooperative=(H % 64 == 0))
+    assert ("proj=fused-dense,rec=persist_b1-dense" if H <= 1280 else "proj=dense,rec=persist_b1-dense") in desc
+
+
+def test_latency_sweep_entry_point():
+    """lstm_latency_sweep itself (Section 3 profile over the gate dimension): positive, ordered percentiles and
+    hysteresis flags that equal lstm_find_lhp at margin 0 on the returned medians."""
+    Hs = [96, 64, 160]
+    med, p10, p90, flags = B.lstm_latency_sweep(Hs, T=6, B=1, warmup=1, iters=3)
+    assert np.all(med > 0) and np.all(p10 <= med + 1e-9) and np.all(med <= p90 + 1e-9)
+    ref, _ = B.lstm_find_lhp(Hs, med, 0.0)
+    np.testing.assert_array_equal(flags, ref)
+    assert flags[2] == 1                                   # the largest dimension always is one
+    with pytest.raises(B.LstmError):
+        B.lstm_latency_sweep(Hs, T=0, B=1, warmup=0, iters=1)
+    empty = B.lstm_latency_sweep([], T=6, B=1, warmup=0, iters=1)        # no points: a no-op
+    assert all(len(a) == 0 for a in empty)
 
 
 @pytest.mark.slow
@@ -423,18 +441,44 @@ def test_model_level_latency_sweep_runs_every_family():
         B.lstm_latency_sweep_model(Hs, None, gate_hidden=True, dtype=B.LSTM_BF16, warmup=0, iters=1)
 
 
-@pytest.mark.parametrize("n,batch,keep", [(64, 16, 0.5), (260, 16, 0.1), (512, 5, 1.0), (1000, 16, 0.05), (132, 70, 0.3)])
-def test_standalone_product_dense_and_compressed_agree(n, batch, keep):
-    """lstm_bench_matmul: both formats multiply the same seeded operands; the products agree to fp32 summation order
-    and have the scale the operand distributions imply (variance n * keep * E[w^2] * E[x^2] = n * keep / 300)."""
+@pytest.mark.parametrize("n,batch,keep", [(64, 16, 0.5), (260, 16, 0.1), (512, 5, 1.0), (1000, 16, 0.05), (132, 70, 0.3),
+                                          (2048, 16, 0.1), (4096, 16, 0.05), (1500, 16, None), (5124, 3, 0.02)])
+@pytest.mark.parametrize("fmt", [DENSE, CSR])
+def test_standalone_product_against_the_oracle(n, batch, keep, fmt):
+    """lstm_bench_matmul on caller-supplied seeded operands (Section 3, matmul latency figures): the product of either
+    format equals the fp64 oracle's X (W (x) Msk)^T within the fp32 tolerance; what lies under a zero mask byte is
+    invisible to the bits of the result."""
+    from oracle import matmul as omm
+    X, W, M = inputs.matmul_operands(n, batch, keep, seed=n + batch)
+    ref = omm.masked_product(X, W, M)
+    _, y = B.lstm_bench_matmul(n, batch, 1.0, fmt, iters=2, want_product=True, X=X, W=W, mask=M)
+    d = y.astype(np.float64) - ref
+    assert np.max(np.abs(d)) <= 1e-5 and np.linalg.norm(d) / np.linalg.norm(ref) <= 1e-4, (np.max(np.abs(d)),)
+    if M is not None:
+        Wj = W.copy()
+        Wj[M == 0] = np.float32(np.nan)
+        _, y2 = B.lstm_bench_matmul(n, batch, 1.0, fmt, iters=1, want_product=True, X=X, W=Wj, mask=M)
+        assert np.array_equal(y.view(np.uint32), y2.view(np.uint32))
+
+
+def test_standalone_product_seeded_operands_and_errors():
+    """With no operands given the library draws its own from the seed: both formats then multiply the same ones, the
+    seed changes them, and the product has the scale the distributions imply (n * keep * E[w^2] E[x^2] = n keep / 300)."""
+    n, batch, keep = 260, 16, 0.1
     _, yd = B.lstm_bench_matmul(n, batch, keep, DENSE, seed=7, iters=2, want_product=True)
     _, yc = B.lstm_bench_matmul(n, batch, keep, CSR, seed=7, iters=2, want_product=True)
-    assert np.all(np.isfinite(yd))
     np.testing.assert_allclose(yc, yd, rtol=0, atol=2e-5)
     var = float(np.mean(yd.astype(np.float64) ** 2))
     assert 0.6 * n * keep / 300 < var < 1.6 * n * keep / 300
     _, other = B.lstm_bench_matmul(n, batch, keep, DENSE, seed=8, iters=1, want_product=True)
     assert np.max(np.abs(other - yd)) > 1e-3
+    X, W, M = inputs.matmul_operands(64, 4, 0.5, seed=1)
+    with pytest.raises(B.LstmError):
+        B.lstm_bench_matmul(64, 4, 1.0, DENSE, X=X)                       # W missing
+    with pytest.raises(B.LstmError):
+        B.lstm_bench_matmul(64, 4, 1.0, DENSE, X=X, W=W, mask=M * 2)      # mask byte not in {0, 1}
+    with pytest.raises(B.LstmError):
+        B.lstm_bench_matmul(64, 4, 0.0, DENSE)                            # keep outside (0, 1]
 
 
 def test_expired_waits_are_reported_and_nothing_hangs(monkeypatch):

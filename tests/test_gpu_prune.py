@@ -51,30 +51,51 @@ def test_weight_pruning_iterated_reaches_the_papers_sparsity():
 @pytest.mark.parametrize("M,N,pr,pc,keep,seed", [
     (4, 3, 0.25, 1 / 3, 1.0, 0), (12, 9, 0.3, 0.5, 0.8, 1), (257, 130, 0.2, 0.2, 0.6, 2), (64, 64, 0.0, 0.4, 1.0, 3),
     (100, 333, 0.5, 0.0, 0.9, 4), (6000, 1500, 0.2, 0.2, 0.65, 5), (33, 7, 1.0, 0.1, 1.0, 6),
+    (1500, 6000, 0.1, 0.0, 0.5, 7), (129, 257, 0.0, 0.3, 0.4, 8), (1, 1, 1.0, 1.0, 1.0, 9), (65, 129, 0.02, 0.01, 0.2, 10),
 ])
 def test_row_column_pruning_matches_oracle(M, N, pr, pc, keep, seed):
+    """Masks and weights after one iteration equal the oracle's bit for bit: both sides accumulate every row / column
+    sum in fp64 in index order and compare sums as fp64, so there is no line whose decision could differ."""
     rng = np.random.default_rng(40 + seed)
-    W = rng.standard_normal((M, N)).astype(np.float32)
+    # a wide range of magnitudes, so that the fp64 sums are not exact and their order matters
+    W = (rng.standard_normal((M, N)) * np.exp(rng.uniform(-12, 3, (M, N)))).astype(np.float32)
     mask = (rng.random((M, N)) < keep).astype(np.uint8)
+    Wg = W.copy()
+    Wg[mask == 0] = np.float32(np.nan)                                    # never looked at
+    dW, dm = _dev(Wg), _dev(mask)
+    rows, cols = B.lstm_prune_rows_cols(dW.data_ptr(), dm.data_ptr(), M, N, pr, pc)
+    Wr, mr = oprune.prune_rows_cols(Wg, mask, pr, pc)
+    gm, gW = dm.cpu().numpy(), dW.cpu().numpy()
+    np.testing.assert_array_equal(gm, mr)
+    # weights bit for bit: zero on the removed lines, untouched elsewhere (the planted NaNs included)
+    np.testing.assert_array_equal(gW.view(np.uint32), Wr.view(np.uint32))
+    r_ref, c_ref = oprune.prune_rows_cols_lines(Wg, mask, pr, pc)
+    assert rows == int(r_ref.sum()) and cols == int(c_ref.sum())
+    assert rows >= math.ceil(pr * M)
+
+
+@pytest.mark.parametrize("axis", ["rows", "cols"])
+def test_row_column_pruning_takes_every_line_tied_with_the_threshold(axis):
+    """Lines with equal sums go together (the policy removes what is at or below the threshold): three identical lines
+    at the threshold rank all go although the ratio asks for fewer."""
+    rng = np.random.default_rng(77)
+    M, N = 70, 90
+    W = rng.uniform(0.5, 1.5, (M, N)).astype(np.float32)
+    mask = np.ones((M, N), np.uint8)
+    small = rng.uniform(0.01, 0.02, N if axis == "rows" else M).astype(np.float32)
+    if axis == "rows":
+        for r in (3, 40, 69):
+            W[r, :] = small
+        pr, pc = 2 / M, 0.0                 # k = 2, but three rows share the smallest sum
+    else:
+        for c in (0, 64, 89):
+            W[:, c] = small
+        pr, pc = 0.0, 2 / N
     dW, dm = _dev(W), _dev(mask)
     rows, cols = B.lstm_prune_rows_cols(dW.data_ptr(), dm.data_ptr(), M, N, pr, pc)
     Wr, mr = oprune.prune_rows_cols(W, mask, pr, pc)
-    gm, gW = dm.cpu().numpy(), dW.cpu().numpy()
-    # The device sums in fp32, the oracle in fp64: a row / column whose sum lies within 1e-5 (relative) of a threshold
-    # may fall on either side; everything else must agree bit for bit, and what was removed must be whole lines.
-    eff = np.where(mask == 1, np.abs(W).astype(np.float64), 0.0)
-    rs, cs = eff.sum(axis=1), eff.sum(axis=0)
-    kr, kc = math.ceil(pr * M), math.ceil(pc * N)
-    near_r = np.zeros(M, bool) if kr == 0 else np.abs(rs - np.sort(rs)[kr - 1]) <= 1e-5 * np.sort(rs)[kr - 1]
-    sure_rows = ~near_r
-    np.testing.assert_array_equal(gm[sure_rows].any(axis=1) | ~mask[sure_rows].any(axis=1),
-                                  mr[sure_rows].any(axis=1) | ~mask[sure_rows].any(axis=1))
-    if not near_r.any() or kr == 0:
-        eff2 = np.where(mr == 1, np.abs(Wr).astype(np.float64), 0.0).sum(axis=0) if kr > 0 else cs
-        near_c = np.zeros(N, bool) if kc == 0 else np.abs(eff2 - np.sort(cs)[kc - 1]) <= 1e-5 * max(np.sort(cs)[kc - 1], 1e-30)
-        ok = np.ones((M, N), bool); ok[:, near_c] = False
-        np.testing.assert_array_equal(gm[ok], mr[ok])
-        np.testing.assert_array_equal(gW[ok], Wr[ok])
-    assert rows >= kr and cols >= (kc if kr < M else 0)
-    assert np.all(gm <= mask)
-    assert np.all((gW != 0) <= (gm == 1) | (mask == 0))   # removed entries are zeroed
+    np.testing.assert_array_equal(dm.cpu().numpy(), mr)
+    np.testing.assert_array_equal(dW.cpu().numpy().view(np.uint32), Wr.view(np.uint32))
+    assert (rows, cols) == ((3, 0) if axis == "rows" else (0, 3))
+    gone = np.flatnonzero(~mr.any(axis=1)) if axis == "rows" else np.flatnonzero(~mr.any(axis=0))
+    assert list(gone) == ([3, 40, 69] if axis == "rows" else [0, 64, 89])

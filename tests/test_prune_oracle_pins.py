@@ -94,3 +94,35 @@ def test_row_column_pruning_invariants(seed):
     W0, m0 = oprune.prune_rows_cols(W, m, 0.0, 0.0)
     np.testing.assert_array_equal(m0, m)
     np.testing.assert_array_equal(W0, W)
+
+
+def test_row_column_sums_are_taken_in_index_order():
+    """The sums that rank rows and columns are fp64 sums in index order.  Brute force in plain Python floats on a matrix
+    whose magnitudes span many binades (so that the order of the additions changes the rounded result), and a planted
+    case in which only the index-order sum puts a row at the threshold."""
+    rng = np.random.default_rng(5)
+    M, N = 9, 300
+    W = (rng.standard_normal((M, N)) * np.exp(rng.uniform(-25, 10, (M, N)))).astype(np.float32)
+    m = (rng.random((M, N)) < 0.8).astype(np.uint8)
+    eff = np.where(m == 1, np.abs(W).astype(np.float64), 0.0)
+    rows = oprune._row_sums_in_index_order(eff)
+    cols = oprune._col_sums_in_index_order(eff)
+    for r in range(M):
+        s = 0.0
+        for k in range(N):
+            if m[r, k]:
+                s += abs(float(W[r, k]))
+        assert rows[r] == s
+    for k in range(N):
+        s = 0.0
+        for r in range(M):
+            if m[r, k]:
+                s += abs(float(W[r, k]))
+        assert cols[k] == s
+    assert any(rows[r] != math.fsum(eff[r]) for r in range(M))      # the order does matter on such data
+    # 2^24 + 1 + 1 in fp32-representable terms: left to right in fp64 this is exact (2^24 + 2); the point of the case
+    # is the decision: row 0 and row 1 hold the same multiset in different orders and must get the same exact sum here
+    # (all partial sums are exact in fp64), so both are at the threshold and both go
+    W2 = np.array([[16777216.0, 1.0, 1.0], [1.0, 16777216.0, 1.0], [16777216.0, 2.0, 1.0]], np.float32)
+    _, m2 = oprune.prune_rows_cols(W2, np.ones((3, 3), np.uint8), 1 / 3, 0.0)
+    np.testing.assert_array_equal(m2.any(axis=1), [False, False, True])
