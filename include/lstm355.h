@@ -274,6 +274,22 @@ int lstm_prune_rows_cols(float* W, uint8_t* mask, int M, int N, double p_r, doub
                          int* cols_removed, void* stream);
 
 /*
+ * lstm_prune_rows_cols for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid it): the same iteration with the same kernels and the same result, bit for bit, but the
+ * scratch (row and column sums, the two thresholds, two counters) lives in a fixed device array inside the library,
+ * about 256 KiB, which every GPU the library runs on holds until the process ends.  Nothing is allocated or freed, and
+ * the call does not synchronise: it is asynchronous on `stream`.
+ *   W, mask, M, N, p_r, p_c as lstm_prune_rows_cols (DEVICE arrays, updated in place).
+ *   M <= 16384 and N <= 16384, else LSTM_ERR_ARG (the scratch is fixed); M * N is not limited otherwise.
+ *   removed: DEVICE int[2] or NULL; receives the number of rows and of columns this call zeroed, on the stream.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two host threads)
+ * race and give undefined masks; calls on one stream, or ordered by events, are fine, and a call does not depend on
+ * what an earlier one left in the array.  The first call on a device looks up that device's array (no allocation, but
+ * make it outside a graph capture).
+ */
+int lstm_prune_rows_cols_static(float* W, uint8_t* mask, int M, int N, double p_r, double p_c, int* removed, void* stream);
+
+/*
  * Dimension compaction after row/column pruning (paper Section 4, "Row/column growth & pruning": the pruning shrinks
  * the dimensions of the weight matrices; Section 5.1 step (b): each control-gate matrix goes from 1500/400 to
  * 1197/317, Section 5.2 step (b): from 800/800 to 626/626).  All array pointers DEVICE, owned by the caller.

@@ -26,7 +26,7 @@ EXPORTS = [
     "lstm_create", "lstm_create_h", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_set_weights_h",
     "lstm_workspace_bytes",
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
-    "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_prune_weights", "lstm_prune_rows_cols",
+    "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_prune_weights", "lstm_prune_rows_cols", "lstm_prune_rows_cols_static",
     "lstm_compact_rows_cols",
     "lstm_bench_copy", "lstm_bench_matmul", "lstm_bench_exchange", "lstm_bench_group_exchange",
 ]
@@ -96,6 +96,8 @@ def load(build_if_missing: bool = True):
     lib.lstm_prune_weights.argtypes = [vp, vp, c.c_size_t, c.c_double, c.POINTER(c.c_size_t), c.POINTER(c.c_size_t), vp]
     lib.lstm_prune_rows_cols.restype = ci
     lib.lstm_prune_rows_cols.argtypes = [vp, vp, ci, ci, c.c_double, c.c_double, c.POINTER(ci), c.POINTER(ci), vp]
+    lib.lstm_prune_rows_cols_static.restype = ci
+    lib.lstm_prune_rows_cols_static.argtypes = [vp, vp, ci, ci, c.c_double, c.c_double, vp, vp]
     lib.lstm_compact_rows_cols.restype = ci
     lib.lstm_compact_rows_cols.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, c.POINTER(ci), c.POINTER(ci), vp]
     lib.lstm_bench_matmul.restype = ci
@@ -301,6 +303,12 @@ def lstm_prune_rows_cols(W_ptr: int, mask_ptr: int, M: int, N: int, p_r: float, 
     r, cc = ctypes.c_int(), ctypes.c_int()
     _check(load().lstm_prune_rows_cols(W_ptr, mask_ptr, M, N, float(p_r), float(p_c), ctypes.byref(r), ctypes.byref(cc), stream))
     return r.value, cc.value
+
+
+def lstm_prune_rows_cols_static(W_ptr: int, mask_ptr: int, M: int, N: int, p_r: float, p_c: float,
+                                removed_ptr: Optional[int] = None, stream: Optional[int] = None) -> None:
+    """Allocation-free, asynchronous variant; removed_ptr: device int[2] or None."""
+    _check(load().lstm_prune_rows_cols_static(W_ptr, mask_ptr, M, N, float(p_r), float(p_c), removed_ptr, stream))
 
 
 def lstm_compact_rows_cols(W_ptr: int, mask_ptr: int, gates: int, R: int, N: int, row_index_ptr: int, col_index_ptr: int,

@@ -386,6 +386,9 @@ hipError_t launch_prune_weights(const float* W, uint8_t* mask, size_t count, dou
 size_t prune_rows_cols_scratch_bytes(int M, int N);
 hipError_t launch_prune_rows_cols(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols, void* scratch,
                                   int** removed_out, hipStream_t s);
+int prune_rows_cols_static_max_lines();
+hipError_t launch_prune_rows_cols_static(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols,
+                                         int* removed_dev, hipStream_t s);
 size_t compact_scratch_bytes(int gates, int R, int N);
 hipError_t launch_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R, int N, int* row_index,
                                     int* col_index, float* Wc, uint8_t* mask_c, void* scratch, int** counts_out, hipStream_t s);

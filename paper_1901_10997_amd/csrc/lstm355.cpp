@@ -1597,6 +1597,23 @@ int lstm_prune_rows_cols(float* W, uint8_t* mask, int M, int N, double p_r, doub
     return LSTM_OK;
 }
 
+int lstm_prune_rows_cols_static(float* W, uint8_t* mask, int M, int N, double p_r, double p_c, int* removed, void* stream)
+{
+    if (!W || !mask || M < 1 || N < 1 || !(p_r >= 0.0) || p_r > 1.0 || !(p_c >= 0.0) || p_c > 1.0)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_prune_rows_cols_static: bad arguments");
+    const int cap = prune_rows_cols_static_max_lines();
+    if (M > cap || N > cap) {
+        char msg[160];
+        std::snprintf(msg, sizeof msg, "lstm_prune_rows_cols_static: M = %d, N = %d exceed the fixed scratch (at most %d rows and %d columns)",
+                      M, N, cap, cap);
+        return fail(nullptr, LSTM_ERR_ARG, msg);
+    }
+    const unsigned kr = (unsigned)std::min<double>(std::ceil(p_r * M), M), kc = (unsigned)std::min<double>(std::ceil(p_c * N), N);
+    const hipError_t e = launch_prune_rows_cols_static(W, mask, M, N, kr, kc, removed, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "lstm_prune_rows_cols_static");
+    return LSTM_OK;
+}
+
 int lstm_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R, int N, int32_t* row_index, int32_t* col_index,
                            float* Wc, uint8_t* mask_c, int* Rc, int* Nc, void* stream)
 {

@@ -10,6 +10,8 @@
 // sums), a few thousand of them, eight passes inside one workgroup.  Nothing returns to the host between the passes.
 #include "common.h"
 
+#include <mutex>
+
 namespace l355 {
 
 struct SelectState {
@@ -322,6 +324,64 @@ hipError_t launch_prune_rows_cols(float* W, uint8_t* mask, int M, int N, unsigne
     hipLaunchKernelGGL(apply_col_threshold_kernel, dim3((N + 255) / 256, std::min(64, (M + 63) / 64)), dim3(256), 0, s, W, mask,
                        M, N, csums, th + 1, removed + 1);
     return hipGetLastError();
+}
+
+// ---- the same iteration with no allocation: scratch in a file-scope device array ----------------------------------
+// Every device that loads the library holds its own copy of the array, at its own address, until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; the address that call returns for the
+// current device is what the kernels get.
+constexpr int kStaticMaxLines = 16384;   // largest M and largest N accepted
+constexpr size_t kStaticScratchBytes = (size_t)2 * kStaticMaxLines * sizeof(double) + 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+int prune_rows_cols_static_max_lines() { return kStaticMaxLines; }
+
+// address of this device's copy of the array, looked up once per device with that device current
+static hipError_t static_scratch_for_current_device(void** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+__global__ void copy_removed_kernel(const int* __restrict__ removed, int* __restrict__ out)
+{
+    if (threadIdx.x < 2) out[threadIdx.x] = removed[threadIdx.x];
+}
+
+// the caller has checked M, N <= kStaticMaxLines
+hipError_t launch_prune_rows_cols_static(float* W, uint8_t* mask, int M, int N, unsigned k_rows, unsigned k_cols,
+                                         int* removed_dev, hipStream_t s)
+{
+    if (prune_rows_cols_scratch_bytes(M, N) > kStaticScratchBytes) return hipErrorInvalidValue;
+    void* ptr = nullptr;
+    hipError_t e = static_scratch_for_current_device(&ptr);
+    if (e != hipSuccess) return e;
+    int* removed = nullptr;
+    // the launcher clears the two counters with a fill kernel and overwrites every sum and threshold it reads,
+    // so what the previous call left in the array does not matter
+    e = launch_prune_rows_cols(W, mask, M, N, k_rows, k_cols, ptr, &removed, s);
+    if (e != hipSuccess) return e;
+    if (removed_dev) {
+        hipLaunchKernelGGL(copy_removed_kernel, dim3(1), dim3(64), 0, s, removed, removed_dev);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace l355
