@@ -49,8 +49,8 @@ def parse():
     ap.add_argument("--plan", default="auto", choices=["auto", "stepwise", "persistent"])
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--launch", default="ordinary", choices=["ordinary", "cooperative"],
-                    help="launch mode of the persistent kernels (ordinary: residency by grid <= compute units on an "
-                         "otherwise idle device; cooperative: guaranteed by the runtime, slower dispatch)")
+                    help="launch mode of the persistent kernels (ordinary, the library's default: residency by grid <= "
+                         "compute units; cooperative: guaranteed by the runtime, slower dispatch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep-fine", action="store_true",
                     help="fine-grained batch-1 latency profile around the register-tier boundaries (writes "
@@ -65,8 +65,11 @@ def parse():
                     help="the exchange inside groups of workgroups with no arithmetic: groups dealt over all XCDs, groups "
                          "placed on one XCD each, and those with workgroup-scope stores (writes exchange_groups.json "
                          "into --out)")
-    ap.add_argument("--compare-launch-modes", action="store_true", help="also time the loop in the other launch mode")
-    ap.add_argument("--sweep", action="store_true", help="also run the hidden-size latency sweep (written to --out)")
+    ap.add_argument("--no-compare-launch-modes", action="store_true", help="do not time the loop in the other launch mode")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the 63-point hidden-size latency sweep (on by default for the default workload)")
+    ap.add_argument("--sweep", action="store_true", help="run the hidden-size latency sweep for a non-default workload too")
+    ap.add_argument("--no-yardsticks", action="store_true", help="skip the achievable-peak yardsticks and the cold-weights figure")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run the 1 GiB device copy kernel (known traffic, for scaling profiler byte counters)")
     ap.add_argument("--out", default=os.path.join(ROOT, "bench_out"))
@@ -137,8 +140,32 @@ def main():
     us_per_seq = ms_per_step * 1e3 / Bn
     plan_desc = B.lstm_describe_plan(m.handle)
 
+    # distribution over single forwards: each bracketed by its own event pair on the stream the library launches on
+    # (torch's current stream), and, separately, host wall-clock of forward + synchronise (what a caller waits for)
+    def percentiles(v):
+        v = sorted(v)
+        pick = lambda q: v[min(len(v) - 1, int(q * len(v)))]
+        return {"median": pick(0.5), "p10": pick(0.1), "p90": pick(0.9), "n": len(v)}
+
+    n_dist = max(20, min(200, args.steps))
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_dist)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize(dev)
+    B.lstm_check(m.handle)
+    dist_events = percentiles([e0.elapsed_time(e1) * 1e3 / Bn for e0, e1 in evs])
+    walls = []
+    for _ in range(n_dist):
+        t1 = time.perf_counter()
+        step()
+        torch.cuda.synchronize(dev)
+        walls.append((time.perf_counter() - t1) * 1e6 / Bn)
+    dist_wall = percentiles(walls)
+
     other_mode = None
-    if args.compare_launch_modes:
+    if not args.no_compare_launch_modes and "persist" in plan_desc:
         other = "cooperative" if args.launch == "ordinary" else "ordinary"
         B.lstm_set_launch_mode(m.handle, other == "cooperative")
         for _ in range(min(args.warmup, 5)):
@@ -216,22 +243,70 @@ def main():
                 "traffic": counter_traffic_bytes(wl.name) if (args.format == "auto" and args.plan == "auto") else None,
                 "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_us": rec_us,
                 "launches_per_forward": rec_launches_per_fwd, "proj_avg_launch_us": proj_us}
+    coop = args.launch == "cooperative"
     if persistent and Bn == 1:
-        # latency criterion of the on-chip-resident plan: time per sequential step against the bare exchange of
-        # the same number of hidden values between the same number of workgroups
+        # latency criterion of the on-chip-resident plan: time per sequential step against (a) a device-wide barrier
+        # of the same grid that carries no data (one tagged slot per workgroup) and (b) the bare exchange of the same
+        # number of hidden values between the same number of workgroups
         try:
             slots = H * layers_per_launch
-            ex_us = B.lstm_bench_exchange(slots, 12 if wavefront else 0, 200, 5, stream, args.launch == "cooperative")
+            waves = 12 if wavefront else 0
+            ex_us = B.lstm_bench_exchange(slots, waves, 200, 5, stream, coop)
             if hl:   # a step of the H-LSTM kernel has two exchanges (h: H values; hidden activations: 4G values);
                 ex_us *= 2.0   # the yardstick counts both at the size of the smaller one, i.e. it is a lower bound
+            ncu = torch.cuda.get_device_properties(dev).multi_processor_count
+            wpg = waves if waves else 16
+            groups = min(ncu, 256, (slots + wpg - 1) // wpg)
+            bar_us = B.lstm_bench_barrier(groups, wpg, 200, 5, coop, stream) * (2.0 if hl else 1.0)
             steps_seq = T + layers_per_launch - 1
             roofline["sequential_steps_per_launch"] = steps_seq
             roofline["step_us"] = rec_us / steps_seq
+            roofline["barrier_only_step_us"] = bar_us
+            roofline["barrier_workgroups"] = groups
+            roofline["step_over_barrier"] = (rec_us / steps_seq) / bar_us if bar_us > 0 else None
             roofline["exchange_only_step_us"] = ex_us
             roofline["step_over_exchange"] = (rec_us / steps_seq) / ex_us if ex_us > 0 else None
         except B.LstmError as e:
             roofline["exchange_only_step_us"] = None
             roofline["exchange_error"] = str(e)
+    # input projection on the matrix cores (the contraction of the large-batch workloads): flops of all projection
+    # launches of a forward over their summed duration, against the spec-sheet peak of the operand type
+    proj = None
+    if prof["proj_launches"] > 0 and T * Bn >= 256:
+        flops = sum(2.0 * T * Bn * wl.layer_input_dim(l) * (4 * (G if hl else H)) for (l, d) in keys)
+        per_fwd_us = prof["proj_us"] / max(args.steps, 1)
+        tf = flops / (per_fwd_us * 1e-6) / 1e12
+        peak = 2500.0 if dtype == B.LSTM_BF16 else 157.3
+        proj = {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
+                "flops_per_forward": flops, "us_per_forward": per_fwd_us, "launches_per_forward": prof["proj_launches"] // max(args.steps, 1)}
+    measured = None
+    cold = None
+    if not args.no_yardsticks:
+        # achievable peaks measured in this run, next to the spec-sheet ones
+        nbytes = 1 << 29
+        src = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        copy_us = B.lstm_bench_copy(dst.data_ptr(), src.data_ptr(), nbytes, 5, stream)
+        measured = {"copy_GBps": 2 * nbytes / copy_us / 1e3, "copy_bytes_each_way": nbytes,
+                    "mfma_bf16_TFLOPs": B.lstm_bench_mfma(B.LSTM_BF16, 20000, 3, stream),
+                    "mfma_f32_TFLOPs": B.lstm_bench_mfma(B.LSTM_F32, 5000, 3, stream)}
+        roofline["frac_of_measured_copy"] = achieved / measured["copy_GBps"]
+        if proj:
+            proj["measured_peak"] = measured["mfma_bf16_TFLOPs" if dtype == B.LSTM_BF16 else "mfma_f32_TFLOPs"]
+            proj["frac_of_measured"] = proj["achieved"] / proj["measured_peak"]
+        # cold weights: one forward right after a 2 x 512 MiB device copy has swept the caches
+        colds = []
+        for _ in range(5):
+            B.lstm_bench_copy(dst.data_ptr(), src.data_ptr(), nbytes, 1, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            step()
+            e1.record()
+            torch.cuda.synchronize(dev)
+            colds.append(e0.elapsed_time(e1) * 1e3 / Bn)
+        cold = {"median_us_per_seq": sorted(colds)[len(colds) // 2], "min": min(colds), "max": max(colds), "n": len(colds),
+                "swept_bytes": 2 * nbytes}
+        del src, dst
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -246,13 +321,26 @@ def main():
         if wl.cid in (4, 7):
             Tc = 30
             sub = dataclasses.replace(sub, x=sub.x[:Tc].copy())
+        oracle_forward = (hlstm_oracle if hl else lstm_oracle).forward_case
+        nthreads = lstm_oracle.max_threads()
         t1 = time.perf_counter()
-        (hlstm_oracle if hl else lstm_oracle).forward_case(sub)
+        oracle_forward(sub, nthreads)
         cpu_s = time.perf_counter() - t1
         cpu_us_per_seq = cpu_s * 1e6 / nseq * (T / Tc)
-        cpu = {"value": cpu_us_per_seq, "unit": "us/seq", "cores": lstm_oracle.max_threads(), "kind": "oracle",
+        # one thread: fewer sequences and, for the long workloads, fewer steps (cost is linear in both)
+        n1 = max(1, nseq // 8)
+        sub1 = inputs.select_batch(sub, list(range(n1)))
+        T1 = min(Tc, 8) if wl.cid in (4, 5, 7) else Tc
+        sub1 = dataclasses.replace(sub1, x=sub1.x[:T1].copy())
+        t1 = time.perf_counter()
+        oracle_forward(sub1, 1)
+        cpu1_s = time.perf_counter() - t1
+        cpu = {"value": cpu_us_per_seq, "unit": "us/seq", "cores": nthreads, "kind": "oracle",
                "sample": f"{nseq} sequence(s) of the same workload, T={Tc} of {T}" + (" (scaled linearly in T)" if Tc != T else ""),
-               "wall_s": cpu_s}
+               "wall_s": cpu_s, "nproc": os.cpu_count(),
+               "one_thread": {"value": cpu1_s * 1e6 / n1 * (T / T1), "unit": "us/seq", "cores": 1,
+                              "sample": f"{n1} sequence(s), T={T1} of {T}" + (" (scaled linearly in T)" if T1 != T else ""),
+                              "wall_s": cpu1_s}}
 
     out = {
         "metric": "lstm_fwd_latency_us_per_seq", "value": us_per_seq, "unit": "us/seq", "n_gpus": 1,
@@ -261,10 +349,12 @@ def main():
         "config": {"workload": wl.name, "layers": wl.layers, "bidirectional": wl.bidirectional, "input_dim": wl.input_dim,
                    "hidden": H, "gate_hidden": wl.gate_hidden, "T": T, "batch": Bn, "mask_keep": wl.keep, "format": args.format, "plan": plan_desc, "launch": args.launch},
         "us_per_seq_other_launch_mode": other_mode,
+        "us_per_seq_single_forward_events": dist_events, "us_per_seq_single_forward_host_wall": dist_wall,
+        "us_per_seq_cold_weights": cold,
         "timestep_batch_per_s": T * Bn / (ms_per_step * 1e-3),
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "projection": proj, "measured_peaks": measured, "cpu_baseline": cpu,
     }
-    if args.sweep:
+    if (args.workload == "c2_b1" and not args.no_sweep) or args.sweep:
         os.makedirs(args.out, exist_ok=True)
         Hs = inputs.c3_hidden_sizes()
         B.lstm_set_default_launch_mode(args.launch == "cooperative")
@@ -275,7 +365,11 @@ def main():
             json.dump({"launch": args.launch, "T": 35, "batch": 1, "H": Hs, "median_us": list(med), "p10_us": list(p10), "p90_us": list(p90),
                        "is_lhp_eps0": [int(v) for v in f0], "is_lhp_eps2pct": [int(v) for v in f2],
                        "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2}, fh)
-        out["sweep"] = {"points": len(Hs), "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2,
+        out["sweep"] = {"workload": "c3: 1 layer, input_dim = H, T=35, batch 1, fp32, dense", "launch": args.launch,
+                        "points": len(Hs), "H": Hs, "median_us": [round(float(v), 2) for v in med],
+                        "p10_us": [round(float(v), 2) for v in p10], "p90_us": [round(float(v), 2) for v in p90],
+                        "lhp_eps0": [h for h, f in zip(Hs, f0) if f], "lhp_eps2pct": [h for h, f in zip(Hs, f2) if f],
+                        "redundancy_pct_eps0": red0, "redundancy_pct_eps2pct": red2,
                         "min_us": float(min(med)), "max_us": float(max(med))}
     if args.sweep_fine:
         # batch 1, dense, step 4 around the tier boundaries of the fused persistent kernel, plus the language-model

@@ -161,12 +161,21 @@ int lstm_check(lstm_t* m);
 int lstm_set_plan(lstm_t* m, int plan, int waves_per_group);
 
 /*
- * How the persistent kernels are launched.  cooperative = 1 (default): hipLaunchCooperativeKernel, which
- * guarantees that every workgroup is resident (the hidden-state exchange needs all of them to make progress)
- * at the price of a slower dispatch.  cooperative = 0: an ordinary launch; residency then rests on the grid
- * never exceeding one workgroup per compute unit AND on the device not being shared with other kernels at
- * that moment.  If that assumption is violated the bounded waits expire and lstm_check reports
- * LSTM_ERR_TIMEOUT; nothing hangs.
+ * How the persistent kernels are launched.  Their workgroups exchange the hidden state among themselves, so all of
+ * them must be resident for any of them to make progress.
+ * cooperative = 0 (default): an ordinary launch.  The grid never exceeds one workgroup per compute unit, so every
+ * workgroup is resident as soon as the device has room for it; on a device that runs nothing else at that moment
+ * that is at once.  If other kernels hold compute units, the workgroups that are already running poll until the
+ * others have started; every wait is bounded (2^22 polls, a few seconds; LSTM355_SPIN_LIMIT in the environment at
+ * lstm_create overrides the count), and if a bound expires the kernel drains and lstm_check reports LSTM_ERR_TIMEOUT
+ * (the outputs of that forward are invalid); nothing hangs.  Callers that share the device with long-running kernels
+ * should call lstm_check after synchronising, or choose the cooperative mode.
+ * cooperative = 1: hipLaunchCooperativeKernel, with which the runtime guarantees the residency, at the price of a
+ * slower dispatch (about 18 microseconds per launch measured on MI355X).
+ *
+ * Environment read at lstm_create: LSTM355_L2_HANDOVER=0 makes every exchange store device-scope (the hand-over of the
+ * hidden state through the L2 of one XCD, used where a group of workgroups has been verified to share an XCD, is
+ * switched off; results are bit-identical, only slower; for A/B checks).
  */
 int lstm_set_launch_mode(lstm_t* m, int cooperative);
 /* Process-wide default that lstm_create gives to new handles (including those lstm_latency_sweep creates). */
@@ -317,10 +326,9 @@ int lstm_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R
                            int32_t* col_index, float* Wc, uint8_t* mask_c, int* Rc, int* Nc, void* stream);
 
 /* Measurement helpers (used by the benchmark to quote achievable peaks next to spec-sheet ones).
- * copy: device-to-device copy kernel of `bytes` bytes, `iters` times, returns the average microseconds.
- * barrier: `steps` rounds of the hidden-state exchange with no arithmetic, for `hidden` units and `groups`
- * workgroups of `waves` waves (launched cooperatively or not, see lstm_set_launch_mode); returns the average
- * microseconds per round.  DEVICE pointers where named. */
+ * copy: device-to-device streaming copy of `bytes` bytes (a multiple of 16), `iters` times after one warm-up; 16-byte
+ * loads, four in flight per thread, eight workgroups per compute unit, non-temporal stores.  *avg_us (HOST): average
+ * microseconds per copy; bandwidth = 2 * bytes / time.  DEVICE pointers dst, src. */
 int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double* avg_us, void* stream);
 
 /*
@@ -339,6 +347,25 @@ int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double*
  */
 int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, const float* X_host,
                       const float* W_host, const uint8_t* mask_host, double* avg_us, float* y_host, void* stream);
+/*
+ * Matrix-instruction issue loop: every wave of two four-wave workgroups per compute unit issues `reps` rounds of four
+ * independent matrix instructions (dtype LSTM_BF16: 32x32x16 bf16, LSTM_F32: 32x32x2 fp32) on operands and
+ * accumulators it holds in registers, so nothing but the matrix pipes limits it: the achievable peak that the
+ * projection kernels' rates are quoted against, next to the spec-sheet one.  *tflops (HOST): 10^12 operations per
+ * second over `iters` launches after one warm-up.  Allocates a small sink buffer; synchronises the stream.
+ */
+int lstm_bench_mfma(int dtype, int reps, int iters, double* tflops, void* stream);
+/*
+ * Device-wide barrier with no data: `workgroups` (<= compute units, <= 256) workgroups of `waves` waves; in each of
+ * `steps` rounds every workgroup raises one tagged 8-byte slot and waits until it has seen the slots of all of them
+ * (the protocol of the recurrence kernels' exchange, carrying nothing).  The yardstick "same grid, T barriers, no
+ * work" for the step time of the persistent kernels.  *avg_us_per_step (HOST).  Allocates its own buffers and
+ * synchronises the stream; LSTM_ERR_TIMEOUT if a bounded wait expired.
+ */
+int lstm_bench_barrier(int workgroups, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream);
+/* exchange: `steps` rounds of the hidden-state exchange with no arithmetic, for `hidden` units (one tagged slot each,
+ * all of them polled by every workgroup) and workgroups of `waves` waves (0: the library's choice); returns the
+ * average microseconds per round. */
 int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream);
 /*
  * The exchange inside groups of workgroups, with no arithmetic (yardstick of the kernels whose workgroups exchange only

@@ -28,7 +28,7 @@ EXPORTS = [
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
     "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_prune_weights", "lstm_prune_rows_cols", "lstm_prune_rows_cols_static",
     "lstm_compact_rows_cols",
-    "lstm_bench_copy", "lstm_bench_matmul", "lstm_bench_exchange", "lstm_bench_group_exchange",
+    "lstm_bench_copy", "lstm_bench_matmul", "lstm_bench_mfma", "lstm_bench_barrier", "lstm_bench_exchange", "lstm_bench_group_exchange",
 ]
 
 _lib = None
@@ -100,6 +100,10 @@ def load(build_if_missing: bool = True):
     lib.lstm_prune_rows_cols_static.argtypes = [vp, vp, ci, ci, c.c_double, c.c_double, vp, vp]
     lib.lstm_compact_rows_cols.restype = ci
     lib.lstm_compact_rows_cols.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, c.POINTER(ci), c.POINTER(ci), vp]
+    lib.lstm_bench_mfma.restype = ci
+    lib.lstm_bench_mfma.argtypes = [ci, ci, ci, c.POINTER(c.c_double), vp]
+    lib.lstm_bench_barrier.restype = ci
+    lib.lstm_bench_barrier.argtypes = [ci, ci, ci, ci, ci, c.POINTER(c.c_double), vp]
     lib.lstm_bench_matmul.restype = ci
     lib.lstm_bench_matmul.argtypes = [ci, ci, c.c_double, ci, c.c_uint64, ci, vp, vp, vp, c.POINTER(c.c_double), vp, vp]
     lib.lstm_find_lhp.restype = ci
@@ -337,6 +341,21 @@ def lstm_bench_matmul(n: int, batch: int, keep: float, fmt: int, seed: int = 1, 
                                     None if mc is None else mc.ctypes.data, ctypes.byref(us),
                                     None if y is None else y.ctypes.data, stream))
     return (us.value, y) if want_product else us.value
+
+
+def lstm_bench_mfma(dtype: int, reps: int = 20000, iters: int = 3, stream: Optional[int] = None) -> float:
+    """Matrix-instruction issue rate in TFLOP/s (operands in registers)."""
+    t = ctypes.c_double()
+    _check(load().lstm_bench_mfma(dtype, reps, iters, ctypes.byref(t), stream))
+    return t.value
+
+
+def lstm_bench_barrier(workgroups: int, waves: int, steps: int = 200, iters: int = 5, cooperative: bool = True,
+                       stream: Optional[int] = None) -> float:
+    """Microseconds per round of a device-wide barrier that carries no data."""
+    us = ctypes.c_double()
+    _check(load().lstm_bench_barrier(workgroups, waves, steps, iters, int(bool(cooperative)), ctypes.byref(us), stream))
+    return us.value
 
 
 def lstm_bench_group_exchange(slots: int, members: int, groups: int, placed: bool, workgroup_stores: bool, steps: int = 200,

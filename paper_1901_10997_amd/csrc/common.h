@@ -214,6 +214,7 @@ struct PersistMfmaArgs {
     unsigned* flags;           // one per tile, [ceil(B/64)][4H/64]; every value below tag_base + 1
     unsigned long long* xcc_ids;  // [row blocks][64] tagged slots for the XCD ids of the tiles' workgroups, or nullptr
     int xcd_local;             // block ids grouped by XCD (set by the launcher)
+    int device_scope_only;     // 1: publish with device-scope stores even where the group shares an XCD (A/B switch)
     unsigned tag_base;         // step s publishes tag_base + s + 1
     int* timeout_flag;
     unsigned spin_limit;
@@ -256,6 +257,7 @@ struct PersistB1Args {
     unsigned long long* xchg;  // [2][H] (value, tag) slots, library-owned
     unsigned long long* xcc_ids;  // [64] tagged slots for the XCD ids of the workgroups, library-owned
     int one_xcd;               // every workgroup on one XCD: only block ids = 0 mod 8 work (filled by the launcher)
+    int device_scope_only;     // 1: publish with device-scope stores even on one XCD (A/B switch)
     unsigned tag_base;         // tags tag_base+1 .. tag_base+T are used by this launch
     int* timeout_flag;         // set to 1 if a bounded wait expired
     unsigned spin_limit;
@@ -326,6 +328,7 @@ struct PersistBatchedArgs {
     int T, B, H;
     int ug, bg;                // unit groups / batch groups per direction (filled by the launcher)
     int ndir, xcd_local;       // directions in the grid; block ids grouped by XCD (filled by the launcher)
+    int device_scope_only;     // 1: publish with device-scope stores even where a group shares an XCD (A/B switch)
     int round_h_bf16;
     unsigned long long* xchg;  // [ndir][2][B][H] slots, zero or older tags only
     unsigned long long* xcc_ids;  // [ndir * bg][64] tagged slots (XCD id of each unit group's workgroup), zero or older tags only
@@ -367,6 +370,7 @@ struct PersistBatchedHArgs {
     int T, B, H, G;
     int ug, bg;                 // unit groups / batch groups per direction (filled by the launcher)
     int ndir, xcd_local;        // directions in the grid; block ids grouped by XCD (filled by the launcher)
+    int device_scope_only;      // 1: publish with device-scope stores even where a group shares an XCD (A/B switch)
     size_t h_stride, u_stride;  // elements per (direction, batch group) in xchg_h / xchg_u (filled by the launcher)
     unsigned long long* xchg_h; // tagged slots, zero or older tags only
     float* xchg_u;              // plain values
@@ -393,6 +397,12 @@ size_t compact_scratch_bytes(int gates, int R, int N);
 hipError_t launch_compact_rows_cols(const float* W, const uint8_t* mask, int gates, int R, int N, int* row_index,
                                     int* col_index, float* Wc, uint8_t* mask_c, void* scratch, int** counts_out, hipStream_t s);
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
+// yardsticks
+hipError_t launch_copy_stream(void* dst, const void* src, size_t bytes, hipStream_t s);
+hipError_t launch_mfma_issue(bool bf16, float* sink, int reps, double* flops, hipStream_t s);
+size_t mfma_issue_sink_floats();
+hipError_t launch_barrier_only(unsigned long long* slots, unsigned tag_base, int groups, int waves, int steps,
+                               int* timeout_flag, unsigned spin_limit, int cooperative, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_exchange_only(unsigned long long* xchg, unsigned tag_base, int H, int waves, int steps,

@@ -25,9 +25,10 @@ struct lstm355 {
     unsigned tag_base = 0;               // tags <= tag_base have been used
     int* timeout_flag = nullptr;         // device int
     unsigned spin_limit = 1u << 22;
+    int device_scope_only = 0;           // 1: no hand-over through an XCD's L2 (environment LSTM355_L2_HANDOVER=0)
     int plan = LSTM_PLAN_AUTO;
     int waves_per_group = 0;
-    int cooperative = 1;
+    int cooperative = 0;
     // set for the duration of a forward whose stream is being captured into a graph
     bool capturing = false;
     bool cap_cleared = false;            // the batch-1 exchange slots have been cleared inside this capture
@@ -42,7 +43,7 @@ struct lstm355 {
 };
 
 static thread_local std::string g_create_error;
-static int g_default_cooperative = 1;
+static int g_default_cooperative = 0;   // ordinary launches (see lstm_set_launch_mode in the header)
 
 static int fail(const lstm_t* m, int code, const std::string& msg)
 {
@@ -304,6 +305,7 @@ static int create_model(int layers, int input_dim, int hidden_dim, int gate_hidd
         const long v = std::atol(sl);
         if (v > 0) m->spin_limit = (unsigned)v;
     }
+    if (const char* l2 = std::getenv("LSTM355_L2_HANDOVER")) m->device_scope_only = (std::atoi(l2) == 0) ? 1 : 0;
     hipError_t e = hipGetDevice(&m->device);
     // two cells (directions, or two stacked layers) x two parities; H-LSTM: h slots, then the 4G hidden-layer slots
     const size_t slots = (m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H) + 64;   // + XCD ids of a launch's workgroups
@@ -751,7 +753,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 }
                 a.T = T; a.B = B; a.H = H; a.G = G;
                 a.xchg_h = hslots; a.xchg_u = U[0]; a.flags = hflags; a.xcc_ids = hxcc;
-                a.tag_base = htag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                a.tag_base = htag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 htag += (unsigned)T + 1u;
                 ProfSpan span(m, s, 1);
                 HIP_TRY(m, launch_persist_batched_h(a, Dn, nz, m->launch_mode(), s));
@@ -1073,7 +1075,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 a.xcc_ids = (unsigned long long*)(mflags + persist_mfma_ids_offset(B, H));
                 a.tag_base = mtag;
                 a.timeout_flag = m->timeout_flag;
-                a.spin_limit = m->spin_limit;
+                a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 a.T = T; a.B = B; a.H = H; a.reverse = d;
                 mtag += (unsigned)T;
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=dense,rec=persist-mfma-bf16;", l, d);
@@ -1187,7 +1189,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     m->last_plan += tag;
                 }
                 a.T = T; a.B = B; a.H = H; a.round_h_bf16 = bf16;
-                a.xchg = bslots; a.xcc_ids = bslots + (size_t)Dn * 2 * B * H; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                a.xchg = bslots; a.xcc_ids = bslots + (size_t)Dn * 2 * B * H; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 btag += (unsigned)T;
                 ProfSpan span(m, s, 1);
                 HIP_TRY(m, launch_persist_batched(a, Dn, nzmax, m->launch_mode(), s));
@@ -1285,7 +1287,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 a.hT = hTn; a.cT = cTn;
                 a.T = T; a.H = H; a.reverse = d; a.round_h_bf16 = bf16;
                 a.xchg = m->xchg + (size_t)d * 2 * H; a.xcc_ids = m->xchg + (size_t)4 * H; a.tag_base = tag0;
-                a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 HIP_TRY(m, launch_persist_b1_dense(a, m->waves_per_group, m->launch_mode(), s));
             } else {
                 const size_t state_bytes = (size_t)B * H * sizeof(float);
@@ -1744,9 +1746,9 @@ int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double*
     hipEvent_t e0, e1;
     HIP_TRY(nullptr, hipEventCreate(&e0));
     HIP_TRY(nullptr, hipEventCreate(&e1));
-    HIP_TRY(nullptr, launch_copy(dst, src, bytes, s));
+    HIP_TRY(nullptr, launch_copy_stream(dst, src, bytes, s));
     HIP_TRY(nullptr, hipEventRecord(e0, s));
-    for (int i = 0; i < iters; ++i) HIP_TRY(nullptr, launch_copy(dst, src, bytes, s));
+    for (int i = 0; i < iters; ++i) HIP_TRY(nullptr, launch_copy_stream(dst, src, bytes, s));
     HIP_TRY(nullptr, hipEventRecord(e1, s));
     HIP_TRY(nullptr, hipEventSynchronize(e1));
     float ms = 0.f;
@@ -1755,6 +1757,73 @@ int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double*
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     return LSTM_OK;
+}
+
+int lstm_bench_mfma(int dtype, int reps, int iters, double* tflops, void* stream)
+{
+    if ((dtype != LSTM_F32 && dtype != LSTM_BF16) || reps < 1 || iters < 1 || !tflops)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_mfma: bad arguments");
+    hipStream_t s = (hipStream_t)stream;
+    float* sink = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    double flops = 0.0;
+    hipError_t e = hipMalloc((void**)&sink, mfma_issue_sink_floats() * sizeof(float));
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess) e = launch_mfma_issue(dtype == LSTM_BF16, sink, reps, &flops, s);      // warm-up
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_mfma_issue(dtype == LSTM_BF16, sink, reps, &flops, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (sink) (void)hipFree(sink);
+    if (e != hipSuccess) return fail_hip(nullptr, e, "lstm_bench_mfma");
+    *tflops = flops * iters / ((double)ms * 1e-3) / 1e12;
+    return LSTM_OK;
+}
+
+int lstm_bench_barrier(int workgroups, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream)
+{
+    if (workgroups < 1 || workgroups > 256 || workgroups > device_num_cus() || waves < 1 || waves > 16 || steps < 2 ||
+        iters < 1 || !avg_us_per_step)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_barrier: bad arguments");
+    hipStream_t s = (hipStream_t)stream;
+    unsigned long long* slots = nullptr;
+    int* flag = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipMalloc((void**)&slots, (size_t)2 * workgroups * 8);
+    if (e == hipSuccess) e = hipMemset(slots, 0, (size_t)2 * workgroups * 8);
+    if (e == hipSuccess) e = hipMalloc((void**)&flag, 4);
+    if (e == hipSuccess) e = hipMemset(flag, 0, 4);
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    unsigned tag = 0;
+    auto run = [&]() {
+        const hipError_t r = launch_barrier_only(slots, tag, workgroups, waves, steps, flag, 1u << 22, cooperative, s);
+        tag += (unsigned)steps;
+        return r;
+    };
+    if (e == hipSuccess) e = run();
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    for (int i = 0; i < iters && e == hipSuccess; ++i) e = run();
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    int f = 0;
+    if (e == hipSuccess) e = hipMemcpy(&f, flag, 4, hipMemcpyDeviceToHost);
+    int rc = LSTM_OK;
+    if (e != hipSuccess) rc = fail_hip(nullptr, e, "lstm_bench_barrier");
+    else if (f) rc = fail(nullptr, LSTM_ERR_TIMEOUT, "lstm_bench_barrier: bounded wait expired");
+    else *avg_us_per_step = (double)ms * 1000.0 / iters / steps;
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (slots) (void)hipFree(slots);
+    if (flag) (void)hipFree(flag);
+    return rc;
 }
 
 int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream)

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
     bool same_xcd = false;
     if (a.one_xcd)
         same_xcd = group_shares_xcd(a.xcc_ids, (int)(gridDim.x >> 3), bid, a.tag_base + 1u, hbuf, tid, nthreads,
-                                    a.timeout_flag, a.spin_limit);
+                                    a.timeout_flag, a.spin_limit) && !a.device_scope_only;
 
     // Input side: x_t does not depend on the recurrence.  The workgroup requests row s+2 with coalesced loads at
     // the top of step s, parks it in LDS at the top of step s+1 (before the wait, so that nothing but h stands

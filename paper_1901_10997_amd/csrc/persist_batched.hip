@@ -147,7 +147,7 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
     bool same_xcd = false;
     if (kXcd && a.xcd_local)
         same_xcd = group_shares_xcd(a.xcc_ids + ((size_t)dir * a.bg + bgi) * 64, a.ug, ugi, a.tag_base + 1u, hbuf, tid,
-                                    nthreads, a.timeout_flag, a.spin_limit);
+                                    nthreads, a.timeout_flag, a.spin_limit) && !a.device_scope_only;
     for (int s = 0; s < a.T; ++s) {
         const int t = D.reverse ? (a.T - 1 - s) : s;
         float pin = 0.f;

@@ -250,7 +250,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
     bool same_xcd = false;
     if (a.xcd_local)
         same_xcd = group_shares_xcd(a.xcc_ids + grp * 64, a.ug, ugi, a.tag_base + 1u, hbuf, tid, nthreads, a.timeout_flag,
-                                    a.spin_limit);
+                                    a.spin_limit) && !a.device_scope_only;
     for (int s = 0; s < a.T; ++s) {
         const int t = D.reverse ? (a.T - 1 - s) : s;
         const unsigned tag = a.tag_base + (unsigned)s + 1u;

@@ -97,7 +97,7 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
     bool same_xcd = false;
     if (a.xcd_local)
         same_xcd = group_shares_xcd(a.xcc_ids + (size_t)tile_m * 64, gn, tile_n, a.tag_base + 1u, part, tid, NTH,
-                                    a.timeout_flag, a.spin_limit);
+                                    a.timeout_flag, a.spin_limit) && !a.device_scope_only;
 
     for (int s = 0; s < a.T; ++s) {
         const int t = a.reverse ? a.T - 1 - s : s;

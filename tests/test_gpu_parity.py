@@ -531,3 +531,46 @@ def test_group_exchange_yardstick_and_the_one_xcd_check():
         B.lstm_bench_group_exchange(3000, 24, 10, True, True)                              # two groups of 24 per XCD
     with pytest.raises(B.LstmError):
         B.lstm_bench_group_exchange(100, 65, 1, False, False)
+
+
+@pytest.mark.parametrize("name", ["c1", "c4", "c5", "h2"])
+def test_l2_handover_off_gives_the_same_bits(name, monkeypatch):
+    """The workloads whose exchange is handed over through one XCD's L2, run with that hand-over on and with every
+    exchange store forced to device scope (LSTM355_L2_HANDOVER=0 at lstm_create): same placement, same arithmetic, so
+    the outputs must be bit-identical; a hand-over that delivered a stale value would show as a difference."""
+    w = {"c1": inputs.c1, "c4": inputs.c4, "c5": inputs.c5, "h2": inputs.h2}[name]()
+    if name in ("c4", "h2"):
+        w = inputs.shrink(w, T=60)
+    case = inputs.make_case(w, 1)
+    on, desc_on = run_gpu(case, cooperative=False)
+    monkeypatch.setenv("LSTM355_L2_HANDOVER", "0")
+    off, desc_off = run_gpu(case, cooperative=False)
+    monkeypatch.delenv("LSTM355_L2_HANDOVER")
+    assert desc_on == desc_off and "persist" in desc_on
+    for a, b in zip(on, off):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
+def test_yardsticks_run_and_are_plausible():
+    """The achievable-peak yardsticks: matrix-instruction issue loops, the streaming copy and the data-free barrier."""
+    import torch
+    bf16 = B.lstm_bench_mfma(B.LSTM_BF16, reps=2000, iters=2)
+    f32 = B.lstm_bench_mfma(B.LSTM_F32, reps=2000, iters=2)
+    assert 500 < bf16 < 2600 and 30 < f32 < 165, (bf16, f32)     # below the spec-sheet peaks, above a third of them
+    n = 1 << 28
+    src = torch.arange(n // 4, dtype=torch.int32, device="cuda:0")
+    dst = torch.zeros_like(src)
+    us = B.lstm_bench_copy(dst.data_ptr(), src.data_ptr(), n, 3)
+    assert torch.equal(src, dst)
+    assert 1000 < 2 * n / us / 1e3 < 8000, us                    # GB/s, read + write
+    m = 4096 + 16 * 37                                           # a size with a ragged tail for the unrolled loop
+    d2 = torch.zeros(m // 4, dtype=torch.int32, device="cuda:0")
+    B.lstm_bench_copy(d2.data_ptr(), src.data_ptr(), m, 1)
+    assert torch.equal(d2, src[: m // 4])
+    for coop in (False, True):
+        us = B.lstm_bench_barrier(256, 12, steps=100, iters=2, cooperative=coop)
+        assert 0.1 < us < 20, us
+    with pytest.raises(B.LstmError):
+        B.lstm_bench_barrier(257, 12)
+    with pytest.raises(B.LstmError):
+        B.lstm_bench_mfma(7)
