@@ -287,13 +287,22 @@ def main():
         src = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
         dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
         copy_us = B.lstm_bench_copy(dst.data_ptr(), src.data_ptr(), nbytes, 5, stream)
+        bf_c, bf_c_ghz = B.lstm_bench_mfma(B.LSTM_BF16, 20000, 3, stream, False, True)
+        bf_r, bf_r_ghz = B.lstm_bench_mfma(B.LSTM_BF16, 20000, 3, stream, True, True)
+        f_c, f_c_ghz = B.lstm_bench_mfma(B.LSTM_F32, 5000, 3, stream, False, True)
+        f_r, f_r_ghz = B.lstm_bench_mfma(B.LSTM_F32, 5000, 3, stream, True, True)
         measured = {"copy_GBps": 2 * nbytes / copy_us / 1e3, "copy_bytes_each_way": nbytes,
-                    "mfma_bf16_TFLOPs": B.lstm_bench_mfma(B.LSTM_BF16, 20000, 3, stream),
-                    "mfma_f32_TFLOPs": B.lstm_bench_mfma(B.LSTM_F32, 5000, 3, stream)}
+                    "mfma_bf16_TFLOPs": bf_c, "mfma_bf16_clock_GHz": bf_c_ghz,
+                    "mfma_bf16_random_operands_TFLOPs": bf_r, "mfma_bf16_random_operands_clock_GHz": bf_r_ghz,
+                    "mfma_f32_TFLOPs": f_c, "mfma_f32_clock_GHz": f_c_ghz,
+                    "mfma_f32_random_operands_TFLOPs": f_r, "mfma_f32_random_operands_clock_GHz": f_r_ghz}
         roofline["frac_of_measured_copy"] = achieved / measured["copy_GBps"]
         if proj:
-            proj["measured_peak"] = measured["mfma_bf16_TFLOPs" if dtype == B.LSTM_BF16 else "mfma_f32_TFLOPs"]
+            key = "mfma_bf16" if dtype == B.LSTM_BF16 else "mfma_f32"
+            proj["measured_peak"] = measured[key + "_TFLOPs"]
             proj["frac_of_measured"] = proj["achieved"] / proj["measured_peak"]
+            proj["measured_peak_random_operands"] = measured[key + "_random_operands_TFLOPs"]
+            proj["frac_of_measured_random_operands"] = proj["achieved"] / proj["measured_peak_random_operands"]
         # cold weights: one forward right after a 2 x 512 MiB device copy has swept the caches
         colds = []
         for _ in range(5):

@@ -348,13 +348,18 @@ int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double*
 int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, int iters, const float* X_host,
                       const float* W_host, const uint8_t* mask_host, double* avg_us, float* y_host, void* stream);
 /*
- * Matrix-instruction issue loop: every wave of two four-wave workgroups per compute unit issues `reps` rounds of four
+ * Matrix-instruction issue loop: every wave of two four-wave workgroups per compute unit issues `reps` rounds of eight
  * independent matrix instructions (dtype LSTM_BF16: 32x32x16 bf16, LSTM_F32: 32x32x2 fp32) on operands and
- * accumulators it holds in registers, so nothing but the matrix pipes limits it: the achievable peak that the
- * projection kernels' rates are quoted against, next to the spec-sheet one.  *tflops (HOST): 10^12 operations per
- * second over `iters` launches after one warm-up.  Allocates a small sink buffer; synchronises the stream.
+ * accumulators it holds in registers, so nothing but the matrix pipes, and the power they draw, limits it: the
+ * achievable peak that the projection kernels' rates are quoted against, next to the spec-sheet one.
+ * random_operands = 0: one constant operand pair (the highest clock the device holds under matrix load);
+ * random_operands = 1: twelve operand fragments of random sign and mantissa, rotated every round, as a product of
+ * real data presents them; the device then settles at a lower clock, and that rate is the ceiling of a product on
+ * real data.  *tflops (HOST): 10^12 operations per second over `iters` launches after one warm-up; *clock_ghz (HOST,
+ * may be NULL): the shader clock during the loop (cycle counter against the 100 MHz counter).  Allocates small
+ * buffers; synchronises the stream.
  */
-int lstm_bench_mfma(int dtype, int reps, int iters, double* tflops, void* stream);
+int lstm_bench_mfma(int dtype, int random_operands, int reps, int iters, double* tflops, double* clock_ghz, void* stream);
 /*
  * Device-wide barrier with no data: `workgroups` (<= compute units, <= 256) workgroups of `waves` waves; in each of
  * `steps` rounds every workgroup raises one tagged 8-byte slot and waits until it has seen the slots of all of them

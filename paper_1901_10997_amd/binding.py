@@ -101,7 +101,7 @@ def load(build_if_missing: bool = True):
     lib.lstm_compact_rows_cols.restype = ci
     lib.lstm_compact_rows_cols.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, c.POINTER(ci), c.POINTER(ci), vp]
     lib.lstm_bench_mfma.restype = ci
-    lib.lstm_bench_mfma.argtypes = [ci, ci, ci, c.POINTER(c.c_double), vp]
+    lib.lstm_bench_mfma.argtypes = [ci, ci, ci, ci, c.POINTER(c.c_double), c.POINTER(c.c_double), vp]
     lib.lstm_bench_barrier.restype = ci
     lib.lstm_bench_barrier.argtypes = [ci, ci, ci, ci, ci, c.POINTER(c.c_double), vp]
     lib.lstm_bench_matmul.restype = ci
@@ -343,11 +343,12 @@ def lstm_bench_matmul(n: int, batch: int, keep: float, fmt: int, seed: int = 1, 
     return (us.value, y) if want_product else us.value
 
 
-def lstm_bench_mfma(dtype: int, reps: int = 20000, iters: int = 3, stream: Optional[int] = None) -> float:
-    """Matrix-instruction issue rate in TFLOP/s (operands in registers)."""
-    t = ctypes.c_double()
-    _check(load().lstm_bench_mfma(dtype, reps, iters, ctypes.byref(t), stream))
-    return t.value
+def lstm_bench_mfma(dtype: int, reps: int = 20000, iters: int = 3, stream: Optional[int] = None, random_operands: bool = False,
+                    with_clock: bool = False):
+    """Matrix-instruction issue rate in TFLOP/s (operands in registers); with_clock: (TFLOP/s, shader clock in GHz)."""
+    t, g = ctypes.c_double(), ctypes.c_double()
+    _check(load().lstm_bench_mfma(dtype, int(bool(random_operands)), reps, iters, ctypes.byref(t), ctypes.byref(g), stream))
+    return (t.value, g.value) if with_clock else t.value
 
 
 def lstm_bench_barrier(workgroups: int, waves: int, steps: int = 200, iters: int = 5, cooperative: bool = True,

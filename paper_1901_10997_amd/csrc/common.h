@@ -399,7 +399,8 @@ hipError_t launch_compact_rows_cols(const float* W, const uint8_t* mask, int gat
 hipError_t launch_fill_u64(unsigned long long* p, size_t n, unsigned long long v, hipStream_t s);
 // yardsticks
 hipError_t launch_copy_stream(void* dst, const void* src, size_t bytes, hipStream_t s);
-hipError_t launch_mfma_issue(bool bf16, float* sink, int reps, double* flops, hipStream_t s);
+int mfma_issue_blocks();
+hipError_t launch_mfma_issue(bool bf16, bool random, float* sink, long long* clocks, int reps, double* flops, hipStream_t s);
 size_t mfma_issue_sink_floats();
 hipError_t launch_barrier_only(unsigned long long* slots, unsigned tag_base, int groups, int waves, int steps,
                                int* timeout_flag, unsigned spin_limit, int cooperative, hipStream_t s);

@@ -1759,29 +1759,42 @@ int lstm_bench_copy(void* dst, const void* src, size_t bytes, int iters, double*
     return LSTM_OK;
 }
 
-int lstm_bench_mfma(int dtype, int reps, int iters, double* tflops, void* stream)
+int lstm_bench_mfma(int dtype, int random_operands, int reps, int iters, double* tflops, double* clock_ghz, void* stream)
 {
-    if ((dtype != LSTM_F32 && dtype != LSTM_BF16) || reps < 1 || iters < 1 || !tflops)
+    if ((dtype != LSTM_F32 && dtype != LSTM_BF16) || reps < 1 || iters < 1 || !tflops ||
+        (random_operands != 0 && random_operands != 1))
         return fail(nullptr, LSTM_ERR_ARG, "lstm_bench_mfma: bad arguments");
     hipStream_t s = (hipStream_t)stream;
     float* sink = nullptr;
+    long long* clocks = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     double flops = 0.0;
+    const int blocks = mfma_issue_blocks();
+    const bool bf16 = dtype == LSTM_BF16, rnd = random_operands != 0;
     hipError_t e = hipMalloc((void**)&sink, mfma_issue_sink_floats() * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&clocks, (size_t)blocks * 2 * sizeof(long long));
     if (e == hipSuccess) e = hipEventCreate(&e0);
     if (e == hipSuccess) e = hipEventCreate(&e1);
-    if (e == hipSuccess) e = launch_mfma_issue(dtype == LSTM_BF16, sink, reps, &flops, s);      // warm-up
+    if (e == hipSuccess) e = launch_mfma_issue(bf16, rnd, sink, clocks, reps, &flops, s);      // warm-up
     if (e == hipSuccess) e = hipEventRecord(e0, s);
-    for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_mfma_issue(dtype == LSTM_BF16, sink, reps, &flops, s);
+    for (int i = 0; i < iters && e == hipSuccess; ++i) e = launch_mfma_issue(bf16, rnd, sink, clocks, reps, &flops, s);
     if (e == hipSuccess) e = hipEventRecord(e1, s);
     if (e == hipSuccess) e = hipEventSynchronize(e1);
     float ms = 0.f;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    std::vector<long long> h((size_t)blocks * 2, 0);
+    if (e == hipSuccess) e = hipMemcpy(h.data(), clocks, h.size() * sizeof(long long), hipMemcpyDeviceToHost);
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
     if (sink) (void)hipFree(sink);
+    if (clocks) (void)hipFree(clocks);
     if (e != hipSuccess) return fail_hip(nullptr, e, "lstm_bench_mfma");
     *tflops = flops * iters / ((double)ms * 1e-3) / 1e12;
+    if (clock_ghz) {
+        double cyc = 0.0, ticks = 0.0;
+        for (int i = 0; i < blocks; ++i) { cyc += (double)h[2 * (size_t)i]; ticks += (double)h[2 * (size_t)i + 1]; }
+        *clock_ghz = ticks > 0.0 ? cyc / (ticks * 10.0) : 0.0;    // shader cycles per 10 ns tick of the 100 MHz counter
+    }
     return LSTM_OK;
 }
 

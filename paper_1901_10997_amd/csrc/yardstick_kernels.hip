@@ -38,57 +38,79 @@ hipError_t launch_copy_stream(void* dst, const void* src, size_t bytes, hipStrea
 }
 
 // ---- matrix-instruction issue loop -------------------------------------------------------------------------------
-// Every wave keeps four independent accumulator tiles and issues `reps` rounds of four matrix instructions on
-// operands it never reloads: nothing but the matrix pipe limits it.  The sink store keeps the loop alive.
-constexpr int kMfmaChains = 4;
+// Every wave keeps eight independent accumulator tiles and issues `reps` rounds of eight matrix instructions on
+// operands it holds in registers: nothing but the matrix pipe (and the power it draws) limits it.  RANDOM = false:
+// one constant operand pair (registers that never toggle: the highest clock the device holds under matrix load);
+// RANDOM = true: eight A and four B fragments of random sign and mantissa, rotated every round, as a product of
+// real data presents them (the device then settles at a lower clock).  The shader clock is read around the loop.
+constexpr int kMfmaChains = 8;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4y;
 
-__global__ __launch_bounds__(256) void mfma_issue_bf16_kernel(float* __restrict__ sink, int reps)
+__device__ __forceinline__ unsigned lcg(unsigned& s) { s = s * 1664525u + 1013904223u; return s; }
+// two bf16 values in (-2, 2) of magnitude >= 1/128: random sign and mantissa, exponents in a narrow range
+__device__ __forceinline__ unsigned random_bf16_pair(unsigned& s, bool random)
 {
-    bf16x8 a, b;
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (__bf16)(0.001f * (float)((threadIdx.x + i) & 7));
-        b[i] = (__bf16)(0.002f * (float)((threadIdx.x * 3 + i) & 7));
-    }
-    f32x16 acc[kMfmaChains];
-    for (int c = 0; c < kMfmaChains; ++c)
-        for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
-    for (int r = 0; r < reps; ++r) {
-#pragma unroll
-        for (int c = 0; c < kMfmaChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[c], 0, 0, 0);
-    }
-    float t = 0.f;
-    for (int c = 0; c < kMfmaChains; ++c)
-        for (int i = 0; i < 16; ++i) t += acc[c][i];
-    if (t == 123.456f) sink[blockIdx.x * blockDim.x + threadIdx.x] = t;
+    const unsigned hi = (random ? (lcg(s) & 0x807F0000u) : 0u) | 0x3C000000u;
+    const unsigned lo = ((random ? (lcg(s) & 0x807F0000u) : 0u) | 0x3C000000u) >> 16;
+    return hi | lo;
 }
 
-__global__ __launch_bounds__(256) void mfma_issue_f32_kernel(float* __restrict__ sink, int reps)
+template <bool BF16, bool RANDOM>
+__global__ __launch_bounds__(256) void mfma_issue_kernel(float* __restrict__ sink, int reps, long long* __restrict__ clocks)
 {
-    const float a = 0.001f * (float)(threadIdx.x & 7), b = 0.002f * (float)((threadIdx.x * 3) & 7);
+    u32x4y a[8], b[4];
+    unsigned s = threadIdx.x * 2654435761u + blockIdx.x * 40503u + 12345u;
+    for (int i = 0; i < 8; ++i)
+        for (int j = 0; j < 4; ++j) a[i][j] = random_bf16_pair(s, RANDOM);
+    for (int i = 0; i < 4; ++i)
+        for (int j = 0; j < 4; ++j) b[i][j] = random_bf16_pair(s, RANDOM);
     f32x16 acc[kMfmaChains];
     for (int c = 0; c < kMfmaChains; ++c)
         for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+    const long long c0 = clock64(), w0 = wall_clock64();
     for (int r = 0; r < reps; ++r) {
 #pragma unroll
-        for (int c = 0; c < kMfmaChains; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[c], 0, 0, 0);
+        for (int c = 0; c < kMfmaChains; ++c) {
+            const u32x4y& fa = a[RANDOM ? c : 0];
+            const u32x4y& fb = b[RANDOM ? (c & 3) : 0];
+            if (BF16)
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa), __builtin_bit_cast(bf16x8, fb),
+                                                                acc[c], 0, 0, 0);
+            else   // fp32: the first register of each fragment, read as a float of small magnitude
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[0] & 0xBFFFFFFFu), __uint_as_float(fb[0] & 0xBFFFFFFFu),
+                                                             acc[c], 0, 0, 0);
+        }
+        if (RANDOM) {   // rotate the B fragments: operands differ from round to round (four moves under 256 pipe cycles)
+            const u32x4y t = b[0];
+            b[0] = b[1]; b[1] = b[2]; b[2] = b[3]; b[3] = t;
+        }
     }
+    const long long c1 = clock64(), w1 = wall_clock64();
     float t = 0.f;
     for (int c = 0; c < kMfmaChains; ++c)
         for (int i = 0; i < 16; ++i) t += acc[c][i];
     if (t == 123.456f) sink[blockIdx.x * blockDim.x + threadIdx.x] = t;
+    if (threadIdx.x == 0) {
+        clocks[2 * blockIdx.x] = c1 - c0;
+        clocks[2 * blockIdx.x + 1] = w1 - w0;   // 100 MHz
+    }
 }
 
 // two workgroups of four waves per compute unit: two waves per SIMD.  *flops receives the operations of one launch.
-hipError_t launch_mfma_issue(bool bf16, float* sink, int reps, double* flops, hipStream_t s)
+// clocks: 2 x blocks 64-bit counters (shader cycles, 100 MHz ticks) per workgroup.
+int mfma_issue_blocks() { return device_num_cus() * 2; }
+hipError_t launch_mfma_issue(bool bf16, bool random, float* sink, long long* clocks, int reps, double* flops, hipStream_t s)
 {
-    const int blocks = device_num_cus() * 2;
-    if (bf16) hipLaunchKernelGGL(mfma_issue_bf16_kernel, dim3(blocks), dim3(256), 0, s, sink, reps);
-    else hipLaunchKernelGGL(mfma_issue_f32_kernel, dim3(blocks), dim3(256), 0, s, sink, reps);
+    const int blocks = mfma_issue_blocks();
+    if (bf16 && random) hipLaunchKernelGGL((mfma_issue_kernel<true, true>), dim3(blocks), dim3(256), 0, s, sink, reps, clocks);
+    else if (bf16) hipLaunchKernelGGL((mfma_issue_kernel<true, false>), dim3(blocks), dim3(256), 0, s, sink, reps, clocks);
+    else if (random) hipLaunchKernelGGL((mfma_issue_kernel<false, true>), dim3(blocks), dim3(256), 0, s, sink, reps, clocks);
+    else hipLaunchKernelGGL((mfma_issue_kernel<false, false>), dim3(blocks), dim3(256), 0, s, sink, reps, clocks);
     const double per_instruction = 2.0 * 32 * 32 * (bf16 ? 16 : 2);
     if (flops) *flops = per_instruction * kMfmaChains * (double)reps * 4.0 * blocks;
     return hipGetLastError();
 }
-size_t mfma_issue_sink_floats() { return (size_t)device_num_cus() * 2 * 256; }
+size_t mfma_issue_sink_floats() { return (size_t)mfma_issue_blocks() * 256; }
 
 // ---- device-wide barrier with no data ------------------------------------------------------------------------------
 // `steps` rounds in which every workgroup raises its own tagged slot and waits until it has seen the slots of all

@@ -554,9 +554,13 @@ def test_l2_handover_off_gives_the_same_bits(name, monkeypatch):
 def test_yardsticks_run_and_are_plausible():
     """The achievable-peak yardsticks: matrix-instruction issue loops, the streaming copy and the data-free barrier."""
     import torch
-    bf16 = B.lstm_bench_mfma(B.LSTM_BF16, reps=2000, iters=2)
+    bf16, ghz = B.lstm_bench_mfma(B.LSTM_BF16, reps=2000, iters=2, with_clock=True)
     f32 = B.lstm_bench_mfma(B.LSTM_F32, reps=2000, iters=2)
     assert 500 < bf16 < 2600 and 30 < f32 < 165, (bf16, f32)     # below the spec-sheet peaks, above a third of them
+    assert 0.5 < ghz < 2.6, ghz
+    rnd, ghz_r = B.lstm_bench_mfma(B.LSTM_BF16, reps=2000, iters=2, random_operands=True, with_clock=True)
+    assert 500 < rnd <= bf16 * 1.05 and 0.5 < ghz_r < 2.6, (rnd, ghz_r)
+    assert 30 < B.lstm_bench_mfma(B.LSTM_F32, reps=2000, iters=2, random_operands=True) < 165
     n = 1 << 28
     src = torch.arange(n // 4, dtype=torch.int32, device="cuda:0")
     dst = torch.zeros_like(src)
