@@ -87,6 +87,21 @@ int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, in
 int lstm_create_h(int layers, int input_dim, int hidden_dim, int gate_hidden_dim, int bidirectional, int dtype,
                   lstm_t** out);
 
+/*
+ * Create a stack whose layers have their own widths (paper Section 4, row/column growth and pruning: the dimensions
+ * of the weight matrices shrink and grow layer by layer; Section 5.1 step (b): 1500/400 -> 1197/317): layer l has
+ * hidden width hidden_dims[l] and input width D_l = input_dim for l = 0, Dn * hidden_dims[l-1] otherwise.
+ * gate_hidden_dims = NULL: conventional cells; otherwise H-LSTM cells with gate hidden width gate_hidden_dims[l] in
+ * layer l (dtype LSTM_F32 only).  Both arrays HOST, `layers` entries, every entry >= 1.
+ * Weights are set per (layer, direction) with lstm_set_weights / lstm_set_weights_h using that layer's widths.
+ * y is [T, B, Dn * hidden_dims[layers-1]].  The states h0, c0, hT, cT are sequences of blocks: block n = l*Dn + d
+ * holds [B, hidden_dims[l]] values and the blocks follow each other in the order of n (with one width for all layers
+ * this is the [L*Dn, B, H] array of lstm_forward).  Two consecutive unidirectional layers run in one launch at
+ * batch 1 only where their widths are equal.
+ */
+int lstm_create_layers(int layers, int input_dim, const int* hidden_dims, const int* gate_hidden_dims, int bidirectional,
+                       int dtype, lstm_t** out);
+
 /* Frees the handle and every device buffer it owns.  NULL is accepted. */
 int lstm_destroy(lstm_t* m);
 

@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "liblstm355.
 
 # every symbol include/lstm355.h declares
 EXPORTS = [
-    "lstm_create", "lstm_create_h", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_set_weights_h",
+    "lstm_create", "lstm_create_h", "lstm_create_layers", "lstm_destroy", "lstm_last_error", "lstm_set_weights", "lstm_set_weights_h",
     "lstm_workspace_bytes",
     "lstm_forward", "lstm_check", "lstm_set_plan", "lstm_set_launch_mode", "lstm_set_default_launch_mode", "lstm_set_profiling", "lstm_get_profile", "lstm_describe_plan", "lstm_get_compressed",
     "lstm_latency_sweep", "lstm_latency_sweep_model", "lstm_find_lhp", "lstm_grow_to_lhp", "lstm_prune_weights", "lstm_prune_rows_cols", "lstm_prune_rows_cols_static",
@@ -57,6 +57,8 @@ def load(build_if_missing: bool = True):
     lib.lstm_create.argtypes = [ci, ci, ci, ci, ci, c.POINTER(vp)]
     lib.lstm_create_h.restype = ci
     lib.lstm_create_h.argtypes = [ci, ci, ci, ci, ci, ci, c.POINTER(vp)]
+    lib.lstm_create_layers.restype = ci
+    lib.lstm_create_layers.argtypes = [ci, ci, vp, vp, ci, ci, c.POINTER(vp)]
     lib.lstm_destroy.restype = ci
     lib.lstm_destroy.argtypes = [vp]
     lib.lstm_last_error.restype = c.c_char_p
@@ -147,6 +149,19 @@ def lstm_create_h(layers: int, input_dim: int, hidden_dim: int, gate_hidden_dim:
     h = ctypes.c_void_p()
     _check(load().lstm_create_h(layers, input_dim, hidden_dim, gate_hidden_dim, int(bool(bidirectional)), dtype,
                                 ctypes.byref(h)))
+    return h
+
+
+def lstm_create_layers(input_dim: int, hidden_dims: Sequence[int], gate_hidden_dims: Optional[Sequence[int]],
+                       bidirectional: bool, dtype: int = LSTM_F32):
+    """A stack whose layers have their own hidden widths (and, for H-LSTM cells, their own gate hidden widths)."""
+    hs = np.ascontiguousarray(hidden_dims, dtype=np.int32)
+    gs = None if gate_hidden_dims is None else np.ascontiguousarray(gate_hidden_dims, dtype=np.int32)
+    if gs is not None and len(gs) != len(hs):
+        raise ValueError("gate_hidden_dims and hidden_dims differ in length")
+    h = ctypes.c_void_p()
+    _check(load().lstm_create_layers(len(hs), input_dim, hs.ctypes.data, None if gs is None else gs.ctypes.data,
+                                     int(bool(bidirectional)), dtype, ctypes.byref(h)))
     return h
 
 
@@ -379,16 +394,34 @@ def lstm_bench_exchange(hidden: int, waves: int = 0, steps: int = 200, iters: in
 # Convenience wrapper for tests and the benchmark: owns a handle plus torch device buffers.
 # ------------------------------------------------------------------------------------------------------------
 class Lstm:
-    def __init__(self, layers: int, input_dim: int, hidden: int, bidirectional: bool = False, dtype: int = LSTM_F32,
-                 gate_hidden: int = 0):
-        self.layers, self.input_dim, self.hidden = layers, input_dim, hidden
+    """hidden (and gate_hidden) may be one width for all layers or one per layer.  With per-layer widths the states are
+    flat tensors: block n = l * ndir + d holds [B, hidden[l]] values, the blocks follow each other in that order."""
+
+    def __init__(self, layers: int, input_dim: int, hidden, bidirectional: bool = False, dtype: int = LSTM_F32,
+                 gate_hidden=0):
+        self.layers, self.input_dim = layers, input_dim
         self.ndir = 2 if bidirectional else 1
         self.dtype = dtype
-        self.gate_hidden = gate_hidden
-        if gate_hidden > 0:
-            self.handle = lstm_create_h(layers, input_dim, hidden, gate_hidden, bidirectional, dtype)
+        self.per_layer = not np.isscalar(hidden)
+        if self.per_layer:
+            self.hiddens = [int(h) for h in hidden]
+            assert len(self.hiddens) == layers
+            gl = None
+            if not np.isscalar(gate_hidden):
+                gl = [int(g) for g in gate_hidden]
+            elif gate_hidden > 0:
+                gl = [int(gate_hidden)] * layers
+            self.gate_hidden = 0 if gl is None else max(gl)
+            self.hidden = self.hiddens[-1]
+            self.handle = lstm_create_layers(input_dim, self.hiddens, gl, bidirectional, dtype)
         else:
-            self.handle = lstm_create(layers, input_dim, hidden, bidirectional, dtype)
+            self.hidden = hidden
+            self.hiddens = [hidden] * layers
+            self.gate_hidden = gate_hidden
+            if gate_hidden > 0:
+                self.handle = lstm_create_h(layers, input_dim, hidden, gate_hidden, bidirectional, dtype)
+            else:
+                self.handle = lstm_create(layers, input_dim, hidden, bidirectional, dtype)
         self._ws = None
 
     def close(self):
@@ -419,8 +452,13 @@ class Lstm:
         dev = x.device
         n = self.layers * self.ndir
         y = torch.empty((T, B, self.ndir * self.hidden), dtype=torch.float32, device=dev)
-        hT = torch.empty((n, B, self.hidden), dtype=torch.float32, device=dev) if want_state else None
-        cT = torch.empty((n, B, self.hidden), dtype=torch.float32, device=dev) if want_state else None
+        if self.per_layer:
+            units = sum(self.hiddens) * self.ndir
+            hT = torch.empty(B * units, dtype=torch.float32, device=dev) if want_state else None
+            cT = torch.empty(B * units, dtype=torch.float32, device=dev) if want_state else None
+        else:
+            hT = torch.empty((n, B, self.hidden), dtype=torch.float32, device=dev) if want_state else None
+            cT = torch.empty((n, B, self.hidden), dtype=torch.float32, device=dev) if want_state else None
         need = lstm_workspace_bytes(self.handle, T, B)
         if self._ws is None or self._ws.numel() < need:
             self._ws = torch.empty(need, dtype=torch.uint8, device=dev)

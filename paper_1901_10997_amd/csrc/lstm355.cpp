@@ -39,7 +39,14 @@ struct lstm355 {
     struct Span { hipEvent_t e0, e1; int kind; };
     std::vector<Span> spans;             // recorded, not yet read
     std::vector<hipEvent_t> event_pool;  // idle events
-    int in_dim(int l) const { return l == 0 ? D0 : Dn * H; }
+    // widths per layer (H and G above hold the largest of them: sizes of shared buffers)
+    std::vector<int> Hs, Gs;
+    std::vector<size_t> state_off;       // state_off[l*Dn + d]: hidden units in front of that cell in h0/c0/hT/cT
+    size_t xchg_slots = 0;               // 64-bit slots in xchg
+    int hid(int l) const { return Hs[(size_t)l]; }
+    int ghid(int l) const { return Gs[(size_t)l]; }
+    int in_dim(int l) const { return l == 0 ? D0 : Dn * Hs[(size_t)l - 1]; }
+    size_t soff(size_t n) const { return state_off[n]; }
 };
 
 static thread_local std::string g_create_error;
@@ -187,11 +194,12 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
     HIP_TRY(m, upload(&out.row_ptr, rp32));
     HIP_TRY(m, upload(&out.col16, c16));
     HIP_TRY(m, upload(&out.val, out.h_val));
-    // 64-lane slices for the register-resident batch-1 kernel.  The kernel gathers h[col] from LDS, whose 32
-    // four-byte banks serve the lanes 0..31 and 32..63 of a wave in two passes; an entry with column c is
-    // therefore placed, where room allows, in a lane congruent to c modulo 32, so that the lanes of a pass hit
-    // distinct banks.  Entries that do not fit their bank's lanes fill the remaining positions.  (The order of
-    // the entries inside a row is free: it only fixes the order of a sum.)
+    // 64-lane slices for the register-resident kernels.  The kernels gather h[col] from LDS (4 bytes per column at
+    // batch 1, 8 or 16 bytes with two or four batch columns adjacent).  Measured on gfx950: a 4- or 8-byte read serves
+    // lanes 0..31 and 32..63 in separate passes, and within a pass two lanes collide when their columns are congruent
+    // modulo 32; a 16-byte read makes four passes of 16 lanes whose columns must differ modulo 16.  An entry with
+    // column c is therefore placed, where room allows, in a lane congruent to c modulo 32, which is conflict-free for
+    // all three widths.  (The order of the entries inside a row is free: it only fixes the order of a sum.)
     out.slots = std::max(1, (max_nnz + 63) / 64);
     // slices of S slots holding the first min(nnz, 64 S) entries of every row
     auto build_slices = [&](int S, std::vector<float>& ev, std::vector<uint16_t>& ec) {
@@ -218,9 +226,12 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
                     leftover.push_back(e);
                 }
             }
-            size_t pos = 0;
+            // An entry whose bank's lanes are full meets a bank that is taken in every pass, so it costs its pass one
+            // more cycle wherever it goes; all of them go to the same pass (free positions taken from the end: the
+            // last slot's upper half fills up last), so that a row pays that cycle once and not once per entry.
+            size_t pos = (size_t)S * 64;
             for (int64_t e : leftover) {
-                while (used[pos]) ++pos;
+                do { --pos; } while (used[pos]);
                 used[pos] = 1;
                 const size_t idx = (size_t)rp * S * 64 + pos;
                 ev[idx] = out.h_val[e];
@@ -279,26 +290,36 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
 
 extern "C" {
 
-static int create_model(int layers, int input_dim, int hidden_dim, int gate_hidden_dim, int bidirectional, int dtype,
-                        lstm_t** out)
+static int create_model(int layers, int input_dim, const int* hidden_dims, const int* gate_hidden_dims, int bidirectional,
+                        int dtype, lstm_t** out)
 {
     if (!out) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: out is NULL");
     *out = nullptr;
-    if (layers < 1 || input_dim < 1 || hidden_dim < 1)
+    if (layers < 1 || input_dim < 1 || !hidden_dims)
         return fail(nullptr, LSTM_ERR_ARG, "lstm_create: layers, input_dim and hidden_dim must be >= 1");
     if (bidirectional != 0 && bidirectional != 1)
         return fail(nullptr, LSTM_ERR_ARG, "lstm_create: bidirectional must be 0 or 1");
     if (dtype != LSTM_F32 && dtype != LSTM_BF16) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: unknown dtype");
-    if ((long long)hidden_dim * 4 > (1 << 28) || input_dim > (1 << 28))
-        return fail(nullptr, LSTM_ERR_ARG, "lstm_create: dimension too large");
+    if (input_dim > (1 << 28)) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: dimension too large");
+    for (int l = 0; l < layers; ++l) {
+        if (hidden_dims[l] < 1) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: layers, input_dim and hidden_dim must be >= 1");
+        if ((long long)hidden_dims[l] * 4 > (1 << 28)) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: dimension too large");
+        if (gate_hidden_dims && (gate_hidden_dims[l] < 1 || (long long)gate_hidden_dims[l] * 4 > (1 << 28)))
+            return fail(nullptr, LSTM_ERR_ARG, "lstm_create_h: gate_hidden_dim must be >= 1");
+    }
     lstm_t* m = new (std::nothrow) lstm355();
     if (!m) return fail(nullptr, LSTM_ERR_NOMEM, "lstm_create: host allocation failed");
     m->L = layers;
     m->D0 = input_dim;
-    m->H = hidden_dim;
     m->Dn = bidirectional ? 2 : 1;
     m->dtype = dtype;
-    m->G = gate_hidden_dim;
+    m->Hs.assign(hidden_dims, hidden_dims + layers);
+    m->Gs.assign((size_t)layers, 0);
+    if (gate_hidden_dims) m->Gs.assign(gate_hidden_dims, gate_hidden_dims + layers);
+    m->H = *std::max_element(m->Hs.begin(), m->Hs.end());
+    m->G = *std::max_element(m->Gs.begin(), m->Gs.end());
+    m->state_off.assign((size_t)m->L * m->Dn + 1, 0);
+    for (size_t n = 0; n < (size_t)m->L * m->Dn; ++n) m->state_off[n + 1] = m->state_off[n] + (size_t)m->Hs[n / (size_t)m->Dn];
     m->ld.resize((size_t)m->L * m->Dn);
     m->cooperative = g_default_cooperative;
     if (const char* sl = std::getenv("LSTM355_SPIN_LIMIT")) {
@@ -308,9 +329,9 @@ static int create_model(int layers, int input_dim, int hidden_dim, int gate_hidd
     if (const char* l2 = std::getenv("LSTM355_L2_HANDOVER")) m->device_scope_only = (std::atoi(l2) == 0) ? 1 : 0;
     hipError_t e = hipGetDevice(&m->device);
     // two cells (directions, or two stacked layers) x two parities; H-LSTM: h slots, then the 4G hidden-layer slots
-    const size_t slots = (m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H) + 64;   // + XCD ids of a launch's workgroups
-    if (e == hipSuccess) e = hipMalloc((void**)&m->xchg, slots * sizeof(unsigned long long));
-    if (e == hipSuccess) e = hipMemset(m->xchg, 0, slots * sizeof(unsigned long long));
+    m->xchg_slots = (m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H) + 64;   // + XCD ids of a launch's workgroups
+    if (e == hipSuccess) e = hipMalloc((void**)&m->xchg, m->xchg_slots * sizeof(unsigned long long));
+    if (e == hipSuccess) e = hipMemset(m->xchg, 0, m->xchg_slots * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipMalloc((void**)&m->timeout_flag, sizeof(int));
     if (e == hipSuccess) e = hipMemset(m->timeout_flag, 0, sizeof(int));
     if (e != hipSuccess) {
@@ -324,7 +345,10 @@ static int create_model(int layers, int input_dim, int hidden_dim, int gate_hidd
 
 int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, int dtype, lstm_t** out)
 {
-    return create_model(layers, input_dim, hidden_dim, 0, bidirectional, dtype, out);
+    if (out) *out = nullptr;
+    if (layers < 1 || layers > (1 << 16)) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: layers, input_dim and hidden_dim must be >= 1");
+    const std::vector<int> hs((size_t)layers, hidden_dim);
+    return create_model(layers, input_dim, hs.data(), nullptr, bidirectional, dtype, out);
 }
 
 int lstm_create_h(int layers, int input_dim, int hidden_dim, int gate_hidden_dim, int bidirectional, int dtype, lstm_t** out)
@@ -333,7 +357,20 @@ int lstm_create_h(int layers, int input_dim, int hidden_dim, int gate_hidden_dim
     if (gate_hidden_dim < 1 || (long long)gate_hidden_dim * 4 > (1 << 28))
         return fail(nullptr, LSTM_ERR_ARG, "lstm_create_h: gate_hidden_dim must be >= 1");
     if (dtype != LSTM_F32) return fail(nullptr, LSTM_ERR_ARG, "lstm_create_h: the H-LSTM cell is implemented for LSTM_F32 only");
-    return create_model(layers, input_dim, hidden_dim, gate_hidden_dim, bidirectional, dtype, out);
+    if (layers < 1 || layers > (1 << 16)) return fail(nullptr, LSTM_ERR_ARG, "lstm_create: layers, input_dim and hidden_dim must be >= 1");
+    const std::vector<int> hs((size_t)layers, hidden_dim), gs((size_t)layers, gate_hidden_dim);
+    return create_model(layers, input_dim, hs.data(), gs.data(), bidirectional, dtype, out);
+}
+
+int lstm_create_layers(int layers, int input_dim, const int* hidden_dims, const int* gate_hidden_dims, int bidirectional,
+                       int dtype, lstm_t** out)
+{
+    if (out) *out = nullptr;
+    if (layers < 1 || layers > (1 << 16) || !hidden_dims)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_create_layers: layers >= 1 and hidden_dims are required");
+    if (gate_hidden_dims && dtype != LSTM_F32)
+        return fail(nullptr, LSTM_ERR_ARG, "lstm_create_layers: the H-LSTM cell is implemented for LSTM_F32 only");
+    return create_model(layers, input_dim, hidden_dims, gate_hidden_dims, bidirectional, dtype, out);
 }
 
 int lstm_destroy(lstm_t* m)
@@ -366,7 +403,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     if (!Wx || !Wh || !b) return fail(m, LSTM_ERR_ARG, "lstm_set_weights: Wx, Wh and b are required");
     if (format != LSTM_FMT_AUTO && format != LSTM_FMT_DENSE_MASKED && format != LSTM_FMT_ROW_COMPRESSED)
         return fail(m, LSTM_ERR_ARG, "lstm_set_weights: unknown format");
-    const int H = m->H, D = m->in_dim(layer), rows = 4 * H;
+    const int H = m->hid(layer), D = m->in_dim(layer), rows = 4 * H;
     size_t kept = 0, total = (size_t)rows * D + (size_t)rows * H;
     for (int which = 0; which < 2; ++which) {
         const uint8_t* mk = which ? mask_h : mask_x;
@@ -412,7 +449,7 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
     if (!W1x || !W1h || !b1 || !W2 || !b2) return fail(m, LSTM_ERR_ARG, "lstm_set_weights_h: W1x, W1h, b1, W2 and b2 are required");
     if (format != LSTM_FMT_AUTO && format != LSTM_FMT_DENSE_MASKED && format != LSTM_FMT_ROW_COMPRESSED)
         return fail(m, LSTM_ERR_ARG, "lstm_set_weights_h: unknown format");
-    const int H = m->H, G = m->G, D = m->in_dim(layer);
+    const int H = m->hid(layer), G = m->ghid(layer), D = m->in_dim(layer);
     const size_t sizes[3] = {(size_t)4 * G * D, (size_t)4 * G * H, (size_t)4 * H * G};
     const uint8_t* masks[3] = {mask_1x, mask_1h, mask_2};
     size_t kept = 0, total = 0;
@@ -502,10 +539,19 @@ static Workspace carve(const lstm_t* m, int T, int B)
     // bf16 large-batch persistent recurrence: two exchange buffers of h_t and one flag per tile
     w.hx_off = off;
     w.mflag_off = off;
-    if (m->dtype == LSTM_BF16 && persist_mfma_supported(B, (int)H)) {
-        off += align256(persist_mfma_exchange_bytes(B, (int)H));
-        w.mflag_off = off;
-        off += align256(persist_mfma_flag_count(B, (int)H) * sizeof(unsigned));
+    if (m->dtype == LSTM_BF16) {
+        // the widest requirement over the layers whose width the kernel takes
+        size_t xbytes = 0, flags = 0;
+        for (int l = 0; l < m->L; ++l)
+            if (persist_mfma_supported(B, m->hid(l))) {
+                xbytes = std::max(xbytes, persist_mfma_exchange_bytes(B, m->hid(l)));
+                flags = std::max(flags, persist_mfma_flag_count(B, m->hid(l)));
+            }
+        if (xbytes > 0) {
+            off += align256(xbytes);
+            w.mflag_off = off;
+            off += align256(flags * sizeof(unsigned));
+        }
     }
     // H-LSTM: hidden-layer activations of the current step, [B][4G] per direction (stepwise paths); the small-batch
     // persistent kernel uses both directions' storage as one array of [k][columns of a batch group] blocks
@@ -622,7 +668,7 @@ static int take_b1_tags(lstm_t* m, unsigned n, size_t slots, hipStream_t s, unsi
 static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0, float* y, float* hT,
                          float* cT, const Workspace& ws, char* base, hipStream_t s)
 {
-    const int H = m->H, G = m->G, Dn = m->Dn, L = m->L;
+    const int Dn = m->Dn, L = m->L;
     const int M = T * B;
     float* P[2] = {(float*)(base + ws.P_off[0]), (float*)(base + ws.P_off[1])};
     float* XT = (float*)(base + ws.XT_off);
@@ -631,8 +677,10 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
     float* U[2] = {(float*)(base + ws.U_off[0]), (float*)(base + ws.U_off[1])};
     char tag[96];
     bool hslots_clean = false;   // exchange slots and flags zeroed during this forward (tags then restart at 1)
+    int hslots_H = 0, hslots_G = 0;   // widths of the layer the region was last laid out for
     unsigned htag = 0;
     for (int l = 0; l < L; ++l) {
+        const int H = m->hid(l), G = m->ghid(l);
         const int D = m->in_dim(l);
         const void* X = (l == 0) ? x : (const void*)Ybuf[(l - 1) & 1];
         float* Yout = (l == L - 1) ? y : Ybuf[l & 1];
@@ -717,9 +765,12 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 const size_t hslot_bytes = (size_t)Dn * (((size_t)B + 3) * H * sizeof(unsigned long long) + groups * 256);
                 unsigned* hflags = (unsigned*)(base + ws.slot_off + hslot_bytes);
                 unsigned long long* hxcc = (unsigned long long*)(hflags + (size_t)Dn * groups * 64);
-                if (!hslots_clean) {
+                // (a layer of other widths lays the region out differently: what the previous layer left under the
+                // new flag positions is not a tag, so the region starts from zero again)
+                if (!hslots_clean || hslots_H != H || hslots_G != G) {
                     HIP_TRY(m, launch_fill_u64(hslots, align256(ws.slot_bytes) / sizeof(unsigned long long), 0ull, s));
                     hslots_clean = true;
+                    hslots_H = H; hslots_G = G;
                     htag = 0;
                 }
                 PersistBatchedHArgs a{};
@@ -741,11 +792,11 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                         q.ell_val_2 = w.w2.ell_val; q.ell_col_2 = w.w2.ell_col; q.slots_2 = w.w2.slots;
                     }
                     q.bias2 = w.bias2;
-                    q.h0 = h0 ? h0 + n * B * H : nullptr;
-                    q.c0 = c0 ? c0 + n * B * H : nullptr;
+                    q.h0 = h0 ? h0 + m->soff(n) * B : nullptr;
+                    q.c0 = c0 ? c0 + m->soff(n) * B : nullptr;
                     q.y = Yout + (size_t)d * H; q.y_ld = y_ld;
-                    q.hT = hT ? hT + n * B * H : nullptr;
-                    q.cT = cT ? cT + n * B * H : nullptr;
+                    q.hT = hT ? hT + m->soff(n) * B : nullptr;
+                    q.cT = cT ? cT + m->soff(n) * B : nullptr;
                     q.reverse = d;
                     std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-hlstm-csr%s(u%d,b%d);", l, d,
                                   proj_dense[d] ? "dense" : "csr", trimmed ? "+ovf" : "", upw, bw);
@@ -776,7 +827,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
             ProfSpan span(m, s, 1);
             for (int d = 0; d < Dn; ++d) {
                 const size_t n = (size_t)l * Dn + d;
-                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
+                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + m->soff(n) * B, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
                 else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=hlstm-stepwise-pair-csr;", l, d, proj_dense[d] ? "dense" : "csr");
                 m->last_plan += tag;
@@ -790,7 +841,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                     HStepDir& q = a.d[d];
                     q.P1 = P[d];
                     if (step == 0) {
-                        q.h_prev = h0 ? h0 + n * B * H : nullptr;
+                        q.h_prev = h0 ? h0 + m->soff(n) * B : nullptr;
                         q.h_prev_ld = H;
                     } else {
                         const int tp = d ? t + 1 : t - 1;
@@ -804,8 +855,8 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                     q.c = cbuf[d];
                     q.y_t = Yout + (size_t)t * B * y_ld + (size_t)d * H;
                     q.y_ld = y_ld;
-                    q.hT = hT ? hT + n * B * H : nullptr;
-                    q.cT = cT ? cT + n * B * H : nullptr;
+                    q.hT = hT ? hT + m->soff(n) * B : nullptr;
+                    q.cT = cT ? cT + m->soff(n) * B : nullptr;
                     q.t = t;
                 }
                 a.B = B; a.H = H; a.G = G; a.last = (step == T - 1);
@@ -827,11 +878,11 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 a.ell_val_2 = w.w2.ell_val; a.ell_col_2 = w.w2.ell_col; a.slots_2 = w.w2.slots;
                 a.bias1 = w.bias; a.bias2 = w.bias2;
                 a.x = (const float*)X; a.x_ld = D; a.D = D;
-                a.h0 = h0 ? h0 + n * H : nullptr;
-                a.c0 = c0 ? c0 + n * H : nullptr;
+                a.h0 = h0 ? h0 + m->soff(n) : nullptr;
+                a.c0 = c0 ? c0 + m->soff(n) : nullptr;
                 a.y = Yout + (size_t)d * H; a.y_ld = y_ld;
-                a.hT = hT ? hT + n * H : nullptr;
-                a.cT = cT ? cT + n * H : nullptr;
+                a.hT = hT ? hT + m->soff(n) : nullptr;
+                a.cT = cT ? cT + m->soff(n) : nullptr;
                 a.T = T; a.H = H; a.G = G; a.reverse = d;
                 a.xchg_h = m->xchg; a.xchg_u = m->xchg + H;
                 a.tag_base = tag0;
@@ -841,7 +892,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 HIP_TRY(m, launch_persist_b1_hlstm(a, m->launch_mode(), s));
                 continue;
             }
-            if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
+            if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + m->soff(n) * B, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
             else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
             std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=hlstm-stepwise-%s;", l, d,
                           proj_dense[d] ? "dense" : "csr", w.wh.compressed ? "csr" : "dense");
@@ -851,7 +902,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 HStage1Args a1{};
                 a1.P1 = P[d];
                 if (step == 0) {
-                    a1.h_prev = h0 ? h0 + n * B * H : nullptr;
+                    a1.h_prev = h0 ? h0 + m->soff(n) * B : nullptr;
                     a1.h_prev_ld = H;
                 } else {
                     const int tp = d ? t + 1 : t - 1;
@@ -871,8 +922,8 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 a2.c = cbuf[d];
                 a2.y_t = Yout + (size_t)t * B * y_ld + (size_t)d * H;
                 a2.y_ld = y_ld;
-                a2.hT = hT ? hT + n * B * H : nullptr;
-                a2.cT = cT ? cT + n * B * H : nullptr;
+                a2.hT = hT ? hT + m->soff(n) * B : nullptr;
+                a2.cT = cT ? cT + m->soff(n) * B : nullptr;
                 a2.last = (step == T - 1);
                 a2.B = B; a2.H = H; a2.G = G;
                 HIP_TRY(m, launch_hstage2(a2, s));
@@ -913,7 +964,7 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
 static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const float* c0, float* y, float* hT,
                        float* cT, const Workspace& ws, char* base, hipStream_t s)
 {
-    const int H = m->H, Dn = m->Dn, L = m->L;
+    const int Dn = m->Dn, L = m->L;
     const int M = T * B;
     const bool bf16 = (m->dtype == LSTM_BF16);
     float* P[2] = {(float*)(base + ws.P_off[0]), (float*)(base + ws.P_off[1])};
@@ -924,20 +975,22 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
     uint16_t* hb0 = (uint16_t*)(base + ws.hb0_off);
     unsigned long long* bslots = (unsigned long long*)(base + ws.slot_off);
     bool bslots_clean = false;   // zeroed during this forward (tags then restart at 1)
+    int bslots_H = 0;            // width of the layer the region was last laid out for
     unsigned btag = 0;
     uint16_t* hx = (uint16_t*)(base + ws.hx_off);
     unsigned* mflags = (unsigned*)(base + ws.mflag_off);
     bool mflags_clean = false;   // zeroed during this forward (tags then restart at 1)
+    int mflags_H = 0;            // width of the layer the flags were last laid out for
     unsigned mtag = 0;
     bool prev_has_bf16 = false;  // the layer below left a bf16 copy of its hidden sequence in Ybf[(l-1)&1]
     m->last_plan.clear();
     if (m->G > 0) return forward_hlstm(m, T, B, x, h0, c0, y, hT, cT, ws, base, s);
 
     unsigned tag0 = 0;   // base of the tags the next batch-1 launch uses
-    auto take_tags = [&](int T_) -> int { return take_b1_tags(m, (unsigned)T_, (size_t)4 * H + 64, s, &tag0); };
+    auto take_tags = [&](int T_) -> int { return take_b1_tags(m, (unsigned)T_, m->xchg_slots, s, &tag0); };
     // slot count the batch-1 kernel will hold in registers: the trimmed slices where they exist
     auto b1_slots = [](const PackedMat& p) { return p.slots_trim > 0 ? p.slots_trim : p.slots; };
-    auto sparse_ok = [&](const LayerDir& w, int D_in, int nl) {
+    auto sparse_ok = [&](const LayerDir& w, int H, int D_in, int nl) {
         return w.wx.compressed && w.wh.compressed && (w.wx.ell_val || w.wx.slots_trim) && (w.wh.ell_val || w.wh.slots_trim) &&
                persist_b1_sparse_supported(H, D_in, b1_slots(w.wx), b1_slots(w.wh), nl);
     };
@@ -955,14 +1008,15 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             a.ell_val_h = w.wh.ell_val; a.ell_col_h = w.wh.ell_col; a.slots_h = w.wh.slots;
         }
         a.bias = w.bias;
-        a.h0 = h0 ? h0 + n * H : nullptr;   // B == 1 on this path
-        a.c0 = c0 ? c0 + n * H : nullptr;
+        a.h0 = h0 ? h0 + m->soff(n) : nullptr;   // B == 1 on this path
+        a.c0 = c0 ? c0 + m->soff(n) : nullptr;
         a.y = yout; a.y_ld = y_ld;
-        a.hT = hT ? hT + n * H : nullptr;
-        a.cT = cT ? cT + n * H : nullptr;
+        a.hT = hT ? hT + m->soff(n) : nullptr;
+        a.cT = cT ? cT + m->soff(n) : nullptr;
     };
 
     for (int l = 0; l < L; ++l) {
+        const int H = m->hid(l);
         const int D = m->in_dim(l);
         const void* X = (l == 0) ? x : (prev_has_bf16 ? (const void*)Ybf[(l - 1) & 1] : (const void*)Ybuf[(l - 1) & 1]);
         const bool x_is_bf16 = bf16 && (l == 0 || prev_has_bf16);
@@ -973,7 +1027,8 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
         char tag[128];
 
         // ---- batch 1, row-compressed, two stacked unidirectional layers in one launch (diagonal wavefront)
-        if (try_persist && Dn == 1 && l + 1 < L && sparse_ok(m->ld[l], D, 2) && sparse_ok(m->ld[l + 1], D, 2)) {
+        if (try_persist && Dn == 1 && l + 1 < L && m->hid(l + 1) == H && sparse_ok(m->ld[l], H, D, 2) &&
+            sparse_ok(m->ld[l + 1], H, D, 2)) {
             ProfSpan span(m, s, 1);
             int rc = take_tags(T);
             if (rc != LSTM_OK) return rc;
@@ -997,7 +1052,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
         for (int d = 0; d < Dn; ++d) {
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             if (try_persist) {
-                if (w.wh.compressed) mode[d] = sparse_ok(w, D, 1) ? 1 : 0;
+                if (w.wh.compressed) mode[d] = sparse_ok(w, H, D, 1) ? 1 : 0;
                 else if (persist_b1_dense_fusable(H, D)) mode[d] = 2;
                 else if (persist_b1_dense_supported(H)) mode[d] = 3;
             }
@@ -1050,9 +1105,10 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
         if (dense_bf16 && m->plan != LSTM_PLAN_STEPWISE && persist_mfma_supported(B, H)) {
             // time loop on the device: W_h stays in registers, h_t travels through flagged exchange buffers
             uint16_t* Yb = Ybf[l & 1];
-            if (!mflags_clean) {
+            if (!mflags_clean || mflags_H != H) {
                 HIP_TRY(m, launch_fill_f32((float*)mflags, persist_mfma_flag_count(B, H), 0.0f, s));
                 mflags_clean = true;
+                mflags_H = H;
                 mtag = 0;
             }
             for (int d = 0; d < Dn; ++d) {
@@ -1062,14 +1118,14 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 PersistMfmaArgs a{};
                 a.P = P[d];
                 a.Wh = (const uint16_t*)w.wh.dense;
-                a.c0 = c0 ? c0 + n * B * H : nullptr;
+                a.c0 = c0 ? c0 + m->soff(n) * B : nullptr;
                 // the layer above reads the bf16 copy; only the last layer's fp32 sequence leaves the library
                 a.y = (l == L - 1) ? Yout + (size_t)d * H : nullptr;
                 a.y_ld = y_ld;
                 a.yb = (l == L - 1) ? nullptr : Yb + (size_t)d * H;
                 a.yb_ld = y_ld;
-                a.hT = hT ? hT + n * B * H : nullptr;
-                a.cT = cT ? cT + n * B * H : nullptr;
+                a.hT = hT ? hT + m->soff(n) * B : nullptr;
+                a.cT = cT ? cT + m->soff(n) * B : nullptr;
                 a.hx = hx;
                 a.flags = mflags;
                 a.xcc_ids = (unsigned long long*)(mflags + persist_mfma_ids_offset(B, H));
@@ -1080,7 +1136,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 mtag += (unsigned)T;
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=dense,rec=persist-mfma-bf16;", l, d);
                 m->last_plan += tag;
-                HIP_TRY(m, launch_persist_mfma_bf16(a, h0 ? h0 + n * B * H : nullptr, m->launch_mode() != 0, s));
+                HIP_TRY(m, launch_persist_mfma_bf16(a, h0 ? h0 + m->soff(n) * B : nullptr, m->launch_mode() != 0, s));
             }
             prev_has_bf16 = true;
             continue;
@@ -1091,10 +1147,10 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 const LayerDir& w = m->ld[(size_t)l * Dn + d];
                 const size_t n = (size_t)l * Dn + d;
                 ProfSpan span(m, s, 1);
-                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
+                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + m->soff(n) * B, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
                 else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
                 uint16_t* hb0d = hb0 + (size_t)d * B * H;
-                if (h0) HIP_TRY(m, launch_f32_to_bf16(h0 + n * B * H, H, hb0d, H, B, H, s));
+                if (h0) HIP_TRY(m, launch_f32_to_bf16(h0 + m->soff(n) * B, H, hb0d, H, B, H, s));
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=dense,rec=stepwise-mfma-bf16;", l, d);
                 m->last_plan += tag;
                 for (int step = 0; step < T; ++step) {
@@ -1115,8 +1171,8 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     a.y_ld = y_ld;
                     a.hb_t = Yb + (size_t)t * B * y_ld + (size_t)d * H;
                     a.hb_ld = y_ld;
-                    a.hT = hT ? hT + n * B * H : nullptr;
-                    a.cT = cT ? cT + n * B * H : nullptr;
+                    a.hT = hT ? hT + m->soff(n) * B : nullptr;
+                    a.cT = cT ? cT + m->soff(n) * B : nullptr;
                     a.last = (step == T - 1);
                     a.t = t;
                     a.B = B;
@@ -1161,9 +1217,10 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 pb_ok = found;
             }
             if (pb_ok) {
-                if (!bslots_clean) {
+                if (!bslots_clean || bslots_H != H) {   // another width is another layout: start from zero again
                     HIP_TRY(m, launch_fill_u64(bslots, align256(ws.slot_bytes) / sizeof(unsigned long long), 0ull, s));
                     bslots_clean = true;
+                    bslots_H = H;
                     btag = 0;
                 }
                 PersistBatchedArgs a{};
@@ -1177,11 +1234,11 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     } else {
                         a.d[d].ell_val = w.wh.ell_val; a.d[d].ell_col = w.wh.ell_col; a.d[d].slots = w.wh.slots;
                     }
-                    a.d[d].h0 = h0 ? h0 + n * B * H : nullptr;
-                    a.d[d].c0 = c0 ? c0 + n * B * H : nullptr;
+                    a.d[d].h0 = h0 ? h0 + m->soff(n) * B : nullptr;
+                    a.d[d].c0 = c0 ? c0 + m->soff(n) * B : nullptr;
                     a.d[d].y = Yout + (size_t)d * H; a.d[d].y_ld = y_ld;
-                    a.d[d].hT = hT ? hT + n * B * H : nullptr;
-                    a.d[d].cT = cT ? cT + n * B * H : nullptr;
+                    a.d[d].hT = hT ? hT + m->soff(n) * B : nullptr;
+                    a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
                     a.d[d].reverse = d;
                     std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-csr%s(u%d,b%d);", l, d,
                                   (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
@@ -1211,7 +1268,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 const LayerDir& w = m->ld[(size_t)l * Dn + d];
                 const size_t n = (size_t)l * Dn + d;
                 ev[d] = w.wh.ell_val; ec[d] = w.wh.ell_col; sl[d] = w.wh.slots;
-                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + n * B * H, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
+                if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + m->soff(n) * B, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
                 else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=stepwise-csr-paired;", l, d,
                               (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr");
@@ -1224,7 +1281,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     const int t = d ? (T - 1 - step) : step;
                     a[d].P = P[d];
                     if (step == 0) {
-                        a[d].h_prev = h0 ? h0 + n * B * H : nullptr;
+                        a[d].h_prev = h0 ? h0 + m->soff(n) * B : nullptr;
                         a[d].h_prev_ld = H;
                     } else {
                         const int tp = d ? t + 1 : t - 1;
@@ -1234,8 +1291,8 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     a[d].c = cbuf[d];
                     a[d].y_t = Yout + (size_t)t * B * y_ld + (size_t)d * H;
                     a[d].y_ld = y_ld;
-                    a[d].hT = hT ? hT + n * B * H : nullptr;
-                    a[d].cT = cT ? cT + n * B * H : nullptr;
+                    a[d].hT = hT ? hT + m->soff(n) * B : nullptr;
+                    a[d].cT = cT ? cT + m->soff(n) * B : nullptr;
                     a[d].last = (step == T - 1);
                     a[d].t = t;
                     a[d].B = B;
@@ -1250,10 +1307,10 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
         for (int d = 0; d < Dn; ++d) {
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             const size_t n = (size_t)l * Dn + d;
-            const float* h0n = h0 ? h0 + n * B * H : nullptr;
-            const float* c0n = c0 ? c0 + n * B * H : nullptr;
-            float* hTn = hT ? hT + n * B * H : nullptr;
-            float* cTn = cT ? cT + n * B * H : nullptr;
+            const float* h0n = h0 ? h0 + m->soff(n) * B : nullptr;
+            const float* c0n = c0 ? c0 + m->soff(n) * B : nullptr;
+            float* hTn = hT ? hT + m->soff(n) * B : nullptr;
+            float* cTn = cT ? cT + m->soff(n) * B : nullptr;
             static const char* const names[4] = {"stepwise", "persist_b1", "persist_b1", "persist_b1"};
             std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s%s,rec=%s-%s%s;", l, d, (mode[d] == 1 || mode[d] == 2) ? "fused-" : "",
                           (w.wx.compressed && !(w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ) ? "csr" : "dense",
@@ -1353,7 +1410,7 @@ int lstm_get_compressed(const lstm_t* m, int layer, int direction, int which, in
     if (!row_ptr && !col && !val) return LSTM_OK;
     if (!row_ptr || !col || !val) return fail(m, LSTM_ERR_ARG, "lstm_get_compressed: pass all of row_ptr, col, val or none");
     // translate packed row order (4j+q) back to the ABI order (q*H + j); the hidden layers of an H-LSTM have G units
-    const int H = (m->G > 0 && which != 2) ? m->G : m->H;
+    const int H = (m->G > 0 && which != 2) ? m->ghid(layer) : m->hid(layer);
     int64_t pos = 0;
     for (int r = 0; r < 4 * H; ++r) {
         const int rp = 4 * (r % H) + (r / H);

@@ -261,3 +261,43 @@ def matmul_operands(n: int, batch: int, keep: Optional[float], seed: int = 0):
     M = None if keep is None else (rng.random((n, n)) < keep).astype(np.uint8)
     X = rng.standard_normal((batch, n)).astype(np.float32)
     return X, W, M
+
+
+def make_layers_case(input_dim: int, hiddens: List[int], bidirectional: bool, T: int, B: int, a: float = 0.3,
+                     keep: Optional[float] = None, gate_hiddens: Optional[List[int]] = None, k: int = 0,
+                     random_state: bool = True):
+    """A stack whose layers have their own widths (what row/column pruning of the paper's Section 4 leaves behind:
+    every layer shrinks by its own amount).  Draw order as make_case, with layer l's shapes.
+    Returns (weights[(l, d)], x[T,B,input_dim], h0 list, c0 list): h0[n], c0[n] are [B, hiddens[l]] for n = l*ndir + d,
+    or None when random_state is off."""
+    ndir = 2 if bidirectional else 1
+    rng = np.random.Generator(np.random.PCG64(SEED_BASE + 1000 * 9 + k))
+    weights: Dict[Tuple[int, int], Dict[str, Optional[np.ndarray]]] = {}
+
+    def draw(shape):
+        Wm = rng.uniform(-a, a, shape).astype(np.float32)
+        Mm = (rng.random(shape) < keep).astype(np.uint8) if keep is not None else None
+        return Wm, Mm
+
+    for l, H in enumerate(hiddens):
+        D = input_dim if l == 0 else ndir * hiddens[l - 1]
+        for d in range(ndir):
+            if gate_hiddens is not None:
+                G = gate_hiddens[l]
+                W1x, M1x = draw((4 * G, D))
+                W1h, M1h = draw((4 * G, H))
+                b1 = rng.uniform(-a, a, 4 * G).astype(np.float32)
+                W2, M2 = draw((4 * H, G))
+                b2 = rng.uniform(-a, a, 4 * H).astype(np.float32)
+                weights[(l, d)] = dict(W1x=W1x, M1x=M1x, W1h=W1h, M1h=M1h, b1=b1, W2=W2, M2=M2, b2=b2)
+            else:
+                Wx, Mx = draw((4 * H, D))
+                Wh, Mh = draw((4 * H, H))
+                b = rng.uniform(-a, a, 4 * H).astype(np.float32)
+                weights[(l, d)] = dict(Wx=Wx, Mx=Mx, Wh=Wh, Mh=Mh, b=b)
+    x = rng.standard_normal((T, B, input_dim)).astype(np.float32)
+    h0 = c0 = None
+    if random_state:
+        h0 = [rng.uniform(-0.5, 0.5, (B, hiddens[n // ndir])).astype(np.float32) for n in range(len(hiddens) * ndir)]
+        c0 = [rng.uniform(-0.5, 0.5, (B, hiddens[n // ndir])).astype(np.float32) for n in range(len(hiddens) * ndir)]
+    return weights, x, h0, c0
