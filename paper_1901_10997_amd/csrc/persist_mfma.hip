@@ -92,7 +92,9 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
 #pragma unroll
     for (int i = 0; i < MT; ++i) aoff[i] = (unsigned)(((kbase >> 4) * Bp + m0 + i * 32 + fr) * 16 + 8 * fk);
     unsigned* const myflag = a.flags + (size_t)tile_m * gn + tile_n;
-    const unsigned* const pollflag = a.flags + (size_t)tile_m * gn + (lane < gn ? lane : gn - 1);
+    // flags of the tiles whose units this wave multiplies: tiles kbase / UT .. (kbase + H/8 - 1) / UT of the row block
+    const int ft0 = kbase / UT, ft1 = (kbase + H / NW - 1) / UT;
+    const unsigned* const pollflag = a.flags + (size_t)tile_m * gn + (ft0 + lane <= ft1 ? ft0 + lane : ft1);
 
     bool same_xcd = false;
     if (a.xcd_local)
@@ -118,23 +120,24 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
 
         if (s > 0 || a.has_h0) {
             if (s > 0) {
-                if (wave == 0) {
-                    const unsigned want = a.tag_base + (unsigned)s;
-                    unsigned spins = 0;
-                    // "at least": a producer that has seen everybody's flag of this step may finish the step and raise its
-                    // flag to the next tag before a slower poller has looked; what that poller needs is still there (the
-                    // next h goes to the other buffer, and nobody can get two steps ahead of it)
-                    while ((int)(__hip_atomic_load(pollflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - want) < 0) {
-                        if (++spins > a.spin_limit) {
-                            __hip_atomic_store(a.timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            break;
-                        }
-                        if ((spins & 255u) == 0 &&
-                            __hip_atomic_load(a.timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
-                            break;
+                // every wave waits for the tiles that produce its own K slice (H/8 units: H/256 tiles, at least one)
+                // and goes on by itself: no workgroup barrier between the flags and the operand loads
+                const unsigned want = a.tag_base + (unsigned)s;
+                unsigned spins = 0;
+                // "at least": a producer that has seen everybody's flag of this step may finish the step and raise its
+                // flag to the next tag before a slower poller has looked; what that poller needs is still there (the
+                // next h goes to the other buffer, and nobody can get two steps ahead of it)
+                for (;;) {
+                    const int behind = (int)(__hip_atomic_load(pollflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - want) < 0;
+                    if (!__builtin_amdgcn_ballot_w64(behind != 0)) break;
+                    if (++spins > a.spin_limit) {
+                        __hip_atomic_store(a.timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
                     }
+                    if ((spins & 255u) == 0 &&
+                        __hip_atomic_load(a.timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+                        break;
                 }
-                __syncthreads();
             }
             const uint16_t* hx = a.hx + (size_t)(s & 1) * xbuf;
             uint4 fa[MT][KS];
@@ -174,6 +177,7 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
         __syncthreads();
         uint16_t* hxo = a.hx + (size_t)((s + 1) & 1) * xbuf;
         const bool last = (s == a.T - 1);
+        float hkeep[PAIRS];
 #pragma unroll
         for (int r = 0; r < PAIRS; ++r) {
             const int m = pb[r] - m0, u = pu[r];
@@ -197,23 +201,28 @@ __global__ __launch_bounds__(512) void persist_mfma_bf16_kernel(PersistMfmaArgs 
             if ((u & 1) == 0 && !last)
                 exchange_store(reinterpret_cast<unsigned*>(hxo + ((size_t)(((n0 >> 2) + u) >> 4) * Bp + pb[r]) * 16 + (u & 15)),
                                hbits | (other << 16), same_xcd);
-            if (pb[r] < a.B) {
-                const int j = (n0 >> 2) + u;
-                const size_t row = (size_t)t * a.B + pb[r];
-                if (a.y) a.y[row * a.y_ld + j] = hn;
-                if (a.yb) a.yb[row * a.yb_ld + j] = (uint16_t)hbits;
-                if (last) {
-                    if (a.hT) a.hT[(size_t)pb[r] * H + j] = hn;
-                    if (a.cT) a.cT[(size_t)pb[r] * H + j] = cn;
-                }
-            }
+            hkeep[r] = hn;
         }
         if (!last) {
-            // stores acknowledged by every wave, then the tile's flag; the barrier also keeps the next step's
+            // exchange stores acknowledged by every wave, then the tile's flag; the barrier also keeps the next step's
             // partial tiles out of LDS until every thread has read this step's
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
             __syncthreads();
             if (tid == 0) exchange_store(myflag, a.tag_base + (unsigned)s + 1u, same_xcd);
+        }
+        // outputs after the publication: nothing on the way of h_t
+#pragma unroll
+        for (int r = 0; r < PAIRS; ++r) {
+            if (pb[r] < a.B) {
+                const int j = (n0 >> 2) + pu[r];
+                const size_t row = (size_t)t * a.B + pb[r];
+                if (a.y) a.y[row * a.y_ld + j] = hkeep[r];
+                if (a.yb) a.yb[row * a.yb_ld + j] = (uint16_t)f32_to_bf16_bits(hkeep[r]);
+                if (last) {
+                    if (a.hT) a.hT[(size_t)pb[r] * H + j] = hkeep[r];
+                    if (a.cT) a.cT[(size_t)pb[r] * H + j] = c[r];
+                }
+            }
         }
     }
 }

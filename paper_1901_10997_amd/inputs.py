@@ -189,8 +189,9 @@ def select_batch(case: Case, cols: List[int]) -> Case:
 def structure_masks(case: Case, unit_frac: float, input_frac: float, k: int = 0, gate_unit_frac: Optional[float] = None):
     """The same case after a row/column pruning outcome has been stamped onto its masks.
 
-    In every (layer, direction) a random subset of round(unit_frac * H) hidden units survives (all of them of one
-    size, the sets differ), and round(input_frac * D0) of the input features; in an H-LSTM workload also
+    In every (layer, direction) a random subset of round(unit_frac * H) hidden units survives (of one size per layer,
+    the sets differ; unit_frac may be a list with one fraction per layer), and round(input_frac * D0) of the input
+    features; in an H-LSTM workload also
     round(gate_unit_frac * G) of the hidden-layer units inside the gates (the same index set for the four gates of a
     cell; default: unit_frac).  A connection stays active iff the case's own mask keeps it (dense workloads: every
     connection), its row belongs to a surviving unit and its column to a surviving source (input feature, unit of
@@ -202,17 +203,19 @@ def structure_masks(case: Case, unit_frac: float, input_frac: float, k: int = 0,
     w = case.w
     rng = np.random.Generator(np.random.PCG64(SEED_BASE + 7777 * w.cid + 31 * k + 5))
     H, D0, G = w.hidden, w.input_dim, w.gate_hidden
-    Hc = max(1, int(round(unit_frac * H)))
+    fracs = [unit_frac] * w.layers if np.isscalar(unit_frac) else list(unit_frac)   # one per layer when a list
+    assert len(fracs) == w.layers
     Dc = max(1, int(round(input_frac * D0)))
     feats = np.sort(rng.permutation(D0)[:Dc]).astype(np.int64)
     units = {}
     for l in range(w.layers):
+        Hc = max(1, int(round(fracs[l] * H)))
         for d in range(w.ndir):
             units[(l, d)] = np.sort(rng.permutation(H)[:Hc]).astype(np.int64)
     gate_units = {}
     if G > 0:
-        Gc = max(1, int(round((unit_frac if gate_unit_frac is None else gate_unit_frac) * G)))
         for l in range(w.layers):
+            Gc = max(1, int(round((fracs[l] if gate_unit_frac is None else gate_unit_frac) * G)))
             for d in range(w.ndir):
                 gate_units[(l, d)] = np.sort(rng.permutation(G)[:Gc]).astype(np.int64)
 

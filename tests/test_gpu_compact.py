@@ -169,3 +169,62 @@ def test_row_column_pruning_then_compaction_on_the_device(M, N, p, seed):
         np.testing.assert_array_equal(g, r)
     assert got[0].size == M - rows and got[1].size == N - cols
     assert got[3].all()                                                       # what is left is dense
+
+
+@pytest.mark.parametrize("bidir,H,D,T,Bsz,fracs", [
+    (False, 96, 40, 9, 1, [0.8, 0.5, 0.65]),      # three layers that shrink by different amounts, batch 1
+    (True, 64, 48, 7, 3, [0.75, 0.9]),            # bidirectional: the upper layer reads both directions' kept units
+    (False, 1500, 400, 5, 1, [0.798, 0.4173]),    # 1500 -> 1197 in one layer and -> 626 in the other (Sections 5.1, 5.2)
+])
+def test_layers_pruned_to_different_widths_run_as_one_model(bidir, H, D, T, Bsz, fracs):
+    """Row/column pruning leaves every layer its own width.  Each matrix is compacted on the device, the compacted
+    matrices make a model with per-layer widths (lstm_create_layers), and its outputs equal the oracle's outputs of
+    the full-size pruned model at the kept units."""
+    import torch
+    layers, ndir = len(fracs), 2 if bidir else 1
+    w = inputs.shrink(inputs.c2(Bsz), layers=layers, bidirectional=bidir, input_dim=D, hidden=H, T=T, B=Bsz, keep=0.6,
+                      bias="uniform", a=min(0.4, 1.5 / np.sqrt(H)))
+    case = inputs.make_case(w, k=6, random_state=True)
+    pruned, units, feats = inputs.structure_masks(case, fracs, 0.7925, k=3)
+    weights, widths = {}, []
+    for l in range(layers):
+        for d in range(ndir):
+            cur = pruned.weights[(l, d)]
+            rx, cx, Wxc, Mxc = gpu_compact(cur["Wx"], cur["Mx"], 4)
+            rh, ch, Whc, Mhc = gpu_compact(cur["Wh"], cur["Mh"], 4)
+            np.testing.assert_array_equal(rx, units[(l, d)])
+            np.testing.assert_array_equal(rh, units[(l, d)])
+            np.testing.assert_array_equal(ch, units[(l, d)])
+            below = feats if l == 0 else np.concatenate([dd * H + units[(l - 1, dd)] for dd in range(ndir)])
+            np.testing.assert_array_equal(cx, below)
+            b = np.ascontiguousarray(cur["b"].reshape(4, H)[:, rh].reshape(-1))
+            weights[(l, d)] = dict(Wx=Wxc, Mx=Mxc, Wh=Whc, Mh=Mhc, b=b)
+        widths.append(len(units[(l, 0)]))
+    if H == 1500:
+        assert widths == [1197, 626] and len(feats) == 317
+    assert len(set(widths)) > 1
+    ref_y, ref_h, ref_c = orc.forward_case(pruned)
+    last = layers - 1
+    ycols = np.concatenate([d * H + units[(last, d)] for d in range(ndir)])
+    dev = torch.device("cuda:0")
+    m = B.Lstm(layers, len(feats), widths, bidir)
+    m.set_weights_from(weights)
+    state = lambda s: torch.from_numpy(np.concatenate(
+        [s[l * ndir + d][:, units[(l, d)]].ravel() for l in range(layers) for d in range(ndir)])).to(dev)
+    y, hT, cT = m.forward(torch.from_numpy(np.ascontiguousarray(pruned.x[:, :, feats])).to(dev), state(pruned.h0),
+                          state(pruned.c0))
+    desc = B.lstm_describe_plan(m.handle)
+    m.close()
+    hT, cT = hT.cpu().numpy(), cT.cpu().numpy()
+    off = 0
+    for l in range(layers):
+        for d in range(ndir):
+            n, Hc = l * ndir + d, widths[l]
+            for name, got, ref in (("hT", hT, ref_h), ("cT", cT, ref_c)):
+                g = got[off:off + Bsz * Hc].reshape(Bsz, Hc).astype(np.float64)
+                dlt = g - ref[n][:, units[(l, d)]]
+                assert np.max(np.abs(dlt)) <= 1e-5, (desc, name, l, d, float(np.max(np.abs(dlt))))
+            off += Bsz * Hc
+    assert off == hT.size
+    dy = y.cpu().numpy().astype(np.float64) - ref_y[:, :, ycols]
+    assert np.max(np.abs(dy)) <= 1e-5 and np.linalg.norm(dy) <= 1e-4 * np.linalg.norm(ref_y[:, :, ycols]), desc
