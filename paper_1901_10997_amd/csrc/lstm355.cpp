@@ -205,6 +205,12 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
     auto build_slices = [&](int S, std::vector<float>& ev, std::vector<uint16_t>& ec) {
         ev.assign((size_t)rows * S * 64, 0.0f);
         ec.assign((size_t)rows * S * 64, 0);
+        // empty positions (value 0) point at the column of their own lane's bank: pointing all of them at column 0
+        // would make them collide, in every pass, with the real entry of bank 0
+        for (size_t pos = 0; pos < ec.size(); ++pos) {
+            const int c = (int)(pos & 31);
+            ec[pos] = (uint16_t)(c < cols ? c : 0);
+        }
         std::vector<char> used((size_t)S * 64);
         std::vector<int64_t> leftover;
         for (int rp = 0; rp < rows; ++rp) {
