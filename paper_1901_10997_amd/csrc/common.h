@@ -34,6 +34,12 @@ struct PackedMat {
     uint32_t* ovf_ent = nullptr;  // device [overflow entries]
     float* ovf_val = nullptr;
     std::vector<int32_t> h_ovf_ptr;   // host copy of ovf_ptr
+    // Quarter-wave form for the small-batch kernel (recurrent matrices whose rows keep at most 256 entries): the four
+    // gate rows of unit j share 64-lane slots, gate q on lanes 16q..16q+15, so that a slot is one gather for all four
+    // gates and a row's partial sums stay inside a 16-lane row.  [rows/4][q16_slots][64]; q16_slots == 0: not built.
+    int q16_slots = 0;            // even, ceil(max_row_nnz / 16) rounded up
+    float* q16_val = nullptr;
+    uint16_t* q16_col = nullptr;
     // host copy of the compressed structure in packed row order (for read-back)
     std::vector<int64_t> h_row_ptr;
     std::vector<int32_t> h_col;
@@ -315,6 +321,10 @@ struct PersistBatchedDir {
     const int32_t* ovf_ptr;
     const uint32_t* ovf_ent;
     const float* ovf_val;
+    // quarter-wave form [H][q16_slots][64] (launch_persist_batched_q16 reads these instead of the slices above)
+    const float* q16_val;
+    const uint16_t* q16_col;
+    int q16_slots;
     const float* h0;           // [B][H] or nullptr
     const float* c0;
     float* y;                  // h_t -> y[(t*B + b)*y_ld + j]  (already offset to this direction's columns)
@@ -330,7 +340,8 @@ struct PersistBatchedArgs {
     int ndir, xcd_local;       // directions in the grid; block ids grouped by XCD (filled by the launcher)
     int device_scope_only;     // 1: publish with device-scope stores even where a group shares an XCD (A/B switch)
     int round_h_bf16;
-    unsigned long long* xchg;  // [ndir][2][B][H] slots, zero or older tags only
+    unsigned long long* xchg;  // slots, zero or older tags only: 2 (B + 3) H per direction ([2][B][H] in the 64-lane-slice
+                               // kernel, [2][batch group][H][columns of a group] in the quarter-wave kernel)
     unsigned long long* xcc_ids;  // [ndir * bg][64] tagged slots (XCD id of each unit group's workgroup), zero or older tags only
     unsigned tag_base;
     int* timeout_flag;
@@ -338,6 +349,9 @@ struct PersistBatchedArgs {
 };
 bool persist_batched_plan(int B, int H, int nz, int ndir, int* upw, int* bw, int* ug, int* bg);
 hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int cooperative, hipStream_t s);
+// the same recurrence on the quarter-wave form; `slots` = the largest q16_slots of the directions (even, <= 16)
+bool persist_batched_q16_plan(int B, int H, int slots, int ndir, int* upw, int* bw, int* ug, int* bg);
+hipError_t launch_persist_batched_q16(PersistBatchedArgs& a, int ndir, int slots, int cooperative, hipStream_t s);
 
 // H-LSTM at small batch (B >= 2), W1h and W2 row-compressed and register-resident, time loop on the device, every
 // direction of a layer in one launch.

@@ -130,6 +130,45 @@ __device__ __forceinline__ void gather_tagged_interleave(const u64* slots, int n
     else gather_tagged_interleave_nf<4>(slots, n, want, dst, rows, stride, tid, nthreads, timeout_flag, spin_limit);
 }
 
+// As gather_tagged for slots stored in the order of their destination (slot e -> dst[e]), where slot e belongs to
+// column e % BW of a batch group that may hold fewer than BW columns: the slots of the missing columns are never
+// published and are skipped.
+template <int NF, int BW>
+__device__ __forceinline__ void gather_tagged_cols(const u64* slots, int n, int bw, unsigned want, float* dst, int tid,
+                                                   int nthreads, int* timeout_flag, unsigned spin_limit)
+{
+    for (int e0 = tid; e0 < n; e0 += NF * nthreads) {
+        u64 v[NF];
+        unsigned spins = 0;
+        bool ok;
+        do {
+            ok = true;
+#pragma unroll
+            for (int u = 0; u < NF; ++u) {
+                const int e = e0 + u * nthreads;
+                const bool live = e < n && (e & (BW - 1)) < bw;
+                v[u] = live ? __hip_atomic_load(slots + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ((u64)want << 32);
+                ok = ok && ((unsigned)(v[u] >> 32) == want);
+            }
+            if (!ok) {
+                ++spins;
+                if (spins > spin_limit) {
+                    __hip_atomic_store(timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                if ((spins & 63u) == 0 &&
+                    __hip_atomic_load(timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+                    break;
+            }
+        } while (!ok);
+#pragma unroll
+        for (int u = 0; u < NF; ++u) {
+            const int e = e0 + u * nthreads;
+            if (e < n && (e & (BW - 1)) < bw) dst[e] = __uint_as_float((unsigned)v[u]);
+        }
+    }
+}
+
 // ---- exchange inside one XCD -------------------------------------------------------------------------------------
 // The compute units of an XCD share one L2.  A store at workgroup scope is written through the compute unit's vector
 // cache into that L2 and stays there; an agent-scope load from any compute unit of the same XCD bypasses its vector

@@ -26,6 +26,7 @@ struct lstm355 {
     int* timeout_flag = nullptr;         // device int
     unsigned spin_limit = 1u << 22;
     int device_scope_only = 0;           // 1: no hand-over through an XCD's L2 (environment LSTM355_L2_HANDOVER=0)
+    int use_q16 = 1;                     // small-batch recurrence on the quarter-wave form (environment LSTM355_Q16=0: 64-lane slices)
     int plan = LSTM_PLAN_AUTO;
     int waves_per_group = 0;
     int cooperative = 0;
@@ -117,6 +118,8 @@ static void free_mat(PackedMat& p)
     if (p.ovf_ptr) (void)hipFree(p.ovf_ptr);
     if (p.ovf_ent) (void)hipFree(p.ovf_ent);
     if (p.ovf_val) (void)hipFree(p.ovf_val);
+    if (p.q16_val) (void)hipFree(p.q16_val);
+    if (p.q16_col) (void)hipFree(p.q16_col);
     p = PackedMat();
 }
 
@@ -133,7 +136,7 @@ static hipError_t upload(T** dst, const std::vector<T>& src)
 
 // Pack one matrix W[4H][cols] (ABI row order q*H + j) with its optional mask into device storage.
 static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t* mask, int H, int cols, bool compressed,
-                       bool bf16, bool keep_dense)
+                       bool bf16, bool keep_dense, bool quarter_rows = false)
 {
     free_mat(out);
     const int rows = 4 * H;
@@ -291,6 +294,92 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
             break;
         }
     }
+    // Quarter-wave form for the small-batch kernel: slot s of unit j is one 64-lane gather that serves all four gate
+    // rows, gate q on lanes 16q..16q+15.  An 8-byte gather serves lanes 0..31 (gates 0, 1) and 32..63 (gates 2, 3) in
+    // separate passes whose 32 columns must differ modulo 32.  Within a pass bank b (= column mod 32) belongs to lane
+    // b mod 16 of one of the two rows: in slot s row q owns the banks of half (s + q) mod 2.  An entry goes to a
+    // position that owns its bank (S/2 slots per row and bank).  What does not fit there is placed in a free lane of a
+    // slot in which the OTHER row of the pass owns the entry's bank but has nothing to put there: that position's
+    // filler (value 0) is pointed at the entry's own column, the two lanes read one address, and nothing collides.  Among
+    // the free lanes one whose bits 2 and 3 differ in parity from the owner's is preferred, which keeps the 16-byte
+    // gather (four passes of 16 lanes, picked by lane bit 5 and the parity of bits 2..4) free of collisions as well.
+    // Only an entry for which no such slot exists takes any free position, from the end.
+    if (quarter_rows && max_nnz <= 256 && rows >= 4) {
+        const int S = std::max(2, 2 * ((max_nnz + 31) / 32));
+        const int units = rows / 4;
+        std::vector<float> qv((size_t)units * S * 64, 0.0f);
+        std::vector<uint16_t> qc((size_t)units * S * 64, 0);
+        std::vector<char> used((size_t)S * 64), aliased((size_t)S * 64);
+        std::vector<int64_t> leftover[4];
+        auto par23 = [](int j) { return ((j >> 2) ^ (j >> 3)) & 1; };
+        for (int u = 0; u < units; ++u) {
+            std::fill(used.begin(), used.end(), 0);
+            std::fill(aliased.begin(), aliased.end(), 0);
+            float* uv = qv.data() + (size_t)u * S * 64;
+            uint16_t* uc = qc.data() + (size_t)u * S * 64;
+            for (int sl = 0; sl < S; ++sl)
+                for (int ln = 0; ln < 64; ++ln) {
+                    const int c = (ln & 15) + 16 * ((sl + (ln >> 4)) & 1);   // a column of the bank this position owns
+                    uc[sl * 64 + ln] = (uint16_t)(c < cols ? c : 0);
+                }
+            for (int q = 0; q < 4; ++q) {
+                const int rp = 4 * u + q;
+                int fill[32] = {0};
+                leftover[q].clear();
+                for (int64_t e = out.h_row_ptr[rp]; e < out.h_row_ptr[rp + 1]; ++e) {
+                    const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
+                    if (fill[bank] < S / 2) {
+                        const int sl = 2 * fill[bank] + ((hb + q) & 1);
+                        ++fill[bank];
+                        const int pos = sl * 64 + 16 * q + j;
+                        used[pos] = 1;
+                        uv[pos] = out.h_val[e];
+                        uc[pos] = (uint16_t)out.h_col[e];
+                    } else {
+                        leftover[q].push_back(e);
+                    }
+                }
+            }
+            for (int q = 0; q < 4; ++q) {
+                for (int64_t e : leftover[q]) {
+                    const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
+                    int best = -1, best_owner = -1;
+                    for (int sl = ((hb + (q ^ 1)) & 1); sl < S && best < 0; sl += 2) {   // slots where the other row owns `bank`
+                        const int owner = sl * 64 + 16 * (q ^ 1) + j;
+                        if (used[owner] || aliased[owner]) continue;
+                        int any = -1;
+                        for (int jj = 0; jj < 16; ++jj) {
+                            const int pos = sl * 64 + 16 * q + jj;
+                            if (used[pos] || aliased[pos]) continue;
+                            if (par23(jj) != par23(j)) { best = pos; break; }
+                            if (any < 0) any = pos;
+                        }
+                        if (best < 0) best = any;
+                        if (best >= 0) best_owner = owner;
+                    }
+                    if (best >= 0) {
+                        aliased[best_owner] = 1;
+                        uc[best_owner] = (uint16_t)out.h_col[e];
+                    } else {
+                        // no such slot: any free position of the row, from the end; a filler that serves the other row's
+                        // entry is given up only when nothing else is left (the row holds at most 16 S entries)
+                        for (int pass = 0; pass < 2 && best < 0; ++pass)
+                            for (int t = S * 16 - 1; t >= 0 && best < 0; --t) {
+                                const int pos = (t / 16) * 64 + 16 * q + (t & 15);
+                                if (!used[pos] && (pass == 1 || !aliased[pos])) best = pos;
+                            }
+                        aliased[best] = 0;
+                    }
+                    used[best] = 1;
+                    uv[best] = out.h_val[e];
+                    uc[best] = (uint16_t)out.h_col[e];
+                }
+            }
+        }
+        out.q16_slots = S;
+        HIP_TRY(m, upload(&out.q16_val, qv));
+        HIP_TRY(m, upload(&out.q16_col, qc));
+    }
     return LSTM_OK;
 }
 
@@ -333,6 +422,7 @@ static int create_model(int layers, int input_dim, const int* hidden_dims, const
         if (v > 0) m->spin_limit = (unsigned)v;
     }
     if (const char* l2 = std::getenv("LSTM355_L2_HANDOVER")) m->device_scope_only = (std::atoi(l2) == 0) ? 1 : 0;
+    if (const char* q = std::getenv("LSTM355_Q16")) m->use_q16 = (std::atoi(q) == 0) ? 0 : 1;
     hipError_t e = hipGetDevice(&m->device);
     // two cells (directions, or two stacked layers) x two parities; H-LSTM: h slots, then the 4G hidden-layer slots
     m->xchg_slots = (m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H) + 64;   // + XCD ids of a launch's workgroups
@@ -434,7 +524,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     // W_x is kept in both forms when compressed: large T*B projections run dense on the matrix cores
     int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16, true);
     if (rc != LSTM_OK) return rc;
-    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16, false);
+    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16, false, true);
     if (rc != LSTM_OK) return rc;
     std::vector<float> bp(rows);
     for (int rp = 0; rp < rows; ++rp) bp[rp] = b[(rp & 3) * H + (rp >> 2)];
@@ -530,8 +620,9 @@ static Workspace carve(const lstm_t* m, int T, int B)
     }
     w.hb0_off = off;
     if (m->dtype == LSTM_BF16) off += align256((size_t)m->Dn * B * H * sizeof(uint16_t));
-    // tagged exchange slots of the small-batch persistent recurrence: [Dn][2][B][H], then one slot per workgroup for
-    // the XCD ids, 64 per batch group
+    // tagged exchange slots of the small-batch persistent recurrence: per direction [2][batch groups][H][columns of a
+    // group] (ragged last group filled up: at most B + 3 columns), then one slot per workgroup for the XCD ids, 64 per
+    // batch group
     // (H-LSTM: h slots in [k][columns of a batch group] blocks padded to 256 bytes, ragged last group filled up,
     // then one flag per unit group, 64 per batch group, then the XCD id slots)
     w.slot_off = off;
@@ -539,7 +630,7 @@ static Workspace carve(const lstm_t* m, int T, int B)
         const size_t groups = (size_t)B / 2 + 1;
         w.slot_bytes = m->G > 0 ? (size_t)m->Dn * (((size_t)B + 3) * H * sizeof(unsigned long long) + groups * 256 +
                                                    groups * 64 * (sizeof(unsigned) + sizeof(unsigned long long)))
-                                : (size_t)m->Dn * (2 * (size_t)B * H + groups * 64) * sizeof(unsigned long long);
+                                : (size_t)m->Dn * (2 * ((size_t)B + 3) * H + groups * 64) * sizeof(unsigned long long);
         off += align256(w.slot_bytes);
     }
     // bf16 large-batch persistent recurrence: two exchange buffers of h_t and one flag per tile
@@ -1194,7 +1285,18 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             int nzmax = 0, upw = 0, bw = 0, ug = 0, bg = 0;
             bool pb_ok = B >= 2 && m->plan != LSTM_PLAN_STEPWISE;
             bool trimmed = false;
-            if (pb_ok) {
+            // quarter-wave form first (rows of at most 256 kept entries)
+            int q16 = 0;
+            if (pb_ok && m->use_q16) {
+                bool ok = true;
+                for (int d = 0; d < Dn && ok; ++d) {
+                    const PackedMat& p = m->ld[(size_t)l * Dn + d].wh;
+                    ok = p.compressed && p.q16_slots > 0;
+                    q16 = std::max(q16, p.q16_slots);
+                }
+                if (!ok || !persist_batched_q16_plan(B, H, q16, Dn, &upw, &bw, &ug, &bg)) q16 = 0;
+            }
+            if (pb_ok && q16 == 0) {
                 // first with the slices cut to the common row length (a wave takes at most 64 overflow entries over
                 // the units it owns), then with the full slices
                 bool found = false;
@@ -1234,7 +1336,9 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     const LayerDir& w = m->ld[(size_t)l * Dn + d];
                     const size_t n = (size_t)l * Dn + d;
                     a.d[d].P = P[d];
-                    if (trimmed && w.wh.slots_trim > 0) {
+                    if (q16) {
+                        a.d[d].q16_val = w.wh.q16_val; a.d[d].q16_col = w.wh.q16_col; a.d[d].q16_slots = w.wh.q16_slots;
+                    } else if (trimmed && w.wh.slots_trim > 0) {
                         a.d[d].ell_val = w.wh.ell_val_trim; a.d[d].ell_col = w.wh.ell_col_trim; a.d[d].slots = w.wh.slots_trim;
                         a.d[d].ovf_ptr = w.wh.ovf_ptr; a.d[d].ovf_ent = w.wh.ovf_ent; a.d[d].ovf_val = w.wh.ovf_val;
                     } else {
@@ -1246,16 +1350,21 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     a.d[d].hT = hT ? hT + m->soff(n) * B : nullptr;
                     a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
                     a.d[d].reverse = d;
-                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-csr%s(u%d,b%d);", l, d,
-                                  (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
-                                  trimmed ? "+ovf" : "", upw, bw);
+                    if (q16)
+                        std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16(s%d,u%d,b%d);", l, d,
+                                      (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr", q16, upw, bw);
+                    else
+                        std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-csr%s(u%d,b%d);", l, d,
+                                      (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
+                                      trimmed ? "+ovf" : "", upw, bw);
                     m->last_plan += tag;
                 }
                 a.T = T; a.B = B; a.H = H; a.round_h_bf16 = bf16;
-                a.xchg = bslots; a.xcc_ids = bslots + (size_t)Dn * 2 * B * H; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
+                a.xchg = bslots; a.xcc_ids = bslots + (size_t)Dn * 2 * (B + 3) * H; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 btag += (unsigned)T;
                 ProfSpan span(m, s, 1);
-                HIP_TRY(m, launch_persist_batched(a, Dn, nzmax, m->launch_mode(), s));
+                if (q16) HIP_TRY(m, launch_persist_batched_q16(a, Dn, q16, m->launch_mode(), s));
+                else HIP_TRY(m, launch_persist_batched(a, Dn, nzmax, m->launch_mode(), s));
                 continue;
             }
         }

@@ -298,6 +298,211 @@ __global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatc
     }
 }
 
+// ------------------------------------------------------------------------------------------------ quarter-wave rows
+// The same recurrence on the quarter-wave form of W_h: slot s of a unit is ONE gather that serves all four gate rows
+// (gate q on lanes 16q..16q+15), so a lane accumulates BW sums per unit instead of 4 BW, and a row's total is a
+// butterfly inside its 16 lanes (four DPP adds) that leaves gate q of pair p in lane 16q + p -- no lane swaps across
+// rows.  S = slots per unit (16 kept entries of each gate per slot).
+constexpr bool persist_batched_q16_xcd_capable(int s, int upw) { return s * upw <= 84; }
+
+template <int S, int UPW, int BW>
+__global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatchedArgs a)
+{
+    extern __shared__ float lds[];  // hbuf[H][BW] (the BW batch values of one k adjacent) | pub[BW][UPB]
+    constexpr int PAIRS = UPW * BW;
+    static_assert(PAIRS <= 16, "pairs must fit one 16-lane row");
+    static_assert(S % 2 == 0, "slots come in pairs (one per bank half)");
+    const int H = a.H, B = a.B;
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    const int upb = nwaves * UPW;
+    float* hbuf = lds;
+    float* pub = lds + (size_t)BW * H;
+    constexpr bool kXcd = persist_batched_q16_xcd_capable(S, UPW);
+    int dir, bgi, ugi;
+    if (kXcd && a.xcd_local) {
+        const int j = blockIdx.x >> 3;
+        const int g = (blockIdx.x & 7) + 8 * (j / a.ug);
+        if (g >= a.ndir * a.bg) return;     // padding ids take no part in the exchange
+        ugi = j % a.ug; dir = g / a.bg; bgi = g % a.bg;
+    } else {
+        const int per_dir = a.ug * a.bg;
+        dir = blockIdx.x / per_dir;
+        const int rem = blockIdx.x % per_dir;
+        bgi = rem / a.ug; ugi = rem % a.ug;
+    }
+    const PersistBatchedDir& D = a.d[dir];
+    const int b0 = bgi * BW;
+    const int bw = (B - b0) < BW ? (B - b0) : BW;         // columns actually present
+    const int u0 = ugi * upb + wave * UPW;                // first unit of this wave
+    // slots of this batch group: [parity][batch group][k][BW], i.e. in the order of the LDS copy of h
+    u64* const xchg = a.xchg + (size_t)dir * 2 * (B + 3) * H + (size_t)bgi * H * BW;
+    const size_t parity_stride = (size_t)a.bg * H * BW;
+
+    // kept weights of this wave's units: values in fp32 registers, columns as 16-bit LDS byte offsets of their h
+    // values, two to a register.  Every load is issued whatever the shape (clamped address, zeroed afterwards).
+    float wv[UPW][S];
+    unsigned wc[UPW][S / 2];
+    {
+        const int slots = D.q16_slots;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            const int unit = (u0 + u < H) ? (u0 + u) : (H - 1);
+            float tv[S];
+            unsigned tk[S];
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                const int ii = i < slots ? i : slots - 1;
+                const size_t idx = ((size_t)unit * slots + ii) * 64 + lane;
+                tv[i] = D.q16_val[idx];
+                tk[i] = D.q16_col[idx];
+            }
+#pragma unroll
+            for (int i = 0; i < S / 2; ++i) wc[u][i] = 0u;
+#pragma unroll
+            for (int i = 0; i < S; ++i) {
+                const bool live = (u0 + u < H) && i < slots;
+                wv[u][i] = live ? tv[i] : 0.f;
+                wc[u][i >> 1] |= ((live ? tk[i] : 0u) * (BW * 4u)) << (16 * (i & 1));
+            }
+        }
+    }
+    // lane 16*gate + pair: pair = local unit * BW + column
+    const int lp = lane & 15, row = lane >> 4;
+    const int pu = lp / BW, pb = lp % BW;
+    const bool pair_ok = lp < PAIRS && pb < bw && (u0 + pu) < H;
+    const int unit_l = u0 + pu;
+    float c = 0.f;
+    if (lane < 16 && pair_ok && D.c0) c = D.c0[(size_t)(b0 + pb) * H + unit_l];
+
+    // The direction is chosen by the block index, so `D` is addressed through memory: its fields are copied once
+    // and the outputs are written after the publication.
+    const float* const Pd_c = D.P;
+    float* const y_c = D.y;
+    const size_t y_ld_c = (size_t)D.y_ld;
+    float* const hT_c = D.hT;
+    float* const cT_c = D.cT;
+    const float* const h0_c = D.h0;
+    const int reverse = D.reverse;
+    bool same_xcd = false;
+    if (kXcd && a.xcd_local)
+        same_xcd = group_shares_xcd(a.xcc_ids + ((size_t)dir * a.bg + bgi) * 64, a.ug, ugi, a.tag_base + 1u, hbuf, tid,
+                                    nthreads, a.timeout_flag, a.spin_limit) && !a.device_scope_only;
+    for (int s = 0; s < a.T; ++s) {
+        const int t = reverse ? (a.T - 1 - s) : s;
+        float pin = 0.f;
+        if (pair_ok) pin = Pd_c[((size_t)t * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row];
+        if (s == 0) {
+            for (int e = tid; e < BW * H; e += nthreads) {
+                const int b = e / H, k = e - b * H;
+                float v = (h0_c && b < bw) ? h0_c[(size_t)(b0 + b) * H + k] : 0.f;
+                if (a.round_h_bf16) v = round_bf16(v);
+                hbuf[k * BW + b] = v;
+            }
+        } else {
+            if (BW * H > 4 * nthreads && S * UPW <= 84)
+                gather_tagged_cols<8, BW>(xchg + (size_t)(s & 1) * parity_stride, BW * H, bw, a.tag_base + (unsigned)s, hbuf, tid,
+                                          nthreads, a.timeout_flag, a.spin_limit);
+            else
+                gather_tagged_cols<4, BW>(xchg + (size_t)(s & 1) * parity_stride, BW * H, bw, a.tag_base + (unsigned)s, hbuf, tid,
+                                          nthreads, a.timeout_flag, a.spin_limit);
+        }
+        __syncthreads();
+        // Gathers software-pipelined by hand in groups of GS slots: the next group's reads are issued before the
+        // current group's multiply-adds.
+        if constexpr (S * UPW >= 84) {
+            // near the register limit the offsets stay packed two to a register: the compiler must not unpack all
+            // of them ahead of the time loop
+#pragma unroll
+            for (int u = 0; u < UPW; ++u)
+#pragma unroll
+                for (int i = 0; i < S / 2; ++i) asm volatile("" : "+v"(wc[u][i]));
+        }
+        float G = 0.f;
+        {
+            using VT = typename std::conditional<BW == 2, float2, float4>::type;
+            constexpr int GS = (S % 4 == 0) ? 4 : 2;
+            constexpr int GPU_ = S / GS;           // groups per unit
+            constexpr int NG = UPW * GPU_;
+            auto read_group = [&](int g, VT (&dst)[GS]) {
+                const int u = g / GPU_, i0 = (g % GPU_) * GS;
+#pragma unroll
+                for (int k = 0; k < GS; ++k) {
+                    const int n = i0 + k;
+                    const unsigned off = (wc[u][n >> 1] >> (16 * (n & 1))) & 0xFFFFu;
+                    dst[k] = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + off);
+                }
+            };
+            VT hv[2][GS];
+            float acc[2][BW];   // two chains per column
+            read_group(0, hv[0]);
+#pragma unroll
+            for (int g = 0; g < NG; ++g) {
+                const int u = g / GPU_, i0 = (g % GPU_) * GS;
+                if (g + 1 < NG) read_group(g + 1, hv[(g + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (i0 == 0) {
+#pragma unroll
+                    for (int b = 0; b < BW; ++b) acc[0][b] = acc[1][b] = 0.f;
+                }
+#pragma unroll
+                for (int k = 0; k < GS; ++k) {
+                    const float w = wv[u][i0 + k];
+                    const VT& x = hv[g & 1][k];
+                    acc[k & 1][0] = fmaf(w, x.x, acc[k & 1][0]);
+                    acc[k & 1][1] = fmaf(w, x.y, acc[k & 1][1]);
+                    if constexpr (BW == 4) {
+                        acc[k & 1][2] = fmaf(w, x.z, acc[k & 1][2]);
+                        acc[k & 1][3] = fmaf(w, x.w, acc[k & 1][3]);
+                    }
+                }
+                if (i0 + GS == S) {
+#pragma unroll
+                    for (int b = 0; b < BW; ++b) {
+                        float r = acc[0][b] + acc[1][b];
+                        r = dpp_add<0xB1>(r);
+                        r = dpp_add<0x4E>(r);
+                        r = dpp_add<0x141>(r);
+                        r = dpp_add<0x140>(r);
+                        G = (lp == u * BW + b) ? r : G;
+                    }
+                }
+            }
+        }
+        G += pin;
+        const bool cand = row == 3;
+        const float sc = cand ? 2.8853900817779268f : -1.4426950408889634f;
+        const float rr = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc * G));
+        const float gate = cand ? fmaf(-2.0f, rr, 1.0f) : rr;
+        const float gi = __shfl(gate, 16 + lp, 64), go = __shfl(gate, 32 + lp, 64), gg = __shfl(gate, 48 + lp, 64);
+        float h_keep = 0.f;
+        if (lane < 16) {
+            c = fmaf(gate, c, gi * gg);
+            const float h = go * tanhf_fast(c);
+            if (lp < PAIRS) pub[(wave * UPW + pu) * BW + pb] = a.round_h_bf16 ? round_bf16(h) : h;
+            h_keep = h;
+        }
+        __syncthreads();
+        if (s + 1 < a.T) {
+            u64* const out = xchg + (size_t)((s + 1) & 1) * parity_stride + (size_t)ugi * upb * BW;
+            for (int e = tid; e < BW * upb; e += nthreads) {
+                const int b = e & (BW - 1), unit = ugi * upb + e / BW;
+                if (b < bw && unit < H)
+                    exchange_store(out + e, pack_slot(pub[e], a.tag_base + (unsigned)s + 1u), kXcd && same_xcd);
+            }
+        }
+        // outputs after the publication: nothing on the way of h_t
+        if (lane < 16 && pair_ok) {
+            y_c[((size_t)t * B + b0 + pb) * y_ld_c + unit_l] = h_keep;
+            if (s + 1 == a.T) {
+                const size_t ci = (size_t)(b0 + pb) * H + unit_l;
+                if (hT_c) hT_c[ci] = h_keep;
+                if (cT_c) cT_c[ci] = c;
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ planning
 // Choose (UPW, BW): the most workgroups that still fit one per compute unit, within the register budget
 // (6*NZ registers per unit for the weights; 512-thread workgroups leave 256 registers per lane) and PAIRS <= 16.
@@ -363,6 +568,72 @@ hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int c
         case 2: return launch_nz<2>(a, upw, bw, blocks, cooperative != 0, s);
         case 3: return launch_nz<3>(a, upw, bw, blocks, cooperative != 0, s);
         case 4: return launch_nz<4>(a, upw, bw, blocks, cooperative != 0, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------------------ quarter-wave launch
+// (UPW, BW) as above; registers: 1.5 per (unit, slot).
+constexpr int kQ16WeightRegs = 156;
+bool persist_batched_q16_plan(int B, int H, int slots, int ndir, int* upw_out, int* bw_out, int* ug_out, int* bg_out)
+{
+    if (B < 2 || slots < 2 || slots > 16 || (slots & 1) || H < 1 || H > 4096) return false;
+    int best = -1;
+    for (int bw = 2; bw <= 4; bw *= 2) {
+        for (int upw = 2; upw <= 8; ++upw) {
+            if (upw * bw > 16 || 3 * slots * upw > 2 * kQ16WeightRegs) continue;
+            if (((size_t)bw * H + (size_t)bw * kWaves * upw) * sizeof(float) > 64 * 1024) continue;
+            const int ug = (H + kWaves * upw - 1) / (kWaves * upw), bg = (B + bw - 1) / bw;
+            const int blocks = ug * bg * ndir;
+            if (blocks > device_num_cus()) continue;
+            if (blocks > best) {
+                best = blocks;
+                *upw_out = upw; *bw_out = bw; *ug_out = ug; *bg_out = bg;
+            }
+        }
+    }
+    return best > 0;
+}
+
+template <int S, int UPW, int BW>
+static hipError_t launch_q16_cfg(PersistBatchedArgs& a, int blocks, bool cooperative, hipStream_t s)
+{
+    const size_t lds = ((size_t)BW * a.H + (size_t)BW * kWaves * UPW) * sizeof(float);
+    void* args[] = {(void*)&a};
+    auto kern = persist_batched_q16_kernel<S, UPW, BW>;
+    if (cooperative) return hipLaunchCooperativeKernel((const void*)kern, dim3(blocks), dim3(64 * kWaves), args, (unsigned)lds, s);
+    return hipLaunchKernel((const void*)kern, dim3(blocks), dim3(64 * kWaves), args, lds, s);
+}
+
+template <int S>
+static hipError_t launch_q16_s(PersistBatchedArgs& a, int upw, int bw, int blocks, bool coop, hipStream_t s)
+{
+#define CFG(U, W) if constexpr (3 * S * U <= 2 * kQ16WeightRegs) { if (upw == U && bw == W) return launch_q16_cfg<S, U, W>(a, blocks, coop, s); }
+    CFG(2, 2) CFG(3, 2) CFG(4, 2) CFG(5, 2) CFG(6, 2) CFG(7, 2) CFG(8, 2) CFG(2, 4) CFG(3, 4) CFG(4, 4)
+#undef CFG
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_persist_batched_q16(PersistBatchedArgs& a, int ndir, int slots, int cooperative, hipStream_t s)
+{
+    if (a.T <= 0) return hipSuccess;
+    int upw, bw, ug, bg;
+    if (!persist_batched_q16_plan(a.B, a.H, slots, ndir, &upw, &bw, &ug, &bg)) return hipErrorInvalidValue;
+    a.ug = ug;
+    a.bg = bg;
+    const int per_xcd = (ndir * bg + 7) / 8;
+    a.ndir = ndir;
+    a.xcd_local = (persist_batched_q16_xcd_capable(slots, upw) && ug <= 64 && per_xcd * ug <= device_num_cus() / 8) ? 1 : 0;
+    const int blocks = a.xcd_local ? 8 * per_xcd * ug : ug * bg * ndir;
+    switch (slots) {
+        case 2: return launch_q16_s<2>(a, upw, bw, blocks, cooperative != 0, s);
+        case 4: return launch_q16_s<4>(a, upw, bw, blocks, cooperative != 0, s);
+        case 6: return launch_q16_s<6>(a, upw, bw, blocks, cooperative != 0, s);
+        case 8: return launch_q16_s<8>(a, upw, bw, blocks, cooperative != 0, s);
+        case 10: return launch_q16_s<10>(a, upw, bw, blocks, cooperative != 0, s);
+        case 12: return launch_q16_s<12>(a, upw, bw, blocks, cooperative != 0, s);
+        case 14: return launch_q16_s<14>(a, upw, bw, blocks, cooperative != 0, s);
+        case 16: return launch_q16_s<16>(a, upw, bw, blocks, cooperative != 0, s);
     }
     return hipErrorInvalidValue;
 }

@@ -17,13 +17,15 @@
 //             tiles of the row block have been found to share an XCD); once the wave's stores have been acknowledged
 //             (outstanding-memory counter at zero) and the workgroup has met at a barrier, one thread publishes
 //             the step number in the tile's flag, with a store of the same scope.
-//   consumer  one wave polls the flags of the tiles that produce its batch rows (device-scope loads, bounded);
-//             after a workgroup barrier every wave reads its operand fragments with device-scope 8-byte loads,
-//             which do not hit stale lines of this compute unit's vector cache or this XCD's L2.  (An acquire
-//             fence followed by ordinary cached loads, which lets the 32 compute units of an XCD share one fetch
-//             of each line, measured 0.9 us per step slower: the invalidate makes all of them miss first.)
-// Two exchange buffers alternate: h_{t+1} can only be written after every tile has published h_t, which each
-// did after it had finished reading h_{t-1} from the buffer h_{t+1} goes to.
+//   consumer  every wave polls the flags of the tiles that produce the units of its own K slice (device-scope
+//             loads, bounded) and then, without a workgroup barrier, reads its operand fragments with device-scope
+//             8-byte loads, which do not hit stale lines of this compute unit's vector cache or this XCD's L2.
+//             A wave issues its memory instructions in order and none past the branch that ends the poll.  (An
+//             acquire fence followed by ordinary cached loads, which lets the 32 compute units of an XCD share one
+//             fetch of each line, measured 0.9 us per step slower: the invalidate makes all of them miss first.)
+// Two exchange buffers alternate: a tile writes h_{t+1} only after its eight waves, whose K slices together cover
+// every tile of the row block, have seen all flags of h_t, and each of those tiles raised its flag after all of its
+// waves had finished reading h_{t-1} from the buffer h_{t+1} goes to.
 // Flags carry monotonically growing tags, so they are never cleared between steps or launches of one forward.
 // Every wait is bounded; an expired wait raises the timeout flag and the kernel runs to its end.
 #include "common.h"

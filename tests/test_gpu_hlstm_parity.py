@@ -244,6 +244,19 @@ def test_small_batch_persistent_random_shapes(shape):
     print(f"[random-shape] {shape} -> {desc}", flush=True)
 
 
+@pytest.mark.parametrize("shape", _random_small_batch_shapes(2024, 12, True)[::4] + _random_small_batch_shapes(2025, 12, False)[::3])
+def test_random_shapes_with_a_fixed_weight_range(shape):
+    """The same shapes with the weight range NOT tied to the fan-in (a = 0.4 throughout): small shapes run with
+    pre-activations well below one, large ones with saturated gates.  The tolerance is the usual one; the measured error
+    is printed."""
+    L, bidir, D, H, G, T, Bn, keep = shape
+    w = _hw(91, L, bidir, D, H, G, T, Bn, a=0.4, keep=keep) if G else \
+        inputs.Workload(91, f"rndfix_L{L}_D{D}_H{H}_T{T}_B{Bn}", L, bidir, D, H, T, Bn, "f32", 0.4, keep, "uniform")
+    case = inputs.make_case(w, k=H + Bn, random_state=True)
+    desc, err = check_case(case, CSR, PAUTO)
+    print(f"[random-shape, a=0.4] {shape} -> {desc} {err}", flush=True)
+
+
 def _random_batch1_shapes(seed, n, kind):
     rng = np.random.Generator(np.random.PCG64(seed))
     shapes = []

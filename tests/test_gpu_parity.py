@@ -103,7 +103,7 @@ def test_small_batch_persistent_overflow_rows(shape):
     L, bidir, D, H, T, Bn, keep = shape
     case = inputs.make_case(_wl(89, L, bidir, D, H, T, Bn, keep=keep), k=H + Bn, random_state=True)
     desc, _ = check_case(case, CSR, PAUTO)
-    assert "persist_batched-csr+ovf" in desc
+    assert "persist_batched-q16" in desc or "persist_batched-csr+ovf" in desc
 
 
 def test_bf16_small():
