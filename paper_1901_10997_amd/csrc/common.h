@@ -217,7 +217,7 @@ struct PersistMfmaArgs {
     float* hT;
     float* cT;
     uint16_t* hx;              // two exchange buffers of H * Bp bf16 each, Bp = B rounded up to 64
-    unsigned* flags;           // one per tile, [ceil(B/64)][4H/64]; every value below tag_base + 1
+    unsigned* flags;           // one per tile, [row blocks][tiles of a row block]; every value below tag_base + 1
     unsigned long long* xcc_ids;  // [row blocks][64] tagged slots for the XCD ids of the tiles' workgroups, or nullptr
     int xcd_local;             // block ids grouped by XCD (set by the launcher)
     int device_scope_only;     // 1: publish with device-scope stores even where the group shares an XCD (A/B switch)
