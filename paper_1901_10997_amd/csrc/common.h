@@ -313,15 +313,7 @@ bool persist_b1_sparse_supported(int H, int D0, int slots_x, int slots_h, int la
 // Small-batch row-compressed recurrence with the time loop on the device (all directions of a layer per launch).
 struct PersistBatchedDir {
     const float* P;            // [T*B][4H] projection incl. bias
-    const float* ell_val;      // [4H][slots][64]
-    const uint16_t* ell_col;
-    int slots;
-    // per-unit overflow lists of rows longer than 64*slots entries (nullptr: none); entry = (gate << 16) | column;
-    // the entries of the units one wave owns must not exceed 64
-    const int32_t* ovf_ptr;
-    const uint32_t* ovf_ent;
-    const float* ovf_val;
-    // quarter-wave form [H][q16_slots][64] (launch_persist_batched_q16 reads these instead of the slices above)
+    // W_h in the quarter-wave form [H][q16_slots][64]
     const float* q16_val;
     const uint16_t* q16_col;
     int q16_slots;
@@ -340,16 +332,13 @@ struct PersistBatchedArgs {
     int ndir, xcd_local;       // directions in the grid; block ids grouped by XCD (filled by the launcher)
     int device_scope_only;     // 1: publish with device-scope stores even where a group shares an XCD (A/B switch)
     int round_h_bf16;
-    unsigned long long* xchg;  // slots, zero or older tags only: 2 (B + 3) H per direction ([2][B][H] in the 64-lane-slice
-                               // kernel, [2][batch group][H][columns of a group] in the quarter-wave kernel)
+    unsigned long long* xchg;  // slots, zero or older tags only: 2 (B + 3) H per direction, [2][batch group][H][columns of a group]
     unsigned long long* xcc_ids;  // [ndir * bg][64] tagged slots (XCD id of each unit group's workgroup), zero or older tags only
     unsigned tag_base;
     int* timeout_flag;
     unsigned spin_limit;
 };
-bool persist_batched_plan(int B, int H, int nz, int ndir, int* upw, int* bw, int* ug, int* bg);
-hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int cooperative, hipStream_t s);
-// the same recurrence on the quarter-wave form; `slots` = the largest q16_slots of the directions (even, <= 16)
+// `slots` = the largest q16_slots of the directions (even, <= 16)
 bool persist_batched_q16_plan(int B, int H, int slots, int ndir, int* upw, int* bw, int* ug, int* bg);
 hipError_t launch_persist_batched_q16(PersistBatchedArgs& a, int ndir, int slots, int cooperative, hipStream_t s);
 

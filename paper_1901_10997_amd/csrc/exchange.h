@@ -81,55 +81,6 @@ __device__ __forceinline__ void gather_tagged_wide(const u64* slots, int H, unsi
     else gather_tagged2<4>(A, none, tid, nthreads, timeout_flag, spin_limit);
 }
 
-// As gather_tagged for `n` slots that hold cols = n / rows consecutive columns of `rows` values each, but the
-// values are stored interleaved: value (col, k) goes to dst[k * stride + col].
-template <int NF>
-__device__ __forceinline__ void gather_tagged_interleave_nf(const u64* slots, int n, unsigned want, float* dst, int rows,
-                                                            int stride, int tid, int nthreads, int* timeout_flag,
-                                                            unsigned spin_limit)
-{
-    for (int e0 = tid; e0 < n; e0 += NF * nthreads) {
-        u64 v[NF];
-        unsigned spins = 0;
-        bool ok;
-        do {
-            ok = true;
-#pragma unroll
-            for (int u = 0; u < NF; ++u) {
-                const int e = e0 + u * nthreads;
-                v[u] = (e < n) ? __hip_atomic_load(slots + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ((u64)want << 32);
-                ok = ok && ((unsigned)(v[u] >> 32) == want);
-            }
-            if (!ok) {
-                ++spins;
-                if (spins > spin_limit) {
-                    __hip_atomic_store(timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-                if ((spins & 63u) == 0 &&
-                    __hip_atomic_load(timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
-                    break;
-            }
-        } while (!ok);
-#pragma unroll
-        for (int u = 0; u < NF; ++u) {
-            const int e = e0 + u * nthreads;
-            if (e < n) {
-                const int col = e / rows, k = e - col * rows;
-                dst[k * stride + col] = __uint_as_float((unsigned)v[u]);
-            }
-        }
-    }
-}
-
-__device__ __forceinline__ void gather_tagged_interleave(const u64* slots, int n, unsigned want, float* dst, int rows,
-                                                         int stride, int tid, int nthreads, int* timeout_flag,
-                                                         unsigned spin_limit)
-{
-    if (n > 4 * nthreads) gather_tagged_interleave_nf<8>(slots, n, want, dst, rows, stride, tid, nthreads, timeout_flag, spin_limit);
-    else gather_tagged_interleave_nf<4>(slots, n, want, dst, rows, stride, tid, nthreads, timeout_flag, spin_limit);
-}
-
 // As gather_tagged for slots stored in the order of their destination (slot e -> dst[e]), where slot e belongs to
 // column e % BW of a batch group that may hold fewer than BW columns: the slots of the missing columns are never
 // published and are skipped.

@@ -26,7 +26,6 @@ struct lstm355 {
     int* timeout_flag = nullptr;         // device int
     unsigned spin_limit = 1u << 22;
     int device_scope_only = 0;           // 1: no hand-over through an XCD's L2 (environment LSTM355_L2_HANDOVER=0)
-    int use_q16 = 1;                     // small-batch recurrence on the quarter-wave form (environment LSTM355_Q16=0: 64-lane slices)
     int plan = LSTM_PLAN_AUTO;
     int waves_per_group = 0;
     int cooperative = 0;
@@ -422,7 +421,6 @@ static int create_model(int layers, int input_dim, const int* hidden_dims, const
         if (v > 0) m->spin_limit = (unsigned)v;
     }
     if (const char* l2 = std::getenv("LSTM355_L2_HANDOVER")) m->device_scope_only = (std::atoi(l2) == 0) ? 1 : 0;
-    if (const char* q = std::getenv("LSTM355_Q16")) m->use_q16 = (std::atoi(q) == 0) ? 0 : 1;
     hipError_t e = hipGetDevice(&m->device);
     // two cells (directions, or two stacked layers) x two parities; H-LSTM: h slots, then the 4G hidden-layer slots
     m->xchg_slots = (m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H) + 64;   // + XCD ids of a launch's workgroups
@@ -1280,50 +1278,17 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             prev_has_bf16 = true;
             continue;
         }
-        // ---- recurrence, small-batch row-compressed, time loop on the device (all directions in one launch)
+        // ---- recurrence, small-batch row-compressed, time loop on the device (all directions in one launch): W_h in
+        // the quarter-wave form (rows of at most 256 kept entries)
         {
-            int nzmax = 0, upw = 0, bw = 0, ug = 0, bg = 0;
+            int upw = 0, bw = 0, ug = 0, bg = 0, q16 = 0;
             bool pb_ok = B >= 2 && m->plan != LSTM_PLAN_STEPWISE;
-            bool trimmed = false;
-            // quarter-wave form first (rows of at most 256 kept entries)
-            int q16 = 0;
-            if (pb_ok && m->use_q16) {
-                bool ok = true;
-                for (int d = 0; d < Dn && ok; ++d) {
-                    const PackedMat& p = m->ld[(size_t)l * Dn + d].wh;
-                    ok = p.compressed && p.q16_slots > 0;
-                    q16 = std::max(q16, p.q16_slots);
-                }
-                if (!ok || !persist_batched_q16_plan(B, H, q16, Dn, &upw, &bw, &ug, &bg)) q16 = 0;
+            for (int d = 0; d < Dn && pb_ok; ++d) {
+                const PackedMat& p = m->ld[(size_t)l * Dn + d].wh;
+                pb_ok = p.compressed && p.q16_slots > 0;
+                q16 = std::max(q16, p.q16_slots);
             }
-            if (pb_ok && q16 == 0) {
-                // first with the slices cut to the common row length (a wave takes at most 64 overflow entries over
-                // the units it owns), then with the full slices
-                bool found = false;
-                for (int pass = 0; pass < 2 && !found; ++pass) {
-                    const bool trim = pass == 0;
-                    bool ok = true, any_trim = false;
-                    nzmax = 0;
-                    for (int d = 0; d < Dn && ok; ++d) {
-                        const PackedMat& p = m->ld[(size_t)l * Dn + d].wh;
-                        const bool use_trim = trim && p.slots_trim > 0;
-                        ok = p.compressed && (use_trim || p.ell_val != nullptr);
-                        nzmax = std::max(nzmax, use_trim ? p.slots_trim : p.slots);
-                        any_trim = any_trim || use_trim;
-                    }
-                    if (trim && !any_trim) continue;
-                    ok = ok && nzmax <= 4 && persist_batched_plan(B, H, nzmax, Dn, &upw, &bw, &ug, &bg);
-                    for (int d = 0; d < Dn && ok && trim; ++d) {
-                        const PackedMat& p = m->ld[(size_t)l * Dn + d].wh;
-                        if (p.slots_trim == 0) continue;
-                        const int units = (int)p.h_ovf_ptr.size() - 1;
-                        for (int u = 0; u < units && ok; u += upw)
-                            ok = p.h_ovf_ptr[(size_t)std::min(u + upw, units)] - p.h_ovf_ptr[(size_t)u] <= 64;
-                    }
-                    if (ok) { found = true; trimmed = trim; }
-                }
-                pb_ok = found;
-            }
+            pb_ok = pb_ok && persist_batched_q16_plan(B, H, q16, Dn, &upw, &bw, &ug, &bg);
             if (pb_ok) {
                 if (!bslots_clean || bslots_H != H) {   // another width is another layout: start from zero again
                     HIP_TRY(m, launch_fill_u64(bslots, align256(ws.slot_bytes) / sizeof(unsigned long long), 0ull, s));
@@ -1336,35 +1301,22 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     const LayerDir& w = m->ld[(size_t)l * Dn + d];
                     const size_t n = (size_t)l * Dn + d;
                     a.d[d].P = P[d];
-                    if (q16) {
-                        a.d[d].q16_val = w.wh.q16_val; a.d[d].q16_col = w.wh.q16_col; a.d[d].q16_slots = w.wh.q16_slots;
-                    } else if (trimmed && w.wh.slots_trim > 0) {
-                        a.d[d].ell_val = w.wh.ell_val_trim; a.d[d].ell_col = w.wh.ell_col_trim; a.d[d].slots = w.wh.slots_trim;
-                        a.d[d].ovf_ptr = w.wh.ovf_ptr; a.d[d].ovf_ent = w.wh.ovf_ent; a.d[d].ovf_val = w.wh.ovf_val;
-                    } else {
-                        a.d[d].ell_val = w.wh.ell_val; a.d[d].ell_col = w.wh.ell_col; a.d[d].slots = w.wh.slots;
-                    }
+                    a.d[d].q16_val = w.wh.q16_val; a.d[d].q16_col = w.wh.q16_col; a.d[d].q16_slots = w.wh.q16_slots;
                     a.d[d].h0 = h0 ? h0 + m->soff(n) * B : nullptr;
                     a.d[d].c0 = c0 ? c0 + m->soff(n) * B : nullptr;
                     a.d[d].y = Yout + (size_t)d * H; a.d[d].y_ld = y_ld;
                     a.d[d].hT = hT ? hT + m->soff(n) * B : nullptr;
                     a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
                     a.d[d].reverse = d;
-                    if (q16)
-                        std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16(s%d,u%d,b%d);", l, d,
-                                      (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr", q16, upw, bw);
-                    else
-                        std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-csr%s(u%d,b%d);", l, d,
-                                      (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
-                                      trimmed ? "+ovf" : "", upw, bw);
+                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16(s%d,u%d,b%d);", l, d,
+                                  (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr", q16, upw, bw);
                     m->last_plan += tag;
                 }
                 a.T = T; a.B = B; a.H = H; a.round_h_bf16 = bf16;
                 a.xchg = bslots; a.xcc_ids = bslots + (size_t)Dn * 2 * (B + 3) * H; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 btag += (unsigned)T;
                 ProfSpan span(m, s, 1);
-                if (q16) HIP_TRY(m, launch_persist_batched_q16(a, Dn, q16, m->launch_mode(), s));
-                else HIP_TRY(m, launch_persist_batched(a, Dn, nzmax, m->launch_mode(), s));
+                HIP_TRY(m, launch_persist_batched_q16(a, Dn, q16, m->launch_mode(), s));
                 continue;
             }
         }

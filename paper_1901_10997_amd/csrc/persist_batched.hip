@@ -7,15 +7,15 @@
 // The grid is a 2-D partition per direction: unit groups x batch groups.  A workgroup owns UPB hidden units
 // and BW batch columns; it needs only the h values of its own batch columns (all H of them), which keeps the
 // polled volume per workgroup at BW*H slots however large the batch is.  Each wave keeps the kept weights of
-// its UPW units in registers (64-lane slices, as the batch-1 kernel), gathers h from LDS, reduces the 4 x BW
-// partial sums of a unit with the lane-swap reduction so that lane 16*gate + pair holds a gate total
-// (pair = local unit * BW + column), evaluates all gates of all its pairs with one exp2 and one reciprocal,
-// and updates c and h in lanes 0..pairs-1.  h travels between workgroups through tagged 64-bit slots (value
-// and step tag published by one store; consumers poll until the tag matches), laid out [parity][B][H] per
-// direction so that a batch group's columns are contiguous.  Only the workgroups of one (direction, batch group)
-// exchange anything; where the groups fit they are placed on one XCD each and, once the launch has verified that
-// from the hardware's XCD ids, publish h with workgroup-scope stores that stay in that XCD's L2 (exchange.h).
-// All waits are bounded.
+// its UPW units in registers in the quarter-wave form: slot s of a unit is one 64-lane gather that serves all
+// four gate rows, gate q on lanes 16q..16q+15, so a lane accumulates BW sums per unit, a row's total is a butterfly
+// inside its 16 lanes, and lane 16*gate + pair ends up with a gate total (pair = local unit * BW + column).  One
+// exp2 and one reciprocal evaluate all gates of all pairs; c and h are updated in lanes 0..pairs-1.  h travels
+// between workgroups through tagged 64-bit slots (value and step tag published by one store; consumers poll until
+// the tag matches), laid out per direction as [parity][batch group][k][BW], the order of the LDS copy, so that the
+// poll is a straight copy.  Only the workgroups of one (direction, batch group) exchange anything; where the groups
+// fit they are placed on one XCD each and, once the launch has verified that from the hardware's XCD ids, publish h
+// with workgroup-scope stores that stay in that XCD's L2 (exchange.h).  All waits are bounded.
 #include <type_traits>
 #include "common.h"
 #include "device_math.h"
@@ -23,286 +23,8 @@
 
 namespace l355 {
 
-// configurations with registers to spare for the XCD-local hand-over
-constexpr bool persist_batched_xcd_capable(int nz, int upw) { return nz * upw < 24; }
-
-template <int NZ, int UPW, int BW>
-__global__ __launch_bounds__(512) void persist_batched_sparse_kernel(PersistBatchedArgs a)
-{
-    extern __shared__ float lds[];  // hbuf[H][BW] (the BW batch values of one k adjacent) | pub[BW][UPB]
-    constexpr int PAIRS = UPW * BW;
-    static_assert(PAIRS <= 16, "pairs must fit one 16-lane row");
-    const int H = a.H, B = a.B;
-    const int tid = threadIdx.x, nthreads = blockDim.x;
-    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
-    const int upb = nwaves * UPW;
-    float* hbuf = lds;
-    float* pub = lds + (size_t)BW * H;
-    // block -> (direction, batch group, unit group).  Workgroups are dealt to the eight XCDs in turn; when the groups
-    // fit, all workgroups of one (direction, batch group) -- the only ones that exchange data -- take ids of one
-    // residue modulo 8, so that they can meet in one XCD's L2 (checked below; only speed depends on the dealing order).
-    // (Not in the configurations at the register limit, where the extra state would spill; the launcher knows.)
-    constexpr bool kXcd = persist_batched_xcd_capable(NZ, UPW);
-    int dir, bgi, ugi;
-    if (kXcd && a.xcd_local) {
-        const int j = blockIdx.x >> 3;
-        const int g = (blockIdx.x & 7) + 8 * (j / a.ug);
-        if (g >= a.ndir * a.bg) return;     // padding ids take no part in the exchange
-        ugi = j % a.ug; dir = g / a.bg; bgi = g % a.bg;
-    } else {
-        const int per_dir = a.ug * a.bg;
-        dir = blockIdx.x / per_dir;
-        const int rem = blockIdx.x % per_dir;
-        bgi = rem / a.ug; ugi = rem % a.ug;
-    }
-    const PersistBatchedDir& D = a.d[dir];
-    const int b0 = bgi * BW;
-    const int bw = (B - b0) < BW ? (B - b0) : BW;         // columns actually present
-    const int u0 = ugi * upb + wave * UPW;                // first unit of this wave
-    u64* xchg = a.xchg + (size_t)dir * 2 * B * H;
-
-    // kept weights of this wave's units: values in fp32 registers; the column is kept as the 16-bit LDS byte
-    // offset of its h values, the 4*NZ offsets of a unit packed two to a register
-    constexpr int NZP = (4 * NZ + 1) / 2;
-    float wv[UPW][4][NZ];
-    unsigned wc[UPW][NZP];
-    {
-        // Every load is issued whatever the shape (units past H and slices past `slots` read a valid element and are
-        // zeroed afterwards): with a branch per element the loads went out one at a time, each waiting for the one
-        // before it, and filling the registers took 30 us.
-        const int slots = D.slots;
-        float tv[4 * NZ];
-        unsigned tk[4 * NZ];
-#pragma unroll
-        for (int u = 0; u < UPW; ++u) {
-            const int unit = (u0 + u < H) ? (u0 + u) : (H - 1);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                for (int i = 0; i < NZ; ++i) {
-                    const int ii = i < slots ? i : slots - 1;
-                    const size_t idx = ((size_t)(4 * unit + q) * slots + ii) * 64 + lane;
-                    tv[q * NZ + i] = D.ell_val[idx];
-                    tk[q * NZ + i] = D.ell_col[idx];
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < NZP; ++i) wc[u][i] = 0u;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                for (int i = 0; i < NZ; ++i) {
-                    const bool live = (u0 + u < H) && i < slots;
-                    const int n = q * NZ + i;
-                    wv[u][q][i] = live ? tv[n] : 0.f;
-                    // byte offset of h[k][0] in LDS (< 65536)
-                    wc[u][n >> 1] |= ((live ? tk[n] : 0u) * (BW * 4u)) << (16 * (n & 1));
-                }
-            }
-        }
-    }
-    // Overflow entries of this wave's units (rows longer than 64*slots; rare): the lists of consecutive units are
-    // adjacent, lane e holds entry e of the wave's run, packed as LDS byte offset | gate << 16 | local unit << 18
-    // (local unit 15: no entry).  Their products are added after the main loop, in waves that have any.
-    unsigned eo = 15u << 18;
-    float evv = 0.f;
-    unsigned ovf_units = 0u;   // bit u: local unit u has entries (wave-uniform)
-    if (D.ovf_ptr != nullptr && u0 < H) {
-        const int first = D.ovf_ptr[u0];
-        int pos = first;
-#pragma unroll
-        for (int u = 0; u < UPW; ++u) {
-            const int nxt = (u0 + u < H) ? D.ovf_ptr[u0 + u + 1] : pos;
-            const int idx = first + lane;
-            if (idx >= pos && idx < nxt) {
-                const unsigned e = D.ovf_ent[idx];
-                eo = ((e & 0xFFFFu) * (BW * 4u)) | ((e >> 16) << 16) | ((unsigned)u << 18);
-                evv = D.ovf_val[idx];
-            }
-            ovf_units |= (nxt > pos ? 1u : 0u) << u;
-            pos = nxt;
-        }
-        ovf_units = __builtin_amdgcn_readfirstlane(ovf_units);
-    }
-    // lane 16*gate + pair: pair = local unit * BW + column
-    const int lp = lane & 15, row = lane >> 4;
-    const int pu = lp / BW, pb = lp % BW;
-    const bool pair_ok = lp < PAIRS && pb < bw && (u0 + pu) < H;
-    const int unit_l = u0 + pu;
-    float c = 0.f;
-    if (lane < 16 && pair_ok && D.c0) c = D.c0[(size_t)(b0 + pb) * H + unit_l];
-
-    // The direction is chosen by the block index, so `D` is addressed through memory: taken inside the time loop its
-    // fields cost a load and a wait per step, some of them in front of the publication.  Where registers allow
-    // (kCopy) they are copied once and the outputs are written after the publication.
-    constexpr bool kCopy = NZ * UPW < 24;
-    const float* Pd_c = nullptr;
-    float *y_c = nullptr, *hT_c = nullptr, *cT_c = nullptr;
-    size_t y_ld_c = 0;
-    if constexpr (kCopy) {
-        Pd_c = D.P; y_c = D.y; y_ld_c = (size_t)D.y_ld; hT_c = D.hT; cT_c = D.cT;
-    }
-    // With the group's workgroups placed on one XCD (checked here, per launch, from the hardware's own id) h is handed
-    // over through that XCD's L2.
-    bool same_xcd = false;
-    if (kXcd && a.xcd_local)
-        same_xcd = group_shares_xcd(a.xcc_ids + ((size_t)dir * a.bg + bgi) * 64, a.ug, ugi, a.tag_base + 1u, hbuf, tid,
-                                    nthreads, a.timeout_flag, a.spin_limit) && !a.device_scope_only;
-    for (int s = 0; s < a.T; ++s) {
-        const int t = D.reverse ? (a.T - 1 - s) : s;
-        float pin = 0.f;
-        if constexpr (kCopy) {
-            if (pair_ok) pin = Pd_c[((size_t)t * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row];
-        } else {
-            if (pair_ok) pin = D.P[((size_t)t * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row];
-        }
-        if (s == 0) {
-            for (int e = tid; e < BW * H; e += nthreads) {
-                const int b = e / H, k = e - b * H;
-                float v = (D.h0 && b < bw) ? D.h0[(size_t)(b0 + b) * H + k] : 0.f;
-                if (a.round_h_bf16) v = round_bf16(v);
-                hbuf[k * BW + b] = v;
-            }
-        } else {
-            // (eight polling loads in flight need sixteen registers: not in the configurations at the register limit;
-            // the heaviest ones serve the widest layers and take six, which covers 3072 slots in one polling round)
-            if constexpr (NZ * UPW >= 24)
-                gather_tagged_interleave_nf<6>(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H,
-                                               BW, tid, nthreads, a.timeout_flag, a.spin_limit);
-            else if constexpr (NZ * UPW >= 20)
-                gather_tagged_interleave_nf<4>(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H,
-                                               BW, tid, nthreads, a.timeout_flag, a.spin_limit);
-            else
-                gather_tagged_interleave(xchg + ((size_t)(s & 1) * B + b0) * H, bw * H, a.tag_base + (unsigned)s, hbuf, H, BW,
-                                         tid, nthreads, a.timeout_flag, a.spin_limit);
-        }
-        __syncthreads();
-        // The gathers are software-pipelined by hand in groups of GS (gates q0..q0+GS-1 of slice i of one unit): the
-        // next group's reads are issued before the current group's multiply-adds, so that LDS latency overlaps
-        // arithmetic.
-        float G = 0.f;
-        {
-            using VT = typename std::conditional<BW == 2, float2, float4>::type;
-            constexpr int GS = (6 * NZ * UPW > 128) ? 2 : 4;
-            constexpr int GPS = 4 / GS;            // groups per slice
-            constexpr int NG = UPW * NZ * GPS;
-            auto read_group = [&](int g, VT (&dst)[GS]) {
-                const int u = g / (NZ * GPS), i = (g / GPS) % NZ, q0 = (g % GPS) * GS;
-#pragma unroll
-                for (int k = 0; k < GS; ++k) {
-                    const int n = (q0 + k) * NZ + i;
-                    const unsigned off = (wc[u][n >> 1] >> (16 * (n & 1))) & 0xFFFFu;
-                    dst[k] = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + off);
-                }
-            };
-            VT hv[2][GS];
-            float acc[4][BW];
-            read_group(0, hv[0]);
-#pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                const int u = g / (NZ * GPS), i = (g / GPS) % NZ, q0 = (g % GPS) * GS;
-                if (g + 1 < NG) read_group(g + 1, hv[(g + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                if (i == 0 && q0 == 0) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q)
-#pragma unroll
-                        for (int b = 0; b < BW; ++b) acc[q][b] = 0.f;
-                }
-#pragma unroll
-                for (int k = 0; k < GS; ++k) {
-                    const int q = q0 + k;
-                    const float w = wv[u][q][i];
-                    const VT& x = hv[g & 1][k];
-                    acc[q][0] = fmaf(w, x.x, acc[q][0]);
-                    acc[q][1] = fmaf(w, x.y, acc[q][1]);
-                    if constexpr (BW == 4) {
-                        acc[q][2] = fmaf(w, x.z, acc[q][2]);
-                        acc[q][3] = fmaf(w, x.w, acc[q][3]);
-                    }
-                }
-                if (i == NZ - 1 && q0 + GS == 4) {
-#pragma unroll
-                    for (int b = 0; b < BW; ++b) {
-                        const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
-                        G = (lp == u * BW + b) ? r : G;
-                    }
-                }
-            }
-            if (ovf_units != 0u) {
-                // overflow entries: lane e multiplies entry e; a unit that has entries reduces them per gate and column
-                unsigned e = eo;
-                asm volatile("" : "+v"(e));   // the selections derived from it are made here, not kept in registers
-                const VT t = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + (e & 0xFFFFu));
-                float xe[BW];
-                xe[0] = t.x * evv; xe[1] = t.y * evv;
-                if constexpr (BW == 4) { xe[2] = t.z * evv; xe[3] = t.w * evv; }
-                const unsigned eu = (e >> 18) & 15u, eg = (e >> 16) & 3u;
-#pragma unroll 1
-                for (int u = 0; u < UPW; ++u) {
-                    if ((ovf_units >> u) & 1u) {
-#pragma unroll
-                        for (int b = 0; b < BW; ++b) {
-                            const float tb = eu == (unsigned)u ? xe[b] : 0.f;
-                            const float r = wave_sum4_rows(eg == 0u ? tb : 0.f, eg == 1u ? tb : 0.f, eg == 2u ? tb : 0.f,
-                                                           eg == 3u ? tb : 0.f);
-                            G += (lp == u * BW + b) ? r : 0.f;
-                        }
-                    }
-                }
-            }
-        }
-        G += pin;
-        const bool cand = row == 3;
-        const float sc = cand ? 2.8853900817779268f : -1.4426950408889634f;
-        const float rr = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc * G));
-        const float gate = cand ? fmaf(-2.0f, rr, 1.0f) : rr;
-        const float gi = __shfl(gate, 16 + lp, 64), go = __shfl(gate, 32 + lp, 64), gg = __shfl(gate, 48 + lp, 64);
-        float h_keep = 0.f;
-        if (lane < 16) {
-            c = fmaf(gate, c, gi * gg);
-            const float h = go * tanhf_fast(c);
-            if (lp < PAIRS) pub[pb * upb + wave * UPW + pu] = a.round_h_bf16 ? round_bf16(h) : h;
-            if constexpr (kCopy) {
-                h_keep = h;
-            } else if (pair_ok) {
-                D.y[((size_t)t * B + b0 + pb) * D.y_ld + unit_l] = h;
-                if (s + 1 == a.T) {
-                    const size_t ci = (size_t)(b0 + pb) * H + unit_l;
-                    if (D.hT) D.hT[ci] = h;
-                    if (D.cT) D.cT[ci] = c;
-                }
-            }
-        }
-        __syncthreads();
-        if (s + 1 < a.T) {
-            for (int e = tid; e < BW * upb; e += nthreads) {
-                const int b = e / upb, ul = e - b * upb;
-                const int unit = ugi * upb + ul;
-                if (b < bw && unit < H)
-                    exchange_store(xchg + ((size_t)((s + 1) & 1) * B + b0 + b) * H + unit,
-                                   pack_slot(pub[e], a.tag_base + (unsigned)s + 1u), kXcd && same_xcd);
-            }
-        }
-        if constexpr (kCopy) {
-            // outputs after the publication: nothing on the way of h_t
-            if (lane < 16 && pair_ok) {
-                y_c[((size_t)t * B + b0 + pb) * y_ld_c + unit_l] = h_keep;
-                if (s + 1 == a.T) {
-                    const size_t ci = (size_t)(b0 + pb) * H + unit_l;
-                    if (hT_c) hT_c[ci] = h_keep;
-                    if (cT_c) cT_c[ci] = c;
-                }
-            }
-        }
-    }
-}
-
-// ------------------------------------------------------------------------------------------------ quarter-wave rows
-// The same recurrence on the quarter-wave form of W_h: slot s of a unit is ONE gather that serves all four gate rows
-// (gate q on lanes 16q..16q+15), so a lane accumulates BW sums per unit instead of 4 BW, and a row's total is a
-// butterfly inside its 16 lanes (four DPP adds) that leaves gate q of pair p in lane 16q + p -- no lane swaps across
-// rows.  S = slots per unit (16 kept entries of each gate per slot).
+// S = slots per unit (16 kept entries of each gate per slot).  Configurations with registers to spare for the
+// XCD-local hand-over:
 constexpr bool persist_batched_q16_xcd_capable(int s, int upw) { return s * upw <= 84; }
 
 template <int S, int UPW, int BW>
@@ -503,77 +225,11 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
     }
 }
 
-// ------------------------------------------------------------------------------------------------ planning
-// Choose (UPW, BW): the most workgroups that still fit one per compute unit, within the register budget
-// (6*NZ registers per unit for the weights; 512-thread workgroups leave 256 registers per lane) and PAIRS <= 16.
 constexpr int kWaves = 8;
-constexpr int kWeightRegs = 150;
-bool persist_batched_plan(int B, int H, int nz, int ndir, int* upw_out, int* bw_out, int* ug_out, int* bg_out)
-{
-    if (B < 2 || nz < 1 || nz > 4 || H < 1 || H > 4096) return false;
-    int best = -1;
-    for (int bw = 2; bw <= 4; bw *= 2) {
-        for (int upw = 2; upw <= 8; ++upw) {
-            if (upw * bw > 16 || 6 * nz * upw > kWeightRegs) continue;
-            if (((size_t)bw * H + (size_t)bw * kWaves * upw) * sizeof(float) > 64 * 1024) continue;
-            const int ug = (H + kWaves * upw - 1) / (kWaves * upw), bg = (B + bw - 1) / bw;
-            const int blocks = ug * bg * ndir;
-            if (blocks > device_num_cus()) continue;
-            if (blocks > best) {
-                best = blocks;
-                *upw_out = upw; *bw_out = bw; *ug_out = ug; *bg_out = bg;
-            }
-        }
-    }
-    return best > 0;
-}
 
-template <int NZ, int UPW, int BW>
-static hipError_t launch_cfg(PersistBatchedArgs& a, int blocks, bool cooperative, hipStream_t s)
-{
-    const size_t lds = ((size_t)BW * a.H + (size_t)BW * kWaves * UPW) * sizeof(float);
-    void* args[] = {(void*)&a};
-    auto kern = persist_batched_sparse_kernel<NZ, UPW, BW>;
-    if (cooperative) return hipLaunchCooperativeKernel((const void*)kern, dim3(blocks), dim3(64 * kWaves), args, (unsigned)lds, s);
-    return hipLaunchKernel((const void*)kern, dim3(blocks), dim3(64 * kWaves), args, lds, s);
-}
-
-template <int NZ>
-static hipError_t launch_nz(PersistBatchedArgs& a, int upw, int bw, int blocks, bool coop, hipStream_t s)
-{
-#define CFG(U, W) if (upw == U && bw == W) return launch_cfg<NZ, U, W>(a, blocks, coop, s);
-    CFG(2, 2) CFG(3, 2) CFG(4, 2) CFG(2, 4) CFG(3, 4) CFG(4, 4)
-    if constexpr (6 * NZ * 5 <= kWeightRegs) { CFG(5, 2) }
-    if constexpr (6 * NZ * 6 <= kWeightRegs) { CFG(6, 2) }
-    if constexpr (6 * NZ * 7 <= kWeightRegs) { CFG(7, 2) }
-    if constexpr (6 * NZ * 8 <= kWeightRegs) { CFG(8, 2) }
-#undef CFG
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_persist_batched(PersistBatchedArgs& a, int ndir, int nz, int cooperative, hipStream_t s)
-{
-    if (a.T <= 0) return hipSuccess;
-    int upw, bw, ug, bg;
-    if (!persist_batched_plan(a.B, a.H, nz, ndir, &upw, &bw, &ug, &bg)) return hipErrorInvalidValue;
-    a.ug = ug;
-    a.bg = bg;
-    // one XCD holds an eighth of the compute units; its share of the groups must fit there
-    const int per_xcd = (ndir * bg + 7) / 8;
-    a.ndir = ndir;
-    a.xcd_local = (persist_batched_xcd_capable(nz, upw) && ug <= 64 && per_xcd * ug <= device_num_cus() / 8) ? 1 : 0;
-    const int blocks = a.xcd_local ? 8 * per_xcd * ug : ug * bg * ndir;
-    switch (nz) {
-        case 1: return launch_nz<1>(a, upw, bw, blocks, cooperative != 0, s);
-        case 2: return launch_nz<2>(a, upw, bw, blocks, cooperative != 0, s);
-        case 3: return launch_nz<3>(a, upw, bw, blocks, cooperative != 0, s);
-        case 4: return launch_nz<4>(a, upw, bw, blocks, cooperative != 0, s);
-    }
-    return hipErrorInvalidValue;
-}
-
-// ------------------------------------------------------------------------------------------------ quarter-wave launch
-// (UPW, BW) as above; registers: 1.5 per (unit, slot).
+// ------------------------------------------------------------------------------------------------ planning
+// Choose (UPW, BW): the most workgroups that still fit one per compute unit, within the register budget (1.5
+// registers per unit and slot; 512-thread workgroups leave 256 registers per lane) and PAIRS <= 16.
 constexpr int kQ16WeightRegs = 156;
 bool persist_batched_q16_plan(int B, int H, int slots, int ndir, int* upw_out, int* bw_out, int* ug_out, int* bg_out)
 {
