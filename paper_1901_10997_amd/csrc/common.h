@@ -37,9 +37,13 @@ struct PackedMat {
     // Quarter-wave form for the small-batch kernel (recurrent matrices whose rows keep at most 256 entries): the four
     // gate rows of unit j share 64-lane slots, gate q on lanes 16q..16q+15, so that a slot is one gather for all four
     // gates and a row's partial sums stay inside a 16-lane row.  [rows/4][q16_slots][64]; q16_slots == 0: not built.
-    int q16_slots = 0;            // even, ceil(max_row_nnz / 16) rounded up
+    int q16_slots = 0;            // even; 16 q16_slots entries of every row are in the slots
     float* q16_val = nullptr;
     uint16_t* q16_col = nullptr;
+    // the few entries of rows longer than that (at most 8 per unit), per unit: entry = (gate << 16) | column; or nullptr
+    int32_t* q16_ovf_ptr = nullptr;   // device [rows/4 + 1]
+    uint32_t* q16_ovf_ent = nullptr;
+    float* q16_ovf_val = nullptr;
     // host copy of the compressed structure in packed row order (for read-back)
     std::vector<int64_t> h_row_ptr;
     std::vector<int32_t> h_col;
@@ -317,6 +321,9 @@ struct PersistBatchedDir {
     const float* q16_val;
     const uint16_t* q16_col;
     int q16_slots;
+    const int32_t* q16_ovf_ptr;   // per-unit lists of the entries beyond 16 q16_slots of a row, or nullptr
+    const uint32_t* q16_ovf_ent;  // (gate << 16) | column
+    const float* q16_ovf_val;
     const float* h0;           // [B][H] or nullptr
     const float* c0;
     float* y;                  // h_t -> y[(t*B + b)*y_ld + j]  (already offset to this direction's columns)

@@ -119,6 +119,9 @@ static void free_mat(PackedMat& p)
     if (p.ovf_val) (void)hipFree(p.ovf_val);
     if (p.q16_val) (void)hipFree(p.q16_val);
     if (p.q16_col) (void)hipFree(p.q16_col);
+    if (p.q16_ovf_ptr) (void)hipFree(p.q16_ovf_ptr);
+    if (p.q16_ovf_ent) (void)hipFree(p.q16_ovf_ent);
+    if (p.q16_ovf_val) (void)hipFree(p.q16_ovf_val);
     p = PackedMat();
 }
 
@@ -304,8 +307,22 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
     // gather (four passes of 16 lanes, picked by lane bit 5 and the parity of bits 2..4) free of collisions as well.
     // Only an entry for which no such slot exists takes any free position, from the end.
     if (quarter_rows && max_nnz <= 256 && rows >= 4) {
-        const int S = std::max(2, 2 * ((max_nnz + 31) / 32));
         const int units = rows / 4;
+        // The slot count is set by the longest row, and with random masks a handful of rows are a few entries longer
+        // than all others.  Take the smallest (even) count that leaves at most 8 entries per unit and rows / 64 entries
+        // in all outside the slots; a wave adds those one at a time (rare: most waves have none).
+        int S = std::max(2, 2 * ((max_nnz + 31) / 32));
+        for (int St = 2; St < S; St += 2) {
+            int64_t worst = 0, total = 0;
+            for (int u = 0; u < units; ++u) {
+                int64_t per_unit = 0;
+                for (int q = 0; q < 4; ++q)
+                    per_unit += std::max<int64_t>(0, out.h_row_ptr[4 * u + q + 1] - out.h_row_ptr[4 * u + q] - (int64_t)16 * St);
+                worst = std::max(worst, per_unit);
+                total += per_unit;
+            }
+            if (worst <= 8 && total <= rows / 64) { S = St; break; }
+        }
         std::vector<float> qv((size_t)units * S * 64, 0.0f);
         std::vector<uint16_t> qc((size_t)units * S * 64, 0);
         std::vector<char> used((size_t)S * 64), aliased((size_t)S * 64);
@@ -325,7 +342,8 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
                 const int rp = 4 * u + q;
                 int fill[32] = {0};
                 leftover[q].clear();
-                for (int64_t e = out.h_row_ptr[rp]; e < out.h_row_ptr[rp + 1]; ++e) {
+                const int64_t row_end = std::min<int64_t>(out.h_row_ptr[rp + 1], out.h_row_ptr[rp] + (int64_t)16 * S);
+                for (int64_t e = out.h_row_ptr[rp]; e < row_end; ++e) {
                     const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
                     if (fill[bank] < S / 2) {
                         const int sl = 2 * fill[bank] + ((hb + q) & 1);
@@ -378,6 +396,24 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
         out.q16_slots = S;
         HIP_TRY(m, upload(&out.q16_val, qv));
         HIP_TRY(m, upload(&out.q16_col, qc));
+        std::vector<int32_t> optr((size_t)units + 1, 0);
+        std::vector<uint32_t> oe;
+        std::vector<float> ov;
+        for (int u = 0; u < units; ++u) {
+            for (int q = 0; q < 4; ++q) {
+                const int rp = 4 * u + q;
+                for (int64_t e = out.h_row_ptr[rp] + (int64_t)16 * S; e < out.h_row_ptr[rp + 1]; ++e) {
+                    oe.push_back(((uint32_t)q << 16) | (uint32_t)out.h_col[e]);
+                    ov.push_back(out.h_val[e]);
+                }
+            }
+            optr[(size_t)u + 1] = (int32_t)oe.size();
+        }
+        if (!oe.empty()) {
+            HIP_TRY(m, upload(&out.q16_ovf_ptr, optr));
+            HIP_TRY(m, upload(&out.q16_ovf_ent, oe));
+            HIP_TRY(m, upload(&out.q16_ovf_val, ov));
+        }
     }
     return LSTM_OK;
 }
@@ -1302,14 +1338,16 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     const size_t n = (size_t)l * Dn + d;
                     a.d[d].P = P[d];
                     a.d[d].q16_val = w.wh.q16_val; a.d[d].q16_col = w.wh.q16_col; a.d[d].q16_slots = w.wh.q16_slots;
+                    a.d[d].q16_ovf_ptr = w.wh.q16_ovf_ptr; a.d[d].q16_ovf_ent = w.wh.q16_ovf_ent; a.d[d].q16_ovf_val = w.wh.q16_ovf_val;
                     a.d[d].h0 = h0 ? h0 + m->soff(n) * B : nullptr;
                     a.d[d].c0 = c0 ? c0 + m->soff(n) * B : nullptr;
                     a.d[d].y = Yout + (size_t)d * H; a.d[d].y_ld = y_ld;
                     a.d[d].hT = hT ? hT + m->soff(n) * B : nullptr;
                     a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
                     a.d[d].reverse = d;
-                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16(s%d,u%d,b%d);", l, d,
-                                  (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr", q16, upw, bw);
+                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16%s(s%d,u%d,b%d);", l, d,
+                                  (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
+                                  w.wh.q16_ovf_ptr ? "+ovf" : "", q16, upw, bw);
                     m->last_plan += tag;
                 }
                 a.T = T; a.B = B; a.H = H; a.round_h_bf16 = bf16;

@@ -216,7 +216,9 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
     float* xbuf = lds + (size_t)NL * H;
     float* pub = xbuf + 2 * (size_t)a.D0;
     const int tid = threadIdx.x, nthreads = blockDim.x;
-    const int lane = tid & 63, wave = tid >> 6, nwaves = nthreads >> 6;
+    // the wave index as a scalar: everything derived from it (layer, unit, liveness) is then wave-uniform for the compiler
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), nwaves = nthreads >> 6;
     const int upb = nwaves / NL;
     const int l = wave / upb;                       // layer served by this wave
     const int j = blockIdx.x * upb + (wave % upb);  // hidden unit
@@ -307,13 +309,21 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
     if (lane < noh) { oeh = oenh[obh + lane]; ovh = ovlh[obh + lane]; }
     nox = __builtin_amdgcn_readfirstlane(nox);
     noh = __builtin_amdgcn_readfirstlane(noh);
-    // lane e adds its overflow product to the partial sum of the gate its entry belongs to
-    auto add_overflow = [&](float (&acc)[4], int n, unsigned ent, float val, const float* vec) {
-        if (n > 0) {
-            const float t = lane < n ? val * vec[ent & 0xFFFFu] : 0.f;
-            const unsigned q = ent >> 16;
+    // lane e adds its overflow product to the partial sum of the gate its entry belongs to: the value is kept once per
+    // gate (zero for the other three), so that a step needs neither a comparison nor a lane mask for it; lanes without
+    // an entry hold value 0 and column 0.  The branch is wave-uniform (n is a scalar) and most waves skip it.
+    float ovxq[4], ovhq[4];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) acc[g] += (q == (unsigned)g) ? t : 0.f;
+    for (int g = 0; g < 4; ++g) {
+        ovxq[g] = (oex >> 16) == (unsigned)g ? ovx : 0.f;
+        ovhq[g] = (oeh >> 16) == (unsigned)g ? ovh : 0.f;
+    }
+    const unsigned ocx = oex & 0xFFFFu, och = oeh & 0xFFFFu;
+    auto add_overflow = [&](float (&acc)[4], int n, unsigned col, const float (&valq)[4], const float* vec) {
+        if (n > 0) {
+            const float x = vec[col];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) acc[g] = fmaf(valq[g], x, acc[g]);
         }
     };
 #define COLX(q, i) ((cxp[q][(i) >> 1] >> (16 * ((i) & 1))) & 0xFFFFu)
@@ -357,7 +367,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
             for (int i = 0; i < NZ; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) xacc[q] = fmaf(vx[q][i], xb[COLX(q, i)], xacc[q]);
-            add_overflow(xacc, nox, oex, ovx, xb);
+            add_overflow(xacc, nox, ocx, ovxq, xb);
         }
     };
     park_x(0);
@@ -396,13 +406,13 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
                 for (int i = 0; i < NZ; ++i)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) acc[q] = fmaf(vx[q][i], hin[COLX(q, i)], acc[q]);
-                add_overflow(acc, nox, oex, ovx, hin);
+                add_overflow(acc, nox, ocx, ovxq, hin);
             }
 #pragma unroll
             for (int i = 0; i < NZ; ++i)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) acc[q] = fmaf(vh[q][i], hrec[COLH(q, i)], acc[q]);
-            add_overflow(acc, noh, oeh, ovh, hrec);
+            add_overflow(acc, noh, och, ovhq, hrec);
             const float pre = wave_sum4_rows(acc[0], acc[1], acc[2], acc[3]) + bias_l;
             h = lstm_cell_rows(pre, lane, c);
         }

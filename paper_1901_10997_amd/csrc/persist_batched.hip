@@ -89,6 +89,31 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
             }
         }
     }
+    // The few entries of rows longer than 16 S (at most 8 per unit, so at most 64 per wave; most waves have none):
+    // lane e holds entry e of the wave's run of lists -- value, LDS byte offset of its column, and the lane that
+    // collects its gate's total for batch column 0 (16 * gate + local unit * BW).
+    float ovf_v = 0.f;
+    unsigned ovf_off = 0u;
+    int ovf_lane = 0, ovf_n = 0;
+    if (D.q16_ovf_ptr != nullptr && u0 < H) {
+        const int first = D.q16_ovf_ptr[u0];
+        const int idx = first + lane;
+        int pos = first;
+#pragma unroll
+        for (int u = 0; u < UPW; ++u) {
+            const int nxt = (u0 + u < H) ? D.q16_ovf_ptr[u0 + u + 1] : pos;
+            if (idx >= pos && idx < nxt) {
+                const unsigned e = D.q16_ovf_ent[idx];
+                ovf_off = (e & 0xFFFFu) * (BW * 4u);
+                ovf_lane = 16 * (int)(e >> 16) + u * BW;
+                ovf_v = D.q16_ovf_val[idx];
+            }
+            pos = nxt;
+        }
+        ovf_n = pos - first;
+        ovf_n = ovf_n < 64 ? ovf_n : 64;
+    }
+    ovf_n = __builtin_amdgcn_readfirstlane(ovf_n);
     // lane 16*gate + pair: pair = local unit * BW + column
     const int lp = lane & 15, row = lane >> 4;
     const int pu = lp / BW, pb = lp % BW;
@@ -189,6 +214,19 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
                         G = (lp == u * BW + b) ? r : G;
                     }
                 }
+            }
+        }
+        for (int e = 0; e < ovf_n; ++e) {   // wave-uniform trip count, zero in almost every wave
+            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ovf_v), e));
+            const unsigned off = (unsigned)__builtin_amdgcn_readlane((int)ovf_off, e);
+            const int tgt = __builtin_amdgcn_readlane(ovf_lane, e);
+            using VT = typename std::conditional<BW == 2, float2, float4>::type;
+            const VT x = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + off);
+            G += (lane == tgt) ? v * x.x : 0.f;
+            G += (lane == tgt + 1) ? v * x.y : 0.f;
+            if constexpr (BW == 4) {
+                G += (lane == tgt + 2) ? v * x.z : 0.f;
+                G += (lane == tgt + 3) ? v * x.w : 0.f;
             }
         }
         G += pin;

@@ -106,6 +106,33 @@ def test_small_batch_persistent_overflow_rows(shape):
     assert "persist_batched-q16" in desc
 
 
+@pytest.mark.parametrize("shape", [
+    # bidir, D, H, T, B, keep, long rows (packed row = 4 * unit + gate), extra entries per long row
+    (False, 48, 256, 6, 5, 0.2, (0, 1, 402, 1023), 4),       # two long rows in one unit, one in the last unit
+    (True, 40, 300, 5, 12, 0.15, (7, 600, 601, 1198), 3),
+    (False, 32, 520, 4, 3, 0.1, (5, 2079), 8),                # the most a unit may hold outside the slots
+])
+def test_small_batch_persistent_rows_longer_than_the_slots(shape):
+    """A handful of recurrent rows a few entries longer than all others: the slot count follows the common row
+    length and those entries are added one at a time by the waves that own them."""
+    bidir, D, H, T, Bn, keep, rows, extra = shape
+    case = inputs.make_case(_wl(97, 1, bidir, D, H, T, Bn, keep=keep), k=H + Bn, random_state=True)
+    for (l, d), p in case.weights.items():
+        Mh = p["Mh"]
+        # every row to the same length (a multiple of 32: the slots are then exactly full), the chosen rows longer
+        target = 32 * max(1, int(round(keep * H / 32.0)))
+        for r in range(4 * H):
+            on = np.flatnonzero(Mh[r])
+            off = np.flatnonzero(Mh[r] == 0)
+            want = target + (extra if ((r % H) * 4 + r // H) in rows else 0)   # ABI row q*H + j is packed row 4j + q
+            if len(on) > want:
+                Mh[r, on[want:]] = 0
+            elif len(on) < want:
+                Mh[r, off[:want - len(on)]] = 1
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "persist_batched-q16+ovf" in desc
+
+
 def test_bf16_small():
     for Bn, keep in ((1, None), (3, 0.3), (9, None)):
         case = inputs.make_case(_wl(92, 2, False, 48, 96, 6, Bn, dtype="bf16", a=0.2, keep=keep), k=Bn, random_state=True)
