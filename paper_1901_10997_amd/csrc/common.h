@@ -40,7 +40,7 @@ struct PackedMat {
     int q16_slots = 0;            // even; 16 q16_slots entries of every row are in the slots
     float* q16_val = nullptr;
     uint16_t* q16_col = nullptr;
-    // the few entries of rows longer than that (at most 8 per unit), per unit: entry = (gate << 16) | column; or nullptr
+    // the few entries of rows longer than that (at most 6 in any eight consecutive units), per unit: entry = (gate << 16) | column; or nullptr
     int32_t* q16_ovf_ptr = nullptr;   // device [rows/4 + 1]
     uint32_t* q16_ovf_ent = nullptr;
     float* q16_ovf_val = nullptr;

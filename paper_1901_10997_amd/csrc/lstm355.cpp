@@ -136,6 +136,150 @@ static hipError_t upload(T** dst, const std::vector<T>& src)
     return e;
 }
 
+// Quarter-wave form for the small-batch kernel: slot s of unit j is one 64-lane gather that serves all four gate
+// rows, gate q on lanes 16q..16q+15.  An 8-byte gather serves lanes 0..31 (gates 0, 1) and 32..63 (gates 2, 3) in
+// separate passes whose 32 columns must differ modulo 32.  Within a pass bank b (= column mod 32) belongs to lane
+// b mod 16 of one of the two rows: in slot s row q owns the banks of half (s + q) mod 2.  An entry goes to a
+// position that owns its bank (S/2 slots per row and bank).  What does not fit there is placed in a free lane of a
+// slot in which the OTHER row of the pass owns the entry's bank but has nothing to put there: that position's
+// filler (value 0) is pointed at the entry's own column, the two lanes read one address, and nothing collides.  Among
+// the free lanes one whose bits 2 and 3 differ in parity from the owner's is preferred, which keeps the 16-byte
+// gather (four passes of 16 lanes, picked by lane bit 5 and the parity of bits 2..4) free of collisions as well.
+// Only an entry for which no such slot exists takes any free position, from the end.
+// force_slots > 0: that many slots (the other direction of the layer uses them: one launch serves both, and the
+// kernel is built for the larger count) instead of the smallest count the rule below allows.
+static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
+{
+    if (out.q16_val) (void)hipFree(out.q16_val);
+    if (out.q16_col) (void)hipFree(out.q16_col);
+    if (out.q16_ovf_ptr) (void)hipFree(out.q16_ovf_ptr);
+    if (out.q16_ovf_ent) (void)hipFree(out.q16_ovf_ent);
+    if (out.q16_ovf_val) (void)hipFree(out.q16_ovf_val);
+    out.q16_val = nullptr; out.q16_col = nullptr; out.q16_ovf_ptr = nullptr; out.q16_ovf_ent = nullptr; out.q16_ovf_val = nullptr;
+    out.q16_slots = 0;
+    const int rows = out.rows, cols = out.cols, max_nnz = out.max_row_nnz;
+    if (!out.compressed || max_nnz > 256 || rows < 4) return LSTM_OK;
+    {
+        const int units = rows / 4;
+        // The slot count is set by the longest row, and with random masks a handful of rows are a few entries longer
+        // than all others.  Take the smallest (even) count that leaves at most 6 entries outside the slots in any eight
+        // consecutive units (a wave owns at most eight): the owning wave adds those one at a time, which costs it about
+        // as much per entry as a tenth of a slot, and the step waits for the slowest wave.
+        int S = std::max(2, 2 * ((max_nnz + 31) / 32));
+        if (force_slots > 0) S = std::max(2, std::min(S, force_slots + (force_slots & 1)));
+        else {
+            std::vector<int> per_unit((size_t)units);
+            for (int St = 2; St < S; St += 2) {
+                for (int u = 0; u < units; ++u) {
+                    int64_t n = 0;
+                    for (int q = 0; q < 4; ++q)
+                        n += std::max<int64_t>(0, out.h_row_ptr[4 * u + q + 1] - out.h_row_ptr[4 * u + q] - (int64_t)16 * St);
+                    per_unit[(size_t)u] = (int)std::min<int64_t>(n, 1 << 20);
+                }
+                int64_t window = 0, worst = 0;
+                for (int u = 0; u < units; ++u) {
+                    window += per_unit[(size_t)u];
+                    if (u >= 8) window -= per_unit[(size_t)u - 8];
+                    worst = std::max(worst, window);
+                }
+                if (worst <= 6) { S = St; break; }
+            }
+        }
+        std::vector<float> qv((size_t)units * S * 64, 0.0f);
+        std::vector<uint16_t> qc((size_t)units * S * 64, 0);
+        std::vector<char> used((size_t)S * 64), aliased((size_t)S * 64);
+        std::vector<int64_t> leftover[4];
+        auto par23 = [](int j) { return ((j >> 2) ^ (j >> 3)) & 1; };
+        for (int u = 0; u < units; ++u) {
+            std::fill(used.begin(), used.end(), 0);
+            std::fill(aliased.begin(), aliased.end(), 0);
+            float* uv = qv.data() + (size_t)u * S * 64;
+            uint16_t* uc = qc.data() + (size_t)u * S * 64;
+            for (int sl = 0; sl < S; ++sl)
+                for (int ln = 0; ln < 64; ++ln) {
+                    const int c = (ln & 15) + 16 * ((sl + (ln >> 4)) & 1);   // a column of the bank this position owns
+                    uc[sl * 64 + ln] = (uint16_t)(c < cols ? c : 0);
+                }
+            for (int q = 0; q < 4; ++q) {
+                const int rp = 4 * u + q;
+                int fill[32] = {0};
+                leftover[q].clear();
+                const int64_t row_end = std::min<int64_t>(out.h_row_ptr[rp + 1], out.h_row_ptr[rp] + (int64_t)16 * S);
+                for (int64_t e = out.h_row_ptr[rp]; e < row_end; ++e) {
+                    const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
+                    if (fill[bank] < S / 2) {
+                        const int sl = 2 * fill[bank] + ((hb + q) & 1);
+                        ++fill[bank];
+                        const int pos = sl * 64 + 16 * q + j;
+                        used[pos] = 1;
+                        uv[pos] = out.h_val[e];
+                        uc[pos] = (uint16_t)out.h_col[e];
+                    } else {
+                        leftover[q].push_back(e);
+                    }
+                }
+            }
+            for (int q = 0; q < 4; ++q) {
+                for (int64_t e : leftover[q]) {
+                    const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
+                    int best = -1, best_owner = -1;
+                    for (int sl = ((hb + (q ^ 1)) & 1); sl < S && best < 0; sl += 2) {   // slots where the other row owns `bank`
+                        const int owner = sl * 64 + 16 * (q ^ 1) + j;
+                        if (used[owner] || aliased[owner]) continue;
+                        int any = -1;
+                        for (int jj = 0; jj < 16; ++jj) {
+                            const int pos = sl * 64 + 16 * q + jj;
+                            if (used[pos] || aliased[pos]) continue;
+                            if (par23(jj) != par23(j)) { best = pos; break; }
+                            if (any < 0) any = pos;
+                        }
+                        if (best < 0) best = any;
+                        if (best >= 0) best_owner = owner;
+                    }
+                    if (best >= 0) {
+                        aliased[best_owner] = 1;
+                        uc[best_owner] = (uint16_t)out.h_col[e];
+                    } else {
+                        // no such slot: any free position of the row, from the end; a filler that serves the other row's
+                        // entry is given up only when nothing else is left (the row holds at most 16 S entries)
+                        for (int pass = 0; pass < 2 && best < 0; ++pass)
+                            for (int t = S * 16 - 1; t >= 0 && best < 0; --t) {
+                                const int pos = (t / 16) * 64 + 16 * q + (t & 15);
+                                if (!used[pos] && (pass == 1 || !aliased[pos])) best = pos;
+                            }
+                        aliased[best] = 0;
+                    }
+                    used[best] = 1;
+                    uv[best] = out.h_val[e];
+                    uc[best] = (uint16_t)out.h_col[e];
+                }
+            }
+        }
+        out.q16_slots = S;
+        HIP_TRY(m, upload(&out.q16_val, qv));
+        HIP_TRY(m, upload(&out.q16_col, qc));
+        std::vector<int32_t> optr((size_t)units + 1, 0);
+        std::vector<uint32_t> oe;
+        std::vector<float> ov;
+        for (int u = 0; u < units; ++u) {
+            for (int q = 0; q < 4; ++q) {
+                const int rp = 4 * u + q;
+                for (int64_t e = out.h_row_ptr[rp] + (int64_t)16 * S; e < out.h_row_ptr[rp + 1]; ++e) {
+                    oe.push_back(((uint32_t)q << 16) | (uint32_t)out.h_col[e]);
+                    ov.push_back(out.h_val[e]);
+                }
+            }
+            optr[(size_t)u + 1] = (int32_t)oe.size();
+        }
+        if (!oe.empty()) {
+            HIP_TRY(m, upload(&out.q16_ovf_ptr, optr));
+            HIP_TRY(m, upload(&out.q16_ovf_ent, oe));
+            HIP_TRY(m, upload(&out.q16_ovf_val, ov));
+        }
+    }
+    return LSTM_OK;
+}
+
 // Pack one matrix W[4H][cols] (ABI row order q*H + j) with its optional mask into device storage.
 static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t* mask, int H, int cols, bool compressed,
                        bool bf16, bool keep_dense, bool quarter_rows = false)
@@ -296,125 +440,7 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
             break;
         }
     }
-    // Quarter-wave form for the small-batch kernel: slot s of unit j is one 64-lane gather that serves all four gate
-    // rows, gate q on lanes 16q..16q+15.  An 8-byte gather serves lanes 0..31 (gates 0, 1) and 32..63 (gates 2, 3) in
-    // separate passes whose 32 columns must differ modulo 32.  Within a pass bank b (= column mod 32) belongs to lane
-    // b mod 16 of one of the two rows: in slot s row q owns the banks of half (s + q) mod 2.  An entry goes to a
-    // position that owns its bank (S/2 slots per row and bank).  What does not fit there is placed in a free lane of a
-    // slot in which the OTHER row of the pass owns the entry's bank but has nothing to put there: that position's
-    // filler (value 0) is pointed at the entry's own column, the two lanes read one address, and nothing collides.  Among
-    // the free lanes one whose bits 2 and 3 differ in parity from the owner's is preferred, which keeps the 16-byte
-    // gather (four passes of 16 lanes, picked by lane bit 5 and the parity of bits 2..4) free of collisions as well.
-    // Only an entry for which no such slot exists takes any free position, from the end.
-    if (quarter_rows && max_nnz <= 256 && rows >= 4) {
-        const int units = rows / 4;
-        // The slot count is set by the longest row, and with random masks a handful of rows are a few entries longer
-        // than all others.  Take the smallest (even) count that leaves at most 8 entries per unit and rows / 64 entries
-        // in all outside the slots; a wave adds those one at a time (rare: most waves have none).
-        int S = std::max(2, 2 * ((max_nnz + 31) / 32));
-        for (int St = 2; St < S; St += 2) {
-            int64_t worst = 0, total = 0;
-            for (int u = 0; u < units; ++u) {
-                int64_t per_unit = 0;
-                for (int q = 0; q < 4; ++q)
-                    per_unit += std::max<int64_t>(0, out.h_row_ptr[4 * u + q + 1] - out.h_row_ptr[4 * u + q] - (int64_t)16 * St);
-                worst = std::max(worst, per_unit);
-                total += per_unit;
-            }
-            if (worst <= 8 && total <= rows / 64) { S = St; break; }
-        }
-        std::vector<float> qv((size_t)units * S * 64, 0.0f);
-        std::vector<uint16_t> qc((size_t)units * S * 64, 0);
-        std::vector<char> used((size_t)S * 64), aliased((size_t)S * 64);
-        std::vector<int64_t> leftover[4];
-        auto par23 = [](int j) { return ((j >> 2) ^ (j >> 3)) & 1; };
-        for (int u = 0; u < units; ++u) {
-            std::fill(used.begin(), used.end(), 0);
-            std::fill(aliased.begin(), aliased.end(), 0);
-            float* uv = qv.data() + (size_t)u * S * 64;
-            uint16_t* uc = qc.data() + (size_t)u * S * 64;
-            for (int sl = 0; sl < S; ++sl)
-                for (int ln = 0; ln < 64; ++ln) {
-                    const int c = (ln & 15) + 16 * ((sl + (ln >> 4)) & 1);   // a column of the bank this position owns
-                    uc[sl * 64 + ln] = (uint16_t)(c < cols ? c : 0);
-                }
-            for (int q = 0; q < 4; ++q) {
-                const int rp = 4 * u + q;
-                int fill[32] = {0};
-                leftover[q].clear();
-                const int64_t row_end = std::min<int64_t>(out.h_row_ptr[rp + 1], out.h_row_ptr[rp] + (int64_t)16 * S);
-                for (int64_t e = out.h_row_ptr[rp]; e < row_end; ++e) {
-                    const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
-                    if (fill[bank] < S / 2) {
-                        const int sl = 2 * fill[bank] + ((hb + q) & 1);
-                        ++fill[bank];
-                        const int pos = sl * 64 + 16 * q + j;
-                        used[pos] = 1;
-                        uv[pos] = out.h_val[e];
-                        uc[pos] = (uint16_t)out.h_col[e];
-                    } else {
-                        leftover[q].push_back(e);
-                    }
-                }
-            }
-            for (int q = 0; q < 4; ++q) {
-                for (int64_t e : leftover[q]) {
-                    const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
-                    int best = -1, best_owner = -1;
-                    for (int sl = ((hb + (q ^ 1)) & 1); sl < S && best < 0; sl += 2) {   // slots where the other row owns `bank`
-                        const int owner = sl * 64 + 16 * (q ^ 1) + j;
-                        if (used[owner] || aliased[owner]) continue;
-                        int any = -1;
-                        for (int jj = 0; jj < 16; ++jj) {
-                            const int pos = sl * 64 + 16 * q + jj;
-                            if (used[pos] || aliased[pos]) continue;
-                            if (par23(jj) != par23(j)) { best = pos; break; }
-                            if (any < 0) any = pos;
-                        }
-                        if (best < 0) best = any;
-                        if (best >= 0) best_owner = owner;
-                    }
-                    if (best >= 0) {
-                        aliased[best_owner] = 1;
-                        uc[best_owner] = (uint16_t)out.h_col[e];
-                    } else {
-                        // no such slot: any free position of the row, from the end; a filler that serves the other row's
-                        // entry is given up only when nothing else is left (the row holds at most 16 S entries)
-                        for (int pass = 0; pass < 2 && best < 0; ++pass)
-                            for (int t = S * 16 - 1; t >= 0 && best < 0; --t) {
-                                const int pos = (t / 16) * 64 + 16 * q + (t & 15);
-                                if (!used[pos] && (pass == 1 || !aliased[pos])) best = pos;
-                            }
-                        aliased[best] = 0;
-                    }
-                    used[best] = 1;
-                    uv[best] = out.h_val[e];
-                    uc[best] = (uint16_t)out.h_col[e];
-                }
-            }
-        }
-        out.q16_slots = S;
-        HIP_TRY(m, upload(&out.q16_val, qv));
-        HIP_TRY(m, upload(&out.q16_col, qc));
-        std::vector<int32_t> optr((size_t)units + 1, 0);
-        std::vector<uint32_t> oe;
-        std::vector<float> ov;
-        for (int u = 0; u < units; ++u) {
-            for (int q = 0; q < 4; ++q) {
-                const int rp = 4 * u + q;
-                for (int64_t e = out.h_row_ptr[rp] + (int64_t)16 * S; e < out.h_row_ptr[rp + 1]; ++e) {
-                    oe.push_back(((uint32_t)q << 16) | (uint32_t)out.h_col[e]);
-                    ov.push_back(out.h_val[e]);
-                }
-            }
-            optr[(size_t)u + 1] = (int32_t)oe.size();
-        }
-        if (!oe.empty()) {
-            HIP_TRY(m, upload(&out.q16_ovf_ptr, optr));
-            HIP_TRY(m, upload(&out.q16_ovf_ent, oe));
-            HIP_TRY(m, upload(&out.q16_ovf_val, ov));
-        }
-    }
+    if (quarter_rows) return build_quarter_wave(m, out, 0);
     return LSTM_OK;
 }
 
@@ -565,6 +591,16 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     if (x.bias) { (void)hipFree(x.bias); x.bias = nullptr; }
     HIP_TRY(m, upload(&x.bias, bp));
     x.set = true;
+    // One launch serves both directions of a layer and is built for the larger slot count: a direction trimmed further
+    // than the other would pay for the other's slots and for its own entries outside them.
+    if (m->Dn == 2) {
+        LayerDir& o = m->ld[(size_t)layer * 2 + (size_t)(1 - direction)];
+        if (o.set && x.wh.q16_slots > 0 && o.wh.q16_slots > 0 && x.wh.q16_slots != o.wh.q16_slots) {
+            const int target = std::max(x.wh.q16_slots, o.wh.q16_slots);
+            rc = build_quarter_wave(m, x.wh.q16_slots < target ? x.wh : o.wh, target);
+            if (rc != LSTM_OK) return rc;
+        }
+    }
     return LSTM_OK;
 }
 

@@ -89,7 +89,7 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
             }
         }
     }
-    // The few entries of rows longer than 16 S (at most 8 per unit, so at most 64 per wave; most waves have none):
+    // The few entries of rows longer than 16 S (at most 6 per wave; most waves have none):
     // lane e holds entry e of the wave's run of lists -- value, LDS byte offset of its column, and the lane that
     // collects its gate's total for batch column 0 (16 * gate + local unit * BW).
     float ovf_v = 0.f;
@@ -216,17 +216,21 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
                 }
             }
         }
-        for (int e = 0; e < ovf_n; ++e) {   // wave-uniform trip count, zero in almost every wave
-            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ovf_v), e));
-            const unsigned off = (unsigned)__builtin_amdgcn_readlane((int)ovf_off, e);
-            const int tgt = __builtin_amdgcn_readlane(ovf_lane, e);
+        if (ovf_n > 0) {   // wave-uniform; false in almost every wave
+            // every lane multiplies its own entry (one gather for all of them); the products are then handed to the lanes
+            // that collect their gates' totals, one entry at a time, without further memory accesses
             using VT = typename std::conditional<BW == 2, float2, float4>::type;
-            const VT x = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + off);
-            G += (lane == tgt) ? v * x.x : 0.f;
-            G += (lane == tgt + 1) ? v * x.y : 0.f;
-            if constexpr (BW == 4) {
-                G += (lane == tgt + 2) ? v * x.z : 0.f;
-                G += (lane == tgt + 3) ? v * x.w : 0.f;
+            const VT x = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + ovf_off);
+            float pr[BW];
+            pr[0] = ovf_v * x.x; pr[1] = ovf_v * x.y;
+            if constexpr (BW == 4) { pr[2] = ovf_v * x.z; pr[3] = ovf_v * x.w; }
+            for (int e = 0; e < ovf_n; ++e) {
+                const int tgt = __builtin_amdgcn_readlane(ovf_lane, e);
+#pragma unroll
+                for (int b = 0; b < BW; ++b) {
+                    const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr[b]), e));
+                    G += (lane == tgt + b) ? v : 0.f;
+                }
             }
         }
         G += pin;

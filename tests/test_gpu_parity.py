@@ -108,9 +108,9 @@ def test_small_batch_persistent_overflow_rows(shape):
 
 @pytest.mark.parametrize("shape", [
     # bidir, D, H, T, B, keep, long rows (packed row = 4 * unit + gate), extra entries per long row
-    (False, 48, 256, 6, 5, 0.2, (0, 1, 402, 1023), 4),       # two long rows in one unit, one in the last unit
-    (True, 40, 300, 5, 12, 0.15, (7, 600, 601, 1198), 3),
-    (False, 32, 520, 4, 3, 0.1, (5, 2079), 8),                # the most a unit may hold outside the slots
+    (False, 48, 256, 6, 5, 0.2, (0, 1, 402, 1023), 2),       # two long rows in one unit, one in the last unit
+    (True, 40, 300, 5, 12, 0.15, (7, 600, 601, 1198), 2),
+    (False, 32, 520, 4, 3, 0.1, (5, 2079), 4),                # the most a unit may hold outside the slots
 ])
 def test_small_batch_persistent_rows_longer_than_the_slots(shape):
     """A handful of recurrent rows a few entries longer than all others: the slot count follows the common row
