@@ -345,6 +345,25 @@ struct PersistBatchedArgs {
     int* timeout_flag;
     unsigned spin_limit;
 };
+// Input projection with W_x in the quarter-wave form, for many input rows (fp32): P[m][4H] = b + W_x . X[m]
+struct ProjQ16Dir {
+    const float* val;            // [H][slots][64]
+    const uint16_t* col;
+    int slots;
+    const int32_t* ovf_ptr;      // entries outside the slots, per unit; or nullptr
+    const uint32_t* ovf_ent;     // (gate << 16) | column
+    const float* ovf_val;
+    const float* bias;           // [4H] packed rows
+    float* P;                    // [M][4H]
+};
+struct ProjQ16Args {
+    ProjQ16Dir d[2];
+    const float* X;              // [M][ldx], K columns used
+    int ldx, M, K, H;
+};
+bool proj_q16_supported(int M, int H, int K, int slots);
+hipError_t launch_proj_q16(const ProjQ16Args& a, int ndir, int slots, hipStream_t s);
+
 // `slots` = the largest q16_slots of the directions (even, <= 16)
 bool persist_batched_q16_plan(int B, int H, int slots, int ndir, int* upw, int* bw, int* ug, int* bg);
 hipError_t launch_persist_batched_q16(PersistBatchedArgs& a, int ndir, int slots, int cooperative, hipStream_t s);

@@ -46,6 +46,36 @@ __device__ __forceinline__ float dpp_add(float v)
 {
     return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
+// v[p] (p = 0..15) holds this lane's partial sum of quantity p.  Returns, in lane l of every 16-lane row, the sum of
+// v[l] over the 16 lanes of the row.  Four stages: the lanes are paired by row mirror (l ^ 15), half-row mirror (l ^ 7),
+// quad mirror (l ^ 3) and neighbour swap (l ^ 1) -- together they reach all 16 lanes -- and after adding its partner's
+// value a lane keeps the quantities whose index bit 3, 2, 1, 0 equals its own lane-index bit (which differs between the
+// two partners in every stage), so the registers halve: 8, 4, 2, 1.
+__device__ __forceinline__ float row16_transpose_sum(const float (&v)[16], int lane_in_row)
+{
+    float a[8], b[4], c[2];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        const float lo = dpp_add<0x140>(v[p]), hi = dpp_add<0x140>(v[p + 8]);
+        // lanes 8..15 (DPP banks 2, 3) take the upper eight quantities
+        a[p] = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(lo), __float_as_int(hi), 0xE4, 0xF, 0xC, false));
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const float lo = dpp_add<0x141>(a[p]), hi = dpp_add<0x141>(a[p + 4]);
+        // lanes 4..7 and 12..15 (banks 1, 3)
+        b[p] = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(lo), __float_as_int(hi), 0xE4, 0xF, 0xA, false));
+    }
+    const bool b1 = (lane_in_row & 2) != 0, b0 = (lane_in_row & 1) != 0;
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const float lo = dpp_add<0x1B>(b[p]), hi = dpp_add<0x1B>(b[p + 2]);   // quad_perm [3,2,1,0]
+        c[p] = b1 ? hi : lo;
+    }
+    const float lo = dpp_add<0xB1>(c[0]), hi = dpp_add<0xB1>(c[1]);           // quad_perm [1,0,3,2]
+    return b0 ? hi : lo;
+}
+
 // Sum four per-lane values over the wavefront: returns a register in which every lane of row q (lanes
 // 16q..16q+15) holds the wave-wide total of a_q.  The four values are first distributed over the four 16-lane
 // rows with the gfx950 lane-swap instructions (lanes 32..63 of one register against lanes 0..31 of another, then

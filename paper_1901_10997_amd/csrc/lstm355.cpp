@@ -147,8 +147,15 @@ static hipError_t upload(T** dst, const std::vector<T>& src)
 // gather (four passes of 16 lanes, picked by lane bit 5 and the parity of bits 2..4) free of collisions as well.
 // Only an entry for which no such slot exists takes any free position, from the end.
 // force_slots > 0: that many slots (the other direction of the layer uses them: one launch serves both, and the
-// kernel is built for the larger count) instead of the smallest count the rule below allows.
-static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
+// kernel is built for the larger count) instead of the smallest count the rule below allows.  max_slots: the most the
+// consuming kernel takes (16 in the recurrence, 24 in the projection); nothing is built for longer rows.
+// gather16: the consumer gathers 16 bytes per entry only (the projection: four input rows per tile).  Such a gather makes
+// four passes of 16 lanes -- lane bit 5 and the parity of bits 2..4 pick the pass, so a pass holds eight lanes of each
+// of two rows, with complementary parities of bits 2, 3 -- whose columns must differ modulo 16.  An entry then goes to
+// lane (column mod 16) of its row in any slot (S places per row and lane instead of S/2 per row and bank), and one that
+// does not fit goes to a free lane of the other parity class in a slot where the other row has nothing at lane
+// (column mod 16), whose filler is pointed at the entry's column.
+static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int max_slots, bool gather16 = false)
 {
     if (out.q16_val) (void)hipFree(out.q16_val);
     if (out.q16_col) (void)hipFree(out.q16_col);
@@ -158,7 +165,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
     out.q16_val = nullptr; out.q16_col = nullptr; out.q16_ovf_ptr = nullptr; out.q16_ovf_ent = nullptr; out.q16_ovf_val = nullptr;
     out.q16_slots = 0;
     const int rows = out.rows, cols = out.cols, max_nnz = out.max_row_nnz;
-    if (!out.compressed || max_nnz > 256 || rows < 4) return LSTM_OK;
+    if (!out.compressed || max_slots < 2 || rows < 4 || cols > 4095) return LSTM_OK;
     {
         const int units = rows / 4;
         // The slot count is set by the longest row, and with random masks a handful of rows are a few entries longer
@@ -185,6 +192,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
                 if (worst <= 6) { S = St; break; }
             }
         }
+        if (S > max_slots) return LSTM_OK;   // rows too long for the kernels that use this form
         std::vector<float> qv((size_t)units * S * 64, 0.0f);
         std::vector<uint16_t> qc((size_t)units * S * 64, 0);
         std::vector<char> used((size_t)S * 64), aliased((size_t)S * 64);
@@ -197,7 +205,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
             uint16_t* uc = qc.data() + (size_t)u * S * 64;
             for (int sl = 0; sl < S; ++sl)
                 for (int ln = 0; ln < 64; ++ln) {
-                    const int c = (ln & 15) + 16 * ((sl + (ln >> 4)) & 1);   // a column of the bank this position owns
+                    const int c = (ln & 15) + (gather16 ? 0 : 16 * ((sl + (ln >> 4)) & 1));   // a column of the bank this position owns
                     uc[sl * 64 + ln] = (uint16_t)(c < cols ? c : 0);
                 }
             for (int q = 0; q < 4; ++q) {
@@ -206,9 +214,9 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
                 leftover[q].clear();
                 const int64_t row_end = std::min<int64_t>(out.h_row_ptr[rp + 1], out.h_row_ptr[rp] + (int64_t)16 * S);
                 for (int64_t e = out.h_row_ptr[rp]; e < row_end; ++e) {
-                    const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
-                    if (fill[bank] < S / 2) {
-                        const int sl = 2 * fill[bank] + ((hb + q) & 1);
+                    const int bank = gather16 ? (out.h_col[e] & 15) : (out.h_col[e] & 31), j = bank & 15, hb = bank >> 4;
+                    if (fill[bank] < (gather16 ? S : S / 2)) {
+                        const int sl = gather16 ? fill[bank] : 2 * fill[bank] + ((hb + q) & 1);
                         ++fill[bank];
                         const int pos = sl * 64 + 16 * q + j;
                         used[pos] = 1;
@@ -221,9 +229,11 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
             }
             for (int q = 0; q < 4; ++q) {
                 for (int64_t e : leftover[q]) {
-                    const int bank = out.h_col[e] & 31, j = bank & 15, hb = bank >> 4;
+                    const int bank = gather16 ? (out.h_col[e] & 15) : (out.h_col[e] & 31), j = bank & 15, hb = bank >> 4;
                     int best = -1, best_owner = -1;
-                    for (int sl = ((hb + (q ^ 1)) & 1); sl < S && best < 0; sl += 2) {   // slots where the other row owns `bank`
+                    // slots where the other row owns `bank` (every slot for 16-byte gathers, where only a lane of the other
+                    // parity class shares a pass with the other row's lane j)
+                    for (int sl = gather16 ? 0 : ((hb + (q ^ 1)) & 1); sl < S && best < 0; sl += gather16 ? 1 : 2) {
                         const int owner = sl * 64 + 16 * (q ^ 1) + j;
                         if (used[owner] || aliased[owner]) continue;
                         int any = -1;
@@ -231,7 +241,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
                             const int pos = sl * 64 + 16 * q + jj;
                             if (used[pos] || aliased[pos]) continue;
                             if (par23(jj) != par23(j)) { best = pos; break; }
-                            if (any < 0) any = pos;
+                            if (any < 0 && !gather16) any = pos;
                         }
                         if (best < 0) best = any;
                         if (best >= 0) best_owner = owner;
@@ -282,7 +292,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots)
 
 // Pack one matrix W[4H][cols] (ABI row order q*H + j) with its optional mask into device storage.
 static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t* mask, int H, int cols, bool compressed,
-                       bool bf16, bool keep_dense, bool quarter_rows = false)
+                       bool bf16, bool keep_dense, int quarter_slots = 0)
 {
     free_mat(out);
     const int rows = 4 * H;
@@ -440,7 +450,7 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
             break;
         }
     }
-    if (quarter_rows) return build_quarter_wave(m, out, 0);
+    if (quarter_slots > 0) return build_quarter_wave(m, out, 0, quarter_slots, quarter_slots > 16);
     return LSTM_OK;
 }
 
@@ -582,9 +592,9 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     x.set = false;
     const bool bf16 = (m->dtype == LSTM_BF16);
     // W_x is kept in both forms when compressed: large T*B projections run dense on the matrix cores
-    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16, true);
+    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16, true, bf16 ? 0 : 24);
     if (rc != LSTM_OK) return rc;
-    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16, false, true);
+    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16, false, 16);
     if (rc != LSTM_OK) return rc;
     std::vector<float> bp(rows);
     for (int rp = 0; rp < rows; ++rp) bp[rp] = b[(rp & 3) * H + (rp >> 2)];
@@ -597,7 +607,12 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
         LayerDir& o = m->ld[(size_t)layer * 2 + (size_t)(1 - direction)];
         if (o.set && x.wh.q16_slots > 0 && o.wh.q16_slots > 0 && x.wh.q16_slots != o.wh.q16_slots) {
             const int target = std::max(x.wh.q16_slots, o.wh.q16_slots);
-            rc = build_quarter_wave(m, x.wh.q16_slots < target ? x.wh : o.wh, target);
+            rc = build_quarter_wave(m, x.wh.q16_slots < target ? x.wh : o.wh, target, 16);
+            if (rc != LSTM_OK) return rc;
+        }
+        if (o.set && x.wx.q16_slots > 0 && o.wx.q16_slots > 0 && x.wx.q16_slots != o.wx.q16_slots) {
+            const int target = std::max(x.wx.q16_slots, o.wx.q16_slots);
+            rc = build_quarter_wave(m, x.wx.q16_slots < target ? x.wx : o.wx, target, 24, true);
             if (rc != LSTM_OK) return rc;
         }
     }
@@ -1229,7 +1244,34 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
         // ---- input projection for every timestep (only the modes that need P)
         bool xt_ready = false;
         bool pair_done = false;
-        if (Dn == 2 && !bf16 && mode[0] != 1 && mode[0] != 2 && mode[1] != 1 && mode[1] != 2) {
+        bool proj_q16_used = false;
+        {
+            // Row-compressed W_x in the quarter-wave form, many input rows, few kept weights: gathers and vector
+            // multiply-adds over the kept entries only.  (Bound by LDS bandwidth at 16 bytes per four multiply-adds;
+            // the dense product on the matrix cores, which multiplies the zeros too, wins above about a fifth kept.)
+            bool q16p = !bf16 && !x_is_bf16 && M >= 64;
+            int pslots = 0;
+            for (int d = 0; d < Dn && q16p; ++d) {
+                const PackedMat& p = m->ld[(size_t)l * Dn + d].wx;
+                q16p = mode[d] != 1 && mode[d] != 2 && p.compressed && p.q16_slots > 0 &&
+                       (double)p.nnz <= 0.18 * (double)p.rows * (double)p.cols;
+                pslots = std::max(pslots, p.q16_slots);
+            }
+            if (q16p && proj_q16_supported(M, H, D, pslots)) {
+                ProfSpan span(m, s, 0);
+                ProjQ16Args a{};
+                for (int d = 0; d < Dn; ++d) {
+                    const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                    a.d[d] = ProjQ16Dir{w.wx.q16_val, w.wx.q16_col, w.wx.q16_slots, w.wx.q16_ovf_ptr, w.wx.q16_ovf_ent,
+                                        w.wx.q16_ovf_val, w.bias, P[d]};
+                }
+                a.X = (const float*)X; a.ldx = D; a.M = M; a.K = D; a.H = H;
+                HIP_TRY(m, launch_proj_q16(a, Dn, pslots, s));
+                pair_done = true;
+                proj_q16_used = true;
+            }
+        }
+        if (!pair_done && Dn == 2 && !bf16 && mode[0] != 1 && mode[0] != 2 && mode[1] != 1 && mode[1] != 2) {
             // fp32, both directions dense on the matrix cores: one launch (they read the same X)
             const LayerDir& w0 = m->ld[(size_t)l * Dn], & w1 = m->ld[(size_t)l * Dn + 1];
             auto dense_ok = [&](const LayerDir& w) {
@@ -1382,7 +1424,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
                     a.d[d].reverse = d;
                     std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16%s(s%d,u%d,b%d);", l, d,
-                                  (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
+                                  proj_q16_used ? "q16" : (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
                                   w.wh.q16_ovf_ptr ? "+ovf" : "", q16, upw, bw);
                     m->last_plan += tag;
                 }
@@ -1412,7 +1454,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + m->soff(n) * B, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
                 else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=stepwise-csr-paired;", l, d,
-                              (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr");
+                              proj_q16_used ? "q16" : (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr");
                 m->last_plan += tag;
             }
             for (int step = 0; step < T; ++step) {
@@ -1454,7 +1496,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             float* cTn = cT ? cT + m->soff(n) * B : nullptr;
             static const char* const names[4] = {"stepwise", "persist_b1", "persist_b1", "persist_b1"};
             std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s%s,rec=%s-%s%s;", l, d, (mode[d] == 1 || mode[d] == 2) ? "fused-" : "",
-                          (w.wx.compressed && !(w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ) ? "csr" : "dense",
+                          proj_q16_used ? "q16" : (w.wx.compressed && !(w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ) ? "csr" : "dense",
                           names[mode[d]], w.wh.compressed ? "csr" : "dense",
                           (mode[d] == 1 && (w.wx.slots_trim || w.wh.slots_trim)) ? "+ovf" : "");
             m->last_plan += tag;

@@ -133,6 +133,41 @@ def test_small_batch_persistent_rows_longer_than_the_slots(shape):
     assert "persist_batched-q16+ovf" in desc
 
 
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, T, B, keep -- row-compressed input matrices, at least 64 input rows, few kept weights: the
+    # projection runs over the kept entries only (ragged last tile of four input rows, widths that are no multiple of
+    # four, the widest input the kernel takes, both directions in one launch, a second layer fed by two directions)
+    (1, True, 333, 200, 9, 11, 0.10),
+    (2, False, 2048, 96, 4, 17, 0.08),
+    (1, False, 1601, 300, 5, 13, 0.12),
+    (2, True, 90, 260, 7, 10, 0.15),
+])
+def test_projection_over_kept_entries(shape):
+    L, bidir, D, H, T, Bn, keep = shape
+    case = inputs.make_case(_wl(96, L, bidir, D, H, T, Bn, keep=keep), k=H + Bn, random_state=True)
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "proj=q16" in desc
+
+
+def test_projection_over_kept_entries_rows_longer_than_the_slots():
+    """Input-side rows a few entries longer than all others: the slot count follows the common row length and the
+    waves that own those rows add the remaining entries one at a time."""
+    D, H, T, Bn = 512, 128, 6, 12
+    case = inputs.make_case(_wl(95, 1, True, D, H, T, Bn, keep=0.1), k=3, random_state=True)
+    for (l, d), p in case.weights.items():
+        Mx = p["Mx"]
+        for r in range(4 * H):
+            on = np.flatnonzero(Mx[r])
+            off = np.flatnonzero(Mx[r] == 0)
+            want = 64 + (3 if r in (0, H, 2 * H + 77, 4 * H - 1) else 0)   # 64 entries = four full slots
+            if len(on) > want:
+                Mx[r, on[want:]] = 0
+            elif len(on) < want:
+                Mx[r, off[:want - len(on)]] = 1
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "proj=q16" in desc
+
+
 def test_bf16_small():
     for Bn, keep in ((1, None), (3, 0.3), (9, None)):
         case = inputs.make_case(_wl(92, 2, False, 48, 96, 6, Bn, dtype="bf16", a=0.2, keep=keep), k=Bn, random_state=True)
