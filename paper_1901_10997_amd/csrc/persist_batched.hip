@@ -155,8 +155,6 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
                                           nthreads, a.timeout_flag, a.spin_limit);
         }
         __syncthreads();
-        // Gathers software-pipelined by hand in groups of GS slots: the next group's reads are issued before the
-        // current group's multiply-adds.
         if constexpr (S * UPW >= 84) {
             // near the register limit the offsets stay packed two to a register: the compiler must not unpack all
             // of them ahead of the time loop
@@ -167,54 +165,48 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
         }
         float G = 0.f;
         {
+            // The wave's UPW * S gathers as one software-pipelined sequence: PD reads are in flight ahead of the
+            // multiply-adds that consume them, whatever unit they belong to.
             using VT = typename std::conditional<BW == 2, float2, float4>::type;
-            constexpr int GS = (S % 4 == 0) ? 4 : 2;
-            constexpr int GPU_ = S / GS;           // groups per unit
-            constexpr int NG = UPW * GPU_;
-            auto read_group = [&](int g, VT (&dst)[GS]) {
-                const int u = g / GPU_, i0 = (g % GPU_) * GS;
-#pragma unroll
-                for (int k = 0; k < GS; ++k) {
-                    const int n = i0 + k;
-                    const unsigned off = (wc[u][n >> 1] >> (16 * (n & 1))) & 0xFFFFu;
-                    dst[k] = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + off);
-                }
+            constexpr int NS = UPW * S;
+            constexpr int PDMAX = (S * UPW >= 84) ? 8 : 12;
+            constexpr int PD = NS < PDMAX ? NS : PDMAX;
+            auto read_slot = [&](int n) {
+                const int u = n / S, i = n % S;
+                const unsigned off = (wc[u][i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
+                return *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(hbuf) + off);
             };
-            VT hv[2][GS];
-            float acc[2][BW];   // two chains per column
-            read_group(0, hv[0]);
+            VT ring[PD];
 #pragma unroll
-            for (int g = 0; g < NG; ++g) {
-                const int u = g / GPU_, i0 = (g % GPU_) * GS;
-                if (g + 1 < NG) read_group(g + 1, hv[(g + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);
-                if (i0 == 0) {
+            for (int n = 0; n < PD; ++n) ring[n] = read_slot(n);
+            float acc[2][BW];   // two chains per column
+            float tot[16];      // per-lane partial sums of the wave's (unit, column) pairs, pair p = BW u + b
+#pragma unroll
+            for (int p = PAIRS; p < 16; ++p) tot[p] = 0.f;
+#pragma unroll
+            for (int n = 0; n < NS; ++n) {
+                const int u = n / S, i = n % S;
+                if (i == 0) {
 #pragma unroll
                     for (int b = 0; b < BW; ++b) acc[0][b] = acc[1][b] = 0.f;
                 }
-#pragma unroll
-                for (int k = 0; k < GS; ++k) {
-                    const float w = wv[u][i0 + k];
-                    const VT& x = hv[g & 1][k];
-                    acc[k & 1][0] = fmaf(w, x.x, acc[k & 1][0]);
-                    acc[k & 1][1] = fmaf(w, x.y, acc[k & 1][1]);
-                    if constexpr (BW == 4) {
-                        acc[k & 1][2] = fmaf(w, x.z, acc[k & 1][2]);
-                        acc[k & 1][3] = fmaf(w, x.w, acc[k & 1][3]);
-                    }
+                const float w = wv[u][i];
+                const VT x = ring[n % PD];
+                acc[i & 1][0] = fmaf(w, x.x, acc[i & 1][0]);
+                acc[i & 1][1] = fmaf(w, x.y, acc[i & 1][1]);
+                if constexpr (BW == 4) {
+                    acc[i & 1][2] = fmaf(w, x.z, acc[i & 1][2]);
+                    acc[i & 1][3] = fmaf(w, x.w, acc[i & 1][3]);
                 }
-                if (i0 + GS == S) {
+                if (n + PD < NS) ring[n % PD] = read_slot(n + PD);
+                __builtin_amdgcn_sched_barrier(0);
+                if (i == S - 1) {
 #pragma unroll
-                    for (int b = 0; b < BW; ++b) {
-                        float r = acc[0][b] + acc[1][b];
-                        r = dpp_add<0xB1>(r);
-                        r = dpp_add<0x4E>(r);
-                        r = dpp_add<0x141>(r);
-                        r = dpp_add<0x140>(r);
-                        G = (lp == u * BW + b) ? r : G;
-                    }
+                    for (int b = 0; b < BW; ++b) tot[u * BW + b] = acc[0][b] + acc[1][b];
                 }
             }
+            // all the sums over the 16 lanes of a row at once: lane p of row q ends up with gate q's total of pair p
+            G = row16_transpose_sum(tot, lp);
         }
         if (ovf_n > 0) {   // wave-uniform; false in almost every wave
             // every lane multiplies its own entry (one gather for all of them); the products are then handed to the lanes
