@@ -275,10 +275,24 @@ def main():
     if prof["proj_launches"] > 0 and T * Bn >= 256:
         flops = sum(2.0 * T * Bn * wl.layer_input_dim(l) * (4 * (G if hl else H)) for (l, d) in keys)
         per_fwd_us = prof["proj_us"] / max(args.steps, 1)
-        tf = flops / (per_fwd_us * 1e-6) / 1e12
-        peak = 2500.0 if dtype == B.LSTM_BF16 else 157.3
-        proj = {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
-                "flops_per_forward": flops, "us_per_forward": per_fwd_us, "launches_per_forward": prof["proj_launches"] // max(args.steps, 1)}
+        if "proj=q16" in plan_desc:
+            # projection over the kept entries only: vector multiply-adds, two flops per kept weight and input row;
+            # peak = the fp32 vector rate of the spec sheet (256 compute units x 4 SIMDs x 32 multiply-adds per clock at
+            # 2.4 GHz with packed instructions; this library is compiled without them, which halves what it can reach)
+            kept = sum(float(case.weights[k]["Mx"].sum()) if case.weights[k].get("Mx") is not None
+                       else float(case.weights[k]["Wx"].size) for k in keys)
+            sflops = 2.0 * T * Bn * kept
+            tf = sflops / (per_fwd_us * 1e-6) / 1e12
+            proj = {"bound": "alu", "achieved": tf, "peak": 157.3, "unit": "TFLOP/s", "frac": tf / 157.3,
+                    "peak_without_packed_fp32": 78.6, "frac_without_packed_fp32": tf / 78.6,
+                    "flops_per_forward": sflops, "dense_flops_per_forward": flops,
+                    "dense_equivalent_TFLOPs": flops / (per_fwd_us * 1e-6) / 1e12,
+                    "us_per_forward": per_fwd_us, "launches_per_forward": prof["proj_launches"] // max(args.steps, 1)}
+        else:
+            tf = flops / (per_fwd_us * 1e-6) / 1e12
+            peak = 2500.0 if dtype == B.LSTM_BF16 else 157.3
+            proj = {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
+                    "flops_per_forward": flops, "us_per_forward": per_fwd_us, "launches_per_forward": prof["proj_launches"] // max(args.steps, 1)}
     measured = None
     cold = None
     if not args.no_yardsticks:
@@ -297,7 +311,7 @@ def main():
                     "mfma_f32_TFLOPs": f_c, "mfma_f32_clock_GHz": f_c_ghz,
                     "mfma_f32_random_operands_TFLOPs": f_r, "mfma_f32_random_operands_clock_GHz": f_r_ghz}
         roofline["frac_of_measured_copy"] = achieved / measured["copy_GBps"]
-        if proj:
+        if proj and proj["bound"] == "mfma":
             key = "mfma_bf16" if dtype == B.LSTM_BF16 else "mfma_f32"
             proj["measured_peak"] = measured[key + "_TFLOPs"]
             proj["frac_of_measured"] = proj["achieved"] / proj["measured_peak"]

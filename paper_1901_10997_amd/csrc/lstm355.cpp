@@ -26,6 +26,7 @@ struct lstm355 {
     int* timeout_flag = nullptr;         // device int
     unsigned spin_limit = 1u << 22;
     int device_scope_only = 0;           // 1: no hand-over through an XCD's L2 (environment LSTM355_L2_HANDOVER=0)
+    double sparse_proj_max_density = 0.18;   // projection over the kept entries up to this kept fraction (environment LSTM355_SPARSE_PROJ_MAX_DENSITY)
     int plan = LSTM_PLAN_AUTO;
     int waves_per_group = 0;
     int cooperative = 0;
@@ -493,6 +494,7 @@ static int create_model(int layers, int input_dim, const int* hidden_dims, const
         if (v > 0) m->spin_limit = (unsigned)v;
     }
     if (const char* l2 = std::getenv("LSTM355_L2_HANDOVER")) m->device_scope_only = (std::atoi(l2) == 0) ? 1 : 0;
+    if (const char* sp = std::getenv("LSTM355_SPARSE_PROJ_MAX_DENSITY")) m->sparse_proj_max_density = std::atof(sp);
     hipError_t e = hipGetDevice(&m->device);
     // two cells (directions, or two stacked layers) x two parities; H-LSTM: h slots, then the 4G hidden-layer slots
     m->xchg_slots = (m->G > 0 ? (size_t)m->H + 4 * (size_t)m->G : (size_t)4 * m->H) + 64;   // + XCD ids of a launch's workgroups
@@ -1254,7 +1256,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             for (int d = 0; d < Dn && q16p; ++d) {
                 const PackedMat& p = m->ld[(size_t)l * Dn + d].wx;
                 q16p = mode[d] != 1 && mode[d] != 2 && p.compressed && p.q16_slots > 0 &&
-                       (double)p.nnz <= 0.18 * (double)p.rows * (double)p.cols;
+                       (double)p.nnz <= m->sparse_proj_max_density * (double)p.rows * (double)p.cols;
                 pslots = std::max(pslots, p.q16_slots);
             }
             if (q16p && proj_q16_supported(M, H, D, pslots)) {
