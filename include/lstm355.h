@@ -191,6 +191,10 @@ int lstm_set_plan(lstm_t* m, int plan, int waves_per_group);
  * Environment read at lstm_create: LSTM355_L2_HANDOVER=0 makes every exchange store device-scope (the hand-over of the
  * hidden state through the L2 of one XCD, used where a group of workgroups has been verified to share an XCD, is
  * switched off; results are bit-identical, only slower; for A/B checks).
+ * LSTM355_SPARSE_PROJ_MAX_DENSITY=<fraction>: the input projection W_x . x_t + b of an fp32 model with row-compressed
+ * W_x and at least 64 input rows (T * B) runs over the kept entries only when at most this fraction of W_x is kept
+ * (default 0.18; 0 sends every such product to the dense matrix-core kernel; for A/B checks -- both compute the sum
+ * of the paper's Section 4 over the mask-selected weights, in different summation orders).
  */
 int lstm_set_launch_mode(lstm_t* m, int cooperative);
 /* Process-wide default that lstm_create gives to new handles (including those lstm_latency_sweep creates). */
