@@ -372,13 +372,15 @@ hipError_t launch_persist_batched_q16(PersistBatchedArgs& a, int ndir, int slots
 // direction of a layer in one launch.
 struct PersistBatchedHDir {
     const float* P1;            // [T*B][4G] packed rows (4g + q): b1 + W1x . x_t
-    const float* ell_val_1h;    // W1h [4G][slots_1h][64]
-    const uint16_t* ell_col_1h;
-    const float* ell_val_2;     // W2 [4H][slots_2][64]
-    const uint16_t* ell_col_2;
+    // W1h [G][slots_1h][64] and W2 [H][slots_2][64] in the quarter-wave form; W2's columns carry their gate's offset
+    // q * G into the hidden-layer vector
+    const float* q16_val_1h;
+    const uint16_t* q16_col_1h;
+    const float* q16_val_2;
+    const uint16_t* q16_col_2;
     int slots_1h, slots_2;
-    // per-unit overflow lists of rows longer than 64*slots entries (nullptr: none); entry = (gate << 16) | column;
-    // the entries of the units one wave owns must not exceed 64
+    // per-unit lists of the few entries outside the slots (nullptr: none); entry = (gate << 16) | column (W2: the
+    // column inside its gate's block); at most 6 in any eight consecutive units
     const int32_t* ovf_ptr_1h;
     const uint32_t* ovf_ent_1h;
     const float* ovf_val_1h;
@@ -409,8 +411,9 @@ struct PersistBatchedHArgs {
     int* timeout_flag;
     unsigned spin_limit;
 };
-bool persist_batched_h_plan(int B, int H, int G, int nz, int ndir, int* upw, int* bw, int* ug, int* bg);
-hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int nz, int cooperative, hipStream_t s);
+// `slots` = the largest slot count of the two matrices over the directions (even, <= 16)
+bool persist_batched_h_plan(int B, int H, int G, int slots, int ndir, int* upw, int* bw, int* ug, int* bg);
+hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int slots, int cooperative, hipStream_t s);
 
 // Pruning mask updates (device arrays; scratch supplied by the caller of the launcher).
 size_t prune_state_bytes();

@@ -156,7 +156,13 @@ static hipError_t upload(T** dst, const std::vector<T>& src)
 // lane (column mod 16) of its row in any slot (S places per row and lane instead of S/2 per row and bank), and one that
 // does not fit goes to a free lane of the other parity class in a slot where the other row has nothing at lane
 // (column mod 16), whose filler is pointed at the entry's column.
-static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int max_slots, bool gather16 = false)
+// gate_col_stride > 0 (the H-LSTM's gate-output matrix): row q of a unit reads block q of a vector of four blocks of
+// that many elements; the stored column, and the bank it is placed by, is gate_col_stride * q + column.
+// soft_slots > 0: the consumer loses its best configuration above that many slots (the H-LSTM kernel keeps two matrices
+// in registers); a matrix that would need more is cut to soft_slots anyway as long as no eight consecutive units
+// leave more than 48 entries outside (the kernels take at most 64 per wave).
+static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int max_slots, bool gather16 = false,
+                              int gate_col_stride = 0, int soft_slots = 0)
 {
     if (out.q16_val) (void)hipFree(out.q16_val);
     if (out.q16_col) (void)hipFree(out.q16_col);
@@ -166,7 +172,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int ma
     out.q16_val = nullptr; out.q16_col = nullptr; out.q16_ovf_ptr = nullptr; out.q16_ovf_ent = nullptr; out.q16_ovf_val = nullptr;
     out.q16_slots = 0;
     const int rows = out.rows, cols = out.cols, max_nnz = out.max_row_nnz;
-    if (!out.compressed || max_slots < 2 || rows < 4 || cols > 4095) return LSTM_OK;
+    if (!out.compressed || max_slots < 2 || rows < 4 || cols + 3 * gate_col_stride > 16383) return LSTM_OK;
     {
         const int units = rows / 4;
         // The slot count is set by the longest row, and with random masks a handful of rows are a few entries longer
@@ -190,7 +196,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int ma
                     if (u >= 8) window -= per_unit[(size_t)u - 8];
                     worst = std::max(worst, window);
                 }
-                if (worst <= 6) { S = St; break; }
+                if (worst <= 6 || (soft_slots > 0 && St >= soft_slots && worst <= 48)) { S = St; break; }
             }
         }
         if (S > max_slots) return LSTM_OK;   // rows too long for the kernels that use this form
@@ -215,14 +221,15 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int ma
                 leftover[q].clear();
                 const int64_t row_end = std::min<int64_t>(out.h_row_ptr[rp + 1], out.h_row_ptr[rp] + (int64_t)16 * S);
                 for (int64_t e = out.h_row_ptr[rp]; e < row_end; ++e) {
-                    const int bank = gather16 ? (out.h_col[e] & 15) : (out.h_col[e] & 31), j = bank & 15, hb = bank >> 4;
+                    const int ec = out.h_col[e] + q * gate_col_stride;   // the column as the kernel addresses it
+                    const int bank = gather16 ? (ec & 15) : (ec & 31), j = bank & 15, hb = bank >> 4;
                     if (fill[bank] < (gather16 ? S : S / 2)) {
                         const int sl = gather16 ? fill[bank] : 2 * fill[bank] + ((hb + q) & 1);
                         ++fill[bank];
                         const int pos = sl * 64 + 16 * q + j;
                         used[pos] = 1;
                         uv[pos] = out.h_val[e];
-                        uc[pos] = (uint16_t)out.h_col[e];
+                        uc[pos] = (uint16_t)ec;
                     } else {
                         leftover[q].push_back(e);
                     }
@@ -230,7 +237,8 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int ma
             }
             for (int q = 0; q < 4; ++q) {
                 for (int64_t e : leftover[q]) {
-                    const int bank = gather16 ? (out.h_col[e] & 15) : (out.h_col[e] & 31), j = bank & 15, hb = bank >> 4;
+                    const int ec = out.h_col[e] + q * gate_col_stride;
+                    const int bank = gather16 ? (ec & 15) : (ec & 31), j = bank & 15, hb = bank >> 4;
                     int best = -1, best_owner = -1;
                     // slots where the other row owns `bank` (every slot for 16-byte gathers, where only a lane of the other
                     // parity class shares a pass with the other row's lane j)
@@ -249,7 +257,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int ma
                     }
                     if (best >= 0) {
                         aliased[best_owner] = 1;
-                        uc[best_owner] = (uint16_t)out.h_col[e];
+                        uc[best_owner] = (uint16_t)ec;
                     } else {
                         // no such slot: any free position of the row, from the end; a filler that serves the other row's
                         // entry is given up only when nothing else is left (the row holds at most 16 S entries)
@@ -262,7 +270,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int ma
                     }
                     used[best] = 1;
                     uv[best] = out.h_val[e];
-                    uc[best] = (uint16_t)out.h_col[e];
+                    uc[best] = (uint16_t)ec;
                 }
             }
         }
@@ -293,7 +301,7 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int ma
 
 // Pack one matrix W[4H][cols] (ABI row order q*H + j) with its optional mask into device storage.
 static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t* mask, int H, int cols, bool compressed,
-                       bool bf16, bool keep_dense, int quarter_slots = 0)
+                       bool bf16, bool keep_dense, int quarter_slots = 0, int gate_col_stride = 0, int soft_slots = 0)
 {
     free_mat(out);
     const int rows = 4 * H;
@@ -451,7 +459,7 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
             break;
         }
     }
-    if (quarter_slots > 0) return build_quarter_wave(m, out, 0, quarter_slots, quarter_slots > 16);
+    if (quarter_slots > 0) return build_quarter_wave(m, out, 0, quarter_slots, quarter_slots > 16, gate_col_stride, soft_slots);
     return LSTM_OK;
 }
 
@@ -657,10 +665,10 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
     // hidden layers: 4G rows, packed row 4g+q; kept dense as well for the projection on the matrix cores
     int rc = pack_matrix(m, x.wx, W1x, mask_1x, G, D, compressed, false, true);
     if (rc != LSTM_OK) return rc;
-    rc = pack_matrix(m, x.wh, W1h, mask_1h, G, H, compressed, false, false);
+    rc = pack_matrix(m, x.wh, W1h, mask_1h, G, H, compressed, false, false, 16, 0, 12);
     if (rc != LSTM_OK) return rc;
     // gate outputs: 4H rows, packed row 4j+q, columns = hidden units of the row's own gate
-    rc = pack_matrix(m, x.w2, W2, mask_2, H, G, compressed, false, false);
+    rc = pack_matrix(m, x.w2, W2, mask_2, H, G, compressed, false, false, 16, G, 12);
     if (rc != LSTM_OK) return rc;
     std::vector<float> bp1((size_t)4 * G), bp2((size_t)4 * H);
     for (int rp = 0; rp < 4 * G; ++rp) bp1[rp] = b1[(size_t)(rp & 3) * G + (rp >> 2)];
@@ -670,6 +678,25 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
     HIP_TRY(m, upload(&x.bias, bp1));
     HIP_TRY(m, upload(&x.bias2, bp2));
     x.set = true;
+    // One launch serves both matrices of every direction of a layer and is built for the largest slot count: bring the
+    // others up to it (a matrix trimmed further would pay for those slots and for its own entries outside them).
+    {
+        PackedMat* mats[4] = {&x.wh, &x.w2, nullptr, nullptr};
+        int strides[4] = {0, G, 0, G};
+        if (m->Dn == 2) {
+            LayerDir& o = m->ld[(size_t)layer * 2 + (size_t)(1 - direction)];
+            if (o.set) { mats[2] = &o.wh; mats[3] = &o.w2; }
+        }
+        int target = 0;
+        bool all = true;
+        for (PackedMat* p : mats)
+            if (p) { all = all && p->q16_slots > 0; target = std::max(target, p->q16_slots); }
+        for (int i = 0; i < 4 && all; ++i)
+            if (mats[i] && mats[i]->q16_slots < target) {
+                rc = build_quarter_wave(m, *mats[i], target, 16, false, strides[i]);
+                if (rc != LSTM_OK) return rc;
+            }
+    }
     return LSTM_OK;
 }
 
@@ -902,45 +929,20 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 HIP_TRY(m, launch_proj_dense(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s));
             }
         }
-        // small batch, W1h and W2 of every direction row-compressed and small enough for registers: one launch per
-        // layer with the time loop on the device
+        // small batch, W1h and W2 of every direction row-compressed with rows of at most 256 kept entries (the
+        // quarter-wave form): one launch per layer with the time loop on the device
         {
-            int nz = 1, upw = 0, bw = 0, ug = 0, bg = 0;
+            int nz = 0, upw = 0, bw = 0, ug = 0, bg = 0;
             bool pb_ok = B >= 2 && m->plan != LSTM_PLAN_STEPWISE;
-            bool trimmed = false;
-            if (pb_ok) {
-                // first with the slices cut to the common row length (a wave takes at most 64 overflow entries over
-                // the units it owns), then with the full slices
-                auto slots_of = [&](const PackedMat& p, bool trim) { return trim && p.slots_trim > 0 ? p.slots_trim : p.slots; };
-                auto wave_fits = [&](const PackedMat& p, int upw_) {
-                    if (p.slots_trim == 0) return true;
-                    const int units = (int)p.h_ovf_ptr.size() - 1;
-                    for (int u = 0; u < units; u += upw_)
-                        if (p.h_ovf_ptr[(size_t)std::min(u + upw_, units)] - p.h_ovf_ptr[(size_t)u] > 64) return false;
-                    return true;
-                };
-                bool found = false;
-                for (int pass = 0; pass < 2 && !found; ++pass) {
-                    const bool trim = pass == 0;
-                    bool ok = true, any_trim = false;
-                    nz = 1;
-                    for (int d = 0; d < Dn && ok; ++d) {
-                        const LayerDir& w = m->ld[(size_t)l * Dn + d];
-                        ok = w.wh.compressed && w.w2.compressed && (w.wh.ell_val || (trim && w.wh.slots_trim)) &&
-                             (w.w2.ell_val || (trim && w.w2.slots_trim));
-                        nz = std::max(nz, std::max(slots_of(w.wh, trim), slots_of(w.w2, trim)));
-                        any_trim = any_trim || (trim && (w.wh.slots_trim || w.w2.slots_trim));
-                    }
-                    if (trim && !any_trim) continue;
-                    ok = ok && persist_batched_h_plan(B, H, G, nz, Dn, &upw, &bw, &ug, &bg);
-                    for (int d = 0; d < Dn && ok && trim; ++d) {
-                        const LayerDir& w = m->ld[(size_t)l * Dn + d];
-                        ok = wave_fits(w.wh, upw) && wave_fits(w.w2, upw);
-                    }
-                    if (ok) { found = true; trimmed = trim; }
-                }
-                pb_ok = found;
+            bool any_extra = false;
+            for (int d = 0; d < Dn && pb_ok; ++d) {
+                const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                pb_ok = w.wh.compressed && w.w2.compressed && w.wh.q16_slots > 0 && w.w2.q16_slots > 0;
+                nz = std::max(nz, std::max(w.wh.q16_slots, w.w2.q16_slots));
+                any_extra = any_extra || w.wh.q16_ovf_ptr || w.w2.q16_ovf_ptr;
             }
+            pb_ok = pb_ok && persist_batched_h_plan(B, H, G, nz, Dn, &upw, &bw, &ug, &bg);
+            const bool trimmed = any_extra;
             if (m->plan == LSTM_PLAN_PERSISTENT && B >= 2 && !pb_ok)
                 return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
             if (pb_ok) {
@@ -963,18 +965,10 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                     const size_t n = (size_t)l * Dn + d;
                     PersistBatchedHDir& q = a.d[d];
                     q.P1 = P[d];
-                    if (trimmed && w.wh.slots_trim > 0) {
-                        q.ell_val_1h = w.wh.ell_val_trim; q.ell_col_1h = w.wh.ell_col_trim; q.slots_1h = w.wh.slots_trim;
-                        q.ovf_ptr_1h = w.wh.ovf_ptr; q.ovf_ent_1h = w.wh.ovf_ent; q.ovf_val_1h = w.wh.ovf_val;
-                    } else {
-                        q.ell_val_1h = w.wh.ell_val; q.ell_col_1h = w.wh.ell_col; q.slots_1h = w.wh.slots;
-                    }
-                    if (trimmed && w.w2.slots_trim > 0) {
-                        q.ell_val_2 = w.w2.ell_val_trim; q.ell_col_2 = w.w2.ell_col_trim; q.slots_2 = w.w2.slots_trim;
-                        q.ovf_ptr_2 = w.w2.ovf_ptr; q.ovf_ent_2 = w.w2.ovf_ent; q.ovf_val_2 = w.w2.ovf_val;
-                    } else {
-                        q.ell_val_2 = w.w2.ell_val; q.ell_col_2 = w.w2.ell_col; q.slots_2 = w.w2.slots;
-                    }
+                    q.q16_val_1h = w.wh.q16_val; q.q16_col_1h = w.wh.q16_col; q.slots_1h = w.wh.q16_slots;
+                    q.ovf_ptr_1h = w.wh.q16_ovf_ptr; q.ovf_ent_1h = w.wh.q16_ovf_ent; q.ovf_val_1h = w.wh.q16_ovf_val;
+                    q.q16_val_2 = w.w2.q16_val; q.q16_col_2 = w.w2.q16_col; q.slots_2 = w.w2.q16_slots;
+                    q.ovf_ptr_2 = w.w2.q16_ovf_ptr; q.ovf_ent_2 = w.w2.q16_ovf_ent; q.ovf_val_2 = w.w2.q16_ovf_val;
                     q.bias2 = w.bias2;
                     q.h0 = h0 ? h0 + m->soff(n) * B : nullptr;
                     q.c0 = c0 ? c0 + m->soff(n) * B : nullptr;
@@ -982,8 +976,8 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                     q.hT = hT ? hT + m->soff(n) * B : nullptr;
                     q.cT = cT ? cT + m->soff(n) * B : nullptr;
                     q.reverse = d;
-                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-hlstm-csr%s(u%d,b%d);", l, d,
-                                  proj_dense[d] ? "dense" : "csr", trimmed ? "+ovf" : "", upw, bw);
+                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-hlstm-csr%s(s%d,u%d,b%d);", l, d,
+                                  proj_dense[d] ? "dense" : "csr", trimmed ? "+ovf" : "", nz, upw, bw);
                     m->last_plan += tag;
                 }
                 a.T = T; a.B = B; a.H = H; a.G = G;

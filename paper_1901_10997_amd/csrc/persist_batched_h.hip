@@ -8,11 +8,12 @@
 //
 // The grid is a 2-D partition per direction: unit groups x batch groups.  A workgroup owns UPB units (hidden-layer
 // units g in the first half of a step, output units j in the second) and BW batch columns for the whole sequence;
-// each wave keeps the kept weights of its UPW units of W1h and of W2 in registers (64-lane slices of value and
-// 16-bit LDS offset) and the cell state of its (unit, column) pairs in lanes 0..15.  A product gathers from an LDS
-// copy of the vector ([k][BW]: the BW batch values of one k adjacent, one 8- or 16-byte read per kept weight), the
-// 4 x BW partial sums of a unit are reduced with the lane-swap reduction so that lane 16*gate + pair holds a gate
-// total (pair = local unit * BW + column), and one exp2 and one reciprocal evaluate all gates of all pairs.
+// each wave keeps the kept weights of its UPW units of W1h and of W2 in registers in the quarter-wave form (slot s of a
+// unit is one 64-lane gather that serves all four gate rows, gate q on lanes 16q..16q+15; value and 16-bit LDS offset)
+// and the cell state of its (unit, column) pairs in lanes 0..15.  A product gathers from an LDS copy of the vector
+// ([k][BW]: the BW batch values of one k adjacent, one 8- or 16-byte read per kept weight), a lane accumulates BW sums
+// per unit, all (unit, column) sums of a wave are reduced together inside the 16-lane rows so that lane 16*gate + pair
+// holds a gate total (pair = local unit * BW + column), and one exp2 and one reciprocal evaluate all gates of all pairs.
 //
 // A step needs two vectors the whole batch group has produced.  They travel differently:
 //   h_t   (H values per column) through tagged 8-byte slots (value and step tag in one store; consumers poll until
@@ -36,19 +37,18 @@ namespace l355 {
 
 namespace {
 constexpr int kWaves = 8;
-constexpr int kWeightRegs = 150;   // registers per lane for the weights of both matrices (12*NZ per unit)
+constexpr int kWeightRegs = 150;   // registers per lane for the weights of both matrices (3 per unit and slot)
 constexpr int kMaxLds = 160 * 1024;
 // hbuf (padded to whole 16-byte units) + ubuf
 size_t lds_bytes(int H, int G, int bw) { return ((((size_t)bw * H + 3) & ~(size_t)3) + 4 * (size_t)G * bw) * sizeof(float); }
 }  // namespace
 
-template <int NZ, int UPW, int BW>
+template <int S, int UPW, int BW>   // S: slots per unit of the quarter-wave form (16 kept entries of each gate per slot)
 __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatchedHArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];  // hbuf[H][BW] | ubuf[4G][BW]
-    constexpr int NZP = (4 * NZ + 1) / 2;   // packed 16-bit offsets of a unit's 4*NZ slices, two to a register
     constexpr int PAIRS = UPW * BW;
-    static_assert(PAIRS <= 16, "pairs must fit one 16-lane row");
+    static_assert(PAIRS <= 16 && S % 2 == 0, "pairs must fit one 16-lane row; slots come in pairs");
     const int H = a.H, G = a.G, B = a.B;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -80,44 +80,38 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
     float* xu = a.xchg_u + grp * a.u_stride;              // [4G][BW]
     unsigned* flags = a.flags + grp * 64;                 // one per unit group
 
-    // kept weights of this wave's units; the column is kept as the 16-bit LDS byte offset of its BW values
-    float w1[UPW][4][NZ], w2[UPW][4][NZ];
-    unsigned o1[UPW][NZP], o2[UPW][NZP];
+    // kept weights of this wave's units in the quarter-wave form (slot s of a unit is one 64-lane gather that serves
+    // all four gate rows, gate q on lanes 16q..16q+15); the column is kept as the 16-bit LDS byte offset of its BW
+    // values (W2's columns are stored with their gate's offset q * G into the hidden-layer vector)
+    float w1[UPW][S], w2[UPW][S];
+    unsigned o1[UPW][S / 2], o2[UPW][S / 2];
     {
-        // Every load is issued whatever the shape (units past the width and slices past a matrix's slot count read a
-        // valid element and are zeroed afterwards): with a branch per element the loads went out one at a time, each
-        // waiting for the one before it.
+        // Every load is issued whatever the shape (units past the width and slots past a matrix's slot count read a
+        // valid element and are zeroed afterwards): with a branch per element the loads went out one at a time.
         const int s1 = D.slots_1h, s2 = D.slots_2;
-        float t1[4 * NZ], t2[4 * NZ];
-        unsigned k1[4 * NZ], k2[4 * NZ];
+        float t1[S], t2[S];
+        unsigned k1[S], k2[S];
 #pragma unroll
         for (int u = 0; u < UPW; ++u) {
             const int g1 = (u0 + u < G) ? (u0 + u) : (G - 1), j2 = (u0 + u < H) ? (u0 + u) : (H - 1);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                for (int i = 0; i < NZ; ++i) {
-                    const size_t i1 = ((size_t)(4 * g1 + q) * s1 + (i < s1 ? i : s1 - 1)) * 64 + lane;
-                    const size_t i2 = ((size_t)(4 * j2 + q) * s2 + (i < s2 ? i : s2 - 1)) * 64 + lane;
-                    t1[q * NZ + i] = D.ell_val_1h[i1];
-                    k1[q * NZ + i] = D.ell_col_1h[i1];
-                    t2[q * NZ + i] = D.ell_val_2[i2];
-                    k2[q * NZ + i] = D.ell_col_2[i2];
-                }
+            for (int i = 0; i < S; ++i) {
+                const size_t i1 = ((size_t)g1 * s1 + (i < s1 ? i : s1 - 1)) * 64 + lane;
+                const size_t i2 = ((size_t)j2 * s2 + (i < s2 ? i : s2 - 1)) * 64 + lane;
+                t1[i] = D.q16_val_1h[i1];
+                k1[i] = D.q16_col_1h[i1];
+                t2[i] = D.q16_val_2[i2];
+                k2[i] = D.q16_col_2[i2];
             }
 #pragma unroll
-            for (int i = 0; i < NZP; ++i) o1[u][i] = o2[u][i] = 0u;
+            for (int i = 0; i < S / 2; ++i) o1[u][i] = o2[u][i] = 0u;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-#pragma unroll
-                for (int i = 0; i < NZ; ++i) {
-                    const bool l1 = (u0 + u < G) && i < s1, l2 = (u0 + u < H) && i < s2;
-                    const int n = q * NZ + i;
-                    w1[u][q][i] = l1 ? t1[n] : 0.f;
-                    w2[u][q][i] = l2 ? t2[n] : 0.f;
-                    o1[u][n >> 1] |= ((l1 ? k1[n] : 0u) * (BW * 4u)) << (16 * (n & 1));                       // h[k][0]
-                    o2[u][n >> 1] |= (((unsigned)q * G + (l2 ? k2[n] : 0u)) * (BW * 4u)) << (16 * (n & 1));   // u[q*G + k][0]
-                }
+            for (int i = 0; i < S; ++i) {
+                const bool l1 = (u0 + u < G) && i < s1, l2 = (u0 + u < H) && i < s2;
+                w1[u][i] = l1 ? t1[i] : 0.f;
+                w2[u][i] = l2 ? t2[i] : 0.f;
+                o1[u][i >> 1] |= ((l1 ? k1[i] : 0u) * (BW * 4u)) << (16 * (i & 1));   // h[k][0]
+                o2[u][i >> 1] |= ((l2 ? k2[i] : 0u) * (BW * 4u)) << (16 * (i & 1));   // u[q*G + k][0]
             }
         }
     }
@@ -133,103 +127,91 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
     if (lane < 16 && ok2 && D.c0) c = D.c0[(size_t)(b0 + pb) * H + unit_l];
     const int poll_i = lane < a.ug ? lane : a.ug - 1;
 
-    // Overflow entries of this wave's units (rows longer than 64*slots; rare): the lists of consecutive units are
-    // adjacent, lane e holds entry e of the wave's run, packed as LDS byte offset | gate << 16 | local unit << 18
-    // (local unit 15: no entry).  The per-unit counts are wave-uniform.
-    unsigned e1 = 15u << 18, e2 = 15u << 18;
-    float ev1 = 0.f, ev2 = 0.f;
-    int n1[UPW], n2[UPW];
-    auto load_overflow = [&](const int32_t* ptr, const uint32_t* ent, const float* val, int units, bool gate_major,
-                             unsigned& eo, float& evv, int (&cnt)[UPW]) {
-#pragma unroll
-        for (int u = 0; u < UPW; ++u) cnt[u] = 0;
-        if (ptr == nullptr || u0 >= units) return;
-        const int first = ptr[u0];
-        int pos = first;
-#pragma unroll
-        for (int u = 0; u < UPW; ++u) {
-            const int nxt = (u0 + u < units) ? ptr[u0 + u + 1] : pos;
-            cnt[u] = __builtin_amdgcn_readfirstlane(nxt - pos);
+    // The few entries of rows longer than 16 S (at most 6 per wave; most waves have none): lane e holds entry e of the
+    // wave's run of per-unit lists -- value, LDS byte offset of its column, and the lane that collects its gate's total
+    // for batch column 0 (16 * gate + local unit * BW).
+    struct Extra { float v; unsigned off; int lane0; int n; };
+    auto load_extra = [&](const int32_t* ptr, const uint32_t* ent, const float* val, int units, int gate_stride) {
+        Extra x{0.f, 0u, 0, 0};
+        if (ptr != nullptr && u0 < units) {
+            const int first = ptr[u0];
             const int idx = first + lane;
-            if (idx >= pos && idx < nxt) {
-                const unsigned e = ent[idx];
-                const unsigned g = e >> 16, col = e & 0xFFFFu;
-                eo = ((gate_major ? g * (unsigned)G + col : col) * (BW * 4u)) | (g << 16) | ((unsigned)u << 18);
-                evv = val[idx];
+            int pos = first;
+#pragma unroll
+            for (int u = 0; u < UPW; ++u) {
+                const int nxt = (u0 + u < units) ? ptr[u0 + u + 1] : pos;
+                if (idx >= pos && idx < nxt) {
+                    const unsigned e = ent[idx];
+                    const unsigned g = e >> 16;
+                    x.off = (g * (unsigned)gate_stride + (e & 0xFFFFu)) * (BW * 4u);
+                    x.lane0 = 16 * (int)g + u * BW;
+                    x.v = val[idx];
+                }
+                pos = nxt;
             }
-            pos = nxt;
+            x.n = pos - first;
+            x.n = x.n < 64 ? x.n : 64;
         }
+        x.n = __builtin_amdgcn_readfirstlane(x.n);
+        return x;
     };
-    load_overflow(D.ovf_ptr_1h, D.ovf_ent_1h, D.ovf_val_1h, G, false, e1, ev1, n1);
-    load_overflow(D.ovf_ptr_2, D.ovf_ent_2, D.ovf_val_2, H, true, e2, ev2, n2);
+    const Extra x1 = load_extra(D.ovf_ptr_1h, D.ovf_ent_1h, D.ovf_val_1h, G, 0);
+    const Extra x2 = load_extra(D.ovf_ptr_2, D.ovf_ent_2, D.ovf_val_2, H, G);
 
-    // gathers of one stage: acc over the NZ slices of every unit, reduced into lane 16*gate + pair
-    // The gathers are software-pipelined by hand in groups of GS (gates q0..q0+GS-1 of slice i of one unit): the next
-    // group's reads are issued before the current group's multiply-adds, so that LDS latency overlaps arithmetic (left
-    // to itself the compiler waits for every read on its own).  Two groups of read results are live at a time; the
-    // configurations with the most weight registers take the smaller group.
+    // One product: the wave's UPW * S gathers as one software-pipelined sequence (PD reads in flight ahead of the
+    // multiply-adds that consume them), the UPW * BW sums reduced together by the transposing 16-lane reduction, so that
+    // lane 16*gate + pair holds the gate's total of the pair; then the rare entries outside the slots.
     using VT = typename std::conditional<BW == 2, float2, float4>::type;
-    constexpr int GS = (12 * NZ * UPW > 128 && BW == 4) ? 2 : 4;
-    auto products = [&](const float (&wv)[UPW][4][NZ], const unsigned (&wo)[UPW][NZP], const int (&cnt)[UPW], unsigned eo,
-                        float evv, const float* vec) -> float {
-        constexpr int GPS = 4 / GS;            // groups per slice
-        constexpr int NG = UPW * NZ * GPS;
-        auto read_group = [&](int g, VT (&dst)[GS]) {
-            const int u = g / (NZ * GPS), i = (g / GPS) % NZ, q0 = (g % GPS) * GS;
-#pragma unroll
-            for (int k = 0; k < GS; ++k) {
-                const int n = (q0 + k) * NZ + i;
-                const unsigned off = (wo[u][n >> 1] >> (16 * (n & 1))) & 0xFFFFu;
-                dst[k] = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(vec) + off);
-            }
+    auto products = [&](const float (&wv)[UPW][S], const unsigned (&wo)[UPW][S / 2], const Extra& xt, const float* vec) -> float {
+        constexpr int NS = UPW * S;
+        constexpr int PDMAX = (3 * S * UPW > 128) ? 8 : 12;
+        constexpr int PD = NS < PDMAX ? NS : PDMAX;
+        auto read_slot = [&](int n) {
+            const int u = n / S, i = n % S;
+            const unsigned off = (wo[u][i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
+            return *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(vec) + off);
         };
-        float Gv = 0.f;
-        VT hv[2][GS];
-        float acc[4][BW];
-        read_group(0, hv[0]);
+        VT ring[PD];
 #pragma unroll
-        for (int g = 0; g < NG; ++g) {
-            const int u = g / (NZ * GPS), i = (g / GPS) % NZ, q0 = (g % GPS) * GS;
-            if (g + 1 < NG) read_group(g + 1, hv[(g + 1) & 1]);
+        for (int n = 0; n < PD; ++n) ring[n] = read_slot(n);
+        float acc[2][BW];
+        float tot[16];
+#pragma unroll
+        for (int p = PAIRS; p < 16; ++p) tot[p] = 0.f;
+#pragma unroll
+        for (int n = 0; n < NS; ++n) {
+            const int u = n / S, i = n % S;
+            if (i == 0) {
+#pragma unroll
+                for (int b = 0; b < BW; ++b) acc[0][b] = acc[1][b] = 0.f;
+            }
+            const float w = wv[u][i];
+            const VT x = ring[n % PD];
+            acc[i & 1][0] = fmaf(w, x.x, acc[i & 1][0]);
+            acc[i & 1][1] = fmaf(w, x.y, acc[i & 1][1]);
+            if constexpr (BW == 4) {
+                acc[i & 1][2] = fmaf(w, x.z, acc[i & 1][2]);
+                acc[i & 1][3] = fmaf(w, x.w, acc[i & 1][3]);
+            }
+            if (n + PD < NS) ring[n % PD] = read_slot(n + PD);
             __builtin_amdgcn_sched_barrier(0);
-            if (i == 0 && q0 == 0) {
+            if (i == S - 1) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
-#pragma unroll
-                    for (int b = 0; b < BW; ++b) acc[q][b] = 0.f;
+                for (int b = 0; b < BW; ++b) tot[u * BW + b] = acc[0][b] + acc[1][b];
             }
-#pragma unroll
-            for (int k = 0; k < GS; ++k) {
-                const int q = q0 + k;
-                const float w = wv[u][q][i];
-                const VT& x = hv[g & 1][k];
-                acc[q][0] = fmaf(w, x.x, acc[q][0]);
-                acc[q][1] = fmaf(w, x.y, acc[q][1]);
-                if constexpr (BW == 4) {
-                    acc[q][2] = fmaf(w, x.z, acc[q][2]);
-                    acc[q][3] = fmaf(w, x.w, acc[q][3]);
-                }
-            }
-            if (i == NZ - 1 && q0 + GS == 4) {
-                if (cnt[u] > 0) {
-                    // this unit's overflow entries, one per lane, into the partial sum of the gate each belongs to
-                    const float v = ((eo >> 18) & 15u) == (unsigned)u ? evv : 0.f;
-                    const unsigned gq = (eo >> 16) & 3u;
-                    const VT t = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(vec) + (eo & 0xFFFFu));
-                    float xv[BW];
-                    xv[0] = t.x; xv[1] = t.y;
-                    if constexpr (BW == 4) { xv[2] = t.z; xv[3] = t.w; }
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float vq = (gq == (unsigned)q) ? v : 0.f;
-#pragma unroll
-                        for (int b = 0; b < BW; ++b) acc[q][b] = fmaf(vq, xv[b], acc[q][b]);
-                    }
-                }
+        }
+        float Gv = row16_transpose_sum(tot, lp);
+        if (xt.n > 0) {   // wave-uniform; false in almost every wave
+            const VT x = *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(vec) + xt.off);
+            float pr[BW];
+            pr[0] = xt.v * x.x; pr[1] = xt.v * x.y;
+            if constexpr (BW == 4) { pr[2] = xt.v * x.z; pr[3] = xt.v * x.w; }
+            for (int e = 0; e < xt.n; ++e) {
+                const int tgt = __builtin_amdgcn_readlane(xt.lane0, e);
 #pragma unroll
                 for (int b = 0; b < BW; ++b) {
-                    const float r = wave_sum4_rows(acc[0][b], acc[1][b], acc[2][b], acc[3][b]);
-                    Gv = (lp == u * BW + b) ? r : Gv;
+                    const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(pr[b]), e));
+                    Gv += (lane == tgt + b) ? v : 0.f;
                 }
             }
         }
@@ -238,7 +220,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
 
     // The direction is chosen by the block index, so `D` is addressed through memory: taken inside the time loop its
     // fields cost a load and a wait per step.  Where registers allow (kCopy) they are copied once.
-    constexpr bool kCopy = NZ * UPW < 12;
+    constexpr bool kCopy = S * UPW < 40;
     const float* P1_c = nullptr;
     float *y_c = nullptr, *hT_c = nullptr, *cT_c = nullptr;
     size_t y_ld_c = 0;
@@ -259,11 +241,10 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
 #pragma unroll
         for (int u = 0; u < UPW; ++u)
 #pragma unroll
-            for (int i = 0; i < NZP; ++i) {
+            for (int i = 0; i < S / 2; ++i) {
                 asm volatile("" : "+v"(o1[u][i]));
                 asm volatile("" : "+v"(o2[u][i]));
             }
-        asm volatile("" : "+v"(e1), "+v"(e2));   // likewise the per-gate selections of the overflow entry
         float pin = 0.f;
         if (ok1) pin = (kCopy ? P1_c : D.P1)[((size_t)t * B + b0 + pb) * (4 * (size_t)G) + 4 * unit_l + row];
         // ---- stage 1: hidden layers from h_{t-1}
@@ -277,7 +258,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
         }
         __syncthreads();
         {
-            const float pre = products(w1, o1, n1, e1, ev1, hbuf) + pin;
+            const float pre = products(w1, o1, x1, hbuf) + pin;
             // dead columns of a ragged batch group are written as zeros: the consumers copy whole rows
             const float uval = (pb < bw && pre > 0.f) ? pre : 0.f;
             if (in_pairs && unit_l < G)
@@ -323,7 +304,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
         }
         __syncthreads();
         {
-            const float pre = products(w2, o2, n2, e2, ev2, ubuf) + bias2;
+            const float pre = products(w2, o2, x2, ubuf) + bias2;
             const bool cand = row == 3;
             const float sc = cand ? 2.8853900817779268f : -1.4426950408889634f;
             const float rr = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(sc * pre));
@@ -352,16 +333,16 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
 // ------------------------------------------------------------------------------------------------ planning
 // Choose (UPW, BW): the most workgroups that still fit one per compute unit, within the register budget, with
 // PAIRS <= 16, 16-bit LDS offsets, and at most 64 unit groups (one flag per polling lane).
-bool persist_batched_h_plan(int B, int H, int G, int nz, int ndir, int* upw_out, int* bw_out, int* ug_out, int* bg_out)
+bool persist_batched_h_plan(int B, int H, int G, int slots, int ndir, int* upw_out, int* bw_out, int* ug_out, int* bg_out)
 {
-    if (B < 2 || nz < 1 || nz > 4 || H < 1 || G < 1) return false;
+    if (B < 2 || slots < 2 || slots > 16 || (slots & 1) || H < 1 || G < 1) return false;
     const int units = std::max(H, G);
     int best = -1;
     for (int bw = 2; bw <= 4; bw *= 2) {
         if ((size_t)H * bw * 4 > 65536 || (size_t)4 * G * bw * 4 > 65536) continue;
         if (lds_bytes(H, G, bw) > (size_t)kMaxLds) continue;
         for (int upw = 2; upw <= 4; ++upw) {
-            if (upw * bw > 16 || 12 * nz * upw > kWeightRegs) continue;
+            if (upw * bw > 16 || 3 * slots * upw > kWeightRegs) continue;   // 1.5 registers per (unit, slot) and matrix
             const int ug = (units + kWaves * upw - 1) / (kWaves * upw), bg = (B + bw - 1) / bw;
             if (ug > 64) continue;
             const int blocks = ug * bg * ndir;
@@ -379,11 +360,11 @@ bool persist_batched_h_plan(int B, int H, int G, int nz, int ndir, int* upw_out,
 size_t persist_batched_h_hstride(int H, int bw) { return (((size_t)H * bw * 8 + 255) / 256) * 256 / 8; }
 size_t persist_batched_h_ustride(int G, int bw) { return (((size_t)4 * G * bw * 4 + 255) / 256) * 256 / 4; }
 
-template <int NZ, int UPW, int BW>
+template <int S, int UPW, int BW>
 static hipError_t launch_cfg(PersistBatchedHArgs& a, int blocks, bool cooperative, hipStream_t s)
 {
     const size_t lds = lds_bytes(a.H, a.G, BW);
-    auto kern = persist_batched_hlstm_kernel<NZ, UPW, BW>;
+    auto kern = persist_batched_hlstm_kernel<S, UPW, BW>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds);
@@ -395,22 +376,20 @@ static hipError_t launch_cfg(PersistBatchedHArgs& a, int blocks, bool cooperativ
     return hipLaunchKernel((const void*)kern, dim3(blocks), dim3(64 * kWaves), args, lds, s);
 }
 
-template <int NZ>
-static hipError_t launch_nz(PersistBatchedHArgs& a, int upw, int bw, int blocks, bool coop, hipStream_t s)
+template <int S>
+static hipError_t launch_s(PersistBatchedHArgs& a, int upw, int bw, int blocks, bool coop, hipStream_t s)
 {
-#define CFG(U, W) if (upw == U && bw == W) return launch_cfg<NZ, U, W>(a, blocks, coop, s);
-    CFG(2, 2) CFG(2, 4)
-    if constexpr (12 * NZ * 3 <= kWeightRegs) { CFG(3, 2) CFG(3, 4) }
-    if constexpr (12 * NZ * 4 <= kWeightRegs) { CFG(4, 2) CFG(4, 4) }
+#define CFG(U, W) if constexpr (3 * S * U <= kWeightRegs) { if (upw == U && bw == W) return launch_cfg<S, U, W>(a, blocks, coop, s); }
+    CFG(2, 2) CFG(2, 4) CFG(3, 2) CFG(3, 4) CFG(4, 2) CFG(4, 4)
 #undef CFG
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int nz, int cooperative, hipStream_t s)
+hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int slots, int cooperative, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
     int upw, bw, ug, bg;
-    if (!persist_batched_h_plan(a.B, a.H, a.G, nz, ndir, &upw, &bw, &ug, &bg)) return hipErrorInvalidValue;
+    if (!persist_batched_h_plan(a.B, a.H, a.G, slots, ndir, &upw, &bw, &ug, &bg)) return hipErrorInvalidValue;
     a.ug = ug;
     a.bg = bg;
     a.h_stride = persist_batched_h_hstride(a.H, bw);
@@ -420,11 +399,15 @@ hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int nz, in
     a.ndir = ndir;
     a.xcd_local = per_xcd * ug <= device_num_cus() / 8;
     const int blocks = a.xcd_local ? 8 * per_xcd * ug : ug * bg * ndir;
-    switch (nz) {
-        case 1: return launch_nz<1>(a, upw, bw, blocks, cooperative != 0, s);
-        case 2: return launch_nz<2>(a, upw, bw, blocks, cooperative != 0, s);
-        case 3: return launch_nz<3>(a, upw, bw, blocks, cooperative != 0, s);
-        case 4: return launch_nz<4>(a, upw, bw, blocks, cooperative != 0, s);
+    switch (slots) {
+        case 2: return launch_s<2>(a, upw, bw, blocks, cooperative != 0, s);
+        case 4: return launch_s<4>(a, upw, bw, blocks, cooperative != 0, s);
+        case 6: return launch_s<6>(a, upw, bw, blocks, cooperative != 0, s);
+        case 8: return launch_s<8>(a, upw, bw, blocks, cooperative != 0, s);
+        case 10: return launch_s<10>(a, upw, bw, blocks, cooperative != 0, s);
+        case 12: return launch_s<12>(a, upw, bw, blocks, cooperative != 0, s);
+        case 14: return launch_s<14>(a, upw, bw, blocks, cooperative != 0, s);
+        case 16: return launch_s<16>(a, upw, bw, blocks, cooperative != 0, s);
     }
     return hipErrorInvalidValue;
 }

@@ -163,15 +163,34 @@ def test_hlstm_persistent_small_batch(shape):
 
 
 @pytest.mark.parametrize("shape", [
-    # L, bidir, D, H, G, T, B, keep -- a few rows a little longer than a multiple of 64 kept entries: the slices hold
-    # the common row length, the remainder comes from per-unit overflow lists
+    # L, bidir, D, H, G, T, B, keep
     (1, True, 100, 400, 400, 7, 4, 0.12),
     (2, False, 120, 410, 380, 6, 7, 0.27),
     (1, False, 64, 600, 520, 5, 16, 0.18),
 ])
-def test_hlstm_persistent_small_batch_overflow_rows(shape):
+def test_hlstm_persistent_small_batch_rows_longer_than_the_slots(shape):
+    """A few rows of the recurrent hidden-layer matrix and of the gate-output matrix a few entries longer than all
+    others: the slot count follows the common row length and the waves that own those rows add the rest one entry
+    at a time."""
     L, bidir, D, H, G, T, Bn, keep = shape
     case = inputs.make_case(_hw(87, L, bidir, D, H, G, T, Bn, keep=keep), k=L, random_state=True)
+
+    def level(M, rows_long, extra):
+        n_rows, n_cols = M.shape
+        units = n_rows // 4
+        target = 32 * max(1, int(round(keep * n_cols / 32.0)))
+        for r in range(n_rows):
+            on = np.flatnonzero(M[r])
+            off = np.flatnonzero(M[r] == 0)
+            want = target + (extra if ((r % units) * 4 + r // units) in rows_long else 0)   # ABI row q*units + j is packed row 4j + q
+            if len(on) > want:
+                M[r, on[want:]] = 0
+            elif len(on) < want:
+                M[r, off[:want - len(on)]] = 1
+
+    for (l, d), p in case.weights.items():
+        level(p["M1h"], (1, 2, 4 * G - 3), 2)      # two long rows in unit 0, one in the last unit
+        level(p["M2"], (6, 4 * (H // 2) + 3), 3)
     desc, _ = check_case(case, CSR, PERSIST)
     assert "persist_batched-hlstm-csr+ovf" in desc
 

@@ -613,6 +613,25 @@ def test_l2_handover_off_gives_the_same_bits(name, monkeypatch):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
+def test_projection_density_switch(monkeypatch):
+    """LSTM355_SPARSE_PROJ_MAX_DENSITY at lstm_create moves the boundary between the projection over the kept entries and
+    the dense matrix-core product; both meet the oracle (they differ from each other only in summation order)."""
+    case = inputs.make_case(_wl(94, 1, True, 320, 256, 8, 40, keep=0.12), k=2, random_state=True)
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "proj=q16" in desc
+    monkeypatch.setenv("LSTM355_SPARSE_PROJ_MAX_DENSITY", "0")
+    desc, _ = check_case(case, CSR, PAUTO)
+    monkeypatch.delenv("LSTM355_SPARSE_PROJ_MAX_DENSITY")
+    assert "proj=dense" in desc
+    case = inputs.make_case(_wl(94, 1, False, 320, 256, 8, 40, keep=0.3), k=3, random_state=True)
+    desc, _ = check_case(case, CSR, PAUTO)
+    assert "proj=dense" in desc      # above the default fraction
+    monkeypatch.setenv("LSTM355_SPARSE_PROJ_MAX_DENSITY", "0.5")
+    desc, _ = check_case(case, CSR, PAUTO)
+    monkeypatch.delenv("LSTM355_SPARSE_PROJ_MAX_DENSITY")
+    assert "proj=q16" in desc
+
+
 def test_yardsticks_run_and_are_plausible():
     """The achievable-peak yardsticks: matrix-instruction issue loops, the streaming copy and the data-free barrier."""
     import torch
