@@ -135,10 +135,16 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
     if (kXcd && a.xcd_local)
         same_xcd = group_shares_xcd(a.xcc_ids + ((size_t)dir * a.bg + bgi) * 64, a.ug, ugi, a.tag_base + 1u, hbuf, tid,
                                     nthreads, a.timeout_flag, a.spin_limit) && !a.device_scope_only;
+    // P comes from memory (never from a cache: every element is read once), and a wave's loads return in order: a
+    // load of P issued in front of the poll would hold back the poll's answer by a memory round trip in every step.
+    // So the element for step s+1 is requested right after the poll of step s has been answered.
+    auto load_p = [&](int s_) {
+        const int t_ = reverse ? (a.T - 1 - s_) : s_;
+        return (pair_ok && s_ < a.T) ? Pd_c[((size_t)t_ * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row] : 0.f;
+    };
+    float pin_next = load_p(0);
     for (int s = 0; s < a.T; ++s) {
         const int t = reverse ? (a.T - 1 - s) : s;
-        float pin = 0.f;
-        if (pair_ok) pin = Pd_c[((size_t)t * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row];
         if (s == 0) {
             for (int e = tid; e < BW * H; e += nthreads) {
                 const int b = e / H, k = e - b * H;
@@ -154,6 +160,11 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
                 gather_tagged_cols<4, BW>(xchg + (size_t)(s & 1) * parity_stride, BW * H, bw, a.tag_base + (unsigned)s, hbuf, tid,
                                           nthreads, a.timeout_flag, a.spin_limit);
         }
+        // (the value is taken over here, behind the poll's own wait, and not at the top of the loop, where waiting for
+        // it would also wait for the acknowledgement of the stores just issued, in front of the poll)
+        if constexpr (S * UPW < 84) asm volatile("" : "+v"(pin_next));   // (near the register limit the pin costs more than it saves)
+        const float pin = pin_next;
+        pin_next = load_p(s + 1);
         __syncthreads();
         if constexpr (S * UPW >= 84) {
             // near the register limit the offsets stay packed two to a register: the compiler must not unpack all
