@@ -168,7 +168,8 @@ int lstm_forward(lstm_t* m, int T, int B, const void* x, const float* h0, const 
                  float* y, float* hT, float* cT, void* workspace, size_t workspace_bytes, void* stream);
 
 /* After the stream has been synchronised: LSTM_OK, or LSTM_ERR_TIMEOUT if a device-side bounded wait
- * expired during an earlier forward on this handle (its outputs are then invalid).  Clears the flag. */
+ * expired during an earlier forward on this handle (its outputs are then invalid).  Clears the flag; exchange
+ * state that the abandoned steps may have left half-written is cleared before the next forward uses it. */
 int lstm_check(lstm_t* m);
 
 /* Override the recurrence plan (LSTM_PLAN_*) and, for measurement, the number of waves per workgroup of

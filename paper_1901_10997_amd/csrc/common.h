@@ -58,6 +58,12 @@ struct LayerDir {
     // packed row 4g+q = hidden unit g of gate q); w2 [4H][G] and bias2 [4H] are the gate outputs (packed row 4j+q)
     PackedMat w2;
     float* bias2 = nullptr;
+    // batch-1 persistent kernel: the hidden-layer activations travel as 32-bit words stamped with the parity of the
+    // step count of the array they live in, so every cell has arrays of its own: [0, 4G) for eager calls (u_epoch counts
+    // their steps), [4G, 8G) for calls captured into a graph (cleared inside the graph, counted from zero)
+    unsigned* u_slots = nullptr;
+    unsigned u_epoch = 0;
+    bool u_dirty = false;   // a wait expired while the array was in use: clear it before the next launch
 };
 
 // Number of compute units of the current device (cached; 256 if the query fails).  The persistent kernels need
@@ -182,8 +188,9 @@ struct PersistHArgs {
     float* cT;
     int T, H, G, reverse;
     unsigned long long* xchg_h; // [H] tagged slots
-    unsigned long long* xchg_u; // [4G] tagged slots, gate-major
-    unsigned tag_base;          // step s publishes tag_base + s + 1 in both arrays
+    unsigned* xchg_u;           // [4G] 32-bit words, gate-major: u >= 0, so the sign bit carries the step's parity
+    unsigned u_epoch;           // steps this array has seen before the launch: step s stamps (u_epoch + s + 1) & 1
+    unsigned tag_base;          // step s publishes tag_base + s + 1 in xchg_h
     int* timeout_flag;
     unsigned spin_limit;
 };

@@ -558,6 +558,7 @@ int lstm_destroy(lstm_t* m)
         free_mat(x.w2);
         if (x.bias) (void)hipFree(x.bias);
         if (x.bias2) (void)hipFree(x.bias2);
+        if (x.u_slots) (void)hipFree(x.u_slots);
     }
     for (auto& sp : m->spans) { (void)hipEventDestroy(sp.e0); (void)hipEventDestroy(sp.e1); }
     for (auto& e : m->event_pool) (void)hipEventDestroy(e);
@@ -677,6 +678,12 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
     if (x.bias2) { (void)hipFree(x.bias2); x.bias2 = nullptr; }
     HIP_TRY(m, upload(&x.bias, bp1));
     HIP_TRY(m, upload(&x.bias2, bp2));
+    // stamped words of the batch-1 kernel's hidden-layer activations: [eager | captured], zero = stamp of an even count
+    if (x.u_slots) { (void)hipFree(x.u_slots); x.u_slots = nullptr; }
+    HIP_TRY(m, hipMalloc((void**)&x.u_slots, (size_t)8 * G * sizeof(unsigned)));
+    HIP_TRY(m, hipMemset(x.u_slots, 0, (size_t)8 * G * sizeof(unsigned)));
+    x.u_epoch = 0;
+    x.u_dirty = false;
     x.set = true;
     // One launch serves both matrices of every direction of a layer and is built for the largest slot count: bring the
     // others up to it (a matrix trimmed further would pay for those slots and for its own entries outside them).
@@ -1043,13 +1050,28 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
             continue;
         }
         for (int d = 0; d < Dn; ++d) {
-            const LayerDir& w = m->ld[(size_t)l * Dn + d];
+            LayerDir& w = m->ld[(size_t)l * Dn + d];
             const size_t n = (size_t)l * Dn + d;
             ProfSpan span(m, s, 1);
             if (persist[d]) {
                 unsigned tag0 = 0;
-                const int trc = take_b1_tags(m, (unsigned)T + 1u, (size_t)H + 4 * (size_t)G, s, &tag0);
+                const int trc = take_b1_tags(m, (unsigned)T + 1u, (size_t)m->H, s, &tag0);
                 if (trc != LSTM_OK) return trc;
+                // the stamped words: a captured launch clears its own array inside the graph and counts from zero (every
+                // replay then starts from the same state); an eager launch goes on counting where the last one stopped
+                unsigned* uarr = w.u_slots;
+                unsigned uepoch = 0;
+                if (m->capturing) {
+                    uarr += (size_t)4 * G;
+                    HIP_TRY(m, launch_fill_u64((unsigned long long*)uarr, (size_t)2 * G, 0ull, s));
+                } else {
+                    if (w.u_dirty || w.u_epoch > 0xFFFFFFFFu - (unsigned)T - 2u) {
+                        HIP_TRY(m, launch_fill_u64((unsigned long long*)uarr, (size_t)2 * G, 0ull, s));
+                        w.u_epoch = 0;
+                        w.u_dirty = false;
+                    }
+                    uepoch = w.u_epoch;
+                }
                 PersistHArgs a{};
                 a.ell_val_1x = w.wx.ell_val; a.ell_col_1x = w.wx.ell_col; a.slots_1x = w.wx.slots;
                 a.ell_val_1h = w.wh.ell_val; a.ell_col_1h = w.wh.ell_col; a.slots_1h = w.wh.slots;
@@ -1062,12 +1084,13 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 a.hT = hT ? hT + m->soff(n) : nullptr;
                 a.cT = cT ? cT + m->soff(n) : nullptr;
                 a.T = T; a.H = H; a.G = G; a.reverse = d;
-                a.xchg_h = m->xchg; a.xchg_u = m->xchg + H;
+                a.xchg_h = m->xchg; a.xchg_u = uarr; a.u_epoch = uepoch;
                 a.tag_base = tag0;
                 a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=fused,rec=persist_b1-hlstm-csr;", l, d);
                 m->last_plan += tag;
                 HIP_TRY(m, launch_persist_b1_hlstm(a, m->launch_mode(), s));
+                if (!m->capturing) w.u_epoch += (unsigned)T;
                 continue;
             }
             if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + m->soff(n) * B, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
@@ -1571,6 +1594,7 @@ int lstm_check(lstm_t* m)
     HIP_TRY(m, hipMemcpy(&flag, m->timeout_flag, sizeof(int), hipMemcpyDeviceToHost));
     if (flag) {
         HIP_TRY(m, hipMemset(m->timeout_flag, 0, sizeof(int)));
+        for (auto& x : m->ld) x.u_dirty = true;   // steps were abandoned half-way: the stamped words hold either parity
         return fail(m, LSTM_ERR_TIMEOUT, "a bounded device-side wait expired; outputs of that forward are invalid");
     }
     return LSTM_OK;

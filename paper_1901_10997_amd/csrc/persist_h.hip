@@ -10,11 +10,16 @@
 // 4g..4g+3 of W1x and W1h: the unit's row in each of the four gates) in the first half of a step and output unit
 // j = w (packed rows 4j..4j+3 of W2) in the second half; its slices of all three matrices stay in registers as
 // 64-lane slices of (value, 16-bit column) pairs for the whole sequence, its cell state in a register.
-// Both vectors travel through tagged 8-byte slots (low word: value, high word: step tag; one store publishes both,
-// consumers poll until the tag matches, no fence and no separate barrier).  u is laid out gate-major ([q][G]), so
-// row q of W2 gathers from one contiguous block of LDS with its stored column indices, and a workgroup publishes
-// one contiguous run of slots per gate.
-// One slot array per vector is enough: u_{t+1} is published only after its producer has received every h_t, and
+// h travels through tagged 8-byte slots (low word: value, high word: step tag; one store publishes both, consumers
+// poll until the tag matches, no fence and no separate barrier).  u has four times as many values and every
+// workgroup needs all of them, which made its exchange a matter of volume (6000 slots: 48 KB per workgroup and step);
+// but u >= 0 (ReLU), so its sign bit is free and carries the stamp instead: a 4-byte word per value, sign bit = parity
+// of the number of steps the array has seen.  One bit is enough: a reader of step s has itself received every word
+// of step s-1, so what it can find in a word is step s-1 (other parity: ask again) or step s.  The count runs on over
+// the launches that use the array (u_epoch), so that what a launch finds from the one before has the other parity
+// than its first step.  u is laid out gate-major ([q][G]), so row q of W2 gathers from one contiguous block of LDS
+// with its stored column indices, and a workgroup publishes one contiguous run of words per gate.
+// One array per vector is enough: u_{t+1} is published only after its producer has received every h_t, and
 // each h_t was published only after its producer had finished reading u_t (and the same with the roles swapped).
 // The input row x_{t+2} is requested at the top of step t, parked in LDS at the top of step t+1 (before the wait), and
 // its products are accumulated after h_{t+1} has been published, off the critical path.
@@ -29,15 +34,55 @@ namespace {
 
 constexpr int hl_maxt(int nz) { return nz <= 2 ? 1024 : nz <= 4 ? 768 : 512; }
 
+// Fetch `npairs` pairs of stamped words into LDS (sign bits cleared): a pair is accepted when both sign bits equal
+// `stamp`.  Each word was published by a store of its own, so each half of a pair is checked by its own bit.
+// Bounded like the tagged polls.
+template <int NF>
+__device__ __forceinline__ void gather_stamped_pairs(const u64* src, int npairs, unsigned stamp, u64* dst, int tid,
+                                                     int nthreads, int* timeout_flag, unsigned spin_limit)
+{
+    constexpr u64 kSigns = 0x8000000080000000ull;
+    const u64 want = stamp ? kSigns : 0ull;
+    for (int e0 = tid; e0 < npairs; e0 += NF * nthreads) {
+        u64 v[NF];
+        unsigned spins = 0;
+        bool ok;
+        do {
+            ok = true;
+#pragma unroll
+            for (int u = 0; u < NF; ++u) {
+                const int e = e0 + u * nthreads;
+                v[u] = (e < npairs) ? __hip_atomic_load(src + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : want;
+                ok = ok && ((v[u] & kSigns) == want);
+            }
+            if (!ok) {
+                ++spins;
+                if (spins > spin_limit) {
+                    __hip_atomic_store(timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    break;
+                }
+                if ((spins & 63u) == 0 &&
+                    __hip_atomic_load(timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+                    break;
+            }
+        } while (!ok);
+#pragma unroll
+        for (int u = 0; u < NF; ++u) {
+            const int e = e0 + u * nthreads;
+            if (e < npairs) dst[e] = v[u] & ~kSigns;
+        }
+    }
+}
+
 }  // namespace
 
 template <int NZ, int MAXT>
 __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
 {
-    extern __shared__ float lds[];  // hbuf[H] | ubuf[4G] | xbuf[2][D] | pub[4 * waves]
+    extern __shared__ float lds[];  // hbuf[H (+1: ubuf is copied in 8-byte pairs)] | ubuf[4G] | xbuf[2][D] | pub[4 * waves]
     const int H = a.H, G = a.G, D = a.D;
     float* hbuf = lds;
-    float* ubuf = hbuf + H;
+    float* ubuf = hbuf + ((H + 1) & ~1);
     float* xbuf = ubuf + 4 * (size_t)G;
     float* pub = xbuf + 2 * (size_t)D;
     const int tid = threadIdx.x, nthreads = blockDim.x;
@@ -124,6 +169,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
     for (int s = 0; s < a.T; ++s) {
         const int t = a.reverse ? (a.T - 1 - s) : s;
         const unsigned tag = a.tag_base + (unsigned)s + 1u;
+        const unsigned stamp = (a.u_epoch + (unsigned)s + 1u) & 1u;
         const bool more_x = s + 1 < a.T;
         if (more_x) park_x(s + 1);                   // requested a whole step ago: nothing to wait for
         if (s + 2 < a.T) request_x(s + 2);           // in flight during this step
@@ -149,14 +195,13 @@ __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
             // slots per gate and workgroup
             const int q = tid / nwaves, w = tid - q * nwaves;
             const int g = blockIdx.x * nwaves + w;
-            if (g < G)
-                __hip_atomic_store(a.xchg_u + (size_t)q * G + g, pack_slot(pub[4 * w + q], tag), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+            if (g < G)   // pub holds +0 or a positive value: the sign bit is the stamp's
+                __hip_atomic_store(a.xchg_u + (size_t)q * G + g, __float_as_uint(pub[4 * w + q]) | (stamp << 31),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // ---- stage 2: gate outputs from u_t, cell update
-        // (the variants with an odd slice count have the registers for eight polling loads in flight)
-        if constexpr (NZ & 1) gather_tagged_wide(a.xchg_u, 4 * G, tag, ubuf, tid, nthreads, a.timeout_flag, a.spin_limit);
-        else gather_tagged(a.xchg_u, 4 * G, tag, ubuf, tid, nthreads, a.timeout_flag, a.spin_limit);
+        gather_stamped_pairs<4>(reinterpret_cast<const u64*>(a.xchg_u), 2 * G, stamp, reinterpret_cast<u64*>(ubuf), tid,
+                                nthreads, a.timeout_flag, a.spin_limit);
         __syncthreads();
         float h = 0.f;
         {
@@ -195,7 +240,7 @@ bool persist_b1_hlstm_supported(int H, int G, int D, int slots_1x, int slots_1h,
     const int nz = std::max(slots_1x, std::max(slots_1h, slots_2));
     if (slots_1x < 1 || slots_1h < 1 || slots_2 < 1 || nz > 5) return false;
     const int waves = hl_maxt(nz) / 64;
-    if (((size_t)H + 4 * (size_t)G + 2 * (size_t)D + 4 * waves) * sizeof(float) > 64 * 1024) return false;
+    if (((size_t)H + 1 + 4 * (size_t)G + 2 * (size_t)D + 4 * waves) * sizeof(float) > 64 * 1024) return false;
     const int units = std::max(H, G);
     return (units + waves - 1) / waves <= device_num_cus();
 }
@@ -208,7 +253,7 @@ static hipError_t launch_hl_nz(PersistHArgs a, bool coop, hipStream_t s)
     const int units = std::max(a.H, a.G);
     const int blocks = (units + waves - 1) / waves;
     if (blocks > device_num_cus()) return hipErrorCooperativeLaunchTooLarge;
-    const size_t lds = ((size_t)a.H + 4 * (size_t)a.G + 2 * (size_t)a.D + 4 * waves) * sizeof(float);
+    const size_t lds = ((size_t)a.H + 1 + 4 * (size_t)a.G + 2 * (size_t)a.D + 4 * waves) * sizeof(float);
     void* args[] = {(void*)&a};
     const void* kern = (const void*)persist_b1_hlstm_kernel<NZ, MAXT>;
     // every workgroup must be resident at the same time: at most one per compute unit

@@ -141,6 +141,32 @@ def test_hlstm_persistent_long_sequence_and_state_chaining():
     np.testing.assert_array_equal(c2.cpu().numpy(), full[2])
 
 
+@pytest.mark.parametrize("L,bidir", [(1, False), (2, True)])
+def test_hlstm_batch1_consecutive_forwards_of_any_length_on_one_handle(L, bidir):
+    """The hidden-layer activations of the batch-1 kernel are stamped with one bit (the parity of the steps their array
+    has seen), which runs on from one forward to the next: sequences of odd and even lengths in any order on one
+    handle, each compared with the oracle, and every one twice in a row (bit-identical)."""
+    import torch
+    from oracle import hlstm_oracle as horc
+    from parity_util import compare
+    dev = torch.device("cuda:0")
+    base = inputs.make_case(_hw(86, L, bidir, 30, 140, 110, 9, 1, keep=0.3), k=L, random_state=True)
+    model = B.Lstm(L, 30, 140, bidir, B.LSTM_F32, gate_hidden=110)
+    model.set_weights_from(base.weights, CSR)
+    h0 = torch.from_numpy(base.h0).to(dev); c0 = torch.from_numpy(base.c0).to(dev)
+    for T in (1, 1, 3, 2, 5, 1, 4, 9, 7, 7, 2):
+        import dataclasses
+        case = dataclasses.replace(base, w=inputs.shrink(base.w, T=T), x=base.x[:T].copy())
+        x = torch.from_numpy(case.x).to(dev)
+        first = [t.cpu().numpy() for t in model.forward(x, h0, c0)]
+        assert "persist_b1-hlstm" in B.lstm_describe_plan(model.handle)
+        again = [t.cpu().numpy() for t in model.forward(x, h0, c0)]
+        for a, b in zip(first, again):
+            np.testing.assert_array_equal(a, b)
+        compare(first, horc.forward_case(case), "f32", f"T={T}")
+    model.close()
+
+
 # ---- small batches, row-compressed: one persistent launch per layer, 2-D grid of unit groups x batch groups -------
 @pytest.mark.parametrize("shape", [
     # L, bidir, D, H, G, T, B, keep, cooperative
