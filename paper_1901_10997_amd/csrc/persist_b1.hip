@@ -204,6 +204,145 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
 }
 
 // ------------------------------------------------------------------------------------------------------------
+// Dense, fused, grid on one XCD: every wave on its own.  A dense row multiplies h in the order it is stored, so
+// the wave can poll the slots straight into the registers its products read (lane l: h[l + 64 i]), load its part
+// of x_t the same way, and publish its h_t with one store from lane 0: no copy of h in LDS, no workgroup barrier
+// (the step of the kernel above spends more time in its two barriers and the LDS round trips between them than in
+// the hand-over through the L2).  Each wave polls all H slots itself, which only the L2 of one XCD serves fast
+// enough, and only for small H (figures below); everything else keeps the kernel above.  The slot ring needs no barrier either: the wave
+// that publishes h_t has received every value of h_{t-1}, and each of those was published by a wave that had
+// received all of h_{t-2}.
+// ------------------------------------------------------------------------------------------------------------
+template <int KI>
+__global__ __launch_bounds__(1024) void persist_b1_dense_wave_kernel(PersistB1Args a)
+{
+    __shared__ float tmp[64];
+    const int tid = threadIdx.x, nthreads = blockDim.x;
+    const int lane = tid & 63, upb = nthreads >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (blockIdx.x & 7) return;                      // the ids of residue 0 are dealt to one XCD (checked below)
+    const int bid = blockIdx.x >> 3;
+    const int j = bid * upb + wave;
+    const bool active = j < a.H;
+    const int jj = active ? j : a.H - 1;
+
+    float wh[4][KI], wx[4][KI];
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+            const int k = lane + 64 * i;
+            float v = 0.f, u = 0.f;
+            if (k < a.H) {
+                const size_t idx = (size_t)(4 * jj + q) * a.H + k;
+                v = a.w_bf16 ? bf16_bits_to_f32(((const uint16_t*)a.Wh)[idx]) : ((const float*)a.Wh)[idx];
+            }
+            if (k < a.D) {
+                const size_t idx = (size_t)(4 * jj + q) * a.D + k;
+                u = a.w_bf16 ? bf16_bits_to_f32(((const uint16_t*)a.Wx)[idx]) : ((const float*)a.Wx)[idx];
+            }
+            wh[q][i] = v;
+            wx[q][i] = u;
+        }
+    const int row = lane >> 4;                       // gate handled by this lane after the reduction
+    const float bias_l = a.bias[4 * jj + row];
+    float c = (active && a.c0) ? a.c0[j] : 0.f;
+    const bool same_xcd = group_shares_xcd(a.xcc_ids, (int)(gridDim.x >> 3), bid, a.tag_base + 1u, tmp, tid, nthreads,
+                                           a.timeout_flag, a.spin_limit) && !a.device_scope_only;
+    if (!active) return;                             // (after the workgroup's barriers)
+
+    // x_t in the lanes' registers; the row of the next step is requested once h_t is out
+    float xr[KI];
+    auto request_x = [&](int s_) {
+        const size_t xrow = (size_t)(a.reverse ? (a.T - 1 - s_) : s_) * a.D;
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+            const int k = lane + 64 * i;
+            xr[i] = (k < a.D) ? load_x(a.x, a.x_bf16, xrow + k) : 0.f;
+        }
+    };
+    float xa[4];
+    auto x_products = [&]() {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) xa[q] = 0.f;
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+            const float v = a.round_x_bf16 ? round_bf16(xr[i]) : xr[i];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) xa[q] = fmaf(wx[q][i], v, xa[q]);
+        }
+    };
+    request_x(0);
+    x_products();
+    if (1 < a.T) request_x(1);
+
+    for (int s = 0; s < a.T; ++s) {
+        const int t = a.reverse ? (a.T - 1 - s) : s;
+        float hv[KI];
+        if (s == 0) {
+#pragma unroll
+            for (int i = 0; i < KI; ++i) {
+                const int k = lane + 64 * i;
+                float v = (a.h0 && k < a.H) ? a.h0[k] : 0.f;
+                hv[i] = a.round_h_bf16 ? round_bf16(v) : v;
+            }
+        } else {
+            const u64* slots = a.xchg + (size_t)(s & 1) * a.H;
+            const unsigned want = a.tag_base + (unsigned)s;
+            u64 v[KI];
+            unsigned spins = 0;
+            bool ok;
+            do {
+                ok = true;
+#pragma unroll
+                for (int i = 0; i < KI; ++i) {
+                    const int k = lane + 64 * i;
+                    v[i] = (k < a.H) ? __hip_atomic_load(slots + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ((u64)want << 32);
+                    ok = ok && ((unsigned)(v[i] >> 32) == want);
+                }
+                if (!ok) {
+                    ++spins;
+                    if (spins > a.spin_limit) {
+                        __hip_atomic_store(a.timeout_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        break;
+                    }
+                    if ((spins & 63u) == 0 && __hip_atomic_load(a.timeout_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+                        break;
+                }
+            } while (!ok);
+#pragma unroll
+            for (int i = 0; i < KI; ++i) hv[i] = (lane + 64 * i < a.H) ? __uint_as_float((unsigned)v[i]) : 0.f;
+        }
+        float acc[4] = {xa[0], xa[1], xa[2], xa[3]};
+#pragma unroll
+        for (int i = 0; i < KI; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = fmaf(wh[q][i], hv[i], acc[q]);
+        const float pre = wave_sum4_rows(acc[0], acc[1], acc[2], acc[3]) + bias_l;
+        const float h = lstm_cell_rows(pre, lane, c);
+        if (lane == 0) {
+            if (s + 1 < a.T)
+                exchange_store(a.xchg + (size_t)((s + 1) & 1) * a.H + j,
+                               pack_slot(a.round_h_bf16 ? round_bf16(h) : h, a.tag_base + (unsigned)s + 1u), same_xcd);
+            // outputs after the publication: nothing on the way of h_t
+            a.y[(size_t)t * a.y_ld + j] = h;
+            if (s + 1 == a.T) {
+                if (a.hT) a.hT[j] = h;
+                if (a.cT) a.cT[j] = c;
+            }
+        }
+        if (s + 1 < a.T) {
+            x_products();                            // for step s+1, off the critical path
+            if (s + 2 < a.T) request_x(s + 2);
+        }
+    }
+}
+// Every wave polls all H slots, so the polled volume grows with H squared and all of it hits the same few lines of
+// the L2: measured against the kernel above (35 steps), H = 64: 37.7 against 45.8 us, 128: 43.6 against 47.2,
+// 192: 50.0 against 47.8, 256: 57.1 against 50.0, 448: 102.6 against 63.2.  Used up to H = 128.
+constexpr int kDenseWaveMaxKI = 2;
+
+// ------------------------------------------------------------------------------------------------------------
 // Row-compressed: (value, column) slices of W_x and W_h in registers; NL stacked layers per launch.
 // Wave w of a workgroup serves layer w / upb, unit blockIdx*upb + w % upb.  Global step s advances layer l
 // at time index s - l.
@@ -521,8 +660,12 @@ static hipError_t launch_dense_ki(PersistB1Args a, int wpg_req, bool coop, hipSt
     // a grid that fits one XCD (an eighth of the compute units) is placed on one
     a.one_xcd = (a.xcc_ids != nullptr && blocks > 1 && blocks <= device_num_cus() / 8) ? 1 : 0;
     if (a.one_xcd) blocks *= 8;
-    const size_t lds = ((size_t)KI * 64 * (FUSEX ? 3 : 1) + 16) * sizeof(float);
     void* args[] = {(void*)&a};
+    if constexpr (FUSEX && KI <= kDenseWaveMaxKI) {
+        // on one XCD every wave works on its own (no LDS, no barriers); x and h must both fit the KI register slices
+        if (a.one_xcd && a.D <= 64 * KI) return coop_launch(persist_b1_dense_wave_kernel<KI>, blocks, wpg * 64, 0, args, coop, s);
+    }
+    const size_t lds = ((size_t)KI * 64 * (FUSEX ? 3 : 1) + 16) * sizeof(float);
     return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT>, blocks, wpg * 64, lds, args, coop, s);
 }
 

@@ -613,6 +613,30 @@ def test_l2_handover_off_gives_the_same_bits(name, monkeypatch):
         assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
 
 
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, T, dtype -- dense batch-1 layers of at most 128 units on one XCD: every wave polls the slots
+    # into its own registers and publishes its own h (no LDS copy, no workgroup barrier)
+    (1, False, 64, 64, 35, "f32"),
+    (1, True, 100, 128, 9, "f32"),
+    (2, False, 33, 100, 12, "f32"),
+    (1, False, 20, 17, 5, "f32"),       # two workgroups, the second nearly empty
+    (1, False, 128, 96, 1, "f32"),      # T = 1: nothing is exchanged
+    (2, True, 70, 80, 7, "bf16"),
+])
+def test_small_dense_widths_every_wave_on_its_own(shape, monkeypatch):
+    L, bidir, D, H, T, dtype = shape
+    case = inputs.make_case(_wl(96, L, bidir, D, H, T, 1, dtype=dtype, a=0.3 if dtype == "f32" else 0.1), k=H + T, random_state=True)
+    for coop in (True, False):
+        desc, _ = check_case(case, DENSE, PERSIST, cooperative=coop)
+        assert "persist_b1-dense" in desc
+    on, _ = run_gpu(case, DENSE, PERSIST)
+    monkeypatch.setenv("LSTM355_L2_HANDOVER", "0")
+    off, _ = run_gpu(case, DENSE, PERSIST)
+    monkeypatch.delenv("LSTM355_L2_HANDOVER")
+    for a, b in zip(on, off):
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+
+
 def test_projection_density_switch(monkeypatch):
     """LSTM355_SPARSE_PROJ_MAX_DENSITY at lstm_create moves the boundary between the projection over the kept entries and
     the dense matrix-core product; both meet the oracle (they differ from each other only in summation order)."""
