@@ -317,6 +317,28 @@ def main():
             proj["frac_of_measured"] = proj["achieved"] / proj["measured_peak"]
             proj["measured_peak_random_operands"] = measured[key + "_random_operands_TFLOPs"]
             proj["frac_of_measured_random_operands"] = proj["achieved"] / proj["measured_peak_random_operands"]
+            # the vendor library's product of the first layer's projection shape, same operand and output types (fp32
+            # out), as a yardstick of what this shape reaches on this device; it is not part of the path
+            try:
+                Mr, Kr, Nr = T * Bn, wl.layer_input_dim(0), 4 * (G if hl else H)
+                tdt = torch.bfloat16 if dtype == B.LSTM_BF16 else torch.float32
+                ga = torch.randn(Mr, Kr, device=dev).to(tdt)
+                gb = ((torch.rand(Nr, Kr, device=dev) * 2 - 1) * wl.a).to(tdt).t()
+                mm = (lambda: torch.mm(ga, gb, out_dtype=torch.float32)) if tdt == torch.bfloat16 else (lambda: torch.mm(ga, gb))
+                for _ in range(3):
+                    mm()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(10):
+                    mm()
+                e1.record()
+                torch.cuda.synchronize(dev)
+                lib_us = e0.elapsed_time(e1) * 1e3 / 10
+                proj["library_gemm"] = {"shape_MKN": [Mr, Kr, Nr], "us": lib_us, "TFLOPs": 2.0 * Mr * Kr * Nr / lib_us / 1e6,
+                                        "kind": "torch.mm (hipBLASLt), fp32 output"}
+                del ga, gb
+            except Exception as e:   # older torch without out_dtype, or no library kernel for the shape
+                proj["library_gemm"] = {"error": str(e)[:200]}
         # cold weights: one forward right after a 2 x 512 MiB device copy has swept the caches
         colds = []
         for _ in range(5):
