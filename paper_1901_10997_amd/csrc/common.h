@@ -15,6 +15,8 @@ struct PackedMat {
     int rows = 0, cols = 0;
     bool compressed = false;
     void* dense = nullptr;       // [rows][cols], fp32 or bf16 bits; +0 where the mask is 0
+    float* dense_frag16 = nullptr;  // fp32 input-side matrices: `dense` once more in the fragment order of the 16x16x4
+                                    // matrix instruction (launch_proj_mfma), for products with at most 64 input rows
     int64_t nnz = 0;             // compressed: kept positions (== popcount of the mask)
     int32_t* row_ptr = nullptr;  // device [rows+1]
     uint16_t* col16 = nullptr;   // device [nnz]  (cols <= 65536)
@@ -77,8 +79,11 @@ hipError_t launch_proj_dense(const void* X, bool x_bf16, int ldx, const void* W,
                              float* P, int M, int N, int K, hipStream_t s);
 // Same product on the matrix cores (needs proj_mfma_supported); fp32 X with bf16 W is rounded to bf16 on load.
 bool proj_mfma_supported(bool w_bf16, int K, int ldx);
+// W_frag16 (fp32 models, may be null): the same W in the fragment order of the 16x16x4 matrix instruction
+// ([ceil(N/16)][ceil(K/16)][64 lanes][4], lane l: row 16 nb + l % 16, k = 16 kb + 4 (l / 16) .. + 3, zero padded),
+// used when X has at most 64 rows.
 hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, bool w_bf16, const float* bias, float* P,
-                            int M, int N, int K, hipStream_t s);
+                            int M, int N, int K, hipStream_t s, const float* W_frag16 = nullptr);
 hipError_t launch_proj_mfma_f32_pair(const float* X, int ldx, const float* W0, const float* bias0, float* P0,
                                      const float* W1, const float* bias1, float* P1, int M, int N, int K, hipStream_t s);
 // XT[k][m] = (float) X[m][k]   (optionally rounding fp32 -> bf16 -> fp32 on the way)

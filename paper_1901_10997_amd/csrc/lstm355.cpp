@@ -108,6 +108,7 @@ static float host_bf16_to_f32(uint16_t b)
 static void free_mat(PackedMat& p)
 {
     if (p.dense) (void)hipFree(p.dense);
+    if (p.dense_frag16) (void)hipFree(p.dense_frag16);
     if (p.row_ptr) (void)hipFree(p.row_ptr);
     if (p.col16) (void)hipFree(p.col16);
     if (p.val) (void)hipFree(p.val);
@@ -299,9 +300,28 @@ static int build_quarter_wave(lstm_t* m, PackedMat& out, int force_slots, int ma
     return LSTM_OK;
 }
 
+// A row-major fp32 matrix W[rows][cols] in the fragment order of the 16x16x4 matrix instruction: tile (nb, kb) is 64 lanes
+// x 4 values, lane l holding W[16 nb + l % 16][16 kb + 4 (l / 16) .. + 3]; zero beyond the matrix (launch_proj_mfma).
+static std::vector<float> to_frag16(const float* W, int rows, int cols)
+{
+    const int NB = (rows + 15) / 16, KB = (cols + 15) / 16;
+    std::vector<float> out((size_t)NB * KB * 256, 0.0f);
+    for (int nb = 0; nb < NB; ++nb)
+        for (int kb = 0; kb < KB; ++kb) {
+            float* tile = out.data() + ((size_t)nb * KB + kb) * 256;
+            for (int l = 0; l < 64; ++l) {
+                const int n = 16 * nb + (l & 15), k0 = 16 * kb + 4 * (l >> 4);
+                if (n >= rows) continue;
+                for (int c = 0; c < 4 && k0 + c < cols; ++c) tile[4 * l + c] = W[(size_t)n * cols + k0 + c];
+            }
+        }
+    return out;
+}
+
 // Pack one matrix W[4H][cols] (ABI row order q*H + j) with its optional mask into device storage.
 static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t* mask, int H, int cols, bool compressed,
-                       bool bf16, bool keep_dense, int quarter_slots = 0, int gate_col_stride = 0, int soft_slots = 0)
+                       bool bf16, bool keep_dense, int quarter_slots = 0, int gate_col_stride = 0, int soft_slots = 0,
+                       bool frag16 = false)
 {
     free_mat(out);
     const int rows = 4 * H;
@@ -330,6 +350,7 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
             float* d = nullptr;
             HIP_TRY(m, upload(&d, buf));
             out.dense = d;
+            if (frag16 && cols % 4 == 0) HIP_TRY(m, upload(&out.dense_frag16, to_frag16(buf.data(), rows, cols)));
         }
         if (!compressed) return LSTM_OK;
     }
@@ -603,7 +624,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     x.set = false;
     const bool bf16 = (m->dtype == LSTM_BF16);
     // W_x is kept in both forms when compressed: large T*B projections run dense on the matrix cores
-    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16, true, bf16 ? 0 : 24);
+    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16, true, bf16 ? 0 : 24, 0, 0, !bf16);
     if (rc != LSTM_OK) return rc;
     rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16, false, 16);
     if (rc != LSTM_OK) return rc;
@@ -664,7 +685,7 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
     LayerDir& x = m->ld[(size_t)layer * m->Dn + direction];
     x.set = false;
     // hidden layers: 4G rows, packed row 4g+q; kept dense as well for the projection on the matrix cores
-    int rc = pack_matrix(m, x.wx, W1x, mask_1x, G, D, compressed, false, true);
+    int rc = pack_matrix(m, x.wx, W1x, mask_1x, G, D, compressed, false, true, 0, 0, 0, true);
     if (rc != LSTM_OK) return rc;
     rc = pack_matrix(m, x.wh, W1h, mask_1h, G, H, compressed, false, false, 16, 0, 12);
     if (rc != LSTM_OK) return rc;
@@ -931,7 +952,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 }
                 HIP_TRY(m, launch_proj_csr(XT, w.wx.row_ptr, w.wx.col16, w.wx.val, w.bias, P[d], M, 4 * G, s));
             } else if (proj_mfma_supported(false, D, D)) {
-                HIP_TRY(m, launch_proj_mfma(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s));
+                HIP_TRY(m, launch_proj_mfma(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s, w.wx.dense_frag16));
             } else {
                 HIP_TRY(m, launch_proj_dense(X, false, D, w.wx.dense, false, w.bias, P[d], M, 4 * G, D, s));
             }
@@ -1321,7 +1342,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 }
                 HIP_TRY(m, launch_proj_csr(XT, w.wx.row_ptr, w.wx.col16, w.wx.val, w.bias, P[d], M, 4 * H, s));
             } else if (proj_mfma_supported(bf16, D, D)) {
-                HIP_TRY(m, launch_proj_mfma(X, x_is_bf16, D, w.wx.dense, bf16, w.bias, P[d], M, 4 * H, D, s));
+                HIP_TRY(m, launch_proj_mfma(X, x_is_bf16, D, w.wx.dense, bf16, w.bias, P[d], M, 4 * H, D, s, bf16 ? nullptr : w.wx.dense_frag16));
             } else {
                 HIP_TRY(m, launch_proj_dense(X, x_is_bf16, D, w.wx.dense, bf16, w.bias, P[d], M, 4 * H, D, s));
             }
@@ -1950,7 +1971,7 @@ int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, 
                 ec[(size_t)r * slots * 64 + (size_t)(e - rp[r])] = col[(size_t)e];
             }
     }
-    float *dX = nullptr, *dW = nullptr, *dB = nullptr, *dY = nullptr, *dXT = nullptr, *dval = nullptr, *dev_ = nullptr;
+    float *dX = nullptr, *dW = nullptr, *dWf = nullptr, *dB = nullptr, *dY = nullptr, *dXT = nullptr, *dval = nullptr, *dev_ = nullptr;
     int32_t* drp = nullptr;
     uint16_t *dcol = nullptr, *dec = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
@@ -1962,7 +1983,7 @@ int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, 
             if (e != hipSuccess) return e;
             return launch_proj_csr(dXT, drp, dcol, dval, dB, dY, batch, n, s);
         }
-        if (proj_mfma_supported(false, n, n)) return launch_proj_mfma(dX, false, n, dW, false, dB, dY, batch, n, n, s);
+        if (proj_mfma_supported(false, n, n)) return launch_proj_mfma(dX, false, n, dW, false, dB, dY, batch, n, n, s, dWf);
         return launch_proj_dense(dX, false, n, dW, false, dB, dY, batch, n, n, s);
     };
     hipError_t e = upload(&dX, X);
@@ -1978,6 +1999,8 @@ int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, 
         if (e == hipSuccess) e = hipMalloc((void**)&dXT, (size_t)batch * n * sizeof(float));
     } else if (e == hipSuccess) {
         e = upload(&dW, W);
+        // as lstm_set_weights stores an input-side matrix: once more in fragment order, for batches of at most 64 rows
+        if (e == hipSuccess && batch <= 64) e = upload(&dWf, to_frag16(W.data(), n, n));
     }
     if (e == hipSuccess) e = hipEventCreate(&e0);
     if (e == hipSuccess) e = hipEventCreate(&e1);
@@ -1993,7 +2016,7 @@ int lstm_bench_matmul(int n, int batch, double keep, int format, uint64_t seed, 
     else *avg_us = (double)ms * 1000.0 / iters;
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
-    for (void* p_ : {(void*)dX, (void*)dW, (void*)dB, (void*)dY, (void*)dXT, (void*)dval, (void*)drp, (void*)dcol, (void*)dev_, (void*)dec})
+    for (void* p_ : {(void*)dX, (void*)dW, (void*)dWf, (void*)dB, (void*)dY, (void*)dXT, (void*)dval, (void*)drp, (void*)dcol, (void*)dev_, (void*)dec})
         if (p_) (void)hipFree(p_);
     return rc;
 }

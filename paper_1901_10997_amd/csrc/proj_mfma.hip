@@ -628,102 +628,141 @@ __global__ __launch_bounds__(256) void proj_mfma_f32_kernel(const float* __restr
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// fp32, at most 64 rows of X (batch-1 sequences: M = T).  The product is a stream over W (read once, 4H*K*4
-// bytes) with X resident in L2, so there is no LDS pipeline: a workgroup owns 32 packed rows of W for all of
-// X, its eight waves split K and stream their operand fragments from global memory straight into registers
-// (16 bytes per lane and row), and the eight partial tiles are summed through LDS in a fixed order.  Two
-// register sets of four k-blocks alternate, so the loads of the next 32 k are in flight while the MFMAs of the
-// current ones execute (an MFMA issue blocks the wave, so without this every block of k paid a memory round
-// trip), and two waves share a SIMD.  MT = 1 when M <= 32: half the MFMAs.  Requires K % 4 == 0 and ldx % 4 == 0.
+// fp32, at most 64 rows of X (batch-1 sequences: M = T; small batches), W stored in fragment order.  The product is a
+// stream over W (read once, N*K*4 bytes) with X resident in L2.  Read row-major with one lane per row of W, as the
+// matrix instruction wants its operand, every load instruction touches 32 rows, 32 bytes of a 128-byte line each, and
+// the stream ran at a fifth of the memory rate.  So the weights are stored once more at set-up in the order the 16x16x4
+// matrix instruction takes them -- tile (16 rows of W, 16 k): 64 lanes x 16 bytes, lane l holding
+// W[16 nb + l % 16][16 kb + 4 (l / 16) .. + 3] -- so that a wave's load of a tile is 1 KB of consecutive bytes, and
+// the rows of X (which stay in L2) are read 64 contiguous bytes per row.  With 16-row tiles a sequence of 35 rows
+// costs three tiles of matrix work instead of the two 32-row tiles' worth of four.  A workgroup owns NT tiles of W
+// rows for all of X; its eight waves split K, keep PD blocks of 16 k in flight, and their partial tiles are summed
+// through LDS in a fixed order.  Requires K % 4 == 0 and ldx % 4 == 0 (16-byte loads of X).
 // ---------------------------------------------------------------------------------------------------------
-template <int MT>
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+template <int MT, int NT, int PD>
 __global__ __launch_bounds__(512) void proj_mfma_f32_skinny_kernel(const float* __restrict__ X, int ldx,
-                                                                   const float* __restrict__ W,
-                                                                   const float* __restrict__ bias, float* __restrict__ P,
-                                                                   int M, int N, int K)
+                                                                     const float4* __restrict__ Wf,
+                                                                     const float* __restrict__ bias, float* __restrict__ P,
+                                                                     int M, int N, int K)
 {
-    constexpr int NW = 8, UN = 4;    // waves splitting K; k-blocks of 8 per register set
-    __shared__ float part[NW][32 * MT][32];   // lanes write and read along the last index: no padding needed
-    const int n0 = blockIdx.x * 32;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int fr = lane & 31, fk = lane >> 5;
-    // K is cut into eight contiguous pieces (multiples of 8), one per wave; K itself only needs to be a multiple of 4:
-    // in the last block of 8 the lanes of the upper half (k + 4 .. k + 7) then have nothing to read
-    const int kq = (((K + 7) / 8 + NW - 1) / NW) * 8;
-    const int kbeg = wave * kq, kend = (kbeg + kq) < K ? (kbeg + kq) : K;
-    f32x16 acc[MT];
+    constexpr int NW = 8;
+    __shared__ float part[NW][MT * 16][NT * 16];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lr = lane & 15, lk = lane >> 4;
+    const int KB = (K + 15) >> 4, NB = (N + 15) >> 4;
+    const int nb0 = blockIdx.x * NT;
+    const int per = (KB + NW - 1) / NW;
+    const int kb_beg = wave * per, kb_end = (kb_beg + per) < KB ? (kb_beg + per) : KB;
+    f32x4 acc[MT][NT];
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-    const float* arow[MT];
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.f;
+    const float* xrow[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
-        int mr = 32 * i + fr;
+        int mr = 16 * i + lr;
         if (mr > M - 1) mr = M - 1;   // rows beyond M are computed on a valid row and never stored
-        arow[i] = X + (size_t)mr * ldx + fk * 4;
+        xrow[i] = X + (size_t)mr * ldx;
     }
-    int nr = n0 + fr;
-    if (nr > N - 1) nr = N - 1;
-    const float* bw = W + (size_t)nr * K + fk * 4;
-    float4 fa0[MT][UN], fb0[UN], fa1[MT][UN], fb1[UN];
-    auto load0 = [&](int k0) {
+    const float4* wtile[NT];
 #pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int k = k0 + 8 * u;
-            const bool ok = k + 4 * fk < kend;
-#pragma unroll
-            for (int i = 0; i < MT; ++i) fa0[i][u] = ok ? *reinterpret_cast<const float4*>(arow[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-            fb0[u] = ok ? *reinterpret_cast<const float4*>(bw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-    auto load1 = [&](int k0) {
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int k = k0 + 8 * u;
-            const bool ok = k + 4 * fk < kend;
-#pragma unroll
-            for (int i = 0; i < MT; ++i) fa1[i][u] = ok ? *reinterpret_cast<const float4*>(arow[i] + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-            fb1[u] = ok ? *reinterpret_cast<const float4*>(bw + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-    };
-    auto mma = [&](const float4 (&fa)[MT][UN], const float4 (&fb)[UN]) {
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-#pragma unroll
-            for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][u].x, fb[u].x, acc[i], 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][u].y, fb[u].y, acc[i], 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][u].z, fb[u].z, acc[i], 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < MT; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][u].w, fb[u].w, acc[i], 0, 0, 0);
-        }
-    };
-    constexpr int KSTEP = 8 * UN;
-    if (kbeg < kend) load0(kbeg);
-    for (int k0 = kbeg; k0 < kend; k0 += 2 * KSTEP) {
-        if (k0 + KSTEP < kend) load1(k0 + KSTEP);
-        mma(fa0, fb0);
-        if (k0 + KSTEP < kend) {
-            if (k0 + 2 * KSTEP < kend) load0(k0 + 2 * KSTEP);
-            mma(fa1, fb1);
-        }
+    for (int j = 0; j < NT; ++j) {
+        const int nb = (nb0 + j < NB) ? (nb0 + j) : (NB - 1);   // a tile beyond N repeats the last one and is never stored
+        wtile[j] = Wf + (size_t)nb * KB * 64 + lane;
     }
+    if (kb_beg < kb_end) {
+        // The loads carry no condition: a prefetch past the wave's share reads the share's last block again and is never
+        // multiplied, and a lane past K reads the last four values of its row against the zero padding of W.  (With a
+        // branch or a select on a load the compiler waits for it where the paths join or where the select sits, and the
+        // blocks no longer overlap.)
+        float4 fa[PD][MT], fb[PD][NT];
+        auto load = [&](int p, int kb) {
+            const int kbc = kb < kb_end ? kb : (kb_end - 1);
+            int k = 16 * kbc + 4 * lk;
+            k = k < K - 4 ? k : K - 4;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) fa[p][i] = *reinterpret_cast<const float4*>(xrow[i] + k);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) fb[p][j] = wtile[j][(size_t)kbc * 64];
+        };
+        auto mma = [&](int p) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[p][i].x, fb[p][j].x, acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[p][i].y, fb[p][j].y, acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[p][i].z, fb[p][j].z, acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < MT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[p][i].w, fb[p][j].w, acc[i][j], 0, 0, 0);
+        };
+#pragma unroll
+        for (int p = 0; p < PD; ++p) load(p, kb_beg + p);
+        int kb = kb_beg;
+        for (; kb + PD <= kb_end; kb += PD) {
+#pragma unroll
+            for (int p = 0; p < PD; ++p) {
+                __builtin_amdgcn_sched_barrier(0);
+                mma(p);
+                __builtin_amdgcn_sched_barrier(0);
+                load(p, kb + p + PD);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const int rest = kb_end - kb;              // < PD blocks are left, already requested
+#pragma unroll
+        for (int p = 0; p < PD - 1; ++p)
+            if (p < rest) mma(p);
+    }
+    // lane l of an accumulator tile holds rows 4 (l / 16) .. + 3 of column l % 16
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) part[wave][i * 32 + 8 * (v >> 2) + 4 * fk + (v & 3)][fr] = acc[i][v];
+        for (int j = 0; j < NT; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) part[wave][16 * i + 4 * lk + v][16 * j + lr] = acc[i][j][v];
     __syncthreads();
-    for (int e = tid; e < 32 * MT * 32; e += 512) {
-        const int m = e >> 5, n = e & 31;
-        if (m < M && n0 + n < N) {
+    for (int e = tid; e < MT * 16 * NT * 16; e += 512) {
+        const int m = e / (NT * 16), n = 16 * nb0 + e % (NT * 16);
+        if (m < M && n < N) {
             float sum = 0.f;
 #pragma unroll
-            for (int w = 0; w < NW; ++w) sum += part[w][m][n];
-            P[(size_t)m * N + n0 + n] = sum + bias[n0 + n];
+            for (int w = 0; w < NW; ++w) sum += part[w][m][e % (NT * 16)];
+            P[(size_t)m * N + n] = sum + bias[n];
         }
     }
+}
+
+template <int MT>
+static hipError_t launch_skinny(const float* X, int ldx, const float* Wf, const float* bias, float* P, int M, int N, int K,
+                                  hipStream_t s)
+{
+    const int NB = (N + 15) / 16, KB = (K + 15) / 16;
+    // Two tiles of W rows per workgroup halve the reads of X; taken when that still gives five in eight compute units a
+    // workgroup (measured: 4H = 5248 rows and more are faster that way, 4096 rows much slower).  Blocks in flight per
+    // wave: four where a wave's share of K is long enough to fill such a pipeline, else two.
+    const bool nt2 = (NB + 1) / 2 >= (device_num_cus() * 5) / 8;
+    const bool deep = (KB + 7) / 8 >= 24;
+    const dim3 grid(nt2 ? (NB + 1) / 2 : NB), block(512);
+    const float4* W4 = (const float4*)Wf;
+    if (nt2 && deep) hipLaunchKernelGGL((proj_mfma_f32_skinny_kernel<MT, 2, 4>), grid, block, 0, s, X, ldx, W4, bias, P, M, N, K);
+    else if (nt2) hipLaunchKernelGGL((proj_mfma_f32_skinny_kernel<MT, 2, 2>), grid, block, 0, s, X, ldx, W4, bias, P, M, N, K);
+    else if (deep) hipLaunchKernelGGL((proj_mfma_f32_skinny_kernel<MT, 1, 4>), grid, block, 0, s, X, ldx, W4, bias, P, M, N, K);
+    else hipLaunchKernelGGL((proj_mfma_f32_skinny_kernel<MT, 1, 2>), grid, block, 0, s, X, ldx, W4, bias, P, M, N, K);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------ launchers
@@ -842,7 +881,7 @@ bool proj_mfma_supported(bool w_bf16, int K, int ldx)
 }
 
 hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, bool w_bf16, const float* bias, float* P,
-                            int M, int N, int K, hipStream_t s)
+                            int M, int N, int K, hipStream_t s, const float* W_frag16)
 {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (!proj_mfma_supported(w_bf16, K, ldx)) return hipErrorInvalidValue;
@@ -864,14 +903,13 @@ hipError_t launch_proj_mfma(const void* X, bool x_bf16, int ldx, const void* W, 
                       : launch_bf16<4, 2, true>(X, ldx, Wb, bias, P, M, N, K, s);
     }
     if (x_bf16) return hipErrorInvalidValue;
-    if (M <= 64 && K % 4 == 0 && ldx % 4 == 0) {
-        if (M <= 32)
-            hipLaunchKernelGGL(proj_mfma_f32_skinny_kernel<1>, dim3((N + 31) / 32), dim3(512), 0, s, (const float*)X, ldx,
-                               (const float*)W, bias, P, M, N, K);
-        else
-            hipLaunchKernelGGL(proj_mfma_f32_skinny_kernel<2>, dim3((N + 31) / 32), dim3(512), 0, s, (const float*)X, ldx,
-                               (const float*)W, bias, P, M, N, K);
-        return hipGetLastError();
+    if (M <= 64 && K % 4 == 0 && ldx % 4 == 0 && W_frag16 != nullptr) {
+        switch ((M + 15) / 16) {
+            case 1: return launch_skinny<1>((const float*)X, ldx, W_frag16, bias, P, M, N, K, s);
+            case 2: return launch_skinny<2>((const float*)X, ldx, W_frag16, bias, P, M, N, K, s);
+            case 3: return launch_skinny<3>((const float*)X, ldx, W_frag16, bias, P, M, N, K, s);
+            default: return launch_skinny<4>((const float*)X, ldx, W_frag16, bias, P, M, N, K, s);
+        }
     }
     if (f32_small_tiles(M, N, 1)) return launch_f32<1, 1, 32>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);
     return launch_f32<2, 2, 32>((const float*)X, ldx, (const float*)W, bias, P, nullptr, nullptr, nullptr, M, N, K, s);

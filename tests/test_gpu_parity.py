@@ -504,7 +504,9 @@ def test_model_level_latency_sweep_runs_every_family():
 
 
 @pytest.mark.parametrize("n,batch,keep", [(64, 16, 0.5), (260, 16, 0.1), (512, 5, 1.0), (1000, 16, 0.05), (132, 70, 0.3),
-                                          (2048, 16, 0.1), (4096, 16, 0.05), (1500, 16, None), (5124, 3, 0.02)])
+                                          (2048, 16, 0.1), (4096, 16, 0.05), (1500, 16, None), (5124, 3, 0.02),
+                                          # one to four 16-row tiles of input rows, widths that end inside a tile
+                                          (260, 35, 0.5), (516, 64, None), (72, 1, None), (1316, 48, 0.3), (2052, 33, None)])
 @pytest.mark.parametrize("fmt", [DENSE, CSR])
 def test_standalone_product_against_the_oracle(n, batch, keep, fmt):
     """lstm_bench_matmul on caller-supplied seeded operands (Section 3, matmul latency figures): the product of either
