@@ -540,6 +540,20 @@ static int create_model(int layers, int input_dim, const int* hidden_dims, const
     return LSTM_OK;
 }
 
+// Does a separate projection launch of this input-side matrix run as a dense product on the matrix cores (zeros included)?
+// Measured on MI355X: with a few hundred input rows or more the dense product beats the compressed ones at 10-15 % kept
+// weights (the projection over the kept entries, tried before this is asked, takes the large sparse cases); with at most
+// 64 input rows the stream over the fragment-ordered dense copy beats the lanes-over-entries kernel down to 5 % kept at
+// every width from 256 to 4096 (batch 16: 14.5 against 15.9 us at n = 4096, 4.2 against 7.1 us at n = 1024).
+static bool proj_runs_dense(const PackedMat& wx, int M, int D, bool bf16)
+{
+    if (!wx.dense) return false;
+    if (!wx.compressed) return true;
+    if (!proj_mfma_supported(bf16, D, D)) return false;
+    if (M >= 256) return true;
+    return M <= 64 && wx.dense_frag16 != nullptr && (double)wx.nnz >= 0.04 * (double)wx.rows * (double)wx.cols;
+}
+
 int lstm_create(int layers, int input_dim, int hidden_dim, int bidirectional, int dtype, lstm_t** out)
 {
     if (out) *out = nullptr;
@@ -940,7 +954,7 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
             if (persist[d]) continue;
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             ProfSpan span(m, s, 0);
-            const bool dense_proj = w.wx.dense && (!w.wx.compressed || (M >= 256 && proj_mfma_supported(false, D, D)));
+            const bool dense_proj = proj_runs_dense(w.wx, M, D, false);
             proj_dense[d] = dense_proj;
             if (!dense_proj && w.wx.ell_val && proj_ell_small_supported(M, 4 * G, D, w.wx.slots)) {
                 HIP_TRY(m, launch_proj_ell_small(X, false, D, false, w.wx.ell_val, w.wx.ell_col, w.wx.slots, w.bias, P[d], M,
@@ -1328,9 +1342,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             if (mode[d] == 1 || mode[d] == 2) continue;
             const LayerDir& w = m->ld[(size_t)l * Dn + d];
             ProfSpan span(m, s, 0);
-            // measured on MI355X: at 10-15 % density the dense MFMA product beats the compressed one once
-            // T*B reaches a few hundred rows; below that the compressed product reads far fewer bytes
-            const bool dense_proj = w.wx.dense && (!w.wx.compressed || (M >= 256 && proj_mfma_supported(bf16, D, D)));
+            const bool dense_proj = proj_runs_dense(w.wx, M, D, bf16);
             if (!dense_proj && w.wx.ell_val && proj_ell_small_supported(M, 4 * H, D, w.wx.slots)) {
                 // few input rows: lanes over the kept entries of a row (no transpose of X)
                 HIP_TRY(m, launch_proj_ell_small(X, x_is_bf16, D, bf16 && !x_is_bf16, w.wx.ell_val, w.wx.ell_col, w.wx.slots,
@@ -1464,7 +1476,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
                     a.d[d].reverse = d;
                     std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16%s(s%d,u%d,b%d);", l, d,
-                                  proj_q16_used ? "q16" : (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr",
+                                  proj_q16_used ? "q16" : proj_runs_dense(w.wx, M, D, bf16) ? "dense" : "csr",
                                   w.wh.q16_ovf_ptr ? "+ovf" : "", q16, upw, bw);
                     m->last_plan += tag;
                 }
@@ -1494,7 +1506,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 if (c0) HIP_TRY(m, hipMemcpyAsync(cbuf[d], c0 + m->soff(n) * B, (size_t)B * H * sizeof(float), hipMemcpyDeviceToDevice, s));
                 else HIP_TRY(m, launch_fill_f32(cbuf[d], (size_t)B * H, 0.0f, s));
                 std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=stepwise-csr-paired;", l, d,
-                              proj_q16_used ? "q16" : (w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ? "dense" : "csr");
+                              proj_q16_used ? "q16" : proj_runs_dense(w.wx, M, D, bf16) ? "dense" : "csr");
                 m->last_plan += tag;
             }
             for (int step = 0; step < T; ++step) {
@@ -1536,7 +1548,7 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             float* cTn = cT ? cT + m->soff(n) * B : nullptr;
             static const char* const names[4] = {"stepwise", "persist_b1", "persist_b1", "persist_b1"};
             std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s%s,rec=%s-%s%s;", l, d, (mode[d] == 1 || mode[d] == 2) ? "fused-" : "",
-                          proj_q16_used ? "q16" : (w.wx.compressed && !(w.wx.dense && M >= 256 && proj_mfma_supported(bf16, D, D)) ) ? "csr" : "dense",
+                          proj_q16_used ? "q16" : ((mode[d] == 1 || mode[d] == 2) ? !w.wx.compressed : proj_runs_dense(w.wx, M, D, bf16)) ? "dense" : "csr",
                           names[mode[d]], w.wh.compressed ? "csr" : "dense",
                           (mode[d] == 1 && (w.wx.slots_trim || w.wh.slots_trim)) ? "+ovf" : "");
             m->last_plan += tag;

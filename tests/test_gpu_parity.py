@@ -658,6 +658,16 @@ def test_projection_density_switch(monkeypatch):
     assert "proj=q16" in desc
 
 
+def test_few_input_rows_take_the_dense_projection_down_to_a_few_percent_kept():
+    """With at most 64 input rows a separate projection launch of a row-compressed W_x streams the fragment-ordered
+    dense copy on the matrix cores unless fewer than 4 % of the weights are kept; both choices meet the oracle."""
+    for keep, want in ((0.3, "proj=dense"), (0.02, "proj=csr")):
+        for T, Bn in ((9, 1), (5, 7), (15, 4)):
+            case = inputs.make_case(_wl(95, 2, True, 72, 100, T, Bn, keep=keep), k=T + Bn, random_state=True)
+            desc, _ = check_case(case, CSR, STEP)
+            assert want in desc, desc
+
+
 def test_yardsticks_run_and_are_plausible():
     """The achievable-peak yardsticks: matrix-instruction issue loops, the streaming copy and the data-free barrier."""
     import torch
