@@ -49,16 +49,21 @@ __device__ __forceinline__ float load_x(const void* x, int x_bf16, size_t idx)
     return x_bf16 ? bf16_bits_to_f32(((const uint16_t*)x)[idx]) : ((const float*)x)[idx];
 }
 
+// widest layer whose waves publish for themselves when the grid sits on one XCD (measured, 35 steps: H = 256 49.8 -> 46.7 us, 320 54.3 ->
+// 49.6, 384 57.3 -> 57.0, 448 62.6 -> 68.1: beyond some 350 stores per step the one coalesced store per workgroup wins)
+constexpr int kDenseDirectMaxH = 352;
+
 // ------------------------------------------------------------------------------------------------------------
 // Dense: W_h (and, when FUSEX, W_x) slices in registers.  One cell (layer, direction) per launch.
 // ------------------------------------------------------------------------------------------------------------
-template <int KI, bool FUSEX, int MAXT>
+template <int KI, bool FUSEX, int MAXT, bool DIRECT>
 __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
 {
-    extern __shared__ float lds[];  // hbuf[KI*64] | pub[16] | xbuf[2][KI*64] (fused only)
+    extern __shared__ float lds[];  // hbuf[DIRECT ? 2 : 1][KI*64] | pub[16] | xbuf[2][KI*64] (fused only)
     constexpr int HP = KI * 64;
+    constexpr int HB = DIRECT ? 2 : 1;
     float* hbuf = lds;
-    float* pub = lds + HP;
+    float* pub = lds + HB * HP;
     float* xbuf = pub + 16;
     const int tid = threadIdx.x, nthreads = blockDim.x;
     const int lane = tid & 63, wave = tid >> 6, upb = nthreads >> 6;
@@ -97,7 +102,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
     const int row = lane >> 4;                       // gate handled by this lane after the reduction
     float bias_l = 0.f;                              // fused: bias of gate `row`
     if (FUSEX && active) bias_l = a.bias[4 * j + row];
-    for (int e = tid; e < HP; e += nthreads) hbuf[e] = 0.f;  // padding beyond H must stay finite
+    for (int e = tid; e < HB * HP; e += nthreads) hbuf[e] = 0.f;  // padding beyond H must stay finite
     float c = (active && a.c0) ? a.c0[j] : 0.f;
     __syncthreads();
     bool same_xcd = false;
@@ -166,16 +171,20 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
         } else if (active) {
             pl = a.P[(size_t)t * 4 * a.H + 4 * j + row];
         }
+        // DIRECT: the copy of h alternates between two buffers, so that the barrier behind the poll is the only one a step
+        // needs when every wave publishes for itself (below): a wave that runs ahead writes the other buffer, and cannot
+        // get two steps ahead without the slowest wave passing a barrier in between.
+        float* const hb = DIRECT ? hbuf + (s & 1) * HP : hbuf;
         if (s == 0)
-            stage_initial(a.h0, a.H, hbuf, tid, nthreads, a.round_h_bf16);
+            stage_initial(a.h0, a.H, hb, tid, nthreads, a.round_h_bf16);
         else
-            gather_tagged(a.xchg + (size_t)(s & 1) * a.H, a.H, a.tag_base + (unsigned)s, hbuf, tid, nthreads,
+            gather_tagged(a.xchg + (size_t)(s & 1) * a.H, a.H, a.tag_base + (unsigned)s, hb, tid, nthreads,
                           a.timeout_flag, a.spin_limit);
         __syncthreads();
         float acc0 = xa0, acc1 = xa1, acc2 = xa2, acc3 = xa3;
 #pragma unroll
         for (int i = 0; i < KI; ++i) {
-            const float hv = hbuf[lane + 64 * i];
+            const float hv = hb[lane + 64 * i];
             acc0 = fmaf(wh[0][i], hv, acc0);
             acc1 = fmaf(wh[1][i], hv, acc1);
             acc2 = fmaf(wh[2][i], hv, acc2);
@@ -183,13 +192,23 @@ __global__ __launch_bounds__(MAXT) void persist_b1_dense_kernel(PersistB1Args a)
         }
         const float pre = wave_sum4_rows(acc0, acc1, acc2, acc3) + pl;
         const float h = lstm_cell_rows(pre, lane, c);
-        if (lane == 0) pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
-        __syncthreads();
-        if (s + 1 < a.T && tid < upb) {
-            const int ju = bid * upb + tid;
-            if (ju < a.H)
-                exchange_store(a.xchg + (size_t)((s + 1) & 1) * a.H + ju, pack_slot(pub[tid], a.tag_base + (unsigned)s + 1u),
-                               same_xcd);
+        if constexpr (DIRECT) {
+            // A narrow layer on one XCD: every wave stores its own slot (through to the shared L2) -- no hand-over through
+            // LDS and no second barrier.  (On the whole device one coalesced store per workgroup is the faster form: 1.6-1.9
+            // against 2.5-3.3 us per step on 256 compute units.)  The slot overwritten held h_{s-2}; every workgroup
+            // finished reading that before any of its waves published h_{s-1}, all of which this workgroup has received.
+            if (lane == 0 && active && s + 1 < a.T)
+                exchange_store(a.xchg + (size_t)((s + 1) & 1) * a.H + j,
+                               pack_slot(a.round_h_bf16 ? round_bf16(h) : h, a.tag_base + (unsigned)s + 1u), same_xcd);
+        } else {
+            if (lane == 0) pub[wave] = a.round_h_bf16 ? round_bf16(h) : h;
+            __syncthreads();
+            if (s + 1 < a.T && tid < upb) {
+                const int ju = bid * upb + tid;
+                if (ju < a.H)
+                    exchange_store(a.xchg + (size_t)((s + 1) & 1) * a.H + ju, pack_slot(pub[tid], a.tag_base + (unsigned)s + 1u),
+                                   same_xcd);
+            }
         }
         // outputs after the publication: nothing on the way of h_t
         if (lane == 0 && active) {
@@ -665,8 +684,14 @@ static hipError_t launch_dense_ki(PersistB1Args a, int wpg_req, bool coop, hipSt
         // on one XCD every wave works on its own (no LDS, no barriers); x and h must both fit the KI register slices
         if (a.one_xcd && a.D <= 64 * KI) return coop_launch(persist_b1_dense_wave_kernel<KI>, blocks, wpg * 64, 0, args, coop, s);
     }
+    if constexpr (64 * (KI - 1) < kDenseDirectMaxH) {
+        if (a.one_xcd && a.H <= kDenseDirectMaxH) {
+            const size_t lds2 = ((size_t)KI * 64 * (FUSEX ? 4 : 2) + 16) * sizeof(float);
+            return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT, true>, blocks, wpg * 64, lds2, args, coop, s);
+        }
+    }
     const size_t lds = ((size_t)KI * 64 * (FUSEX ? 3 : 1) + 16) * sizeof(float);
-    return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT>, blocks, wpg * 64, lds, args, coop, s);
+    return coop_launch(persist_b1_dense_kernel<KI, FUSEX, MAXT, false>, blocks, wpg * 64, lds, args, coop, s);
 }
 
 hipError_t launch_persist_b1_dense(const PersistB1Args& a, int wpg, int cooperative, hipStream_t s)
