@@ -119,6 +119,9 @@ const char* lstm_last_error(const lstm_t* m);
  * with mask byte 1 (a kept zero value stays a stored entry), columns ascending within a row.
  * With dtype LSTM_BF16 the matrices are rounded to bf16 (nearest, ties to even); b stays fp32.
  * The library copies everything; the caller may free its arrays on return.  Synchronous.
+ * Device memory held per (layer, direction): the input-side matrix is always kept dense (4H * D_l values; in fp32
+ * models a second time in the operand order of the matrix instruction, for products with at most 64 input rows) and,
+ * when row-compressed, in the compressed forms as well; the recurrent matrix in the one form its kernels read.
  */
 int lstm_set_weights(lstm_t* m, int layer, int direction,
                      const float* Wx, const uint8_t* mask_x,
