@@ -1325,8 +1325,9 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 proj_q16_used = true;
             }
         }
-        if (!pair_done && Dn == 2 && !bf16 && mode[0] != 1 && mode[0] != 2 && mode[1] != 1 && mode[1] != 2) {
-            // fp32, both directions dense on the matrix cores: one launch (they read the same X)
+        if (!pair_done && Dn == 2 && !bf16 && M > 64 && mode[0] != 1 && mode[0] != 2 && mode[1] != 1 && mode[1] != 2) {
+            // fp32, both directions dense on the matrix cores: one launch (they read the same X).  (At most 64 input rows:
+            // one stream over the fragment-ordered weights per direction, below.)
             const LayerDir& w0 = m->ld[(size_t)l * Dn], & w1 = m->ld[(size_t)l * Dn + 1];
             auto dense_ok = [&](const LayerDir& w) {
                 return w.wx.dense && (!w.wx.compressed || M >= 256) && proj_mfma_supported(false, D, D);

@@ -658,6 +658,14 @@ def test_projection_density_switch(monkeypatch):
     assert "proj=q16" in desc
 
 
+def test_wide_dense_bidirectional_batch1():
+    """Both directions of a dense batch-1 layer too wide for the fused input side: a projection launch per direction
+    (the stream over the fragment-ordered weights) and the persistent recurrence."""
+    case = inputs.make_case(_wl(96, 1, True, 200, 1344, 6, 1, a=0.05), k=5, random_state=True)
+    desc, _ = check_case(case, DENSE, PAUTO)
+    assert desc.count("proj=dense,rec=persist_b1-dense") == 2, desc
+
+
 def test_few_input_rows_take_the_dense_projection_down_to_a_few_percent_kept():
     """With at most 64 input rows a separate projection launch of a row-compressed W_x streams the fragment-ordered
     dense copy on the matrix cores unless fewer than 4 % of the weights are kept; both choices meet the oracle."""
