@@ -40,6 +40,38 @@ def test_hlstm_odd_shapes_stepwise(shape, fmt):
     assert ("hlstm-stepwise-pair-csr" if fmt == CSR else "hlstm-stepwise-dense") in desc
 
 
+@pytest.mark.parametrize("which", ["hidden_layers_empty", "gate_outputs_empty", "input_side_empty", "rows_and_columns_gone", "all_kept_compressed"])
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, G, T, B
+    (2, False, 40, 130, 120, 6, 1),
+    (1, True, 33, 72, 80, 5, 3),
+])
+def test_hlstm_degenerate_masks(which, shape):
+    """Masks with nothing kept in one of the three matrices, with whole rows and columns gone, and a mask that keeps
+    everything stored in the compressed form; every format and plan against the oracle on the same masks."""
+    L, bidir, D, H, G, T, Bn = shape
+    case = inputs.make_case(_hw(81, L, bidir, D, H, G, T, Bn, keep=0.3), k=len(which) + G, random_state=True)
+    for p in case.weights.values():
+        if which == "hidden_layers_empty":
+            p["M1x"][:] = 0
+            p["M1h"][:] = 0
+        if which == "gate_outputs_empty":
+            p["M2"][:] = 0
+        if which == "input_side_empty":
+            p["M1x"][:] = 0
+        if which == "rows_and_columns_gone":
+            for M in (p["M1x"], p["M1h"], p["M2"]):
+                M[::3, :] = 0
+                M[:, 1::4] = 0
+            p["M2"][0:H, :] = 0            # the forget gate's whole output layer
+        if which == "all_kept_compressed":
+            for M in (p["M1x"], p["M1h"], p["M2"]):
+                M[:] = 1
+    for fmt in (DENSE, CSR):
+        for plan in (PAUTO, STEP):
+            check_case(case, fmt, plan)
+
+
 def test_hlstm_generic_compressed_kernels_for_long_rows():
     """Rows with more than six 64-entry slices fall back from the paired small-batch kernels to the generic ones."""
     case = inputs.make_case(_hw(80, 1, True, 30, 450, 420, 4, 3, a=0.1), k=9, random_state=True)

@@ -676,6 +676,37 @@ def test_few_input_rows_take_the_dense_projection_down_to_a_few_percent_kept():
             assert want in desc, desc
 
 
+@pytest.mark.parametrize("which", ["mask_h_empty", "mask_x_empty", "both_empty", "rows_and_columns_gone", "all_kept_compressed"])
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, T, B
+    (2, False, 40, 130, 6, 1),      # batch 1: two-layer wavefront / register-resident slices
+    (1, True, 33, 72, 5, 3),        # small batch: quarter-wave recurrence, projection over few rows
+    (2, True, 64, 96, 12, 8),       # enough input rows for the projection over the kept entries
+])
+def test_degenerate_masks(which, shape):
+    """What grow-and-prune can leave behind: a matrix with nothing kept, rows and columns pruned away entirely (Section 4,
+    row/column pruning), and a mask that keeps everything stored in the compressed form.  Every format and plan against
+    the oracle on the same masks."""
+    L, bidir, D, H, T, Bn = shape
+    case = inputs.make_case(_wl(97, L, bidir, D, H, T, Bn, keep=0.3), k=len(which) + H, random_state=True)
+    for p in case.weights.values():
+        if which in ("mask_h_empty", "both_empty"):
+            p["Mh"][:] = 0
+        if which in ("mask_x_empty", "both_empty"):
+            p["Mx"][:] = 0
+        if which == "rows_and_columns_gone":
+            for M in (p["Mx"], p["Mh"]):
+                M[::3, :] = 0               # every third row of the stacked matrix (all gates of some units, single gates of others)
+                M[:, 1::4] = 0
+            p["Mh"][0:H, :] = 0            # the whole forget gate of the recurrent matrix
+        if which == "all_kept_compressed":
+            p["Mx"][:] = 1
+            p["Mh"][:] = 1
+    for fmt in (DENSE, CSR):
+        for plan in (PAUTO, STEP):
+            check_case(case, fmt, plan)
+
+
 def test_yardsticks_run_and_are_plausible():
     """The achievable-peak yardsticks: matrix-instruction issue loops, the streaming copy and the data-free barrier."""
     import torch
