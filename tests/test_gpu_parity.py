@@ -707,6 +707,16 @@ def test_degenerate_masks(which, shape):
             check_case(case, fmt, plan)
 
 
+@pytest.mark.parametrize("Bn", [1, 4])
+@pytest.mark.parametrize("fmt", [DENSE, CSR])
+def test_wider_than_any_persistent_kernel(Bn, fmt):
+    """A layer wider than the on-chip-resident kernels take (their LDS copy of h ends at 64 KB, the dense batch-1 kernel
+    at 2048 units): the planner falls back to one launch per step and the result still meets the oracle."""
+    case = inputs.make_case(_wl(98, 1, False, 48, 6200 if fmt == CSR else 2304, 3, Bn, a=0.02, keep=0.02 if fmt == CSR else None), k=Bn, random_state=True)
+    desc, _ = check_case(case, fmt, PAUTO)
+    assert "stepwise" in desc, desc
+
+
 def test_yardsticks_run_and_are_plausible():
     """The achievable-peak yardsticks: matrix-instruction issue loops, the streaming copy and the data-free barrier."""
     import torch
