@@ -387,13 +387,15 @@ int lstm_bench_mfma(int dtype, int random_operands, int reps, int iters, double*
  * Device-wide barrier with no data: `workgroups` (<= compute units, <= 256) workgroups of `waves` waves; in each of
  * `steps` rounds every workgroup raises one tagged 8-byte slot and waits until it has seen the slots of all of them
  * (the protocol of the recurrence kernels' exchange, carrying nothing).  The yardstick "same grid, T barriers, no
- * work" for the step time of the persistent kernels.  *avg_us_per_step (HOST).  Allocates its own buffers and
+ * work" for the step time of the persistent kernels.  The poll of a round is tried unpaced and behind a short wait
+ * (6, 10, 12, 16 times 64 clocks after the workgroup's own store, which lets the first polling round find the other
+ * workgroups' stores visible); *avg_us_per_step (HOST) is the fastest of those.  Allocates its own buffers and
  * synchronises the stream; LSTM_ERR_TIMEOUT if a bounded wait expired.
  */
 int lstm_bench_barrier(int workgroups, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream);
 /* exchange: `steps` rounds of the hidden-state exchange with no arithmetic, for `hidden` units (one tagged slot each,
  * all of them polled by every workgroup) and workgroups of `waves` waves (0: the library's choice); returns the
- * average microseconds per round. */
+ * average microseconds per round for the fastest pacing of the poll (as lstm_bench_barrier). */
 int lstm_bench_exchange(int hidden, int waves, int steps, int iters, int cooperative, double* avg_us_per_step, void* stream);
 /*
  * The exchange inside groups of workgroups, with no arithmetic (yardstick of the kernels whose workgroups exchange only

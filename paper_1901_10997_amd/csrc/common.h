@@ -198,6 +198,7 @@ struct PersistHArgs {
     unsigned tag_base;          // step s publishes tag_base + s + 1 in xchg_h
     int* timeout_flag;
     unsigned spin_limit;
+    int poll_pace_u;            // pace_poll units between the publication of the hidden activations and their poll
 };
 bool persist_b1_hlstm_supported(int H, int G, int D, int slots_1x, int slots_1h, int slots_2);
 hipError_t launch_persist_b1_hlstm(const PersistHArgs& a, int cooperative, hipStream_t s);
@@ -356,6 +357,7 @@ struct PersistBatchedArgs {
     unsigned tag_base;
     int* timeout_flag;
     unsigned spin_limit;
+    int poll_pace;             // pace_poll units in front of the poll of h where the exchange is device-wide (set by the launcher)
 };
 // Input projection with W_x in the quarter-wave form, for many input rows (fp32): P[m][4H] = b + W_x . X[m]
 struct ProjQ16Dir {
@@ -447,11 +449,11 @@ int mfma_issue_blocks();
 hipError_t launch_mfma_issue(bool bf16, bool random, float* sink, long long* clocks, int reps, double* flops, hipStream_t s);
 size_t mfma_issue_sink_floats();
 hipError_t launch_barrier_only(unsigned long long* slots, unsigned tag_base, int groups, int waves, int steps,
-                               int* timeout_flag, unsigned spin_limit, int cooperative, hipStream_t s);
+                               int* timeout_flag, unsigned spin_limit, int poll_pace, int cooperative, hipStream_t s);
 hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 hipError_t launch_exchange_only(unsigned long long* xchg, unsigned tag_base, int H, int waves, int steps,
-                                int* timeout_flag, unsigned spin_limit, int cooperative, hipStream_t s);
+                                int* timeout_flag, unsigned spin_limit, int poll_pace, int cooperative, hipStream_t s);
 hipError_t launch_group_exchange(unsigned long long* slots, unsigned long long* ids, unsigned tag_base, int n, int members,
                                  int groups, int placed, int workgroup_stores, int steps, int* timeout_flag,
                                  unsigned spin_limit, int* verified, int cooperative, hipStream_t s);

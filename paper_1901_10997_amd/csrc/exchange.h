@@ -13,6 +13,17 @@ __device__ __forceinline__ u64 pack_slot(float v, unsigned tag)
     return ((u64)tag << 32) | (u64)__float_as_uint(v);
 }
 
+// Pacing of a poll that would otherwise follow the wave's own publication at once.  A device-scope store takes about
+// 0.3 us plus half a load round trip to become visible to the other XCDs; a poll round issued before that comes back
+// without the value and the next round costs a whole further round trip (about 1 us with a few thousand slots polled by
+// every workgroup).  Waiting `units` x 64 clocks first makes the first round the one that succeeds: the bare exchange of
+// 3000 slots among 250 workgroups takes 1.83 us per round unpaced and 1.43 us with 10-12 units.  Where a kernel has work
+// of its own between publication and poll (outputs, the next step's input products) that work is the pacing.
+__device__ __forceinline__ void pace_poll(int units)
+{
+    for (int i = 0; i < units; ++i) __builtin_amdgcn_s_sleep(1);
+}
+
 // One polled slot array: n slots tagged `want` go to dst[0..n).  n = 0 switches the array off.
 struct PollSrc {
     const u64* slots;

@@ -604,7 +604,7 @@ __global__ __launch_bounds__(MAXT) void persist_b1_sparse_kernel(SparseStackArgs
 
 // Exchange with no arithmetic: the yardstick for the per-step cost of the persistent kernels.
 __global__ __launch_bounds__(1024) void exchange_only_kernel(u64* xchg, unsigned tag_base, int H, int steps,
-                                                             int* timeout_flag, unsigned spin_limit)
+                                                             int* timeout_flag, unsigned spin_limit, int poll_pace)
 {
     extern __shared__ float lds[];  // hbuf[H] | pub[waves]
     float* pub = lds + H;
@@ -613,9 +613,11 @@ __global__ __launch_bounds__(1024) void exchange_only_kernel(u64* xchg, unsigned
     const int j = blockIdx.x * upb + wave;
     float acc = 0.f;
     for (int s = 0; s < steps; ++s) {
-        if (s > 0)
+        if (s > 0) {
+            pace_poll(poll_pace);
             gather_tagged(xchg + (size_t)(s & 1) * H, H, tag_base + (unsigned)s, lds, tid, nthreads, timeout_flag,
                           spin_limit);
+        }
         __syncthreads();
         if (s > 0) acc += lds[j < H ? j : 0];
         if (lane == 0) pub[wave] = acc * 1e-30f;
@@ -754,14 +756,14 @@ hipError_t launch_persist_b1_sparse(const SparseStackArgs& a, int nl, int wpg, i
 }
 
 hipError_t launch_exchange_only(u64* xchg, unsigned tag_base, int H, int waves, int steps, int* timeout_flag,
-                                unsigned spin_limit, int cooperative, hipStream_t s)
+                                unsigned spin_limit, int poll_pace, int cooperative, hipStream_t s)
 {
     if (H <= 0 || steps <= 0) return hipSuccess;
     const int wpg = pick_waves(H, waves, 16, 1);
     const int blocks = (H + wpg - 1) / wpg;
     const size_t lds = ((size_t)H + wpg) * sizeof(float);
     if (lds > 64 * 1024) return hipErrorInvalidValue;
-    void* args[] = {(void*)&xchg, (void*)&tag_base, (void*)&H, (void*)&steps, (void*)&timeout_flag, (void*)&spin_limit};
+    void* args[] = {(void*)&xchg, (void*)&tag_base, (void*)&H, (void*)&steps, (void*)&timeout_flag, (void*)&spin_limit, (void*)&poll_pace};
     return coop_launch(exchange_only_kernel, blocks, wpg * 64, lds, args, cooperative != 0, s);
 }
 

@@ -153,6 +153,7 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
                 hbuf[k * BW + b] = v;
             }
         } else {
+            pace_poll(a.poll_pace);   // device-wide exchange only (exchange.h); inside one XCD any wait costs what it lasts
             if (BW * H > 4 * nthreads && S * UPW <= 84)
                 gather_tagged_cols<8, BW>(xchg + (size_t)(s & 1) * parity_stride, BW * H, bw, a.tag_base + (unsigned)s, hbuf, tid,
                                           nthreads, a.timeout_flag, a.spin_limit);
@@ -326,6 +327,7 @@ hipError_t launch_persist_batched_q16(PersistBatchedArgs& a, int ndir, int slots
     a.ndir = ndir;
     a.xcd_local = (persist_batched_q16_xcd_capable(slots, upw) && ug <= 64 && per_xcd * ug <= device_num_cus() / 8) ? 1 : 0;
     const int blocks = a.xcd_local ? 8 * per_xcd * ug : ug * bg * ndir;
+    if (a.xcd_local) a.poll_pace = 0;
     switch (slots) {
         case 2: return launch_q16_s<2>(a, upw, bw, blocks, cooperative != 0, s);
         case 4: return launch_q16_s<4>(a, upw, bw, blocks, cooperative != 0, s);

@@ -200,6 +200,9 @@ __global__ __launch_bounds__(MAXT) void persist_b1_hlstm_kernel(PersistHArgs a)
                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // ---- stage 2: gate outputs from u_t, cell update
+        // (nothing of this wave's own stands between its publication and this poll, so the poll is paced: exchange.h.  The
+        // poll of h at the top of the step comes after the outputs and the next step's input products and needs none.)
+        pace_poll(a.poll_pace_u);
         gather_stamped_pairs<4>(reinterpret_cast<const u64*>(a.xchg_u), 2 * G, stamp, reinterpret_cast<u64*>(ubuf), tid,
                                 nthreads, a.timeout_flag, a.spin_limit);
         __syncthreads();

@@ -117,13 +117,16 @@ size_t mfma_issue_sink_floats() { return (size_t)mfma_issue_blocks() * 256; }
 // workgroups: the same tagged-slot protocol as the recurrence kernels, carrying nothing.  One slot per workgroup, two
 // arrays alternating by round parity.
 __global__ __launch_bounds__(1024) void barrier_only_kernel(u64* slots, unsigned tag_base, int groups, int steps,
-                                                            int* timeout_flag, unsigned spin_limit)
+                                                            int* timeout_flag, unsigned spin_limit, int poll_pace)
 {
     __shared__ float seen[256];
     const int tid = threadIdx.x, nthreads = blockDim.x;
     for (int s = 0; s < steps; ++s) {
-        if (s > 0) gather_tagged(slots + (size_t)(s & 1) * groups, groups, tag_base + (unsigned)s, seen, tid, nthreads,
-                                 timeout_flag, spin_limit);
+        if (s > 0) {
+            pace_poll(poll_pace);
+            gather_tagged(slots + (size_t)(s & 1) * groups, groups, tag_base + (unsigned)s, seen, tid, nthreads,
+                          timeout_flag, spin_limit);
+        }
         __syncthreads();
         if (s + 1 < steps && tid == 0)
             __hip_atomic_store(slots + (size_t)((s + 1) & 1) * groups + blockIdx.x,
@@ -133,11 +136,11 @@ __global__ __launch_bounds__(1024) void barrier_only_kernel(u64* slots, unsigned
 }
 
 hipError_t launch_barrier_only(u64* slots, unsigned tag_base, int groups, int waves, int steps, int* timeout_flag,
-                               unsigned spin_limit, int cooperative, hipStream_t s)
+                               unsigned spin_limit, int poll_pace, int cooperative, hipStream_t s)
 {
     if (groups < 1 || groups > 256 || groups > device_num_cus() || waves < 1 || waves > 16 || steps < 2)
         return hipErrorInvalidValue;
-    void* args[] = {(void*)&slots, (void*)&tag_base, (void*)&groups, (void*)&steps, (void*)&timeout_flag, (void*)&spin_limit};
+    void* args[] = {(void*)&slots, (void*)&tag_base, (void*)&groups, (void*)&steps, (void*)&timeout_flag, (void*)&spin_limit, (void*)&poll_pace};
     if (cooperative) return hipLaunchCooperativeKernel((const void*)barrier_only_kernel, dim3(groups), dim3(waves * 64), args, 0, s);
     return hipLaunchKernel((const void*)barrier_only_kernel, dim3(groups), dim3(waves * 64), args, 0, s);
 }

@@ -72,6 +72,31 @@ def test_hlstm_degenerate_masks(which, shape):
             check_case(case, fmt, plan)
 
 
+def test_poll_pacing_changes_no_bit(monkeypatch):
+    """The wait in front of a paced poll (LSTM355_POLL_PACE at lstm_create: units of 64 clocks; default: each kernel's
+    measured optimum) only moves the first polling round in time: outputs are bit-identical whatever its length, for the
+    batch-1 H-LSTM kernel and for the small-batch recurrence with a device-wide exchange."""
+    cases = [
+        (inputs.make_case(_hw(82, 1, False, 40, 300, 280, 12, 1, keep=0.2), k=1, random_state=True), "persist_b1-hlstm"),
+        (inputs.make_case(inputs.Workload(82, "wide_b12", 1, False, 64, 1100, 9, 12, "f32", 0.05, 0.1, "uniform"), k=2, random_state=True),
+         "persist_batched"),
+    ]
+    for case, want in cases:
+        outs = []
+        for pace in (None, "0", "40"):
+            if pace is not None:
+                monkeypatch.setenv("LSTM355_POLL_PACE", pace)
+            gpu, desc = run_gpu(case, CSR, PAUTO)
+            monkeypatch.delenv("LSTM355_POLL_PACE", raising=False)
+            assert want in desc, desc
+            outs.append(gpu)
+        for other in outs[1:]:
+            for a, b in zip(outs[0], other):
+                assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    check_case(cases[0][0], CSR, PAUTO)
+    check_case(cases[1][0], CSR, PAUTO)
+
+
 def test_hlstm_generic_compressed_kernels_for_long_rows():
     """Rows with more than six 64-entry slices fall back from the paired small-batch kernels to the generic ones."""
     case = inputs.make_case(_hw(80, 1, True, 30, 450, 420, 4, 3, a=0.1), k=9, random_state=True)
