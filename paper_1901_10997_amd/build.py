@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "liblstm355.so")
 
-SOURCES = ["lstm355.cpp", "proj_kernels.hip", "proj_mfma.hip", "proj_sparse.hip", "step_kernels.hip", "step_mfma.hip", "persist_b1.hip", "persist_batched.hip", "persist_mfma.hip", "hlstm_kernels.hip", "persist_h.hip", "persist_batched_h.hip", "prune_kernels.hip", "compact_kernels.hip", "exchange_bench.hip", "yardstick_kernels.hip", "util_kernels.hip"]
+SOURCES = ["lstm355.cpp", "proj_kernels.hip", "proj_mfma.hip", "proj_sparse.hip", "step_kernels.hip", "step_mfma.hip", "persist_b1.hip", "persist_batched.hip", "persist_mfma.hip", "persist_dense_f32.hip", "hlstm_kernels.hip", "persist_h.hip", "persist_batched_h.hip", "prune_kernels.hip", "compact_kernels.hip", "exchange_bench.hip", "yardstick_kernels.hip", "util_kernels.hip"]
 HEADERS = ["common.h", "device_math.h", "exchange.h", os.path.join("..", "..", "include", "lstm355.h")]
 
 # packed fp32 instructions are switched off for all device code

@@ -245,6 +245,32 @@ struct PersistMfmaArgs {
     int T, B, H, reverse;
 };
 bool persist_mfma_supported(int B, int H);
+// fp32 dense recurrence at small and medium batch with the time loop on the device (all directions of a layer per launch)
+struct PersistDenseDir {
+    const float* P;            // [T*B][4H]
+    const float* Wh;           // [4H][H] fp32, packed rows
+    const float* c0;           // [B][H] or nullptr
+    float* y;                  // h_t -> y[(t*B + b)*y_ld + j]
+    int y_ld;
+    float* hT;
+    float* cT;
+    int reverse;
+    int has_h0;                // exchange buffer 0 holds h0 (set by the launcher)
+};
+struct PersistDenseArgs {
+    PersistDenseDir d[2];
+    float* hx;                 // per direction two exchange buffers of ceil(H/16) * Bp * 16 words (Bp: B rounded up to the
+                               // row blocks), all zero at launch
+    int* timeout_flag;
+    unsigned spin_limit;
+    int T, B, H, ndir;
+    int gm, gn;                // row blocks, workgroups per row block (set by the launcher)
+    int poll_pace;             // pace_poll units in front of a step's first read of h (exchange.h)
+};
+bool persist_dense_f32_supported(int B, int H, int ndir);
+size_t persist_dense_f32_exchange_floats(int B, int H, int ndir);
+// h0[d]: fp32 [B][H] of direction d or nullptr
+hipError_t launch_persist_dense_f32(PersistDenseArgs& a, const float* const* h0, bool cooperative, hipStream_t s);
 size_t persist_mfma_exchange_bytes(int B, int H);
 size_t persist_mfma_flag_count(int B, int H);   // 32-bit words of flag storage, XCD id slots included
 size_t persist_mfma_ids_offset(int B, int H);   // word offset of the XCD id slots inside it

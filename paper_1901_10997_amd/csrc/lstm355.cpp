@@ -114,6 +114,10 @@ static float host_bf16_to_f32(uint16_t b)
 // or an exchange inside one XCD, already puts the first poll round where it succeeds).
 constexpr int kPollPaceHlstmB1 = 10;
 constexpr int kPollPaceBatchedDeviceWide = 8;
+// dense fp32 recurrence at small and medium batch, first read of h in a step (its own stores just in front of it): layers of
+// 256 to 1024 units at batch 4 to 64 are fastest between 16 and 24 (H = 800, both directions, batch 16: 1665 us per layer
+// unpaced, 1567 at 16, 1453 at 24, 1503 at 32; H = 256, batch 16: 2.48 us per step unpaced, 2.31 at 16, 2.54 at 24)
+constexpr int kPollPaceDenseNarrow = 16, kPollPaceDenseWide = 24;
 // the yardsticks try these and report the fastest
 static const int kYardstickPaces[] = {0, 6, 10, 12, 16};
 
@@ -818,6 +822,15 @@ static Workspace carve(const lstm_t* m, int T, int B)
             w.mflag_off = off;
             off += align256(flags * sizeof(unsigned));
         }
+    } else if (m->G == 0) {
+        // fp32 dense persistent recurrence at small and medium batch: the same two regions (whether a layer's recurrent
+        // matrix is held dense is not known before its weights are set, so every width the kernel takes is provided for)
+        size_t xfloats = 0;
+        for (int l = 0; l < m->L; ++l)
+            if (persist_dense_f32_supported(B, m->hid(l), m->Dn))
+                xfloats = std::max(xfloats, persist_dense_f32_exchange_floats(B, m->hid(l), m->Dn));
+        off += align256(xfloats * sizeof(float));
+        w.mflag_off = off;
     }
     // H-LSTM: hidden-layer activations of the current step, [B][4G] per direction (stepwise paths); the small-batch
     // persistent kernel uses both directions' storage as one array of [k][columns of a batch group] blocks
@@ -1458,6 +1471,43 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
             }
             prev_has_bf16 = true;
             continue;
+        }
+        // ---- recurrence, fp32 dense at small and medium batch, time loop on the device (all directions in one launch):
+        // W_h as matrix-instruction operand fragments in registers, h_t through flagged exchange buffers
+        {
+            bool dense_f32 = !bf16 && B >= 2 && m->plan != LSTM_PLAN_STEPWISE;
+            for (int d = 0; d < Dn; ++d) {
+                const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                dense_f32 = dense_f32 && mode[d] == 0 && !w.wh.compressed && w.wh.dense;
+            }
+            if (dense_f32 && persist_dense_f32_supported(B, H, Dn)) {
+                // the exchange buffers start every launch with all stamps clear
+                HIP_TRY(m, launch_fill_f32((float*)hx, persist_dense_f32_exchange_floats(B, H, Dn), 0.0f, s));
+                PersistDenseArgs a{};
+                const float* h0d[2] = {nullptr, nullptr};
+                for (int d = 0; d < Dn; ++d) {
+                    const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                    const size_t n = (size_t)l * Dn + d;
+                    a.d[d].P = P[d];
+                    a.d[d].Wh = (const float*)w.wh.dense;
+                    a.d[d].c0 = c0 ? c0 + m->soff(n) * B : nullptr;
+                    a.d[d].y = Yout + (size_t)d * H; a.d[d].y_ld = y_ld;
+                    a.d[d].hT = hT ? hT + m->soff(n) * B : nullptr;
+                    a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
+                    a.d[d].reverse = d;
+                    h0d[d] = h0 ? h0 + m->soff(n) * B : nullptr;
+                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist-dense-f32;", l, d,
+                                  proj_runs_dense(w.wx, M, D, bf16) ? "dense" : "csr");
+                    m->last_plan += tag;
+                }
+                a.hx = (float*)hx;
+                a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                a.T = T; a.B = B; a.H = H; a.ndir = Dn;
+                a.poll_pace = m->poll_pace >= 0 ? m->poll_pace : (H <= 512 ? kPollPaceDenseNarrow : kPollPaceDenseWide);
+                ProfSpan span(m, s, 1);
+                HIP_TRY(m, launch_persist_dense_f32(a, h0d, m->launch_mode() != 0, s));
+                continue;
+            }
         }
         // ---- recurrence, small-batch row-compressed, time loop on the device (all directions in one launch): W_h in
         // the quarter-wave form (rows of at most 256 kept entries)

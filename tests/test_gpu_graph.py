@@ -20,7 +20,8 @@ CASES = [
     (2, False, 40, 96, 12, 1, "f32", 0.2, 0, "wavefront"),          # batch 1, two layers per launch, handle-owned slots
     (2, True, 24, 80, 9, 1, "f32", None, 0, "persist_b1-dense"),    # batch 1, dense, both directions
     (1, True, 24, 96, 15, 4, "f32", 0.2, 0, "persist_batched"),     # small batch, workspace-owned slots
-    (1, False, 64, 128, 6, 64, "f32", None, 0, "stepwise"),         # one launch per step: the launch-bound loop
+    (1, True, 64, 128, 6, 64, "f32", None, 0, "persist-dense-f32"), # dense fp32 at medium batch, flags cleared inside the graph
+    (1, False, 24, 2304, 3, 2, "f32", None, 0, "stepwise"),         # wider than any resident kernel: one launch per step
     (1, False, 32, 64, 10, 1, "f32", 0.2, 48, "persist_b1-hlstm"),  # H-LSTM, batch 1
     (1, True, 32, 64, 8, 4, "f32", 0.2, 48, "persist_batched-hlstm"),               # H-LSTM, small batch
     (1, False, 256, 256, 6, 64, "bf16", None, 0, ""),               # bf16, large batch

@@ -75,18 +75,20 @@ def test_hlstm_degenerate_masks(which, shape):
 def test_poll_pacing_changes_no_bit(monkeypatch):
     """The wait in front of a paced poll (LSTM355_POLL_PACE at lstm_create: units of 64 clocks; default: each kernel's
     measured optimum) only moves the first polling round in time: outputs are bit-identical whatever its length, for the
-    batch-1 H-LSTM kernel and for the small-batch recurrence with a device-wide exchange."""
+    batch-1 H-LSTM kernel, for the small-batch recurrence with a device-wide exchange and for the dense fp32 recurrence."""
     cases = [
         (inputs.make_case(_hw(82, 1, False, 40, 300, 280, 12, 1, keep=0.2), k=1, random_state=True), "persist_b1-hlstm"),
         (inputs.make_case(inputs.Workload(82, "wide_b12", 1, False, 64, 1100, 9, 12, "f32", 0.05, 0.1, "uniform"), k=2, random_state=True),
          "persist_batched"),
+        (inputs.make_case(inputs.Workload(82, "dense_b8", 1, True, 40, 100, 9, 8, "f32", 0.1, None, "uniform"), k=3, random_state=True),
+         "persist-dense-f32"),
     ]
     for case, want in cases:
         outs = []
         for pace in (None, "0", "40"):
             if pace is not None:
                 monkeypatch.setenv("LSTM355_POLL_PACE", pace)
-            gpu, desc = run_gpu(case, CSR, PAUTO)
+            gpu, desc = run_gpu(case, CSR if case.w.keep is not None else DENSE, PAUTO)
             monkeypatch.delenv("LSTM355_POLL_PACE", raising=False)
             assert want in desc, desc
             outs.append(gpu)
@@ -95,6 +97,7 @@ def test_poll_pacing_changes_no_bit(monkeypatch):
                 assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
     check_case(cases[0][0], CSR, PAUTO)
     check_case(cases[1][0], CSR, PAUTO)
+    check_case(cases[2][0], DENSE, PAUTO)
 
 
 def test_hlstm_generic_compressed_kernels_for_long_rows():

@@ -717,6 +717,28 @@ def test_wider_than_any_persistent_kernel(Bn, fmt):
     assert "stepwise" in desc, desc
 
 
+@pytest.mark.parametrize("shape", [
+    # L, bidir, D, H, T, B -- dense fp32 layers at small and medium batch: W_h as matrix-instruction fragments in registers
+    (1, False, 40, 72, 6, 3),        # one 16-row block, nine workgroups, the last with one unit
+    (2, True, 33, 100, 5, 16),
+    (1, True, 64, 200, 7, 20),       # two 16-row blocks, ragged
+    (1, False, 48, 330, 4, 40),      # three
+    (1, False, 32, 520, 3, 64),      # four do not fit the registers at this width: two row blocks of two
+    (1, False, 24, 1100, 3, 5),      # twelve k-blocks per wave
+    (1, False, 16, 1530, 2, 2),      # the widest layer the kernel takes (k-blocks of a wave in registers)
+    (3, True, 20, 50, 9, 130),       # nine row blocks
+    (1, False, 8, 3, 4, 2),          # a single unit-less workgroup edge: three units, most waves without a k-block
+])
+def test_dense_small_batch_persistent(shape):
+    L, bidir, D, H, T, Bn = shape
+    for rs in (False, True):
+        case = inputs.make_case(_wl(99, L, bidir, D, H, T, Bn, a=min(0.3, 1.5 / np.sqrt(max(H, D)))), k=H + Bn, random_state=rs)
+        for coop in (True, False):
+            desc, _ = check_case(case, DENSE, PAUTO, cooperative=coop)
+            assert "rec=persist-dense-f32" in desc, desc
+    check_case(case, DENSE, STEP)
+
+
 def test_yardsticks_run_and_are_plausible():
     """The achievable-peak yardsticks: matrix-instruction issue loops, the streaming copy and the data-free barrier."""
     import torch
