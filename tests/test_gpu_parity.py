@@ -721,13 +721,15 @@ def test_wider_than_any_persistent_kernel(Bn, fmt):
     # L, bidir, D, H, T, B -- dense fp32 layers at small and medium batch: W_h as matrix-instruction fragments in registers
     (1, False, 40, 72, 6, 3),        # one 16-row block, nine workgroups, the last with one unit
     (2, True, 33, 100, 5, 16),
-    (1, True, 64, 200, 7, 20),       # two 16-row blocks, ragged
-    (1, False, 48, 330, 4, 40),      # three
-    (1, False, 32, 520, 3, 64),      # four do not fit the registers at this width: two row blocks of two
+    (1, True, 64, 200, 7, 20),       # two row blocks, the second ragged
+    (1, False, 48, 330, 4, 40),      # three row blocks
+    (1, False, 32, 520, 3, 64),      # four row blocks of 16 would exceed the grid: two of 32
     (1, False, 24, 1100, 3, 5),      # twelve k-blocks per wave
     (1, False, 16, 1530, 2, 2),      # the widest layer the kernel takes (k-blocks of a wave in registers)
     (3, True, 20, 50, 9, 130),       # nine row blocks
-    (1, False, 8, 3, 4, 2),          # a single unit-less workgroup edge: three units, most waves without a k-block
+    (1, False, 8, 3, 4, 2),          # three units: one workgroup, most of its waves without a k-block
+    (1, True, 24, 500, 3, 96),       # the grid only fits with three 16-row blocks per workgroup
+    (1, True, 24, 500, 2, 128),      # ... with four
 ])
 def test_dense_small_batch_persistent(shape):
     L, bidir, D, H, T, Bn = shape
