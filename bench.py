@@ -44,7 +44,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2_b1", choices=["c1", "c2_b1", "c2_b20", "c4", "c5", "h1", "h2"])
+    ap.add_argument("--workload", default="c2_b1", choices=["c1", "c2_b1", "c2_b20", "c4", "c4_dense", "c5", "h1", "h2"],
+                    help="c4_dense: the c4 stack with its weights held dense (the unpruned model; --format dense implied)")
     ap.add_argument("--format", default="auto", choices=["auto", "dense", "csr"])
     ap.add_argument("--plan", default="auto", choices=["auto", "stepwise", "persistent"])
     ap.add_argument("--waves", type=int, default=0)
@@ -98,8 +99,10 @@ def main():
         print(json.dumps({"metric": "device_copy_bandwidth", "value": 2 * n / us / 1e3, "unit": "GB/s",
                           "bytes_read": n, "bytes_written": n, "avg_us": us}))
         return
-    wl = {"c1": inputs.c1(), "c2_b1": inputs.c2(1), "c2_b20": inputs.c2(20), "c4": inputs.c4(), "c5": inputs.c5(),
-          "h1": inputs.h1(), "h2": inputs.h2()}[args.workload]
+    if args.workload == "c4_dense":
+        args.format = "dense"
+    wl = {"c1": inputs.c1(), "c2_b1": inputs.c2(1), "c2_b20": inputs.c2(20), "c4": inputs.c4(), "c4_dense": inputs.c4(),
+          "c5": inputs.c5(), "h1": inputs.h1(), "h2": inputs.h2()}[args.workload]
     hl = wl.gate_hidden > 0     # H-LSTM cell: one hidden layer of that width inside each gate
     case = inputs.make_case(wl, 0)
     dtype = B.LSTM_BF16 if wl.dtype == "bf16" else B.LSTM_F32
@@ -478,11 +481,19 @@ def main():
         med, p10, p90, _ = B.lstm_latency_sweep_model(Hs, Ds, layers=5, bidirectional=True, keep=0.15, T=100, B=16,
                                                       warmup=2, iters=10, stream=stream)
         f2, red2 = B.lstm_find_lhp(Hs, med, 0.02)
+        # the same stack with dense weights (keep = 0 means no masks): the unpruned model, and what a row/column-pruned
+        # model is once it has been compacted to its smaller dimensions
+        dmed, dp10, dp90, _ = B.lstm_latency_sweep_model(Hs, Ds, layers=5, bidirectional=True, keep=0.0, T=100, B=16,
+                                                         warmup=2, iters=10, stream=stream)
+        df2, dred2 = B.lstm_find_lhp(Hs, dmed, 0.02)
         with open(os.path.join(args.out, "latency_sweep_speech.json"), "w") as fh:
             json.dump({"launch": args.launch, "layers": 5, "bidirectional": True, "keep": 0.15, "T": 100, "batch": 16,
                        "H": Hs, "median_us": list(med), "p10_us": list(p10), "p90_us": list(p90),
-                       "is_lhp_eps2pct": [int(v) for v in f2], "redundancy_pct_eps2pct": red2}, fh)
-        out["sweep_speech"] = {"points": len(Hs), "redundancy_pct_eps2pct": red2, "min_us": float(min(med)), "max_us": float(max(med))}
+                       "is_lhp_eps2pct": [int(v) for v in f2], "redundancy_pct_eps2pct": red2,
+                       "dense": {"median_us": list(dmed), "p10_us": list(dp10), "p90_us": list(dp90),
+                                 "is_lhp_eps2pct": [int(v) for v in df2], "redundancy_pct_eps2pct": dred2}}, fh)
+        out["sweep_speech"] = {"points": len(Hs), "redundancy_pct_eps2pct": red2, "min_us": float(min(med)), "max_us": float(max(med)),
+                               "dense_redundancy_pct_eps2pct": dred2, "dense_min_us": float(min(dmed)), "dense_max_us": float(max(dmed))}
     m.close()
     print(json.dumps(out))
 
