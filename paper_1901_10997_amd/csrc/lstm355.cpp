@@ -1009,7 +1009,12 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 nz = std::max(nz, std::max(w.wh.q16_slots, w.w2.q16_slots));
                 any_extra = any_extra || w.wh.q16_ovf_ptr || w.w2.q16_ovf_ptr;
             }
-            pb_ok = pb_ok && persist_batched_h_plan(B, H, G, nz, Dn, &upw, &bw, &ug, &bg);
+            // both directions in one grid where they fit one workgroup per compute unit, else one launch per direction
+            int passes = 1;
+            if (pb_ok && !persist_batched_h_plan(B, H, G, nz, Dn, &upw, &bw, &ug, &bg)) {
+                pb_ok = Dn == 2 && persist_batched_h_plan(B, H, G, nz, 1, &upw, &bw, &ug, &bg);
+                passes = 2;
+            }
             const bool trimmed = any_extra;
             if (m->plan == LSTM_PLAN_PERSISTENT && B >= 2 && !pb_ok)
                 return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
@@ -1027,11 +1032,13 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                     hslots_H = H; hslots_G = G;
                     htag = 0;
                 }
+                for (int pass = 0; pass < passes; ++pass) {
+                const int d_lo = passes == 2 ? pass : 0, nd = passes == 2 ? 1 : Dn;
                 PersistBatchedHArgs a{};
-                for (int d = 0; d < Dn; ++d) {
+                for (int d = d_lo; d < d_lo + nd; ++d) {
                     const LayerDir& w = m->ld[(size_t)l * Dn + d];
                     const size_t n = (size_t)l * Dn + d;
-                    PersistBatchedHDir& q = a.d[d];
+                    PersistBatchedHDir& q = a.d[d - d_lo];
                     q.P1 = P[d];
                     q.q16_val_1h = w.wh.q16_val; q.q16_col_1h = w.wh.q16_col; q.slots_1h = w.wh.q16_slots;
                     q.ovf_ptr_1h = w.wh.q16_ovf_ptr; q.ovf_ent_1h = w.wh.q16_ovf_ent; q.ovf_val_1h = w.wh.q16_ovf_val;
@@ -1053,7 +1060,8 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 a.tag_base = htag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 htag += (unsigned)T + 1u;
                 ProfSpan span(m, s, 1);
-                HIP_TRY(m, launch_persist_batched_h(a, Dn, nz, m->launch_mode(), s));
+                HIP_TRY(m, launch_persist_batched_h(a, nd, nz, m->launch_mode(), s));
+                }
                 continue;
             }
         }
@@ -1519,7 +1527,12 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 pb_ok = p.compressed && p.q16_slots > 0;
                 q16 = std::max(q16, p.q16_slots);
             }
-            pb_ok = pb_ok && persist_batched_q16_plan(B, H, q16, Dn, &upw, &bw, &ug, &bg);
+            // both directions in one grid where they fit one workgroup per compute unit, else one launch per direction
+            int passes = 1;
+            if (pb_ok && !persist_batched_q16_plan(B, H, q16, Dn, &upw, &bw, &ug, &bg)) {
+                pb_ok = Dn == 2 && persist_batched_q16_plan(B, H, q16, 1, &upw, &bw, &ug, &bg);
+                passes = 2;
+            }
             if (pb_ok) {
                 if (!bslots_clean || bslots_H != H) {   // another width is another layout: start from zero again
                     HIP_TRY(m, launch_fill_u64(bslots, align256(ws.slot_bytes) / sizeof(unsigned long long), 0ull, s));
@@ -1527,19 +1540,22 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     bslots_H = H;
                     btag = 0;
                 }
+                for (int pass = 0; pass < passes; ++pass) {
+                const int d_lo = passes == 2 ? pass : 0, nd = passes == 2 ? 1 : Dn;
                 PersistBatchedArgs a{};
-                for (int d = 0; d < Dn; ++d) {
+                for (int d = d_lo; d < d_lo + nd; ++d) {
                     const LayerDir& w = m->ld[(size_t)l * Dn + d];
                     const size_t n = (size_t)l * Dn + d;
-                    a.d[d].P = P[d];
-                    a.d[d].q16_val = w.wh.q16_val; a.d[d].q16_col = w.wh.q16_col; a.d[d].q16_slots = w.wh.q16_slots;
-                    a.d[d].q16_ovf_ptr = w.wh.q16_ovf_ptr; a.d[d].q16_ovf_ent = w.wh.q16_ovf_ent; a.d[d].q16_ovf_val = w.wh.q16_ovf_val;
-                    a.d[d].h0 = h0 ? h0 + m->soff(n) * B : nullptr;
-                    a.d[d].c0 = c0 ? c0 + m->soff(n) * B : nullptr;
-                    a.d[d].y = Yout + (size_t)d * H; a.d[d].y_ld = y_ld;
-                    a.d[d].hT = hT ? hT + m->soff(n) * B : nullptr;
-                    a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
-                    a.d[d].reverse = d;
+                    PersistBatchedDir& q = a.d[d - d_lo];
+                    q.P = P[d];
+                    q.q16_val = w.wh.q16_val; q.q16_col = w.wh.q16_col; q.q16_slots = w.wh.q16_slots;
+                    q.q16_ovf_ptr = w.wh.q16_ovf_ptr; q.q16_ovf_ent = w.wh.q16_ovf_ent; q.q16_ovf_val = w.wh.q16_ovf_val;
+                    q.h0 = h0 ? h0 + m->soff(n) * B : nullptr;
+                    q.c0 = c0 ? c0 + m->soff(n) * B : nullptr;
+                    q.y = Yout + (size_t)d * H; q.y_ld = y_ld;
+                    q.hT = hT ? hT + m->soff(n) * B : nullptr;
+                    q.cT = cT ? cT + m->soff(n) * B : nullptr;
+                    q.reverse = d;
                     std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16%s(s%d,u%d,b%d);", l, d,
                                   proj_q16_used ? "q16" : proj_runs_dense(w.wx, M, D, bf16) ? "dense" : "csr",
                                   w.wh.q16_ovf_ptr ? "+ovf" : "", q16, upw, bw);
@@ -1550,7 +1566,8 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 a.poll_pace = m->poll_pace >= 0 ? m->poll_pace : kPollPaceBatchedDeviceWide;   // (the launcher clears it where the exchange stays inside XCDs)
                 btag += (unsigned)T;
                 ProfSpan span(m, s, 1);
-                HIP_TRY(m, launch_persist_batched_q16(a, Dn, q16, m->launch_mode(), s));
+                HIP_TRY(m, launch_persist_batched_q16(a, nd, q16, m->launch_mode(), s));
+                }
                 continue;
             }
         }

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
     unsigned* flags = a.flags + grp * 64;                 // one per unit group
 
     // kept weights of this wave's units in the quarter-wave form (slot s of a unit is one 64-lane gather that serves
-    // all four gate rows, gate q on lanes 16q..16q+15); the column is kept as the 16-bit LDS byte offset of its BW
+    // all four gate rows, gate q on lanes 16q..16q+15); the column is kept as the 16-bit LDS offset, in floats, of its BW
     // values (W2's columns are stored with their gate's offset q * G into the hidden-layer vector)
     float w1[UPW][S], w2[UPW][S];
     unsigned o1[UPW][S / 2], o2[UPW][S / 2];
@@ -110,8 +110,8 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
                 const bool l1 = (u0 + u < G) && i < s1, l2 = (u0 + u < H) && i < s2;
                 w1[u][i] = l1 ? t1[i] : 0.f;
                 w2[u][i] = l2 ? t2[i] : 0.f;
-                o1[u][i >> 1] |= ((l1 ? k1[i] : 0u) * (BW * 4u)) << (16 * (i & 1));   // h[k][0]
-                o2[u][i >> 1] |= ((l2 ? k2[i] : 0u) * (BW * 4u)) << (16 * (i & 1));   // u[q*G + k][0]
+                o1[u][i >> 1] |= ((l1 ? k1[i] : 0u) * (unsigned)BW) << (16 * (i & 1));   // h[k][0]
+                o2[u][i >> 1] |= ((l2 ? k2[i] : 0u) * (unsigned)BW) << (16 * (i & 1));   // u[q*G + k][0]
             }
         }
     }
@@ -168,8 +168,8 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
         constexpr int PD = NS < PDMAX ? NS : PDMAX;
         auto read_slot = [&](int n) {
             const int u = n / S, i = n % S;
-            const unsigned off = (wo[u][i >> 1] >> (16 * (i & 1))) & 0xFFFFu;
-            return *reinterpret_cast<const VT*>(reinterpret_cast<const char*>(vec) + off);
+            const unsigned off = (wo[u][i >> 1] >> (16 * (i & 1))) & 0xFFFFu;   // in floats: shift and add are one instruction
+            return *reinterpret_cast<const VT*>(vec + off);
         };
         VT ring[PD];
 #pragma unroll
@@ -339,7 +339,7 @@ bool persist_batched_h_plan(int B, int H, int G, int slots, int ndir, int* upw_o
     const int units = std::max(H, G);
     int best = -1;
     for (int bw = 2; bw <= 4; bw *= 2) {
-        if ((size_t)H * bw * 4 > 65536 || (size_t)4 * G * bw * 4 > 65536) continue;
+        if ((size_t)H * bw > 65535 || (size_t)4 * G * bw > 65535) continue;      // 16-bit offsets, in floats
         if (lds_bytes(H, G, bw) > (size_t)kMaxLds) continue;
         for (int upw = 2; upw <= 4; ++upw) {
             if (upw * bw > 16 || 3 * slots * upw > kWeightRegs) continue;   // 1.5 registers per (unit, slot) and matrix

@@ -238,14 +238,17 @@ def test_hlstm_batch1_consecutive_forwards_of_any_length_on_one_handle(L, bidir)
     (1, False, 20, 333, 257, 1, 4, 0.4, True),      # T = 1: no exchange of h at all
     (1, True, 64, 400, 400, 6, 16, 0.35, True),     # three slices per row, 4 units per wave and 4 columns
     (1, False, 30, 37, 41, 9, 33, 0.6, True),       # many batch groups, few units
+    (1, False, 400, 1500, 1500, 4, 20, 0.10, False),  # the language-model cell at batch 20: 96 KB of hidden activations
+    (1, False, 100, 1100, 1300, 3, 12, 0.10, True),   # per batch group in LDS (offsets beyond 64 KB)
+    (2, True, 100, 1200, 1200, 3, 24, 0.10, False),   # two directions that do not fit one grid together: a launch each
 ])
 def test_hlstm_persistent_small_batch(shape):
     L, bidir, D, H, G, T, Bn, keep, coop = shape
     case = inputs.make_case(_hw(85, L, bidir, D, H, G, T, Bn, keep=keep), k=H + G + T + Bn, random_state=True)
     desc, _ = check_case(case, CSR, PERSIST, cooperative=coop)
-    assert "persist_batched-hlstm" in desc
+    assert desc.count("persist_batched-hlstm") == L * (2 if bidir else 1)
     desc, _ = check_case(case, CSR, PAUTO, cooperative=coop)
-    assert "persist_batched-hlstm" in desc
+    assert desc.count("persist_batched-hlstm") == L * (2 if bidir else 1)
 
 
 @pytest.mark.parametrize("shape", [

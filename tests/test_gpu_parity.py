@@ -82,12 +82,14 @@ def test_batch1_overflow_rows(shape):
     (1, False, 40, 333, 7, 20, 0.10),
     (2, False, 48, 130, 6, 3, 0.5),
     (1, True, 32, 96, 5, 33, 0.3),
+    (2, True, 200, 1500, 4, 20, 0.10),   # two directions that do not fit one grid together: one launch per direction
 ])
 def test_small_batch_persistent(shape):
     L, bidir, D, H, T, Bn, keep = shape
-    case = inputs.make_case(_wl(88, L, bidir, D, H, T, Bn, keep=keep), k=H + Bn, random_state=True)
+    a = 0.3 if H < 1000 else 0.04
+    case = inputs.make_case(_wl(88, L, bidir, D, H, T, Bn, a=a, keep=keep), k=H + Bn, random_state=True)
     desc, _ = check_case(case, CSR, PAUTO)
-    assert "persist_batched" in desc
+    assert desc.count("persist_batched") == L * (2 if bidir else 1)
     desc, _ = check_case(case, CSR, STEP)
     assert "stepwise" in desc
 
@@ -481,6 +483,14 @@ def test_c4_full_sampled_columns():
 
 
 @pytest.mark.slow
+def test_c4_full_dense_masked_sampled_columns():
+    """The same five bidirectional layers with the weights held dense-masked (what `bench.py --workload c4_dense`
+    times): matrix-core fp32 projection and the dense fp32 persistent recurrence at full size."""
+    desc, _ = check_case(inputs.make_case(inputs.c4(), 3), DENSE, oracle_cols=[4, 14])
+    assert desc.count("rec=persist-dense-f32") == 10
+
+
+@pytest.mark.slow
 def test_c5_full_sampled_columns():
     for k in (0, 1, 2):
         check_case(inputs.make_case(inputs.c5(), k, random_state=(k == 2)), AUTO, oracle_cols=[0, 131, 255] if k == 0 else [77])
@@ -556,6 +566,7 @@ def test_expired_waits_are_reported_and_nothing_hangs(monkeypatch):
         (_wl(70, 2, False, 60, 500, 40, 1, keep=0.2), CSR, "wavefront"),
         (_wl(70, 1, True, 48, 400, 30, 12, keep=0.15), CSR, "persist_batched"),
         (_wl(70, 1, False, 64, 512, 30, 128, dtype="bf16", a=0.05), DENSE, "persist-mfma"),
+        (_wl(70, 1, True, 48, 400, 30, 12), DENSE, "persist-dense-f32"),
         (inputs.Workload(70, "hl", 1, False, 40, 400, 30, 1, "f32", 0.3, 0.2, "uniform", 400), CSR, "persist_b1-hlstm"),
         (inputs.Workload(70, "hlb", 1, True, 40, 300, 20, 6, "f32", 0.3, 0.2, "uniform", 260), CSR, "persist_batched-hlstm"),
     ]
