@@ -264,6 +264,7 @@ struct PersistDenseArgs {
     int* timeout_flag;
     unsigned spin_limit;
     int T, B, H, ndir;
+    int Bld;                   // rows per timestep in P and y (>= B: the launch may cover a run of the batch's columns)
     int gm, gn;                // row blocks, workgroups per row block (set by the launcher)
     int poll_pace;             // pace_poll units in front of a step's first read of h (exchange.h)
 };
@@ -374,6 +375,7 @@ struct PersistBatchedDir {
 struct PersistBatchedArgs {
     PersistBatchedDir d[2];
     int T, B, H;
+    int Bld;                   // rows per timestep in P and y (>= B: the launch may cover a run of the batch's columns)
     int ug, bg;                // unit groups / batch groups per direction (filled by the launcher)
     int ndir, xcd_local;       // directions in the grid; block ids grouped by XCD (filled by the launcher)
     int device_scope_only;     // 1: publish with device-scope stores even where a group shares an XCD (A/B switch)
@@ -439,6 +441,7 @@ struct PersistBatchedHDir {
 struct PersistBatchedHArgs {
     PersistBatchedHDir d[2];
     int T, B, H, G;
+    int Bld;                    // rows per timestep in P1 and y (>= B: the launch may cover a run of the batch's columns)
     int ug, bg;                 // unit groups / batch groups per direction (filled by the launcher)
     int ndir, xcd_local;        // directions in the grid; block ids grouped by XCD (filled by the launcher)
     int device_scope_only;      // 1: publish with device-scope stores even where a group shares an XCD (A/B switch)

@@ -106,6 +106,30 @@ static float host_bf16_to_f32(uint16_t b)
     return f;
 }
 
+// How the recurrence of a layer is cut when its persistent kernel cannot take it in one launch (more workgroups than
+// compute units): `passes` launches over the directions (1: all directions in one grid, 2: one launch each) times `chunks`
+// runs of batch columns of nearly equal length (batch columns are independent).  The cut with the fewest launches that
+// `fits(columns, directions)` accepts for its longest and shortest run wins; at most eight launches per layer.
+struct LaunchCut { int passes = 0, chunks = 0; };
+template <class Fits>
+static bool choose_cut(int B, int Dn, Fits fits, LaunchCut* out)
+{
+    for (int total = 1; total <= 8; ++total)
+        for (int passes = 1; passes <= Dn; ++passes) {
+            if (total % passes) continue;
+            const int chunks = total / passes, nd = Dn / passes;
+            const int lo = B / chunks, hi = (B + chunks - 1) / chunks;
+            if (lo < 2) continue;
+            if (fits(hi, nd) && (lo == hi || fits(lo, nd))) {
+                out->passes = passes;
+                out->chunks = chunks;
+                return true;
+            }
+        }
+    return false;
+}
+static inline int chunk_begin(int B, int chunks, int c) { return (int)((long long)c * B / chunks); }
+
 // pace_poll units (64 clocks each) in front of a device-wide poll that follows the wave's own publication at once (exchange.h).
 // Measured optima, both broad: batch-1 H-LSTM, poll of the hidden activations: 135.4 us per sequence unpaced, 121.6 at 8,
 // 120.1 at 10, 121.0 at 12, 124.0 at 16; small-batch recurrence with a device-wide exchange (two 1500-wide layers, batch
@@ -826,9 +850,13 @@ static Workspace carve(const lstm_t* m, int T, int B)
         // fp32 dense persistent recurrence at small and medium batch: the same two regions (whether a layer's recurrent
         // matrix is held dense is not known before its weights are set, so every width the kernel takes is provided for)
         size_t xfloats = 0;
-        for (int l = 0; l < m->L; ++l)
-            if (persist_dense_f32_supported(B, m->hid(l), m->Dn))
-                xfloats = std::max(xfloats, persist_dense_f32_exchange_floats(B, m->hid(l), m->Dn));
+        for (int l = 0; l < m->L; ++l) {
+            const int Hl = m->hid(l);
+            LaunchCut cut;
+            if (choose_cut(B, m->Dn, [&](int b, int nd) { return persist_dense_f32_supported(b, Hl, nd); }, &cut))
+                for (int b : {(B + cut.chunks - 1) / cut.chunks, B / cut.chunks})
+                    xfloats = std::max(xfloats, persist_dense_f32_exchange_floats(b, Hl, m->Dn / cut.passes));
+        }
         off += align256(xfloats * sizeof(float));
         w.mflag_off = off;
     }
@@ -1009,12 +1037,8 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                 nz = std::max(nz, std::max(w.wh.q16_slots, w.w2.q16_slots));
                 any_extra = any_extra || w.wh.q16_ovf_ptr || w.w2.q16_ovf_ptr;
             }
-            // both directions in one grid where they fit one workgroup per compute unit, else one launch per direction
-            int passes = 1;
-            if (pb_ok && !persist_batched_h_plan(B, H, G, nz, Dn, &upw, &bw, &ug, &bg)) {
-                pb_ok = Dn == 2 && persist_batched_h_plan(B, H, G, nz, 1, &upw, &bw, &ug, &bg);
-                passes = 2;
-            }
+            LaunchCut cut;
+            pb_ok = pb_ok && choose_cut(B, Dn, [&](int b, int nd) { return persist_batched_h_plan(b, H, G, nz, nd, &upw, &bw, &ug, &bg); }, &cut);
             const bool trimmed = any_extra;
             if (m->plan == LSTM_PLAN_PERSISTENT && B >= 2 && !pb_ok)
                 return fail(m, LSTM_ERR_ARG, "lstm_forward: persistent plan not available for this shape");
@@ -1032,30 +1056,38 @@ static int forward_hlstm(lstm_t* m, int T, int B, const void* x, const float* h0
                     hslots_H = H; hslots_G = G;
                     htag = 0;
                 }
-                for (int pass = 0; pass < passes; ++pass) {
-                const int d_lo = passes == 2 ? pass : 0, nd = passes == 2 ? 1 : Dn;
+                for (int launch = 0; launch < cut.passes * cut.chunks; ++launch) {
+                const int pass = launch / cut.chunks, chunk = launch % cut.chunks;
+                const int nd = Dn / cut.passes, d_lo = pass * nd;
+                const int b_lo = chunk_begin(B, cut.chunks, chunk), bn = chunk_begin(B, cut.chunks, chunk + 1) - b_lo;
+                persist_batched_h_plan(bn, H, G, nz, nd, &upw, &bw, &ug, &bg);
                 PersistBatchedHArgs a{};
                 for (int d = d_lo; d < d_lo + nd; ++d) {
                     const LayerDir& w = m->ld[(size_t)l * Dn + d];
                     const size_t n = (size_t)l * Dn + d;
                     PersistBatchedHDir& q = a.d[d - d_lo];
-                    q.P1 = P[d];
+                    q.P1 = P[d] + (size_t)b_lo * 4 * G;
                     q.q16_val_1h = w.wh.q16_val; q.q16_col_1h = w.wh.q16_col; q.slots_1h = w.wh.q16_slots;
                     q.ovf_ptr_1h = w.wh.q16_ovf_ptr; q.ovf_ent_1h = w.wh.q16_ovf_ent; q.ovf_val_1h = w.wh.q16_ovf_val;
                     q.q16_val_2 = w.w2.q16_val; q.q16_col_2 = w.w2.q16_col; q.slots_2 = w.w2.q16_slots;
                     q.ovf_ptr_2 = w.w2.q16_ovf_ptr; q.ovf_ent_2 = w.w2.q16_ovf_ent; q.ovf_val_2 = w.w2.q16_ovf_val;
                     q.bias2 = w.bias2;
-                    q.h0 = h0 ? h0 + m->soff(n) * B : nullptr;
-                    q.c0 = c0 ? c0 + m->soff(n) * B : nullptr;
-                    q.y = Yout + (size_t)d * H; q.y_ld = y_ld;
-                    q.hT = hT ? hT + m->soff(n) * B : nullptr;
-                    q.cT = cT ? cT + m->soff(n) * B : nullptr;
+                    const size_t so = m->soff(n) * B + (size_t)b_lo * H;
+                    q.h0 = h0 ? h0 + so : nullptr;
+                    q.c0 = c0 ? c0 + so : nullptr;
+                    q.y = Yout + (size_t)b_lo * y_ld + (size_t)d * H; q.y_ld = y_ld;
+                    q.hT = hT ? hT + so : nullptr;
+                    q.cT = cT ? cT + so : nullptr;
                     q.reverse = d;
-                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-hlstm-csr%s(s%d,u%d,b%d);", l, d,
-                                  proj_dense[d] ? "dense" : "csr", trimmed ? "+ovf" : "", nz, upw, bw);
-                    m->last_plan += tag;
+                    if (chunk == 0) {
+                        char cuts[24] = "";
+                        if (cut.chunks > 1) std::snprintf(cuts, sizeof cuts, ",batch/%d", cut.chunks);
+                        std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-hlstm-csr%s(s%d,u%d,b%d%s);", l, d,
+                                      proj_dense[d] ? "dense" : "csr", trimmed ? "+ovf" : "", nz, upw, bw, cuts);
+                        m->last_plan += tag;
+                    }
                 }
-                a.T = T; a.B = B; a.H = H; a.G = G;
+                a.T = T; a.B = bn; a.Bld = B; a.H = H; a.G = G;
                 a.xchg_h = hslots; a.xchg_u = U[0]; a.flags = hflags; a.xcc_ids = hxcc;
                 a.tag_base = htag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 htag += (unsigned)T + 1u;
@@ -1488,32 +1520,44 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 const LayerDir& w = m->ld[(size_t)l * Dn + d];
                 dense_f32 = dense_f32 && mode[d] == 0 && !w.wh.compressed && w.wh.dense;
             }
-            if (dense_f32 && persist_dense_f32_supported(B, H, Dn)) {
-                // the exchange buffers start every launch with all stamps clear
-                HIP_TRY(m, launch_fill_f32((float*)hx, persist_dense_f32_exchange_floats(B, H, Dn), 0.0f, s));
-                PersistDenseArgs a{};
-                const float* h0d[2] = {nullptr, nullptr};
-                for (int d = 0; d < Dn; ++d) {
-                    const LayerDir& w = m->ld[(size_t)l * Dn + d];
-                    const size_t n = (size_t)l * Dn + d;
-                    a.d[d].P = P[d];
-                    a.d[d].Wh = (const float*)w.wh.dense;
-                    a.d[d].c0 = c0 ? c0 + m->soff(n) * B : nullptr;
-                    a.d[d].y = Yout + (size_t)d * H; a.d[d].y_ld = y_ld;
-                    a.d[d].hT = hT ? hT + m->soff(n) * B : nullptr;
-                    a.d[d].cT = cT ? cT + m->soff(n) * B : nullptr;
-                    a.d[d].reverse = d;
-                    h0d[d] = h0 ? h0 + m->soff(n) * B : nullptr;
-                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist-dense-f32;", l, d,
-                                  proj_runs_dense(w.wx, M, D, bf16) ? "dense" : "csr");
-                    m->last_plan += tag;
+            LaunchCut cut;
+            if (dense_f32 && choose_cut(B, Dn, [&](int b, int nd) { return persist_dense_f32_supported(b, H, nd); }, &cut)) {
+                for (int launch = 0; launch < cut.passes * cut.chunks; ++launch) {
+                    const int pass = launch / cut.chunks, chunk = launch % cut.chunks;
+                    const int nd = Dn / cut.passes, d_lo = pass * nd;
+                    const int b_lo = chunk_begin(B, cut.chunks, chunk), bn = chunk_begin(B, cut.chunks, chunk + 1) - b_lo;
+                    // the exchange buffers start every launch with all stamps clear
+                    HIP_TRY(m, launch_fill_f32((float*)hx, persist_dense_f32_exchange_floats(bn, H, nd), 0.0f, s));
+                    PersistDenseArgs a{};
+                    const float* h0d[2] = {nullptr, nullptr};
+                    for (int d = d_lo; d < d_lo + nd; ++d) {
+                        const LayerDir& w = m->ld[(size_t)l * Dn + d];
+                        const size_t n = (size_t)l * Dn + d;
+                        const size_t so = m->soff(n) * B + (size_t)b_lo * H;
+                        PersistDenseDir& q = a.d[d - d_lo];
+                        q.P = P[d] + (size_t)b_lo * 4 * H;
+                        q.Wh = (const float*)w.wh.dense;
+                        q.c0 = c0 ? c0 + so : nullptr;
+                        q.y = Yout + (size_t)b_lo * y_ld + (size_t)d * H; q.y_ld = y_ld;
+                        q.hT = hT ? hT + so : nullptr;
+                        q.cT = cT ? cT + so : nullptr;
+                        q.reverse = d;
+                        h0d[d - d_lo] = h0 ? h0 + so : nullptr;
+                        if (chunk == 0) {
+                            char cuts[24] = "";
+                            if (cut.chunks > 1) std::snprintf(cuts, sizeof cuts, "(batch/%d)", cut.chunks);
+                            std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist-dense-f32%s;", l, d,
+                                          proj_runs_dense(w.wx, M, D, bf16) ? "dense" : "csr", cuts);
+                            m->last_plan += tag;
+                        }
+                    }
+                    a.hx = (float*)hx;
+                    a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
+                    a.T = T; a.B = bn; a.Bld = B; a.H = H; a.ndir = nd;
+                    a.poll_pace = m->poll_pace >= 0 ? m->poll_pace : (H <= 512 ? kPollPaceDenseNarrow : kPollPaceDenseWide);
+                    ProfSpan span(m, s, 1);
+                    HIP_TRY(m, launch_persist_dense_f32(a, h0d, m->launch_mode() != 0, s));
                 }
-                a.hx = (float*)hx;
-                a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
-                a.T = T; a.B = B; a.H = H; a.ndir = Dn;
-                a.poll_pace = m->poll_pace >= 0 ? m->poll_pace : (H <= 512 ? kPollPaceDenseNarrow : kPollPaceDenseWide);
-                ProfSpan span(m, s, 1);
-                HIP_TRY(m, launch_persist_dense_f32(a, h0d, m->launch_mode() != 0, s));
                 continue;
             }
         }
@@ -1527,12 +1571,8 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                 pb_ok = p.compressed && p.q16_slots > 0;
                 q16 = std::max(q16, p.q16_slots);
             }
-            // both directions in one grid where they fit one workgroup per compute unit, else one launch per direction
-            int passes = 1;
-            if (pb_ok && !persist_batched_q16_plan(B, H, q16, Dn, &upw, &bw, &ug, &bg)) {
-                pb_ok = Dn == 2 && persist_batched_q16_plan(B, H, q16, 1, &upw, &bw, &ug, &bg);
-                passes = 2;
-            }
+            LaunchCut cut;
+            pb_ok = pb_ok && choose_cut(B, Dn, [&](int b, int nd) { return persist_batched_q16_plan(b, H, q16, nd, &upw, &bw, &ug, &bg); }, &cut);
             if (pb_ok) {
                 if (!bslots_clean || bslots_H != H) {   // another width is another layout: start from zero again
                     HIP_TRY(m, launch_fill_u64(bslots, align256(ws.slot_bytes) / sizeof(unsigned long long), 0ull, s));
@@ -1540,28 +1580,36 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                     bslots_H = H;
                     btag = 0;
                 }
-                for (int pass = 0; pass < passes; ++pass) {
-                const int d_lo = passes == 2 ? pass : 0, nd = passes == 2 ? 1 : Dn;
+                for (int launch = 0; launch < cut.passes * cut.chunks; ++launch) {
+                const int pass = launch / cut.chunks, chunk = launch % cut.chunks;
+                const int nd = Dn / cut.passes, d_lo = pass * nd;
+                const int b_lo = chunk_begin(B, cut.chunks, chunk), bn = chunk_begin(B, cut.chunks, chunk + 1) - b_lo;
+                persist_batched_q16_plan(bn, H, q16, nd, &upw, &bw, &ug, &bg);
                 PersistBatchedArgs a{};
                 for (int d = d_lo; d < d_lo + nd; ++d) {
                     const LayerDir& w = m->ld[(size_t)l * Dn + d];
                     const size_t n = (size_t)l * Dn + d;
                     PersistBatchedDir& q = a.d[d - d_lo];
-                    q.P = P[d];
+                    q.P = P[d] + (size_t)b_lo * 4 * H;
                     q.q16_val = w.wh.q16_val; q.q16_col = w.wh.q16_col; q.q16_slots = w.wh.q16_slots;
                     q.q16_ovf_ptr = w.wh.q16_ovf_ptr; q.q16_ovf_ent = w.wh.q16_ovf_ent; q.q16_ovf_val = w.wh.q16_ovf_val;
-                    q.h0 = h0 ? h0 + m->soff(n) * B : nullptr;
-                    q.c0 = c0 ? c0 + m->soff(n) * B : nullptr;
-                    q.y = Yout + (size_t)d * H; q.y_ld = y_ld;
-                    q.hT = hT ? hT + m->soff(n) * B : nullptr;
-                    q.cT = cT ? cT + m->soff(n) * B : nullptr;
+                    const size_t so = m->soff(n) * B + (size_t)b_lo * H;
+                    q.h0 = h0 ? h0 + so : nullptr;
+                    q.c0 = c0 ? c0 + so : nullptr;
+                    q.y = Yout + (size_t)b_lo * y_ld + (size_t)d * H; q.y_ld = y_ld;
+                    q.hT = hT ? hT + so : nullptr;
+                    q.cT = cT ? cT + so : nullptr;
                     q.reverse = d;
-                    std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16%s(s%d,u%d,b%d);", l, d,
-                                  proj_q16_used ? "q16" : proj_runs_dense(w.wx, M, D, bf16) ? "dense" : "csr",
-                                  w.wh.q16_ovf_ptr ? "+ovf" : "", q16, upw, bw);
-                    m->last_plan += tag;
+                    if (chunk == 0) {
+                        char cuts[24] = "";
+                        if (cut.chunks > 1) std::snprintf(cuts, sizeof cuts, ",batch/%d", cut.chunks);
+                        std::snprintf(tag, sizeof tag, "l%d.d%d:proj=%s,rec=persist_batched-q16%s(s%d,u%d,b%d%s);", l, d,
+                                      proj_q16_used ? "q16" : proj_runs_dense(w.wx, M, D, bf16) ? "dense" : "csr",
+                                      w.wh.q16_ovf_ptr ? "+ovf" : "", q16, upw, bw, cuts);
+                        m->last_plan += tag;
+                    }
                 }
-                a.T = T; a.B = B; a.H = H; a.round_h_bf16 = bf16;
+                a.T = T; a.B = bn; a.Bld = B; a.H = H; a.round_h_bf16 = bf16;
                 a.xchg = bslots; a.xcc_ids = bslots + (size_t)Dn * 2 * (B + 3) * H; a.tag_base = btag; a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit; a.device_scope_only = m->device_scope_only;
                 a.poll_pace = m->poll_pace >= 0 ? m->poll_pace : kPollPaceBatchedDeviceWide;   // (the launcher clears it where the exchange stays inside XCDs)
                 btag += (unsigned)T;

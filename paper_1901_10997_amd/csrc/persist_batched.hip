@@ -140,7 +140,7 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
     // So the element for step s+1 is requested right after the poll of step s has been answered.
     auto load_p = [&](int s_) {
         const int t_ = reverse ? (a.T - 1 - s_) : s_;
-        return (pair_ok && s_ < a.T) ? Pd_c[((size_t)t_ * B + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row] : 0.f;
+        return (pair_ok && s_ < a.T) ? Pd_c[((size_t)t_ * a.Bld + b0 + pb) * (4 * (size_t)H) + 4 * unit_l + row] : 0.f;
     };
     float pin_next = load_p(0);
     for (int s = 0; s < a.T; ++s) {
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
         }
         // outputs after the publication: nothing on the way of h_t
         if (lane < 16 && pair_ok) {
-            y_c[((size_t)t * B + b0 + pb) * y_ld_c + unit_l] = h_keep;
+            y_c[((size_t)t * a.Bld + b0 + pb) * y_ld_c + unit_l] = h_keep;
             if (s + 1 == a.T) {
                 const size_t ci = (size_t)(b0 + pb) * H + unit_l;
                 if (hT_c) hT_c[ci] = h_keep;

@@ -246,7 +246,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
                 asm volatile("" : "+v"(o2[u][i]));
             }
         float pin = 0.f;
-        if (ok1) pin = (kCopy ? P1_c : D.P1)[((size_t)t * B + b0 + pb) * (4 * (size_t)G) + 4 * unit_l + row];
+        if (ok1) pin = (kCopy ? P1_c : D.P1)[((size_t)t * a.Bld + b0 + pb) * (4 * (size_t)G) + 4 * unit_l + row];
         // ---- stage 1: hidden layers from h_{t-1}
         if (s == 0) {
             for (int e = tid; e < BW * H; e += nthreads) {
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
                 if (in_pairs && unit_l < H && s + 1 < a.T)
                     exchange_store(xh + (size_t)unit_l * BW + pb, pack_slot(pb < bw ? h : 0.f, tag), same_xcd);
                 if (ok2) {
-                    (kCopy ? y_c : D.y)[((size_t)t * B + b0 + pb) * (kCopy ? y_ld_c : (size_t)D.y_ld) + unit_l] = h;
+                    (kCopy ? y_c : D.y)[((size_t)t * a.Bld + b0 + pb) * (kCopy ? y_ld_c : (size_t)D.y_ld) + unit_l] = h;
                     if (s + 1 == a.T) {
                         const size_t ci = (size_t)(b0 + pb) * H + unit_l;
                         float* const hT_out = kCopy ? hT_c : D.hT;

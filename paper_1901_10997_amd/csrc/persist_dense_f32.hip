@@ -97,7 +97,7 @@ __global__ __launch_bounds__(512) void persist_dense_f32_kernel(PersistDenseArgs
         const int t = reverse ? a.T - 1 - s : s;
         // epilogue operand, requested first
         float4 pre = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (live) pre = *reinterpret_cast<const float4*>(Pd + ((size_t)t * B + pb) * (4 * (size_t)H) + n0 + 4 * pu);
+        if (live) pre = *reinterpret_cast<const float4*>(Pd + ((size_t)t * a.Bld + pb) * (4 * (size_t)H) + n0 + 4 * pu);
         f32x4 acc[MT][2];
 #pragma unroll
         for (int i = 0; i < MT; ++i)
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(512) void persist_dense_f32_kernel(PersistDenseArgs
         if (!last) __syncthreads();
         // outputs after the publication: nothing on the way of h_t
         if (live) {
-            y_c[((size_t)t * B + pb) * y_ld + unit] = hn;
+            y_c[((size_t)t * a.Bld + pb) * y_ld + unit] = hn;
             if (last) {
                 if (hT_c) hT_c[(size_t)pb * H + unit] = hn;
                 if (cT_c) cT_c[(size_t)pb * H + unit] = c;

@@ -240,7 +240,9 @@ def test_hlstm_batch1_consecutive_forwards_of_any_length_on_one_handle(L, bidir)
     (1, False, 30, 37, 41, 9, 33, 0.6, True),       # many batch groups, few units
     (1, False, 400, 1500, 1500, 4, 20, 0.10, False),  # the language-model cell at batch 20: 96 KB of hidden activations
     (1, False, 100, 1100, 1300, 3, 12, 0.10, True),   # per batch group in LDS (offsets beyond 64 KB)
-    (2, True, 100, 1200, 1200, 3, 24, 0.10, False),   # two directions that do not fit one grid together: a launch each
+    (2, True, 100, 1200, 1200, 3, 24, 0.10, False),   # two directions that do not fit one grid together: two launches
+    (1, False, 100, 1500, 1500, 3, 33, 0.10, True),   # more batch groups than fit the device: runs of batch columns
+    (1, True, 80, 800, 800, 3, 64, 0.20, False),
 ])
 def test_hlstm_persistent_small_batch(shape):
     L, bidir, D, H, G, T, Bn, keep, coop = shape
