@@ -21,6 +21,7 @@ CASES = [
     (2, True, 24, 80, 9, 1, "f32", None, 0, "persist_b1-dense"),    # batch 1, dense, both directions
     (1, True, 24, 96, 15, 4, "f32", 0.2, 0, "persist_batched"),     # small batch, workspace-owned slots
     (1, True, 64, 128, 6, 64, "f32", None, 0, "persist-dense-f32"), # dense fp32 at medium batch, flags cleared inside the graph
+    (1, False, 48, 800, 4, 64, "f32", 0.1, 0, "batch/"),            # a layer cut into runs of batch columns, a launch each
     (1, False, 24, 2304, 3, 2, "f32", None, 0, "stepwise"),         # wider than any resident kernel: one launch per step
     (1, False, 32, 64, 10, 1, "f32", 0.2, 48, "persist_b1-hlstm"),  # H-LSTM, batch 1
     (1, True, 32, 64, 8, 4, "f32", 0.2, 48, "persist_batched-hlstm"),               # H-LSTM, small batch

@@ -83,7 +83,7 @@ def test_batch1_overflow_rows(shape):
     (2, False, 48, 130, 6, 3, 0.5),
     (1, True, 32, 96, 5, 33, 0.3),
     (2, True, 200, 1500, 4, 20, 0.10),   # two directions that do not fit one grid together: the layer is cut in two launches
-    (1, False, 100, 1500, 3, 45, 0.10),  # more batch groups than fit the device: runs of batch columns, a launch each
+    (2, False, 100, 1500, 3, 45, 0.10),  # more batch groups than fit the device: runs of batch columns, a launch each
     (1, True, 64, 2048, 3, 21, 0.08),    # both cuts, runs of unequal length
 ])
 def test_small_batch_persistent(shape):
@@ -745,7 +745,7 @@ def test_wider_than_any_persistent_kernel(Bn, fmt):
     (1, True, 24, 500, 2, 128),      # ... with four
     (1, False, 24, 1500, 2, 20),     # twelve k-blocks per wave take one 16-row block only: two runs of ten batch columns
     (1, True, 24, 1500, 2, 9),       # both directions need more workgroups than there are compute units: a launch each
-    (1, True, 24, 800, 2, 100),      # ... and runs of batch columns on top
+    (2, True, 24, 800, 2, 100),      # ... and runs of batch columns on top, in both layers
 ])
 def test_dense_small_batch_persistent(shape):
     L, bidir, D, H, T, Bn = shape
