@@ -267,7 +267,13 @@ struct PersistDenseArgs {
     int Bld;                   // rows per timestep in P and y (>= B: the launch may cover a run of the batch's columns)
     int gm, gn;                // row blocks, workgroups per row block (set by the launcher)
     int poll_pace;             // pace_poll units in front of a step's first read of h (exchange.h)
+    unsigned long long* xcc_ids;  // [ndir * row blocks][64] tagged slots for the XCD ids of a group's workgroups (zero or
+                               // older tags only), or nullptr: no hand-over through one XCD's L2
+    unsigned tag_base;         // the XCD ids of this launch carry tag_base + 1
+    int xcd_local;             // block ids grouped by XCD (set by the launcher)
+    int device_scope_only;     // 1: publish with device-scope stores even where a group shares an XCD (A/B switch)
 };
+size_t persist_dense_f32_ids_count();   // 8-byte slots behind xcc_ids
 bool persist_dense_f32_supported(int B, int H, int ndir);
 size_t persist_dense_f32_exchange_floats(int B, int H, int ndir);
 // h0[d]: fp32 [B][H] of direction d or nullptr

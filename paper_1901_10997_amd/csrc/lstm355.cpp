@@ -859,6 +859,7 @@ static Workspace carve(const lstm_t* m, int T, int B)
         }
         off += align256(xfloats * sizeof(float));
         w.mflag_off = off;
+        if (xfloats > 0) off += align256(persist_dense_f32_ids_count() * sizeof(unsigned long long));
     }
     // H-LSTM: hidden-layer activations of the current step, [B][4G] per direction (stepwise paths); the small-batch
     // persistent kernel uses both directions' storage as one array of [k][columns of a batch group] blocks
@@ -1552,6 +1553,14 @@ static int run_forward(lstm_t* m, int T, int B, const void* x, const float* h0, 
                         }
                     }
                     a.hx = (float*)hx;
+                    if (!mflags_clean) {
+                        HIP_TRY(m, launch_fill_u64((unsigned long long*)mflags, persist_dense_f32_ids_count(), 0ull, s));
+                        mflags_clean = true;
+                        mtag = 0;
+                    }
+                    a.xcc_ids = (unsigned long long*)mflags;
+                    a.tag_base = mtag++;
+                    a.device_scope_only = m->device_scope_only;
                     a.timeout_flag = m->timeout_flag; a.spin_limit = m->spin_limit;
                     a.T = T; a.B = bn; a.Bld = B; a.H = H; a.ndir = nd;
                     a.poll_pace = m->poll_pace >= 0 ? m->poll_pace : (H <= 512 ? kPollPaceDenseNarrow : kPollPaceDenseWide);

@@ -43,10 +43,21 @@ __global__ __launch_bounds__(512) void persist_dense_f32_kernel(PersistDenseArgs
     extern __shared__ __attribute__((aligned(16))) float part[];   // [8][16 MT][36]
     constexpr int RM = 16 * MT;
     const int H = a.H, B = a.B, gm = a.gm, gn = a.gn;
-    const int per_dir = gm * gn;
-    const int dir = blockIdx.x / per_dir;
-    const int rem = blockIdx.x - dir * per_dir;
-    const int tile_m = rem / gn, tile_n = rem - tile_m * gn;
+    // Workgroups are dealt to the eight XCDs in turn.  The gn workgroups of one (direction, row block) are the only ones
+    // that exchange h among themselves; where those groups fit, each takes block ids of one residue modulo 8, so that
+    // it can hand h over through one XCD's L2 (checked below).
+    int dir, tile_m, tile_n;
+    if (a.xcd_local) {
+        const int jj = blockIdx.x >> 3;
+        const int grp = (blockIdx.x & 7) + 8 * (jj / gn);
+        if (grp >= a.ndir * gm) return;                        // padding ids take no part in the exchange
+        tile_n = jj % gn; dir = grp / gm; tile_m = grp - dir * gm;
+    } else {
+        const int per_dir = gm * gn;
+        dir = blockIdx.x / per_dir;
+        const int rem = blockIdx.x - dir * per_dir;
+        tile_m = rem / gn; tile_n = rem - tile_m * gn;
+    }
     const int m0 = tile_m * RM, n0 = tile_n * kRN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -92,6 +103,11 @@ __global__ __launch_bounds__(512) void persist_dense_f32_kernel(PersistDenseArgs
     const bool in_tile = tid < RM * kUT;
     const bool live = in_tile && pb < B && unit < H;
     float c = (live && D.c0) ? D.c0[(size_t)pb * H + unit] : 0.f;
+
+    bool same_xcd = false;
+    if (a.xcd_local)
+        same_xcd = group_shares_xcd(a.xcc_ids + (size_t)(dir * gm + tile_m) * 64, gn, tile_n, a.tag_base + 1u, part, tid, kNTH,
+                                    a.timeout_flag, a.spin_limit) && !a.device_scope_only;
 
     for (int s = 0; s < a.T; ++s) {
         const int t = reverse ? a.T - 1 - s : s;
@@ -205,9 +221,8 @@ __global__ __launch_bounds__(512) void persist_dense_f32_kernel(PersistDenseArgs
             // brought below 2 by clearing the exponent's top bit first.
             if (!last && unit < H) {
                 const unsigned gw = (unsigned)s + 2u;
-                __hip_atomic_store(hx + (size_t)(gw & 1u) * xbuf + ((size_t)(unit >> 4) * Bp + pb) * 16 + (unit & 15),
-                                   (__float_as_uint(hn) & ~kStampBit) | (((gw >> 1) & 1u) << 30), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+                exchange_store(hx + (size_t)(gw & 1u) * xbuf + ((size_t)(unit >> 4) * Bp + pb) * 16 + (unit & 15),
+                               (__float_as_uint(hn) & ~kStampBit) | (((gw >> 1) & 1u) << 30), same_xcd);
             }
         }
         // keeps the next step's partial tiles out of LDS until every thread has read this step's
@@ -267,6 +282,9 @@ bool persist_dense_f32_supported(int B, int H, int ndir)
     return dense_mt(B, H, ndir) > 0;
 }
 
+// one run of 64 slots per (direction, row block); there are at most as many of those as compute units
+size_t persist_dense_f32_ids_count() { return (size_t)device_num_cus() * 64; }
+
 size_t persist_dense_f32_exchange_floats(int B, int H, int ndir)
 {
     const int mt = dense_mt(B, H, ndir);
@@ -281,7 +299,14 @@ static hipError_t launch_dense_shape(PersistDenseArgs& a, const float* const* h0
     constexpr int RM = 16 * MT;
     a.gm = (a.B + RM - 1) / RM;
     a.gn = (4 * a.H + kRN - 1) / kRN;
-    const int grid = a.ndir * a.gm * a.gn;
+    // One XCD holds an eighth of the compute units; its share of the groups (gn workgroups each) must fit there: layers of
+    // at most 256 units.  (H = 256 at batch 16: 2.31 us per step across the device, 1.89 inside one XCD.  Workgroups of 64
+    // packed rows, which would let groups of layers up to 512 wide fit, measured slower than 32 rows across the device:
+    // 2.96 against 2.68 us at H = 320, 3.96 against 3.3 at 512 -- twice the partial tiles per workgroup.)
+    const int groups_per_xcd = (a.ndir * a.gm + 7) / 8;
+    a.xcd_local = (a.xcc_ids != nullptr && a.gn <= 64 && groups_per_xcd * a.gn <= device_num_cus() / 8) ? 1 : 0;
+    if (a.xcd_local) a.poll_pace = 0;   // an exchange inside one XCD is visible by the time the first read arrives
+    const int grid = a.xcd_local ? 8 * groups_per_xcd * a.gn : a.ndir * a.gm * a.gn;
     const size_t lds = (size_t)kNW * RM * kLDP * sizeof(float);
     const size_t xbuf = (size_t)((a.H + 15) / 16) * a.gm * RM * 16;
     for (int d = 0; d < a.ndir; ++d) {

@@ -610,12 +610,13 @@ def test_group_exchange_yardstick_and_the_one_xcd_check():
         B.lstm_bench_group_exchange(100, 65, 1, False, False)
 
 
-@pytest.mark.parametrize("name", ["c1", "c4", "c5", "h2"])
+@pytest.mark.parametrize("name", ["c1", "c4", "c5", "h2", "dense_narrow"])
 def test_l2_handover_off_gives_the_same_bits(name, monkeypatch):
     """The workloads whose exchange is handed over through one XCD's L2, run with that hand-over on and with every
     exchange store forced to device scope (LSTM355_L2_HANDOVER=0 at lstm_create): same placement, same arithmetic, so
     the outputs must be bit-identical; a hand-over that delivered a stale value would show as a difference."""
-    w = {"c1": inputs.c1, "c4": inputs.c4, "c5": inputs.c5, "h2": inputs.h2}[name]()
+    w = {"c1": inputs.c1, "c4": inputs.c4, "c5": inputs.c5, "h2": inputs.h2,
+         "dense_narrow": lambda: _wl(97, 2, True, 64, 256, 40, 16, a=0.1)}[name]()   # dense fp32 at batch, 32 workgroups per group
     if name in ("c4", "h2"):
         w = inputs.shrink(w, T=60)
     case = inputs.make_case(w, 1)
@@ -743,6 +744,7 @@ def test_wider_than_any_persistent_kernel(Bn, fmt):
     (1, False, 8, 3, 4, 2),          # three units: one workgroup, most of its waves without a k-block
     (1, True, 24, 500, 3, 96),       # the grid only fits with three 16-row blocks per workgroup
     (1, True, 24, 500, 2, 128),      # ... with four
+    (2, True, 40, 256, 6, 100),      # eight groups of 32 workgroups, each group on one XCD
     (1, False, 24, 1500, 2, 20),     # twelve k-blocks per wave take one 16-row block only: two runs of ten batch columns
     (1, True, 24, 1500, 2, 9),       # both directions need more workgroups than there are compute units: a launch each
     (2, True, 24, 800, 2, 100),      # ... and runs of batch columns on top, in both layers
