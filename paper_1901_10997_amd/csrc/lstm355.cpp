@@ -110,6 +110,8 @@ static float host_bf16_to_f32(uint16_t b)
 // compute units): `passes` launches over the directions (1: all directions in one grid, 2: one launch each) times `chunks`
 // runs of batch columns of nearly equal length (batch columns are independent).  The cut with the fewest launches that
 // `fits(columns, directions)` accepts for its longest and shortest run wins; at most eight launches per layer.
+// slots of the quarter-wave form the small-batch LSTM recurrence takes (rows of up to 16 x 24 = 384 kept entries)
+constexpr int kMaxRecurrentSlots = 24;
 struct LaunchCut { int passes = 0, chunks = 0; };
 template <class Fits>
 static bool choose_cut(int B, int Dn, Fits fits, LaunchCut* out)
@@ -190,7 +192,8 @@ static hipError_t upload(T** dst, const std::vector<T>& src)
 // Only an entry for which no such slot exists takes any free position, from the end.
 // force_slots > 0: that many slots (the other direction of the layer uses them: one launch serves both, and the
 // kernel is built for the larger count) instead of the smallest count the rule below allows.  max_slots: the most the
-// consuming kernel takes (16 in the recurrence, 24 in the projection); nothing is built for longer rows.
+// consuming kernel takes (24 in the LSTM recurrence and the projection, 16 in the H-LSTM recurrence); nothing is built for
+// longer rows.
 // gather16: the consumer gathers 16 bytes per entry only (the projection: four input rows per tile).  Such a gather makes
 // four passes of 16 lanes -- lane bit 5 and the parity of bits 2..4 pick the pass, so a pass holds eight lanes of each
 // of two rows, with complementary parities of bits 2, 3 -- whose columns must differ modulo 16.  An entry then goes to
@@ -361,7 +364,7 @@ static std::vector<float> to_frag16(const float* W, int rows, int cols)
 // Pack one matrix W[4H][cols] (ABI row order q*H + j) with its optional mask into device storage.
 static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t* mask, int H, int cols, bool compressed,
                        bool bf16, bool keep_dense, int quarter_slots = 0, int gate_col_stride = 0, int soft_slots = 0,
-                       bool frag16 = false)
+                       bool frag16 = false, bool q16_gather16 = false)
 {
     free_mat(out);
     const int rows = 4 * H;
@@ -520,7 +523,7 @@ static int pack_matrix(lstm_t* m, PackedMat& out, const float* W, const uint8_t*
             break;
         }
     }
-    if (quarter_slots > 0) return build_quarter_wave(m, out, 0, quarter_slots, quarter_slots > 16, gate_col_stride, soft_slots);
+    if (quarter_slots > 0) return build_quarter_wave(m, out, 0, quarter_slots, q16_gather16, gate_col_stride, soft_slots);
     return LSTM_OK;
 }
 
@@ -679,9 +682,9 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     x.set = false;
     const bool bf16 = (m->dtype == LSTM_BF16);
     // W_x is kept in both forms when compressed: large T*B projections run dense on the matrix cores
-    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16, true, bf16 ? 0 : 24, 0, 0, !bf16);
+    int rc = pack_matrix(m, x.wx, Wx, mask_x, H, D, compressed, bf16, true, bf16 ? 0 : 24, 0, 0, !bf16, true);
     if (rc != LSTM_OK) return rc;
-    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16, false, 16);
+    rc = pack_matrix(m, x.wh, Wh, mask_h, H, H, compressed, bf16, false, kMaxRecurrentSlots);
     if (rc != LSTM_OK) return rc;
     std::vector<float> bp(rows);
     for (int rp = 0; rp < rows; ++rp) bp[rp] = b[(rp & 3) * H + (rp >> 2)];
@@ -694,7 +697,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
         LayerDir& o = m->ld[(size_t)layer * 2 + (size_t)(1 - direction)];
         if (o.set && x.wh.q16_slots > 0 && o.wh.q16_slots > 0 && x.wh.q16_slots != o.wh.q16_slots) {
             const int target = std::max(x.wh.q16_slots, o.wh.q16_slots);
-            rc = build_quarter_wave(m, x.wh.q16_slots < target ? x.wh : o.wh, target, 16);
+            rc = build_quarter_wave(m, x.wh.q16_slots < target ? x.wh : o.wh, target, kMaxRecurrentSlots);
             if (rc != LSTM_OK) return rc;
         }
         if (o.set && x.wx.q16_slots > 0 && o.wx.q16_slots > 0 && x.wx.q16_slots != o.wx.q16_slots) {

@@ -163,11 +163,12 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
         }
         // (the value is taken over here, behind the poll's own wait, and not at the top of the loop, where waiting for
         // it would also wait for the acknowledgement of the stores just issued, in front of the poll)
-        if constexpr (S * UPW < 84) asm volatile("" : "+v"(pin_next));   // (near the register limit the pin costs more than it saves)
+        constexpr bool kTight = S * UPW >= 84 || (BW == 4 && S * UPW >= 72);   // near the register limit
+        if constexpr (!kTight) asm volatile("" : "+v"(pin_next));   // (near the register limit the pin costs more than it saves)
         const float pin = pin_next;
         pin_next = load_p(s + 1);
         __syncthreads();
-        if constexpr (S * UPW >= 84) {
+        if constexpr (kTight) {
             // near the register limit the offsets stay packed two to a register: the compiler must not unpack all
             // of them ahead of the time loop
 #pragma unroll
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(512) void persist_batched_q16_kernel(PersistBatched
             // multiply-adds that consume them, whatever unit they belong to.
             using VT = typename std::conditional<BW == 2, float2, float4>::type;
             constexpr int NS = UPW * S;
-            constexpr int PDMAX = (S * UPW >= 84) ? 8 : 12;
+            constexpr int PDMAX = kTight ? 8 : 12;
             constexpr int PD = NS < PDMAX ? NS : PDMAX;
             auto read_slot = [&](int n) {
                 const int u = n / S, i = n % S;
@@ -279,7 +280,7 @@ constexpr int kWaves = 8;
 constexpr int kQ16WeightRegs = 156;
 bool persist_batched_q16_plan(int B, int H, int slots, int ndir, int* upw_out, int* bw_out, int* ug_out, int* bg_out)
 {
-    if (B < 2 || slots < 2 || slots > 16 || (slots & 1) || H < 1 || H > 4096) return false;
+    if (B < 2 || slots < 2 || slots > 24 || (slots & 1) || H < 1 || H > 4096) return false;
     // Two rounds.  The first takes the shape with the most workgroups.  The second prefers a shape whose batch groups fit
     // one XCD each (their exchange then stays in that XCD's L2, which is worth more than the extra workgroups: H = 512
     // at batch 20, 2.09 -> 1.80 us per step; two directions of 256 at batch 20, 1.94 -> 1.64), as long as a wave gets at
@@ -347,6 +348,10 @@ hipError_t launch_persist_batched_q16(PersistBatchedArgs& a, int ndir, int slots
         case 12: return launch_q16_s<12>(a, upw, bw, blocks, cooperative != 0, s);
         case 14: return launch_q16_s<14>(a, upw, bw, blocks, cooperative != 0, s);
         case 16: return launch_q16_s<16>(a, upw, bw, blocks, cooperative != 0, s);
+        case 18: return launch_q16_s<18>(a, upw, bw, blocks, cooperative != 0, s);
+        case 20: return launch_q16_s<20>(a, upw, bw, blocks, cooperative != 0, s);
+        case 22: return launch_q16_s<22>(a, upw, bw, blocks, cooperative != 0, s);
+        case 24: return launch_q16_s<24>(a, upw, bw, blocks, cooperative != 0, s);
     }
     return hipErrorInvalidValue;
 }

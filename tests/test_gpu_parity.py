@@ -85,6 +85,9 @@ def test_batch1_overflow_rows(shape):
     (2, True, 200, 1500, 4, 20, 0.10),   # two directions that do not fit one grid together: the layer is cut in two launches
     (2, False, 100, 1500, 3, 45, 0.10),  # more batch groups than fit the device: runs of batch columns, a launch each
     (1, True, 64, 2048, 3, 21, 0.08),    # both cuts, runs of unequal length
+    (1, False, 100, 1500, 3, 17, 0.15),  # rows of 225 kept entries and more: 16 to 18 slots
+    (1, True, 64, 1500, 3, 16, 0.20),    # 300 and more: 20 to 22 slots, four units and four columns at the register limit
+    (2, False, 64, 2048, 2, 8, 0.15),    # 310 and more: 22 to 24 slots
 ])
 def test_small_batch_persistent(shape):
     L, bidir, D, H, T, Bn, keep = shape
