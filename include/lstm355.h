@@ -215,7 +215,11 @@ int lstm_set_default_launch_mode(int cooperative);
 int lstm_set_profiling(lstm_t* m, int enable);
 int lstm_get_profile(lstm_t* m, double* proj_us, int* proj_launches, double* rec_us, int* rec_launches);
 
-/* Writes a short description of the plan the last forward used ("l0:proj=...,rec=...;...") into buf. */
+/* Writes a short description of the plan the last forward used ("l0.d0:proj=...,rec=...;...", one entry per layer and
+ * direction) into buf.  In a recurrence entry "(s, u, b)" are the kernel's slot count, units per wave and batch columns
+ * per workgroup, and "batch/N" says that the layer's batch columns were run as N launches over runs of columns (a layer
+ * whose time-loop kernel would need more workgroups than the device has compute units is cut that way, and/or into one
+ * launch per direction, before the library falls back to one launch per timestep). */
 int lstm_describe_plan(const lstm_t* m, char* buf, size_t buf_bytes);
 
 /*
