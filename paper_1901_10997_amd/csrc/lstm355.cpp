@@ -649,6 +649,20 @@ int lstm_destroy(lstm_t* m)
 
 const char* lstm_last_error(const lstm_t* m) { return m ? m->err.c_str() : g_create_error.c_str(); }
 
+// LSTM_FMT_AUTO: row-compressed when at most a quarter of the entries are kept.  The kernels that run both directions of
+// a layer in one launch need both in the same form, so close to the threshold (20 to 30 % kept) the direction set second
+// follows the one set first instead of landing on the other side of it by a few entries.
+static bool auto_compressed(const lstm_t* m, int layer, int direction, bool masked, size_t kept, size_t total)
+{
+    if (!masked) return false;
+    const double density = (double)kept / (double)total;
+    if (m->Dn == 2) {
+        const LayerDir& o = m->ld[(size_t)layer * 2 + (size_t)(1 - direction)];
+        if (o.set && density > 0.20 && density < 0.30) return o.wh.compressed;
+    }
+    return density <= 0.25;
+}
+
 int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const uint8_t* mask_x, const float* Wh,
                      const uint8_t* mask_h, const float* b, int format)
 {
@@ -672,7 +686,7 @@ int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const
     }
     bool compressed;
     if (format == LSTM_FMT_AUTO)
-        compressed = (mask_x || mask_h) && (double)kept <= 0.25 * (double)total;
+        compressed = auto_compressed(m, layer, direction, mask_x || mask_h, kept, total);
     else
         compressed = (format == LSTM_FMT_ROW_COMPRESSED);
     if (compressed && (D > 65536 || H > 65536))
@@ -734,7 +748,7 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
     }
     bool compressed;
     if (format == LSTM_FMT_AUTO)
-        compressed = (mask_1x || mask_1h || mask_2) && (double)kept <= 0.25 * (double)total;
+        compressed = auto_compressed(m, layer, direction, mask_1x || mask_1h || mask_2, kept, total);
     else
         compressed = (format == LSTM_FMT_ROW_COMPRESSED);
     if (compressed && (D > 65536 || H > 65536 || G > 65536))

@@ -99,6 +99,15 @@ def test_small_batch_persistent(shape):
     assert "stepwise" in desc
 
 
+def test_auto_format_keeps_both_directions_of_a_layer_in_one_form():
+    """Masks that keep a quarter of the entries sit on the threshold of LSTM_FMT_AUTO: the two directions of a layer
+    must not end up in different forms (the time-loop kernels take both directions only in one form)."""
+    for seed in range(5):
+        case = inputs.make_case(_wl(96, 2, True, 48, 256, 4, 8, keep=0.25), seed)
+        desc, _ = check_case(case, AUTO, PAUTO)
+        assert "stepwise" not in desc, desc
+
+
 @pytest.mark.parametrize("shape", [
     # L, bidir, D, H, T, B, keep -- recurrent rows a little longer than a multiple of 64 kept entries (slot counts 6,
     # 8 and 10 of the quarter-wave form, with entries whose bank is full placed by the packer's second pass)
