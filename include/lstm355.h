@@ -54,8 +54,8 @@ enum {
 
 /* storage format of one (layer, direction)'s matrices on the device */
 enum {
-    LSTM_FMT_AUTO = 0,          /* library chooses from the mask density: row-compressed up to 25 % kept (between 20 and
-                                   30 % the second direction of a layer follows the first) */
+    LSTM_FMT_AUTO = 0,          /* library chooses from the mask density: row-compressed up to 25 % kept (H-LSTM: 50 %);
+                                   within 5 % of that the second direction of a layer follows the first */
     LSTM_FMT_DENSE_MASKED = 1,  /* dense matrix with +0 stored where Msk = 0 */
     LSTM_FMT_ROW_COMPRESSED = 2 /* per row: the kept positions only, ascending column order */
 };

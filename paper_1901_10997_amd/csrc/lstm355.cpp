@@ -110,7 +110,7 @@ static float host_bf16_to_f32(uint16_t b)
 // compute units): `passes` launches over the directions (1: all directions in one grid, 2: one launch each) times `chunks`
 // runs of batch columns of nearly equal length (batch columns are independent).  The cut with the fewest launches that
 // `fits(columns, directions)` accepts for its longest and shortest run wins; at most eight launches per layer.
-// slots of the quarter-wave form the small-batch LSTM recurrence takes (rows of up to 16 x 24 = 384 kept entries)
+// slots of the quarter-wave form the small-batch recurrences take (rows of up to 16 x 24 = 384 kept entries)
 constexpr int kMaxRecurrentSlots = 24;
 struct LaunchCut { int passes = 0, chunks = 0; };
 template <class Fits>
@@ -192,8 +192,7 @@ static hipError_t upload(T** dst, const std::vector<T>& src)
 // Only an entry for which no such slot exists takes any free position, from the end.
 // force_slots > 0: that many slots (the other direction of the layer uses them: one launch serves both, and the
 // kernel is built for the larger count) instead of the smallest count the rule below allows.  max_slots: the most the
-// consuming kernel takes (24 in the LSTM recurrence and the projection, 16 in the H-LSTM recurrence); nothing is built for
-// longer rows.
+// consuming kernel takes (24); nothing is built for longer rows.
 // gather16: the consumer gathers 16 bytes per entry only (the projection: four input rows per tile).  Such a gather makes
 // four passes of 16 lanes -- lane bit 5 and the parity of bits 2..4 pick the pass, so a pass holds eight lanes of each
 // of two rows, with complementary parities of bits 2, 3 -- whose columns must differ modulo 16.  An entry then goes to
@@ -649,18 +648,22 @@ int lstm_destroy(lstm_t* m)
 
 const char* lstm_last_error(const lstm_t* m) { return m ? m->err.c_str() : g_create_error.c_str(); }
 
-// LSTM_FMT_AUTO: row-compressed when at most a quarter of the entries are kept.  The kernels that run both directions of
-// a layer in one launch need both in the same form, so close to the threshold (20 to 30 % kept) the direction set second
-// follows the one set first instead of landing on the other side of it by a few entries.
+// LSTM_FMT_AUTO: row-compressed when at most a quarter of the entries are kept (H-LSTM: half).  The kernels that run both
+// directions of a layer in one launch need both in the same form, so close to the threshold (within 5 % of all entries)
+// the direction set second follows the one set first instead of landing on the other side of it by a few entries.
 static bool auto_compressed(const lstm_t* m, int layer, int direction, bool masked, size_t kept, size_t total)
 {
     if (!masked) return false;
+    // The H-LSTM has no matrix-core path for dense weights at small batch, and its row-compressed kernels beat the dense
+    // ones up to half the entries kept (800/800, two directions, batch 16, 40 % kept: 135 us per step dense, 37 compressed
+    // with a launch per stage, 21 with the time loop on the device).
+    const double limit = m->G > 0 ? 0.50 : 0.25;
     const double density = (double)kept / (double)total;
     if (m->Dn == 2) {
         const LayerDir& o = m->ld[(size_t)layer * 2 + (size_t)(1 - direction)];
-        if (o.set && density > 0.20 && density < 0.30) return o.wh.compressed;
+        if (o.set && density > limit - 0.05 && density < limit + 0.05) return o.wh.compressed;
     }
-    return density <= 0.25;
+    return density <= limit;
 }
 
 int lstm_set_weights(lstm_t* m, int layer, int direction, const float* Wx, const uint8_t* mask_x, const float* Wh,
@@ -759,10 +762,10 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
     // hidden layers: 4G rows, packed row 4g+q; kept dense as well for the projection on the matrix cores
     int rc = pack_matrix(m, x.wx, W1x, mask_1x, G, D, compressed, false, true, 0, 0, 0, true);
     if (rc != LSTM_OK) return rc;
-    rc = pack_matrix(m, x.wh, W1h, mask_1h, G, H, compressed, false, false, 16, 0, 12);
+    rc = pack_matrix(m, x.wh, W1h, mask_1h, G, H, compressed, false, false, kMaxRecurrentSlots, 0, 12);
     if (rc != LSTM_OK) return rc;
     // gate outputs: 4H rows, packed row 4j+q, columns = hidden units of the row's own gate
-    rc = pack_matrix(m, x.w2, W2, mask_2, H, G, compressed, false, false, 16, G, 12);
+    rc = pack_matrix(m, x.w2, W2, mask_2, H, G, compressed, false, false, kMaxRecurrentSlots, G, 12);
     if (rc != LSTM_OK) return rc;
     std::vector<float> bp1((size_t)4 * G), bp2((size_t)4 * H);
     for (int rp = 0; rp < 4 * G; ++rp) bp1[rp] = b1[(size_t)(rp & 3) * G + (rp >> 2)];
@@ -793,7 +796,7 @@ int lstm_set_weights_h(lstm_t* m, int layer, int direction, const float* W1x, co
             if (p) { all = all && p->q16_slots > 0; target = std::max(target, p->q16_slots); }
         for (int i = 0; i < 4 && all; ++i)
             if (mats[i] && mats[i]->q16_slots < target) {
-                rc = build_quarter_wave(m, *mats[i], target, 16, false, strides[i]);
+                rc = build_quarter_wave(m, *mats[i], target, kMaxRecurrentSlots, false, strides[i]);
                 if (rc != LSTM_OK) return rc;
             }
     }

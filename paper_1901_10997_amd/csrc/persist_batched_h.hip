@@ -336,7 +336,7 @@ __global__ __launch_bounds__(512) void persist_batched_hlstm_kernel(PersistBatch
 // PAIRS <= 16, 16-bit LDS offsets, and at most 64 unit groups (one flag per polling lane).
 bool persist_batched_h_plan(int B, int H, int G, int slots, int ndir, int* upw_out, int* bw_out, int* ug_out, int* bg_out)
 {
-    if (B < 2 || slots < 2 || slots > 16 || (slots & 1) || H < 1 || G < 1) return false;
+    if (B < 2 || slots < 2 || slots > 24 || (slots & 1) || H < 1 || G < 1) return false;
     const int units = std::max(H, G);
     int best = -1;
     for (int bw = 2; bw <= 4; bw *= 2) {
@@ -414,6 +414,10 @@ hipError_t launch_persist_batched_h(PersistBatchedHArgs& a, int ndir, int slots,
         case 12: return launch_s<12>(a, upw, bw, blocks, cooperative != 0, s);
         case 14: return launch_s<14>(a, upw, bw, blocks, cooperative != 0, s);
         case 16: return launch_s<16>(a, upw, bw, blocks, cooperative != 0, s);
+        case 18: return launch_s<18>(a, upw, bw, blocks, cooperative != 0, s);
+        case 20: return launch_s<20>(a, upw, bw, blocks, cooperative != 0, s);
+        case 22: return launch_s<22>(a, upw, bw, blocks, cooperative != 0, s);
+        case 24: return launch_s<24>(a, upw, bw, blocks, cooperative != 0, s);
     }
     return hipErrorInvalidValue;
 }

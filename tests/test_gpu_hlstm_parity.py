@@ -243,6 +243,8 @@ def test_hlstm_batch1_consecutive_forwards_of_any_length_on_one_handle(L, bidir)
     (2, True, 100, 1200, 1200, 3, 24, 0.10, False),   # two directions that do not fit one grid together: two launches
     (1, False, 100, 1500, 1500, 3, 33, 0.10, True),   # more batch groups than fit the device: runs of batch columns
     (1, True, 80, 800, 800, 3, 64, 0.20, False),
+    (1, True, 64, 800, 800, 3, 16, 0.40, False),      # rows of 320 kept entries and more: 22 to 24 slots, two units per wave
+    (2, False, 64, 500, 640, 3, 6, 0.33, True),
 ])
 def test_hlstm_persistent_small_batch(shape):
     L, bidir, D, H, G, T, Bn, keep, coop = shape
@@ -409,3 +411,14 @@ def test_hlstm_full_size_speech_sampled_columns():
     case = inputs.make_case(inputs.h2(), 0)
     desc, _ = check_case(case, AUTO, PAUTO, oracle_cols=[3, 12])
     assert "persist_batched-hlstm" in desc
+
+
+def test_hlstm_auto_format_compresses_up_to_half_kept():
+    """LSTM_FMT_AUTO on an H-LSTM: masks that keep 35 % are held row-compressed (the H-LSTM's dense kernels are the slow
+    ones) and the layer runs in the persistent small-batch kernel; unmasked weights stay dense."""
+    w = _hw(86, 1, True, 48, 320, 320, 4, 8, keep=0.35)
+    desc, _ = check_case(inputs.make_case(w, 3), B.LSTM_FMT_AUTO, PAUTO)
+    assert desc.count("persist_batched-hlstm-csr") == 2, desc
+    desc, _ = check_case(inputs.make_case(_hw(86, 1, False, 48, 96, 96, 3, 4), 3), B.LSTM_FMT_AUTO, PAUTO)
+    assert "dense" in desc.split("rec=")[1], desc
+
