@@ -241,7 +241,7 @@ bool persist_b1_hlstm_supported(int H, int G, int D, int slots_1x, int slots_1h,
 {
     if (H < 1 || G < 1 || D < 1) return false;
     const int nz = std::max(slots_1x, std::max(slots_1h, slots_2));
-    if (slots_1x < 1 || slots_1h < 1 || slots_2 < 1 || nz > 5) return false;
+    if (slots_1x < 1 || slots_1h < 1 || slots_2 < 1 || nz > 7) return false;
     const int waves = hl_maxt(nz) / 64;
     if (((size_t)H + 1 + 4 * (size_t)G + 2 * (size_t)D + 4 * waves) * sizeof(float) > 64 * 1024) return false;
     const int units = std::max(H, G);
@@ -275,6 +275,8 @@ hipError_t launch_persist_b1_hlstm(const PersistHArgs& a, int cooperative, hipSt
         case 3: return launch_hl_nz<3>(a, cooperative != 0, s);
         case 4: return launch_hl_nz<4>(a, cooperative != 0, s);
         case 5: return launch_hl_nz<5>(a, cooperative != 0, s);
+        case 6: return launch_hl_nz<6>(a, cooperative != 0, s);
+        case 7: return launch_hl_nz<7>(a, cooperative != 0, s);
     }
     return hipErrorInvalidValue;
 }

@@ -173,10 +173,12 @@ def test_hlstm_garbage_under_mask_is_invisible_and_runs_are_deterministic():
     (3, True, 31, 96, 96, 5, 0.15, True),
     (1, False, 20, 333, 257, 1, 0.4, True),      # T = 1: no exchange of h at all
     (1, False, 700, 64, 64, 6, 0.2, True),       # input wider than two elements per thread
+    (1, False, 100, 1500, 1500, 3, 0.25, False), # the language-model cell with a quarter kept: six to seven slices per row
+    (1, False, 64, 600, 400, 4, 0.6, True),      # six slices
 ])
 def test_hlstm_persistent_batch1(shape):
     L, bidir, D, H, G, T, keep, coop = shape
-    case = inputs.make_case(_hw(83, L, bidir, D, H, G, T, 1, keep=keep), k=H + G + T, random_state=True)
+    case = inputs.make_case(_hw(83, L, bidir, D, H, G, T, 1, a=0.4 if H < 1000 else 0.04, keep=keep), k=H + G + T, random_state=True)
     desc, _ = check_case(case, CSR, PERSIST, cooperative=coop)
     assert "persist_b1-hlstm" in desc
     desc, _ = check_case(case, CSR, STEP)
